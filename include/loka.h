@@ -1,0 +1,216 @@
+/* loka.h -- C ABI of the MI355X (gfx950) FP8 hot path of LoKA-style low-precision
+ * linear layers: quantize -> FP8 GEMM -> scale epilogue fused with the row
+ * LayerNorm/RMSNorm -> probe error statistics -> per-shape dispatch.
+ *
+ * Conventions that hold for every entry point unless its comment says otherwise:
+ *  - every data pointer is a DEVICE pointer owned by the caller (hipMalloc or any
+ *    allocator built on it); the library keeps no reference after the call's
+ *    kernels have run;
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream);
+ *    the call enqueues its kernels on it and returns without synchronizing;
+ *  - the hot calls never allocate: scratch comes from the caller through
+ *    `workspace`, sized by the matching *_workspace() query (0 bytes => NULL is fine);
+ *  - errors are return codes, never aborts or exceptions; arguments are validated
+ *    before the first HIP call, so validation can be exercised on a host without a GPU;
+ *  - matrices are row-major; bf16 is the upper half of an IEEE binary32; FP8 is
+ *    OCP e4m3 (1-4-3, bias 7, no Inf, max 448) stored one code per byte.
+ */
+#ifndef LOKA_H
+#define LOKA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LOKA_OK = 0,
+    LOKA_ERR_NULL = 1,         /* a required pointer is NULL */
+    LOKA_ERR_SHAPE = 2,        /* non-positive size, K not a multiple of 128, a block mode that does not divide the shape, ld < cols */
+    LOKA_ERR_ALIGN = 3,        /* a pointer or stride is not 16-byte aligned */
+    LOKA_ERR_UNSUPPORTED = 4,  /* enum out of range, or a scale/norm/N/variant combination no kernel covers */
+    LOKA_ERR_WORKSPACE = 5,    /* workspace NULL or smaller than the *_workspace() query */
+    LOKA_ERR_HIP = 6,          /* a HIP runtime call failed (launch error, no device) */
+    LOKA_ERR_NO_CANDIDATE = 7  /* dispatch: no FP8 variant meets the error budget / speedup floor */
+} loka_status;
+
+/* Scale granularity of a [rows, cols] matrix (Section 3.3, "Library and Recipe
+ * Selection": tensorwise, rowwise and blockwise quantization strategies). */
+typedef enum {
+    LOKA_SCALE_TENSOR = 0,        /* one scale                                  -> 1 */
+    LOKA_SCALE_ROW = 1,           /* one per row                                -> rows */
+    LOKA_SCALE_COL = 2,           /* one per column (weights: per output channel)-> cols */
+    LOKA_SCALE_BLOCK_1x128 = 3,   /* one per (row, 128 consecutive columns)     -> rows * cols/128 */
+    LOKA_SCALE_BLOCK_128x128 = 4  /* one per 128 x 128 block                    -> rows/128 * cols/128 */
+} loka_scale_mode;
+
+/* Row normalization fused into the GEMM epilogue (Section 3.2, "Block-wise
+ * Normalization", Case 1: the whole output row is normalized while the tile is
+ * still on chip and equals the standard layer). */
+typedef enum { LOKA_NORM_NONE = 0, LOKA_NORM_LAYERNORM = 1, LOKA_NORM_RMSNORM = 2 } loka_norm;
+
+const char* loka_status_string(loka_status s);
+
+/* Number of fp32 scales `mode` produces for a [rows, cols] matrix; -1 when the
+ * mode is out of range or (block modes) does not divide the shape. Host only. */
+int64_t loka_scale_count(loka_scale_mode mode, int64_t rows, int64_t cols);
+
+/* ---------------------------------------------------------------- quantize
+ * amax -> scale -> OCP e4m3 cast of a bf16 matrix (the quantization step whose
+ * overhead Section 2.3, "Throughput Analysis", puts above 30 % of GEMM latency).
+ * Per scale group g:  amax_g = max(max|x|, 1e-12);  scales[g] = amax_g / 448
+ * (the DEQUANTIZATION factor, one fp32 division);  q = e4m3_rne(clamp(x * (448 /
+ * amax_g), -448, 448)) with one fp32 division for 448/amax_g and one fp32 multiply
+ * per element.  Codes and scales are bit-exact with that recipe.
+ *
+ *   x_bf16   [rows, ld] bf16, ld >= cols, ld % 8 == 0, 16-byte aligned
+ *   q        [rows, cols] uint8, or [cols, rows] when transpose_out != 0 (used for
+ *            weights W[K, N] -> Wq[N, K] so the GEMM reads K-contiguous operands)
+ *   scales   [loka_scale_count(mode, rows, cols)] fp32, group order: row-major over
+ *            (row group, column group)
+ *   cols must be a multiple of 16 (rows too when transpose_out != 0).
+ * Workspace: loka_quantize_workspace() bytes (0 for ROW and BLOCK_1x128 without
+ * transpose); contents are scratch.  */
+size_t loka_quantize_workspace(loka_scale_mode mode, int64_t rows, int64_t cols, int transpose_out);
+loka_status loka_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, loka_scale_mode mode,
+                          int transpose_out, uint8_t* q, float* scales, void* workspace, size_t ws_bytes,
+                          void* hip_stream);
+
+/* Test aid: OCP e4m3 cast (round-to-nearest-even, saturating) of n device floats with
+ * the same device routine loka_quantize uses.  t and codes are device pointers. */
+loka_status loka_e4m3_from_f32(const float* t, uint8_t* codes, int64_t n, void* hip_stream);
+
+/* ---------------------------------------------------------------- FP8 GEMM + fused norm
+ * O = norm( (Xq . Wq^T) scaled )  for `batch` independent problems of one shape
+ * (Section 2.1: LRMs are dominated by many small GEMMs each followed by a
+ * normalization; Section 3.2: the normalization is applied in the GEMM epilogue
+ * while the output tile is on chip).
+ *   acc[m,n] = sum_k dq(xq[m,k]) * dq(wq[n,k])           FP8 MFMA, fp32 accumulate
+ *   Y[m,n]   = acc * sx * sw                              TENSOR/ROW x TENSOR/COL scales
+ *            = sum_kb acc_kb * sx[m,kb] * sw[kb, n/128]   BLOCK_1x128 x BLOCK_128x128: each
+ *                                                         128-wide K block is promoted to an
+ *                                                         fp32 accumulator with its scales
+ *   O[m,n]   = bf16_rne( LayerNorm / RMSNorm / identity over the N entries of row m )
+ *     LayerNorm: (Y-mu)/sqrt(var+eps)*gamma+beta, biased variance;  RMSNorm: Y/sqrt(mean(Y^2)+eps)*gamma.
+ * There is no bias input (Section 3.2, "No Bias").
+ * Supported scale pairs: x in {TENSOR, ROW} with w in {TENSOR, COL}; or x = BLOCK_1x128
+ * with w = BLOCK_128x128 (needs N % 128 == 0).  K % 128 == 0, N % 16 == 0.
+ */
+typedef struct {
+    int64_t M, N, K;
+    int64_t batch;            /* >= 1 independent problems in one launch (grouped small GEMMs) */
+    int64_t strideX;          /* elements between consecutive problems' Xq ([M,K] each); 0 = shared */
+    int64_t strideW;          /* ... Wq ([N,K] each); 0 = one weight shared by all problems */
+    int64_t strideO;          /* ... O and Y ([M,N] each) */
+    int32_t x_mode, w_mode;   /* loka_scale_mode of sx / sw; problem g's scales start at g * loka_scale_count(...)
+                                 (at 0 when the operand's stride is 0) */
+    int32_t norm;             /* loka_norm */
+    float eps;
+    int32_t variant;          /* kernel variant id (see loka_variant_name), or -1 = library's choice for the shape */
+} loka_gemm_desc;
+
+int loka_variant_count(void);
+const char* loka_variant_name(int variant);      /* NULL when out of range */
+/* 1 when `variant` can run `desc` (shape limits of the tile and its epilogue schedule). Host only. */
+int loka_variant_supports(const loka_gemm_desc* desc, int variant);
+
+/*   xq  [batch][M, K] codes         sx  scales of X         wq [batch][N, K] codes      sw scales of W
+ *   gamma, beta: bf16 [N] or NULL (= 1 / 0), shared by all problems; beta is ignored by RMSNorm
+ *   out_bf16 [batch][M, N] bf16 (required)
+ *   y_fp32   [batch][M, N] fp32 pre-norm Y for the probe, or NULL to skip that store
+ * Workspace: loka_fp8_gemm_norm_workspace(desc) bytes (non-zero only for variants whose row
+ * statistics cross workgroups).  Returns LOKA_ERR_UNSUPPORTED when desc->variant cannot run
+ * the shape.  */
+size_t loka_fp8_gemm_norm_workspace(const loka_gemm_desc* desc);
+loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
+                               const float* sw, const void* gamma_bf16, const void* beta_bf16, void* out_bf16,
+                               float* y_fp32, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------- probe reference
+ * Yref = X . W from the UNQUANTIZED bf16 operands with fp32 accumulation: the
+ * high-precision reference the probe measures FP8 against (Section 2.3, "Error
+ * Analysis"; the paper's reference is TF32, this build's is BF16 operands with fp32
+ * accumulate).  x [batch][M, K] bf16, w [batch][K, N] bf16 (strideW 0 = shared),
+ * yref [batch][M, N] fp32.  Only M, N, K, batch and the strides of `desc` are read.
+ * K % 32 == 0, N % 16 == 0.  Workspace: loka_bf16_gemm_workspace() bytes (a transposed copy of W). */
+size_t loka_bf16_gemm_workspace(const loka_gemm_desc* desc);
+loka_status loka_bf16_gemm(const loka_gemm_desc* desc, const void* x_bf16, const void* w_bf16, float* yref_fp32,
+                           void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------- probe error statistics
+ * Error of Y against Yref (Section 2.3, "Error Analysis"), both fp32 [M, ld]:
+ *   d = Y - Yref (one fp32 subtraction)
+ *   rowmax[m]  = max_n |d|            (bit-exact)           max_abs = max_m rowmax[m]
+ *   rel_fro    = sqrt(sum d^2) / sqrt(sum Yref^2)            (fp64 sums)
+ *   mere       = (1/(M N)) * sum |d| / max(|Yref|, 1e-30)    the paper's MERE read as a mean
+ * The sums are combined in a fixed order, so results are repeatable run to run.
+ * stats_device: one loka_probe_stats in DEVICE memory; rowmax_device: fp32 [M] or NULL.
+ * ld % 4 == 0, N % 4 == 0.  */
+typedef struct {
+    double rel_fro;
+    double max_abs;
+    double mere;
+    double sum_sq_err;
+    double sum_sq_ref;
+} loka_probe_stats;
+
+size_t loka_probe_error_workspace(int64_t M, int64_t N);
+loka_status loka_probe_error(const float* y, const float* yref, int64_t M, int64_t N, int64_t ld,
+                             loka_probe_stats* stats_device, float* rowmax_device, void* workspace, size_t ws_bytes,
+                             void* hip_stream);
+
+/* ---------------------------------------------------------------- dispatch
+ * Per-shape selection (Section 3.3, "Library and Recipe Selection"): among the
+ * library's own candidates (scale recipe x kernel variant) keep those whose probe
+ * error is within the budget and whose speedup over the BF16 GEMM reaches
+ * min_speedup, and take the fastest.  The paper's typical thresholds are an error
+ * bound of 0.2 on MERE and a speedup floor of 1.05; here the budget applies to
+ * rel_fro (MERE is reported in the candidate table).  */
+typedef struct {
+    int32_t x_mode, w_mode;   /* scale recipe */
+    int32_t variant;          /* kernel variant */
+    int32_t feasible;         /* met the budget and the speedup floor */
+    float usec;               /* quantize(X) + GEMM+norm, average of the timed launches */
+    float usec_gemm;          /* GEMM+norm alone */
+    loka_probe_stats stats;   /* probe of this candidate's Y against the BF16 reference */
+} loka_candidate;
+
+typedef struct {
+    int32_t x_mode, w_mode, variant;
+    int32_t from_cache;       /* 1 when the per-shape cache answered */
+    float usec;               /* of the chosen candidate */
+    float usec_bf16;          /* BF16 reference GEMM on the same shape */
+    loka_probe_stats stats;
+} loka_choice;
+
+/* Pure host rule, exposed so it can be tested with injected tables: index of the
+ * fastest candidate with err[i] <= budget and (min_speedup <= 0 or usec_bf16/usec[i] >=
+ * min_speedup); ties to the lowest index; -1 when none qualifies. */
+int loka_dispatch_select(int n, const double* usec, const double* err, double budget, double min_speedup,
+                         double usec_bf16);
+
+/* Profiles every candidate that supports `shape` on the given bf16 operands
+ * (x [batch][M,K], w [batch][K,N], device), fills `choice`, and remembers it per
+ * (M, N, K, batch, norm, budget, min_speedup).  Later calls with the same key return the
+ * cached choice without touching the GPU.  This call ALLOCATES device scratch and
+ * SYNCHRONIZES the stream; it is a profiling step, not a hot call.
+ * `table`/`table_cap`/`n_table` (optional) receive one row per profiled candidate.
+ * shape->x_mode, w_mode and variant are ignored.
+ * Returns LOKA_ERR_NO_CANDIDATE (and x_mode = w_mode = variant = -1 in `choice`, meaning: keep
+ * this layer in BF16 -- the outcome the paper's Limitations describe for layers that do not
+ * tolerate low precision) when the feasible set is empty.  */
+loka_status loka_dispatch(const loka_gemm_desc* shape, const void* x_bf16, const void* w_bf16, double err_budget,
+                          double min_speedup, loka_choice* choice, loka_candidate* table, int table_cap, int* n_table,
+                          void* hip_stream);
+/* Forget every cached choice (host only). */
+void loka_dispatch_clear(void);
+/* Variant the library would run for desc with variant = -1 (cached dispatch choice for the
+ * shape and recipe if there is one, else a static heuristic); -1 when nothing supports it. */
+int loka_default_variant(const loka_gemm_desc* desc);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOKA_H */

@@ -1,0 +1,194 @@
+// C ABI of the library: argument validation (host only, before any HIP call) and
+// forwarding to the kernel launchers.  See include/loka.h for the contract.
+#include "common.h"
+
+#include <cstdlib>
+#include <cstring>
+
+namespace loka {
+// quantize.hip
+loka_status quantize_launch(const void*, int64_t, int64_t, int64_t, loka_scale_mode, int, uint8_t*, float*, void*,
+                            hipStream_t);
+loka_status e4m3_from_f32_launch(const float*, uint8_t*, int64_t, hipStream_t);
+// gemm.hip
+int variant_count();
+const char* variant_name(int);
+bool variant_supports(const loka_gemm_desc*, int);
+size_t variant_workspace(const loka_gemm_desc*, int);
+loka_status fp8_gemm_norm_launch(const loka_gemm_desc*, int, const uint8_t*, const float*, const uint8_t*, const float*,
+                                 const void*, const void*, void*, float*, void*, hipStream_t);
+size_t bf16_gemm_workspace_bytes(const loka_gemm_desc*);
+loka_status bf16_gemm_launch(const loka_gemm_desc*, const void*, const void*, float*, void*, hipStream_t);
+// probe.hip
+size_t probe_workspace_bytes();
+loka_status probe_launch(const float*, const float*, int64_t, int64_t, int64_t, loka_probe_stats*, float*, void*,
+                         hipStream_t);
+// dispatch.hip
+int default_variant(const loka_gemm_desc*);
+
+static bool mode_ok(int m) { return m >= LOKA_SCALE_TENSOR && m <= LOKA_SCALE_BLOCK_128x128; }
+
+// Shape / enum validation shared by the GEMM entry points; does not look at pointers.
+loka_status validate_desc(const loka_gemm_desc* d, bool fp8) {
+    if (!d) return LOKA_ERR_NULL;
+    if (d->M <= 0 || d->N <= 0 || d->K <= 0 || d->batch <= 0) return LOKA_ERR_SHAPE;
+    if (d->M > INT32_MAX || d->N > INT32_MAX || d->K > INT32_MAX / 2 || d->batch > INT32_MAX) return LOKA_ERR_SHAPE;
+    if (d->N % 16) return LOKA_ERR_SHAPE;
+    if (fp8 ? (d->K % 128) : (d->K % 64)) return LOKA_ERR_SHAPE;
+    if (d->strideX < 0 || d->strideW < 0 || d->strideO < 0) return LOKA_ERR_SHAPE;
+    if (d->batch > 1 && d->strideO < d->M * d->N) return LOKA_ERR_SHAPE;
+    if ((d->strideX % 16) || (d->strideW % 16) || (d->strideO % 8)) return LOKA_ERR_ALIGN;
+    if (!fp8) return LOKA_OK;
+    if (!mode_ok(d->x_mode) || !mode_ok(d->w_mode)) return LOKA_ERR_UNSUPPORTED;
+    if (d->norm < LOKA_NORM_NONE || d->norm > LOKA_NORM_RMSNORM) return LOKA_ERR_UNSUPPORTED;
+    const bool xb = d->x_mode == LOKA_SCALE_BLOCK_1x128, wb = d->w_mode == LOKA_SCALE_BLOCK_128x128;
+    if (xb != wb) return LOKA_ERR_UNSUPPORTED;
+    if (xb && (d->N % 128)) return LOKA_ERR_SHAPE;
+    if (!xb) {
+        if (!(d->x_mode == LOKA_SCALE_TENSOR || d->x_mode == LOKA_SCALE_ROW)) return LOKA_ERR_UNSUPPORTED;
+        if (!(d->w_mode == LOKA_SCALE_TENSOR || d->w_mode == LOKA_SCALE_COL)) return LOKA_ERR_UNSUPPORTED;
+    }
+    if (!(d->eps >= 0.f)) return LOKA_ERR_UNSUPPORTED;
+    return LOKA_OK;
+}
+
+int resolve_variant(const loka_gemm_desc* d) {
+    if (d->variant >= 0) return variant_supports(d, d->variant) ? d->variant : -1;
+    if (const char* f = std::getenv("LOKA_FORCE_VARIANT")) {
+        const int v = std::atoi(f);
+        if (variant_supports(d, v)) return v;
+    }
+    return default_variant(d);
+}
+
+}  // namespace loka
+
+using namespace loka;
+
+extern "C" {
+
+const char* loka_status_string(loka_status s) {
+    switch (s) {
+        case LOKA_OK: return "ok";
+        case LOKA_ERR_NULL: return "null pointer";
+        case LOKA_ERR_SHAPE: return "bad shape";
+        case LOKA_ERR_ALIGN: return "misaligned pointer or stride";
+        case LOKA_ERR_UNSUPPORTED: return "unsupported combination";
+        case LOKA_ERR_WORKSPACE: return "workspace missing or too small";
+        case LOKA_ERR_HIP: return "HIP runtime error";
+        case LOKA_ERR_NO_CANDIDATE: return "no FP8 candidate within the error budget";
+    }
+    return "unknown status";
+}
+
+int64_t loka_scale_count(loka_scale_mode mode, int64_t rows, int64_t cols) {
+    if (rows <= 0 || cols <= 0) return -1;
+    switch (mode) {
+        case LOKA_SCALE_TENSOR: return 1;
+        case LOKA_SCALE_ROW: return rows;
+        case LOKA_SCALE_COL: return cols;
+        case LOKA_SCALE_BLOCK_1x128: return (cols % 128) ? -1 : rows * (cols / 128);
+        case LOKA_SCALE_BLOCK_128x128: return (cols % 128 || rows % 128) ? -1 : (rows / 128) * (cols / 128);
+    }
+    return -1;
+}
+
+size_t loka_quantize_workspace(loka_scale_mode mode, int64_t rows, int64_t cols, int transpose_out) {
+    if (!transpose_out && (mode == LOKA_SCALE_ROW || mode == LOKA_SCALE_BLOCK_1x128)) return 0;
+    const int64_t ng = loka_scale_count(mode, rows, cols);
+    if (ng < 0) return 0;
+    return static_cast<size_t>(ng) * 8;       // amax bits + quantization factors
+}
+
+loka_status loka_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, loka_scale_mode mode,
+                          int transpose_out, uint8_t* q, float* scales, void* workspace, size_t ws_bytes,
+                          void* hip_stream) {
+    if (!x_bf16 || !q || !scales) return LOKA_ERR_NULL;
+    if (!mode_ok(mode)) return LOKA_ERR_UNSUPPORTED;
+    if (rows <= 0 || cols <= 0 || ld < cols) return LOKA_ERR_SHAPE;
+    if (cols % 16 || (transpose_out && rows % 16)) return LOKA_ERR_SHAPE;
+    if (loka_scale_count(mode, rows, cols) < 0) return LOKA_ERR_SHAPE;
+    if (ld % 8) return LOKA_ERR_ALIGN;
+    if (!aligned16(x_bf16) || !aligned16(q) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return LOKA_ERR_ALIGN;
+    if (transpose_out && (mode == LOKA_SCALE_ROW || mode == LOKA_SCALE_BLOCK_1x128)) return LOKA_ERR_UNSUPPORTED;
+    const size_t need = loka_quantize_workspace(mode, rows, cols, transpose_out);
+    if (need && (!workspace || ws_bytes < need)) return LOKA_ERR_WORKSPACE;
+    if (need && !aligned16(workspace)) return LOKA_ERR_ALIGN;
+    return quantize_launch(x_bf16, rows, cols, ld, mode, transpose_out, q, scales, workspace,
+                           static_cast<hipStream_t>(hip_stream));
+}
+
+loka_status loka_e4m3_from_f32(const float* t, uint8_t* codes, int64_t n, void* hip_stream) {
+    if (!t || !codes) return LOKA_ERR_NULL;
+    if (n <= 0) return LOKA_ERR_SHAPE;
+    return e4m3_from_f32_launch(t, codes, n, static_cast<hipStream_t>(hip_stream));
+}
+
+int loka_variant_count(void) { return variant_count(); }
+const char* loka_variant_name(int variant) { return variant_name(variant); }
+
+int loka_variant_supports(const loka_gemm_desc* desc, int variant) {
+    if (validate_desc(desc, true) != LOKA_OK) return 0;
+    return variant_supports(desc, variant) ? 1 : 0;
+}
+
+size_t loka_fp8_gemm_norm_workspace(const loka_gemm_desc* desc) {
+    if (validate_desc(desc, true) != LOKA_OK) return 0;
+    const int v = resolve_variant(desc);
+    return v < 0 ? 0 : variant_workspace(desc, v);
+}
+
+loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
+                               const float* sw, const void* gamma_bf16, const void* beta_bf16, void* out_bf16,
+                               float* y_fp32, void* workspace, size_t ws_bytes, void* hip_stream) {
+    if (!desc || !xq || !sx || !wq || !sw || !out_bf16) return LOKA_ERR_NULL;
+    const loka_status st = validate_desc(desc, true);
+    if (st != LOKA_OK) return st;
+    if (!aligned16(xq) || !aligned16(wq) || !aligned16(sx) || !aligned16(sw) || !aligned16(out_bf16) ||
+        !aligned16(y_fp32) || !aligned16(gamma_bf16) || !aligned16(beta_bf16))
+        return LOKA_ERR_ALIGN;
+    const int v = resolve_variant(desc);
+    if (v < 0) return LOKA_ERR_UNSUPPORTED;
+    const size_t need = variant_workspace(desc, v);
+    if (need && (!workspace || ws_bytes < need)) return LOKA_ERR_WORKSPACE;
+    if (need && !aligned16(workspace)) return LOKA_ERR_ALIGN;
+    return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, out_bf16, y_fp32, workspace,
+                                static_cast<hipStream_t>(hip_stream));
+}
+
+size_t loka_bf16_gemm_workspace(const loka_gemm_desc* desc) {
+    if (validate_desc(desc, false) != LOKA_OK) return 0;
+    return bf16_gemm_workspace_bytes(desc);
+}
+
+loka_status loka_bf16_gemm(const loka_gemm_desc* desc, const void* x_bf16, const void* w_bf16, float* yref_fp32,
+                           void* workspace, size_t ws_bytes, void* hip_stream) {
+    if (!desc || !x_bf16 || !w_bf16 || !yref_fp32) return LOKA_ERR_NULL;
+    const loka_status st = validate_desc(desc, false);
+    if (st != LOKA_OK) return st;
+    if (!aligned16(x_bf16) || !aligned16(w_bf16) || !aligned16(yref_fp32)) return LOKA_ERR_ALIGN;
+    const size_t need = bf16_gemm_workspace_bytes(desc);
+    if (!workspace || ws_bytes < need) return LOKA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return LOKA_ERR_ALIGN;
+    return bf16_gemm_launch(desc, x_bf16, w_bf16, yref_fp32, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t loka_probe_error_workspace(int64_t M, int64_t N) {
+    (void)M; (void)N;
+    return probe_workspace_bytes();
+}
+
+loka_status loka_probe_error(const float* y, const float* yref, int64_t M, int64_t N, int64_t ld,
+                             loka_probe_stats* stats_device, float* rowmax_device, void* workspace, size_t ws_bytes,
+                             void* hip_stream) {
+    if (!y || !yref || !stats_device) return LOKA_ERR_NULL;
+    if (M <= 0 || N <= 0 || ld < N) return LOKA_ERR_SHAPE;
+    if (N % 4 || ld % 4) return LOKA_ERR_SHAPE;
+    if (!aligned16(y) || !aligned16(yref) || (reinterpret_cast<uintptr_t>(stats_device) & 7u)) return LOKA_ERR_ALIGN;
+    if (!workspace || ws_bytes < probe_workspace_bytes()) return LOKA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return LOKA_ERR_ALIGN;
+    return probe_launch(y, yref, M, N, ld, stats_device, rowmax_device, workspace,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

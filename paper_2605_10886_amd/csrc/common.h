@@ -1,0 +1,66 @@
+// Shared host/device helpers of the HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/loka.h"
+
+#define LOKA_HIP_TRY(expr)                        \
+    do {                                          \
+        hipError_t e__ = (expr);                  \
+        if (e__ != hipSuccess) return LOKA_ERR_HIP; \
+    } while (0)
+
+namespace loka {
+
+constexpr float kE4M3Max = 448.0f;
+constexpr float kAmaxFloor = 1e-12f;
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+// low / high bf16 of a 32-bit word holding two consecutive elements
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// Round-to-nearest-even narrowing of a finite fp32 to bf16 bits.
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (u >> 16) | ((u & 0x007FFFFFu) ? 0x40u : 0u);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+}
+
+// OCP e4m3 cast of four fp32 values (round-to-nearest-even by the gfx950 convert
+// instruction, which encodes OCP e4m3 on this target).  The clamp comes first: the
+// hardware maps magnitudes of 480 and above to NaN instead of saturating.
+__device__ __forceinline__ float clamp448(float t) { return __builtin_fminf(__builtin_fmaxf(t, -kE4M3Max), kE4M3Max); }
+__device__ __forceinline__ uint32_t e4m3x4(float t0, float t1, float t2, float t3) {
+    int pk = 0;
+    pk = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(t0), clamp448(t1), pk, false);
+    pk = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(t2), clamp448(t3), pk, true);
+    return static_cast<uint32_t>(pk);
+}
+
+// amax floor, dequantization scale and quantization factor of one scale group:
+// each a single IEEE fp32 division.
+__device__ __forceinline__ void group_scale(float amax, float& scale, float& inv) {
+    float a = amax < kAmaxFloor ? kAmaxFloor : amax;
+    scale = a / kE4M3Max;
+    inv = kE4M3Max / a;
+}
+
+__device__ __forceinline__ float wave_shfl_xor(float v, int mask) { return __shfl_xor(v, mask, 64); }
+
+}  // namespace loka

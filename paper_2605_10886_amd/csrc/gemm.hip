@@ -1,0 +1,649 @@
+// FP8 (e4m3) GEMM with the dequantization scales and the row LayerNorm / RMSNorm
+// fused into the epilogue, plus the BF16 reference GEMM that shares its skeleton.
+//
+// Data flow of one workgroup (tile BM rows of X by BN columns of W):
+//   global --global_load_lds (16 B per lane, straight into LDS)--> double-buffered
+//   K-slices of 128 bytes per row --ds_read_b128--> MFMA operand registers
+//   --v_mfma_f32_16x16x128_f8f6f4 (FP8) / v_mfma_f32_16x16x32_bf16--> fp32 accumulators
+//   --epilogue in registers + a few LDS words--> bf16 O (and optionally fp32 Y).
+//
+// Operand roles are swapped on purpose: rows of W feed the MFMA's row operand and rows
+// of X its column operand, so D[n][m] lands with lane l holding column m = l % 16 and
+// four consecutive n.  The W rows handed to each MFMA are permuted so that a lane ends
+// up with 4*NI CONSECUTIVE output columns of one row m: it can scale, reduce and store
+// them as 16-byte vectors without a transpose, and the row statistics need only two
+// cross-lane steps (lanes l, l^16, l^32, l^48 share a row).
+//
+// LDS rows are 128 bytes = 8 chunks of 16 bytes; chunk c of row r is stored at chunk
+// position c ^ key(r), with key chosen so that the 8 lanes a ds_read_b128 serves at
+// once hit 8 different chunk positions for both operand read patterns.
+#include "common.h"
+
+namespace loka {
+
+enum { EPI_ROW_IN_TILE = 0, EPI_PARTIAL_STATS = 1 };
+
+struct GemmParams {
+    const uint8_t* X;      // [batch][M][KB] bytes (KB = K for FP8, 2K for BF16)
+    const uint8_t* W;      // [batch][N][KB]
+    int M, N, KB;
+    int batch;
+    int64_t strideX, strideW;   // bytes between problems
+    int64_t strideO;            // elements between problems (O, Y)
+    const float* sx;
+    const float* sw;
+    int64_t strideSx, strideSw; // scales between problems
+    int x_mode, w_mode;
+    const uint16_t* gamma;
+    const uint16_t* beta;
+    uint16_t* out;
+    float* y;
+    int norm;
+    float eps;
+    int tiles_m, tiles_n;
+    float* part;           // EPI_PARTIAL_STATS: [batch][M][tiles_n * 2] (mean, M2) or (sumsq, -)
+};
+
+// Chan's pairwise merge of (count, mean, M2).
+__device__ __forceinline__ void merge_stats(float& n, float& mean, float& m2, float nb, float mb, float m2b) {
+    const float nn = n + nb;
+    if (nb > 0.f) {
+        const float d = mb - mean;
+        const float f = nb / nn;          // nn > 0 here
+        mean = mean + d * f;
+        m2 = m2 + m2b + d * d * n * f;
+        n = nn;
+    }
+}
+
+template <int BM, int BN_SUB, int NSPLIT, int WAVES_M, int WAVES_N, bool IS_BF16, bool BLOCKWISE, int EPI>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmParams p) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M;           // rows of X per wave
+    constexpr int WN = BN_SUB / WAVES_N;       // columns per wave and N-part
+    constexpr int MI = WM / 16;
+    constexpr int NI = WN / 16;
+    constexpr int RUN = 4 * NI;                // consecutive columns a lane owns per N-part
+    constexpr int BN = BN_SUB * NSPLIT;
+    constexpr int XS = BM * 128;               // bytes of one X stage
+    constexpr int WS = BN_SUB * 128;           // bytes of one W stage
+    static_assert(WM % 16 == 0 && WN % 16 == 0 && (NI == 2 || NI == 4 || NI == 8), "tile shape");
+    static_assert(BM % 8 == 0 && BN_SUB % 8 == 0, "loader works on 8-row groups");
+    static_assert(!(BLOCKWISE && (RUN > 128 || 128 % RUN)), "a lane's run must stay inside one 128-column block");
+
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    uint8_t* const xbuf = smem;                // 2 stages
+    uint8_t* const wbuf = smem + 2 * XS;       // 2 stages
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+    const int l16 = lane & 15, q = lane >> 4;
+
+    // tile coordinates: blockIdx.x enumerates (problem, m tile, n tile), n fastest
+    int t = blockIdx.x;
+    const int tn = t % p.tiles_n; t /= p.tiles_n;
+    const int tm = t % p.tiles_m;
+    const int g = t / p.tiles_m;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const uint8_t* Xg = p.X + static_cast<int64_t>(g) * p.strideX;
+    const uint8_t* Wg = p.W + static_cast<int64_t>(g) * p.strideW;
+
+    // ---- loader: one wave-load moves 8 rows x 128 B; lane -> (row lane/8, chunk position lane%8)
+    const int ld_row = lane >> 3, ld_pos = lane & 7;
+    // X rows: key(r) = r & 7  (rows of an 8-row group starting at a multiple of 8)
+    const int x_chunk = ld_pos ^ ld_row;
+    // W rows: key(r) = (r & 3) | (((r_local / RUN) & 1) << 2), r_local = r % WN
+    auto w_key = [](int r) { return (r & 3) | ((((r % WN) / RUN) & 1) << 2); };
+
+    auto issue_x = [&](int stage, int kb) {
+        constexpr int GROUPS = BM / 8;
+#pragma unroll
+        for (int j = 0; j < (GROUPS + NW - 1) / NW; ++j) {
+            const int grp = wave + j * NW;
+            if (GROUPS % NW == 0 || grp < GROUPS) {
+                int r = m0 + grp * 8 + ld_row;
+                r = r < p.M ? r : p.M - 1;
+                const uint8_t* src = Xg + static_cast<int64_t>(r) * p.KB + kb + x_chunk * 16;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                 (__attribute__((address_space(3))) void*)(xbuf + stage * XS + grp * 1024),
+                                                 16, 0, 0);
+            }
+        }
+    };
+    auto issue_w = [&](int stage, int kb, int h) {
+        constexpr int GROUPS = BN_SUB / 8;
+#pragma unroll
+        for (int j = 0; j < (GROUPS + NW - 1) / NW; ++j) {
+            const int grp = wave + j * NW;
+            if (GROUPS % NW == 0 || grp < GROUPS) {
+                const int rl = grp * 8 + ld_row;              // row inside the W stage
+                int r = n0 + h * BN_SUB + rl;
+                r = r < p.N ? r : p.N - 1;
+                const int chunk = ld_pos ^ w_key(rl);
+                const uint8_t* src = Wg + static_cast<int64_t>(r) * p.KB + kb + chunk * 16;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                 (__attribute__((address_space(3))) void*)(wbuf + stage * WS + grp * 1024),
+                                                 16, 0, 0);
+            }
+        }
+    };
+
+    // ---- fragment addresses (bytes inside a stage)
+    // FP8: a lane supplies K bytes [32q, 32q+32) = chunks 2q, 2q+1 (any K order works as long
+    // as both operands use the same one).  BF16: two MFMAs per 128-byte row, lane chunk q and 4+q.
+    const int c0 = IS_BF16 ? q : 2 * q, c1 = IS_BF16 ? 4 + q : 2 * q + 1;
+    const int xrow = wave_m * WM + l16;                         // + mi * 16
+    const int xkey = xrow & 7;
+    const int x_off0 = xrow * 128 + ((c0 ^ xkey) << 4), x_off1 = xrow * 128 + ((c1 ^ xkey) << 4);
+    const int wrow = wave_n * WN + (l16 >> 2) * RUN + (l16 & 3);  // + 4 * t
+    const int wkey = w_key(wrow);
+    const int w_off0 = wrow * 128 + ((c0 ^ wkey) << 4), w_off1 = wrow * 128 + ((c1 ^ wkey) << 4);
+
+    v4f acc[NSPLIT][MI][NI];
+#pragma unroll
+    for (int h = 0; h < NSPLIT; ++h)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ti = 0; ti < NI; ++ti) acc[h][mi][ti] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    const int ksteps = p.KB / 128;
+    const int iters = ksteps * NSPLIT;
+
+    // blockwise scales: sx[m, kb] per row of this lane, sw[kb, nb] per N-part
+    const float* sxg = p.sx + static_cast<int64_t>(g) * p.strideSx;
+    const float* swg = p.sw + static_cast<int64_t>(g) * p.strideSw;
+
+    issue_x(0, 0);
+    issue_w(0, 0, 0);
+
+    for (int it = 0; it < iters; ++it) {
+        const int k = it / NSPLIT, h = it % NSPLIT;
+        __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0): this wave's loads for stage `it` have landed
+        __syncthreads();                                        // everyone's have; everyone left iteration it-1
+        if (it + 1 < iters) {
+            const int k1 = (it + 1) / NSPLIT, h1 = (it + 1) % NSPLIT;
+            issue_w((it + 1) & 1, k1 * 128, h1);
+            if (h1 == 0) issue_x(k1 & 1, k1 * 128);
+        }
+        const uint8_t* xs = xbuf + (k & 1) * XS;
+        const uint8_t* ws = wbuf + (it & 1) * WS;
+
+        v8i bx[MI];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const v4i lo = *reinterpret_cast<const v4i*>(xs + x_off0 + mi * 16 * 128);
+            const v4i hi = *reinterpret_cast<const v4i*>(xs + x_off1 + mi * 16 * 128);
+            bx[mi] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
+        float sxk[MI];
+        if (BLOCKWISE) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                int m = m0 + wave_m * WM + mi * 16 + l16;
+                m = m < p.M ? m : p.M - 1;
+                sxk[mi] = sxg[static_cast<int64_t>(m) * ksteps + k];
+            }
+        }
+#pragma unroll
+        for (int hh = 0; hh < NSPLIT; ++hh) {
+            if (hh != h) continue;
+            float swk = 0.f;
+            if (BLOCKWISE) {
+                int nrun = n0 + hh * BN_SUB + wave_n * WN + q * RUN;
+                nrun = nrun < p.N ? nrun : p.N - 1;
+                swk = swg[static_cast<int64_t>(k) * (p.N >> 7) + (nrun >> 7)];
+            }
+#pragma unroll
+            for (int ti = 0; ti < NI; ++ti) {
+                const v4i lo = *reinterpret_cast<const v4i*>(ws + w_off0 + ti * 4 * 128);
+                const v4i hi = *reinterpret_cast<const v4i*>(ws + w_off1 + ti * 4 * 128);
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    if (IS_BF16) {
+                        v4f c = acc[hh][mi][ti];
+                        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, lo),
+                                                                    __builtin_bit_cast(v8bf, v4i{bx[mi][0], bx[mi][1], bx[mi][2], bx[mi][3]}),
+                                                                    c, 0, 0, 0);
+                        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, hi),
+                                                                    __builtin_bit_cast(v8bf, v4i{bx[mi][4], bx[mi][5], bx[mi][6], bx[mi][7]}),
+                                                                    c, 0, 0, 0);
+                        acc[hh][mi][ti] = c;
+                    } else {
+                        const v8i aw = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        if (BLOCKWISE) {
+                            // promote this 128-wide K block into the fp32 accumulator with its scales
+                            v4f c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aw, bx[mi], v4f{0.f, 0.f, 0.f, 0.f},
+                                                                                     0, 0, 0, 0, 0, 0);
+                            const float s = sxk[mi] * swk;
+                            acc[hh][mi][ti] += c * s;
+                        } else {
+                            acc[hh][mi][ti] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aw, bx[mi], acc[hh][mi][ti],
+                                                                                               0, 0, 0, 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    // ------------------------------------------------------------------ epilogue
+    // lane owns row m (per mi) and, per N-part h, columns ncol(h) + [0, RUN)
+    __syncthreads();                       // all waves are done reading the stages: LDS is free
+    float* red = reinterpret_cast<float*>(smem);   // [BM][WAVES_N][3]
+    const int64_t obase = static_cast<int64_t>(g) * p.strideO;
+    const bool tensor_x = p.x_mode == LOKA_SCALE_TENSOR, tensor_w = p.w_mode == LOKA_SCALE_TENSOR;
+
+    int ncol[NSPLIT];
+    float cnt_lane = 0.f;                  // valid columns this lane holds per row
+#pragma unroll
+    for (int h = 0; h < NSPLIT; ++h) {
+        ncol[h] = n0 + h * BN_SUB + wave_n * WN + q * RUN;
+#pragma unroll
+        for (int ti = 0; ti < NI; ++ti)
+            if (ncol[h] + 4 * ti < p.N) cnt_lane += 4.f;
+    }
+
+    // apply scales in place
+    if (!BLOCKWISE && !IS_BF16) {
+#pragma unroll
+        for (int h = 0; h < NSPLIT; ++h)
+#pragma unroll
+            for (int ti = 0; ti < NI; ++ti) {
+                const int n = ncol[h] + 4 * ti;
+                v4f s4;
+                if (tensor_w) {
+                    const float s = swg[0];
+                    s4 = v4f{s, s, s, s};
+                } else {
+                    s4 = (n < p.N) ? *reinterpret_cast<const v4f*>(swg + n) : v4f{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    int m = m0 + wave_m * WM + mi * 16 + l16;
+                    m = m < p.M ? m : p.M - 1;
+                    const float sxm = tensor_x ? sxg[0] : sxg[m];
+                    acc[h][mi][ti] *= s4 * sxm;
+                }
+            }
+    }
+
+    if (p.y) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int m = m0 + wave_m * WM + mi * 16 + l16;
+            if (m < p.M) {
+#pragma unroll
+                for (int h = 0; h < NSPLIT; ++h)
+#pragma unroll
+                    for (int ti = 0; ti < NI; ++ti) {
+                        const int n = ncol[h] + 4 * ti;
+                        if (n < p.N)
+                            *reinterpret_cast<v4f*>(p.y + obase + static_cast<int64_t>(m) * p.N + n) = acc[h][mi][ti];
+                    }
+            }
+        }
+    }
+    if (IS_BF16) return;                   // reference GEMM: fp32 Y only
+
+    // ---- row statistics
+    float mean_r[MI], rstd_r[MI];
+    if (p.norm == LOKA_NORM_NONE) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) { mean_r[mi] = 0.f; rstd_r[mi] = 1.f; }
+    } else {
+        const bool ln = p.norm == LOKA_NORM_LAYERNORM;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            float n_ = cnt_lane, mean = 0.f, m2 = 0.f;
+            if (ln) {
+                float s = 0.f;
+#pragma unroll
+                for (int h = 0; h < NSPLIT; ++h)
+#pragma unroll
+                    for (int ti = 0; ti < NI; ++ti)
+                        if (ncol[h] + 4 * ti < p.N)
+                            s += (acc[h][mi][ti][0] + acc[h][mi][ti][1]) + (acc[h][mi][ti][2] + acc[h][mi][ti][3]);
+                mean = n_ > 0.f ? s / n_ : 0.f;
+#pragma unroll
+                for (int h = 0; h < NSPLIT; ++h)
+#pragma unroll
+                    for (int ti = 0; ti < NI; ++ti)
+                        if (ncol[h] + 4 * ti < p.N) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float d = acc[h][mi][ti][e] - mean;
+                                m2 += d * d;
+                            }
+                        }
+                // lanes l, l^16, l^32, l^48 hold the same row
+#pragma unroll
+                for (int msk = 16; msk < 64; msk <<= 1) {
+                    const float nb = wave_shfl_xor(n_, msk), mb = wave_shfl_xor(mean, msk), m2b = wave_shfl_xor(m2, msk);
+                    // symmetric form so both partners compute identical bits
+                    const float nn = n_ + nb;
+                    if (nn > 0.f) {
+                        const float d = mb - mean;
+                        const float newmean = (n_ * mean + nb * mb) / nn;
+                        m2 = m2 + m2b + d * d * (n_ * nb / nn);
+                        mean = newmean;
+                    }
+                    n_ = nn;
+                }
+            } else {
+#pragma unroll
+                for (int h = 0; h < NSPLIT; ++h)
+#pragma unroll
+                    for (int ti = 0; ti < NI; ++ti)
+                        if (ncol[h] + 4 * ti < p.N) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) m2 += acc[h][mi][ti][e] * acc[h][mi][ti][e];
+                        }
+                m2 += wave_shfl_xor(m2, 16);
+                m2 += wave_shfl_xor(m2, 32);
+            }
+            if (WAVES_N > 1) {
+                const int row = wave_m * WM + mi * 16 + l16;
+                if (q == 0) {
+                    float* r3 = red + (row * WAVES_N + wave_n) * 3;
+                    r3[0] = n_; r3[1] = mean; r3[2] = m2;
+                }
+            }
+            mean_r[mi] = mean; rstd_r[mi] = m2;        // rstd_r holds M2 / sumsq until finalized
+            if (WAVES_N == 1 && EPI == EPI_ROW_IN_TILE) {
+                const float var = m2 / static_cast<float>(p.N);
+                rstd_r[mi] = 1.0f / sqrtf(var + p.eps);
+            }
+        }
+        if (WAVES_N > 1) {
+            __syncthreads();
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int row = wave_m * WM + mi * 16 + l16;
+                float n_ = 0.f, mean = 0.f, m2 = 0.f;
+#pragma unroll
+                for (int w = 0; w < WAVES_N; ++w) {             // fixed order: every wave gets identical bits
+                    const float* r3 = red + (row * WAVES_N + w) * 3;
+                    if (ln) merge_stats(n_, mean, m2, r3[0], r3[1], r3[2]);
+                    else m2 += r3[2];
+                }
+                mean_r[mi] = mean; rstd_r[mi] = m2;
+                if (EPI == EPI_ROW_IN_TILE) {
+                    const float var = m2 / static_cast<float>(p.N);
+                    rstd_r[mi] = 1.0f / sqrtf(var + p.eps);
+                }
+            }
+        }
+    }
+
+    if (EPI == EPI_PARTIAL_STATS) {
+        // the row spans several workgroups: publish this tile's (mean, M2) [or (sumsq, 0)] and leave the
+        // normalization to the second pass; Y has been stored above
+        if (p.norm != LOKA_NORM_NONE && wave_n == 0 && q == 0) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int m = m0 + wave_m * WM + mi * 16 + l16;
+                if (m < p.M) {
+                    float* dst = p.part + (static_cast<int64_t>(g) * p.M + m) * (2 * p.tiles_n) + 2 * tn;
+                    dst[0] = mean_r[mi];
+                    dst[1] = rstd_r[mi];
+                }
+            }
+        }
+        if (p.norm != LOKA_NORM_NONE) return;
+    }
+
+    // ---- normalize, affine, bf16 store
+    const bool has_g = p.gamma != nullptr, has_b = p.beta != nullptr && p.norm == LOKA_NORM_LAYERNORM;
+#pragma unroll
+    for (int h = 0; h < NSPLIT; ++h) {
+#pragma unroll
+        for (int tp = 0; tp < NI; tp += 2) {                    // two tiles = 8 columns = one 16-byte store
+            const int n = ncol[h] + 4 * tp;
+            if (n >= p.N) continue;
+            float gm[8], bt[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { gm[e] = 1.f; bt[e] = 0.f; }
+            if (has_g && p.norm != LOKA_NORM_NONE) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(p.gamma + n);
+                gm[0] = bf16_lo(w.x); gm[1] = bf16_hi(w.x); gm[2] = bf16_lo(w.y); gm[3] = bf16_hi(w.y);
+                gm[4] = bf16_lo(w.z); gm[5] = bf16_hi(w.z); gm[6] = bf16_lo(w.w); gm[7] = bf16_hi(w.w);
+            }
+            if (has_b) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(p.beta + n);
+                bt[0] = bf16_lo(w.x); bt[1] = bf16_hi(w.x); bt[2] = bf16_lo(w.y); bt[3] = bf16_hi(w.y);
+                bt[4] = bf16_lo(w.z); bt[5] = bf16_hi(w.z); bt[6] = bf16_lo(w.w); bt[7] = bf16_hi(w.w);
+            }
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int m = m0 + wave_m * WM + mi * 16 + l16;
+                if (m >= p.M) continue;
+                float o[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float yv = acc[h][mi][tp + (e >> 2)][e & 3];
+                    o[e] = (yv - mean_r[mi]) * rstd_r[mi];
+                    if (has_g && p.norm != LOKA_NORM_NONE) o[e] *= gm[e];
+                    if (has_b) o[e] += bt[e];
+                }
+                u32x4 pk;
+                pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
+                pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
+                *reinterpret_cast<u32x4*>(p.out + obase + static_cast<int64_t>(m) * p.N + n) = pk;
+            }
+        }
+    }
+}
+
+// Second pass of the two-pass schedule: combine the per-tile statistics of each row in a
+// fixed order and normalize fp32 Y into bf16 O.  One wave per row.
+__global__ __launch_bounds__(256) void norm_rows_kernel(const float* __restrict__ y, const float* __restrict__ part,
+                                                        int64_t rows, int N, int tiles_n, int tile_w, int norm,
+                                                        float eps, const uint16_t* __restrict__ gamma,
+                                                        const uint16_t* __restrict__ beta, uint16_t* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    float n_ = 0.f, mean = 0.f, m2 = 0.f;
+    for (int t = 0; t < tiles_n; ++t) {
+        const float a = part[r * 2 * tiles_n + 2 * t], b = part[r * 2 * tiles_n + 2 * t + 1];
+        const int w = (t + 1) * tile_w <= N ? tile_w : N - t * tile_w;
+        if (norm == LOKA_NORM_LAYERNORM) merge_stats(n_, mean, m2, static_cast<float>(w), a, b);
+        else m2 += b;
+    }
+    if (norm != LOKA_NORM_LAYERNORM) mean = 0.f;
+    const float rstd = 1.0f / sqrtf(m2 / static_cast<float>(N) + eps);
+    const bool has_b = beta != nullptr && norm == LOKA_NORM_LAYERNORM;
+    for (int c = lane * 8; c < N; c += 512) {
+        const v4f a = *reinterpret_cast<const v4f*>(y + r * N + c);
+        const v4f b = *reinterpret_cast<const v4f*>(y + r * N + c + 4);
+        float o[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+        float gm[8], bt[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { gm[e] = 1.f; bt[e] = 0.f; }
+        if (gamma) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(gamma + c);
+            gm[0] = bf16_lo(w.x); gm[1] = bf16_hi(w.x); gm[2] = bf16_lo(w.y); gm[3] = bf16_hi(w.y);
+            gm[4] = bf16_lo(w.z); gm[5] = bf16_hi(w.z); gm[6] = bf16_lo(w.w); gm[7] = bf16_hi(w.w);
+        }
+        if (has_b) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(beta + c);
+            bt[0] = bf16_lo(w.x); bt[1] = bf16_hi(w.x); bt[2] = bf16_lo(w.y); bt[3] = bf16_hi(w.y);
+            bt[4] = bf16_lo(w.z); bt[5] = bf16_hi(w.z); bt[6] = bf16_lo(w.w); bt[7] = bf16_hi(w.w);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            o[e] = (o[e] - mean) * rstd;
+            if (gamma) o[e] *= gm[e];
+            if (has_b) o[e] += bt[e];
+        }
+        u32x4 pk;
+        pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
+        pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
+        *reinterpret_cast<u32x4*>(out + r * N + c) = pk;
+    }
+}
+
+// [K, N] bf16 -> [N, K] bf16 (the reference GEMM reads K-contiguous operands like the FP8 one)
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ w, int K, int N,
+                                                             uint16_t* __restrict__ wt) {
+    __shared__ uint16_t tile[64][66];
+    const int k0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int kk = i >> 6, nn = i & 63;
+        if (k0 + kk < K && n0 + nn < N) tile[kk][nn] = w[static_cast<int64_t>(k0 + kk) * N + n0 + nn];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int nn = i >> 6, kk = i & 63;
+        if (k0 + kk < K && n0 + nn < N) wt[static_cast<int64_t>(n0 + nn) * K + k0 + kk] = tile[kk][nn];
+    }
+}
+
+// ------------------------------------------------------------------------------ host side
+struct VariantInfo {
+    const char* name;
+    int bm, bn;            // workgroup tile (bn = full width the tile covers)
+    int threads;
+    int epi;               // EPI_*
+    size_t lds;
+    void (*launch)(const GemmParams&, bool blockwise, dim3 grid, hipStream_t s);
+    const void* fn_plain;
+    const void* fn_block;
+};
+
+template <int BM, int BN_SUB, int NSPLIT, int WAVES_M, int WAVES_N, int EPI>
+static void launch_fp8(const GemmParams& p, bool blockwise, dim3 grid, hipStream_t s) {
+    constexpr size_t lds = 2 * (BM * 128 + BN_SUB * 128);
+    constexpr int threads = WAVES_M * WAVES_N * 64;
+    if (blockwise) gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, true, EPI><<<grid, threads, lds, s>>>(p);
+    else gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, false, EPI><<<grid, threads, lds, s>>>(p);
+}
+
+#define LOKA_VARIANT(NAME, BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, EPI)                                        \
+    {NAME, BM, BN_SUB * NSPLIT, WAVES_M * WAVES_N * 64, EPI, 2 * (BM * 128 + BN_SUB * 128),                  \
+     &launch_fp8<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, EPI>,                                                 \
+     reinterpret_cast<const void*>(&gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, false, EPI>),   \
+     reinterpret_cast<const void*>(&gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, true, EPI>)}
+
+static const VariantInfo kVariants[] = {
+    // rows normalized inside the tile (the tile spans the whole row)
+    LOKA_VARIANT("row32x128", 32, 128, 1, 1, 4, EPI_ROW_IN_TILE),
+    LOKA_VARIANT("row64x128", 64, 128, 1, 2, 2, EPI_ROW_IN_TILE),
+    LOKA_VARIANT("row64x256", 64, 256, 1, 1, 4, EPI_ROW_IN_TILE),
+    LOKA_VARIANT("row128x256", 128, 256, 1, 2, 4, EPI_ROW_IN_TILE),
+    LOKA_VARIANT("row64x512", 64, 512, 1, 1, 8, EPI_ROW_IN_TILE),
+    LOKA_VARIANT("row64x1024", 64, 512, 2, 1, 8, EPI_ROW_IN_TILE),
+    // rows spanning several workgroups: Y + per-tile statistics, then a normalization pass
+    LOKA_VARIANT("twopass128x128", 128, 128, 1, 2, 2, EPI_PARTIAL_STATS),
+    LOKA_VARIANT("twopass256x256", 256, 256, 1, 2, 2, EPI_PARTIAL_STATS),
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+int variant_count() { return kNumVariants; }
+const char* variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
+int variant_epilogue(int v) { return kVariants[v].epi; }
+int variant_bn(int v) { return kVariants[v].bn; }
+int variant_bm(int v) { return kVariants[v].bm; }
+
+bool variant_supports(const loka_gemm_desc* d, int v) {
+    if (v < 0 || v >= kNumVariants) return false;
+    const VariantInfo& vi = kVariants[v];
+    if (vi.epi == EPI_ROW_IN_TILE && d->N > vi.bn) return false;
+    const int64_t tiles = ((d->M + vi.bm - 1) / vi.bm) * ((d->N + vi.bn - 1) / vi.bn) * d->batch;
+    return tiles < (int64_t(1) << 31);
+}
+
+size_t variant_workspace(const loka_gemm_desc* d, int v) {
+    const VariantInfo& vi = kVariants[v];
+    if (vi.epi != EPI_PARTIAL_STATS || d->norm == LOKA_NORM_NONE) return 0;
+    const int64_t tiles_n = (d->N + vi.bn - 1) / vi.bn;
+    size_t stats = static_cast<size_t>(d->batch) * d->M * tiles_n * 2 * sizeof(float);
+    stats = (stats + 255) & ~size_t(255);
+    // fp32 Y staging for the normalization pass (used when the caller does not ask for Y)
+    return stats + static_cast<size_t>(d->batch) * d->M * d->N * sizeof(float);
+}
+
+static loka_status set_lds(const void* fn, size_t lds) {
+    LOKA_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    return LOKA_OK;
+}
+
+loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* xq, const float* sx, const uint8_t* wq,
+                                 const float* sw, const void* gamma, const void* beta, void* out, float* y,
+                                 void* workspace, hipStream_t s) {
+    const VariantInfo& vi = kVariants[v];
+    const bool blockwise = d->x_mode == LOKA_SCALE_BLOCK_1x128;
+    GemmParams p{};
+    p.X = xq; p.W = wq;
+    p.M = static_cast<int>(d->M); p.N = static_cast<int>(d->N); p.KB = static_cast<int>(d->K);
+    p.batch = static_cast<int>(d->batch);
+    p.strideX = d->strideX; p.strideW = d->strideW; p.strideO = d->strideO;
+    p.sx = sx; p.sw = sw;
+    p.strideSx = d->strideX ? loka_scale_count(static_cast<loka_scale_mode>(d->x_mode), d->M, d->K) : 0;
+    p.strideSw = d->strideW ? loka_scale_count(static_cast<loka_scale_mode>(d->w_mode), d->K, d->N) : 0;
+    p.x_mode = d->x_mode; p.w_mode = d->w_mode;
+    p.gamma = static_cast<const uint16_t*>(gamma); p.beta = static_cast<const uint16_t*>(beta);
+    p.out = static_cast<uint16_t*>(out); p.y = y;
+    p.norm = d->norm; p.eps = d->eps;
+    p.tiles_m = static_cast<int>((d->M + vi.bm - 1) / vi.bm);
+    p.tiles_n = static_cast<int>((d->N + vi.bn - 1) / vi.bn);
+    const bool two_pass = vi.epi == EPI_PARTIAL_STATS && d->norm != LOKA_NORM_NONE;
+    if (two_pass) {
+        size_t stats = static_cast<size_t>(d->batch) * d->M * p.tiles_n * 2 * sizeof(float);
+        stats = (stats + 255) & ~size_t(255);
+        p.part = static_cast<float*>(workspace);
+        if (!y) p.y = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + stats);
+    }
+    if (set_lds(blockwise ? vi.fn_block : vi.fn_plain, vi.lds) != LOKA_OK) return LOKA_ERR_HIP;
+    const dim3 grid(static_cast<unsigned>(static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.batch));
+    vi.launch(p, blockwise, grid, s);
+    if (two_pass) {
+        // with a strided batch the rows of all problems are contiguous only when strideO == M*N
+        for (int g = 0; g < p.batch; ++g) {
+            const float* yg = p.y + static_cast<int64_t>(g) * p.strideO;
+            const float* pg = p.part + static_cast<int64_t>(g) * d->M * p.tiles_n * 2;
+            uint16_t* og = p.out + static_cast<int64_t>(g) * p.strideO;
+            norm_rows_kernel<<<dim3(static_cast<unsigned>((d->M + 3) / 4)), 256, 0, s>>>(
+                yg, pg, d->M, p.N, p.tiles_n, vi.bn, d->norm, d->eps, p.gamma, p.beta, og);
+        }
+    }
+    return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
+}
+
+// BF16 reference GEMM: 128 x 128 tiles, fp32 Y only.
+size_t bf16_gemm_workspace_bytes(const loka_gemm_desc* d) {
+    const int64_t nw = d->strideW ? d->batch : 1;
+    return static_cast<size_t>(nw) * d->K * d->N * 2;
+}
+
+loka_status bf16_gemm_launch(const loka_gemm_desc* d, const void* x, const void* w, float* yref, void* workspace,
+                             hipStream_t s) {
+    uint16_t* wt = static_cast<uint16_t*>(workspace);
+    const int64_t nw = d->strideW ? d->batch : 1;
+    for (int64_t g = 0; g < nw; ++g) {
+        dim3 grid(static_cast<unsigned>((d->N + 63) / 64), static_cast<unsigned>((d->K + 63) / 64));
+        transpose_bf16_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(w) + g * d->strideW,
+                                                   static_cast<int>(d->K), static_cast<int>(d->N), wt + g * d->K * d->N);
+    }
+    constexpr int BM = 128, BN = 128;
+    GemmParams p{};
+    p.X = static_cast<const uint8_t*>(x); p.W = reinterpret_cast<const uint8_t*>(wt);
+    p.M = static_cast<int>(d->M); p.N = static_cast<int>(d->N); p.KB = static_cast<int>(d->K * 2);
+    p.batch = static_cast<int>(d->batch);
+    p.strideX = d->strideX * 2; p.strideW = d->strideW ? d->K * d->N * 2 : 0; p.strideO = d->strideO;
+    p.y = yref;
+    p.norm = LOKA_NORM_NONE;
+    p.tiles_m = static_cast<int>((d->M + BM - 1) / BM);
+    p.tiles_n = static_cast<int>((d->N + BN - 1) / BN);
+    auto fn = &gemm_kernel<BM, BN, 1, 2, 2, true, false, EPI_PARTIAL_STATS>;
+    constexpr size_t lds = 2 * (BM * 128 + BN * 128);
+    if (set_lds(reinterpret_cast<const void*>(fn), lds) != LOKA_OK) return LOKA_ERR_HIP;
+    const dim3 grid(static_cast<unsigned>(static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.batch));
+    fn<<<grid, 256, lds, s>>>(p);
+    return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
+}
+
+}  // namespace loka

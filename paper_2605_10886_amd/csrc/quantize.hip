@@ -1,0 +1,378 @@
+// amax -> scale -> OCP e4m3 cast of bf16 matrices (bandwidth-bound streaming kernels).
+//
+// ROW and BLOCK_1x128 scaling are single-pass: the lanes that share a scale group
+// keep their elements in registers between the amax reduction and the cast, so the
+// matrix is read once (2 B/elem) and the codes written once (1 B/elem).
+// TENSOR, COL and BLOCK_128x128 scaling need every row of a group before the first
+// cast: an amax pass (atomic max on the bit pattern of non-negative floats), a tiny
+// finalize kernel (scale = amax/448, inv = 448/amax, one division each), and a cast
+// pass that can also write the transposed layout used for weights.
+#include "common.h"
+
+namespace loka {
+
+// ---------------------------------------------------------------------------------
+// Single pass: TPR lanes share one row (TPR = 16, 32 or 64); each lane holds CPL
+// chunks of 8 consecutive bf16 (one 16-byte load each); a wave works on RU row sets at
+// once so that enough loads are in flight.  GW = lanes per scale group: TPR for ROW
+// scaling (one group per row), 16 for 1x128 blocks (16 lanes x 8 elements).
+template <int TPR, int CPL, int RU, bool BLOCK128>
+__global__ __launch_bounds__(256) void quant_rows_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                         int64_t ld, uint8_t* __restrict__ q,
+                                                         float* __restrict__ scales) {
+    constexpr int ROWS_PER_WAVE = (64 / TPR) * RU;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int lr = lane % TPR;               // lane within its row
+    const int sub = lane / TPR;              // which of the wave's concurrent rows
+    const int64_t chunks = cols >> 3;        // 8-element chunks per row
+    const int64_t row0 = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * ROWS_PER_WAVE;
+
+    u32x4 v[RU][CPL];
+#pragma unroll
+    for (int u = 0; u < RU; ++u) {
+        const int64_t r = row0 + u * (64 / TPR) + sub;
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const int64_t c = lr + static_cast<int64_t>(j) * TPR;
+            if (r < rows && c < chunks)
+                v[u][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + r * ld + c * 8));
+            else
+                v[u][j] = u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < RU; ++u) {
+        const int64_t r = row0 + u * (64 / TPR) + sub;
+        float am[CPL];
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const u32x4 w = v[u][j];
+            float a = fmaxf(fabsf(bf16_lo(w.x)), fabsf(bf16_hi(w.x)));
+            a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.y)), fabsf(bf16_hi(w.y))));
+            a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.z)), fabsf(bf16_hi(w.z))));
+            a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.w)), fabsf(bf16_hi(w.w))));
+            am[j] = a;
+        }
+        if (!BLOCK128) {
+#pragma unroll
+            for (int j = 1; j < CPL; ++j) am[0] = fmaxf(am[0], am[j]);
+#pragma unroll
+            for (int m = 1; m < TPR; m <<= 1) am[0] = fmaxf(am[0], wave_shfl_xor(am[0], m));
+        } else {
+#pragma unroll
+            for (int j = 0; j < CPL; ++j)
+#pragma unroll
+                for (int m = 1; m < 16; m <<= 1) am[j] = fmaxf(am[j], wave_shfl_xor(am[j], m));
+        }
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const int64_t c = lr + static_cast<int64_t>(j) * TPR;
+            float scale, inv;
+            group_scale(BLOCK128 ? am[j] : am[0], scale, inv);
+            if (r < rows && c < chunks) {
+                const u32x4 w = v[u][j];
+                u32x2 o;
+                o.x = e4m3x4(bf16_lo(w.x) * inv, bf16_hi(w.x) * inv, bf16_lo(w.y) * inv, bf16_hi(w.y) * inv);
+                o.y = e4m3x4(bf16_lo(w.z) * inv, bf16_hi(w.z) * inv, bf16_lo(w.w) * inv, bf16_hi(w.w) * inv);
+                __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(q + r * cols + c * 8));
+                if (BLOCK128) {
+                    if ((c & 15) == 0) scales[r * (cols >> 7) + (c >> 4)] = scale;
+                } else if (j == 0 && lr == 0) {
+                    scales[r] = scale;
+                }
+            }
+        }
+    }
+}
+
+// Rows longer than the register-resident kernel covers: one workgroup per row, two
+// sweeps over the row (the second one hits the cache).
+template <bool BLOCK128>
+__global__ __launch_bounds__(256) void quant_long_rows_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                              int64_t cols, int64_t ld, uint8_t* __restrict__ q,
+                                                              float* __restrict__ scales) {
+    __shared__ float red[4];
+    const int64_t r = blockIdx.x;
+    const int64_t chunks = cols >> 3;
+    const uint16_t* xr = x + r * ld;
+    float inv_row = 0.f;
+    if (!BLOCK128) {
+        float a = 0.f;
+        for (int64_t c = threadIdx.x; c < chunks; c += 256) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(xr + c * 8);
+            a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.x)), fabsf(bf16_hi(w.x))));
+            a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.y)), fabsf(bf16_hi(w.y))));
+            a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.z)), fabsf(bf16_hi(w.z))));
+            a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.w)), fabsf(bf16_hi(w.w))));
+        }
+        for (int m = 1; m < 64; m <<= 1) a = fmaxf(a, wave_shfl_xor(a, m));
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+        __syncthreads();
+        a = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        float scale;
+        group_scale(a, scale, inv_row);
+        if (threadIdx.x == 0) scales[r] = scale;
+    }
+    // chunks is a multiple of 16 for 1x128 blocks, so the 16 lanes of a group stay together
+    for (int64_t c0 = 0; c0 < chunks; c0 += 256) {
+        const int64_t c = c0 + threadIdx.x;
+        const bool ok = c < chunks;
+        u32x4 w = u32x4{0u, 0u, 0u, 0u};
+        if (ok) w = *reinterpret_cast<const u32x4*>(xr + c * 8);
+        float inv = inv_row;
+        if (BLOCK128) {
+            float a = fmaxf(fabsf(bf16_lo(w.x)), fabsf(bf16_hi(w.x)));
+            a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.y)), fabsf(bf16_hi(w.y))));
+            a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.z)), fabsf(bf16_hi(w.z))));
+            a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.w)), fabsf(bf16_hi(w.w))));
+            for (int m = 1; m < 16; m <<= 1) a = fmaxf(a, wave_shfl_xor(a, m));
+            float scale;
+            group_scale(a, scale, inv);
+            if (ok && (c & 15) == 0) scales[r * (cols >> 7) + (c >> 4)] = scale;
+        }
+        if (ok) {
+            u32x2 o;
+            o.x = e4m3x4(bf16_lo(w.x) * inv, bf16_hi(w.x) * inv, bf16_lo(w.y) * inv, bf16_hi(w.y) * inv);
+            o.y = e4m3x4(bf16_lo(w.z) * inv, bf16_hi(w.z) * inv, bf16_lo(w.w) * inv, bf16_hi(w.w) * inv);
+            *reinterpret_cast<u32x2*>(q + r * cols + c * 8) = o;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Multi-pass path.  Workspace layout: uint32 amax_bits[ng] followed by float inv[ng].
+__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
+    int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__device__ __forceinline__ float chunk_amax(const u32x4 w) {
+    float a = fmaxf(fabsf(bf16_lo(w.x)), fabsf(bf16_hi(w.x)));
+    a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.y)), fabsf(bf16_hi(w.y))));
+    a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.z)), fabsf(bf16_hi(w.z))));
+    return fmaxf(a, fmaxf(fabsf(bf16_lo(w.w)), fabsf(bf16_hi(w.w))));
+}
+
+// TENSOR: grid-stride over all chunks, one atomic per workgroup.
+__global__ __launch_bounds__(256) void amax_tensor_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                          int64_t ld, uint32_t* __restrict__ amax_bits) {
+    __shared__ float red[4];
+    const int64_t chunks = cols >> 3;
+    const int64_t total = rows * chunks;
+    float a = 0.f;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < total;
+         i += static_cast<int64_t>(gridDim.x) * 256) {
+        const int64_t r = i / chunks, c = i - r * chunks;
+        a = fmaxf(a, chunk_amax(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + r * ld + c * 8))));
+    }
+    for (int m = 1; m < 64; m <<= 1) a = fmaxf(a, wave_shfl_xor(a, m));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        atomicMax(amax_bits, __float_as_uint(a));
+    }
+}
+
+// COL: a workgroup owns 2048 columns x ROWS_PER_BLOCK rows; each thread keeps the
+// maxima of its 8 columns and publishes them with 8 atomics.
+constexpr int kColRowsPerBlock = 64;
+__global__ __launch_bounds__(256) void amax_col_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                       int64_t ld, uint32_t* __restrict__ amax_bits) {
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;      // chunk column
+    if (c >= (cols >> 3)) return;
+    const int64_t r0 = static_cast<int64_t>(blockIdx.y) * kColRowsPerBlock;
+    const int64_t r1 = r0 + kColRowsPerBlock < rows ? r0 + kColRowsPerBlock : rows;
+    float a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int64_t r = r0; r < r1; ++r) {
+        const u32x4 w = *reinterpret_cast<const u32x4*>(x + r * ld + c * 8);
+        a[0] = fmaxf(a[0], fabsf(bf16_lo(w.x))); a[1] = fmaxf(a[1], fabsf(bf16_hi(w.x)));
+        a[2] = fmaxf(a[2], fabsf(bf16_lo(w.y))); a[3] = fmaxf(a[3], fabsf(bf16_hi(w.y)));
+        a[4] = fmaxf(a[4], fabsf(bf16_lo(w.z))); a[5] = fmaxf(a[5], fabsf(bf16_hi(w.z)));
+        a[6] = fmaxf(a[6], fabsf(bf16_lo(w.w))); a[7] = fmaxf(a[7], fabsf(bf16_hi(w.w)));
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) atomicMax(amax_bits + c * 8 + j, __float_as_uint(a[j]));
+}
+
+// BLOCK_128x128: one workgroup per block, plain store (no atomics needed).
+__global__ __launch_bounds__(256) void amax_block128_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                            int64_t ld, uint32_t* __restrict__ amax_bits) {
+    __shared__ float red[4];
+    const int64_t bc = blockIdx.x, br = blockIdx.y;
+    const int cc = threadIdx.x & 15, rr = threadIdx.x >> 4;     // 16 chunks x 16 rows per sweep
+    float a = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const int64_t r = br * 128 + s * 16 + rr;
+        a = fmaxf(a, chunk_amax(*reinterpret_cast<const u32x4*>(x + r * ld + bc * 128 + cc * 8)));
+    }
+    for (int m = 1; m < 64; m <<= 1) a = fmaxf(a, wave_shfl_xor(a, m));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        amax_bits[br * (cols >> 7) + bc] = __float_as_uint(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])));
+}
+
+__global__ void finalize_scales_kernel(const uint32_t* __restrict__ amax_bits, float* __restrict__ inv,
+                                       float* __restrict__ scales, int64_t ng) {
+    int64_t g = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (g < ng) {
+        float s, i;
+        group_scale(__uint_as_float(amax_bits[g]), s, i);
+        scales[g] = s;
+        inv[g] = i;
+    }
+}
+
+// Cast pass.  MODE selects how a chunk finds its factor(s); TRANSPOSE writes q[c, r].
+template <int MODE>
+__device__ __forceinline__ void load_inv8(const float* __restrict__ inv, int64_t r, int64_t c8, int64_t cols,
+                                          float (&f)[8]) {
+    if (MODE == LOKA_SCALE_TENSOR) {
+        const float v = inv[0];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) f[j] = v;
+    } else if (MODE == LOKA_SCALE_COL) {
+        const float4 a = *reinterpret_cast<const float4*>(inv + c8);
+        const float4 b = *reinterpret_cast<const float4*>(inv + c8 + 4);
+        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+    } else {
+        const float v = inv[(r >> 7) * (cols >> 7) + (c8 >> 7)];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) f[j] = v;
+    }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void cast_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                   int64_t ld, const float* __restrict__ inv,
+                                                   uint8_t* __restrict__ q) {
+    const int64_t chunks = cols >> 3;
+    const int64_t total = rows * chunks;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < total;
+         i += static_cast<int64_t>(gridDim.x) * 256) {
+        const int64_t r = i / chunks, c = i - r * chunks;
+        const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + r * ld + c * 8));
+        float f[8];
+        load_inv8<MODE>(inv, r, c * 8, cols, f);
+        u32x2 o;
+        o.x = e4m3x4(bf16_lo(w.x) * f[0], bf16_hi(w.x) * f[1], bf16_lo(w.y) * f[2], bf16_hi(w.y) * f[3]);
+        o.y = e4m3x4(bf16_lo(w.z) * f[4], bf16_hi(w.z) * f[5], bf16_lo(w.w) * f[6], bf16_hi(w.w) * f[7]);
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(q + r * cols + c * 8));
+    }
+}
+
+// 64 x 64 tile through LDS; rows % 16 == 0 and cols % 16 == 0, so 16-row / 8-column
+// pieces are either fully inside or fully outside the matrix.
+template <int MODE>
+__global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                             int64_t ld, const float* __restrict__ inv,
+                                                             uint8_t* __restrict__ q) {
+    __shared__ uint8_t tile[64][64 + 16];        // [c][r], padded rows keep 16-byte alignment
+    const int64_t r0 = static_cast<int64_t>(blockIdx.y) * 64, c0 = static_cast<int64_t>(blockIdx.x) * 64;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int idx = threadIdx.x + s * 256;   // 512 chunks: 64 rows x 8 chunks
+        const int rr = idx >> 3, cc = (idx & 7) * 8;
+        const int64_t r = r0 + rr, c = c0 + cc;
+        if (r < rows && c < cols) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(x + r * ld + c);
+            float f[8];
+            load_inv8<MODE>(inv, r, c, cols, f);
+            const uint32_t lo = e4m3x4(bf16_lo(w.x) * f[0], bf16_hi(w.x) * f[1], bf16_lo(w.y) * f[2], bf16_hi(w.y) * f[3]);
+            const uint32_t hi = e4m3x4(bf16_lo(w.z) * f[4], bf16_hi(w.z) * f[5], bf16_lo(w.w) * f[6], bf16_hi(w.w) * f[7]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                tile[cc + j][rr] = static_cast<uint8_t>(lo >> (8 * j));
+                tile[cc + 4 + j][rr] = static_cast<uint8_t>(hi >> (8 * j));
+            }
+        }
+    }
+    __syncthreads();
+    const int cc = threadIdx.x >> 2, rr = (threadIdx.x & 3) * 16;
+    const int64_t c = c0 + cc, r = r0 + rr;
+    if (c < cols && r < rows)
+        *reinterpret_cast<u32x4*>(q + c * rows + r) = *reinterpret_cast<const u32x4*>(&tile[cc][rr]);
+}
+
+__global__ void e4m3_from_f32_kernel(const float* __restrict__ t, uint8_t* __restrict__ codes, int64_t n) {
+    int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) codes[i] = static_cast<uint8_t>(e4m3x4(t[i], 0.f, 0.f, 0.f) & 0xFFu);
+}
+
+// ---------------------------------------------------------------------------------
+template <bool B128>
+static void launch_rows(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, uint8_t* q, float* scales,
+                        hipStream_t s) {
+    const int64_t chunks = cols / 8;
+    auto grid = [&](int rows_per_wave) {
+        return dim3(static_cast<unsigned>((rows + 4 * rows_per_wave - 1) / (4 * rows_per_wave)));
+    };
+#define LOKA_QR(TPR, CPL, RU) \
+    quant_rows_kernel<TPR, CPL, RU, B128><<<grid((64 / TPR) * RU), 256, 0, s>>>(x, rows, cols, ld, q, scales)
+    if (chunks <= 16) LOKA_QR(16, 1, 2);
+    else if (chunks <= 32) LOKA_QR(32, 1, 4);
+    else if (chunks <= 64) LOKA_QR(64, 1, 8);
+    else if (chunks <= 128) LOKA_QR(64, 2, 4);
+    else if (chunks <= 256) LOKA_QR(64, 4, 2);
+    else if (chunks <= 512) LOKA_QR(64, 8, 1);
+    else if (chunks <= 1024) LOKA_QR(64, 16, 1);
+    else quant_long_rows_kernel<B128><<<dim3(static_cast<unsigned>(rows)), 256, 0, s>>>(x, rows, cols, ld, q, scales);
+#undef LOKA_QR
+}
+
+template <int MODE>
+static void launch_cast(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, const float* inv, uint8_t* q,
+                        int transpose_out, hipStream_t s) {
+    if (transpose_out) {
+        dim3 g(static_cast<unsigned>((cols + 63) / 64), static_cast<unsigned>((rows + 63) / 64));
+        cast_transpose_kernel<MODE><<<g, 256, 0, s>>>(x, rows, cols, ld, inv, q);
+    } else {
+        const int64_t total = rows * (cols / 8);
+        int64_t blocks = (total + 255) / 256;
+        if (blocks > 256 * 64) blocks = 256 * 64;
+        cast_kernel<MODE><<<dim3(static_cast<unsigned>(blocks)), 256, 0, s>>>(x, rows, cols, ld, inv, q);
+    }
+}
+
+loka_status quantize_launch(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, loka_scale_mode mode,
+                            int transpose_out, uint8_t* q, float* scales, void* workspace, hipStream_t s) {
+    const uint16_t* x = static_cast<const uint16_t*>(x_bf16);
+    if (!transpose_out && (mode == LOKA_SCALE_ROW || mode == LOKA_SCALE_BLOCK_1x128)) {
+        if (mode == LOKA_SCALE_ROW) launch_rows<false>(x, rows, cols, ld, q, scales, s);
+        else launch_rows<true>(x, rows, cols, ld, q, scales, s);
+        return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
+    }
+    const int64_t ng = loka_scale_count(mode, rows, cols);
+    uint32_t* amax_bits = static_cast<uint32_t*>(workspace);
+    float* inv = reinterpret_cast<float*>(amax_bits + ng);
+    if (mode == LOKA_SCALE_TENSOR) {
+        fill_u32_kernel<<<1, 64, 0, s>>>(amax_bits, 1, 0u);
+        const int64_t total = rows * (cols / 8);
+        int64_t blocks = (total + 255) / 256;
+        if (blocks > 256 * 16) blocks = 256 * 16;
+        amax_tensor_kernel<<<dim3(static_cast<unsigned>(blocks)), 256, 0, s>>>(x, rows, cols, ld, amax_bits);
+    } else if (mode == LOKA_SCALE_COL) {
+        fill_u32_kernel<<<dim3(static_cast<unsigned>((ng + 255) / 256)), 256, 0, s>>>(amax_bits, ng, 0u);
+        dim3 g(static_cast<unsigned>((cols / 8 + 255) / 256),
+               static_cast<unsigned>((rows + kColRowsPerBlock - 1) / kColRowsPerBlock));
+        amax_col_kernel<<<g, 256, 0, s>>>(x, rows, cols, ld, amax_bits);
+    } else {  // BLOCK_128x128
+        dim3 g(static_cast<unsigned>(cols / 128), static_cast<unsigned>(rows / 128));
+        amax_block128_kernel<<<g, 256, 0, s>>>(x, rows, cols, ld, amax_bits);
+    }
+    finalize_scales_kernel<<<dim3(static_cast<unsigned>((ng + 255) / 256)), 256, 0, s>>>(amax_bits, inv, scales, ng);
+    if (mode == LOKA_SCALE_TENSOR) launch_cast<LOKA_SCALE_TENSOR>(x, rows, cols, ld, inv, q, transpose_out, s);
+    else if (mode == LOKA_SCALE_COL) launch_cast<LOKA_SCALE_COL>(x, rows, cols, ld, inv, q, transpose_out, s);
+    else launch_cast<LOKA_SCALE_BLOCK_128x128>(x, rows, cols, ld, inv, q, transpose_out, s);
+    return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
+}
+
+loka_status e4m3_from_f32_launch(const float* t, uint8_t* codes, int64_t n, hipStream_t s) {
+    e4m3_from_f32_kernel<<<dim3(static_cast<unsigned>((n + 255) / 256)), 256, 0, s>>>(t, codes, n);
+    return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
+}
+
+}  // namespace loka

@@ -1,0 +1,270 @@
+"""GPU parity of loka_fp8_gemm_norm (and loka_bf16_gemm) against the CPU oracle.
+
+The GPU consumes the codes and scales its own loka_quantize produced; those are
+checked bit-exact against the oracle first, so both sides contract the same operands.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_10886_amd import binding as B
+from paper_2605_10886_amd import synth
+from parity_util import check_bf16_out, gemm_tolerance, propagated_abs_tol, rel_fro, to_np_bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+RECIPES = {"tensor": (B.SCALE_TENSOR, B.SCALE_TENSOR), "row": (B.SCALE_ROW, B.SCALE_COL),
+           "block": (B.SCALE_BLOCK_1x128, B.SCALE_BLOCK_128x128)}
+
+
+def _variants_for(desc):
+    return [v for v in range(B.loka_variant_count()) if B.loka_variant_supports(desc, v)]
+
+
+def _run_case(orc, x, w, recipe, norm, variant, gamma=None, beta=None, rows=None, tag=""):
+    """One problem, full GPU run; oracle on `rows` (all when None).  Returns measured error figures."""
+    M, K = x.shape
+    N = w.shape[1]
+    xm, wm = RECIPES[recipe]
+    xd, wd = x.to(DEV), w.to(DEV)
+    xq, sx = B.loka_quantize(xd, xm)
+    wq, sw = B.loka_quantize(wd, wm, transpose_out=True)
+    desc = B.make_desc(M, N, K, 1, xm, wm, B.NORMS[norm], 1e-5, variant)
+    gd = None if gamma is None else gamma.to(DEV)
+    bd = None if beta is None else beta.to(DEV)
+    out, y = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, gd, bd, want_y=True)
+    out2, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, gd, bd, want_y=False)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), f"{tag}: O differs with/without the Y store"
+
+    # oracle on the same operands (its own quantization, checked equal to the GPU's)
+    sel = np.arange(M) if rows is None else np.asarray(rows)
+    xb = synth.bf16_bits(x)
+    if xm == B.SCALE_TENSOR:
+        xq_o, sx_o = orc.quantize(xb, xm)
+        xq_o = xq_o[sel]
+    else:
+        xq_o, sx_o = orc.quantize(xb[sel].copy(), xm)
+    wq_o, sw_o = orc.quantize(synth.bf16_bits(w), wm, transpose_out=True)
+    idx = torch.from_numpy(sel).to(DEV)
+    assert np.array_equal(xq[idx].cpu().numpy(), xq_o), f"{tag}: X codes"
+    assert np.array_equal(wq.cpu().numpy(), wq_o), f"{tag}: W codes"
+    sx_g = sx.cpu().numpy()
+    if xm == B.SCALE_ROW:
+        sx_g = sx_g[sel]
+    elif xm == B.SCALE_BLOCK_1x128:
+        sx_g = sx_g.reshape(M, K // 128)[sel].ravel()
+    assert np.array_equal(sx_g, sx_o) and np.array_equal(sw.cpu().numpy(), sw_o), f"{tag}: scales"
+
+    y_o, absdot = orc.fp8_gemm(np.ascontiguousarray(xq_o), sx_o, xm, wq_o, sw_o, wm, want_absdot=True)
+    y_g = y[idx].cpu().numpy()
+    err = np.abs(y_g.astype(np.float64) - y_o.astype(np.float64))
+    tol = gemm_tolerance(absdot, y_o, K)
+    worst = float((err / np.maximum(tol, 1e-300)).max())
+    assert worst <= 1.0, f"{tag}: fp32 Y off by {worst:.3g} x tolerance"
+    fro = rel_fro(y_g, y_o)
+    assert fro <= 2e-4, f"{tag}: rel-Frobenius of Y vs oracle {fro:.3g}"
+
+    gb = None if gamma is None else synth.bf16_bits(gamma)
+    bb = None if beta is None else synth.bf16_bits(beta)
+    o_o = orc.norm(y_o, B.NORMS[norm], 1e-5, gb, bb)
+    o_g = to_np_bits(out[idx])
+    gam = None if gamma is None else gamma.float().numpy()
+    ok, worst_ulp, n_abs = check_bf16_out(o_g, o_o, abs_tol=propagated_abs_tol(y_o, err, B.NORMS[norm], 1e-5, gam))
+    assert ok, f"{tag}: bf16 O beyond 2 ulps (worst {worst_ulp})"
+    # isolate the norm arithmetic: the oracle's norm of the GPU's own Y must match within 1 ulp
+    o_iso = orc.norm(np.ascontiguousarray(y_g), B.NORMS[norm], 1e-5, gb, bb)
+    ok1, w1, _ = check_bf16_out(o_g, o_iso, max_ulp=1)
+    assert ok1, f"{tag}: norm arithmetic alone is off by {w1} ulps"
+    return {"y_rel_fro": fro, "y_worst_over_tol": worst, "o_worst_ulp": worst_ulp, "o_abs_clause": n_abs}
+
+
+# ----------------------------------------------------------------------------- small shapes, every variant
+@pytest.mark.parametrize("recipe", ["tensor", "row", "block"])
+@pytest.mark.parametrize("norm", ["layernorm", "rmsnorm", "none"])
+def test_c1_every_variant(orc, recipe, norm):
+    w = synth.WORKLOADS["C1"]
+    x, wt = synth.activations(w), synth.weights(w)
+    xm, wm = RECIPES[recipe]
+    desc = B.make_desc(w.M, w.N, w.K, 1, xm, wm, B.NORMS[norm])
+    vs = _variants_for(desc)
+    assert vs
+    for v in vs:
+        _run_case(orc, x, wt, recipe, norm, v, tag=f"C1 {recipe} {norm} {B.loka_variant_name(v)}")
+
+
+@pytest.mark.parametrize("shape", [(200, 128, 48), (77, 256, 240), (333, 384, 512), (130, 128, 1008), (64, 512, 2048)])
+def test_ragged_tiles_every_variant(orc, shape):
+    # M not a multiple of any tile height, N not a multiple of the tile width (but of 16), several K steps
+    M, K, N = shape
+    x = synth.student_t4(M, K, seed=M)
+    wt = synth.weight(K, N, seed=N)
+    gamma, beta = synth.affine(N, seed=3)
+    desc = B.make_desc(M, N, K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM)
+    for v in _variants_for(desc):
+        _run_case(orc, x, wt, "row", "layernorm", v, gamma, beta, tag=f"{shape} LN {B.loka_variant_name(v)}")
+        _run_case(orc, x, wt, "row", "rmsnorm", v, gamma, None, tag=f"{shape} RMS {B.loka_variant_name(v)}")
+
+
+def test_blockwise_ragged(orc):
+    M, K, N = 150, 384, 640
+    x, _ = synth.normal_outlier4(M, K, seed=8)
+    wt = synth.weight(K, N, seed=9)
+    desc = B.make_desc(M, N, K, 1, B.SCALE_BLOCK_1x128, B.SCALE_BLOCK_128x128, B.NORM_LAYERNORM)
+    for v in _variants_for(desc):
+        _run_case(orc, x, wt, "block", "layernorm", v, tag=f"block {B.loka_variant_name(v)}")
+
+
+def test_layernorm_rows_with_large_mean(orc):
+    # rows whose mean is far larger than their spread: the fused statistics must not cancel
+    M, K, N = 64, 128, 256
+    x = (synth.normal(M, K, seed=1).float() * 0.05 + 3.0).to(torch.bfloat16)
+    wt = (synth.weight(K, N, seed=2).float().abs() + 0.05).to(torch.bfloat16)
+    desc = B.make_desc(M, N, K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM)
+    for v in _variants_for(desc):
+        _run_case(orc, x, wt, "row", "layernorm", v, tag=f"large-mean {B.loka_variant_name(v)}")
+
+
+def test_scale_invariance_of_fused_norm():
+    # multiplying a row of X by a power of two changes sx only: codes and normalized output stay identical
+    # (RMSNorm / LayerNorm are invariant to input scaling up to eps)
+    M, K, N = 64, 256, 256
+    x = synth.normal(M, K, seed=4)
+    x2 = (x.float() * 8.0).to(torch.bfloat16)
+    wt = synth.weight(K, N, seed=5).to(DEV)
+    wq, sw = B.loka_quantize(wt, B.SCALE_COL, transpose_out=True)
+    desc = B.make_desc(M, N, K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM, eps=0.0)
+    q1, s1 = B.loka_quantize(x.to(DEV), B.SCALE_ROW)
+    q2, s2 = B.loka_quantize(x2.to(DEV), B.SCALE_ROW)
+    assert torch.equal(q1, q2) and torch.equal(s2, s1 * 8.0)
+    o1, _ = B.loka_fp8_gemm_norm(desc, q1, s1, wq, sw)
+    o2, _ = B.loka_fp8_gemm_norm(desc, q2, s2, wq, sw)
+    d = (o1.float() - o2.float()).abs().max().item()
+    assert d <= 2.0 ** -7                                     # at most 1 bf16 ulp at |o| ~ 1
+
+
+# ----------------------------------------------------------------------------- benchmark configurations, full size
+def _sample_rows(M, n=192):
+    rng = np.random.default_rng(M)
+    return np.unique(np.concatenate([np.arange(40), rng.integers(0, M, n), np.arange(M - 40, M)]))
+
+
+def test_c2_full_size_both_recipes(orc):
+    w = synth.WORKLOADS["C2"]
+    x, wt = synth.activations(w), synth.weights(w)
+    for recipe in ("row", "tensor"):
+        r = _run_case(orc, x, wt, recipe, w.norm, -1, rows=_sample_rows(w.M, 512), tag=f"C2 {recipe}")
+        print("C2", recipe, r)
+
+
+def test_c3_skinny_pair_chained(orc):
+    # layer a's LayerNorm output (bf16, from the GPU) is layer b's input, as in the configuration
+    wa, wb = synth.WORKLOADS["C3a"], synth.WORKLOADS["C3b"]
+    x, w1, w2 = synth.activations(wa), synth.weights(wa), synth.weights(wb)
+    rows = _sample_rows(wa.M, 160)
+    r = _run_case(orc, x, w1, "row", "layernorm", -1, rows=rows, tag="C3a")
+    print("C3a", r)
+    xq, sx = B.loka_quantize(x.to(DEV), B.SCALE_ROW)
+    wq, sw = B.loka_quantize(w1.to(DEV), B.SCALE_COL, transpose_out=True)
+    da = B.make_desc(wa.M, wa.N, wa.K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM)
+    h, _ = B.loka_fp8_gemm_norm(da, xq, sx, wq, sw)
+    r = _run_case(orc, h.cpu(), w2, "row", "layernorm", -1, rows=rows, tag="C3b")
+    print("C3b", r)
+
+
+def test_c4_grouped_launch(orc):
+    w = synth.WORKLOADS["C4"]
+    G = w.batch
+    xs = torch.cat([synth.activations(w, g) for g in range(G)], 0)          # [G*M, K]
+    ws = torch.cat([synth.weights(w, g) for g in range(G)], 0)              # [G*K, N]
+    xd, wd = xs.to(DEV), ws.to(DEV)
+    xq, sx = B.loka_quantize(xd, B.SCALE_ROW)                               # row-local: all groups at once
+    wq = torch.empty(G * w.N, w.K, dtype=torch.uint8, device=DEV)
+    sw = torch.empty(G * w.N, dtype=torch.float32, device=DEV)
+    for g in range(G):
+        q, s = B.loka_quantize(wd[g * w.K:(g + 1) * w.K], B.SCALE_COL, transpose_out=True)
+        wq[g * w.N:(g + 1) * w.N] = q
+        sw[g * w.N:(g + 1) * w.N] = s
+    desc = B.make_desc(w.M, w.N, w.K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM)
+    out, y = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, want_y=True)
+    torch.cuda.synchronize()
+    for g in (0, 1, 31, 63):
+        rows = _sample_rows(w.M, 64)
+        xb = synth.bf16_bits(xs[g * w.M:(g + 1) * w.M])[rows].copy()
+        xq_o, sx_o = orc.quantize(xb, B.SCALE_ROW)
+        wq_o, sw_o = orc.quantize(synth.bf16_bits(ws[g * w.K:(g + 1) * w.K]), B.SCALE_COL, transpose_out=True)
+        y_o, absdot = orc.fp8_gemm(xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, want_absdot=True)
+        idx = torch.from_numpy(rows + g * w.M).to(DEV)
+        assert np.array_equal(xq[idx].cpu().numpy(), xq_o)
+        y_g = y[idx].cpu().numpy()
+        err = np.abs(y_g.astype(np.float64) - y_o)
+        assert (err <= gemm_tolerance(absdot, y_o, w.K)).all(), f"group {g}"
+        o_o = orc.norm(y_o, B.NORM_RMSNORM)
+        ok, worst, _ = check_bf16_out(to_np_bits(out[idx]), o_o,
+                                      abs_tol=propagated_abs_tol(y_o, err, B.NORM_RMSNORM, 1e-5))
+        assert ok, f"group {g}: worst {worst} ulps"
+    # a single weight shared by all groups (strideW = 0) must equal group 0's weight applied to every group
+    desc0 = B.make_desc(w.M, w.N, w.K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM, shared_w=True)
+    out_s, _ = B.loka_fp8_gemm_norm(desc0, xq, sx, wq[:w.N], sw[:w.N])
+    d1 = B.make_desc(w.M, w.N, w.K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM)
+    out_1, _ = B.loka_fp8_gemm_norm(d1, xq[5 * w.M:6 * w.M], sx[5 * w.M:6 * w.M], wq[:w.N], sw[:w.N])
+    assert torch.equal(out_s[5 * w.M:6 * w.M].view(torch.int16), out_1.view(torch.int16))
+
+
+@pytest.mark.parametrize("recipe", ["row", "block", "tensor"])
+def test_c5_full_size(orc, recipe):
+    w = synth.WORKLOADS["C5"]
+    x, wt = synth.activations(w), synth.weights(w)
+    desc = B.make_desc(w.M, w.N, w.K, 1, *RECIPES[recipe], B.NORM_LAYERNORM)
+    rows = _sample_rows(w.M, 48)
+    if recipe == "tensor":
+        x = x[:4096].contiguous()                   # the oracle quantizes the whole tensor for this recipe
+        rows = _sample_rows(4096, 48)
+    for v in _variants_for(desc):
+        if recipe != "row" and v != B.loka_default_variant(desc):
+            continue
+        r = _run_case(orc, x, wt, recipe, "layernorm", v, rows=rows, tag=f"C5 {recipe} {B.loka_variant_name(v)}")
+        print("C5", recipe, B.loka_variant_name(v), r)
+
+
+def test_repeatable_bits():
+    # same inputs, 10 launches: identical output bits (catches LDS races / missing barriers)
+    w = synth.WORKLOADS["C2"]
+    x, wt = synth.activations(w, rows=2048).to(DEV), synth.weights(w).to(DEV)
+    xq, sx = B.loka_quantize(x, B.SCALE_ROW)
+    wq, sw = B.loka_quantize(wt, B.SCALE_COL, transpose_out=True)
+    for v in range(B.loka_variant_count()):
+        desc = B.make_desc(2048, w.N, w.K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM, variant=v)
+        if not B.loka_variant_supports(desc, v):
+            continue
+        ref, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+        for _ in range(10):
+            o, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+            assert torch.equal(o.view(torch.int16), ref.view(torch.int16)), B.loka_variant_name(v)
+
+
+# ----------------------------------------------------------------------------- BF16 reference GEMM
+@pytest.mark.parametrize("shape", [(256, 128, 128), (300, 192, 272), (1024, 512, 512)])
+def test_bf16_reference_gemm(orc, shape):
+    M, K, N = shape
+    x = synth.student_t4(M, K, seed=M + 1)
+    wt = synth.weight(K, N, seed=N + 1)
+    desc = B.make_desc(M, N, K, 1, norm=B.NORM_NONE)
+    y = B.loka_bf16_gemm(desc, x.to(DEV), wt.to(DEV)).cpu().numpy()
+    y_o = orc.ref_gemm(synth.bf16_bits(x), synth.bf16_bits(wt))
+    absdot = (x.double().abs() @ wt.double().abs()).numpy()
+    # exact bf16 products, fp32 accumulation in K/32 MFMA steps
+    tol = (K / 32 + 8) * 2.0 ** -24 * absdot + 2.0 ** -23 * np.abs(y_o)
+    assert (np.abs(y.astype(np.float64) - y_o) <= tol).all()
+    assert rel_fro(y, y_o) <= 1e-5
+
+
+def test_bf16_reference_gemm_grouped(orc):
+    G, M, K, N = 3, 200, 128, 144
+    x = synth.normal(G * M, K, seed=1)
+    wt = synth.weight(G * K, N, seed=2)
+    desc = B.make_desc(M, N, K, G, norm=B.NORM_NONE)
+    y = B.loka_bf16_gemm(desc, x.to(DEV), wt.to(DEV)).cpu().numpy()
+    for g in range(G):
+        y_o = orc.ref_gemm(synth.bf16_bits(x[g * M:(g + 1) * M]), synth.bf16_bits(wt[g * K:(g + 1) * K]))
+        assert rel_fro(y[g * M:(g + 1) * M], y_o) <= 1e-5
