@@ -38,8 +38,12 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     if ((u & 0x7F800000u) == 0x7F800000u) return (u >> 16) | ((u & 0x007FFFFFu) ? 0x40u : 0u);
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
+// Two fp32 -> packed bf16 (round-to-nearest-even) with the gfx950 convert instruction.
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+    const bf16x2_t v = __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, v);
 }
 
 // OCP e4m3 cast of four fp32 values (round-to-nearest-even by the gfx950 convert

@@ -15,13 +15,16 @@
 // cross-lane steps (lanes l, l^16, l^32, l^48 share a row).
 //
 // LDS rows are 128 bytes = 8 chunks of 16 bytes; chunk c of row r is stored at chunk
-// position c ^ key(r), with key chosen so that the 8 lanes a ds_read_b128 serves at
-// once hit 8 different chunk positions for both operand read patterns.
+// position c ^ key(r).  The LDS has 64 banks of 4 bytes and serves a ds_read_b128 sixteen
+// lanes at a time, so the 16 rows those lanes address must differ in (row parity, chunk
+// position): key(r) takes 8 values over the 8 same-parity rows of each operand's read pattern.
 #include "common.h"
+
+#include <cstdlib>
 
 namespace loka {
 
-enum { EPI_ROW_IN_TILE = 0, EPI_PARTIAL_STATS = 1 };
+enum { EPI_ROW_IN_TILE = 0, EPI_PARTIAL_STATS = 1, EPI_PANEL_SYNC = 2 };
 
 struct GemmParams {
     const uint8_t* X;      // [batch][M][KB] bytes (KB = K for FP8, 2K for BF16)
@@ -41,15 +44,25 @@ struct GemmParams {
     int norm;
     float eps;
     int tiles_m, tiles_n;
-    float* part;           // EPI_PARTIAL_STATS: [batch][M][tiles_n * 2] (mean, M2) or (sumsq, -)
+    float* part;           // EPI_PARTIAL_STATS / EPI_PANEL_SYNC: [batch][M][tiles_n * 2] (mean, M2) or (0, sumsq)
+    unsigned* counters;    // EPI_PANEL_SYNC: arrivals per (problem, m tile), zeroed before the launch
+    unsigned* error_flag;  // EPI_PANEL_SYNC: set when a bounded wait ran out
+    unsigned spin_limit;
 };
+
+#ifdef LOKA_DEBUG_TIMES
+__device__ unsigned long long loka_dbg_times[8 * 4096];
+#define LOKA_STAMP(slot) do { if (threadIdx.x == 0 && tile < 4096) loka_dbg_times[tile * 8 + (slot)] = wall_clock64(); } while (0)
+#else
+#define LOKA_STAMP(slot) do { } while (0)
+#endif
 
 // Chan's pairwise merge of (count, mean, M2).
 __device__ __forceinline__ void merge_stats(float& n, float& mean, float& m2, float nb, float mb, float m2b) {
     const float nn = n + nb;
     if (nb > 0.f) {
         const float d = mb - mean;
-        const float f = nb / nn;          // nn > 0 here
+        const float f = nb * __builtin_amdgcn_rcpf(nn);   // nn > 0 here; 1-ulp reciprocal (an IEEE divide costs ~300 cycles)
         mean = mean + d * f;
         m2 = m2 + m2b + d * d * n * f;
         n = nn;
@@ -80,8 +93,21 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
     const int l16 = lane & 15, q = lane >> 4;
 
-    // tile coordinates: blockIdx.x enumerates (problem, m tile, n tile), n fastest
-    int t = blockIdx.x;
+    // Tiles are enumerated (problem, m tile, n tile), n fastest.  The one-tile-per-workgroup schedules
+    // take tile blockIdx.x.  The panel-synchronous schedule is persistent: gridDim.x (a multiple of
+    // tiles_n, all co-resident) workgroups walk the tile list in rounds of gridDim.x tiles, so the
+    // tiles_n workgroups that share a row panel always run in the same round.  Workgroups are handed
+    // to the 8 XCDs round-robin; logical slot (id % 8) * (grid / 8) + id / 8 keeps a panel's
+    // workgroups (and the W tiles they stream) on one XCD's L2 when grid is a multiple of 8 * tiles_n.
+    const int total_tiles = p.tiles_m * p.tiles_n * p.batch;
+    int tile_first = blockIdx.x, tile_stride = total_tiles;
+    if (EPI == EPI_PANEL_SYNC) {
+        const int G = gridDim.x;
+        tile_first = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+        tile_stride = G;
+    }
+  for (int tile = tile_first; tile < total_tiles; tile += tile_stride) {
+    int t = tile;
     const int tn = t % p.tiles_n; t /= p.tiles_n;
     const int tm = t % p.tiles_m;
     const int g = t / p.tiles_m;
@@ -92,41 +118,59 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
 
     // ---- loader: one wave-load moves 8 rows x 128 B; lane -> (row lane/8, chunk position lane%8)
     const int ld_row = lane >> 3, ld_pos = lane & 7;
-    // X rows: key(r) = r & 7  (rows of an 8-row group starting at a multiple of 8)
-    const int x_chunk = ld_pos ^ ld_row;
-    // W rows: key(r) = (r & 3) | (((r_local / RUN) & 1) << 2), r_local = r % WN
-    auto w_key = [](int r) { return (r & 3) | ((((r % WN) / RUN) & 1) << 2); };
+    // X rows are read 16 consecutive rows at a time: key(r) = (r >> 1) & 7
+    auto x_key = [](int r) { return (r >> 1) & 7; };
+    // W rows are read as rows g*RUN + 4t + i (g = 0..3, i = 0..3) of a wave's WN rows:
+    // key(r) = ((r >> 1) & 1) | (((r_local / RUN) & 3) << 1), r_local = r % WN
+    auto w_key = [](int r) { return ((r >> 1) & 1) | ((((r % WN) / RUN) & 3) << 1); };
 
-    auto issue_x = [&](int stage, int kb) {
-        constexpr int GROUPS = BM / 8;
-#pragma unroll
-        for (int j = 0; j < (GROUPS + NW - 1) / NW; ++j) {
-            const int grp = wave + j * NW;
-            if (GROUPS % NW == 0 || grp < GROUPS) {
-                int r = m0 + grp * 8 + ld_row;
-                r = r < p.M ? r : p.M - 1;
-                const uint8_t* src = Xg + static_cast<int64_t>(r) * p.KB + kb + x_chunk * 16;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                                 (__attribute__((address_space(3))) void*)(xbuf + stage * XS + grp * 1024),
+    // The X and W groups of a stage form one list; wave w owns entries w, w + NW, ...; entry j of a
+    // wave can be issued on its own so the loads are spread between the MFMAs of the running stage.
+    // Addressing: a uniform 64-bit base (problem, tile row group, K offset) in scalar registers plus one
+    // 32-bit per-lane offset, so no per-load address registers stay live across the main loop.  The
+    // lane offset is (row-in-group * KB + chunk * 16); the group-dependent part of the swizzle key only
+    // flips bits 5..6 of it (an xor with a uniform value).  Groups that reach past the last valid row
+    // (ragged M or N tail) re-read the last valid row instead: their results are never stored.
+    constexpr int XG = BM / 8, WGR = BN_SUB / 8, TOT = XG + WGR;
+    constexpr int JN = (TOT + NW - 1) / NW;
+    const unsigned x_lane_off = static_cast<unsigned>(ld_row) * p.KB + ((ld_pos ^ (ld_row >> 1)) << 4);
+    const unsigned w_lane_off = static_cast<unsigned>(ld_row) * p.KB + ((ld_pos ^ ((ld_row >> 1) & 1)) << 4);
+    auto issue_j = [&](int j, int stage_x, int stage_w, int kb, int h, bool with_x) {
+        const int idx = wave + j * NW;                        // wave-uniform
+        if (idx < XG) {
+            if (with_x) {
+                const int row0 = m0 + idx * 8;                // uniform
+                unsigned voff = x_lane_off ^ ((idx & 1) << 6);
+                const uint8_t* base;
+                if (row0 + 8 <= p.M) {
+                    base = Xg + static_cast<int64_t>(row0) * p.KB + kb;
+                } else {                                      // tail group: clamp each lane's row
+                    int r = row0 + ld_row;
+                    r = r < p.M ? r : p.M - 1;
+                    base = Xg + kb;
+                    voff = static_cast<unsigned>(r) * p.KB + ((voff & 127u));
+                }
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + voff),
+                                                 (__attribute__((address_space(3))) void*)(xbuf + stage_x * XS + idx * 1024),
                                                  16, 0, 0);
             }
-        }
-    };
-    auto issue_w = [&](int stage, int kb, int h) {
-        constexpr int GROUPS = BN_SUB / 8;
-#pragma unroll
-        for (int j = 0; j < (GROUPS + NW - 1) / NW; ++j) {
-            const int grp = wave + j * NW;
-            if (GROUPS % NW == 0 || grp < GROUPS) {
-                const int rl = grp * 8 + ld_row;              // row inside the W stage
-                int r = n0 + h * BN_SUB + rl;
+        } else if (TOT % NW == 0 || idx < TOT) {
+            const int grp = idx - XG;
+            const int row0 = n0 + h * BN_SUB + grp * 8;       // uniform
+            const int ukey = (((grp * 8) % WN) / RUN) & 3;    // uniform part of the W swizzle key
+            unsigned voff = w_lane_off ^ (ukey << 5);
+            const uint8_t* base;
+            if (row0 + 8 <= p.N) {
+                base = Wg + static_cast<int64_t>(row0) * p.KB + kb;
+            } else {
+                int r = row0 + ld_row;
                 r = r < p.N ? r : p.N - 1;
-                const int chunk = ld_pos ^ w_key(rl);
-                const uint8_t* src = Wg + static_cast<int64_t>(r) * p.KB + kb + chunk * 16;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                                 (__attribute__((address_space(3))) void*)(wbuf + stage * WS + grp * 1024),
-                                                 16, 0, 0);
+                base = Wg + kb;
+                voff = static_cast<unsigned>(r) * p.KB + (voff & 127u);
             }
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + voff),
+                                             (__attribute__((address_space(3))) void*)(wbuf + stage_w * WS + grp * 1024),
+                                             16, 0, 0);
         }
     };
 
@@ -135,7 +179,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     // as both operands use the same one).  BF16: two MFMAs per 128-byte row, lane chunk q and 4+q.
     const int c0 = IS_BF16 ? q : 2 * q, c1 = IS_BF16 ? 4 + q : 2 * q + 1;
     const int xrow = wave_m * WM + l16;                         // + mi * 16
-    const int xkey = xrow & 7;
+    const int xkey = x_key(xrow);
     const int x_off0 = xrow * 128 + ((c0 ^ xkey) << 4), x_off1 = xrow * 128 + ((c1 ^ xkey) << 4);
     const int wrow = wave_n * WN + (l16 >> 2) * RUN + (l16 & 3);  // + 4 * t
     const int wkey = w_key(wrow);
@@ -156,18 +200,20 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     const float* sxg = p.sx + static_cast<int64_t>(g) * p.strideSx;
     const float* swg = p.sw + static_cast<int64_t>(g) * p.strideSw;
 
-    issue_x(0, 0);
-    issue_w(0, 0, 0);
+    LOKA_STAMP(0);
+#pragma unroll
+    for (int j = 0; j < JN; ++j) issue_j(j, 0, 0, 0, 0, true);
+
+    // loads of the next stage are issued in the first ISSUE_STEPS tile steps of the running stage
+    constexpr int ISSUE_STEPS = NI >= 4 ? NI / 2 : NI;
+    constexpr int J_PER_STEP = (JN + ISSUE_STEPS - 1) / ISSUE_STEPS;
 
     for (int it = 0; it < iters; ++it) {
         const int k = it / NSPLIT, h = it % NSPLIT;
         __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0): this wave's loads for stage `it` have landed
         __syncthreads();                                        // everyone's have; everyone left iteration it-1
-        if (it + 1 < iters) {
-            const int k1 = (it + 1) / NSPLIT, h1 = (it + 1) % NSPLIT;
-            issue_w((it + 1) & 1, k1 * 128, h1);
-            if (h1 == 0) issue_x(k1 & 1, k1 * 128);
-        }
+        const bool more = it + 1 < iters;
+        const int k1 = (it + 1) / NSPLIT, h1 = (it + 1) % NSPLIT;
         const uint8_t* xs = xbuf + (k & 1) * XS;
         const uint8_t* ws = wbuf + (it & 1) * WS;
 
@@ -196,10 +242,21 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                 nrun = nrun < p.N ? nrun : p.N - 1;
                 swk = swg[static_cast<int64_t>(k) * (p.N >> 7) + (nrun >> 7)];
             }
+            // W fragments are fetched one tile ahead of the MFMAs that consume them
+            v4i lo = *reinterpret_cast<const v4i*>(ws + w_off0);
+            v4i hi = *reinterpret_cast<const v4i*>(ws + w_off1);
 #pragma unroll
             for (int ti = 0; ti < NI; ++ti) {
-                const v4i lo = *reinterpret_cast<const v4i*>(ws + w_off0 + ti * 4 * 128);
-                const v4i hi = *reinterpret_cast<const v4i*>(ws + w_off1 + ti * 4 * 128);
+                if (more && ti < ISSUE_STEPS) {
+#pragma unroll
+                    for (int j = ti * J_PER_STEP; j < (ti + 1) * J_PER_STEP && j < JN; ++j)
+                        issue_j(j, k1 & 1, (it + 1) & 1, k1 * 128, h1, h1 == 0);
+                }
+                v4i lo_n = lo, hi_n = hi;
+                if (ti + 1 < NI) {
+                    lo_n = *reinterpret_cast<const v4i*>(ws + w_off0 + (ti + 1) * 4 * 128);
+                    hi_n = *reinterpret_cast<const v4i*>(ws + w_off1 + (ti + 1) * 4 * 128);
+                }
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi) {
                     if (IS_BF16) {
@@ -225,6 +282,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                         }
                     }
                 }
+                lo = lo_n;
+                hi = hi_n;
             }
         }
     }
@@ -232,6 +291,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     // ------------------------------------------------------------------ epilogue
     // lane owns row m (per mi) and, per N-part h, columns ncol(h) + [0, RUN)
     __syncthreads();                       // all waves are done reading the stages: LDS is free
+    LOKA_STAMP(1);
     float* red = reinterpret_cast<float*>(smem);   // [BM][WAVES_N][3]
     const int64_t obase = static_cast<int64_t>(g) * p.strideO;
     const bool tensor_x = p.x_mode == LOKA_SCALE_TENSOR, tensor_w = p.w_mode == LOKA_SCALE_TENSOR;
@@ -286,9 +346,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
             }
         }
     }
-    if (IS_BF16) return;                   // reference GEMM: fp32 Y only
+    if (IS_BF16) continue;                 // reference GEMM: fp32 Y only
 
-    // ---- row statistics
+    // ---- row statistics (reciprocals and the inverse square root are the 1-ulp hardware ones: their
+    // error is four orders of magnitude below a bf16 ulp, and the IEEE sequences are ~300 cycles each)
+    const float inv_n = 1.0f / static_cast<float>(p.N);
     float mean_r[MI], rstd_r[MI];
     if (p.norm == LOKA_NORM_NONE) {
 #pragma unroll
@@ -306,7 +368,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                     for (int ti = 0; ti < NI; ++ti)
                         if (ncol[h] + 4 * ti < p.N)
                             s += (acc[h][mi][ti][0] + acc[h][mi][ti][1]) + (acc[h][mi][ti][2] + acc[h][mi][ti][3]);
-                mean = n_ > 0.f ? s / n_ : 0.f;
+                mean = n_ > 0.f ? s * __builtin_amdgcn_rcpf(n_) : 0.f;
 #pragma unroll
                 for (int h = 0; h < NSPLIT; ++h)
 #pragma unroll
@@ -326,8 +388,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                     const float nn = n_ + nb;
                     if (nn > 0.f) {
                         const float d = mb - mean;
-                        const float newmean = (n_ * mean + nb * mb) / nn;
-                        m2 = m2 + m2b + d * d * (n_ * nb / nn);
+                        const float rn = __builtin_amdgcn_rcpf(nn);
+                        const float newmean = (n_ * mean + nb * mb) * rn;
+                        m2 = m2 + m2b + d * d * (n_ * nb * rn);
                         mean = newmean;
                     }
                     n_ = nn;
@@ -353,8 +416,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
             }
             mean_r[mi] = mean; rstd_r[mi] = m2;        // rstd_r holds M2 / sumsq until finalized
             if (WAVES_N == 1 && EPI == EPI_ROW_IN_TILE) {
-                const float var = m2 / static_cast<float>(p.N);
-                rstd_r[mi] = 1.0f / sqrtf(var + p.eps);
+                rstd_r[mi] = __builtin_amdgcn_rsqf(m2 * inv_n + p.eps);
             }
         }
         if (WAVES_N > 1) {
@@ -371,8 +433,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                 }
                 mean_r[mi] = mean; rstd_r[mi] = m2;
                 if (EPI == EPI_ROW_IN_TILE) {
-                    const float var = m2 / static_cast<float>(p.N);
-                    rstd_r[mi] = 1.0f / sqrtf(var + p.eps);
+                    rstd_r[mi] = __builtin_amdgcn_rsqf(m2 * inv_n + p.eps);
                 }
             }
         }
@@ -392,9 +453,118 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                 }
             }
         }
-        if (p.norm != LOKA_NORM_NONE) return;
+        if (p.norm != LOKA_NORM_NONE) continue;
     }
 
+    if (EPI == EPI_PANEL_SYNC && p.norm != LOKA_NORM_NONE) {
+        // The row spans tiles_n workgroups that run in the same round.  Each publishes its tile's
+        // (mean, M2) [or (0, sumsq)] per row, bumps the panel's arrival counter, waits until all
+        // tiles_n have arrived, and merges every tile's statistics in one fixed order, so all of them
+        // normalize with identical row statistics.  Only these few words per row leave the CU.
+        LOKA_STAMP(2);
+        const int panel = g * p.tiles_m + tm;
+        float* prow = p.part + (static_cast<int64_t>(g) * p.M) * (2 * p.tiles_n);
+        if (wave_n == 0 && q == 0) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int m = m0 + wave_m * WM + mi * 16 + l16;
+                if (m < p.M) {
+                    float* dst = prow + static_cast<int64_t>(m) * (2 * p.tiles_n) + 2 * tn;
+                    // device-coherent (write-through) stores: no L2-wide write-back is needed to publish them
+                    __hip_atomic_store(dst, mean_r[mi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(dst + 1, rstd_r[mi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the stores have completed before the barrier
+        }
+        __syncthreads();
+        LOKA_STAMP(3);
+        if (threadIdx.x == 0) {
+            unsigned* ctr = p.counters + panel;
+            // the publishers' stores completed before the barrier, so a relaxed add orders after them;
+            // polling is relaxed too (an acquiring poll would invalidate the L2 under the neighbours' main loops)
+            __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // bounded wait: every workgroup of the panel is resident, so this ends after the slowest
+            // one's main loop; the limit only turns a scheduling surprise into an error flag
+            unsigned spins = 0;
+            while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < static_cast<unsigned>(p.tiles_n)) {
+                __builtin_amdgcn_s_sleep(16);
+                if (++spins > p.spin_limit) {
+                    __hip_atomic_store(p.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+            }
+        }
+        __syncthreads();
+        LOKA_STAMP(4);
+        const bool ln = p.norm == LOKA_NORM_LAYERNORM;
+        // Merge: the workgroup's BM rows are spread over its threads (TPR threads per row, each folding a
+        // contiguous share of the row's tiles_n entries in order, read with device-coherent 8-byte loads
+        // that bypass stale cache lines); shares are combined with the symmetric merge, the row's final
+        // (mean, rstd) goes through LDS to the lanes that own the row.  Every workgroup of the panel runs
+        // the same procedure on the same words, so all of them normalize with identical statistics.
+        {
+            constexpr int T = NW * 64, TPR = T / BM >= 1 ? T / BM : 1;
+            static_assert(T % BM == 0 || T < BM, "threads per row");
+            float2* fin = reinterpret_cast<float2*>(smem) + BM * WAVES_N * 3 / 2 + 8;   // after `red`
+            for (int r0 = 0; r0 < BM; r0 += T / TPR) {
+                const int r = r0 + static_cast<int>(threadIdx.x) / TPR, sub = static_cast<int>(threadIdx.x) % TPR;
+                int m = m0 + r;
+                m = m < p.M ? m : p.M - 1;
+                const float* src = prow + static_cast<int64_t>(m) * (2 * p.tiles_n);
+                const int TH = (p.tiles_n + TPR - 1) / TPR;
+                float n_ = 0.f, mean = 0.f, m2 = 0.f;
+                for (int t0 = sub * TH; t0 < (sub + 1) * TH && t0 < p.tiles_n; t0 += 8) {
+                    unsigned long long raw[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        int tt = t0 + u;
+                        tt = tt < p.tiles_n ? tt : p.tiles_n - 1;
+                        raw[u] = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src + 2 * tt),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int tt = t0 + u;
+                        if (tt < (sub + 1) * TH && tt < p.tiles_n) {
+                            const float a = __uint_as_float(static_cast<unsigned>(raw[u]));
+                            const float b2 = __uint_as_float(static_cast<unsigned>(raw[u] >> 32));
+                            const int wcols = (tt + 1) * BN <= p.N ? BN : p.N - tt * BN;
+                            if (ln) merge_stats(n_, mean, m2, static_cast<float>(wcols), a, b2);
+                            else m2 += b2;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int msk = 1; msk < TPR; msk <<= 1) {
+                    const float nb = wave_shfl_xor(n_, msk), mb = wave_shfl_xor(mean, msk), m2b = wave_shfl_xor(m2, msk);
+                    if (ln) {
+                        const float nn = n_ + nb;
+                        if (nn > 0.f) {
+                            const float d = mb - mean;
+                            const float rn = __builtin_amdgcn_rcpf(nn);
+                            const float newmean = (n_ * mean + nb * mb) * rn;
+                            m2 = m2 + m2b + d * d * (n_ * nb * rn);
+                            mean = newmean;
+                        }
+                        n_ = nn;
+                    } else {
+                        m2 = m2 + m2b;
+                    }
+                }
+                if (sub == 0 && r < BM) fin[r] = make_float2(ln ? mean : 0.f, __builtin_amdgcn_rsqf(m2 * inv_n + p.eps));
+            }
+            __syncthreads();
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const float2 f = fin[wave_m * WM + mi * 16 + l16];
+                mean_r[mi] = f.x;
+                rstd_r[mi] = f.y;
+            }
+        }
+    }
+
+    LOKA_STAMP(5);
     // ---- normalize, affine, bf16 store
     const bool has_g = p.gamma != nullptr, has_b = p.beta != nullptr && p.norm == LOKA_NORM_LAYERNORM;
 #pragma unroll
@@ -431,10 +601,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                 u32x4 pk;
                 pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
                 pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
-                *reinterpret_cast<u32x4*>(p.out + obase + static_cast<int64_t>(m) * p.N + n) = pk;
+                u32x4* dst = reinterpret_cast<u32x4*>(p.out + obase + static_cast<int64_t>(m) * p.N + n);
+                if (EPI == EPI_PANEL_SYNC) __builtin_nontemporal_store(pk, dst);   // streamed: keeps X / W in the L2
+                else *dst = pk;
             }
         }
     }
+    LOKA_STAMP(6);
+  }  // tile loop
 }
 
 // Second pass of the two-pass schedule: combine the per-tile statistics of each row in a
@@ -539,8 +713,21 @@ static const VariantInfo kVariants[] = {
     // rows spanning several workgroups: Y + per-tile statistics, then a normalization pass
     LOKA_VARIANT("twopass128x128", 128, 128, 1, 2, 2, EPI_PARTIAL_STATS),
     LOKA_VARIANT("twopass256x256", 256, 256, 1, 2, 2, EPI_PARTIAL_STATS),
+    LOKA_VARIANT("twopass256x256w8", 256, 256, 1, 2, 4, EPI_PARTIAL_STATS),
+    // persistent, panel-synchronous: the tiles_n workgroups of a row panel exchange row statistics
+    // through a few words of global memory and normalize their own tile in registers
+    LOKA_VARIANT("panel256x256", 256, 256, 1, 2, 2, EPI_PANEL_SYNC),
+    LOKA_VARIANT("panel256x256w8", 256, 256, 1, 2, 4, EPI_PANEL_SYNC),
 };
+constexpr int kNumCUs = 256;          // MI355X; the launch re-checks against the device it runs on
+constexpr unsigned kSpinLimit = 1u << 18;   // x s_sleep(16) ~ 0.1 s: far beyond any main loop
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+#ifdef LOKA_DEBUG_TIMES
+extern "C" int loka_debug_read_times(unsigned long long* host, int n) {
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(loka_dbg_times), sizeof(unsigned long long) * n) == hipSuccess ? 0 : 1;
+}
+#endif
 
 int variant_count() { return kNumVariants; }
 const char* variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
@@ -552,18 +739,38 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
     if (v < 0 || v >= kNumVariants) return false;
     const VariantInfo& vi = kVariants[v];
     if (vi.epi == EPI_ROW_IN_TILE && d->N > vi.bn) return false;
+    if (vi.epi == EPI_PANEL_SYNC && (d->N + vi.bn - 1) / vi.bn > kNumCUs) return false;
     const int64_t tiles = ((d->M + vi.bm - 1) / vi.bm) * ((d->N + vi.bn - 1) / vi.bn) * d->batch;
     return tiles < (int64_t(1) << 31);
 }
 
 size_t variant_workspace(const loka_gemm_desc* d, int v) {
     const VariantInfo& vi = kVariants[v];
-    if (vi.epi != EPI_PARTIAL_STATS || d->norm == LOKA_NORM_NONE) return 0;
+    if (vi.epi == EPI_ROW_IN_TILE || d->norm == LOKA_NORM_NONE) return 0;
     const int64_t tiles_n = (d->N + vi.bn - 1) / vi.bn;
     size_t stats = static_cast<size_t>(d->batch) * d->M * tiles_n * 2 * sizeof(float);
     stats = (stats + 255) & ~size_t(255);
+    if (vi.epi == EPI_PANEL_SYNC) {
+        // [error flag, 256 B][arrival counters][per-tile row statistics]
+        const int64_t panels = d->batch * ((d->M + vi.bm - 1) / vi.bm);
+        return 256 + ((static_cast<size_t>(panels) * 4 + 255) & ~size_t(255)) + stats;
+    }
     // fp32 Y staging for the normalization pass (used when the caller does not ask for Y)
     return stats + static_cast<size_t>(d->batch) * d->M * d->N * sizeof(float);
+}
+
+__global__ void zero_u32_kernel(uint32_t* p, int64_t n) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// CUs of the current device and workgroups of `fn` that fit on one of them.
+static loka_status resident_capacity(const void* fn, int threads, size_t lds, int* cus, int* per_cu) {
+    int dev = 0;
+    LOKA_HIP_TRY(hipGetDevice(&dev));
+    LOKA_HIP_TRY(hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev));
+    LOKA_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, fn, threads, lds));
+    return LOKA_OK;
 }
 
 static loka_status set_lds(const void* fn, size_t lds) {
@@ -598,7 +805,31 @@ loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* 
         if (!y) p.y = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + stats);
     }
     if (set_lds(blockwise ? vi.fn_block : vi.fn_plain, vi.lds) != LOKA_OK) return LOKA_ERR_HIP;
-    const dim3 grid(static_cast<unsigned>(static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.batch));
+    dim3 grid(static_cast<unsigned>(static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.batch));
+    if (vi.epi == EPI_PANEL_SYNC) {
+        // persistent grid: a multiple of tiles_n workgroups, all resident at once (one per CU)
+        int cus = 0, per_cu = 0;
+        if (resident_capacity(blockwise ? vi.fn_block : vi.fn_plain, vi.threads, vi.lds, &cus, &per_cu) != LOKA_OK)
+            return LOKA_ERR_HIP;
+        const int64_t slots = static_cast<int64_t>(cus) * (per_cu > 0 ? 1 : 0);
+        int64_t g = (slots / p.tiles_n) * p.tiles_n;
+        if (g <= 0) return LOKA_ERR_UNSUPPORTED;
+        if (g > grid.x) g = (static_cast<int64_t>(grid.x) / p.tiles_n) * p.tiles_n;   // fewer tiles than slots
+        grid = dim3(static_cast<unsigned>(g));
+        if (d->norm != LOKA_NORM_NONE) {
+            const int64_t panels = static_cast<int64_t>(p.batch) * p.tiles_m;
+            const size_t ctr_bytes = (static_cast<size_t>(panels) * 4 + 255) & ~size_t(255);
+            uint8_t* ws = static_cast<uint8_t*>(workspace);
+            p.error_flag = reinterpret_cast<unsigned*>(ws);
+            p.counters = reinterpret_cast<unsigned*>(ws + 256);
+            p.part = reinterpret_cast<float*>(ws + 256 + ctr_bytes);
+            p.spin_limit = kSpinLimit;
+            if (const char* e = std::getenv("LOKA_SPIN_LIMIT")) p.spin_limit = static_cast<unsigned>(std::strtoul(e, nullptr, 10));
+            const int64_t words = (256 + static_cast<int64_t>(ctr_bytes)) / 4;
+            zero_u32_kernel<<<dim3(static_cast<unsigned>((words + 255) / 256)), 256, 0, s>>>(
+                reinterpret_cast<uint32_t*>(ws), words);
+        }
+    }
     vi.launch(p, blockwise, grid, s);
     if (two_pass) {
         // with a strided batch the rows of all problems are contiguous only when strideO == M*N
