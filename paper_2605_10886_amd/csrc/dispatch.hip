@@ -70,11 +70,11 @@ int default_variant(const loka_gemm_desc* d) {
         if (better) { best = v; best_bn = bn; best_bm = bm; }
     }
     if (best >= 0) return best;
-    for (int v = variant_count() - 1; v >= 0; --v)        // widest two-pass tile first
-        if (variant_epilogue(v) == 1 && variant_supports(d, v)) {
-            if (variant_bm(v) >= 256 && d->M * d->N * d->batch < int64_t(1) << 24) continue;
-            return v;
-        }
+    // rows wider than a tile: the persistent panel-synchronous schedule once there is enough work to fill
+    // the chip for several rounds, the small two-pass tile otherwise
+    const bool big = d->M * d->N * d->batch >= (int64_t(1) << 24);
+    for (int v = 0; v < variant_count(); ++v)
+        if (variant_supports(d, v) && variant_epilogue(v) == (big ? 2 : 1)) return v;
     for (int v = 0; v < variant_count(); ++v)
         if (variant_supports(d, v)) return v;
     return -1;

@@ -716,7 +716,6 @@ static const VariantInfo kVariants[] = {
     LOKA_VARIANT("twopass256x256w8", 256, 256, 1, 2, 4, EPI_PARTIAL_STATS),
     // persistent, panel-synchronous: the tiles_n workgroups of a row panel exchange row statistics
     // through a few words of global memory and normalize their own tile in registers
-    LOKA_VARIANT("panel256x256", 256, 256, 1, 2, 2, EPI_PANEL_SYNC),
     LOKA_VARIANT("panel256x256w8", 256, 256, 1, 2, 4, EPI_PANEL_SYNC),
 };
 constexpr int kNumCUs = 256;          // MI355X; the launch re-checks against the device it runs on
