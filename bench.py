@@ -48,6 +48,10 @@ def main():
     ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3a", "C3b", "C4", "C5"])
     ap.add_argument("--budget", type=float, default=5e-2, help="rel-Frobenius budget the timed variant must meet")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dispatch", action="store_true",
+                    help="skip the profiling step: rowwise recipe, library's static variant choice (for clean rocprofv3 stats)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed loop run a plain 1 GiB device copy 3x (reference for the HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the path shards along M with no exchange; see DESIGN.md); "
@@ -78,11 +82,15 @@ def main():
     # ---- dispatch (profiling step, outside the timed region); its choice is cached per shape
     shape = B.make_desc(M, N, K, G, norm=norm, eps=w.eps)
     B.loka_dispatch_clear()
-    st_strict, ch_strict, _ = B.loka_dispatch(shape, x, wt, 1e-2)
-    st, ch, table = B.loka_dispatch(shape, x, wt, args.budget)
-    if st != B.LOKA_OK:
-        print(f"bench.py: no FP8 candidate within budget {args.budget}", file=sys.stderr)
-        sys.exit(3)
+    if args.no_dispatch:
+        st_strict, ch_strict, table = B.LOKA_ERR_NO_CANDIDATE, None, []
+        ch = {"x_mode": B.SCALE_ROW, "w_mode": B.SCALE_COL, "usec_bf16": None}
+    else:
+        st_strict, ch_strict, _ = B.loka_dispatch(shape, x, wt, 1e-2)
+        st, ch, table = B.loka_dispatch(shape, x, wt, args.budget)
+        if st != B.LOKA_OK:
+            print(f"bench.py: no FP8 candidate within budget {args.budget}", file=sys.stderr)
+            sys.exit(3)
     xm, wm = ch["x_mode"], ch["w_mode"]
     desc = B.make_desc(M, N, K, G, xm, wm, norm, w.eps, variant=-1)
     variant = B.loka_default_variant(desc)
@@ -217,7 +225,8 @@ def main():
                    "recipe": RECIPE_NAMES.get((xm, wm), f"{xm}/{wm}"), "variant": B.loka_variant_name(variant),
                    "flops_counted": "2*M*K*N of the FP8 GEMM", "pct_fp8_peak": 100 * value / FP8_PEAK_TFLOPS,
                    "input_sets_rotated": n_sets,
-                   "dispatch": {"budget_1e-2": "no FP8 candidate (stay in BF16)" if st_strict != B.LOKA_OK else
+                   "dispatch": "skipped (--no-dispatch)" if args.no_dispatch else
+                               {"budget_1e-2": "no FP8 candidate (stay in BF16)" if st_strict != B.LOKA_OK else
                                 RECIPE_NAMES.get((ch_strict["x_mode"], ch_strict["w_mode"])),
                                 "budget_used": args.budget, "usec_bf16": ch["usec_bf16"],
                                 "candidates": [{"recipe": RECIPE_NAMES.get((r["x_mode"], r["w_mode"])),
@@ -230,6 +239,12 @@ def main():
         "kernels": kernels,
         "probe_stats": pstats,
     }
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     print(json.dumps(line))
 
 

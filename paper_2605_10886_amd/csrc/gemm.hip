@@ -9,10 +9,11 @@
 //
 // Operand roles are swapped on purpose: rows of W feed the MFMA's row operand and rows
 // of X its column operand, so D[n][m] lands with lane l holding column m = l % 16 and
-// four consecutive n.  The W rows handed to each MFMA are permuted so that a lane ends
-// up with 4*NI CONSECUTIVE output columns of one row m: it can scale, reduce and store
-// them as 16-byte vectors without a transpose, and the row statistics need only two
-// cross-lane steps (lanes l, l^16, l^32, l^48 share a row).
+// four consecutive n.  The W rows handed to each MFMA are permuted so that each pair of
+// MFMA tiles gives a lane 8 CONSECUTIVE output columns of one row m, and the four lanes
+// that share the row 32 consecutive columns: scales, statistics and 16-byte stores need
+// no transpose, and the row statistics need only two cross-lane steps (lanes l, l^16,
+// l^32, l^48 share a row).
 //
 // LDS rows are 128 bytes = 8 chunks of 16 bytes; chunk c of row r is stored at chunk
 // position c ^ key(r).  The LDS has 64 banks of 4 bytes and serves a ds_read_b128 sixteen
@@ -57,6 +58,12 @@ __device__ unsigned long long loka_dbg_times[8 * 4096];
 #define LOKA_STAMP(slot) do { } while (0)
 #endif
 
+// Output column of MFMA tile ti, element i, for a lane of group q (= lane / 16), relative to the wave's
+// first column: (ti / 2) * 32 + q * 8 + (ti % 2) * 4 + i.  A lane owns 8 consecutive columns per tile pair,
+// and the four lane groups of a row together cover 32 consecutive columns: one 16-byte bf16 store per
+// lane writes full 64-byte runs per row.
+__host__ __device__ constexpr int coff_of(int ti) { return (ti >> 1) * 32 + (ti & 1) * 4; }
+
 // Chan's pairwise merge of (count, mean, M2).
 __device__ __forceinline__ void merge_stats(float& n, float& mean, float& m2, float nb, float mb, float m2b) {
     const float nn = n + nb;
@@ -76,13 +83,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     constexpr int WN = BN_SUB / WAVES_N;       // columns per wave and N-part
     constexpr int MI = WM / 16;
     constexpr int NI = WN / 16;
-    constexpr int RUN = 4 * NI;                // consecutive columns a lane owns per N-part
     constexpr int BN = BN_SUB * NSPLIT;
     constexpr int XS = BM * 128;               // bytes of one X stage
     constexpr int WS = BN_SUB * 128;           // bytes of one W stage
     static_assert(WM % 16 == 0 && WN % 16 == 0 && (NI == 2 || NI == 4 || NI == 8), "tile shape");
     static_assert(BM % 8 == 0 && BN_SUB % 8 == 0, "loader works on 8-row groups");
-    static_assert(!(BLOCKWISE && (RUN > 128 || 128 % RUN)), "a lane's run must stay inside one 128-column block");
+    static_assert(!(BLOCKWISE && (WN > 128 || 128 % WN)), "a wave's columns must stay inside one 128-column block");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     uint8_t* const xbuf = smem;                // 2 stages
@@ -120,9 +126,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     const int ld_row = lane >> 3, ld_pos = lane & 7;
     // X rows are read 16 consecutive rows at a time: key(r) = (r >> 1) & 7
     auto x_key = [](int r) { return (r >> 1) & 7; };
-    // W rows are read as rows g*RUN + 4t + i (g = 0..3, i = 0..3) of a wave's WN rows:
-    // key(r) = ((r >> 1) & 1) | (((r_local / RUN) & 3) << 1), r_local = r % WN
-    auto w_key = [](int r) { return ((r >> 1) & 1) | ((((r % WN) / RUN) & 3) << 1); };
+    // W rows are read as rows u*32 + g*8 + v*4 + i (g = 0..3, i = 0..3) of a wave's WN rows:
+    // key(r) = ((r >> 1) & 1) | (((r >> 3) & 3) << 1)
+    auto w_key = [](int r) { return ((r >> 1) & 1) | (((r >> 3) & 3) << 1); };
 
     // The X and W groups of a stage form one list; wave w owns entries w, w + NW, ...; entry j of a
     // wave can be issued on its own so the loads are spread between the MFMAs of the running stage.
@@ -157,7 +163,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
         } else if (TOT % NW == 0 || idx < TOT) {
             const int grp = idx - XG;
             const int row0 = n0 + h * BN_SUB + grp * 8;       // uniform
-            const int ukey = (((grp * 8) % WN) / RUN) & 3;    // uniform part of the W swizzle key
+            const int ukey = grp & 3;                         // uniform part of the W swizzle key
             unsigned voff = w_lane_off ^ (ukey << 5);
             const uint8_t* base;
             if (row0 + 8 <= p.N) {
@@ -181,7 +187,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     const int xrow = wave_m * WM + l16;                         // + mi * 16
     const int xkey = x_key(xrow);
     const int x_off0 = xrow * 128 + ((c0 ^ xkey) << 4), x_off1 = xrow * 128 + ((c1 ^ xkey) << 4);
-    const int wrow = wave_n * WN + (l16 >> 2) * RUN + (l16 & 3);  // + 4 * t
+    const int wrow = wave_n * WN + (l16 >> 2) * 8 + (l16 & 3);    // + coff_of(ti)
     const int wkey = w_key(wrow);
     const int w_off0 = wrow * 128 + ((c0 ^ wkey) << 4), w_off1 = wrow * 128 + ((c1 ^ wkey) << 4);
 
@@ -238,13 +244,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
             if (hh != h) continue;
             float swk = 0.f;
             if (BLOCKWISE) {
-                int nrun = n0 + hh * BN_SUB + wave_n * WN + q * RUN;
+                int nrun = n0 + hh * BN_SUB + wave_n * WN + q * 8;
                 nrun = nrun < p.N ? nrun : p.N - 1;
                 swk = swg[static_cast<int64_t>(k) * (p.N >> 7) + (nrun >> 7)];
             }
             // W fragments are fetched one tile ahead of the MFMAs that consume them
             v4i lo = *reinterpret_cast<const v4i*>(ws + w_off0);
-            v4i hi = *reinterpret_cast<const v4i*>(ws + w_off1);
+            v4i hi = *reinterpret_cast<const v4i*>(ws + w_off1);      // coff_of(0) == 0
 #pragma unroll
             for (int ti = 0; ti < NI; ++ti) {
                 if (more && ti < ISSUE_STEPS) {
@@ -254,8 +260,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                 }
                 v4i lo_n = lo, hi_n = hi;
                 if (ti + 1 < NI) {
-                    lo_n = *reinterpret_cast<const v4i*>(ws + w_off0 + (ti + 1) * 4 * 128);
-                    hi_n = *reinterpret_cast<const v4i*>(ws + w_off1 + (ti + 1) * 4 * 128);
+                    lo_n = *reinterpret_cast<const v4i*>(ws + w_off0 + coff_of(ti + 1) * 128);
+                    hi_n = *reinterpret_cast<const v4i*>(ws + w_off1 + coff_of(ti + 1) * 128);
                 }
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi) {
@@ -289,7 +295,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     }
 
     // ------------------------------------------------------------------ epilogue
-    // lane owns row m (per mi) and, per N-part h, columns ncol(h) + [0, RUN)
+    // lane owns row m (per mi) and, per N-part h and tile ti, columns ncol(h) + coff_of(ti) + [0, 4)
     __syncthreads();                       // all waves are done reading the stages: LDS is free
     LOKA_STAMP(1);
     float* red = reinterpret_cast<float*>(smem);   // [BM][WAVES_N][3]
@@ -300,10 +306,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     float cnt_lane = 0.f;                  // valid columns this lane holds per row
 #pragma unroll
     for (int h = 0; h < NSPLIT; ++h) {
-        ncol[h] = n0 + h * BN_SUB + wave_n * WN + q * RUN;
+        ncol[h] = n0 + h * BN_SUB + wave_n * WN + q * 8;
 #pragma unroll
         for (int ti = 0; ti < NI; ++ti)
-            if (ncol[h] + 4 * ti < p.N) cnt_lane += 4.f;
+            if (ncol[h] + coff_of(ti) < p.N) cnt_lane += 4.f;
     }
 
     // apply scales in place
@@ -312,7 +318,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
         for (int h = 0; h < NSPLIT; ++h)
 #pragma unroll
             for (int ti = 0; ti < NI; ++ti) {
-                const int n = ncol[h] + 4 * ti;
+                const int n = ncol[h] + coff_of(ti);
                 v4f s4;
                 if (tensor_w) {
                     const float s = swg[0];
@@ -339,7 +345,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                 for (int h = 0; h < NSPLIT; ++h)
 #pragma unroll
                     for (int ti = 0; ti < NI; ++ti) {
-                        const int n = ncol[h] + 4 * ti;
+                        const int n = ncol[h] + coff_of(ti);
                         if (n < p.N)
                             *reinterpret_cast<v4f*>(p.y + obase + static_cast<int64_t>(m) * p.N + n) = acc[h][mi][ti];
                     }
@@ -366,14 +372,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                 for (int h = 0; h < NSPLIT; ++h)
 #pragma unroll
                     for (int ti = 0; ti < NI; ++ti)
-                        if (ncol[h] + 4 * ti < p.N)
+                        if (ncol[h] + coff_of(ti) < p.N)
                             s += (acc[h][mi][ti][0] + acc[h][mi][ti][1]) + (acc[h][mi][ti][2] + acc[h][mi][ti][3]);
                 mean = n_ > 0.f ? s * __builtin_amdgcn_rcpf(n_) : 0.f;
 #pragma unroll
                 for (int h = 0; h < NSPLIT; ++h)
 #pragma unroll
                     for (int ti = 0; ti < NI; ++ti)
-                        if (ncol[h] + 4 * ti < p.N) {
+                        if (ncol[h] + coff_of(ti) < p.N) {
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 const float d = acc[h][mi][ti][e] - mean;
@@ -400,7 +406,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                 for (int h = 0; h < NSPLIT; ++h)
 #pragma unroll
                     for (int ti = 0; ti < NI; ++ti)
-                        if (ncol[h] + 4 * ti < p.N) {
+                        if (ncol[h] + coff_of(ti) < p.N) {
 #pragma unroll
                             for (int e = 0; e < 4; ++e) m2 += acc[h][mi][ti][e] * acc[h][mi][ti][e];
                         }
@@ -571,7 +577,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     for (int h = 0; h < NSPLIT; ++h) {
 #pragma unroll
         for (int tp = 0; tp < NI; tp += 2) {                    // two tiles = 8 columns = one 16-byte store
-            const int n = ncol[h] + 4 * tp;
+            const int n = ncol[h] + coff_of(tp);
             if (n >= p.N) continue;
             float gm[8], bt[8];
 #pragma unroll
