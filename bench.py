@@ -25,6 +25,10 @@ FP8_PEAK_TFLOPS = 5000.0      # MI355X dense FP8 MFMA, published
 BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
+# HBM-side bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# file, scaled by a plain 1 GiB copy (profiles/bench_C5_panel256x256w8.md); counters cannot be read in-process.
+MEASURED_TRAFFIC_BYTES = {("C5", "panel256x256w8"): 1.217e9 + 0.347e9}
+
 RECIPE_NAMES = {(0, 0): "tensor/tensor", (1, 2): "row/col", (3, 4): "1x128/128x128"}
 
 
@@ -171,6 +175,9 @@ def main():
                     "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                     "traffic": None, "avg_launch_ms": t_gemm, "tflops": gemm_tflops,
                     "pct_fp8_peak": 100 * gemm_tflops / FP8_PEAK_TFLOPS}
+
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, B.loka_variant_name(variant)))
+    roofline["algorithmic_bytes"] = gemm_bytes
 
     # ---- probe leg (offline in the method): Y store, BF16 reference GEMM, error statistics
     y = torch.empty(rows, N, dtype=torch.float32, device=dev)
