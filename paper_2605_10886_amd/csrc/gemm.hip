@@ -64,6 +64,15 @@ __device__ unsigned long long loka_dbg_times[8 * 4096];
 // lane writes full 64-byte runs per row.
 __host__ __device__ constexpr int coff_of(int ti) { return (ti >> 1) * 32 + (ti & 1) * 4; }
 
+// Workgroup barrier that orders LDS traffic only: LDS reads/writes issued before it are complete, but
+// global loads (including the loads that stream the next stage into LDS) stay in flight across it.
+// Completion of those is awaited explicitly (s_waitcnt vmcnt) where a stage is about to be read.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Chan's pairwise merge of (count, mean, M2).
 __device__ __forceinline__ void merge_stats(float& n, float& mean, float& m2, float nb, float mb, float m2b) {
     const float nn = n + nb;
@@ -130,53 +139,38 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     // key(r) = ((r >> 1) & 1) | (((r >> 3) & 3) << 1)
     auto w_key = [](int r) { return ((r >> 1) & 1) | (((r >> 3) & 3) << 1); };
 
-    // The X and W groups of a stage form one list; wave w owns entries w, w + NW, ...; entry j of a
-    // wave can be issued on its own so the loads are spread between the MFMAs of the running stage.
-    // Addressing: a uniform 64-bit base (problem, tile row group, K offset) in scalar registers plus one
-    // 32-bit per-lane offset, so no per-load address registers stay live across the main loop.  The
-    // lane offset is (row-in-group * KB + chunk * 16); the group-dependent part of the swizzle key only
-    // flips bits 5..6 of it (an xor with a uniform value).  Groups that reach past the last valid row
-    // (ragged M or N tail) re-read the last valid row instead: their results are never stored.
-    constexpr int XG = BM / 8, WGR = BN_SUB / 8, TOT = XG + WGR;
-    constexpr int JN = (TOT + NW - 1) / NW;
-    const unsigned x_lane_off = static_cast<unsigned>(ld_row) * p.KB + ((ld_pos ^ (ld_row >> 1)) << 4);
-    const unsigned w_lane_off = static_cast<unsigned>(ld_row) * p.KB + ((ld_pos ^ ((ld_row >> 1) & 1)) << 4);
-    auto issue_j = [&](int j, int stage_x, int stage_w, int kb, int h, bool with_x) {
-        const int idx = wave + j * NW;                        // wave-uniform
-        if (idx < XG) {
+    // A stage is XG + WGR groups of 8 rows; wave w loads X groups w, w + NW, ... (entries j < XJ) and
+    // W groups w, w + NW, ... (entries j >= XJ); an entry can be issued on its own, so the loads can be
+    // spread between the MFMAs of the running stage.
+    // Addressing: buffer loads straight into LDS.  One buffer descriptor per operand covers exactly the
+    // tile's valid rows (scalar registers), one loop-invariant 32-bit per-lane offset per operand
+    // (row-in-group * KB + swizzled chunk * 16; the group-dependent part of the swizzle key depends only
+    // on the wave, because NW and XG are multiples of 4), and a uniform scalar offset per entry (group
+    // row offset + K offset).  Rows past the end of a ragged M or N tail fall outside the descriptor and
+    // load zeros; their results are never stored.
+    constexpr int XG = BM / 8, WGR = BN_SUB / 8;
+    static_assert(XG % NW == 0 && WGR % NW == 0 && NW % 4 == 0 && XG % 4 == 0, "loader split");
+    constexpr int XJ = XG / NW, JN = XJ + WGR / NW;
+    const int x_lane_off = ld_row * p.KB + (((ld_pos ^ (ld_row >> 1)) << 4) ^ ((wave & 1) << 6));
+    const int w_lane_off = ld_row * p.KB + (((ld_pos ^ ((ld_row >> 1) & 1)) << 4) ^ ((wave & 3) << 5));
+    const int x_rows = p.M - m0 < BM ? p.M - m0 : BM, w_rows = p.N - n0 < BN ? p.N - n0 : BN;
+    const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(Xg + static_cast<int64_t>(m0) * p.KB), 0, x_rows * p.KB, 0x00020000);
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(Wg + static_cast<int64_t>(n0) * p.KB), 0, w_rows * p.KB, 0x00020000);
+    auto issue_j = [&](int j, int stage_x, int stage_w, int kb, int h, bool with_x) __attribute__((always_inline)) {
+        if (j < XJ) {
             if (with_x) {
-                const int row0 = m0 + idx * 8;                // uniform
-                unsigned voff = x_lane_off ^ ((idx & 1) << 6);
-                const uint8_t* base;
-                if (row0 + 8 <= p.M) {
-                    base = Xg + static_cast<int64_t>(row0) * p.KB + kb;
-                } else {                                      // tail group: clamp each lane's row
-                    int r = row0 + ld_row;
-                    r = r < p.M ? r : p.M - 1;
-                    base = Xg + kb;
-                    voff = static_cast<unsigned>(r) * p.KB + ((voff & 127u));
-                }
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + voff),
-                                                 (__attribute__((address_space(3))) void*)(xbuf + stage_x * XS + idx * 1024),
-                                                 16, 0, 0);
+                const int grp = wave + j * NW;                // uniform
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    x_rsrc, (__attribute__((address_space(3))) void*)(xbuf + stage_x * XS + grp * 1024), 16,
+                    x_lane_off, grp * 8 * p.KB + kb, 0, 0);
             }
-        } else if (TOT % NW == 0 || idx < TOT) {
-            const int grp = idx - XG;
-            const int row0 = n0 + h * BN_SUB + grp * 8;       // uniform
-            const int ukey = grp & 3;                         // uniform part of the W swizzle key
-            unsigned voff = w_lane_off ^ (ukey << 5);
-            const uint8_t* base;
-            if (row0 + 8 <= p.N) {
-                base = Wg + static_cast<int64_t>(row0) * p.KB + kb;
-            } else {
-                int r = row0 + ld_row;
-                r = r < p.N ? r : p.N - 1;
-                base = Wg + kb;
-                voff = static_cast<unsigned>(r) * p.KB + (voff & 127u);
-            }
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + voff),
-                                             (__attribute__((address_space(3))) void*)(wbuf + stage_w * WS + grp * 1024),
-                                             16, 0, 0);
+        } else {
+            const int grp = wave + (j - XJ) * NW;             // uniform
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                w_rsrc, (__attribute__((address_space(3))) void*)(wbuf + stage_w * WS + grp * 1024), 16,
+                w_lane_off, (h * BN_SUB + grp * 8) * p.KB + kb, 0, 0);
         }
     };
 
@@ -208,12 +202,76 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
 
     LOKA_STAMP(0);
 #pragma unroll
-    for (int j = 0; j < JN; ++j) issue_j(j, 0, 0, 0, 0, true);
+    for (int j = 0; j < JN; ++j) issue_j(j, 0, 0, 0, 0, true);   // stage 0, every wave's share
 
     // loads of the next stage are issued in the first ISSUE_STEPS tile steps of the running stage
     constexpr int ISSUE_STEPS = NI >= 4 ? NI / 2 : NI;
     constexpr int J_PER_STEP = (JN + ISSUE_STEPS - 1) / ISSUE_STEPS;
 
+    // Ping-pong schedule for the 8-wave 256-row tiles: waves 0..3 (group A, upper 128 rows) and 4..7
+    // (group B, lower 128 rows) sit one of each on every SIMD.  Each K step has two phases separated by
+    // workgroup barriers: while A reads its 12 operand fragments of stage k from LDS, B runs the 32 MFMAs
+    // of stage k-1 from registers; then A computes stage k while B reads stage k.  The MFMA pipe of every
+    // SIMD always has a computing wave, and the LDS reads of one group hide behind the other's MFMAs.
+    constexpr bool PINGPONG = (NW == 8 && WAVES_M == 2 && NSPLIT == 1 && !IS_BF16 && !BLOCKWISE);
+    if constexpr (PINGPONG) {
+        const bool grp_b = wave >= 4;                           // wave-uniform
+        v8i bx[MI], aw[NI];
+        auto read_frags = [&](int k) __attribute__((always_inline)) {
+            const uint8_t* xs = xbuf + (k & 1) * XS;
+            const uint8_t* ws = wbuf + (k & 1) * WS;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const v4i lo = *reinterpret_cast<const v4i*>(xs + x_off0 + mi * 16 * 128);
+                const v4i hi = *reinterpret_cast<const v4i*>(xs + x_off1 + mi * 16 * 128);
+                bx[mi] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            }
+#pragma unroll
+            for (int ti = 0; ti < NI; ++ti) {
+                const v4i lo = *reinterpret_cast<const v4i*>(ws + w_off0 + coff_of(ti) * 128);
+                const v4i hi = *reinterpret_cast<const v4i*>(ws + w_off1 + coff_of(ti) * 128);
+                aw[ti] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            }
+        };
+        auto compute = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int ti = 0; ti < NI; ++ti)
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+                    acc[0][mi][ti] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aw[ti], bx[mi], acc[0][mi][ti],
+                                                                                     0, 0, 0, 0, 0, 0);
+        };
+        // Group B runs the same loop one phase behind A (one extra barrier up front, one fewer at the end),
+        // so the loop body has no group-dependent control flow around the accumulators.  A issues its share
+        // of stage k+1 after the top barrier of step k and waits for it before the next top barrier; B issues
+        // its share of stage k+2 after its mid barrier and waits before its next mid barrier: each share has a
+        // full K step to land, and every stage is complete one barrier before its first reader.
+        if (grp_b) {
+            if (ksteps > 1) {
+#pragma unroll
+                for (int j = 0; j < JN; ++j) issue_j(j, 1, 1, 128, 0, true);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            lds_barrier();
+        }
+        for (int k = 0; k < ksteps; ++k) {
+            if (!grp_b) __builtin_amdgcn_s_waitcnt(0x0F70);
+            lds_barrier();
+            if (!grp_b && k + 1 < ksteps) {
+#pragma unroll
+                for (int j = 0; j < JN; ++j) issue_j(j, (k + 1) & 1, (k + 1) & 1, (k + 1) * 128, 0, true);
+            }
+            read_frags(k);
+            if (grp_b) __builtin_amdgcn_s_waitcnt(0x0F70);
+            lds_barrier();
+            if (grp_b && k + 2 < ksteps) {
+#pragma unroll
+                for (int j = 0; j < JN; ++j) issue_j(j, k & 1, k & 1, (k + 2) * 128, 0, true);
+            }
+            compute();
+        }
+        if (!grp_b) lds_barrier();
+    } else {
     for (int it = 0; it < iters; ++it) {
         const int k = it / NSPLIT, h = it % NSPLIT;
         __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0): this wave's loads for stage `it` have landed
@@ -292,6 +350,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                 hi = hi_n;
             }
         }
+    }
     }
 
     // ------------------------------------------------------------------ epilogue
@@ -745,6 +804,7 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
     const VariantInfo& vi = kVariants[v];
     if (vi.epi == EPI_ROW_IN_TILE && d->N > vi.bn) return false;
     if (vi.epi == EPI_PANEL_SYNC && (d->N + vi.bn - 1) / vi.bn > kNumCUs) return false;
+    if (static_cast<int64_t>(vi.bm > vi.bn ? vi.bm : vi.bn) * d->K >= (int64_t(1) << 31)) return false;   // tile-relative offsets are 32-bit
     const int64_t tiles = ((d->M + vi.bm - 1) / vi.bm) * ((d->N + vi.bn - 1) / vi.bn) * d->batch;
     return tiles < (int64_t(1) << 31);
 }
