@@ -72,9 +72,14 @@ int default_variant(const loka_gemm_desc* d) {
     if (best >= 0) return best;
     // rows wider than a tile: the persistent panel-synchronous schedule once there is enough work to fill
     // the chip for several rounds, the small two-pass tile otherwise
+    // (later table entries of a kind are the faster ones where they apply: 32x32x64 MFMAs for non-blockwise scales)
     const bool big = d->M * d->N * d->batch >= (int64_t(1) << 24);
+    if (big) {
+        for (int v = variant_count() - 1; v >= 0; --v)
+            if (variant_supports(d, v) && variant_epilogue(v) == 2) return v;
+    }
     for (int v = 0; v < variant_count(); ++v)
-        if (variant_supports(d, v) && variant_epilogue(v) == (big ? 2 : 1)) return v;
+        if (variant_supports(d, v) && variant_epilogue(v) == 1) return v;
     for (int v = 0; v < variant_count(); ++v)
         if (variant_supports(d, v)) return v;
     return -1;

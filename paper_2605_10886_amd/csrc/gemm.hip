@@ -19,71 +19,11 @@
 // position c ^ key(r).  The LDS has 64 banks of 4 bytes and serves a ds_read_b128 sixteen
 // lanes at a time, so the 16 rows those lanes address must differ in (row parity, chunk
 // position): key(r) takes 8 values over the 8 same-parity rows of each operand's read pattern.
-#include "common.h"
+#include "gemm_common.h"
 
 #include <cstdlib>
 
 namespace loka {
-
-enum { EPI_ROW_IN_TILE = 0, EPI_PARTIAL_STATS = 1, EPI_PANEL_SYNC = 2 };
-
-struct GemmParams {
-    const uint8_t* X;      // [batch][M][KB] bytes (KB = K for FP8, 2K for BF16)
-    const uint8_t* W;      // [batch][N][KB]
-    int M, N, KB;
-    int batch;
-    int64_t strideX, strideW;   // bytes between problems
-    int64_t strideO;            // elements between problems (O, Y)
-    const float* sx;
-    const float* sw;
-    int64_t strideSx, strideSw; // scales between problems
-    int x_mode, w_mode;
-    const uint16_t* gamma;
-    const uint16_t* beta;
-    uint16_t* out;
-    float* y;
-    int norm;
-    float eps;
-    int tiles_m, tiles_n;
-    float* part;           // EPI_PARTIAL_STATS / EPI_PANEL_SYNC: [batch][M][tiles_n * 2] (mean, M2) or (0, sumsq)
-    unsigned* counters;    // EPI_PANEL_SYNC: arrivals per (problem, m tile), zeroed before the launch
-    unsigned* error_flag;  // EPI_PANEL_SYNC: set when a bounded wait ran out
-    unsigned spin_limit;
-};
-
-#ifdef LOKA_DEBUG_TIMES
-__device__ unsigned long long loka_dbg_times[8 * 4096];
-#define LOKA_STAMP(slot) do { if (threadIdx.x == 0 && tile < 4096) loka_dbg_times[tile * 8 + (slot)] = wall_clock64(); } while (0)
-#else
-#define LOKA_STAMP(slot) do { } while (0)
-#endif
-
-// Output column of MFMA tile ti, element i, for a lane of group q (= lane / 16), relative to the wave's
-// first column: (ti / 2) * 32 + q * 8 + (ti % 2) * 4 + i.  A lane owns 8 consecutive columns per tile pair,
-// and the four lane groups of a row together cover 32 consecutive columns: one 16-byte bf16 store per
-// lane writes full 64-byte runs per row.
-__host__ __device__ constexpr int coff_of(int ti) { return (ti >> 1) * 32 + (ti & 1) * 4; }
-
-// Workgroup barrier that orders LDS traffic only: LDS reads/writes issued before it are complete, but
-// global loads (including the loads that stream the next stage into LDS) stay in flight across it.
-// Completion of those is awaited explicitly (s_waitcnt vmcnt) where a stage is about to be read.
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// Chan's pairwise merge of (count, mean, M2).
-__device__ __forceinline__ void merge_stats(float& n, float& mean, float& m2, float nb, float mb, float m2b) {
-    const float nn = n + nb;
-    if (nb > 0.f) {
-        const float d = mb - mean;
-        const float f = nb * __builtin_amdgcn_rcpf(nn);   // nn > 0 here; 1-ulp reciprocal (an IEEE divide costs ~300 cycles)
-        mean = mean + d * f;
-        m2 = m2 + m2b + d * d * n * f;
-        n = nn;
-    }
-}
 
 template <int BM, int BN_SUB, int NSPLIT, int WAVES_M, int WAVES_N, bool IS_BF16, bool BLOCKWISE, int EPI>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmParams p) {
@@ -761,6 +701,12 @@ static void launch_fp8(const GemmParams& p, bool blockwise, dim3 grid, hipStream
     else gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, false, EPI><<<grid, threads, lds, s>>>(p);
 }
 
+// gemm_panel32.hip
+const void* panel32_fn();
+size_t panel32_lds();
+void panel32_launch(const GemmParams& p, dim3 grid, hipStream_t s);
+static void launch_panel32(const GemmParams& p, bool, dim3 grid, hipStream_t s) { panel32_launch(p, grid, s); }
+
 #define LOKA_VARIANT(NAME, BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, EPI)                                        \
     {NAME, BM, BN_SUB * NSPLIT, WAVES_M * WAVES_N * 64, EPI, 2 * (BM * 128 + BN_SUB * 128),                  \
      &launch_fp8<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, EPI>,                                                 \
@@ -782,6 +728,8 @@ static const VariantInfo kVariants[] = {
     // persistent, panel-synchronous: the tiles_n workgroups of a row panel exchange row statistics
     // through a few words of global memory and normalize their own tile in registers
     LOKA_VARIANT("panel256x256w8", 256, 256, 1, 2, 4, EPI_PANEL_SYNC),
+    // the same schedule on 32x32x64 MFMAs (non-blockwise scales only): the throughput variant
+    {"panel32_256x256", 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(), nullptr},
 };
 constexpr int kNumCUs = 256;          // MI355X; the launch re-checks against the device it runs on
 constexpr unsigned kSpinLimit = 1u << 18;   // x s_sleep(16) ~ 0.1 s: far beyond any main loop
@@ -802,6 +750,7 @@ int variant_bm(int v) { return kVariants[v].bm; }
 bool variant_supports(const loka_gemm_desc* d, int v) {
     if (v < 0 || v >= kNumVariants) return false;
     const VariantInfo& vi = kVariants[v];
+    if ((d->x_mode == LOKA_SCALE_BLOCK_1x128 ? vi.fn_block : vi.fn_plain) == nullptr) return false;
     if (vi.epi == EPI_ROW_IN_TILE && d->N > vi.bn) return false;
     if (vi.epi == EPI_PANEL_SYNC && (d->N + vi.bn - 1) / vi.bn > kNumCUs) return false;
     if (static_cast<int64_t>(vi.bm > vi.bn ? vi.bm : vi.bn) * d->K >= (int64_t(1) << 31)) return false;   // tile-relative offsets are 32-bit

@@ -1,0 +1,463 @@
+// Large-tile FP8 GEMM with the row norm fused across workgroups: 256 x 256 tiles, 8 waves,
+// v_mfma_f32_32x32x64_f8f6f4, persistent panel-synchronous schedule (see gemm.hip for the schedule's
+// description; this file is its throughput-oriented instantiation for non-blockwise scales).
+//
+// Why a second kernel: measured on MI355X, back-to-back 16x16x128 MFMAs issued by ONE wave reach ~70-80 %
+// of the FP8 rate (each instruction reads 16 operand registers for 32 cycles of work), while 32x32x64
+// reaches 98 % (same operand registers, 64 cycles of work).  In the ping-pong main loop only one wave
+// per SIMD computes at a time, so the 32x32x64 form is the one that keeps the matrix pipe full.
+//
+// Work split: waves 0..3 own rows 0..127 of the tile, waves 4..7 rows 128..255; wave w % 4 owns columns
+// [64 (w % 4), +64).  Per K step of 128 bytes a wave runs 4 (row tiles of 32) x 2
+// (column tiles of 32) x 2 (K halves of 64) = 16 MFMAs from 12 operand fragments of 8 registers.
+//
+// Operand roles are swapped as in gemm.hip (W rows -> MFMA rows, X rows -> MFMA columns).  MFMA row
+// rho = 8a + 4h + b (a = 0..3, h = lane / 32, b = 0..3) is fed W row 16h + 4a + b of the 32-row tile, so a
+// lane ends with 16 CONSECUTIVE output columns (accumulator element i <-> column 16h + i) of one output
+// row m = lane % 32, and the two lanes that share a row cover 32 consecutive columns.
+//
+// LDS: rows of 128 bytes, chunk c of row r at position c ^ key(r); X rows are read 16 consecutive rows at a
+// time (key = (r >> 1) & 7); the W read pattern above touches rows {16h + 4a + b} with a in a pair
+// {0,1} or {2,3} per 16 lanes: key = bits (1, 2, 4) of r.  Both give 16 lanes x 16 bytes on 64 distinct banks.
+#include "gemm_common.h"
+
+namespace loka {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
+    constexpr int BM = 256, BN = 256, NW = 8, WM = 128, WN = 64, MI = 4, NI = 2;
+    constexpr int ES = 256 * 128;           // one ring entry: 256 rows x 128 bytes of X or of W
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave_m = wave >> 2, wave_n = wave & 3;
+    const int l32 = lane & 31, hk = lane >> 5;
+
+    const int total_tiles = p.tiles_m * p.tiles_n * p.batch;
+    int tile_first = blockIdx.x, tile_stride = total_tiles;
+    if (EPI == EPI_PANEL_SYNC) {
+        const int G = gridDim.x;
+        tile_first = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+        tile_stride = G;
+    }
+    // loop-invariant lane offsets
+    const int ld_row = lane >> 3, ld_pos = lane & 7;
+    const int x_lane_off = ld_row * p.KB + (((ld_pos ^ (ld_row >> 1)) << 4) ^ ((wave & 1) << 6));
+    const int w_lane_off = ld_row * p.KB + (((ld_pos ^ ((ld_row >> 1) & 3)) << 4) ^ (((wave >> 1) & 1) << 6));
+    // fragment read offsets inside a stage: K half s uses chunks 4s + 2hk, 4s + 2hk + 1
+    const int xrow = wave_m * WM + l32;                                    // + 32 mi
+    const int xkey = (xrow >> 1) & 7;
+    const int x_off0 = xrow * 128 + (((2 * hk) ^ xkey) << 4), x_off1 = xrow * 128 + (((2 * hk + 1) ^ xkey) << 4);
+    const int wperm = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);  // W row of the 32-row tile this lane feeds
+    const int wrow = wave_n * WN + wperm;                                  // + 32 ni
+    const int wkey = ((wrow >> 1) & 1) | (((wrow >> 2) & 1) << 1) | (((wrow >> 4) & 1) << 2);
+    const int w_off0 = wrow * 128 + (((2 * hk) ^ wkey) << 4), w_off1 = wrow * 128 + (((2 * hk + 1) ^ wkey) << 4);
+    const int ksteps = p.KB / 128;
+    const float inv_n = 1.0f / static_cast<float>(p.N);
+
+  for (int tile = tile_first; tile < total_tiles; tile += tile_stride) {
+    int t = tile;
+    const int tn = t % p.tiles_n; t /= p.tiles_n;
+    const int tm = t % p.tiles_m;
+    const int g = t / p.tiles_m;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const uint8_t* Xg = p.X + static_cast<int64_t>(g) * p.strideX;
+    const uint8_t* Wg = p.W + static_cast<int64_t>(g) * p.strideW;
+    const float* sxg = p.sx + static_cast<int64_t>(g) * p.strideSx;
+    const float* swg = p.sw + static_cast<int64_t>(g) * p.strideSw;
+
+    const int x_rows = p.M - m0 < BM ? p.M - m0 : BM, w_rows = p.N - n0 < BN ? p.N - n0 : BN;
+    const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(Xg + static_cast<int64_t>(m0) * p.KB), 0, x_rows * p.KB, 0x00020000);
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(Wg + static_cast<int64_t>(n0) * p.KB), 0, w_rows * p.KB, 0x00020000);
+    // this wave's share of one ring entry (the X or the W rows of K step kb / 128) is four loads of 1 KB:
+    // row groups wave, wave + 8, wave + 16, wave + 24; load j of an entry
+    auto issue_x1 = [&](int slot, int kb, int j) __attribute__((always_inline)) {
+        const int grp = wave + j * NW;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            x_rsrc, (__attribute__((address_space(3))) void*)(smem + slot * ES + grp * 1024), 16, x_lane_off,
+            grp * 8 * p.KB + kb, 0, 0);
+    };
+    auto issue_w1 = [&](int slot, int kb, int j) __attribute__((always_inline)) {
+        const int grp = wave + j * NW;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            w_rsrc, (__attribute__((address_space(3))) void*)(smem + slot * ES + grp * 1024), 16, w_lane_off,
+            grp * 8 * p.KB + kb, 0, 0);
+    };
+    auto issue_x = [&](int slot, int kb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) issue_x1(slot, kb, j);
+    };
+    auto issue_w = [&](int slot, int kb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) issue_w1(slot, kb, j);
+    };
+
+    v16f acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+
+    // Fragments of one K half (64 bytes): 2 W (two sets, double buffered) and 4 X (one set, refilled in place
+    // as soon as the two MFMAs that use a fragment have been issued) of 8 registers each.
+    v8i bx[MI], aw[2][NI];
+    auto read_w = [&](int slot, int s, int set) __attribute__((always_inline)) {
+        const uint8_t* ws = smem + slot * ES;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const v4i lo = *reinterpret_cast<const v4i*>(ws + (w_off0 ^ (s << 6)) + ni * 32 * 128);
+            const v4i hi = *reinterpret_cast<const v4i*>(ws + (w_off1 ^ (s << 6)) + ni * 32 * 128);
+            aw[set][ni] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
+    };
+    auto read_x = [&](int slot, int s, int mi) __attribute__((always_inline)) {
+        const uint8_t* xs = smem + slot * ES + mi * 32 * 128;
+        const v4i lo = *reinterpret_cast<const v4i*>(xs + (x_off0 ^ (s << 6)));
+        const v4i hi = *reinterpret_cast<const v4i*>(xs + (x_off1 ^ (s << 6)));
+        bx[mi] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    };
+    auto mfma_one = [&](int mi, int ni, int set) __attribute__((always_inline)) {
+        acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(aw[set][ni], bx[mi], acc[mi][ni], 0, 0, 0, 0, 0, 0);
+    };
+    auto mfma_row = [&](int mi, int set) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) mfma_one(mi, ni, set);
+    };
+    // MFMAs of the K half whose W fragments are in SET, with the LDS reads of K half S_READ of the entries in
+    // slots SLOT_X / SLOT_W, and (ISSUE) this wave's eight loads of the next two ring entries, spread between
+    // them in source order.  The matrix pipe then always has an instruction queued: a burst of LDS reads or of
+    // loads keeps the wave in the issue stage for hundreds of cycles (the load path accepts 64 bytes per
+    // clock per CU), and the other wave of the SIMD is in the same phase.
+#define LOKA_HALF_STEP(SLOT_X, SLOT_W, S_READ, SET, ISSUE)                           \
+    do {                                                                             \
+        __builtin_amdgcn_sched_barrier(0);                                           \
+        read_w(SLOT_W, S_READ, (SET) ^ 1);                                           \
+        _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) {                          \
+            __builtin_amdgcn_sched_barrier(0);                                       \
+            mfma_one(mi, 0, SET);                                                    \
+            __builtin_amdgcn_sched_barrier(0);                                       \
+            if (ISSUE) {                                                             \
+                if (mi < 2) { if (more_w) issue_w1(slot_w_new, kb_w_new, 2 * mi); }  \
+                else if (more_x) issue_x1(slot_x_new, kb_x_new, 2 * mi - 4);         \
+            }                                                                        \
+            __builtin_amdgcn_sched_barrier(0);                                       \
+            mfma_one(mi, 1, SET);                                                    \
+            __builtin_amdgcn_sched_barrier(0);                                       \
+            read_x(SLOT_X, S_READ, mi);                                              \
+            if (ISSUE) {                                                             \
+                if (mi < 2) { if (more_w) issue_w1(slot_w_new, kb_w_new, 2 * mi + 1); } \
+                else if (more_x) issue_x1(slot_x_new, kb_x_new, 2 * mi - 3);         \
+            }                                                                        \
+        }                                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                           \
+    } while (0)
+
+    // ---- main loop.  LDS holds a ring of five 32 KB entries X(0) W(0) X(1) W(1) X(2) ...; entry e lives in
+    // slot e % 5.  One barrier per K step, in its middle, when every wave has read X(k) and W(k) completely and
+    // every wave's share of X(k + 1), W(k + 1) has landed; the two freed slots then take W(k + 2) and X(k + 3).
+    // X entries are requested two steps before their first read, W entries one step (half the bytes of a
+    // stage: the round trip through L2 under load is ~1 us for 64 KB, ~0.6 us for 32 KB; a step is ~1.2 us).
+    // All of a wave's loads return in issue order, so "vmcnt(4)" = everything but the newest entry's share.
+    auto mod5 = [](int v) { return v >= 5 ? v - 5 : v; };
+    LOKA_STAMP(0);
+    issue_x(0, 0);
+    issue_w(1, 0);
+    if (ksteps > 1) { issue_x(2, 128); issue_w(3, 128); }
+    if (ksteps > 2) issue_x(4, 256);
+    if (ksteps > 2) __builtin_amdgcn_s_waitcnt(0x0F7C);         // vmcnt(12)
+    else if (ksteps > 1) __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    lds_barrier();
+    read_w(1, 0, 0);
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) read_x(0, 0, mi);
+    int e5 = 0;                                                 // slot of X(k)
+    // (the last K step is peeled: MFMAs under a condition inside the loop make the compiler copy accumulators)
+    for (int k = 0; k + 1 < ksteps; ++k) {
+        const int sw_cur = mod5(e5 + 1), sx_nxt = mod5(e5 + 2), sw_nxt = mod5(e5 + 3);
+        const bool more_w = k + 2 < ksteps, more_x = k + 3 < ksteps;
+        const int slot_w_new = e5, kb_w_new = (k + 2) * 128, slot_x_new = sw_cur, kb_x_new = (k + 3) * 128;
+        LOKA_HALF_STEP(e5, sw_cur, 1, 0, false);
+        if (more_w) __builtin_amdgcn_s_waitcnt(0x0F74);         // vmcnt(4): all but X(k + 2)
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        lds_barrier();                                          // (also waits for this wave's LDS reads)
+        LOKA_HALF_STEP(sx_nxt, sw_nxt, 0, 1, true);             // + loads of W(k + 2), X(k + 3) into the freed slots
+        e5 = sx_nxt;
+    }
+    {
+        const bool more_w = false, more_x = false;
+        const int slot_w_new = 0, kb_w_new = 0, slot_x_new = 0, kb_x_new = 0;
+        LOKA_HALF_STEP(e5, mod5(e5 + 1), 1, 0, false);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) mfma_row(mi, 1);
+#undef LOKA_HALF_STEP
+    __syncthreads();                                        // LDS is free for the epilogue
+    LOKA_STAMP(1);
+
+    // ------------------------------------------------------------------ epilogue
+    // lane: rows m(mi) = m0 + 128 wave_m + 32 mi + l32; columns ncol(ni) + [0, 16), ncol = n0 + 64 wave_n + 32 ni + 16 hk
+    float* red = reinterpret_cast<float*>(smem);                                   // [BM][4][3]
+    float2* fin = reinterpret_cast<float2*>(smem) + BM * 4 * 3 / 2 + 8;            // [BM] (mean, rstd)
+    const int64_t obase = static_cast<int64_t>(g) * p.strideO;
+    const bool tensor_x = p.x_mode == LOKA_SCALE_TENSOR, tensor_w = p.w_mode == LOKA_SCALE_TENSOR;
+    int ncol[NI];
+    float cnt_lane = 0.f;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        ncol[ni] = n0 + wave_n * WN + ni * 32 + hk * 16;
+        if (ncol[ni] < p.N) cnt_lane += 16.f;               // N % 16 == 0: a run of 16 is all in or all out
+    }
+    // scales
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        v4f s4[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            if (tensor_w) { const float s = swg[0]; s4[a] = v4f{s, s, s, s}; }
+            else s4[a] = ncol[ni] < p.N ? *reinterpret_cast<const v4f*>(swg + ncol[ni] + 4 * a) : v4f{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            int m = m0 + wave_m * WM + mi * 32 + l32;
+            m = m < p.M ? m : p.M - 1;
+            const float sxm = tensor_x ? sxg[0] : sxg[m];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] *= s4[i >> 2][i & 3] * sxm;
+        }
+    }
+    if (p.y) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int m = m0 + wave_m * WM + mi * 32 + l32;
+            if (m < p.M) {
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    if (ncol[ni] < p.N) {
+                        float* dst = p.y + obase + static_cast<int64_t>(m) * p.N + ncol[ni];
+#pragma unroll
+                        for (int a = 0; a < 4; ++a)
+                            *reinterpret_cast<v4f*>(dst + 4 * a) =
+                                v4f{acc[mi][ni][4 * a], acc[mi][ni][4 * a + 1], acc[mi][ni][4 * a + 2], acc[mi][ni][4 * a + 3]};
+                    }
+            }
+        }
+    }
+
+    float mean_r[MI], rstd_r[MI];
+    const bool ln = p.norm == LOKA_NORM_LAYERNORM;
+    if (p.norm == LOKA_NORM_NONE) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) { mean_r[mi] = 0.f; rstd_r[mi] = 1.f; }
+    } else {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            float n_ = cnt_lane, mean = 0.f, m2 = 0.f;
+            if (ln) {
+                float s = 0.f;
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    if (ncol[ni] < p.N) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) s += acc[mi][ni][i];
+                    }
+                mean = n_ > 0.f ? s * __builtin_amdgcn_rcpf(n_) : 0.f;
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    if (ncol[ni] < p.N) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) { const float d = acc[mi][ni][i] - mean; m2 += d * d; }
+                    }
+                // lanes l and l ^ 32 hold the same row: symmetric merge, identical bits on both
+                const float nb = wave_shfl_xor(n_, 32), mb = wave_shfl_xor(mean, 32), m2b = wave_shfl_xor(m2, 32);
+                const float nn = n_ + nb;
+                if (nn > 0.f) {
+                    const float d = mb - mean;
+                    const float rn = __builtin_amdgcn_rcpf(nn);
+                    const float newmean = (n_ * mean + nb * mb) * rn;
+                    m2 = m2 + m2b + d * d * (n_ * nb * rn);
+                    mean = newmean;
+                }
+                n_ = nn;
+            } else {
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    if (ncol[ni] < p.N) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) m2 += acc[mi][ni][i] * acc[mi][ni][i];
+                    }
+                m2 += wave_shfl_xor(m2, 32);
+            }
+            if (hk == 0) {
+                float* r3 = red + ((wave_m * WM + mi * 32 + l32) * 4 + wave_n) * 3;
+                r3[0] = n_; r3[1] = mean; r3[2] = m2;
+            }
+        }
+        __syncthreads();
+        // tile statistics per row: thread r < 256 merges the four column waves in order
+        float t_mean = 0.f, t_m2 = 0.f;
+        if (threadIdx.x < BM) {
+            float n_ = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float* r3 = red + (threadIdx.x * 4 + w) * 3;
+                if (ln) merge_stats(n_, t_mean, t_m2, r3[0], r3[1], r3[2]);
+                else t_m2 += r3[2];
+            }
+        }
+        LOKA_STAMP(2);
+        if (EPI == EPI_PANEL_SYNC) {
+            // publish (mean, M2) of this tile per row, signal, wait for the panel's other tiles, merge all tiles
+            const int panel = g * p.tiles_m + tm;
+            float* prow = p.part + (static_cast<int64_t>(g) * p.M) * (2 * p.tiles_n);
+            if (threadIdx.x < BM) {
+                const int m = m0 + threadIdx.x;
+                if (m < p.M) {
+                    float* dst = prow + static_cast<int64_t>(m) * (2 * p.tiles_n) + 2 * tn;
+                    __hip_atomic_store(dst, t_mean, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(dst + 1, t_m2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // the stores have completed before the barrier
+            }
+            __syncthreads();
+            LOKA_STAMP(3);
+            if (threadIdx.x == 0) {
+                unsigned* ctr = p.counters + panel;
+                __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                unsigned spins = 0;
+                while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < static_cast<unsigned>(p.tiles_n)) {
+                    __builtin_amdgcn_s_sleep(16);
+                    if (++spins > p.spin_limit) {
+                        __hip_atomic_store(p.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                }
+            }
+            __syncthreads();
+            LOKA_STAMP(4);
+            // two threads per row, each folds a contiguous half of the row's tiles in order (device-coherent
+            // 8-byte loads), symmetric merge of the halves: identical bits in every workgroup of the panel
+            {
+                const int r = static_cast<int>(threadIdx.x) >> 1, sub = static_cast<int>(threadIdx.x) & 1;
+                int m = m0 + r;
+                m = m < p.M ? m : p.M - 1;
+                const float* src = prow + static_cast<int64_t>(m) * (2 * p.tiles_n);
+                const int TH = (p.tiles_n + 1) >> 1;
+                float n_ = 0.f, mean = 0.f, m2 = 0.f;
+                for (int t0 = sub * TH; t0 < (sub + 1) * TH && t0 < p.tiles_n; t0 += 8) {
+                    unsigned long long raw[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        int tt = t0 + u;
+                        tt = tt < p.tiles_n ? tt : p.tiles_n - 1;
+                        raw[u] = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src + 2 * tt),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int tt = t0 + u;
+                        if (tt < (sub + 1) * TH && tt < p.tiles_n) {
+                            const float a = __uint_as_float(static_cast<unsigned>(raw[u]));
+                            const float b2 = __uint_as_float(static_cast<unsigned>(raw[u] >> 32));
+                            const int wcols = (tt + 1) * BN <= p.N ? BN : p.N - tt * BN;
+                            if (ln) merge_stats(n_, mean, m2, static_cast<float>(wcols), a, b2);
+                            else m2 += b2;
+                        }
+                    }
+                }
+                const float nb = wave_shfl_xor(n_, 1), mb = wave_shfl_xor(mean, 1), m2b = wave_shfl_xor(m2, 1);
+                if (ln) {
+                    const float nn = n_ + nb;
+                    if (nn > 0.f) {
+                        const float d = mb - mean;
+                        const float rn = __builtin_amdgcn_rcpf(nn);
+                        const float newmean = (n_ * mean + nb * mb) * rn;
+                        m2 = m2 + m2b + d * d * (n_ * nb * rn);
+                        mean = newmean;
+                    }
+                } else {
+                    m2 = m2 + m2b;
+                }
+                if (sub == 0) fin[r] = make_float2(ln ? mean : 0.f, __builtin_amdgcn_rsqf(m2 * inv_n + p.eps));
+            }
+        } else {
+            // the tile spans the whole row (N <= 256): finalize here
+            if (threadIdx.x < BM) fin[threadIdx.x] = make_float2(ln ? t_mean : 0.f, __builtin_amdgcn_rsqf(t_m2 * inv_n + p.eps));
+        }
+        __syncthreads();
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const float2 f = fin[wave_m * WM + mi * 32 + l32];
+            mean_r[mi] = f.x;
+            rstd_r[mi] = f.y;
+        }
+    }
+    LOKA_STAMP(5);
+
+    // ---- normalize, affine, bf16 store (two 16-byte stores per lane per 32-column tile)
+    const bool has_g = p.gamma != nullptr && p.norm != LOKA_NORM_NONE, has_b = p.beta != nullptr && ln;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        if (ncol[ni] >= p.N) continue;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int n = ncol[ni] + 8 * half;
+            float gm[8], bt[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { gm[e] = 1.f; bt[e] = 0.f; }
+            if (has_g) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(p.gamma + n);
+                gm[0] = bf16_lo(w.x); gm[1] = bf16_hi(w.x); gm[2] = bf16_lo(w.y); gm[3] = bf16_hi(w.y);
+                gm[4] = bf16_lo(w.z); gm[5] = bf16_hi(w.z); gm[6] = bf16_lo(w.w); gm[7] = bf16_hi(w.w);
+            }
+            if (has_b) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(p.beta + n);
+                bt[0] = bf16_lo(w.x); bt[1] = bf16_hi(w.x); bt[2] = bf16_lo(w.y); bt[3] = bf16_hi(w.y);
+                bt[4] = bf16_lo(w.z); bt[5] = bf16_hi(w.z); bt[6] = bf16_lo(w.w); bt[7] = bf16_hi(w.w);
+            }
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int m = m0 + wave_m * WM + mi * 32 + l32;
+                if (m >= p.M) continue;
+                float o[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    o[e] = (acc[mi][ni][8 * half + e] - mean_r[mi]) * rstd_r[mi];
+                    if (has_g) o[e] *= gm[e];
+                    if (has_b) o[e] += bt[e];
+                }
+                u32x4 pk;
+                pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
+                pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
+                __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(p.out + obase + static_cast<int64_t>(m) * p.N + n));
+            }
+        }
+    }
+    LOKA_STAMP(6);
+    __syncthreads();            // `fin` / `red` are read: the next tile's loads may overwrite the stages
+  }
+}
+
+#ifdef LOKA_DEBUG_TIMES
+extern "C" int loka_debug_read_times32(unsigned long long* host, int n) {
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(loka_dbg_times), sizeof(unsigned long long) * n) == hipSuccess ? 0 : 1;
+}
+#endif
+
+constexpr size_t kPanel32Lds = 5 * 256 * 128;   // the ring; the epilogue's scratch aliases it
+
+const void* panel32_fn() { return reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC>); }
+size_t panel32_lds() { return kPanel32Lds; }
+void panel32_launch(const GemmParams& p, dim3 grid, hipStream_t s) {
+    gemm_panel32_kernel<EPI_PANEL_SYNC><<<grid, 512, kPanel32Lds, s>>>(p);
+}
+
+}  // namespace loka
