@@ -34,6 +34,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wave_m = wave >> 2, wave_n = wave & 3;
+    const bool grp_b = wave >= 4;           // the second wave of each SIMD
     const int l32 = lane & 31, hk = lane >> 5;
 
     const int total_tiles = p.tiles_m * p.tiles_n * p.batch;
@@ -131,11 +132,12 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         for (int ni = 0; ni < NI; ++ni) mfma_one(mi, ni, set);
     };
     // MFMAs of the K half whose W fragments are in SET, with the LDS reads of K half S_READ of the entries in
-    // slots SLOT_X / SLOT_W, and (ISSUE) this wave's eight loads of the next two ring entries, spread between
-    // them in source order.  The matrix pipe then always has an instruction queued: a burst of LDS reads or of
-    // loads keeps the wave in the issue stage for hundreds of cycles (the load path accepts 64 bytes per
-    // clock per CU), and the other wave of the SIMD is in the same phase.
-#define LOKA_HALF_STEP(SLOT_X, SLOT_W, S_READ, SET, ISSUE)                           \
+    // slots SLOT_X / SLOT_W, and this wave's four loads of one new ring entry (LD: 0 none, 1 an X entry, 2 a W
+    // entry; into ld_slot, K offset ld_kb), spread between them in source order.  The matrix pipe then always
+    // has an instruction queued: a burst of LDS reads or of loads keeps a wave in the issue stage for hundreds
+    // of cycles (the load path accepts 64 bytes per clock per CU).  The two waves of a SIMD (w, w + 4) issue
+    // their loads in different gaps, so one of them is always free to feed the pipe.
+#define LOKA_HALF_STEP(SLOT_X, SLOT_W, S_READ, SET, LD)                              \
     do {                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                           \
         read_w(SLOT_W, S_READ, (SET) ^ 1);                                           \
@@ -143,27 +145,24 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             __builtin_amdgcn_sched_barrier(0);                                       \
             mfma_one(mi, 0, SET);                                                    \
             __builtin_amdgcn_sched_barrier(0);                                       \
-            if (ISSUE) {                                                             \
-                if (mi < 2) { if (more_w) issue_w1(slot_w_new, kb_w_new, 2 * mi); }  \
-                else if (more_x) issue_x1(slot_x_new, kb_x_new, 2 * mi - 4);         \
-            }                                                                        \
+            if ((LD) == 1 && ld_x && !grp_b) issue_x1(ld_x_slot, ld_x_kb, mi);       \
+            if ((LD) == 2 && ld_w && !grp_b) issue_w1(ld_w_slot, ld_w_kb, mi);       \
             __builtin_amdgcn_sched_barrier(0);                                       \
             mfma_one(mi, 1, SET);                                                    \
             __builtin_amdgcn_sched_barrier(0);                                       \
             read_x(SLOT_X, S_READ, mi);                                              \
-            if (ISSUE) {                                                             \
-                if (mi < 2) { if (more_w) issue_w1(slot_w_new, kb_w_new, 2 * mi + 1); } \
-                else if (more_x) issue_x1(slot_x_new, kb_x_new, 2 * mi - 3);         \
-            }                                                                        \
+            if ((LD) == 1 && ld_x && grp_b) issue_x1(ld_x_slot, ld_x_kb, mi);        \
+            if ((LD) == 2 && ld_w && grp_b) issue_w1(ld_w_slot, ld_w_kb, mi);        \
         }                                                                            \
         __builtin_amdgcn_sched_barrier(0);                                           \
     } while (0)
 
     // ---- main loop.  LDS holds a ring of five 32 KB entries X(0) W(0) X(1) W(1) X(2) ...; entry e lives in
     // slot e % 5.  One barrier per K step, in its middle, when every wave has read X(k) and W(k) completely and
-    // every wave's share of X(k + 1), W(k + 1) has landed; the two freed slots then take W(k + 2) and X(k + 3).
-    // X entries are requested two steps before their first read, W entries one step (half the bytes of a
-    // stage: the round trip through L2 under load is ~1 us for 64 KB, ~0.6 us for 32 KB; a step is ~1.2 us).
+    // every wave's share of X(k + 1), W(k + 1) has landed.  The slot of X(k) then takes W(k + 2) (loads issued
+    // in the second half of step k), the slot of W(k) takes X(k + 3) (first half of step k + 1): an X entry is
+    // requested 1.5 steps before its first read, a W entry one step (half the bytes of a stage: the round
+    // trip through L2 under load is ~1 us for 64 KB, ~0.6 us for 32 KB; a step is ~1.2 us).
     // All of a wave's loads return in issue order, so "vmcnt(4)" = everything but the newest entry's share.
     auto mod5 = [](int v) { return v >= 5 ? v - 5 : v; };
     LOKA_STAMP(0);
@@ -182,19 +181,47 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     // (the last K step is peeled: MFMAs under a condition inside the loop make the compiler copy accumulators)
     for (int k = 0; k + 1 < ksteps; ++k) {
         const int sw_cur = mod5(e5 + 1), sx_nxt = mod5(e5 + 2), sw_nxt = mod5(e5 + 3);
-        const bool more_w = k + 2 < ksteps, more_x = k + 3 < ksteps;
-        const int slot_w_new = e5, kb_w_new = (k + 2) * 128, slot_x_new = sw_cur, kb_x_new = (k + 3) * 128;
-        LOKA_HALF_STEP(e5, sw_cur, 1, 0, false);
-        if (more_w) __builtin_amdgcn_s_waitcnt(0x0F74);         // vmcnt(4): all but X(k + 2)
+        const bool ld_x = k >= 1 && k + 2 < ksteps, ld_w = k + 2 < ksteps;
+        const int ld_x_slot = mod5(e5 + 4), ld_x_kb = (k + 2) * 128;    // X(k + 2) -> the slot W(k - 1) left
+        const int ld_w_slot = e5, ld_w_kb = (k + 2) * 128;              // W(k + 2) -> the slot X(k) leaves
+        LOKA_HALF_STEP(e5, sw_cur, 1, 0, 1);
+        if (ld_w) __builtin_amdgcn_s_waitcnt(0x0F74);           // vmcnt(4): all but X(k + 2)
         else __builtin_amdgcn_s_waitcnt(0x0F70);
         lds_barrier();                                          // (also waits for this wave's LDS reads)
-        LOKA_HALF_STEP(sx_nxt, sw_nxt, 0, 1, true);             // + loads of W(k + 2), X(k + 3) into the freed slots
+        LOKA_HALF_STEP(sx_nxt, sw_nxt, 0, 1, 2);
         e5 = sx_nxt;
     }
     {
-        const bool more_w = false, more_x = false;
-        const int slot_w_new = 0, kb_w_new = 0, slot_x_new = 0, kb_x_new = 0;
-        LOKA_HALF_STEP(e5, mod5(e5 + 1), 1, 0, false);
+        const bool ld_x = false, ld_w = false;
+        const int ld_x_slot = 0, ld_x_kb = 0, ld_w_slot = 0, ld_w_kb = 0;
+        LOKA_HALF_STEP(e5, mod5(e5 + 1), 1, 0, 0);
+        (void)ld_x; (void)ld_w; (void)ld_x_slot; (void)ld_x_kb; (void)ld_w_slot; (void)ld_w_kb;
+    }
+    // scales of this lane's rows and columns: requested before the last eight MFMAs so that the round trip
+    // through L2 is covered (the fragment registers of the other K half are free by now)
+    // lane: rows m(mi) = m0 + 128 wave_m + 32 mi + l32; columns ncol(ni) + [0, 16), ncol = n0 + 64 wave_n + 32 ni + 16 hk
+    const bool tensor_x = p.x_mode == LOKA_SCALE_TENSOR, tensor_w = p.w_mode == LOKA_SCALE_TENSOR;
+    int ncol[NI];
+    float cnt_lane = 0.f;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        ncol[ni] = n0 + wave_n * WN + ni * 32 + hk * 16;
+        if (ncol[ni] < p.N) cnt_lane += 16.f;               // N % 16 == 0: a run of 16 is all in or all out
+    }
+    v4f s4[NI][4];
+    float sxm[MI];
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            if (tensor_w) { const float s = swg[0]; s4[ni][a] = v4f{s, s, s, s}; }
+            else s4[ni][a] = ncol[ni] < p.N ? *reinterpret_cast<const v4f*>(swg + ncol[ni] + 4 * a) : v4f{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        int m = m0 + wave_m * WM + mi * 32 + l32;
+        m = m < p.M ? m : p.M - 1;
+        sxm[mi] = tensor_x ? sxg[0] : sxg[m];
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -204,36 +231,15 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     LOKA_STAMP(1);
 
     // ------------------------------------------------------------------ epilogue
-    // lane: rows m(mi) = m0 + 128 wave_m + 32 mi + l32; columns ncol(ni) + [0, 16), ncol = n0 + 64 wave_n + 32 ni + 16 hk
     float* red = reinterpret_cast<float*>(smem);                                   // [BM][4][3]
     float2* fin = reinterpret_cast<float2*>(smem) + BM * 4 * 3 / 2 + 8;            // [BM] (mean, rstd)
     const int64_t obase = static_cast<int64_t>(g) * p.strideO;
-    const bool tensor_x = p.x_mode == LOKA_SCALE_TENSOR, tensor_w = p.w_mode == LOKA_SCALE_TENSOR;
-    int ncol[NI];
-    float cnt_lane = 0.f;
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-        ncol[ni] = n0 + wave_n * WN + ni * 32 + hk * 16;
-        if (ncol[ni] < p.N) cnt_lane += 16.f;               // N % 16 == 0: a run of 16 is all in or all out
-    }
-    // scales
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-        v4f s4[4];
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            if (tensor_w) { const float s = swg[0]; s4[a] = v4f{s, s, s, s}; }
-            else s4[a] = ncol[ni] < p.N ? *reinterpret_cast<const v4f*>(swg + ncol[ni] + 4 * a) : v4f{0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            int m = m0 + wave_m * WM + mi * 32 + l32;
-            m = m < p.M ? m : p.M - 1;
-            const float sxm = tensor_x ? sxg[0] : sxg[m];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[mi][ni][i] *= s4[i >> 2][i & 3] * sxm;
-        }
-    }
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] *= s4[ni][i >> 2][i & 3] * sxm[mi];
     if (p.y) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
@@ -274,7 +280,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 for (int ni = 0; ni < NI; ++ni)
                     if (ncol[ni] < p.N) {
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) { const float d = acc[mi][ni][i] - mean; m2 += d * d; }
+                        for (int i = 0; i < 16; ++i) { const float d = acc[mi][ni][i] - mean; m2 = __builtin_fmaf(d, d, m2); }
                     }
                 // lanes l and l ^ 32 hold the same row: symmetric merge, identical bits on both
                 const float nb = wave_shfl_xor(n_, 32), mb = wave_shfl_xor(mean, 32), m2b = wave_shfl_xor(m2, 32);
@@ -292,7 +298,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 for (int ni = 0; ni < NI; ++ni)
                     if (ncol[ni] < p.N) {
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) m2 += acc[mi][ni][i] * acc[mi][ni][i];
+                        for (int i = 0; i < 16; ++i) m2 = __builtin_fmaf(acc[mi][ni][i], acc[mi][ni][i], m2);
                     }
                 m2 += wave_shfl_xor(m2, 32);
             }
@@ -400,44 +406,66 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             rstd_r[mi] = f.y;
         }
     }
+    float nmr_r[MI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) nmr_r[mi] = -mean_r[mi] * rstd_r[mi];
     LOKA_STAMP(5);
 
-    // ---- normalize, affine, bf16 store (two 16-byte stores per lane per 32-column tile)
+    // ---- normalize, affine, bf16 store.  A lane holds 16 consecutive columns of ONE row per 32 x 32 sub-tile;
+    // stored from there, an instruction would touch 32 rows with 32 bytes each.  Each wave instead passes the
+    // sub-tile through 2 KB of its own LDS (64-byte rows, 16-byte chunk c of row r at position c ^ (r / 4 % 4):
+    // conflict-free both ways) and stores it with 4 lanes per row: 16 full 64-byte runs per instruction.
+    // LDS executes one wave's instructions in order, so the same buffer serves every sub-tile without a barrier.
     const bool has_g = p.gamma != nullptr && p.norm != LOKA_NORM_NONE, has_b = p.beta != nullptr && ln;
+    uint8_t* const tbuf = smem + 16384 + wave * 2048;
+    const int t_wr = l32 * 64, t_key = (l32 >> 2) & 3;
+    const int t_row = lane >> 2, t_c = lane & 3;                       // store side: row (+ 16 j), chunk
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
-        if (ncol[ni] >= p.N) continue;
+        float gm[16], bt[16];
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int n = ncol[ni] + 8 * half;
-            float gm[8], bt[8];
+        for (int e = 0; e < 16; ++e) { gm[e] = 1.f; bt[e] = 0.f; }
+        if (ncol[ni] < p.N) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) { gm[e] = 1.f; bt[e] = 0.f; }
-            if (has_g) {
-                const u32x4 w = *reinterpret_cast<const u32x4*>(p.gamma + n);
-                gm[0] = bf16_lo(w.x); gm[1] = bf16_hi(w.x); gm[2] = bf16_lo(w.y); gm[3] = bf16_hi(w.y);
-                gm[4] = bf16_lo(w.z); gm[5] = bf16_hi(w.z); gm[6] = bf16_lo(w.w); gm[7] = bf16_hi(w.w);
+            for (int half = 0; half < 2; ++half) {
+                if (has_g) {
+                    const u32x4 w = *reinterpret_cast<const u32x4*>(p.gamma + ncol[ni] + 8 * half);
+                    float* q = gm + 8 * half;
+                    q[0] = bf16_lo(w.x); q[1] = bf16_hi(w.x); q[2] = bf16_lo(w.y); q[3] = bf16_hi(w.y);
+                    q[4] = bf16_lo(w.z); q[5] = bf16_hi(w.z); q[6] = bf16_lo(w.w); q[7] = bf16_hi(w.w);
+                }
+                if (has_b) {
+                    const u32x4 w = *reinterpret_cast<const u32x4*>(p.beta + ncol[ni] + 8 * half);
+                    float* q = bt + 8 * half;
+                    q[0] = bf16_lo(w.x); q[1] = bf16_hi(w.x); q[2] = bf16_lo(w.y); q[3] = bf16_hi(w.y);
+                    q[4] = bf16_lo(w.z); q[5] = bf16_hi(w.z); q[6] = bf16_lo(w.w); q[7] = bf16_hi(w.w);
+                }
             }
-            if (has_b) {
-                const u32x4 w = *reinterpret_cast<const u32x4*>(p.beta + n);
-                bt[0] = bf16_lo(w.x); bt[1] = bf16_hi(w.x); bt[2] = bf16_lo(w.y); bt[3] = bf16_hi(w.y);
-                bt[4] = bf16_lo(w.z); bt[5] = bf16_hi(w.z); bt[6] = bf16_lo(w.w); bt[7] = bf16_hi(w.w);
-            }
+        }
+        const int col = n0 + wave_n * WN + ni * 32 + t_c * 8;         // store side: this lane's 8 columns
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                const int m = m0 + wave_m * WM + mi * 32 + l32;
-                if (m >= p.M) continue;
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
                 float o[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    o[e] = (acc[mi][ni][8 * half + e] - mean_r[mi]) * rstd_r[mi];
-                    if (has_g) o[e] *= gm[e];
-                    if (has_b) o[e] += bt[e];
+                    // (y - mean) * rstd as one fused multiply-add, the affine part as another
+                    o[e] = __builtin_fmaf(acc[mi][ni][8 * half + e], rstd_r[mi], nmr_r[mi]);
+                    if (has_g || has_b) o[e] = __builtin_fmaf(o[e], gm[8 * half + e], bt[8 * half + e]);
                 }
                 u32x4 pk;
                 pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
                 pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
-                __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(p.out + obase + static_cast<int64_t>(m) * p.N + n));
+                *reinterpret_cast<u32x4*>(tbuf + t_wr + (((2 * hk + half) ^ t_key) << 4)) = pk;
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int r = 16 * j + t_row;
+                const u32x4 pk = *reinterpret_cast<const u32x4*>(tbuf + r * 64 + ((t_c ^ ((r >> 2) & 3)) << 4));
+                const int m = m0 + wave_m * WM + mi * 32 + r;
+                if (m < p.M && col < p.N)
+                    __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(p.out + obase + static_cast<int64_t>(m) * p.N + col));
             }
         }
     }
