@@ -59,22 +59,34 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     const int ksteps = p.KB / 128;
     const float inv_n = 1.0f / static_cast<float>(p.N);
 
+    // buffer descriptors of the tile whose operands are being streamed (bounds = the rows that exist: rows
+    // past the end of X or W read as zeros)
+    __amdgpu_buffer_rsrc_t x_rsrc, w_rsrc;
+    auto set_rsrc = [&](int tile_id) __attribute__((always_inline)) {
+        int t = tile_id;
+        const int tn_ = t % p.tiles_n; t /= p.tiles_n;
+        const int tm_ = t % p.tiles_m;
+        const int g_ = t / p.tiles_m;
+        const int m0_ = tm_ * BM, n0_ = tn_ * BN;
+        const int x_rows = p.M - m0_ < BM ? p.M - m0_ : BM, w_rows = p.N - n0_ < BN ? p.N - n0_ : BN;
+        x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t*>(p.X + static_cast<int64_t>(g_) * p.strideX + static_cast<int64_t>(m0_) * p.KB), 0,
+            x_rows * p.KB, 0x00020000);
+        w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t*>(p.W + static_cast<int64_t>(g_) * p.strideW + static_cast<int64_t>(n0_) * p.KB), 0,
+            w_rows * p.KB, 0x00020000);
+    };
+    bool prefetched = false;        // ring entries X(0) W(0) X(1) W(1) of `tile` were requested during the previous epilogue
+
   for (int tile = tile_first; tile < total_tiles; tile += tile_stride) {
     int t = tile;
     const int tn = t % p.tiles_n; t /= p.tiles_n;
     const int tm = t % p.tiles_m;
     const int g = t / p.tiles_m;
     const int m0 = tm * BM, n0 = tn * BN;
-    const uint8_t* Xg = p.X + static_cast<int64_t>(g) * p.strideX;
-    const uint8_t* Wg = p.W + static_cast<int64_t>(g) * p.strideW;
     const float* sxg = p.sx + static_cast<int64_t>(g) * p.strideSx;
     const float* swg = p.sw + static_cast<int64_t>(g) * p.strideSw;
-
-    const int x_rows = p.M - m0 < BM ? p.M - m0 : BM, w_rows = p.N - n0 < BN ? p.N - n0 : BN;
-    const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t*>(Xg + static_cast<int64_t>(m0) * p.KB), 0, x_rows * p.KB, 0x00020000);
-    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t*>(Wg + static_cast<int64_t>(n0) * p.KB), 0, w_rows * p.KB, 0x00020000);
+    if (!prefetched) set_rsrc(tile);
     // this wave's share of one ring entry (the X or the W rows of K step kb / 128) is four loads of 1 KB:
     // row groups wave, wave + 8, wave + 16, wave + 24; load j of an entry
     auto issue_x1 = [&](int slot, int kb, int j) __attribute__((always_inline)) {
@@ -166,18 +178,27 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     // All of a wave's loads return in issue order, so "vmcnt(4)" = everything but the newest entry's share.
     auto mod5 = [](int v) { return v >= 5 ? v - 5 : v; };
     LOKA_STAMP(0);
-    issue_x(0, 0);
-    issue_w(1, 0);
-    if (ksteps > 1) { issue_x(2, 128); issue_w(3, 128); }
-    if (ksteps > 2) issue_x(4, 256);
-    if (ksteps > 2) __builtin_amdgcn_s_waitcnt(0x0F7C);         // vmcnt(12)
-    else if (ksteps > 1) __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8)
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    // entry e of a tile lives in slot (e + 1) % 5: slot 0, which the epilogue uses as scratch, is the last to fill
+    if (!prefetched) {
+        issue_x(1, 0);
+        issue_w(2, 0);
+        if (ksteps > 1) { issue_x(3, 128); issue_w(4, 128); }
+    }
+    if (ksteps > 2) issue_x(0, 256);
+    if (ksteps > 2) {
+        // loads return in issue order, so "at most 4 (12) outstanding" covers X(0), W(0) whatever else (the
+        // previous tile's stores) is still in flight
+        if (prefetched) __builtin_amdgcn_s_waitcnt(0x0F74); else __builtin_amdgcn_s_waitcnt(0x0F7C);
+    } else if (ksteps > 1 && !prefetched) {
+        __builtin_amdgcn_s_waitcnt(0x0F78);
+    } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
     lds_barrier();
-    read_w(1, 0, 0);
+    read_w(2, 0, 0);
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) read_x(0, 0, mi);
-    int e5 = 0;                                                 // slot of X(k)
+    for (int mi = 0; mi < MI; ++mi) read_x(1, 0, mi);
+    int e5 = 1;                                                 // slot of X(k)
     // (the last K step is peeled: MFMAs under a condition inside the loop make the compiler copy accumulators)
     for (int k = 0; k + 1 < ksteps; ++k) {
         const int sw_cur = mod5(e5 + 1), sx_nxt = mod5(e5 + 2), sw_nxt = mod5(e5 + 3);
@@ -229,6 +250,14 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
 #undef LOKA_HALF_STEP
     __syncthreads();                                        // LDS is free for the epilogue
     LOKA_STAMP(1);
+    // the next tile's first four ring entries stream in while this tile's statistics are exchanged
+    prefetched = tile + tile_stride < total_tiles;
+    if (prefetched) {
+        set_rsrc(tile + tile_stride);
+        issue_x(1, 0);
+        issue_w(2, 0);
+        if (ksteps > 1) { issue_x(3, 128); issue_w(4, 128); }
+    }
 
     // ------------------------------------------------------------------ epilogue
     float* red = reinterpret_cast<float*>(smem);                                   // [BM][4][3]
@@ -470,7 +499,8 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         }
     }
     LOKA_STAMP(6);
-    __syncthreads();            // `fin` / `red` are read: the next tile's loads may overwrite the stages
+    lds_barrier();              // the epilogue's scratch (slot 0) is read: the next tile may load into it.  The
+                                // stores stay in flight.
   }
 }
 
