@@ -701,6 +701,13 @@ static void launch_fp8(const GemmParams& p, bool blockwise, dim3 grid, hipStream
     else gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, false, EPI><<<grid, threads, lds, s>>>(p);
 }
 
+// gemm_wreg.hip
+bool wreg_supports(int64_t M, int64_t N, int64_t K);
+int wreg_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, const void** fn, size_t* lds);
+void wreg_launch(const GemmParams& p, dim3 grid, hipStream_t s);
+static void launch_wreg_any(const GemmParams& p, bool, dim3 grid, hipStream_t s) { wreg_launch(p, grid, s); }
+static const char kWregName[] = "wreg32";
+
 // gemm_panel32.hip
 const void* panel32_fn();
 size_t panel32_lds();
@@ -721,6 +728,9 @@ static const VariantInfo kVariants[] = {
     LOKA_VARIANT("row128x256", 128, 256, 1, 2, 4, EPI_ROW_IN_TILE),
     LOKA_VARIANT("row64x512", 64, 512, 1, 1, 8, EPI_ROW_IN_TILE),
     LOKA_VARIANT("row64x1024", 64, 512, 2, 1, 8, EPI_ROW_IN_TILE),
+    // skinny layers (K * N <= 256 KB, non-blockwise scales): W resident in registers, X streamed in 32-row
+    // blocks; one of several instantiations behind one name, workgroup count and LDS decided at launch
+    {kWregName, 32, 1024, 512, EPI_ROW_IN_TILE, 0, &launch_wreg_any, nullptr, nullptr},
     // rows spanning several workgroups: Y + per-tile statistics, then a normalization pass
     LOKA_VARIANT("twopass128x128", 128, 128, 1, 2, 2, EPI_PARTIAL_STATS),
     LOKA_VARIANT("twopass256x256", 256, 256, 1, 2, 2, EPI_PARTIAL_STATS),
@@ -750,6 +760,7 @@ int variant_bm(int v) { return kVariants[v].bm; }
 bool variant_supports(const loka_gemm_desc* d, int v) {
     if (v < 0 || v >= kNumVariants) return false;
     const VariantInfo& vi = kVariants[v];
+    if (vi.name == kWregName) return d->x_mode != LOKA_SCALE_BLOCK_1x128 && wreg_supports(d->M, d->N, d->K);
     if ((d->x_mode == LOKA_SCALE_BLOCK_1x128 ? vi.fn_block : vi.fn_plain) == nullptr) return false;
     if (vi.epi == EPI_ROW_IN_TILE && d->N > vi.bn) return false;
     if (vi.epi == EPI_PANEL_SYNC && (d->N + vi.bn - 1) / vi.bn > kNumCUs) return false;
@@ -817,6 +828,18 @@ loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* 
         stats = (stats + 255) & ~size_t(255);
         p.part = static_cast<float*>(workspace);
         if (!y) p.y = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + stats);
+    }
+    if (vi.name == kWregName) {
+        int dev = 0, cus = 0;
+        const void* fn = nullptr;
+        size_t lds = 0;
+        LOKA_HIP_TRY(hipGetDevice(&dev));
+        LOKA_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        const int wgs = wreg_plan(d->M, d->N, d->K, d->batch, cus, &fn, &lds);
+        if (wgs <= 0) return LOKA_ERR_UNSUPPORTED;
+        if (set_lds(fn, lds) != LOKA_OK) return LOKA_ERR_HIP;
+        vi.launch(p, false, dim3(static_cast<unsigned>(wgs)), s);
+        return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
     }
     if (set_lds(blockwise ? vi.fn_block : vi.fn_plain, vi.lds) != LOKA_OK) return LOKA_ERR_HIP;
     dim3 grid(static_cast<unsigned>(static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.batch));

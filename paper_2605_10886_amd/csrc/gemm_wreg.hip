@@ -1,0 +1,435 @@
+// Skinny FP8 GEMM with the row norm fused: W stays in registers, X streams through LDS.
+//
+// The layers this serves (K * N <= 256 KB: 256 x 1024, 512 x 512, 1024 x 256, 256 x 256 ...) are bound by the
+// HBM traffic of X and O, not by the matrix pipe: per 32 rows of X a CU reads 32 K bytes, writes 64 N bytes and
+// spends well under a microsecond on MFMAs.  A tiled kernel re-streams W through LDS for every tile and runs
+// load -> compute -> normalize -> store one after the other; here
+//   * each of the 8 waves keeps its N / 8 columns of W (all of K) in registers for the whole launch (at most
+//     128 registers per lane: the 256 KB of W fill half the register file of a CU), so W costs no LDS or L2
+//     traffic after the first block;
+//   * X arrives in blocks of 32 rows through a ring of 3-4 LDS buffers, requested 2-3 blocks ahead by waves
+//     0..3 ONLY; the bf16 output leaves through an LDS staging buffer and is stored by waves 4..7 ONLY.  The
+//     counter that tracks a wave's outstanding memory operations counts loads and stores together, so a wave
+//     that did both would have to wait for its stores (an HBM round trip) before it could tell that the next
+//     block has landed; with the roles split, the loaders' counter sees only loads (which return in order) and
+//     the storers never wait at all.
+//   * the row statistics of a block are exchanged between the 8 waves through LDS (the tile spans the row).
+// One workgroup per CU walks a contiguous range of row blocks (a grouped launch keeps a workgroup inside one
+// problem as long as possible; W is reloaded when the problem changes).
+//
+// MFMA operand roles and the W row permutation are those of gemm_panel32.hip: W rows -> MFMA rows, X rows ->
+// MFMA columns, so a lane ends with 16 consecutive output columns of one output row (= lane % 32).
+#include "gemm_common.h"
+
+namespace loka {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int N_>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N_ & 15) | ((N_ >> 4) << 14));
+}
+
+template <int WNC, int KS, int RT>
+struct WregCfg {
+    static constexpr int NIW = WNC / 32;                  // 32-column MFMA tiles per wave
+    static constexpr int KB = KS * 64;                    // bytes per row of X / W
+    static constexpr int NT = 8 * WNC;                    // columns the workgroup covers
+    static constexpr int RB = 32 * RT;                    // rows per block
+    static constexpr int XBYTES = RB * KB;
+    static constexpr int OBYTES = RB * NT * 2;
+    static constexpr int NBUF_ = (131072 - OBYTES) / XBYTES;
+    static constexpr int NBUF = NBUF_ > 4 ? 4 : NBUF_ < 2 ? 2 : NBUF_;
+    static constexpr int LPW = XBYTES / 1024 / 4;         // X loads of 1 KB per loader wave per block
+    static constexpr int SXL = (RB + 63) / 64;            // loads of 64 row scales per loader wave per block
+    static constexpr int LDW = LPW + SXL;
+    static constexpr int SWIN = KB / 16 < 16 ? KB / 16 : 16;   // swizzle window, 16-byte chunks
+    static constexpr int OFF_X = 0;
+    static constexpr int OFF_SX = OFF_X + NBUF * XBYTES;  // [NBUF][4 loaders][SXL][64] fp32
+    static constexpr int OFF_OB = OFF_SX + NBUF * 4 * SXL * 256;   // [RB][NT] bf16, chunk c of row r at c ^ (r % 16)
+    static constexpr int OFF_SW = OFF_OB + OBYTES;        // [NT] fp32 column scales (0 beyond N)
+    static constexpr int OFF_GM = OFF_SW + NT * 4;        // [NT] fp32 gamma (1 when absent)
+    static constexpr int OFF_BT = OFF_GM + NT * 4;        // [NT] fp32 beta (0 when absent)
+    static constexpr int OFF_RED = OFF_BT + NT * 4;       // [RB][9] (count, mean, M2, -); 9: rows on distinct banks
+    static constexpr int LDS = OFF_RED + RB * 9 * 16;
+    static_assert(LDS <= 160 * 1024, "LDS budget");
+    static_assert(LPW >= 1, "a block is at least 4 KB");
+};
+
+template <int WNC, int KS, int RT>
+__global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, const int blocks_per_problem) {
+    using C = WregCfg<WNC, KS, RT>;
+    constexpr int NIW = C::NIW, KB = C::KB, NT = C::NT, RB = C::RB, NBUF = C::NBUF, LPW = C::LPW, LDW = C::LDW, SXL = C::SXL;
+    constexpr int KEYMASK = C::SWIN - 1;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool loader = wave < 4, storer = wave >= 4;
+    const bool ln = p.norm == LOKA_NORM_LAYERNORM;
+    const bool tensor_x = p.x_mode == LOKA_SCALE_TENSOR, tensor_w = p.w_mode == LOKA_SCALE_TENSOR;
+    const float inv_n = 1.0f / static_cast<float>(p.N);
+
+    // contiguous range of row blocks of this workgroup
+    const int64_t total = static_cast<int64_t>(p.batch) * blocks_per_problem;
+    const int b0 = static_cast<int>(total * blockIdx.x / gridDim.x), b1 = static_cast<int>(total * (blockIdx.x + 1) / gridDim.x);
+    if (b0 >= b1) return;
+
+    // ---- loader side: block `b` -> ring slot b % NBUF.  Lane i of load `ld` fills bytes [16 i, +16) of the
+    // ld-th KB of the block: row (1024 ld + 16 i) / KB, chunk position pos; it fetches chunk pos ^ key(row).
+    auto issue_block = [&](int b) __attribute__((always_inline)) {
+        const int g = b / blocks_per_problem, m0 = (b - g * blocks_per_problem) * RB;
+        const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t*>(p.X + static_cast<int64_t>(g) * p.strideX), 0, p.M * KB, 0x00020000);
+        uint8_t* const dst = smem + C::OFF_X + (b % NBUF) * C::XBYTES;
+        int lv = lane;
+        asm volatile("; lane id" : "+v"(lv));                           // (offsets recomputed here, not kept in registers)
+#pragma unroll
+        for (int q = 0; q < LPW; ++q) {
+            const int ld = wave + 4 * q;
+            const int byte = ld * 1024 + lv * 16;
+            const int row = byte / KB, pos = (byte % KB) >> 4;
+            const int voff = row * KB + ((pos ^ (row & KEYMASK)) << 4);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void*)(dst + ld * 1024), 16, voff,
+                                                     m0 * KB, 0, 0);
+        }
+        // row scales of the block, 64 per load (4 bytes per lane); rows past M read as 0
+        const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(p.sx + static_cast<int64_t>(g) * p.strideSx), 0, tensor_x ? 4 : p.M * 4, 0x00020000);
+#pragma unroll
+        for (int q = 0; q < SXL; ++q)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                sr, (__attribute__((address_space(3))) void*)(smem + C::OFF_SX + (((b % NBUF) * 4 + wave) * SXL + q) * 256), 4,
+                tensor_x ? 0 : (m0 + 64 * q + lv) * 4, 0, 0, 0);
+    };
+
+    // ---- W fragments of this wave's columns, all of K: wreg[ni][j] feeds MFMA rows with W rows (= output
+    // columns) wave * WNC + 32 ni + wperm(lane), K bytes [64 j + 32 hk, +32)
+    v8i wreg[NIW][KS];
+    auto load_problem = [&](int g) __attribute__((always_inline)) {
+        int lv = lane;
+        asm volatile("; lane id" : "+v"(lv));                           // (offsets recomputed here, not kept in registers)
+        const int l32 = lv & 31, hk = lv >> 5;
+        const int wperm = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
+        const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t*>(p.W + static_cast<int64_t>(g) * p.strideW), 0, p.N * KB, 0x00020000);
+#pragma unroll
+        for (int ni = 0; ni < NIW; ++ni) {
+            const int n = wave * WNC + ni * 32 + wperm;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                const int off = n * KB + j * 64 + hk * 32;
+                const u32x4 lo = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0));
+                const u32x4 hi = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(wr, off + 16, 0, 0));
+                wreg[ni][j] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            }
+        }
+        const float* swg = p.sw + static_cast<int64_t>(g) * p.strideSw;
+        float* swl = reinterpret_cast<float*>(smem + C::OFF_SW);
+        float* gml = reinterpret_cast<float*>(smem + C::OFF_GM);
+        float* btl = reinterpret_cast<float*>(smem + C::OFF_BT);
+        for (int n = threadIdx.x; n < NT; n += 512) {
+            const bool in = n < p.N;
+            swl[n] = in ? (tensor_w ? swg[0] : swg[n]) : 0.f;
+            gml[n] = (in && p.gamma && p.norm != LOKA_NORM_NONE) ? bf16_bits_to_f32(p.gamma[n]) : 1.f;
+            btl[n] = (in && p.beta && ln) ? bf16_bits_to_f32(p.beta[n]) : 0.f;
+        }
+    };
+
+    { const int tile = b0; (void)tile; LOKA_STAMP(6); }
+    int cur_g = b0 / blocks_per_problem;
+    load_problem(cur_g);
+    if (loader) {
+#pragma unroll
+        for (int i = 0; i < NBUF - 1; ++i)
+            if (b0 + i < b1) issue_block(b0 + i);
+    }
+    __syncthreads();                                                    // scales / gamma / beta are in LDS
+    { const int tile = b0; (void)tile; LOKA_STAMP(7); }
+
+    for (int b = b0; b < b1; ++b) {
+        const int g = b / blocks_per_problem, m0 = (b - g * blocks_per_problem) * RB;
+        const int tile = b;
+        (void)tile;
+        LOKA_STAMP(0);
+        if (g != cur_g) {
+            __syncthreads();                                            // everyone is done with the previous problem's tables
+            load_problem(g);
+            cur_g = g;
+            __syncthreads();
+        }
+        // block b has landed: the loaders' newer requests (up to NBUF - 2 blocks) may still be in flight
+        if (loader) {
+            const int newer = b1 - 1 - b < NBUF - 2 ? b1 - 1 - b : NBUF - 2;
+            if (p.y) wait_vmcnt<0>();                                   // Y stores share the counter
+            else if (newer >= 2) wait_vmcnt<(NBUF >= 4 ? 2 : 0) * LDW>();
+            else if (newer == 1) wait_vmcnt<(NBUF >= 3 ? 1 : 0) * LDW>();
+            else wait_vmcnt<0>();
+        }
+        lds_barrier();
+        LOKA_STAMP(1);
+        if (loader && b + NBUF - 1 < b1) issue_block(b + NBUF - 1);     // into the slot block b - 1 left
+
+        // Per-lane offsets are recomputed from an opaque copy of the lane id in every block: derived from a
+        // loop-invariant value the compiler would keep dozens of addresses in registers, which W needs.
+        int lanev = lane;
+        asm volatile("; per-block lane id" : "+v"(lanev));
+        const int l32 = lanev & 31, hk = lanev >> 5;
+        const int xkey = l32 & KEYMASK;
+        const int x_rd = l32 * KB + (((2 * hk) ^ xkey) << 4);          // + 32 KB rt, ^ (64 j + 16 h) per fragment half
+        int colbase[NIW];
+        float cnt_lane = 0.f;
+#pragma unroll
+        for (int ni = 0; ni < NIW; ++ni) {
+            colbase[ni] = wave * WNC + ni * 32 + hk * 16;
+            if (colbase[ni] < p.N) cnt_lane += 16.f;                    // N % 16 == 0
+        }
+        uint8_t* const obuf = smem + C::OFF_OB;
+        float4* const red = reinterpret_cast<float4*>(smem + C::OFF_RED);
+
+        // ---- MFMAs: for each K step of 64, RT row tiles x NIW column tiles
+        const uint8_t* xs = smem + C::OFF_X + (b % NBUF) * C::XBYTES;
+        v16f acc[RT][NIW];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int ni = 0; ni < NIW; ++ni)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[rt][ni][i] = 0.f;
+        // X fragments one or two (row tile, K step) pairs ahead of the MFMAs that use them
+        constexpr int XD = (NIW * KS + RT * NIW * 2) >= 20 ? 2 : 3;     // ring of fragments (registers are short when W fills 128)
+        constexpr int NS = KS * RT;
+        v8i xf[XD];
+        auto read_xf = [&](int q) __attribute__((always_inline)) {      // q = j * RT + rt
+            const int j = q / RT, rt = q % RT;
+            const v4i lo = *reinterpret_cast<const v4i*>(xs + rt * 32 * KB + (x_rd ^ (64 * j)));
+            const v4i hi = *reinterpret_cast<const v4i*>(xs + rt * 32 * KB + (x_rd ^ (64 * j + 16)));
+            xf[q % XD] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        };
+#pragma unroll
+        for (int q = 0; q < XD - 1 && q < NS; ++q) read_xf(q);
+#pragma unroll
+        for (int q = 0; q < NS; ++q) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (q + XD - 1 < NS) read_xf(q + XD - 1);
+#pragma unroll
+            for (int ni = 0; ni < NIW; ++ni)
+                acc[q % RT][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wreg[ni][q / RT], xf[q % XD], acc[q % RT][ni],
+                                                                                 0, 0, 0, 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        LOKA_STAMP(2);
+
+        // ---- scales, row statistics (lane -> pair of lanes with the same row -> the 8 waves through LDS)
+        const float* sxl = reinterpret_cast<const float*>(smem + C::OFF_SX + (b % NBUF) * 4 * SXL * 256);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const float sxm = sxl[rt * 32 + l32];
+#pragma unroll
+            for (int ni = 0; ni < NIW; ++ni) {
+                __builtin_amdgcn_sched_barrier(0);      // one tile's table reads at a time: W leaves few registers free
+                const v4f* sw4 = reinterpret_cast<const v4f*>(smem + C::OFF_SW + colbase[ni] * 4);
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const v4f s = sw4[a];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[rt][ni][4 * a + e] *= s[e] * sxm;
+                }
+            }
+            const int m = m0 + rt * 32 + l32;
+            if (p.y && m < p.M) {
+                float* yrow = p.y + static_cast<int64_t>(g) * p.strideO + static_cast<int64_t>(m) * p.N;
+#pragma unroll
+                for (int ni = 0; ni < NIW; ++ni)
+                    if (colbase[ni] < p.N) {
+#pragma unroll
+                        for (int a = 0; a < 4; ++a)
+                            *reinterpret_cast<v4f*>(yrow + colbase[ni] + 4 * a) =
+                                v4f{acc[rt][ni][4 * a], acc[rt][ni][4 * a + 1], acc[rt][ni][4 * a + 2], acc[rt][ni][4 * a + 3]};
+                    }
+            }
+            if (p.norm != LOKA_NORM_NONE) {
+                float n_ = cnt_lane, mean = 0.f, m2 = 0.f;
+                if (ln) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int ni = 0; ni < NIW; ++ni)
+                        if (colbase[ni] < p.N) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) s += acc[rt][ni][i];
+                        }
+                    mean = n_ > 0.f ? s * __builtin_amdgcn_rcpf(n_) : 0.f;
+#pragma unroll
+                    for (int ni = 0; ni < NIW; ++ni)
+                        if (colbase[ni] < p.N) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) { const float d = acc[rt][ni][i] - mean; m2 = __builtin_fmaf(d, d, m2); }
+                        }
+                    // lanes l and l ^ 32 hold the same row: symmetric merge, identical bits on both
+                    const float nb = wave_shfl_xor(n_, 32), mb = wave_shfl_xor(mean, 32), m2b = wave_shfl_xor(m2, 32);
+                    const float nn = n_ + nb;
+                    if (nn > 0.f) {
+                        const float d = mb - mean;
+                        const float rn = __builtin_amdgcn_rcpf(nn);
+                        const float newmean = (n_ * mean + nb * mb) * rn;
+                        m2 = m2 + m2b + d * d * (n_ * nb * rn);
+                        mean = newmean;
+                    }
+                    n_ = nn;
+                } else {
+#pragma unroll
+                    for (int ni = 0; ni < NIW; ++ni)
+                        if (colbase[ni] < p.N) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) m2 = __builtin_fmaf(acc[rt][ni][i], acc[rt][ni][i], m2);
+                        }
+                    m2 += wave_shfl_xor(m2, 32);
+                }
+                if (hk == 0) red[(rt * 32 + l32) * 9 + wave] = make_float4(n_, mean, m2, 0.f);
+            }
+        }
+        float mean_r[RT], rstd_r[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) { mean_r[rt] = 0.f; rstd_r[rt] = 1.f; }
+        if (p.norm != LOKA_NORM_NONE) {
+            LOKA_STAMP(3);
+            lds_barrier();
+            // every lane folds the 8 waves of its rows in the same order: identical bits everywhere.  Four
+            // entries are read at a time, the folds are branch-free (an empty part has count 0 and changes nothing).
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                float tn = 0.f, tmean = 0.f, tm2 = 0.f;
+#pragma unroll
+                for (int h4 = 0; h4 < 2; ++h4) {
+                    float4 r[4];
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) r[w] = red[(rt * 32 + l32) * 9 + 4 * h4 + w];
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        if (ln) {
+                            const float nn = tn + r[w].x;
+                            const float f = r[w].x > 0.f ? r[w].x * __builtin_amdgcn_rcpf(nn) : 0.f;
+                            const float d = r[w].y - tmean;
+                            tmean = tmean + d * f;
+                            tm2 = tm2 + r[w].z + d * d * tn * f;
+                            tn = nn;
+                        } else {
+                            tm2 += r[w].z;
+                        }
+                    }
+                }
+                mean_r[rt] = ln ? tmean : 0.f;
+                rstd_r[rt] = __builtin_amdgcn_rsqf(tm2 * inv_n + p.eps);
+            }
+        }
+        LOKA_STAMP(4);
+
+        // ---- normalize, affine, bf16 into the staging buffer (row 32 rt + l32; 16-byte chunk c at position c ^ (row % 16))
+#pragma unroll
+        for (int ni = 0; ni < NIW; ++ni) {
+            const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + colbase[ni] * 4);
+            const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + colbase[ni] * 4);
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                __builtin_amdgcn_sched_barrier(0);
+                const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
+                const int c = (colbase[ni] >> 3) + half;
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    const float nmr = -mean_r[rt] * rstd_r[rt];
+                    float o[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        o[e] = __builtin_fmaf(__builtin_fmaf(acc[rt][ni][8 * half + e], rstd_r[rt], nmr), gq0[e], bq0[e]);
+                        o[4 + e] = __builtin_fmaf(__builtin_fmaf(acc[rt][ni][8 * half + 4 + e], rstd_r[rt], nmr), gq1[e], bq1[e]);
+                    }
+                    u32x4 pk;
+                    pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
+                    pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
+                    *reinterpret_cast<u32x4*>(obuf + (rt * 32 + l32) * (NT * 2) + ((c ^ (l32 & 15)) << 4)) = pk;
+                }
+            }
+        }
+        lds_barrier();
+        LOKA_STAMP(5);
+        // ---- the storers write the block: 64 consecutive chunks (1 KB) per instruction, whole rows
+        if (storer) {
+            constexpr int CPR = NT / 8;                                 // chunks per row
+            constexpr int INSTR = RB * CPR / 64 / 4;                    // per storer wave
+            uint16_t* const og = p.out + static_cast<int64_t>(g) * p.strideO;
+#pragma unroll
+            for (int s = 0; s < INSTR; ++s) {
+                if (s % 2 == 0) __builtin_amdgcn_sched_barrier(0);      // two in flight: W leaves few registers free
+                const int id = ((wave - 4) + 4 * s) * 64 + lanev;
+                const int r = id / CPR, c = id % CPR;
+                const u32x4 pk = *reinterpret_cast<const u32x4*>(obuf + r * (NT * 2) + ((c ^ (r & 15)) << 4));
+                if (m0 + r < p.M && c * 8 < p.N)
+                    __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(og + static_cast<int64_t>(m0 + r) * p.N + c * 8));
+            }
+        }
+    }
+}
+
+#ifdef LOKA_DEBUG_TIMES
+extern "C" int loka_debug_read_times_wreg(unsigned long long* host, int n) {
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(loka_dbg_times), sizeof(unsigned long long) * n) == hipSuccess ? 0 : 1;
+}
+#endif
+
+// ---------------------------------------------------------------------------------------------- host side
+namespace {
+
+struct WregInst {
+    int wnc, ks, rb;
+    const void* fn;
+    size_t lds;
+    void (*launch)(const GemmParams&, int, dim3, hipStream_t);
+};
+
+template <int WNC, int KS, int RT>
+void launch_wreg(const GemmParams& p, int bpp, dim3 grid, hipStream_t s) {
+    gemm_wreg_kernel<WNC, KS, RT><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);
+}
+
+#define LOKA_WREG(WNC, KS, RT)                                                                                   \
+    {WNC, KS, 32 * RT, reinterpret_cast<const void*>(&gemm_wreg_kernel<WNC, KS, RT>), WregCfg<WNC, KS, RT>::LDS, \
+     &launch_wreg<WNC, KS, RT>}
+
+// columns per wave, K / 64, row tiles per block (as many as registers and LDS allow: fewer, longer iterations)
+const WregInst kWreg[] = {
+    LOKA_WREG(32, 2, 4),  LOKA_WREG(32, 4, 4), LOKA_WREG(32, 8, 2), LOKA_WREG(32, 16, 1),
+    LOKA_WREG(64, 2, 2),  LOKA_WREG(64, 4, 2), LOKA_WREG(64, 8, 1),
+    LOKA_WREG(128, 2, 1), LOKA_WREG(128, 4, 1),
+};
+
+const WregInst* wreg_pick(int64_t N, int64_t K) {
+    if (K % 64) return nullptr;
+    const int ks = static_cast<int>(K / 64);
+    const int wnc = N <= 256 ? 32 : N <= 512 ? 64 : N <= 1024 ? 128 : 0;
+    for (const WregInst& w : kWreg)
+        if (w.wnc == wnc && w.ks == ks) return &w;
+    return nullptr;
+}
+
+}  // namespace
+
+bool wreg_supports(int64_t M, int64_t N, int64_t K) {
+    return wreg_pick(N, K) != nullptr && M * K < (int64_t(1) << 31) && M * 4 < (int64_t(1) << 31);
+}
+
+// Workgroups to launch and the kernel's entry (for the dynamic-LDS attribute); 0 when unsupported.
+int wreg_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, const void** fn, size_t* lds) {
+    const WregInst* w = wreg_pick(N, K);
+    if (!w) return 0;
+    *fn = w->fn;
+    *lds = w->lds;
+    const int64_t blocks = batch * ((M + w->rb - 1) / w->rb);
+    return static_cast<int>(blocks < cus ? blocks : cus);
+}
+
+void wreg_launch(const GemmParams& p, dim3 grid, hipStream_t s) {
+    const WregInst* w = wreg_pick(p.N, p.KB);
+    w->launch(p, (p.M + w->rb - 1) / w->rb, grid, s);
+}
+
+}  // namespace loka
