@@ -16,6 +16,7 @@ int variant_count();
 const char* variant_name(int);
 bool variant_supports(const loka_gemm_desc*, int);
 int variant_epilogue(int);
+bool variant_is_streaming(int);
 int variant_bn(int);
 int variant_bm(int);
 loka_status validate_desc(const loka_gemm_desc* d, bool fp8);
@@ -57,10 +58,15 @@ int default_variant(const loka_gemm_desc* d) {
         auto it = g_best_variant.find(RecipeKey(d->M, d->N, d->K, d->batch, d->norm, d->x_mode, d->w_mode));
         if (it != g_best_variant.end() && variant_supports(d, it->second)) return it->second;
     }
+    // skinny layers with enough rows to give every CU several row blocks: W in registers, X streamed
+    if (d->M * d->batch >= 8192) {
+        for (int v = 0; v < variant_count(); ++v)
+            if (variant_is_streaming(v) && variant_supports(d, v)) return v;
+    }
     int best = -1;
     int64_t best_bn = 0, best_bm = 0;
     for (int v = 0; v < variant_count(); ++v) {
-        if (variant_epilogue(v) != 0 || !variant_supports(d, v)) continue;
+        if (variant_epilogue(v) != 0 || variant_is_streaming(v) || !variant_supports(d, v)) continue;
         const int64_t bn = variant_bn(v), bm = variant_bm(v);
         const int64_t tiles = ((d->M + bm - 1) / bm) * d->batch;
         bool better;

@@ -754,6 +754,7 @@ extern "C" int loka_debug_read_times(unsigned long long* host, int n) {
 int variant_count() { return kNumVariants; }
 const char* variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
 int variant_epilogue(int v) { return kVariants[v].epi; }
+bool variant_is_streaming(int v) { return kVariants[v].name == kWregName; }
 int variant_bn(int v) { return kVariants[v].bn; }
 int variant_bm(int v) { return kVariants[v].bm; }
 

@@ -51,7 +51,9 @@ struct WregCfg {
     static constexpr int OFF_GM = OFF_SW + NT * 4;        // [NT] fp32 gamma (1 when absent)
     static constexpr int OFF_BT = OFF_GM + NT * 4;        // [NT] fp32 beta (0 when absent)
     static constexpr int OFF_RED = OFF_BT + NT * 4;       // [RB][9] (count, mean, M2, -); 9: rows on distinct banks
-    static constexpr int LDS = OFF_RED + RB * 9 * 16;
+    static constexpr int LDS_RUN = OFF_RED + RB * 9 * 16;
+    static constexpr int STAGE = NT * KB < 131072 ? NT * KB : 131072;   // W staging at the start of a problem (overlays the rest)
+    static constexpr int LDS = LDS_RUN > STAGE ? LDS_RUN : STAGE;
     static_assert(LDS <= 160 * 1024, "LDS budget");
     static_assert(LPW >= 1, "a block is at least 4 KB");
 };
@@ -104,9 +106,14 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
     };
 
     // ---- W fragments of this wave's columns, all of K: wreg[ni][j] feeds MFMA rows with W rows (= output
-    // columns) wave * WNC + 32 ni + wperm(lane), K bytes [64 j + 32 hk, +32)
+    // columns) wave * WNC + 32 ni + wperm(lane), K bytes [64 j + 32 hk, +32).  W passes through LDS in rounds of
+    // up to 128 KB, fetched in whole 1 KB runs (every workgroup reads the same W: fragment-shaped 16-byte
+    // reads straight from global memory put 8x the requests on the same few L2 lines and take twice as long).
+    // The staging area overlays the X ring and the output buffer: callers re-request X afterwards.
     v8i wreg[NIW][KS];
     auto load_problem = [&](int g) __attribute__((always_inline)) {
+        constexpr int RROWS = 131072 / KB;                              // W rows per round
+        constexpr int ROUNDS = (NT + RROWS - 1) / RROWS;
         int lv = lane;
         asm volatile("; lane id" : "+v"(lv));                           // (offsets recomputed here, not kept in registers)
         const int l32 = lv & 31, hk = lv >> 5;
@@ -114,16 +121,35 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint8_t*>(p.W + static_cast<int64_t>(g) * p.strideW), 0, p.N * KB, 0x00020000);
 #pragma unroll
-        for (int ni = 0; ni < NIW; ++ni) {
-            const int n = wave * WNC + ni * 32 + wperm;
+        for (int r = 0; r < ROUNDS; ++r) {
+            constexpr int ROWS_ALL = NT < RROWS ? NT : RROWS;
+            const int rows = (r + 1) * RROWS <= NT ? ROWS_ALL : NT - r * RROWS;   // compile-time after unrolling
+            __syncthreads();                                            // the staging area is free
+            for (int ld = wave; ld < rows * KB / 1024; ld += 8) {
+                const int byte = ld * 1024 + lv * 16;
+                const int row = byte / KB, pos = (byte % KB) >> 4;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void*)(smem + ld * 1024), 16,
+                                                         row * KB + ((pos ^ (row & KEYMASK)) << 4), r * RROWS * KB, 0, 0);
+            }
+            wait_vmcnt<0>();
+            __syncthreads();
 #pragma unroll
-            for (int j = 0; j < KS; ++j) {
-                const int off = n * KB + j * 64 + hk * 32;
-                const u32x4 lo = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0));
-                const u32x4 hi = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(wr, off + 16, 0, 0));
-                wreg[ni][j] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            for (int ni = 0; ni < NIW; ++ni) {
+                const int tb = wave * WNC + ni * 32;                    // first W row of the tile
+                if (tb >= r * RROWS && tb < r * RROWS + rows) {
+                    const int row = tb - r * RROWS + wperm;
+                    const uint8_t* src = smem + row * KB;
+                    const int key = row & KEYMASK;
+#pragma unroll
+                    for (int j = 0; j < KS; ++j) {
+                        const v4i lo = *reinterpret_cast<const v4i*>(src + (((4 * j + 2 * hk) ^ key) << 4));
+                        const v4i hi = *reinterpret_cast<const v4i*>(src + (((4 * j + 2 * hk + 1) ^ key) << 4));
+                        wreg[ni][j] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    }
+                }
             }
         }
+        __syncthreads();                                                // fragments are read: the area may be reused
         const float* swg = p.sw + static_cast<int64_t>(g) * p.strideSw;
         float* swl = reinterpret_cast<float*>(smem + C::OFF_SW);
         float* gml = reinterpret_cast<float*>(smem + C::OFF_GM);
@@ -135,16 +161,20 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
             btl[n] = (in && p.beta && ln) ? bf16_bits_to_f32(p.beta[n]) : 0.f;
         }
     };
+    // W and the tables of problem g, then the first requests for X from block `bf` on
+    auto start_problem = [&](int g, int bf) __attribute__((always_inline)) {
+        load_problem(g);
+        if (loader) {
+#pragma unroll
+            for (int i = 0; i < NBUF - 1; ++i)
+                if (bf + i < b1) issue_block(bf + i);
+        }
+        __syncthreads();                                                // scales / gamma / beta are in LDS
+    };
 
     { const int tile = b0; (void)tile; LOKA_STAMP(6); }
     int cur_g = b0 / blocks_per_problem;
-    load_problem(cur_g);
-    if (loader) {
-#pragma unroll
-        for (int i = 0; i < NBUF - 1; ++i)
-            if (b0 + i < b1) issue_block(b0 + i);
-    }
-    __syncthreads();                                                    // scales / gamma / beta are in LDS
+    start_problem(cur_g, b0);
     { const int tile = b0; (void)tile; LOKA_STAMP(7); }
 
     for (int b = b0; b < b1; ++b) {
@@ -153,10 +183,10 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         (void)tile;
         LOKA_STAMP(0);
         if (g != cur_g) {
-            __syncthreads();                                            // everyone is done with the previous problem's tables
-            load_problem(g);
+            // (the staging of W overwrites the X blocks requested so far: they are requested again)
+            if (loader) wait_vmcnt<0>();
+            start_problem(g, b);
             cur_g = g;
-            __syncthreads();
         }
         // block b has landed: the loaders' newer requests (up to NBUF - 2 blocks) may still be in flight
         if (loader) {
