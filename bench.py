@@ -26,8 +26,8 @@ BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
 # HBM-side bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# file, scaled by a plain 1 GiB copy (profiles/bench_C5_panel256x256w8.md); counters cannot be read in-process.
-MEASURED_TRAFFIC_BYTES = {("C5", "panel256x256w8"): 1.217e9 + 0.347e9}
+# file, scaled by a plain 1 GiB copy (profiles/bench_C5_panel32_256x256.md); counters cannot be read in-process.
+MEASURED_TRAFFIC_BYTES = {("C5", "panel32_256x256"): 1.241e9 + 0.354e9}
 
 RECIPE_NAMES = {(0, 0): "tensor/tensor", (1, 2): "row/col", (3, 4): "1x128/128x128"}
 
