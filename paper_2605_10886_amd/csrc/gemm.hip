@@ -709,10 +709,10 @@ static void launch_wreg_any(const GemmParams& p, bool, dim3 grid, hipStream_t s)
 static const char kWregName[] = "wreg32";
 
 // gemm_panel32.hip
-const void* panel32_fn();
+const void* panel32_fn(bool blockwise);
 size_t panel32_lds();
-void panel32_launch(const GemmParams& p, dim3 grid, hipStream_t s);
-static void launch_panel32(const GemmParams& p, bool, dim3 grid, hipStream_t s) { panel32_launch(p, grid, s); }
+void panel32_launch(const GemmParams& p, bool blockwise, dim3 grid, hipStream_t s);
+static void launch_panel32(const GemmParams& p, bool blockwise, dim3 grid, hipStream_t s) { panel32_launch(p, blockwise, grid, s); }
 
 #define LOKA_VARIANT(NAME, BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, EPI)                                        \
     {NAME, BM, BN_SUB * NSPLIT, WAVES_M * WAVES_N * 64, EPI, 2 * (BM * 128 + BN_SUB * 128),                  \
@@ -738,8 +738,8 @@ static const VariantInfo kVariants[] = {
     // persistent, panel-synchronous: the tiles_n workgroups of a row panel exchange row statistics
     // through a few words of global memory and normalize their own tile in registers
     LOKA_VARIANT("panel256x256w8", 256, 256, 1, 2, 4, EPI_PANEL_SYNC),
-    // the same schedule on 32x32x64 MFMAs (non-blockwise scales only): the throughput variant
-    {"panel32_256x256", 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(), nullptr},
+    // the same schedule on 32x32x64 MFMAs: the throughput variant
+    {"panel32_256x256", 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(false), panel32_fn(true)},
 };
 constexpr int kNumCUs = 256;          // MI355X; the launch re-checks against the device it runs on
 constexpr unsigned kSpinLimit = 1u << 18;   // x s_sleep(16) ~ 0.1 s: far beyond any main loop

@@ -25,7 +25,7 @@ namespace loka {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-template <int EPI>
+template <int EPI, bool BLOCKWISE>
 __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     constexpr int BM = 256, BN = 256, NW = 8, WM = 128, WN = 64, MI = 4, NI = 2;
     constexpr int ES = 256 * 128;           // one ring entry: 256 rows x 128 bytes of X or of W
@@ -118,6 +118,46 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
 
+    // Blockwise scales (1 x 128 for X, 128 x 128 for W): the accumulators are kept in units of the CURRENT K
+    // block's scale s(kb) = sx[m, kb] * sw[kb, n / 128] (one value per lane and row tile: a wave's 64 columns lie
+    // inside one 128-column block).  Entering block kb they are multiplied by s(kb - 1) / s(kb), the MFMAs of
+    // the block then accumulate raw code products on top, and the epilogue multiplies by the last s: the sum
+    // over kb of s(kb) * P(kb) without a second set of accumulators for the per-block partial products P.  The
+    // 16 multiplies per tile and K step sit in front of the tile's first MFMA of the step (the vector ALU is idle
+    // there).  One extra fp32 rounding of the running sum per K step (and a 1-ulp reciprocal in the ratio):
+    // K / 128 * 2^-23 relative to sum |terms|, two orders below the matrix pipe's own truncation.
+    // The scales of block k + 1 are fetched at the start of step k.
+    float s_cur[MI], r_sc[MI], sx_nx[MI], sw_nx = 0.f;
+    const int bw_nb = ((n0 + wave_n * WN < p.N ? n0 + wave_n * WN : p.N - 1) >> 7), bw_nblk = p.N >> 7;
+    auto bw_row = [&](int mi) __attribute__((always_inline)) {
+        const int m = m0 + wave_m * WM + mi * 32 + l32;
+        return static_cast<int64_t>(m < p.M ? m : p.M - 1) * ksteps;
+    };
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) { s_cur[mi] = 1.f; r_sc[mi] = 1.f; sx_nx[mi] = 1.f; }
+    if (BLOCKWISE) {
+        const float sw0 = swg[bw_nb];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) s_cur[mi] = sxg[bw_row(mi)] * sw0;
+    }
+    // ratio for the step that begins (its scales were fetched one step earlier), then the fetch for the next one
+    auto bw_step = [&](int k) __attribute__((always_inline)) {
+        if (!BLOCKWISE) return;
+        if (k >= 1) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const float s_new = sx_nx[mi] * sw_nx;
+                r_sc[mi] = s_cur[mi] * __builtin_amdgcn_rcpf(s_new);
+                s_cur[mi] = s_new;
+            }
+        }
+        if (k + 1 < ksteps) {
+            sw_nx = swg[static_cast<int64_t>(k + 1) * bw_nblk + bw_nb];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) sx_nx[mi] = sxg[bw_row(mi) + k + 1];
+        }
+    };
+
     // Fragments of one K half (64 bytes): 2 W (two sets, double buffered) and 4 X (one set, refilled in place
     // as soon as the two MFMAs that use a fragment have been issued) of 8 registers each.
     v8i bx[MI], aw[2][NI];
@@ -149,12 +189,16 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     // has an instruction queued: a burst of LDS reads or of loads keeps a wave in the issue stage for hundreds
     // of cycles (the load path accepts 64 bytes per clock per CU).  The two waves of a SIMD (w, w + 4) issue
     // their loads in different gaps, so one of them is always free to feed the pipe.
-#define LOKA_HALF_STEP(SLOT_X, SLOT_W, S_READ, SET, LD)                              \
+#define LOKA_HALF_STEP(SLOT_X, SLOT_W, S_READ, SET, LD, RESC)                              \
     do {                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                           \
         read_w(SLOT_W, S_READ, (SET) ^ 1);                                           \
         _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) {                          \
             __builtin_amdgcn_sched_barrier(0);                                       \
+            if (BLOCKWISE && (RESC)) {                                               \
+                _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                    \
+                    _Pragma("unroll") for (int i = 0; i < 16; ++i) acc[mi][ni][i] *= r_sc[mi]; \
+            }                                                                        \
             mfma_one(mi, 0, SET);                                                    \
             __builtin_amdgcn_sched_barrier(0);                                       \
             if ((LD) == 1 && ld_x && !grp_b) issue_x1(ld_x_slot, ld_x_kb, mi);       \
@@ -205,19 +249,30 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         const bool ld_x = k >= 1 && k + 2 < ksteps, ld_w = k + 2 < ksteps;
         const int ld_x_slot = mod5(e5 + 4), ld_x_kb = (k + 2) * 128;    // X(k + 2) -> the slot W(k - 1) left
         const int ld_w_slot = e5, ld_w_kb = (k + 2) * 128;              // W(k + 2) -> the slot X(k) leaves
-        LOKA_HALF_STEP(e5, sw_cur, 1, 0, 1);
-        if (ld_w) __builtin_amdgcn_s_waitcnt(0x0F74);           // vmcnt(4): all but X(k + 2)
+        bw_step(k);
+        LOKA_HALF_STEP(e5, sw_cur, 1, 0, 1, 1);
+        // all but this step's newest loads: X(k + 2) (4) and, blockwise, the scales of block k + 1 (MI + 1)
+        if (ld_w) { if (BLOCKWISE) __builtin_amdgcn_s_waitcnt(0x0F79); else __builtin_amdgcn_s_waitcnt(0x0F74); }
         else __builtin_amdgcn_s_waitcnt(0x0F70);
         lds_barrier();                                          // (also waits for this wave's LDS reads)
-        LOKA_HALF_STEP(sx_nxt, sw_nxt, 0, 1, 2);
+        LOKA_HALF_STEP(sx_nxt, sw_nxt, 0, 1, 2, 0);
         e5 = sx_nxt;
     }
     {
         const bool ld_x = false, ld_w = false;
         const int ld_x_slot = 0, ld_x_kb = 0, ld_w_slot = 0, ld_w_kb = 0;
-        LOKA_HALF_STEP(e5, mod5(e5 + 1), 1, 0, 0);
+        bw_step(ksteps - 1);
+        LOKA_HALF_STEP(e5, mod5(e5 + 1), 1, 0, 0, 1);
         (void)ld_x; (void)ld_w; (void)ld_x_slot; (void)ld_x_kb; (void)ld_w_slot; (void)ld_w_kb;
     }
+    {   // Epilogue scope.  Lane- and thread-derived offsets restart from opaque copies of the ids: derived from
+        // loop-invariant values the compiler would compute them once before the tile loop and keep dozens of
+        // registers live through the main loop.
+    int lane_o = static_cast<int>(threadIdx.x) & 63, tid_o = static_cast<int>(threadIdx.x);
+    asm volatile("; epilogue ids" : "+v"(lane_o), "+v"(tid_o));
+    const int lane = lane_o, l32 = lane & 31, hk = lane >> 5;
+    const unsigned tid = static_cast<unsigned>(tid_o);
+    (void)lane;
     // scales of this lane's rows and columns: requested before the last eight MFMAs so that the round trip
     // through L2 is covered (the fragment registers of the other K half are free by now)
     // lane: rows m(mi) = m0 + 128 wave_m + 32 mi + l32; columns ncol(ni) + [0, 16), ncol = n0 + 64 wave_n + 32 ni + 16 hk
@@ -235,14 +290,15 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-            if (tensor_w) { const float s = swg[0]; s4[ni][a] = v4f{s, s, s, s}; }
+            if (BLOCKWISE) s4[ni][a] = v4f{1.f, 1.f, 1.f, 1.f};
+            else if (tensor_w) { const float s = swg[0]; s4[ni][a] = v4f{s, s, s, s}; }
             else s4[ni][a] = ncol[ni] < p.N ? *reinterpret_cast<const v4f*>(swg + ncol[ni] + 4 * a) : v4f{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         int m = m0 + wave_m * WM + mi * 32 + l32;
         m = m < p.M ? m : p.M - 1;
-        sxm[mi] = tensor_x ? sxg[0] : sxg[m];
+        sxm[mi] = BLOCKWISE ? s_cur[mi] : tensor_x ? sxg[0] : sxg[m];
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -339,11 +395,11 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         __syncthreads();
         // tile statistics per row: thread r < 256 merges the four column waves in order
         float t_mean = 0.f, t_m2 = 0.f;
-        if (threadIdx.x < BM) {
+        if (tid < BM) {
             float n_ = 0.f;
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const float* r3 = red + (threadIdx.x * 4 + w) * 3;
+                const float* r3 = red + (tid * 4 + w) * 3;
                 if (ln) merge_stats(n_, t_mean, t_m2, r3[0], r3[1], r3[2]);
                 else t_m2 += r3[2];
             }
@@ -353,8 +409,8 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             // publish (mean, M2) of this tile per row, signal, wait for the panel's other tiles, merge all tiles
             const int panel = g * p.tiles_m + tm;
             float* prow = p.part + (static_cast<int64_t>(g) * p.M) * (2 * p.tiles_n);
-            if (threadIdx.x < BM) {
-                const int m = m0 + threadIdx.x;
+            if (tid < BM) {
+                const int m = m0 + tid;
                 if (m < p.M) {
                     float* dst = prow + static_cast<int64_t>(m) * (2 * p.tiles_n) + 2 * tn;
                     __hip_atomic_store(dst, t_mean, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -364,7 +420,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             }
             __syncthreads();
             LOKA_STAMP(3);
-            if (threadIdx.x == 0) {
+            if (tid == 0) {
                 unsigned* ctr = p.counters + panel;
                 __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 unsigned spins = 0;
@@ -381,7 +437,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             // two threads per row, each folds a contiguous half of the row's tiles in order (device-coherent
             // 8-byte loads), symmetric merge of the halves: identical bits in every workgroup of the panel
             {
-                const int r = static_cast<int>(threadIdx.x) >> 1, sub = static_cast<int>(threadIdx.x) & 1;
+                const int r = static_cast<int>(tid) >> 1, sub = static_cast<int>(tid) & 1;
                 int m = m0 + r;
                 m = m < p.M ? m : p.M - 1;
                 const float* src = prow + static_cast<int64_t>(m) * (2 * p.tiles_n);
@@ -425,7 +481,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             }
         } else {
             // the tile spans the whole row (N <= 256): finalize here
-            if (threadIdx.x < BM) fin[threadIdx.x] = make_float2(ln ? t_mean : 0.f, __builtin_amdgcn_rsqf(t_m2 * inv_n + p.eps));
+            if (tid < BM) fin[tid] = make_float2(ln ? t_mean : 0.f, __builtin_amdgcn_rsqf(t_m2 * inv_n + p.eps));
         }
         __syncthreads();
 #pragma unroll
@@ -499,6 +555,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         }
     }
     LOKA_STAMP(6);
+    }
     lds_barrier();              // the epilogue's scratch (slot 0) is read: the next tile may load into it.  The
                                 // stores stay in flight.
   }
@@ -512,10 +569,14 @@ extern "C" int loka_debug_read_times32(unsigned long long* host, int n) {
 
 constexpr size_t kPanel32Lds = 5 * 256 * 128;   // the ring; the epilogue's scratch aliases it
 
-const void* panel32_fn() { return reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC>); }
+const void* panel32_fn(bool blockwise) {
+    return blockwise ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, true>)
+                     : reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, false>);
+}
 size_t panel32_lds() { return kPanel32Lds; }
-void panel32_launch(const GemmParams& p, dim3 grid, hipStream_t s) {
-    gemm_panel32_kernel<EPI_PANEL_SYNC><<<grid, 512, kPanel32Lds, s>>>(p);
+void panel32_launch(const GemmParams& p, bool blockwise, dim3 grid, hipStream_t s) {
+    if (blockwise) gemm_panel32_kernel<EPI_PANEL_SYNC, true><<<grid, 512, kPanel32Lds, s>>>(p);
+    else gemm_panel32_kernel<EPI_PANEL_SYNC, false><<<grid, 512, kPanel32Lds, s>>>(p);
 }
 
 }  // namespace loka
