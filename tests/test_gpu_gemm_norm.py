@@ -213,6 +213,43 @@ def test_c4_grouped_launch(orc):
     assert torch.equal(out_s[5 * w.M:6 * w.M].view(torch.int16), out_1.view(torch.int16))
 
 
+def test_streaming_variant_crosses_problem_boundaries(orc):
+    # 300 small problems with their own weights: with one row block per problem and fewer workgroups than
+    # blocks, some workgroups walk from one problem into the next and must reload W and re-request X
+    G, M, K, N = 300, 64, 256, 256
+    v = B.variant_id("wreg32")
+    xs = torch.cat([synth.normal(M, K, seed=1000 + g) for g in range(G)], 0)
+    ws = torch.cat([synth.weight(K, N, seed=5000 + g) for g in range(G)], 0)
+    gamma, beta = synth.affine(N, seed=11)
+    xd, wd = xs.to(DEV), ws.to(DEV)
+    xq, sx = B.loka_quantize(xd, B.SCALE_ROW)
+    wq = torch.empty(G * N, K, dtype=torch.uint8, device=DEV)
+    sw = torch.empty(G * N, dtype=torch.float32, device=DEV)
+    for g in range(G):
+        q, s = B.loka_quantize(wd[g * K:(g + 1) * K], B.SCALE_COL, transpose_out=True)
+        wq[g * N:(g + 1) * N] = q
+        sw[g * N:(g + 1) * N] = s
+    desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, variant=v)
+    assert B.loka_variant_supports(desc, v)
+    out, y = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, gamma.to(DEV), beta.to(DEV), want_y=True)
+    out2, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, gamma.to(DEV), beta.to(DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+    gb, bb = synth.bf16_bits(gamma), synth.bf16_bits(beta)
+    for g in (0, 1, 127, 128, 255, 256, 257, 299):
+        xq_o, sx_o = orc.quantize(synth.bf16_bits(xs[g * M:(g + 1) * M]), B.SCALE_ROW)
+        wq_o, sw_o = orc.quantize(synth.bf16_bits(ws[g * K:(g + 1) * K]), B.SCALE_COL, transpose_out=True)
+        assert np.array_equal(xq[g * M:(g + 1) * M].cpu().numpy(), xq_o)
+        y_o, absdot = orc.fp8_gemm(xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, want_absdot=True)
+        y_g = y[g * M:(g + 1) * M].cpu().numpy()
+        err = np.abs(y_g.astype(np.float64) - y_o)
+        assert (err <= gemm_tolerance(absdot, y_o, K)).all(), f"problem {g}"
+        o_o = orc.norm(y_o, B.NORM_LAYERNORM, 1e-5, gb, bb)
+        ok, worst, _ = check_bf16_out(to_np_bits(out[g * M:(g + 1) * M]), o_o,
+                                      abs_tol=propagated_abs_tol(y_o, err, B.NORM_LAYERNORM, 1e-5, gamma.float().numpy()))
+        assert ok, f"problem {g}: worst {worst} ulps"
+
+
 @pytest.mark.parametrize("recipe", ["row", "block", "tensor"])
 def test_c5_full_size(orc, recipe):
     w = synth.WORKLOADS["C5"]
