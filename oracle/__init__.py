@@ -59,6 +59,8 @@ def _load():
     L.orc_quantize.argtypes = [vp, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int, vp, vp, c.c_int]
     L.orc_fp8_gemm.restype = c.c_int
     L.orc_fp8_gemm.argtypes = [c.c_int64, c.c_int64, c.c_int64, vp, vp, c.c_int, vp, vp, c.c_int, vp, vp, c.c_int]
+    L.orc_blocknorm.restype = c.c_int
+    L.orc_blocknorm.argtypes = [vp, c.c_int64, c.c_int64, c.c_int64, c.c_float, c.c_int, vp, c.c_int]
     L.orc_norm.restype = c.c_int
     L.orc_norm.argtypes = [vp, c.c_int64, c.c_int64, c.c_int, c.c_float, vp, vp, vp, c.c_int]
     L.orc_ref_gemm.restype = c.c_int
@@ -158,6 +160,21 @@ def norm(y, kind: int, eps: float = 1e-5, gamma_bits=None, beta_bits=None, threa
     rc = _load().orc_norm(_p(y), M, N, kind, eps, _p(gamma_bits), _p(beta_bits), _p(out), threads or default_threads())
     if rc:
         raise ValueError("bad norm kind")
+    return out
+
+
+ACT_NONE, ACT_HARDSWISH = 0, 1
+
+
+def blocknorm(y, block_n: int, eps: float = 1e-5, act: int = ACT_NONE, threads: int | None = None):
+    """BlockNorm (unparameterized RMS normalization of consecutive groups of block_n columns) with an optional
+    Hard-Swish: y float32 [M,N] -> bf16 bits uint16 [M,N]."""
+    _chk(y, np.float32, "y")
+    M, N = y.shape
+    out = np.empty((M, N), dtype=np.uint16)
+    rc = _load().orc_blocknorm(_p(y), M, N, int(block_n), eps, int(act), _p(out), threads or default_threads())
+    if rc:
+        raise ValueError("block_n must divide N; act in {0, 1}")
     return out
 
 

@@ -307,6 +307,38 @@ int orc_norm(const float* y, int64_t M, int64_t N, int norm, float eps, const ui
     return 0;
 }
 
+// BlockNorm with an optional fused Hard-Swish (Section 3.2, "Block-wise Normalization" and "Hard Swish"):
+// the output row is cut into consecutive groups of block_n columns and each group is RMS-normalized on
+// its own, without learned parameters -- RMSNorm(Y.view(-1, BlockN)).view(B, N):
+//   o = Y / sqrt(sum_{group}(Y^2) / block_n + eps)
+//   act == 1:  o = o * ReLU6(o + 3) / 6,  ReLU6(t) = min(max(t, 0), 6)
+//   out = bf16_rne(float(o)).
+// Readings where the paper is silent: eps sits inside the square root like RMSNorm's; the activation acts on
+// the normalized value before the single rounding to bf16; N must be a multiple of block_n.
+int orc_blocknorm(const float* y, int64_t M, int64_t N, int64_t block_n, float eps, int act, uint16_t* out, int threads) {
+    if (block_n <= 0 || N % block_n || act < 0 || act > 1) return -1;
+    parallel_rows(M, threads, [&](int64_t lo, int64_t hi) {
+        for (int64_t m = lo; m < hi; ++m) {
+            for (int64_t b0 = 0; b0 < N; b0 += block_n) {
+                const float* grp = y + m * N + b0;
+                double v = 0.0;
+                for (int64_t n = 0; n < block_n; ++n) v += static_cast<double>(grp[n]) * grp[n];
+                const double denom = std::sqrt(v / static_cast<double>(block_n) + static_cast<double>(eps));
+                for (int64_t n = 0; n < block_n; ++n) {
+                    double o = grp[n] / denom;
+                    if (act == 1) {
+                        double t = o + 3.0;
+                        t = t < 0.0 ? 0.0 : (t > 6.0 ? 6.0 : t);
+                        o = o * t / 6.0;
+                    }
+                    out[m * N + b0 + n] = f32_to_bf16_rne(static_cast<float>(o));
+                }
+            }
+        }
+    });
+    return 0;
+}
+
 // High-precision reference the probe compares against: the unquantized bf16
 // operands contracted in fp64, rounded once to fp32.  x [M, K], w [K, N].
 int orc_ref_gemm(const uint16_t* x, const uint16_t* w, int64_t M, int64_t N, int64_t K, float* yref, int threads) {

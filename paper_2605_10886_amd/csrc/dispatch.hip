@@ -58,6 +58,15 @@ int default_variant(const loka_gemm_desc* d) {
         auto it = g_best_variant.find(RecipeKey(d->M, d->N, d->K, d->batch, d->norm, d->x_mode, d->w_mode));
         if (it != g_best_variant.end() && variant_supports(d, it->second)) return it->second;
     }
+    // Measured on the skinny shapes (65536 x 1024 x 256, 65536 x 256 x 1024, 16384 x 512 x 512, 64 x 4096 x 256 x 256):
+    // with at least one 256 x 256 tile per CU the large-tile kernel wins when K is long and the row fits one
+    // tile (no cross-workgroup exchange then), and for blockwise scales, which the streaming kernel lacks.
+    const int64_t tiles256 = ((d->M + 255) / 256) * ((d->N + 255) / 256) * d->batch;
+    const bool blockwise = d->x_mode == LOKA_SCALE_BLOCK_1x128;
+    if (tiles256 >= 256 && d->N <= 1024 && (blockwise || (d->N <= 256 && d->K >= 1024))) {
+        for (int v = variant_count() - 1; v >= 0; --v)
+            if (variant_supports(d, v) && variant_epilogue(v) == 2) return v;
+    }
     // skinny layers with enough rows to give every CU several row blocks: W in registers, X streamed
     if (d->M * d->batch >= 8192) {
         for (int v = 0; v < variant_count(); ++v)

@@ -301,6 +301,58 @@ def test_norm_against_torch_float64(orc, affine):
         assert d.max() <= 1 and (d == 0).mean() > 0.999
 
 
+def test_blocknorm_is_rmsnorm_of_the_reshaped_rows(orc):
+    # Section 3.2: BlockNorm = RMSNorm(Y.view(-1, BlockN)).view(B, N), unparameterized
+    rng = np.random.default_rng(21)
+    M, N = 12, 768
+    y = (rng.standard_normal((M, N)) * rng.uniform(0.05, 20, (M, 1))).astype(np.float32)
+    y[:, 256:512] *= 37.0                                    # one group with its own magnitude
+    for bn in (16, 128, 256, 768):
+        got = orc.blocknorm(y, bn, 1e-5)
+        # (a) the already pinned RMSNorm of this oracle on the reshaped matrix
+        want = orc.norm(np.ascontiguousarray(y.reshape(-1, bn)), orc.NORM_RMSNORM, 1e-5).reshape(M, N)
+        assert np.array_equal(got, want)
+        # (b) the library routine in fp64
+        ref = torch.nn.functional.rms_norm(torch.from_numpy(y).double().view(-1, bn), (bn,), eps=1e-5).view(M, N)
+        assert _bf16_ulp_distance(got, synth.bf16_bits(ref.to(torch.bfloat16))).max() <= 1
+    # BlockN = N is RMSNorm without gamma
+    assert np.array_equal(orc.blocknorm(y, N, 1e-5), orc.norm(y, orc.NORM_RMSNORM, 1e-5))
+    # groups do not see each other: changing one group leaves the others' outputs untouched
+    y2 = y.copy()
+    y2[:, 512:] = rng.standard_normal((M, 256)).astype(np.float32) * 1e3
+    a, b = orc.blocknorm(y, 256, 1e-5), orc.blocknorm(y2, 256, 1e-5)
+    assert np.array_equal(a[:, :512], b[:, :512]) and not np.array_equal(a[:, 512:], b[:, 512:])
+    with pytest.raises(ValueError):
+        orc.blocknorm(y, 100)
+
+
+def test_blocknorm_hardswish_closed_forms_and_library(orc):
+    # h-swish(x) = x * ReLU6(x + 3) / 6 (Section 3.2, "Hard Swish"), applied to the normalized value
+    bn = 16
+    row = np.zeros((4, 2 * bn), dtype=np.float32)
+    row[0, :] = 2.0                                          # every group normalizes to 1 -> 1 * 4 / 6
+    row[1, 0], row[1, bn] = 5.0, -5.0                        # lone element: +-sqrt(16) = +-4 -> 4 and 0 (both saturated)
+    row[2, ::2], row[2, 1::2] = 3.0, -3.0                    # +-1 -> 2/3 and -1/3
+    out = synth.bits_to_bf16(orc.blocknorm(row, bn, 0.0, orc.ACT_HARDSWISH)).float().numpy()
+    bf = lambda v: torch.tensor(v, dtype=torch.float64).to(torch.bfloat16).float().item()
+    assert np.all(out[0] == bf(4.0 / 6.0))
+    assert out[1, 0] == 4.0 and out[1, bn] == 0.0 and np.all(out[1, 1:bn] == 0.0)
+    assert np.all(out[2, ::2] == bf(2.0 / 3.0)) and np.all(out[2, 1::2] == bf(-1.0 / 3.0))
+    out3 = orc.blocknorm(row[3:4], bn, 1e-5, orc.ACT_HARDSWISH)   # an all-zero group (eps > 0): 0 / sqrt(eps) = 0
+    assert np.all(out3 == 0)
+    # against the library routines in fp64 on random data, every branch of ReLU6 populated
+    rng = np.random.default_rng(22)
+    y = (rng.standard_normal((64, 512)) * 2.5).astype(np.float32)
+    y[:, ::37] *= 6.0
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(y).double().view(-1, 256), (256,), eps=1e-5).view(64, 512)
+    assert (ref > 3).any() and (ref < -3).any()
+    want = torch.nn.functional.hardswish(ref)
+    got = orc.blocknorm(y, 256, 1e-5, orc.ACT_HARDSWISH)
+    assert _bf16_ulp_distance(got, synth.bf16_bits(want.to(torch.bfloat16))).max() <= 1
+    none = orc.blocknorm(y, 256, 1e-5, orc.ACT_NONE)
+    assert _bf16_ulp_distance(none, synth.bf16_bits(ref.to(torch.bfloat16))).max() <= 1
+
+
 def test_layernorm_moments_of_fp64_row(orc):
     # after LayerNorm with gamma=1, beta=0 the row has mean 0 and variance var/(var+eps)
     y = (np.random.default_rng(4).standard_normal((8, 1024)) * 0.01).astype(np.float32)   # var ~ 1e-4: eps matters
