@@ -49,7 +49,19 @@ typedef enum {
 /* Row normalization fused into the GEMM epilogue (Section 3.2, "Block-wise
  * Normalization", Case 1: the whole output row is normalized while the tile is
  * still on chip and equals the standard layer). */
-typedef enum { LOKA_NORM_NONE = 0, LOKA_NORM_LAYERNORM = 1, LOKA_NORM_RMSNORM = 2 } loka_norm;
+typedef enum {
+    LOKA_NORM_NONE = 0,
+    LOKA_NORM_LAYERNORM = 1,
+    LOKA_NORM_RMSNORM = 2,
+    /* BlockNorm (Section 3.2, "Block-wise Normalization", the final formulation): the row is cut into
+     * consecutive groups of block_n columns, each RMS-normalized on its own, no learned parameters:
+     * RMSNorm(Y.view(-1, BlockN)).view(B, N).  Statistics never leave the workgroup that owns the group. */
+    LOKA_NORM_BLOCKNORM = 3
+} loka_norm;
+
+/* Activation fused after the normalization (Section 3.2, "Hard Swish"):
+ * h-swish(x) = x * ReLU6(x + 3) / 6.  Only with LOKA_NORM_BLOCKNORM. */
+typedef enum { LOKA_ACT_NONE = 0, LOKA_ACT_HARDSWISH = 1 } loka_act;
 
 const char* loka_status_string(loka_status s);
 
@@ -94,6 +106,8 @@ loka_status loka_e4m3_from_f32(const float* t, uint8_t* codes, int64_t n, void* 
  *                                                         fp32 accumulator with its scales
  *   O[m,n]   = bf16_rne( LayerNorm / RMSNorm / identity over the N entries of row m )
  *     LayerNorm: (Y-mu)/sqrt(var+eps)*gamma+beta, biased variance;  RMSNorm: Y/sqrt(mean(Y^2)+eps)*gamma.
+ *     BlockNorm: Y/sqrt(mean over the element's group of block_n columns (Y^2)+eps), then the activation;
+ *     gamma and beta are ignored.
  * There is no bias input (Section 3.2, "No Bias").
  * Supported scale pairs: x in {TENSOR, ROW} with w in {TENSOR, COL}; or x = BLOCK_1x128
  * with w = BLOCK_128x128 (needs N % 128 == 0).  K % 128 == 0, N % 16 == 0.
@@ -109,6 +123,8 @@ typedef struct {
     int32_t norm;             /* loka_norm */
     float eps;
     int32_t variant;          /* kernel variant id (see loka_variant_name), or -1 = library's choice for the shape */
+    int32_t block_n;          /* LOKA_NORM_BLOCKNORM: group width; 256 is built (N % 256 == 0).  Ignored otherwise */
+    int32_t act;              /* loka_act; LOKA_ACT_HARDSWISH needs LOKA_NORM_BLOCKNORM */
 } loka_gemm_desc;
 
 int loka_variant_count(void);

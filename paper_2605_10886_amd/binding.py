@@ -20,15 +20,16 @@ LOKA_OK = 0
 LOKA_ERR_NULL, LOKA_ERR_SHAPE, LOKA_ERR_ALIGN, LOKA_ERR_UNSUPPORTED = 1, 2, 3, 4
 LOKA_ERR_WORKSPACE, LOKA_ERR_HIP, LOKA_ERR_NO_CANDIDATE = 5, 6, 7
 SCALE_TENSOR, SCALE_ROW, SCALE_COL, SCALE_BLOCK_1x128, SCALE_BLOCK_128x128 = range(5)
-NORM_NONE, NORM_LAYERNORM, NORM_RMSNORM = range(3)
-NORMS = {"none": NORM_NONE, "layernorm": NORM_LAYERNORM, "rmsnorm": NORM_RMSNORM}
+NORM_NONE, NORM_LAYERNORM, NORM_RMSNORM, NORM_BLOCKNORM = range(4)
+NORMS = {"none": NORM_NONE, "layernorm": NORM_LAYERNORM, "rmsnorm": NORM_RMSNORM, "blocknorm": NORM_BLOCKNORM}
+ACT_NONE, ACT_HARDSWISH = 0, 1
 
 
 class GemmDesc(Structure):
     _fields_ = [("M", c_int64), ("N", c_int64), ("K", c_int64), ("batch", c_int64),
                 ("strideX", c_int64), ("strideW", c_int64), ("strideO", c_int64),
                 ("x_mode", c_int32), ("w_mode", c_int32), ("norm", c_int32), ("eps", c_float),
-                ("variant", c_int32)]
+                ("variant", c_int32), ("block_n", c_int32), ("act", c_int32)]
 
 
 class ProbeStats(Structure):
@@ -166,8 +167,9 @@ def variant_id(name: str) -> int:
 
 
 def make_desc(M, N, K, batch=1, x_mode=SCALE_ROW, w_mode=SCALE_COL, norm=NORM_LAYERNORM, eps=1e-5, variant=-1,
-              shared_w=False) -> GemmDesc:
-    return GemmDesc(M, N, K, batch, M * K, 0 if shared_w else N * K, M * N, x_mode, w_mode, norm, eps, variant)
+              shared_w=False, block_n=0, act=ACT_NONE) -> GemmDesc:
+    return GemmDesc(M, N, K, batch, M * K, 0 if shared_w else N * K, M * N, x_mode, w_mode, norm, eps, variant,
+                    block_n, act)
 
 
 def loka_variant_supports(desc: GemmDesc, v: int) -> bool:

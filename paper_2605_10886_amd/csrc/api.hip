@@ -40,7 +40,13 @@ loka_status validate_desc(const loka_gemm_desc* d, bool fp8) {
     if ((d->strideX % 16) || (d->strideW % 16) || (d->strideO % 8)) return LOKA_ERR_ALIGN;
     if (!fp8) return LOKA_OK;
     if (!mode_ok(d->x_mode) || !mode_ok(d->w_mode)) return LOKA_ERR_UNSUPPORTED;
-    if (d->norm < LOKA_NORM_NONE || d->norm > LOKA_NORM_RMSNORM) return LOKA_ERR_UNSUPPORTED;
+    if (d->norm < LOKA_NORM_NONE || d->norm > LOKA_NORM_BLOCKNORM) return LOKA_ERR_UNSUPPORTED;
+    if (d->act < LOKA_ACT_NONE || d->act > LOKA_ACT_HARDSWISH) return LOKA_ERR_UNSUPPORTED;
+    if (d->act != LOKA_ACT_NONE && d->norm != LOKA_NORM_BLOCKNORM) return LOKA_ERR_UNSUPPORTED;
+    if (d->norm == LOKA_NORM_BLOCKNORM) {
+        if (d->block_n <= 0 || d->N % d->block_n) return LOKA_ERR_SHAPE;
+        if (d->block_n != 256) return LOKA_ERR_UNSUPPORTED;
+    }
     const bool xb = d->x_mode == LOKA_SCALE_BLOCK_1x128, wb = d->w_mode == LOKA_SCALE_BLOCK_128x128;
     if (xb != wb) return LOKA_ERR_UNSUPPORTED;
     if (xb && (d->N % 128)) return LOKA_ERR_SHAPE;

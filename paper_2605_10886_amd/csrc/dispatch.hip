@@ -58,6 +58,16 @@ int default_variant(const loka_gemm_desc* d) {
         auto it = g_best_variant.find(RecipeKey(d->M, d->N, d->K, d->batch, d->norm, d->x_mode, d->w_mode));
         if (it != g_best_variant.end() && variant_supports(d, it->second)) return it->second;
     }
+    if (d->norm == LOKA_NORM_BLOCKNORM) {
+        // groups never leave a workgroup: the streaming kernel for skinny layers with many rows (unless K is
+        // long and there is a 256 x 256 tile per CU), the large-tile kernel otherwise
+        const int64_t t256 = ((d->M + 255) / 256) * ((d->N + 255) / 256) * d->batch;
+        const bool stream = d->M * d->batch >= 8192 && !(t256 >= 256 && d->K >= 1024);
+        for (int pass = 0; pass < 2; ++pass)
+            for (int v = variant_count() - 1; v >= 0; --v)
+                if (variant_supports(d, v) && (pass == 1 || variant_is_streaming(v) == stream)) return v;
+        return -1;
+    }
     // Measured on the skinny shapes (65536 x 1024 x 256, 65536 x 256 x 1024, 16384 x 512 x 512, 64 x 4096 x 256 x 256):
     // with at least one 256 x 256 tile per CU the large-tile kernel wins when K is long and the row fits one
     // tile (no cross-workgroup exchange then), and for blockwise scales, which the streaming kernel lacks.

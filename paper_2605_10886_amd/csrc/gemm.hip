@@ -762,6 +762,8 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
     if (v < 0 || v >= kNumVariants) return false;
     const VariantInfo& vi = kVariants[v];
     if (vi.name == kWregName) return d->x_mode != LOKA_SCALE_BLOCK_1x128 && wreg_supports(d->M, d->N, d->K);
+    // BlockNorm (groups of 256 columns) is built into the kernels whose tile is 256 columns wide
+    if (d->norm == LOKA_NORM_BLOCKNORM && vi.launch != &launch_panel32) return false;
     if ((d->x_mode == LOKA_SCALE_BLOCK_1x128 ? vi.fn_block : vi.fn_plain) == nullptr) return false;
     if (vi.epi == EPI_ROW_IN_TILE && d->N > vi.bn) return false;
     if (vi.epi == EPI_PANEL_SYNC && (d->N + vi.bn - 1) / vi.bn > kNumCUs) return false;
@@ -772,7 +774,7 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
 
 size_t variant_workspace(const loka_gemm_desc* d, int v) {
     const VariantInfo& vi = kVariants[v];
-    if (vi.epi == EPI_ROW_IN_TILE || d->norm == LOKA_NORM_NONE) return 0;
+    if (vi.epi == EPI_ROW_IN_TILE || d->norm == LOKA_NORM_NONE || d->norm == LOKA_NORM_BLOCKNORM) return 0;
     const int64_t tiles_n = (d->N + vi.bn - 1) / vi.bn;
     size_t stats = static_cast<size_t>(d->batch) * d->M * tiles_n * 2 * sizeof(float);
     stats = (stats + 255) & ~size_t(255);
@@ -820,10 +822,10 @@ loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* 
     p.x_mode = d->x_mode; p.w_mode = d->w_mode;
     p.gamma = static_cast<const uint16_t*>(gamma); p.beta = static_cast<const uint16_t*>(beta);
     p.out = static_cast<uint16_t*>(out); p.y = y;
-    p.norm = d->norm; p.eps = d->eps;
+    p.norm = d->norm; p.eps = d->eps; p.block_n = d->block_n; p.act = d->act;
     p.tiles_m = static_cast<int>((d->M + vi.bm - 1) / vi.bm);
     p.tiles_n = static_cast<int>((d->N + vi.bn - 1) / vi.bn);
-    const bool two_pass = vi.epi == EPI_PARTIAL_STATS && d->norm != LOKA_NORM_NONE;
+    const bool two_pass = vi.epi == EPI_PARTIAL_STATS && d->norm != LOKA_NORM_NONE && d->norm != LOKA_NORM_BLOCKNORM;
     if (two_pass) {
         size_t stats = static_cast<size_t>(d->batch) * d->M * p.tiles_n * 2 * sizeof(float);
         stats = (stats + 255) & ~size_t(255);
@@ -854,7 +856,7 @@ loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* 
         if (g <= 0) return LOKA_ERR_UNSUPPORTED;
         if (g > grid.x) g = (static_cast<int64_t>(grid.x) / p.tiles_n) * p.tiles_n;   // fewer tiles than slots
         grid = dim3(static_cast<unsigned>(g));
-        if (d->norm != LOKA_NORM_NONE) {
+        if (d->norm != LOKA_NORM_NONE && d->norm != LOKA_NORM_BLOCKNORM) {
             const int64_t panels = static_cast<int64_t>(p.batch) * p.tiles_m;
             const size_t ctr_bytes = (static_cast<size_t>(panels) * 4 + 255) & ~size_t(255);
             uint8_t* ws = static_cast<uint8_t*>(workspace);

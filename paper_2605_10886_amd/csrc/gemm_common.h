@@ -22,7 +22,8 @@ struct GemmParams {
     const uint16_t* beta;
     uint16_t* out;
     float* y;
-    int norm;
+    int norm;              // loka_norm
+    int block_n, act;      // LOKA_NORM_BLOCKNORM group width; loka_act
     float eps;
     int tiles_m, tiles_n;
     float* part;           // EPI_PARTIAL_STATS / EPI_PANEL_SYNC: [batch][M][tiles_n * 2] (mean, M2) or (0, sumsq)

@@ -405,7 +405,8 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             }
         }
         LOKA_STAMP(2);
-        if (EPI == EPI_PANEL_SYNC) {
+        const bool blocknorm = p.norm == LOKA_NORM_BLOCKNORM;   // groups of 256 columns = this tile: nothing to exchange
+        if (EPI == EPI_PANEL_SYNC && !blocknorm) {
             // publish (mean, M2) of this tile per row, signal, wait for the panel's other tiles, merge all tiles
             const int panel = g * p.tiles_m + tm;
             float* prow = p.part + (static_cast<int64_t>(g) * p.M) * (2 * p.tiles_n);
@@ -481,7 +482,8 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             }
         } else {
             // the tile spans the whole row (N <= 256): finalize here
-            if (tid < BM) fin[tid] = make_float2(ln ? t_mean : 0.f, __builtin_amdgcn_rsqf(t_m2 * inv_n + p.eps));
+            if (tid < BM)
+                fin[tid] = make_float2(ln ? t_mean : 0.f, __builtin_amdgcn_rsqf(t_m2 * (blocknorm ? 1.0f / BN : inv_n) + p.eps));
         }
         __syncthreads();
 #pragma unroll
@@ -501,7 +503,8 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     // sub-tile through 2 KB of its own LDS (64-byte rows, 16-byte chunk c of row r at position c ^ (r / 4 % 4):
     // conflict-free both ways) and stores it with 4 lanes per row: 16 full 64-byte runs per instruction.
     // LDS executes one wave's instructions in order, so the same buffer serves every sub-tile without a barrier.
-    const bool has_g = p.gamma != nullptr && p.norm != LOKA_NORM_NONE, has_b = p.beta != nullptr && ln;
+    const bool has_g = p.gamma != nullptr && (ln || p.norm == LOKA_NORM_RMSNORM), has_b = p.beta != nullptr && ln;
+    const bool hswish = p.act == LOKA_ACT_HARDSWISH;
     uint8_t* const tbuf = smem + 16384 + wave * 2048;
     const int t_wr = l32 * 64, t_key = (l32 >> 2) & 3;
     const int t_row = lane >> 2, t_c = lane & 3;                       // store side: row (+ 16 j), chunk
@@ -538,6 +541,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                     // (y - mean) * rstd as one fused multiply-add, the affine part as another
                     o[e] = __builtin_fmaf(acc[mi][ni][8 * half + e], rstd_r[mi], nmr_r[mi]);
                     if (has_g || has_b) o[e] = __builtin_fmaf(o[e], gm[8 * half + e], bt[8 * half + e]);
+                    if (hswish) o[e] = o[e] * __builtin_fminf(__builtin_fmaxf(o[e] + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
                 }
                 u32x4 pk;
                 pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);

@@ -71,6 +71,8 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
     const bool ln = p.norm == LOKA_NORM_LAYERNORM;
     const bool tensor_x = p.x_mode == LOKA_SCALE_TENSOR, tensor_w = p.w_mode == LOKA_SCALE_TENSOR;
     const float inv_n = 1.0f / static_cast<float>(p.N);
+    const bool blocknorm = p.norm == LOKA_NORM_BLOCKNORM, hswish = p.act == LOKA_ACT_HARDSWISH;
+    constexpr int WPG = 256 / WNC;          // waves per BlockNorm group of 256 columns
 
     // contiguous range of row blocks of this workgroup
     const int64_t total = static_cast<int64_t>(p.batch) * blocks_per_problem;
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         for (int n = threadIdx.x; n < NT; n += 512) {
             const bool in = n < p.N;
             swl[n] = in ? (tensor_w ? swg[0] : swg[n]) : 0.f;
-            gml[n] = (in && p.gamma && p.norm != LOKA_NORM_NONE) ? bf16_bits_to_f32(p.gamma[n]) : 1.f;
+            gml[n] = (in && p.gamma && (ln || p.norm == LOKA_NORM_RMSNORM)) ? bf16_bits_to_f32(p.gamma[n]) : 1.f;
             btl[n] = (in && p.beta && ln) ? bf16_bits_to_f32(p.beta[n]) : 0.f;
         }
     };
@@ -343,13 +345,16 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
                             tmean = tmean + d * f;
                             tm2 = tm2 + r[w].z + d * d * tn * f;
                             tn = nn;
+                        } else if (blocknorm) {
+                            // only the waves that share this wave's group of 256 columns
+                            if ((4 * h4 + w) / WPG == wave / WPG) tm2 += r[w].z;
                         } else {
                             tm2 += r[w].z;
                         }
                     }
                 }
                 mean_r[rt] = ln ? tmean : 0.f;
-                rstd_r[rt] = __builtin_amdgcn_rsqf(tm2 * inv_n + p.eps);
+                rstd_r[rt] = __builtin_amdgcn_rsqf(tm2 * (blocknorm ? 1.0f / 256.0f : inv_n) + p.eps);
             }
         }
         LOKA_STAMP(4);
@@ -372,6 +377,11 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
                     for (int e = 0; e < 4; ++e) {
                         o[e] = __builtin_fmaf(__builtin_fmaf(acc[rt][ni][8 * half + e], rstd_r[rt], nmr), gq0[e], bq0[e]);
                         o[4 + e] = __builtin_fmaf(__builtin_fmaf(acc[rt][ni][8 * half + 4 + e], rstd_r[rt], nmr), gq1[e], bq1[e]);
+                    }
+                    if (hswish) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            o[e] = o[e] * __builtin_fminf(__builtin_fmaxf(o[e] + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
                     }
                     u32x4 pk;
                     pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);

@@ -57,6 +57,17 @@ def propagated_abs_tol(y_orc, dy, norm_kind, eps, gamma=None):
     return 2.0 ** -13 + 2.0 * rstd[:, None] * g[None, :] * dy.max(axis=1)[:, None]
 
 
+def propagated_abs_tol_blocknorm(y_orc, dy, block_n, eps, hardswish):
+    """Same bound for BlockNorm: rstd is per (row, group of block_n columns); Hard-Swish has slope <= 1.5."""
+    y = y_orc.astype(np.float64)
+    M, N = y.shape
+    g = y.reshape(M, N // block_n, block_n)
+    rstd = 1.0 / np.sqrt((g * g).mean(axis=2) + eps)                          # [M, groups]
+    dmax = dy.reshape(M, N // block_n, block_n).max(axis=2)                    # [M, groups]
+    tol = 2.0 ** -13 + 2.0 * (1.5 if hardswish else 1.0) * rstd * dmax
+    return np.repeat(tol, block_n, axis=1)
+
+
 def gemm_tolerance(absdot: np.ndarray, y_orc: np.ndarray, K: int) -> np.ndarray:
     """Rigorous per-element bound from the oracle's conditioning term (see module docstring)."""
     return (7.0 * 2.0 ** -13 + (K / 128 + 16) * 2.0 ** -24) * absdot + 2.0 ** -22 * np.abs(y_orc.astype(np.float64))

@@ -9,7 +9,8 @@ import torch
 
 from paper_2605_10886_amd import binding as B
 from paper_2605_10886_amd import synth
-from parity_util import check_bf16_out, gemm_tolerance, propagated_abs_tol, rel_fro, to_np_bits
+from parity_util import (check_bf16_out, gemm_tolerance, propagated_abs_tol, propagated_abs_tol_blocknorm, rel_fro,
+                         to_np_bits)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -248,6 +249,74 @@ def test_streaming_variant_crosses_problem_boundaries(orc):
         ok, worst, _ = check_bf16_out(to_np_bits(out[g * M:(g + 1) * M]), o_o,
                                       abs_tol=propagated_abs_tol(y_o, err, B.NORM_LAYERNORM, 1e-5, gamma.float().numpy()))
         assert ok, f"problem {g}: worst {worst} ulps"
+
+
+# ----------------------------------------------------------------------------- BlockNorm + Hard-Swish
+def _run_blocknorm_case(orc, x, w, recipe, act, variant, rows=None, tag=""):
+    M, K = x.shape
+    N = w.shape[1]
+    xm, wm = RECIPES[recipe]
+    xq, sx = B.loka_quantize(x.to(DEV), xm)
+    wq, sw = B.loka_quantize(w.to(DEV), wm, transpose_out=True)
+    desc = B.make_desc(M, N, K, 1, xm, wm, B.NORM_BLOCKNORM, 1e-5, variant, block_n=256, act=act)
+    out, y = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, want_y=True)
+    out2, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), f"{tag}: O differs with/without the Y store"
+    sel = np.arange(M) if rows is None else np.asarray(rows)
+    idx = torch.from_numpy(sel).to(DEV)
+    xb = synth.bf16_bits(x)
+    if xm == B.SCALE_TENSOR:
+        xq_o, sx_o = orc.quantize(xb, xm)
+        xq_o = xq_o[sel]
+    else:
+        xq_o, sx_o = orc.quantize(xb[sel].copy(), xm)
+    wq_o, sw_o = orc.quantize(synth.bf16_bits(w), wm, transpose_out=True)
+    assert np.array_equal(xq[idx].cpu().numpy(), xq_o) and np.array_equal(wq.cpu().numpy(), wq_o), f"{tag}: codes"
+    y_o, absdot = orc.fp8_gemm(np.ascontiguousarray(xq_o), sx_o, xm, wq_o, sw_o, wm, want_absdot=True)
+    y_g = y[idx].cpu().numpy()
+    err = np.abs(y_g.astype(np.float64) - y_o.astype(np.float64))
+    assert (err <= gemm_tolerance(absdot, y_o, K)).all(), f"{tag}: fp32 Y"
+    o_o = orc.blocknorm(y_o, 256, 1e-5, act)
+    o_g = to_np_bits(out[idx])
+    ok, worst, n_abs = check_bf16_out(o_g, o_o, abs_tol=propagated_abs_tol_blocknorm(y_o, err, 256, 1e-5, act == B.ACT_HARDSWISH))
+    assert ok, f"{tag}: bf16 O beyond 2 ulps (worst {worst})"
+    o_iso = orc.blocknorm(np.ascontiguousarray(y_g), 256, 1e-5, act)       # norm + activation arithmetic alone
+    ok1, w1, _ = check_bf16_out(o_g, o_iso, max_ulp=1)
+    assert ok1, f"{tag}: norm arithmetic alone is off by {w1} ulps"
+    return worst
+
+
+@pytest.mark.parametrize("act", [B.ACT_NONE, B.ACT_HARDSWISH])
+@pytest.mark.parametrize("shape", [(300, 256, 256), (200, 128, 512), (130, 256, 1024), (77, 384, 768), (513, 1024, 256)])
+def test_blocknorm_every_variant(orc, shape, act):
+    M, K, N = shape
+    x = synth.student_t4(M, K, seed=M + 1)
+    wt = synth.weight(K, N, seed=N + 1)
+    for recipe in ("row", "tensor", "block"):
+        xm, wm = RECIPES[recipe]
+        desc = B.make_desc(M, N, K, 1, xm, wm, B.NORM_BLOCKNORM, block_n=256, act=act)
+        vs = _variants_for(desc)
+        assert vs and all(B.loka_variant_name(v) in ("wreg32", "panel32_256x256") for v in vs)
+        assert B.loka_default_variant(desc) in vs
+        for v in vs:
+            _run_blocknorm_case(orc, x, wt, recipe, act, v, tag=f"{shape} {recipe} act{act} {B.loka_variant_name(v)}")
+
+
+def test_blocknorm_rejects_what_is_not_built():
+    d = B.make_desc(256, 512, 256, 1, norm=B.NORM_BLOCKNORM, block_n=128)
+    assert not any(B.loka_variant_supports(d, v) for v in range(B.loka_variant_count()))
+    d = B.make_desc(256, 384, 256, 1, norm=B.NORM_BLOCKNORM, block_n=256)       # N not a multiple of the group
+    assert not any(B.loka_variant_supports(d, v) for v in range(B.loka_variant_count()))
+    d = B.make_desc(256, 512, 256, 1, norm=B.NORM_RMSNORM, act=B.ACT_HARDSWISH)  # activation only with BlockNorm
+    assert not any(B.loka_variant_supports(d, v) for v in range(B.loka_variant_count()))
+
+
+def test_blocknorm_c5_full_size(orc):
+    w = synth.WORKLOADS["C5"]
+    x, wt = synth.activations(w), synth.weights(w)
+    r = _run_blocknorm_case(orc, x, wt, "row", B.ACT_HARDSWISH, -1, rows=_sample_rows(w.M, 96), tag="C5 blocknorm")
+    print("C5 blocknorm + hardswish: worst ulp", r)
 
 
 @pytest.mark.parametrize("recipe", ["row", "block", "tensor"])
