@@ -144,6 +144,19 @@ loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, co
                                const float* sw, const void* gamma_bf16, const void* beta_bf16, void* out_bf16,
                                float* y_fp32, void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* FP8 output for the next layer (Section 3.2, "Block-wise Normalization", Case 1: when the whole row is
+ * normalized inside one workgroup, "activation and (de)quantization can also be fused together before the
+ * final output is written to HBM").  Same computation as loka_fp8_gemm_norm, but instead of bf16 O the call
+ * writes what loka_quantize(O_bf16, LOKA_SCALE_ROW) would produce from it, bit for bit:
+ *   oq [batch][M, N] e4m3 codes,  so [batch][M] fp32 row scales (amax of the row's bf16 values / 448).
+ * The next layer's loka_fp8_gemm_norm takes (oq, so) as its (xq, sx) with x_mode = LOKA_SCALE_ROW.
+ * Built for the shapes the streaming skinny-layer kernel covers (N <= 1024, K in {128, 256, 512, 1024},
+ * K * N <= 256 KB, non-blockwise input scales); LOKA_ERR_UNSUPPORTED otherwise.  No workspace.
+ * y_fp32 as above (NULL to skip).  oq, so: device pointers, 16-byte aligned, caller-owned. */
+loka_status loka_fp8_gemm_norm_fp8out(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
+                                      const float* sw, const void* gamma_bf16, const void* beta_bf16, uint8_t* oq,
+                                      float* so, float* y_fp32, void* hip_stream);
+
 /* ---------------------------------------------------------------- probe reference
  * Yref = X . W from the UNQUANTIZED bf16 operands with fp32 accumulation: the
  * high-precision reference the probe measures FP8 against (Section 2.3, "Error

@@ -72,6 +72,8 @@ _SIGNATURES = [
     ("loka_fp8_gemm_norm_workspace", c_size_t, [POINTER(GemmDesc)]),
     ("loka_fp8_gemm_norm", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                    c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    ("loka_fp8_gemm_norm_fp8out", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                          c_void_p, c_void_p, c_void_p, c_void_p]),
     ("loka_bf16_gemm_workspace", c_size_t, [POINTER(GemmDesc)]),
     ("loka_bf16_gemm", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     ("loka_probe_error_workspace", c_size_t, [c_int64, c_int64]),
@@ -195,6 +197,22 @@ def loka_fp8_gemm_norm(desc: GemmDesc, xq, sx, wq, sw, gamma=None, beta=None, wa
                                     _ptr(out), _ptr(y), _ptr(workspace), workspace.numel(), _stream()),
            "loka_fp8_gemm_norm")
     return out, y
+
+
+def loka_fp8_gemm_norm_fp8out(desc: GemmDesc, xq, sx, wq, sw, gamma=None, beta=None, want_y: bool = False, oq=None,
+                              so=None, y=None):
+    """Returns (codes uint8 [batch*M, N], row scales fp32 [batch*M], Y fp32 or None)."""
+    rows = desc.batch * desc.M
+    dev = xq.device
+    if oq is None:
+        oq = torch.empty((rows, desc.N), dtype=torch.uint8, device=dev)
+    if so is None:
+        so = torch.empty(rows, dtype=torch.float32, device=dev)
+    if want_y and y is None:
+        y = torch.empty((rows, desc.N), dtype=torch.float32, device=dev)
+    _check(lib().loka_fp8_gemm_norm_fp8out(byref(desc), _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), _ptr(gamma), _ptr(beta),
+                                           _ptr(oq), _ptr(so), _ptr(y), _stream()), "loka_fp8_gemm_norm_fp8out")
+    return oq, so, y
 
 
 def loka_bf16_gemm(desc: GemmDesc, x, w, yref=None, workspace=None):

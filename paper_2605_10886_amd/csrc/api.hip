@@ -16,7 +16,8 @@ const char* variant_name(int);
 bool variant_supports(const loka_gemm_desc*, int);
 size_t variant_workspace(const loka_gemm_desc*, int);
 loka_status fp8_gemm_norm_launch(const loka_gemm_desc*, int, const uint8_t*, const float*, const uint8_t*, const float*,
-                                 const void*, const void*, void*, float*, void*, hipStream_t);
+                                 const void*, const void*, void*, float*, uint8_t*, float*, void*, hipStream_t);
+int variant_streaming_id();
 size_t bf16_gemm_workspace_bytes(const loka_gemm_desc*);
 loka_status bf16_gemm_launch(const loka_gemm_desc*, const void*, const void*, float*, void*, hipStream_t);
 // probe.hip
@@ -158,7 +159,23 @@ loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, co
     const size_t need = variant_workspace(desc, v);
     if (need && (!workspace || ws_bytes < need)) return LOKA_ERR_WORKSPACE;
     if (need && !aligned16(workspace)) return LOKA_ERR_ALIGN;
-    return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, out_bf16, y_fp32, workspace,
+    return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, out_bf16, y_fp32, nullptr, nullptr,
+                                workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+loka_status loka_fp8_gemm_norm_fp8out(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
+                                      const float* sw, const void* gamma_bf16, const void* beta_bf16, uint8_t* oq,
+                                      float* so, float* y_fp32, void* hip_stream) {
+    if (!desc || !xq || !sx || !wq || !sw || !oq || !so) return LOKA_ERR_NULL;
+    const loka_status st = validate_desc(desc, true);
+    if (st != LOKA_OK) return st;
+    if (!aligned16(xq) || !aligned16(wq) || !aligned16(sx) || !aligned16(sw) || !aligned16(oq) || !aligned16(so) ||
+        !aligned16(y_fp32) || !aligned16(gamma_bf16) || !aligned16(beta_bf16))
+        return LOKA_ERR_ALIGN;
+    // only the streaming kernel keeps a whole output row inside one workgroup and has this epilogue
+    const int v = variant_streaming_id();
+    if (v < 0 || !variant_supports(desc, v) || (desc->variant >= 0 && desc->variant != v)) return LOKA_ERR_UNSUPPORTED;
+    return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, nullptr, y_fp32, oq, so, nullptr,
                                 static_cast<hipStream_t>(hip_stream));
 }
 

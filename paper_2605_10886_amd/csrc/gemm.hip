@@ -703,7 +703,7 @@ static void launch_fp8(const GemmParams& p, bool blockwise, dim3 grid, hipStream
 
 // gemm_wreg.hip
 bool wreg_supports(int64_t M, int64_t N, int64_t K);
-int wreg_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, const void** fn, size_t* lds);
+int wreg_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool fp8_out, const void** fn, size_t* lds);
 void wreg_launch(const GemmParams& p, dim3 grid, hipStream_t s);
 static void launch_wreg_any(const GemmParams& p, bool, dim3 grid, hipStream_t s) { wreg_launch(p, grid, s); }
 static const char kWregName[] = "wreg32";
@@ -754,6 +754,11 @@ extern "C" int loka_debug_read_times(unsigned long long* host, int n) {
 int variant_count() { return kNumVariants; }
 const char* variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
 int variant_epilogue(int v) { return kVariants[v].epi; }
+int variant_streaming_id() {
+    for (int v = 0; v < kNumVariants; ++v)
+        if (kVariants[v].name == kWregName) return v;
+    return -1;
+}
 bool variant_is_streaming(int v) { return kVariants[v].name == kWregName; }
 int variant_bn(int v) { return kVariants[v].bn; }
 int variant_bm(int v) { return kVariants[v].bm; }
@@ -808,7 +813,7 @@ static loka_status set_lds(const void* fn, size_t lds) {
 
 loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* xq, const float* sx, const uint8_t* wq,
                                  const float* sw, const void* gamma, const void* beta, void* out, float* y,
-                                 void* workspace, hipStream_t s) {
+                                 uint8_t* outq, float* outs, void* workspace, hipStream_t s) {
     const VariantInfo& vi = kVariants[v];
     const bool blockwise = d->x_mode == LOKA_SCALE_BLOCK_1x128;
     GemmParams p{};
@@ -822,6 +827,8 @@ loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* 
     p.x_mode = d->x_mode; p.w_mode = d->w_mode;
     p.gamma = static_cast<const uint16_t*>(gamma); p.beta = static_cast<const uint16_t*>(beta);
     p.out = static_cast<uint16_t*>(out); p.y = y;
+    p.outq = outq; p.outs = outs;
+    if (outq && vi.name != kWregName) return LOKA_ERR_UNSUPPORTED;   // FP8 output: the row must stay inside one workgroup
     p.norm = d->norm; p.eps = d->eps; p.block_n = d->block_n; p.act = d->act;
     p.tiles_m = static_cast<int>((d->M + vi.bm - 1) / vi.bm);
     p.tiles_n = static_cast<int>((d->N + vi.bn - 1) / vi.bn);
@@ -838,7 +845,7 @@ loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* 
         size_t lds = 0;
         LOKA_HIP_TRY(hipGetDevice(&dev));
         LOKA_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        const int wgs = wreg_plan(d->M, d->N, d->K, d->batch, cus, &fn, &lds);
+        const int wgs = wreg_plan(d->M, d->N, d->K, d->batch, cus, p.outq != nullptr, &fn, &lds);
         if (wgs <= 0) return LOKA_ERR_UNSUPPORTED;
         if (set_lds(fn, lds) != LOKA_OK) return LOKA_ERR_HIP;
         vi.launch(p, false, dim3(static_cast<unsigned>(wgs)), s);

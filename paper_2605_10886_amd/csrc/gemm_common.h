@@ -21,6 +21,8 @@ struct GemmParams {
     const uint16_t* gamma;
     const uint16_t* beta;
     uint16_t* out;
+    uint8_t* outq;         // FP8 output instead of `out`: e4m3 codes [batch][M][N] ...
+    float* outs;           // ... and their row scales [batch][M]
     float* y;
     int norm;              // loka_norm
     int block_n, act;      // LOKA_NORM_BLOCKNORM group width; loka_act

@@ -58,7 +58,7 @@ struct WregCfg {
     static_assert(LPW >= 1, "a block is at least 4 KB");
 };
 
-template <int WNC, int KS, int RT>
+template <int WNC, int KS, int RT, bool FP8OUT>
 __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, const int blocks_per_problem) {
     using C = WregCfg<WNC, KS, RT>;
     constexpr int NIW = C::NIW, KB = C::KB, NT = C::NT, RB = C::RB, NBUF = C::NBUF, LPW = C::LPW, LDW = C::LDW, SXL = C::SXL;
@@ -359,52 +359,159 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         }
         LOKA_STAMP(4);
 
-        // ---- normalize, affine, bf16 into the staging buffer (row 32 rt + l32; 16-byte chunk c at position c ^ (row % 16))
+        // normalized (+ affine, + activation) values of 8 consecutive columns of row tile rt, as packed bf16
+        auto norm8 = [&](int rt, int ni, int half, const v4f gq0, const v4f gq1, const v4f bq0, const v4f bq1,
+                         const float rstd) __attribute__((always_inline)) {
+            const float nmr = -mean_r[rt] * rstd;
+            float o[8];
 #pragma unroll
-        for (int ni = 0; ni < NIW; ++ni) {
-            const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + colbase[ni] * 4);
-            const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + colbase[ni] * 4);
+            for (int e = 0; e < 4; ++e) {
+                o[e] = __builtin_fmaf(__builtin_fmaf(acc[rt][ni][8 * half + e], rstd, nmr), gq0[e], bq0[e]);
+                o[4 + e] = __builtin_fmaf(__builtin_fmaf(acc[rt][ni][8 * half + 4 + e], rstd, nmr), gq1[e], bq1[e]);
+            }
+            if (hswish) {
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                __builtin_amdgcn_sched_barrier(0);
-                const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
-                const int c = (colbase[ni] >> 3) + half;
+                for (int e = 0; e < 8; ++e)
+                    o[e] = o[e] * __builtin_fminf(__builtin_fmaxf(o[e] + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
+            }
+            u32x4 pk;
+            pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
+            pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
+            return pk;
+        };
+        if (!FP8OUT) {
+            // ---- bf16 into the staging buffer (row 32 rt + l32; 16-byte chunk c at position c ^ (row % 16))
 #pragma unroll
-                for (int rt = 0; rt < RT; ++rt) {
-                    const float nmr = -mean_r[rt] * rstd_r[rt];
-                    float o[8];
+            for (int ni = 0; ni < NIW; ++ni) {
+                const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + colbase[ni] * 4);
+                const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + colbase[ni] * 4);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        o[e] = __builtin_fmaf(__builtin_fmaf(acc[rt][ni][8 * half + e], rstd_r[rt], nmr), gq0[e], bq0[e]);
-                        o[4 + e] = __builtin_fmaf(__builtin_fmaf(acc[rt][ni][8 * half + 4 + e], rstd_r[rt], nmr), gq1[e], bq1[e]);
-                    }
-                    if (hswish) {
+                for (int half = 0; half < 2; ++half) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
+                    const int c = (colbase[ni] >> 3) + half;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            o[e] = o[e] * __builtin_fminf(__builtin_fmaxf(o[e] + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
-                    }
-                    u32x4 pk;
-                    pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
-                    pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
-                    *reinterpret_cast<u32x4*>(obuf + (rt * 32 + l32) * (NT * 2) + ((c ^ (l32 & 15)) << 4)) = pk;
+                    for (int rt = 0; rt < RT; ++rt)
+                        *reinterpret_cast<u32x4*>(obuf + (rt * 32 + l32) * (NT * 2) + ((c ^ (l32 & 15)) << 4)) =
+                            norm8(rt, ni, half, gq0, gq1, bq0, bq1, rstd_r[rt]);
                 }
             }
-        }
-        lds_barrier();
-        LOKA_STAMP(5);
-        // ---- the storers write the block: 64 consecutive chunks (1 KB) per instruction, whole rows
-        if (storer) {
-            constexpr int CPR = NT / 8;                                 // chunks per row
-            constexpr int INSTR = RB * CPR / 64 / 4;                    // per storer wave
-            uint16_t* const og = p.out + static_cast<int64_t>(g) * p.strideO;
+            lds_barrier();
+            LOKA_STAMP(5);
+            // ---- the storers write the block: 64 consecutive chunks (1 KB) per instruction, whole rows
+            if (storer) {
+                constexpr int CPR = NT / 8;                                 // chunks per row
+                constexpr int INSTR = RB * CPR / 64 / 4;                    // per storer wave
+                uint16_t* const og = p.out + static_cast<int64_t>(g) * p.strideO;
 #pragma unroll
-            for (int s = 0; s < INSTR; ++s) {
-                if (s % 2 == 0) __builtin_amdgcn_sched_barrier(0);      // two in flight: W leaves few registers free
-                const int id = ((wave - 4) + 4 * s) * 64 + lanev;
-                const int r = id / CPR, c = id % CPR;
-                const u32x4 pk = *reinterpret_cast<const u32x4*>(obuf + r * (NT * 2) + ((c ^ (r & 15)) << 4));
-                if (m0 + r < p.M && c * 8 < p.N)
-                    __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(og + static_cast<int64_t>(m0 + r) * p.N + c * 8));
+                for (int s = 0; s < INSTR; ++s) {
+                    if (s % 2 == 0) __builtin_amdgcn_sched_barrier(0);      // two in flight: W leaves few registers free
+                    const int id = ((wave - 4) + 4 * s) * 64 + lanev;
+                    const int r = id / CPR, c = id % CPR;
+                    const u32x4 pk = *reinterpret_cast<const u32x4*>(obuf + r * (NT * 2) + ((c ^ (r & 15)) << 4));
+                    if (m0 + r < p.M && c * 8 < p.N)
+                        __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(og + static_cast<int64_t>(m0 + r) * p.N + c * 8));
+                }
+            }
+        } else {
+            // ---- FP8 output for the next layer: the bf16 values above, quantized per row exactly as the
+            // quantize entry point would quantize the stored bf16 tensor (amax over the row of |bf16 value|,
+            // scale = amax / 448, code = e4m3(value * (448 / amax))).  Pass 1: row amax (integer max of the
+            // bf16 magnitudes; lanes, then the 8 waves through LDS).  Pass 2: recompute, scale, convert.
+            // (the row amax travels in the unused fourth word of the statistics entries)
+            unsigned* const redq = reinterpret_cast<unsigned*>(smem + C::OFF_RED) + 3;
+            unsigned amax_b[RT];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) amax_b[rt] = 0u;
+#pragma unroll
+            for (int ni = 0; ni < NIW; ++ni) {
+                const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + colbase[ni] * 4);
+                const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + colbase[ni] * 4);
+                const bool in = colbase[ni] < p.N;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) {
+                        const u32x4 pk = norm8(rt, ni, half, gq0, gq1, bq0, bq1, rstd_r[rt]);
+                        unsigned a = amax_b[rt];
+                        const unsigned ws4[4] = {pk.x, pk.y, pk.z, pk.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const unsigned lo = ws4[e] & 0x7FFFu, hi = (ws4[e] >> 16) & 0x7FFFu;
+                            a = a > lo ? a : lo;
+                            a = a > hi ? a : hi;
+                        }
+                        if (in) amax_b[rt] = a;
+                    }
+                }
+            }
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                const unsigned o2 = static_cast<unsigned>(__shfl_xor(static_cast<int>(amax_b[rt]), 32, 64));
+                amax_b[rt] = amax_b[rt] > o2 ? amax_b[rt] : o2;
+                if (hk == 0) redq[((rt * 32 + l32) * 9 + wave) * 4] = amax_b[rt];
+            }
+            lds_barrier();
+            float inv_q[RT], scale_q[RT];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                unsigned a = 0u;
+#pragma unroll
+                for (int w = 0; w < 8; ++w) { const unsigned v = redq[((rt * 32 + l32) * 9 + w) * 4]; a = a > v ? a : v; }
+                group_scale(__uint_as_float(a << 16), scale_q[rt], inv_q[rt]);
+            }
+            // pass 2: codes into the staging buffer (row pitch NT bytes, 16-byte chunk = 16 columns, same swizzle).
+            // The values are recomputed from an opaque copy of rstd: kept from pass 1 they would hold one
+            // register per two outputs across the barrier.
+            float rstd2[RT];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) { rstd2[rt] = rstd_r[rt]; asm volatile("; pass 2" : "+v"(rstd2[rt])); }
+#pragma unroll
+            for (int ni = 0; ni < NIW; ++ni) {
+                const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + colbase[ni] * 4);
+                const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + colbase[ni] * 4);
+                const int c = colbase[ni] >> 4;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) {
+                        const u32x4 pk = norm8(rt, ni, half, gq0, gq1, bq0, bq1, rstd2[rt]);
+                        const float iq = inv_q[rt];
+                        u32x2 codes;
+                        codes.x = e4m3x4(bf16_lo(pk.x) * iq, bf16_hi(pk.x) * iq, bf16_lo(pk.y) * iq, bf16_hi(pk.y) * iq);
+                        codes.y = e4m3x4(bf16_lo(pk.z) * iq, bf16_hi(pk.z) * iq, bf16_lo(pk.w) * iq, bf16_hi(pk.w) * iq);
+                        *reinterpret_cast<u32x2*>(obuf + (rt * 32 + l32) * NT + ((c ^ (l32 & 15)) << 4) + 8 * half) = codes;
+                    }
+                }
+            }
+            lds_barrier();
+            LOKA_STAMP(5);
+            if (storer) {
+                constexpr int CPRQ = NT / 16;                               // 16-byte chunks per row
+                constexpr int INSTRQ = RB * CPRQ / 64 / 4 > 0 ? RB * CPRQ / 64 / 4 : 1;
+                uint8_t* const og = p.outq + static_cast<int64_t>(g) * p.strideO;
+#pragma unroll
+                for (int s = 0; s < INSTRQ; ++s) {
+                    if (s % 2 == 0) __builtin_amdgcn_sched_barrier(0);
+                    const int id = ((wave - 4) + 4 * s) * 64 + lanev;
+                    const int r = id / CPRQ, c = id % CPRQ;
+                    if (r < RB) {
+                        const u32x4 ck = *reinterpret_cast<const u32x4*>(obuf + r * NT + ((c ^ (r & 15)) << 4));
+                        if (m0 + r < p.M && c * 16 < p.N)
+                            __builtin_nontemporal_store(ck, reinterpret_cast<u32x4*>(og + static_cast<int64_t>(m0 + r) * p.N + c * 16));
+                    }
+                }
+                if (wave == 4 && hk == 0) {
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) {
+                        const int m = m0 + rt * 32 + l32;
+                        if (m < p.M) p.outs[static_cast<int64_t>(g) * p.M + m] = scale_q[rt];
+                    }
+                }
             }
         }
     }
@@ -421,18 +528,21 @@ namespace {
 
 struct WregInst {
     int wnc, ks, rb;
-    const void* fn;
+    const void* fn;      // bf16 output
+    const void* fn_q;    // e4m3 output
     size_t lds;
     void (*launch)(const GemmParams&, int, dim3, hipStream_t);
 };
 
 template <int WNC, int KS, int RT>
 void launch_wreg(const GemmParams& p, int bpp, dim3 grid, hipStream_t s) {
-    gemm_wreg_kernel<WNC, KS, RT><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);
+    if (p.outq) gemm_wreg_kernel<WNC, KS, RT, true><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);
+    else gemm_wreg_kernel<WNC, KS, RT, false><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);
 }
 
 #define LOKA_WREG(WNC, KS, RT)                                                                                   \
-    {WNC, KS, 32 * RT, reinterpret_cast<const void*>(&gemm_wreg_kernel<WNC, KS, RT>), WregCfg<WNC, KS, RT>::LDS, \
+    {WNC, KS, 32 * RT, reinterpret_cast<const void*>(&gemm_wreg_kernel<WNC, KS, RT, false>),                      \
+     reinterpret_cast<const void*>(&gemm_wreg_kernel<WNC, KS, RT, true>), WregCfg<WNC, KS, RT>::LDS,              \
      &launch_wreg<WNC, KS, RT>}
 
 // columns per wave, K / 64, row tiles per block (as many as registers and LDS allow: fewer, longer iterations)
@@ -458,10 +568,10 @@ bool wreg_supports(int64_t M, int64_t N, int64_t K) {
 }
 
 // Workgroups to launch and the kernel's entry (for the dynamic-LDS attribute); 0 when unsupported.
-int wreg_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, const void** fn, size_t* lds) {
+int wreg_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool fp8_out, const void** fn, size_t* lds) {
     const WregInst* w = wreg_pick(N, K);
     if (!w) return 0;
-    *fn = w->fn;
+    *fn = fp8_out ? w->fn_q : w->fn;
     *lds = w->lds;
     const int64_t blocks = batch * ((M + w->rb - 1) / w->rb);
     return static_cast<int>(blocks < cus ? blocks : cus);

@@ -319,6 +319,64 @@ def test_blocknorm_c5_full_size(orc):
     print("C5 blocknorm + hardswish: worst ulp", r)
 
 
+# ----------------------------------------------------------------------------- FP8 output for the next layer
+@pytest.mark.parametrize("case", [(300, 256, 256, "layernorm"), (200, 128, 512, "rmsnorm"), (130, 256, 1024, "layernorm"),
+                                  (513, 1024, 256, "none"), (96, 512, 512, "blocknorm")])
+def test_fp8_output_equals_quantize_of_the_bf16_output(orc, case):
+    # the fused epilogue must write exactly what loka_quantize(O_bf16, ROW) writes (codes and scales bit for
+    # bit); O_bf16 itself is checked against the oracle by the tests above, and the oracle's quantize of the
+    # same bf16 tensor is compared as well
+    M, K, N, norm = case
+    x = synth.student_t4(M, K, seed=7 * M)
+    wt = synth.weight(K, N, seed=7 * N)
+    gamma, beta = synth.affine(N, seed=5)
+    v = B.variant_id("wreg32")
+    kw = dict(block_n=256, act=B.ACT_HARDSWISH) if norm == "blocknorm" else {}
+    for xm, wm in ((B.SCALE_ROW, B.SCALE_COL), (B.SCALE_TENSOR, B.SCALE_TENSOR)):
+        xq, sx = B.loka_quantize(x.to(DEV), xm)
+        wq, sw = B.loka_quantize(wt.to(DEV), wm, transpose_out=True)
+        desc = B.make_desc(M, N, K, 1, xm, wm, B.NORMS[norm], 1e-5, v, **kw)
+        out, y = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, gamma.to(DEV), beta.to(DEV), want_y=True)
+        oq, so, y2 = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, gamma.to(DEV), beta.to(DEV), want_y=True)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y2)
+        q_ref, s_ref = B.loka_quantize(out, B.SCALE_ROW)
+        assert torch.equal(oq, q_ref), f"{case} codes differ from loka_quantize of the bf16 output"
+        assert torch.equal(so.view(torch.int32), s_ref.view(torch.int32)), f"{case} scales differ"
+        q_o, s_o = orc.quantize(to_np_bits(out), B.SCALE_ROW)
+        assert np.array_equal(oq.cpu().numpy(), q_o) and np.array_equal(so.cpu().numpy(), s_o)
+
+
+def test_fp8_output_chains_the_skinny_pair(orc):
+    # C3 at reduced M: layer a writes codes + row scales, layer b consumes them directly
+    wa, wb = synth.WORKLOADS["C3a"], synth.WORKLOADS["C3b"]
+    M = 4096
+    x = synth.activations(wa, rows=M)
+    w1, w2 = synth.weights(wa), synth.weights(wb)
+    xq, sx = B.loka_quantize(x.to(DEV), B.SCALE_ROW)
+    w1q, s1 = B.loka_quantize(w1.to(DEV), B.SCALE_COL, transpose_out=True)
+    w2q, s2 = B.loka_quantize(w2.to(DEV), B.SCALE_COL, transpose_out=True)
+    v = B.variant_id("wreg32")
+    da = B.make_desc(M, wa.N, wa.K, 1, norm=B.NORM_LAYERNORM, variant=v)
+    db = B.make_desc(M, wb.N, wb.K, 1, norm=B.NORM_LAYERNORM, variant=v)
+    hq, hs, _ = B.loka_fp8_gemm_norm_fp8out(da, xq, sx, w1q, s1)
+    out_fused, _ = B.loka_fp8_gemm_norm(db, hq, hs, w2q, s2)
+    h, _ = B.loka_fp8_gemm_norm(da, xq, sx, w1q, s1)                       # the unfused chain: bf16 through HBM
+    hq2, hs2 = B.loka_quantize(h, B.SCALE_ROW)
+    out_ref, _ = B.loka_fp8_gemm_norm(db, hq2, hs2, w2q, s2)
+    torch.cuda.synchronize()
+    assert torch.equal(hq, hq2) and torch.equal(hs, hs2)
+    assert torch.equal(out_fused.view(torch.int16), out_ref.view(torch.int16))
+
+
+def test_fp8_output_unsupported_shapes():
+    d = B.make_desc(512, 4096, 4096, 1)                                       # rows wider than a workgroup keeps
+    with pytest.raises(B.LokaError):
+        B.loka_fp8_gemm_norm_fp8out(d, torch.zeros(512, 4096, dtype=torch.uint8, device=DEV),
+                                    torch.ones(512, device=DEV), torch.zeros(4096, 4096, dtype=torch.uint8, device=DEV),
+                                    torch.ones(4096, device=DEV))
+
+
 @pytest.mark.parametrize("recipe", ["row", "block", "tensor"])
 def test_c5_full_size(orc, recipe):
     w = synth.WORKLOADS["C5"]
