@@ -377,6 +377,46 @@ def test_fp8_output_unsupported_shapes():
                                     torch.ones(4096, device=DEV))
 
 
+# ----------------------------------------------------------------------------- backward-pass GEMMs through the same entry points
+@pytest.mark.parametrize("shape", [(512, 256, 384), (1024, 512, 256)])
+def test_backward_gemms_with_the_forward_entry_points(orc, shape):
+    # dX = dY . W^T and dW = X^T . dY (Section 3.3: forward and backward GEMMs are routed separately): both are
+    # "rows times K-contiguous rows" products once the operands are quantized in the right orientation
+    M, K, N = shape
+    x = synth.normal(M, K, seed=3 * M)
+    w = synth.weight(K, N, seed=3 * N)
+    dy = synth.normal(M, N, seed=3 * K, std=0.02)
+    xd, wd, dyd = x.to(DEV), w.to(DEV), dy.to(DEV)
+
+    # dX [M, K]: contraction over N.  dY rowwise; W [K, N] quantized as it lies (one scale per row k = per output column)
+    dyq, sdy = B.loka_quantize(dyd, B.SCALE_ROW)
+    wq, sw = B.loka_quantize(wd, B.SCALE_ROW)
+    d1 = B.make_desc(M, K, N, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_NONE)
+    _, dx = B.loka_fp8_gemm_norm(d1, dyq, sdy, wq, sw, want_y=True)
+    dyq_o, sdy_o = orc.quantize(synth.bf16_bits(dy), B.SCALE_ROW)
+    wq_o, sw_o = orc.quantize(synth.bf16_bits(w), B.SCALE_ROW)
+    assert np.array_equal(dyq.cpu().numpy(), dyq_o) and np.array_equal(wq.cpu().numpy(), wq_o)
+    dx_o, ad = orc.fp8_gemm(dyq_o, sdy_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, want_absdot=True)
+    err = np.abs(dx.cpu().numpy().astype(np.float64) - dx_o)
+    assert (err <= gemm_tolerance(ad, dx_o, N)).all(), "dX"
+    ref = dy.double() @ w.double().T                                        # sanity against the unquantized product
+    assert rel_fro(dx.cpu().numpy(), ref.numpy()) < 0.06
+
+    # dW [K, N]: contraction over M.  X and dY quantized per column and written transposed ([K, M], [N, M])
+    xtq, sxt = B.loka_quantize(xd, B.SCALE_COL, transpose_out=True)
+    dytq, sdyt = B.loka_quantize(dyd, B.SCALE_COL, transpose_out=True)
+    d2 = B.make_desc(K, N, M, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_NONE)
+    _, dw = B.loka_fp8_gemm_norm(d2, xtq, sxt, dytq, sdyt, want_y=True)
+    xtq_o, sxt_o = orc.quantize(synth.bf16_bits(x), B.SCALE_COL, transpose_out=True)
+    dytq_o, sdyt_o = orc.quantize(synth.bf16_bits(dy), B.SCALE_COL, transpose_out=True)
+    assert np.array_equal(xtq.cpu().numpy(), xtq_o) and np.array_equal(dytq.cpu().numpy(), dytq_o)
+    dw_o, ad = orc.fp8_gemm(xtq_o, sxt_o, B.SCALE_ROW, dytq_o, sdyt_o, B.SCALE_COL, want_absdot=True)
+    err = np.abs(dw.cpu().numpy().astype(np.float64) - dw_o)
+    assert (err <= gemm_tolerance(ad, dw_o, M)).all(), "dW"
+    ref = x.double().T @ dy.double()
+    assert rel_fro(dw.cpu().numpy(), ref.numpy()) < 0.06
+
+
 @pytest.mark.parametrize("recipe", ["row", "block", "tensor"])
 def test_c5_full_size(orc, recipe):
     w = synth.WORKLOADS["C5"]
