@@ -59,6 +59,8 @@ def _load():
     L.orc_quantize.argtypes = [vp, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int, vp, vp, c.c_int]
     L.orc_fp8_gemm.restype = c.c_int
     L.orc_fp8_gemm.argtypes = [c.c_int64, c.c_int64, c.c_int64, vp, vp, c.c_int, vp, vp, c.c_int, vp, vp, c.c_int]
+    L.orc_tracker_update.restype = c.c_int
+    L.orc_tracker_update.argtypes = [vp, c.c_int64, c.c_int64, c.c_int64, vp, vp, vp, c.c_int]
     L.orc_blocknorm.restype = c.c_int
     L.orc_blocknorm.argtypes = [vp, c.c_int64, c.c_int64, c.c_int64, c.c_float, c.c_int, vp, c.c_int]
     L.orc_norm.restype = c.c_int
@@ -176,6 +178,19 @@ def blocknorm(y, block_n: int, eps: float = 1e-5, act: int = ACT_NONE, threads: 
     if rc:
         raise ValueError("block_n must divide N; act in {0, 1}")
     return out
+
+
+def tracker_update(x_bits, n_old: int, mu, sigma, want_abs: bool = False, threads: int | None = None):
+    """Merges the batch x (bf16 bits uint16 [B,K]) into (n_old, mu float32 [K], sigma float32 [K,K]) IN PLACE;
+    returns n_new (and the fp64 [K,K] magnitude sum |x_i||x_j| + B|mu_b,i||mu_b,j| when want_abs)."""
+    _chk(x_bits, np.uint16, "x"); _chk(mu, np.float32, "mu"); _chk(sigma, np.float32, "sigma")
+    Bn, K = x_bits.shape
+    assert mu.shape == (K,) and sigma.shape == (K, K)
+    ab = np.empty((K, K), dtype=np.float64) if want_abs else None
+    rc = _load().orc_tracker_update(_p(x_bits), Bn, K, int(n_old), _p(mu), _p(sigma), _p(ab), threads or default_threads())
+    if rc:
+        raise ValueError("bad tracker arguments")
+    return (n_old + Bn, ab) if want_abs else n_old + Bn
 
 
 def ref_gemm(x_bits, w_bits, threads: int | None = None):

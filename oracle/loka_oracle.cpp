@@ -339,6 +339,47 @@ int orc_blocknorm(const float* y, int64_t M, int64_t N, int64_t block_n, float e
     return 0;
 }
 
+// Online distribution tracker of the probe (Section 3.1, "Online Distribution Learning", the batched Welford
+// tracker for activations): one batch X [B, K] (bf16) is merged into the running summary (n, mu [K], Sigma
+// [K, K] = unnormalized scatter, fp32 storage):
+//   mu_b = column means of X,   S_b = (X - 1 mu_b^T)^T (X - 1 mu_b^T),
+//   n_new = n_old + B,  delta = mu_b - mu_old,  mu_new = mu_old + (B / n_new) delta,
+//   Sigma_new = Sigma_old + S_b + (n_old B / n_new) delta delta^T.
+// All arithmetic in fp64 on the fp32 state, results rounded once to fp32.  abs_scatter (optional, [K, K]
+// fp64) receives sum_m |x_mi| |x_mj| + B |mu_b,i| |mu_b,j|: the magnitude a test bounds fp32 accumulation with.
+int orc_tracker_update(const uint16_t* x, int64_t B, int64_t K, int64_t n_old, float* mu, float* sigma,
+                       double* abs_scatter, int threads) {
+    if (B <= 0 || K <= 0 || n_old < 0) return -1;
+    std::vector<double> mub(K, 0.0);
+    for (int64_t m = 0; m < B; ++m)
+        for (int64_t k = 0; k < K; ++k) mub[k] += bf16_to_f32(x[m * K + k]);
+    for (int64_t k = 0; k < K; ++k) mub[k] /= static_cast<double>(B);
+    const double n_new = static_cast<double>(n_old) + static_cast<double>(B);
+    const double coef = static_cast<double>(n_old) * static_cast<double>(B) / n_new;
+    std::vector<double> delta(K);
+    for (int64_t k = 0; k < K; ++k) delta[k] = mub[k] - static_cast<double>(mu[k]);
+    parallel_rows(K, threads, [&](int64_t lo, int64_t hi) {
+        std::vector<double> ci(B);
+        for (int64_t i = lo; i < hi; ++i) {
+            for (int64_t m = 0; m < B; ++m) ci[m] = bf16_to_f32(x[m * K + i]) - mub[i];
+            for (int64_t j = 0; j < K; ++j) {
+                double sb = 0.0, ab = 0.0;
+                for (int64_t m = 0; m < B; ++m) {
+                    const double xj = bf16_to_f32(x[m * K + j]);
+                    sb += ci[m] * (xj - mub[j]);
+                    if (abs_scatter) ab += std::fabs(ci[m] + mub[i]) * std::fabs(xj);
+                }
+                const double v = static_cast<double>(sigma[i * K + j]) + sb + coef * delta[i] * delta[j];
+                sigma[i * K + j] = static_cast<float>(v);
+                if (abs_scatter) abs_scatter[i * K + j] = ab + static_cast<double>(B) * std::fabs(mub[i]) * std::fabs(mub[j]);
+            }
+        }
+    });
+    for (int64_t k = 0; k < K; ++k)
+        mu[k] = static_cast<float>(static_cast<double>(mu[k]) + static_cast<double>(B) / n_new * delta[k]);
+    return 0;
+}
+
 // High-precision reference the probe compares against: the unquantized bf16
 // operands contracted in fp64, rounded once to fp32.  x [M, K], w [K, N].
 int orc_ref_gemm(const uint16_t* x, const uint16_t* w, int64_t M, int64_t N, int64_t K, float* yref, int threads) {

@@ -353,6 +353,59 @@ def test_blocknorm_hardswish_closed_forms_and_library(orc):
     assert _bf16_ulp_distance(none, synth.bf16_bits(ref.to(torch.bfloat16))).max() <= 1
 
 
+# ----------------------------------------------------------------------------- online tracker (Section 3.1)
+def _bf16_matrix(rng, rows, cols, loc, scale):
+    return (torch.from_numpy(rng.standard_normal((rows, cols)) * scale + loc)).to(torch.bfloat16)
+
+
+def test_tracker_batches_merge_to_the_covariance_of_all_rows(orc):
+    # merging batches one after the other equals the scatter of the concatenation (numpy, fp64); the unbiased
+    # covariance is Sigma / (n - 1); batches with different means exercise the delta delta^T term
+    rng = np.random.default_rng(41)
+    K = 24
+    parts = [_bf16_matrix(rng, 40, K, rng.uniform(-3, 3, K), rng.uniform(0.2, 2, K)),
+             _bf16_matrix(rng, 7, K, rng.uniform(-3, 3, K) + 5.0, 0.5),
+             _bf16_matrix(rng, 129, K, 0.0, 1.0)]
+    mu = np.zeros(K, dtype=np.float32)
+    sigma = np.zeros((K, K), dtype=np.float32)
+    n = 0
+    seen = []
+    for part in parts:
+        n = orc.tracker_update(synth.bf16_bits(part), n, mu, sigma)
+        seen.append(part.double().numpy())
+        allx = np.concatenate(seen, 0)
+        assert n == allx.shape[0]
+        np.testing.assert_allclose(mu, allx.mean(0), rtol=2e-7, atol=1e-7)
+        c = allx - allx.mean(0)
+        np.testing.assert_allclose(sigma, c.T @ c, rtol=5e-7, atol=1e-5)
+        np.testing.assert_allclose(sigma / (n - 1), np.cov(allx, rowvar=False), rtol=5e-7, atol=1e-6)
+        assert np.array_equal(sigma, sigma.T)
+    # one batch or three: same summary up to the fp32 roundings of the stored state
+    mu1 = np.zeros(K, dtype=np.float32); s1 = np.zeros((K, K), dtype=np.float32)
+    orc.tracker_update(synth.bf16_bits(torch.cat(parts, 0)), 0, mu1, s1)
+    np.testing.assert_allclose(s1, sigma, rtol=1e-6, atol=1e-5)
+    np.testing.assert_allclose(mu1, mu, rtol=1e-6, atol=1e-7)
+
+
+def test_tracker_closed_forms(orc):
+    K = 8
+    # constant columns: zero scatter, mean = the constant; a second batch at another constant: only delta delta^T
+    a = torch.full((10, K), 1.5, dtype=torch.bfloat16)
+    b = torch.full((30, K), -0.5, dtype=torch.bfloat16)
+    mu = np.zeros(K, dtype=np.float32); sg = np.zeros((K, K), dtype=np.float32)
+    n = orc.tracker_update(synth.bf16_bits(a), 0, mu, sg)
+    assert n == 10 and np.all(mu == 1.5) and np.all(sg == 0)
+    n = orc.tracker_update(synth.bf16_bits(b), n, mu, sg)
+    assert n == 40 and np.all(mu == 0.0)                              # (10 * 1.5 - 30 * 0.5) / 40
+    assert np.all(sg == 10 * 30 / 40 * 4.0)                           # n_old B / n_new * delta^2, delta = -2
+    # two points +-1 in one feature: scatter 2 there, 0 elsewhere; abs magnitude is the plain |x||x| sum
+    x = torch.zeros((2, K), dtype=torch.bfloat16); x[0, 3], x[1, 3] = 1.0, -1.0
+    mu = np.zeros(K, dtype=np.float32); sg = np.zeros((K, K), dtype=np.float32)
+    n, ab = orc.tracker_update(synth.bf16_bits(x), 0, mu, sg, want_abs=True)
+    want = np.zeros((K, K)); want[3, 3] = 2.0
+    assert np.array_equal(sg, want.astype(np.float32)) and np.array_equal(ab, want) and np.all(mu == 0)
+
+
 def test_layernorm_moments_of_fp64_row(orc):
     # after LayerNorm with gamma=1, beta=0 the row has mean 0 and variance var/(var+eps)
     y = (np.random.default_rng(4).standard_normal((8, 1024)) * 0.01).astype(np.float32)   # var ~ 1e-4: eps matters
