@@ -190,6 +190,25 @@ loka_status loka_probe_error(const float* y, const float* yref, int64_t M, int64
                              loka_probe_stats* stats_device, float* rowmax_device, void* workspace, size_t ws_bytes,
                              void* hip_stream);
 
+/* ---------------------------------------------------------------- probe online tracker
+ * Merges one batch of activations into the running distribution summary of a layer's input (Section 3.1,
+ * "Online Distribution Learning": mean tracked by streaming, covariance by a batched Welford tracker that
+ * needs O(K^2) memory).  State: n (kept by the caller), mu [K] fp32, sigma [K, K] fp32 = the UNNORMALIZED
+ * scatter sum_m (x_m - mu)(x_m - mu)^T of all rows seen so far (unbiased covariance = sigma / (n - 1)).
+ *   mu_b  = column means of X            S_b = (X - 1 mu_b^T)^T (X - 1 mu_b^T)
+ *   n'    = n_old + B                    delta = mu_b - mu
+ *   mu'   = mu + (B / n') delta          sigma' = sigma + S_b + (n_old B / n') delta delta^T
+ * S_b is evaluated as X^T X - B mu_b mu_b^T with X^T X on the BF16 matrix cores (exact products, fp32
+ * accumulation over the batch rows), column sums in fp64, the subtraction and the merge in fp64, one rounding
+ * to fp32.  Both triangles of sigma are written; results are repeatable run to run (fixed reduction order).
+ *   x_bf16 [B, ld] bf16 (ld >= K, K % 8 == 0, ld % 8 == 0, K <= 32768), 16-byte aligned
+ *   mu, sigma: device, updated in place; start a stream of batches from n_old = 0, mu = 0, sigma = 0
+ * The new row count n_old + B is the caller's to keep.
+ * Workspace: loka_tracker_update_workspace(B, K) bytes (partial scatters of the batch splits); scratch. */
+size_t loka_tracker_update_workspace(int64_t B, int64_t K);
+loka_status loka_tracker_update(const void* x_bf16, int64_t B, int64_t K, int64_t ld, int64_t n_old, float* mu,
+                                float* sigma, void* workspace, size_t ws_bytes, void* hip_stream);
+
 /* ---------------------------------------------------------------- dispatch
  * Per-shape selection (Section 3.3, "Library and Recipe Selection"): among the
  * library's own candidates (scale recipe x kernel variant) keep those whose probe

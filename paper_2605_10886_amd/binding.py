@@ -79,6 +79,9 @@ _SIGNATURES = [
     ("loka_probe_error_workspace", c_size_t, [c_int64, c_int64]),
     ("loka_probe_error", c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p,
                                  c_size_t, c_void_p]),
+    ("loka_tracker_update_workspace", c_size_t, [c_int64, c_int64]),
+    ("loka_tracker_update", c_int, [c_void_p, c_int64, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_size_t,
+                                    c_void_p]),
     ("loka_dispatch_select", c_int, [c_int, POINTER(c_double), POINTER(c_double), c_double, c_double, c_double]),
     ("loka_dispatch", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_double, c_double, POINTER(Choice),
                               POINTER(Candidate), c_int, POINTER(c_int), c_void_p]),
@@ -246,6 +249,16 @@ def loka_probe_error(y, yref, stats=None, rowmax=None, workspace=None, sync: boo
         return stats, rowmax
     v = stats.cpu().tolist()
     return dict(zip(("rel_fro", "max_abs", "mere", "sum_sq_err", "sum_sq_ref"), v)), rowmax
+
+
+def loka_tracker_update(x: torch.Tensor, n_old: int, mu: torch.Tensor, sigma: torch.Tensor, workspace=None) -> int:
+    """Merges the batch x [B, K] bf16 into (n_old, mu [K], sigma [K, K]) in place; returns the new row count."""
+    B, K = x.shape
+    need = int(lib().loka_tracker_update_workspace(B, K))
+    ws = workspace if workspace is not None else _ws(need, x.device)
+    _check(lib().loka_tracker_update(_ptr(x), B, K, x.stride(0), int(n_old), _ptr(mu), _ptr(sigma), _ptr(ws), ws.numel(),
+                                     _stream()), "loka_tracker_update")
+    return int(n_old) + B
 
 
 def loka_dispatch_select(usec, err, budget: float, min_speedup: float = 0.0, usec_bf16: float = 0.0) -> int:

@@ -26,6 +26,9 @@ loka_status probe_launch(const float*, const float*, int64_t, int64_t, int64_t, 
                          hipStream_t);
 // dispatch.hip
 int default_variant(const loka_gemm_desc*);
+// tracker.hip
+size_t tracker_workspace_bytes(int64_t, int64_t);
+loka_status tracker_update_launch(const void*, int64_t, int64_t, int64_t, int64_t, float*, float*, void*, hipStream_t);
 
 static bool mode_ok(int m) { return m >= LOKA_SCALE_TENSOR && m <= LOKA_SCALE_BLOCK_128x128; }
 
@@ -212,6 +215,30 @@ loka_status loka_probe_error(const float* y, const float* yref, int64_t M, int64
     if (!aligned16(workspace)) return LOKA_ERR_ALIGN;
     return probe_launch(y, yref, M, N, ld, stats_device, rowmax_device, workspace,
                         static_cast<hipStream_t>(hip_stream));
+}
+
+// Shape rules of the tracker, shared by the workspace query and the call.
+static loka_status validate_tracker(int64_t B, int64_t K, int64_t ld, int64_t n_old) {
+    if (B <= 0 || K <= 0 || ld < K || n_old < 0) return LOKA_ERR_SHAPE;
+    if (K % 8 || ld % 8) return LOKA_ERR_SHAPE;
+    if (K > 32768 || B > (INT64_C(1) << 40) || n_old > (INT64_C(1) << 52)) return LOKA_ERR_SHAPE;
+    return LOKA_OK;
+}
+
+size_t loka_tracker_update_workspace(int64_t B, int64_t K) {
+    if (validate_tracker(B, K, K, 0) != LOKA_OK) return 0;
+    return tracker_workspace_bytes(B, K);
+}
+
+loka_status loka_tracker_update(const void* x_bf16, int64_t B, int64_t K, int64_t ld, int64_t n_old, float* mu,
+                                float* sigma, void* workspace, size_t ws_bytes, void* hip_stream) {
+    if (!x_bf16 || !mu || !sigma) return LOKA_ERR_NULL;
+    const loka_status st = validate_tracker(B, K, ld, n_old);
+    if (st != LOKA_OK) return st;
+    if (!aligned16(x_bf16) || !aligned16(mu) || !aligned16(sigma)) return LOKA_ERR_ALIGN;
+    if (!workspace || ws_bytes < tracker_workspace_bytes(B, K)) return LOKA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return LOKA_ERR_ALIGN;
+    return tracker_update_launch(x_bf16, B, K, ld, n_old, mu, sigma, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"

@@ -90,6 +90,20 @@ def normal_outlier4(rows: int, cols: int, seed: int, factor: float = 100.0):
     return x.to(torch.bfloat16), cols_idx
 
 
+def correlated(rows: int, cols: int, seed: int, mean_span: float = 2.0, mix: float = 0.6) -> torch.Tensor:
+    """[rows, cols] bf16 with a non-zero per-column mean and correlated columns: x = 1 mu^T + Z L^T with a
+    banded lower-triangular L (each column mixes `mix` of its left neighbour's noise) and mu ~ U(-span, span).
+    Stands in for a layer input whose distribution the online tracker learns (means of the size of the
+    standard deviations, so the mean correction of the scatter matters)."""
+    g = _gen(seed)
+    z = torch.randn(rows, cols, generator=g, dtype=torch.float32)
+    mu = (torch.rand(cols, generator=g, dtype=torch.float32) * 2.0 - 1.0) * mean_span
+    sd = 0.25 + 1.5 * torch.rand(cols, generator=g, dtype=torch.float32)
+    x = z.clone()
+    x[:, 1:] += mix * z[:, :-1]
+    return (x * sd + mu).to(torch.bfloat16)
+
+
 def weight(K: int, N: int, seed: int) -> torch.Tensor:
     """[K, N] bf16 ~ N(0, 1/K)."""
     return normal(K, N, seed, std=1.0 / math.sqrt(K))

@@ -117,6 +117,24 @@ def test_probe_and_bf16_argument_validation():
     assert L.loka_e4m3_from_f32(None, FAKE, 4, None) == B.LOKA_ERR_NULL
 
 
+def test_tracker_argument_validation():
+    L = B.lib()
+    t = L.loka_tracker_update
+    need = L.loka_tracker_update_workspace(1000, 256)
+    assert need >= 3 * 128 * 128 * 4                                        # at least one partial per tile pair
+    assert L.loka_tracker_update_workspace(1000, 100) == 0                  # K % 8
+    assert t(None, 1000, 256, 256, 0, FAKE, FAKE, FAKE, need, None) == B.LOKA_ERR_NULL
+    assert t(FAKE, 1000, 256, 256, 0, None, FAKE, FAKE, need, None) == B.LOKA_ERR_NULL
+    assert t(FAKE, 0, 256, 256, 0, FAKE, FAKE, FAKE, need, None) == B.LOKA_ERR_SHAPE
+    assert t(FAKE, 1000, 100, 104, 0, FAKE, FAKE, FAKE, need, None) == B.LOKA_ERR_SHAPE     # K % 8
+    assert t(FAKE, 1000, 256, 128, 0, FAKE, FAKE, FAKE, need, None) == B.LOKA_ERR_SHAPE     # ld < K
+    assert t(FAKE, 1000, 256, 260, 0, FAKE, FAKE, FAKE, need, None) == B.LOKA_ERR_SHAPE     # ld % 8
+    assert t(FAKE, 1000, 256, 256, -1, FAKE, FAKE, FAKE, need, None) == B.LOKA_ERR_SHAPE
+    assert t(ODD, 1000, 256, 256, 0, FAKE, FAKE, FAKE, need, None) == B.LOKA_ERR_ALIGN
+    assert t(FAKE, 1000, 256, 256, 0, FAKE, FAKE, None, 0, None) == B.LOKA_ERR_WORKSPACE
+    assert t(FAKE, 1000, 256, 256, 0, FAKE, FAKE, FAKE, need - 1, None) == B.LOKA_ERR_WORKSPACE
+
+
 def test_dispatch_rule_and_validation_on_host():
     assert B.loka_dispatch_select([10, 8, 6, 12], [0.01, 0.03, 0.05, 0.001], 0.04) == 1
     assert B.loka_dispatch_select([10, 8, 6, 12], [0.01, 0.03, 0.05, 0.001], 0.0005) == -1
