@@ -59,6 +59,13 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_sched_barrier(0);
 }
 
+// Waits until at most N_ of this wave's vector-memory operations are outstanding (6-bit count, split
+// over two fields of the instruction's immediate); the LDS and scalar counters are left alone.
+template <int N_>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N_ & 15) | ((N_ >> 4) << 14));
+}
+
 // Chan's pairwise merge of (count, mean, M2).
 __device__ __forceinline__ void merge_stats(float& n, float& mean, float& m2, float nb, float mb, float m2b) {
     const float nn = n + nb;

@@ -25,11 +25,6 @@ namespace loka {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-template <int N_>
-__device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (N_ & 15) | ((N_ >> 4) << 14));
-}
-
 template <int WNC, int KS, int RT>
 struct WregCfg {
     static constexpr int NIW = WNC / 32;                  // 32-column MFMA tiles per wave
