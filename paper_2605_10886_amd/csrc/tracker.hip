@@ -184,29 +184,48 @@ __global__ __launch_bounds__(512) void tracker_scatter_kernel(const TrackerParam
                 for (int r = 0; r < 16; ++r) acc[t][e][r] = 0.f;
         double cs0 = 0.0, cs1 = 0.0;
 
+        // Software pipeline: the fragments of k step q + 1 are read from LDS while the MFMAs of k step q run
+        // (a wave that reads all fragments and then issues all MFMAs leaves the matrix pipe idle during the
+        // reads: the other wave of the SIMD is in the same phase).  One barrier per stage, in the middle of it.
+        auto read_frags = [&](const uint8_t* At, const uint8_t* Bt, int kk, v8bf (&fa)[4], v8bf (&fb)[2])
+                              __attribute__((always_inline)) {
 #pragma unroll
-        for (int s = 0; s < TRK_NS - 1; ++s) issue(s);
-        for (int s = 0; s < nsteps; ++s) {
-            wait_vmcnt<(TRK_NS - 2) * 4>();          // this wave's share of stage s has landed (loads return in order)
-            lds_barrier();                            // everyone's has; everyone has left stage s - 1
-            issue(s + TRK_NS - 1);                    // into the buffer of stage s - 1 (past the end: empty descriptors)
-            const uint8_t* At = smem + (s & (TRK_NS - 1)) * TRK_STAGEB;
-            const uint8_t* Bt = diag ? At : At + TRK_TILEB;
+            for (int t = 0; t < 4; ++t)
+                fa[t] = tr_fragment(At + (a_off ^ (t << 6)) + kk * 16 * TRK_ROWB, At + (a_off ^ (t << 6)) + (kk * 16 + 4) * TRK_ROWB);
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                v8bf fa[4], fb[2];
+            for (int e = 0; e < 2; ++e)
+                fb[e] = tr_fragment(Bt + (b_off ^ (e << 6)) + kk * 16 * TRK_ROWB, Bt + (b_off ^ (e << 6)) + (kk * 16 + 4) * TRK_ROWB);
+        };
+        auto mma = [&](const v8bf (&fa)[4], const v8bf (&fb)[2]) __attribute__((always_inline)) {
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    fa[t] = tr_fragment(At + (a_off ^ (t << 6)) + kk * 16 * TRK_ROWB, At + (a_off ^ (t << 6)) + (kk * 16 + 4) * TRK_ROWB);
+            for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int e = 0; e < 2; ++e)
-                    fb[e] = tr_fragment(Bt + (b_off ^ (e << 6)) + kk * 16 * TRK_ROWB, Bt + (b_off ^ (e << 6)) + (kk * 16 + 4) * TRK_ROWB);
+                    acc[t][e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[t], fb[e], acc[t][e], 0, 0, 0);
+        };
+        // issue order of one k step: an MFMA, then two LDS reads of the next step's fragments, six times over
+        auto interleave = [&]() __attribute__((always_inline)) {
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int e = 0; e < 2; ++e)
-                        acc[t][e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[t], fb[e], acc[t][e], 0, 0, 0);
+            for (int i = 0; i < 6; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             }
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        };
+
+#pragma unroll
+        for (int s = 0; s < TRK_NS - 1; ++s) issue(s);
+        wait_vmcnt<(TRK_NS - 2) * 4>();              // this wave's share of stage 0 has landed (loads return in order)
+        lds_barrier();
+        issue(TRK_NS - 1);
+        v8bf fa0[4], fb0[2], fa1[4], fb1[2];
+        read_frags(smem, diag ? smem : smem + TRK_TILEB, 0, fa0, fb0);
+        for (int s = 0; s < nsteps; ++s) {
+            const uint8_t* At = smem + (s & (TRK_NS - 1)) * TRK_STAGEB;
+            const uint8_t* Bt = diag ? At : At + TRK_TILEB;
+            read_frags(At, Bt, 1, fa1, fb1);
+            mma(fa0, fb0);
+            interleave();
             if (diag) {
 #pragma unroll
                 for (int r = 0; r < 8; ++r) {
@@ -215,6 +234,13 @@ __global__ __launch_bounds__(512) void tracker_scatter_kernel(const TrackerParam
                     cs1 += static_cast<double>(bf16_hi(w));
                 }
             }
+            wait_vmcnt<(TRK_NS - 2) * 4>();          // stage s + 1 has landed
+            lds_barrier();                            // for everyone; and everyone has read all of stage s
+            issue(s + TRK_NS);                        // into the buffer of stage s (past the end: empty descriptors)
+            const uint8_t* An = smem + ((s + 1) & (TRK_NS - 1)) * TRK_STAGEB;
+            read_frags(An, diag ? An : An + TRK_TILEB, 0, fa0, fb0);   // past the last stage: read, never used
+            mma(fa1, fb1);
+            interleave();
         }
         wait_vmcnt<0>();                              // the empty tail loads too, before the wave may end
 
