@@ -192,6 +192,12 @@ def main():
         lambda: B.loka_probe_error(y, yref, stats, rowmax, ws_p, sync=False), k_steps, stream)))
     pstats = dict(zip(("rel_fro", "max_abs", "mere", "sum_sq_err", "sum_sq_ref"), stats.cpu().tolist()))
     probe_bytes = rows * N * 8 + rows * 4
+    # online tracker of the probe (offline work too): one batch = the workload's activations, merged into (mu, Sigma)
+    mu_t = torch.zeros(K, dtype=torch.float32, device=dev)
+    sg_t = torch.zeros(K, K, dtype=torch.float32, device=dev)
+    ws_t = torch.empty(max(16, L.loka_tracker_update_workspace(rows, K)), dtype=torch.uint8, device=dev)
+    t_trk = float(np.mean(_event_times(lambda: B.loka_tracker_update(x, 0, mu_t, sg_t, ws_t), 5, stream)))
+    trk_flops = float(rows) * K * (K + 1)                 # symmetric scatter: K (K + 1) / 2 multiply-adds per row
 
     kernels = {
         "quantize": {"ms": t_quant, "GBps": quant_bytes / t_quant / 1e6, "frac_hbm": quant_bytes / t_quant / 1e6 / HBM_PEAK_GBS},
@@ -199,6 +205,8 @@ def main():
                           "roofline_frac": max(t_mfma_ms, t_mem_ms) / t_gemm},
         "bf16_gemm": {"ms": t_bf16, "TFLOPs": flops / t_bf16 / 1e9, "pct_bf16_peak": 100 * flops / t_bf16 / 1e9 / BF16_PEAK_TFLOPS},
         "probe": {"ms": t_probe, "GBps": probe_bytes / t_probe / 1e6, "frac_hbm": probe_bytes / t_probe / 1e6 / HBM_PEAK_GBS},
+        "tracker_update": {"ms": t_trk, "TFLOPs": trk_flops / t_trk / 1e9, "pct_bf16_peak": 100 * trk_flops / t_trk / 1e9 / BF16_PEAK_TFLOPS,
+                           "GBps": (rows * K * 2 + K * K * 8) / t_trk / 1e6},
     }
 
     # ---- the oracle on the host cores, bounded sample of the same workload
