@@ -18,11 +18,9 @@
 //                            updates Sigma (both triangles; the mirror image goes through an LDS transpose)
 //
 // The contraction runs over the rows of a row-major matrix, i.e. over the strided dimension of both MFMA
-// operands.  The staged rows stay row-major in LDS and the operand fragments (8 contraction values of one
-// column per lane) come out of the transposing LDS read of gfx950 (ds_read_b64_tr_b16): within 16 lanes,
-// source lane 4 e + q supplies the address of 4 consecutive columns (4 q .. 4 q + 3) of contraction row e,
-// and lane i receives column i of rows e = 0..3.  Two such reads fill one operand of
-// v_mfma_f32_32x32x16_bf16.  The MFMA's k order is irrelevant here because both operands come from the same
+// operands: an MFMA lane needs 8 consecutive batch rows of ONE column.  Each 8 x 8 block of X is transposed
+// once, in registers, on its way from global memory to LDS (byte permutes), so that an operand fragment is a
+// single 16-byte LDS read.  The MFMA's k order is irrelevant here because both operands come from the same
 // rows in the same order.
 #include "gemm_common.h"
 
@@ -31,12 +29,10 @@ namespace loka {
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int TRK_T = 256;                      // output tile (columns i x columns j) per workgroup
-constexpr int TRK_MS = 32;                      // batch rows per pipeline stage (two MFMA k steps of 16)
-constexpr int TRK_NS = 4;                       // LDS ring: stages in flight
-constexpr int TRK_ROWB = TRK_T * 2;             // bytes of one staged row
-constexpr int TRK_TILEB = TRK_MS * TRK_ROWB;    // one operand tile of a stage (16 KB)
+constexpr int TRK_MS = 64;                      // batch rows per pipeline stage (four MFMA k steps of 16)
+constexpr int TRK_TILEB = TRK_MS * TRK_T * 2;   // one operand tile of a stage (32 KB)
 constexpr int TRK_STAGEB = 2 * TRK_TILEB;       // i tile, then j tile
-constexpr size_t TRK_LDS = TRK_NS * TRK_STAGEB + 4 * TRK_T * sizeof(double);
+constexpr size_t TRK_LDS = 2 * TRK_STAGEB + 2 * TRK_T * sizeof(double);
 constexpr int TRK_CUS = 256;                    // workgroups resident at once (one per CU)
 
 // Work decomposition: workgroup = (tile pair ti <= tj, one of S equal row ranges of the batch).  All
@@ -54,15 +50,15 @@ TrackerPlan tracker_plan(int64_t B, int64_t K) {
     pl.T = static_cast<int>((K + TRK_T - 1) / TRK_T);
     pl.pairs = pl.T * (pl.T + 1) / 2;
     const int64_t steps = (B + TRK_MS - 1) / TRK_MS;
-    int64_t max_s = steps / 4 > 0 ? steps / 4 : 1;                    // at least 4 steps per workgroup
+    int64_t max_s = steps / 2 > 0 ? steps / 2 : 1;                    // at least 2 stages per workgroup
     if (max_s > 256) max_s = 256;
-    // estimated time in units of one step (about 0.5 us): rounds * (steps per workgroup + start-up) for the
-    // scatter, and 0.2 per partial tile (256 KB written, then read back by the merge, at HBM speed)
+    // estimated time in units of one stage (about 1.2 us): rounds * (stages per workgroup + start-up) for the
+    // scatter, and 0.1 per partial tile (256 KB written, then read back by the merge, at HBM speed)
     int64_t best_s = 1;
     double best = 1e300;
     for (int64_t sp = 1; sp <= max_s; ++sp) {
         const int64_t rounds = (static_cast<int64_t>(pl.pairs) * sp + TRK_CUS - 1) / TRK_CUS;
-        const double cost = static_cast<double>(rounds) * ((steps + sp - 1) / sp + 6) + 0.2 * pl.pairs * static_cast<double>(sp);
+        const double cost = static_cast<double>(rounds) * ((steps + sp - 1) / sp + 3) + 0.1 * pl.pairs * static_cast<double>(sp);
         if (cost < best) { best = cost; best_s = sp; }
     }
     int64_t rows = (B + best_s - 1) / best_s;
@@ -93,180 +89,172 @@ __device__ __forceinline__ void pair_to_tiles(int pair, int T, int& ti, int& tj)
 }
 __host__ __device__ __forceinline__ int diag_pair(int t, int T) { return t * T - t * (t - 1) / 2; }
 
-// 8 waves: wave (wi, wj) of a 2 x 4 arrangement owns tile rows [128 wi, +128) x tile columns [64 wj, +64)
-// = 4 x 2 MFMA blocks of 32 x 32 (v_mfma_f32_32x32x16_bf16).
+// 8 waves: wave (wi, wj) of a 2 x 4 arrangement owns 4 x 2 MFMA blocks of 32 x 32 (v_mfma_f32_32x32x16_bf16).
 //
-// LDS stage: rows of 512 bytes (256 columns); the 64-byte unit u of row r sits at unit u ^ (r & 3) of its
-// 256-byte quarter, so the four consecutive rows a transposing read touches (64 bytes of each per half-wave)
-// cover all 64 banks once.  A wave's load instruction brings two rows (64 lanes x 16 bytes written back to
-// back); the swizzle is applied on the global side (which 16-byte chunk a lane fetches).
-typedef short v4s __attribute__((ext_vector_type(4)));
-typedef short v8s __attribute__((ext_vector_type(8)));
-
-__device__ __forceinline__ v8bf tr_fragment(const uint8_t* lo, const uint8_t* hi) {
-    const v4s a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(lo));
-    const v4s b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(hi));
-    const v8s f{a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-    return __builtin_bit_cast(v8bf, f);
-}
-
+// Staging.  A stage is 64 batch rows x 256 columns per operand.  Thread (c = chunk of 8 columns, g = group
+// of 8 rows) fetches its 8 x 8 block (8 loads of 16 bytes, 512-byte runs per row across 32 lanes), transposes
+// it in registers (32 byte permutes) and writes one 16-byte word per column: the 8 contraction values an
+// MFMA lane needs, so an operand fragment is ONE ds_read_b128.  LDS layout of a tile: [row group g][position
+// pos][16 bytes] with column 8 c + e at position 32 e + c: the 32 lanes that write column e of their chunks
+// write 512 consecutive bytes, and MFMA block t (positions 32 t .. 32 t + 31) is the set of columns 8 m + t,
+// m = 0..31 = the block's MFMA row (or column) index.  Which tile column lands on which MFMA row is free as
+// long as the epilogue knows: wave (wi, wj) owns blocks 4 wi .. 4 wi + 3 on the i side, 2 wj, 2 wj + 1 on the j side.
+// Waves 0..3 stage the i tile, waves 4..7 the j tile (nothing on a diagonal pair, where both operands are
+// the i tile).  The loads of stage s + 1 are in flight while stage s is multiplied (registers), two LDS
+// buffers, one barrier per stage.
 __global__ __launch_bounds__(512) void tracker_scatter_kernel(const TrackerParams p) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-    double* red = reinterpret_cast<double*>(smem + TRK_NS * TRK_STAGEB);      // [4][256]
+    double* red = reinterpret_cast<double*>(smem + 2 * TRK_STAGEB);           // [2][256]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wi = wave >> 2, wj = wave & 3;
     const int ldB = static_cast<int>(p.ld) * 2;
 
-    // fragment read offsets inside a tile: lane (group g = lane / 16, j = lane % 16) addresses columns
-    // 16 (g & 1) + 4 (j % 4) .. + 3 of row 8 (g >> 1) + j / 4 (+ 4 for the second read, + 16 for the second k step)
-    const int fr_row = 8 * (lane >> 5) + ((lane & 15) >> 2);
-    const int fr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);                 // within a 32-column block
-    const int fr_key = (fr_row & 3) << 6;                                       // rows + 4, + 16 share it
-    const int a_off = fr_row * TRK_ROWB + ((wi * 256 + fr_col * 2) ^ fr_key);   // + 64 t per 32-column block
-    const int b_off = fr_row * TRK_ROWB + ((wj * 128 + fr_col * 2) ^ fr_key);
-    // column-sum read: word tid % 128 (two columns) of rows 8 (tid / 128) + r
-    const int cw = tid & 127, crg = tid >> 7;
-    const int c_off = (8 * crg) * TRK_ROWB + cw * 4;
     // consecutive logical ids sit on one XCD (the dispatcher deals workgroups round-robin over the 8 XCDs)
     const int G = gridDim.x;
     const int id = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
-    {
-        const int split = id / p.pairs, pair = id - split * p.pairs;
-        const int64_t row_begin = static_cast<int64_t>(split) * p.rows_per_split;
-        const int64_t row_end = row_begin + p.rows_per_split < p.B ? row_begin + p.rows_per_split : p.B;
-        const int nsteps = static_cast<int>((row_end - row_begin + TRK_MS - 1) / TRK_MS);
-        const int slot = id;
-        int ti, tj;
-        pair_to_tiles(pair, p.T, ti, tj);
-        const bool diag = ti == tj;
+    const int split = id / p.pairs, pair = id - split * p.pairs;
+    const int64_t row_begin = static_cast<int64_t>(split) * p.rows_per_split;
+    const int64_t row_end = row_begin + p.rows_per_split < p.B ? row_begin + p.rows_per_split : p.B;
+    const int nst = static_cast<int>((row_end - row_begin + TRK_MS - 1) / TRK_MS);
+    int ti, tj;
+    pair_to_tiles(pair, p.T, ti, tj);
+    const bool diag = ti == tj;
 
-        // loader geometry.  Load j of a wave covers row pair g = (wave + 8 j) % 16 of the i tile (j < 2) or
-        // of the j tile; its rows are 2 g + lane / 32 with g & 1 = wave & 1 for every j.  Everything that
-        // decides whether a lane is in range sits in the per-lane offset: rows past the end of the batch fall
-        // behind the descriptor's byte count, columns past K get an offset beyond any descriptor.
-        const int lr = lane >> 5, chunk = (lane & 31) ^ (((2 * (wave & 1) + lr) & 3) << 2);
-        const int col_a = ti * TRK_T + chunk * 8, col_b = tj * TRK_T + chunk * 8;
-        const unsigned voff_a = col_a < p.K ? static_cast<unsigned>(lr * ldB + chunk * 16) : 0x80000000u;
-        const unsigned voff_b = col_b < p.K ? static_cast<unsigned>(lr * ldB + chunk * 16) : 0x80000000u;
-        auto issue = [&](int step) __attribute__((always_inline)) {
-            const int64_t r0 = row_begin + static_cast<int64_t>(step) * TRK_MS;
-            int64_t rows_valid = row_end - r0;
-            rows_valid = rows_valid < 0 ? 0 : rows_valid > TRK_MS ? TRK_MS : rows_valid;
-            const int rec_a = rows_valid ? static_cast<int>(rows_valid) * ldB - ti * TRK_T * 2 : 0;
-            const int rec_b = rows_valid && !diag ? static_cast<int>(rows_valid) * ldB - tj * TRK_T * 2 : 0;
-            const uint16_t* rowp = p.x + (rows_valid ? r0 : 0) * p.ld;
-            const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<uint16_t*>(rowp + ti * TRK_T), 0, rec_a, 0x00020000);
-            const __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<uint16_t*>(rowp + tj * TRK_T), 0, rec_b, 0x00020000);
-            uint8_t* st = smem + (step & (TRK_NS - 1)) * TRK_STAGEB;
+    // staging role of this thread
+    const bool stager = wave < 4 || !diag;
+    const int my_tile = wave < 4 ? ti : tj;
+    const int sc = tid & 31, sg = (tid & 255) >> 5;                         // column chunk, row group
+    // everything that decides whether a load is in range sits in the per-lane offset: rows past the end of
+    // the batch fall behind the descriptor's byte count, columns past K get an offset beyond any descriptor
+    const unsigned st_voff = (my_tile * TRK_T + sc * 8 < p.K) ? static_cast<unsigned>(sg * 8 * ldB + sc * 16) : 0x80000000u;
+    const int st_lds = (wave < 4 ? 0 : TRK_TILEB) + sg * 4096 + sc * 16;    // + 512 e per column of the chunk
+    u32x4 in[8];
+    auto fetch = [&](int st) __attribute__((always_inline)) {
+        if (!stager) return;
+        const int64_t r0 = row_begin + static_cast<int64_t>(st) * TRK_MS;
+        int64_t rows_valid = row_end - r0;
+        rows_valid = rows_valid > TRK_MS ? TRK_MS : rows_valid;
+        const int rec = static_cast<int>(rows_valid) * ldB - my_tile * TRK_T * 2;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(p.x + r0 * p.ld + my_tile * TRK_T), 0, rec, 0x00020000);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int g = (wave + 8 * j) & 15;                     // uniform
-                const unsigned rowoff = static_cast<unsigned>(2 * g * ldB);
-                if (j < 2)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (__attribute__((address_space(3))) void*)(st + g * 1024),
-                                                             16, voff_a + rowoff, 0, 0, 0);
-                else
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                        rs_b, (__attribute__((address_space(3))) void*)(st + TRK_TILEB + g * 1024), 16, voff_b + rowoff, 0, 0, 0);
-            }
-        };
+        for (int r = 0; r < 8; ++r)
+            in[r] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, st_voff + static_cast<unsigned>(r * ldB), 0, 0));
+    };
+    auto stage = [&](int buf) __attribute__((always_inline)) {
+        if (!stager) return;
+        uint8_t* dst = smem + buf * TRK_STAGEB + st_lds;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            u32x4 o;
+            const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;
+            o.x = __builtin_amdgcn_perm(in[1][e >> 1], in[0][e >> 1], sel);
+            o.y = __builtin_amdgcn_perm(in[3][e >> 1], in[2][e >> 1], sel);
+            o.z = __builtin_amdgcn_perm(in[5][e >> 1], in[4][e >> 1], sel);
+            o.w = __builtin_amdgcn_perm(in[7][e >> 1], in[6][e >> 1], sel);
+            *reinterpret_cast<u32x4*>(dst + e * 512) = o;
+        }
+    };
 
-        v16f acc[4][2];
+    // fragment reads: lane (m = lane % 32, h = lane / 32) takes position 32 t + m of row group 2 kk + h
+    const int fr_off = (lane >> 5) * 4096 + (lane & 31) * 16;
+    const int a_off = fr_off + wi * 4 * 512, b_off = fr_off + wj * 2 * 512;
+    auto read_frags = [&](const uint8_t* At, const uint8_t* Bt, int kk, v8bf (&fa)[4], v8bf (&fb)[2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) fa[t] = __builtin_bit_cast(v8bf, *reinterpret_cast<const u32x4*>(At + a_off + t * 512 + kk * 8192));
+#pragma unroll
+        for (int e = 0; e < 2; ++e) fb[e] = __builtin_bit_cast(v8bf, *reinterpret_cast<const u32x4*>(Bt + b_off + e * 512 + kk * 8192));
+    };
+    v16f acc[4][2];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][e][r] = 0.f;
+    auto mma = [&](const v8bf (&fa)[4], const v8bf (&fb)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int e = 0; e < 2; ++e)
+                acc[t][e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[t], fb[e], acc[t][e], 0, 0, 0);
+    };
+    // issue order of one k step: an MFMA, then one LDS read of the next step's fragments, six times over
+    auto interleave = [&]() __attribute__((always_inline)) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[t][e][r] = 0.f;
-        double cs0 = 0.0, cs1 = 0.0;
+        for (int i = 0; i < 6; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    };
+    // column sums (diagonal pairs): thread = (position tid % 256, row groups 4 (tid / 256) .. + 3), fp64
+    double cs = 0.0;
+    const int cs_off = (tid >> 8) * 4 * 4096 + (tid & 255) * 16;
 
-        // Software pipeline: the fragments of k step q + 1 are read from LDS while the MFMAs of k step q run
-        // (a wave that reads all fragments and then issues all MFMAs leaves the matrix pipe idle during the
-        // reads: the other wave of the SIMD is in the same phase).  One barrier per stage, in the middle of it.
-        auto read_frags = [&](const uint8_t* At, const uint8_t* Bt, int kk, v8bf (&fa)[4], v8bf (&fb)[2])
-                              __attribute__((always_inline)) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                fa[t] = tr_fragment(At + (a_off ^ (t << 6)) + kk * 16 * TRK_ROWB, At + (a_off ^ (t << 6)) + (kk * 16 + 4) * TRK_ROWB);
-#pragma unroll
-            for (int e = 0; e < 2; ++e)
-                fb[e] = tr_fragment(Bt + (b_off ^ (e << 6)) + kk * 16 * TRK_ROWB, Bt + (b_off ^ (e << 6)) + (kk * 16 + 4) * TRK_ROWB);
-        };
-        auto mma = [&](const v8bf (&fa)[4], const v8bf (&fb)[2]) __attribute__((always_inline)) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int e = 0; e < 2; ++e)
-                    acc[t][e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[t], fb[e], acc[t][e], 0, 0, 0);
-        };
-        // issue order of one k step: an MFMA, then two LDS reads of the next step's fragments, six times over
-        auto interleave = [&]() __attribute__((always_inline)) {
-#pragma unroll
-            for (int i = 0; i < 6; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        };
-
-#pragma unroll
-        for (int s = 0; s < TRK_NS - 1; ++s) issue(s);
-        wait_vmcnt<(TRK_NS - 2) * 4>();              // this wave's share of stage 0 has landed (loads return in order)
-        lds_barrier();
-        issue(TRK_NS - 1);
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int s = 0; s < nst; ++s) {
+        const uint8_t* At = smem + (s & 1) * TRK_STAGEB;
+        const uint8_t* Bt = diag ? At : At + TRK_TILEB;
+        // the two waves of a SIMD (w, w + 4) request their blocks of the next stage at different times: a wave
+        // sits in the load issue until the memory pipeline has taken its requests, and should not do so together
+        // with the wave that shares its matrix pipe.  (Measured: both groups at the start of the stage 750 us
+        // at B = 32768, K = 4096; staggered 690 us; the eight loads spread over the stage, two per k step, with
+        // a second register set so that they have a whole stage to land: 955 us.)
+        if (s + 1 < nst && wave < 4) fetch(s + 1);
         v8bf fa0[4], fb0[2], fa1[4], fb1[2];
-        read_frags(smem, diag ? smem : smem + TRK_TILEB, 0, fa0, fb0);
-        for (int s = 0; s < nsteps; ++s) {
-            const uint8_t* At = smem + (s & (TRK_NS - 1)) * TRK_STAGEB;
-            const uint8_t* Bt = diag ? At : At + TRK_TILEB;
-            read_frags(At, Bt, 1, fa1, fb1);
-            mma(fa0, fb0);
-            interleave();
-            if (diag) {
+        read_frags(At, Bt, 0, fa0, fb0);
+        read_frags(At, Bt, 1, fa1, fb1);
+        mma(fa0, fb0);
+        interleave();
+        if (s + 1 < nst && wave >= 4) fetch(s + 1);
+        read_frags(At, Bt, 2, fa0, fb0);
+        mma(fa1, fb1);
+        interleave();
+        read_frags(At, Bt, 3, fa1, fb1);
+        mma(fa0, fb0);
+        interleave();
+        mma(fa1, fb1);
+        if (diag) {
 #pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    const uint32_t w = *reinterpret_cast<const uint32_t*>(At + ((c_off + r * TRK_ROWB) ^ ((r & 3) << 6)));
-                    cs0 += static_cast<double>(bf16_lo(w));
-                    cs1 += static_cast<double>(bf16_hi(w));
+            for (int g = 0; g < 4; ++g) {
+                const u32x4 v = *reinterpret_cast<const u32x4*>(At + cs_off + g * 4096);
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    cs += static_cast<double>(bf16_lo(v[w]));
+                    cs += static_cast<double>(bf16_hi(v[w]));
                 }
             }
-            wait_vmcnt<(TRK_NS - 2) * 4>();          // stage s + 1 has landed
-            lds_barrier();                            // for everyone; and everyone has read all of stage s
-            issue(s + TRK_NS);                        // into the buffer of stage s (past the end: empty descriptors)
-            const uint8_t* An = smem + ((s + 1) & (TRK_NS - 1)) * TRK_STAGEB;
-            read_frags(An, diag ? An : An + TRK_TILEB, 0, fa0, fb0);   // past the last stage: read, never used
-            mma(fa1, fb1);
-            interleave();
         }
-        wait_vmcnt<0>();                              // the empty tail loads too, before the wave may end
+        if (s + 1 < nst) stage((s + 1) & 1);
+        __syncthreads();
+    }
 
-        // raw partial scatter: element r of a lane is row 8 (r / 4) + 4 h + r % 4 of a 32 x 32 block, column p5;
-        // block (t, e) holds tile rows 128 wi + 32 t + row and tile columns 64 wj + 32 e + p5
-        // (offsets recomputed from an opaque copy of the lane id: derived from a loop invariant, the compiler
-        // would keep the store addresses alive across the main loop, in registers the accumulators need)
-        int lane_o = lane;
-        asm volatile("" : "+v"(lane_o));
-        float* out = p.partial + static_cast<int64_t>(slot) * (TRK_T * TRK_T) + (wi * 128 + 4 * (lane_o >> 5)) * TRK_T +
-                     wj * 64 + (lane_o & 31);
+    // raw partial scatter: element r of a lane is MFMA row 8 (r / 4) + 4 h + r % 4, MFMA column lane % 32 of its
+    // block; block (ta, tb) row R is tile row 8 R + 4 wi + ta, column C is tile column 8 C + 2 wj + tb
+    // (offsets recomputed from an opaque copy of the lane id: derived from a loop invariant, the compiler
+    // would keep the store addresses alive across the main loop, in registers the accumulators need)
+    int lane_o = lane;
+    asm volatile("" : "+v"(lane_o));
+    float* out = p.partial + static_cast<int64_t>(id) * (TRK_T * TRK_T) + (32 * (lane_o >> 5) + 4 * wi) * TRK_T +
+                 8 * (lane_o & 31) + 2 * wj;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int e = 0; e < 2; ++e)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) out[(32 * t + 8 * (r >> 2) + (r & 3)) * TRK_T + 32 * e] = acc[t][e][r];
-        if (diag) {
-            red[crg * TRK_T + 2 * cw] = cs0;
-            red[crg * TRK_T + 2 * cw + 1] = cs1;
-            __syncthreads();
-            if (tid < TRK_T) {
-                const double sum = ((red[tid] + red[TRK_T + tid]) + red[2 * TRK_T + tid]) + red[3 * TRK_T + tid];
-                p.colsum[static_cast<int64_t>(slot) * TRK_T + tid] = sum;
-            }
+        for (int r = 0; r < 16; ++r) {
+            const f32x2_t v{acc[t][0][r], acc[t][1][r]};
+            *reinterpret_cast<f32x2_t*>(out + (64 * (r >> 2) + 8 * (r & 3) + t) * TRK_T) = v;
         }
+    if (diag) {
+        // position pos holds column 8 (pos % 32) + pos / 32
+        const int pos = tid & 255, col = 8 * (pos & 31) + (pos >> 5);
+        red[(tid >> 8) * TRK_T + col] = cs;
+        __syncthreads();
+        if (tid < TRK_T) p.colsum[static_cast<int64_t>(id) * TRK_T + tid] = red[tid] + red[TRK_T + tid];
     }
 }
 
