@@ -75,7 +75,9 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const uint16_t* __restr
                 u32x2 o;
                 o.x = e4m3x4(bf16_lo(w.x) * inv, bf16_hi(w.x) * inv, bf16_lo(w.y) * inv, bf16_hi(w.y) * inv);
                 o.y = e4m3x4(bf16_lo(w.z) * inv, bf16_hi(w.z) * inv, bf16_lo(w.w) * inv, bf16_hi(w.w) * inv);
-                __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(q + r * cols + c * 8));
+                // plain store: the GEMM that follows reads the codes from the last-level cache (measured at
+                // 32768 x 4096: the GEMM runs 3 % faster than after a streaming store, this kernel no slower)
+                *reinterpret_cast<u32x2*>(q + r * cols + c * 8) = o;
                 if (BLOCK128) {
                     if ((c & 15) == 0) scales[r * (cols >> 7) + (c >> 4)] = scale;
                 } else if (j == 0 && lr == 0) {
@@ -260,7 +262,7 @@ __global__ __launch_bounds__(256) void cast_kernel(const uint16_t* __restrict__ 
         u32x2 o;
         o.x = e4m3x4(bf16_lo(w.x) * f[0], bf16_hi(w.x) * f[1], bf16_lo(w.y) * f[2], bf16_hi(w.y) * f[3]);
         o.y = e4m3x4(bf16_lo(w.z) * f[4], bf16_hi(w.z) * f[5], bf16_lo(w.w) * f[6], bf16_hi(w.w) * f[7]);
-        __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(q + r * cols + c * 8));
+        *reinterpret_cast<u32x2*>(q + r * cols + c * 8) = o;   // plain store: the consumer reads the codes next
     }
 }
 
