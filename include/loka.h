@@ -33,7 +33,8 @@ typedef enum {
     LOKA_ERR_UNSUPPORTED = 4,  /* enum out of range, or a scale/norm/N/variant combination no kernel covers */
     LOKA_ERR_WORKSPACE = 5,    /* workspace NULL or smaller than the *_workspace() query */
     LOKA_ERR_HIP = 6,          /* a HIP runtime call failed (launch error, no device) */
-    LOKA_ERR_NO_CANDIDATE = 7  /* dispatch: no FP8 variant meets the error budget / speedup floor */
+    LOKA_ERR_NO_CANDIDATE = 7, /* dispatch: no FP8 variant meets the error budget / speedup floor */
+    LOKA_ERR_TIMEOUT = 8       /* loka_fp8_gemm_norm_check: a bounded wait inside the last launch ran out; its output is invalid */
 } loka_status;
 
 /* Scale granularity of a [rows, cols] matrix (Section 3.3, "Library and Recipe
@@ -143,6 +144,15 @@ size_t loka_fp8_gemm_norm_workspace(const loka_gemm_desc* desc);
 loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
                                const float* sw, const void* gamma_bf16, const void* beta_bf16, void* out_bf16,
                                float* y_fp32, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* Variants whose row statistics cross workgroups inside one launch (rows wider than a tile) make every
+ * workgroup wait for the other tiles of its row panel.  The wait is bounded: if it runs out (it never does when
+ * the launch's workgroups are all resident, which the launch arranges), the workgroup raises a flag in the
+ * workspace and goes on, so the kernel always ends; the output of that launch is then invalid.  This call reports
+ * the flag of the LAST loka_fp8_gemm_norm call that used `workspace` with `desc`: LOKA_OK, or LOKA_ERR_TIMEOUT.
+ * It SYNCHRONIZES hip_stream (4 bytes are copied to the host); variants without such a wait return LOKA_OK
+ * without touching the GPU.  Not needed on the hot path; meant for health checks and tests. */
+loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* workspace, size_t ws_bytes, void* hip_stream);
 
 /* FP8 output for the next layer (Section 3.2, "Block-wise Normalization", Case 1: when the whole row is
  * normalized inside one workgroup, "activation and (de)quantization can also be fused together before the

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libloka.so")
 
 LOKA_OK = 0
 LOKA_ERR_NULL, LOKA_ERR_SHAPE, LOKA_ERR_ALIGN, LOKA_ERR_UNSUPPORTED = 1, 2, 3, 4
-LOKA_ERR_WORKSPACE, LOKA_ERR_HIP, LOKA_ERR_NO_CANDIDATE = 5, 6, 7
+LOKA_ERR_WORKSPACE, LOKA_ERR_HIP, LOKA_ERR_NO_CANDIDATE, LOKA_ERR_TIMEOUT = 5, 6, 7, 8
 SCALE_TENSOR, SCALE_ROW, SCALE_COL, SCALE_BLOCK_1x128, SCALE_BLOCK_128x128 = range(5)
 NORM_NONE, NORM_LAYERNORM, NORM_RMSNORM, NORM_BLOCKNORM = range(4)
 NORMS = {"none": NORM_NONE, "layernorm": NORM_LAYERNORM, "rmsnorm": NORM_RMSNORM, "blocknorm": NORM_BLOCKNORM}
@@ -72,6 +72,7 @@ _SIGNATURES = [
     ("loka_fp8_gemm_norm_workspace", c_size_t, [POINTER(GemmDesc)]),
     ("loka_fp8_gemm_norm", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                    c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    ("loka_fp8_gemm_norm_check", c_int, [POINTER(GemmDesc), c_void_p, c_size_t, c_void_p]),
     ("loka_fp8_gemm_norm_fp8out", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                           c_void_p, c_void_p, c_void_p, c_void_p]),
     ("loka_bf16_gemm_workspace", c_size_t, [POINTER(GemmDesc)]),
@@ -200,6 +201,13 @@ def loka_fp8_gemm_norm(desc: GemmDesc, xq, sx, wq, sw, gamma=None, beta=None, wa
                                     _ptr(out), _ptr(y), _ptr(workspace), workspace.numel(), _stream()),
            "loka_fp8_gemm_norm")
     return out, y
+
+
+def loka_fp8_gemm_norm_check(desc: GemmDesc, workspace) -> int:
+    """Status of the bounded waits of the last loka_fp8_gemm_norm call on `workspace` (synchronizes): LOKA_OK or
+    LOKA_ERR_TIMEOUT."""
+    return int(lib().loka_fp8_gemm_norm_check(byref(desc), _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                              _stream()))
 
 
 def loka_fp8_gemm_norm_fp8out(desc: GemmDesc, xq, sx, wq, sw, gamma=None, beta=None, want_y: bool = False, oq=None,

@@ -18,6 +18,7 @@ size_t variant_workspace(const loka_gemm_desc*, int);
 loka_status fp8_gemm_norm_launch(const loka_gemm_desc*, int, const uint8_t*, const float*, const uint8_t*, const float*,
                                  const void*, const void*, void*, float*, uint8_t*, float*, void*, hipStream_t);
 int variant_streaming_id();
+bool variant_has_wait_flag(const loka_gemm_desc*, int);
 size_t bf16_gemm_workspace_bytes(const loka_gemm_desc*);
 loka_status bf16_gemm_launch(const loka_gemm_desc*, const void*, const void*, float*, void*, hipStream_t);
 // probe.hip
@@ -87,6 +88,7 @@ const char* loka_status_string(loka_status s) {
         case LOKA_ERR_WORKSPACE: return "workspace missing or too small";
         case LOKA_ERR_HIP: return "HIP runtime error";
         case LOKA_ERR_NO_CANDIDATE: return "no FP8 candidate within the error budget";
+        case LOKA_ERR_TIMEOUT: return "a bounded wait inside the launch ran out";
     }
     return "unknown status";
 }
@@ -164,6 +166,21 @@ loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, co
     if (need && !aligned16(workspace)) return LOKA_ERR_ALIGN;
     return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, out_bf16, y_fp32, nullptr, nullptr,
                                 workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* workspace, size_t ws_bytes, void* hip_stream) {
+    if (!desc) return LOKA_ERR_NULL;
+    const loka_status st = validate_desc(desc, true);
+    if (st != LOKA_OK) return st;
+    const int v = resolve_variant(desc);
+    if (v < 0) return LOKA_ERR_UNSUPPORTED;
+    if (!variant_has_wait_flag(desc, v)) return LOKA_OK;
+    if (!workspace || ws_bytes < variant_workspace(desc, v)) return LOKA_ERR_WORKSPACE;
+    unsigned flag = 0;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    LOKA_HIP_TRY(hipMemcpyAsync(&flag, workspace, sizeof(flag), hipMemcpyDeviceToHost, s));
+    LOKA_HIP_TRY(hipStreamSynchronize(s));
+    return flag ? LOKA_ERR_TIMEOUT : LOKA_OK;
 }
 
 loka_status loka_fp8_gemm_norm_fp8out(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,

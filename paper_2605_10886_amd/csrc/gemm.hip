@@ -777,6 +777,11 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
     return tiles < (int64_t(1) << 31);
 }
 
+// the variant's workspace starts with the flag a workgroup raises when its bounded wait for the panel runs out
+bool variant_has_wait_flag(const loka_gemm_desc* d, int v) {
+    return kVariants[v].epi == EPI_PANEL_SYNC && d->norm != LOKA_NORM_NONE && d->norm != LOKA_NORM_BLOCKNORM;
+}
+
 size_t variant_workspace(const loka_gemm_desc* d, int v) {
     const VariantInfo& vi = kVariants[v];
     if (vi.epi == EPI_ROW_IN_TILE || d->norm == LOKA_NORM_NONE || d->norm == LOKA_NORM_BLOCKNORM) return 0;

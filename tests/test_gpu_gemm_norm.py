@@ -3,6 +3,8 @@
 The GPU consumes the codes and scales its own loka_quantize produced; those are
 checked bit-exact against the oracle first, so both sides contract the same operands.
 """
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -474,3 +476,26 @@ def test_bf16_reference_gemm_grouped(orc):
     for g in range(G):
         y_o = orc.ref_gemm(synth.bf16_bits(x[g * M:(g + 1) * M]), synth.bf16_bits(wt[g * K:(g + 1) * K]))
         assert rel_fro(y[g * M:(g + 1) * M], y_o) <= 1e-5
+
+
+def test_bounded_wait_is_reported(monkeypatch):
+    # the panel-synchronous variants wait for the other tiles of a row panel; a wait that runs out raises a flag
+    # and the kernel still ends.  Forced from the host with a spin limit of zero polls (read at every launch).
+    M, K, N = 2048, 256, 2048
+    x, wt = synth.normal(M, K, 3).to(DEV), synth.weight(K, N, 4).to(DEV)
+    xq, sx = B.loka_quantize(x, B.SCALE_ROW)
+    wq, sw = B.loka_quantize(wt, B.SCALE_COL, transpose_out=True)
+    desc = B.make_desc(M, N, K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, 1e-5, variant=B.variant_id("panel32_256x256"))
+    ws = torch.empty(B.lib().loka_fp8_gemm_norm_workspace(ctypes.byref(desc)), dtype=torch.uint8, device=DEV)
+    good, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, workspace=ws)
+    assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
+    monkeypatch.setenv("LOKA_SPIN_LIMIT", "0")
+    B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, workspace=ws)
+    assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_ERR_TIMEOUT
+    monkeypatch.delenv("LOKA_SPIN_LIMIT")
+    again, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, workspace=ws)
+    assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
+    assert torch.equal(good, again)
+    # variants without a cross-workgroup wait have nothing to report
+    row = B.make_desc(256, 128, 128, variant=B.variant_id("row64x128"))
+    assert B.loka_fp8_gemm_norm_check(row, None) == B.LOKA_OK
