@@ -72,6 +72,8 @@ _SIGNATURES = [
     ("loka_fp8_gemm_norm_workspace", c_size_t, [POINTER(GemmDesc)]),
     ("loka_fp8_gemm_norm", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                    c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    ("loka_fp8_linear_norm", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                     c_void_p, c_void_p]),
     ("loka_fp8_gemm_norm_check", c_int, [POINTER(GemmDesc), c_void_p, c_size_t, c_void_p]),
     ("loka_fp8_gemm_norm_fp8out", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                           c_void_p, c_void_p, c_void_p, c_void_p]),
@@ -201,6 +203,20 @@ def loka_fp8_gemm_norm(desc: GemmDesc, xq, sx, wq, sw, gamma=None, beta=None, wa
                                     _ptr(out), _ptr(y), _ptr(workspace), workspace.numel(), _stream()),
            "loka_fp8_gemm_norm")
     return out, y
+
+
+def loka_fp8_linear_norm(desc: GemmDesc, x, wq, sw, gamma=None, beta=None, want_y: bool = False, want_sx: bool = False,
+                         out=None):
+    """Rowwise quantization of bf16 x fused into the GEMM + norm.  Returns (O bf16, Y fp32 or None, sx or None)."""
+    rows = desc.batch * desc.M
+    dev = x.device
+    if out is None:
+        out = torch.empty((rows, desc.N), dtype=torch.bfloat16, device=dev)
+    y = torch.empty((rows, desc.N), dtype=torch.float32, device=dev) if want_y else None
+    sx = torch.empty(rows, dtype=torch.float32, device=dev) if want_sx else None
+    _check(lib().loka_fp8_linear_norm(byref(desc), _ptr(x), _ptr(wq), _ptr(sw), _ptr(gamma), _ptr(beta), _ptr(out), _ptr(y),
+                                      _ptr(sx), _stream()), "loka_fp8_linear_norm")
+    return out, y, sx
 
 
 def loka_fp8_gemm_norm_check(desc: GemmDesc, workspace) -> int:

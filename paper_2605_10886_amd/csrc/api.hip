@@ -18,6 +18,8 @@ size_t variant_workspace(const loka_gemm_desc*, int);
 loka_status fp8_gemm_norm_launch(const loka_gemm_desc*, int, const uint8_t*, const float*, const uint8_t*, const float*,
                                  const void*, const void*, void*, float*, uint8_t*, float*, void*, hipStream_t);
 int variant_streaming_id();
+loka_status fp8_linear_norm_launch(const loka_gemm_desc*, int, const void*, const uint8_t*, const float*, const void*,
+                                   const void*, void*, float*, float*, hipStream_t);
 bool variant_has_wait_flag(const loka_gemm_desc*, int);
 size_t bf16_gemm_workspace_bytes(const loka_gemm_desc*);
 loka_status bf16_gemm_launch(const loka_gemm_desc*, const void*, const void*, float*, void*, hipStream_t);
@@ -166,6 +168,23 @@ loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, co
     if (need && !aligned16(workspace)) return LOKA_ERR_ALIGN;
     return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, out_bf16, y_fp32, nullptr, nullptr,
                                 workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+loka_status loka_fp8_linear_norm(const loka_gemm_desc* desc, const void* x_bf16, const uint8_t* wq, const float* sw,
+                                 const void* gamma_bf16, const void* beta_bf16, void* out_bf16, float* y_fp32,
+                                 float* sx_out, void* hip_stream) {
+    if (!desc || !x_bf16 || !wq || !sw || !out_bf16) return LOKA_ERR_NULL;
+    const loka_status st = validate_desc(desc, true);
+    if (st != LOKA_OK) return st;
+    if (desc->x_mode != LOKA_SCALE_ROW) return LOKA_ERR_UNSUPPORTED;
+    if (!aligned16(x_bf16) || !aligned16(wq) || !aligned16(sw) || !aligned16(out_bf16) || !aligned16(y_fp32) ||
+        !aligned16(gamma_bf16) || !aligned16(beta_bf16) || !aligned16(sx_out))
+        return LOKA_ERR_ALIGN;
+    // the streaming kernel keeps whole rows of X in one workgroup: the row amax needs no second pass
+    const int v = variant_streaming_id();
+    if (v < 0 || !variant_supports(desc, v) || (desc->variant >= 0 && desc->variant != v)) return LOKA_ERR_UNSUPPORTED;
+    return fp8_linear_norm_launch(desc, v, x_bf16, wq, sw, gamma_bf16, beta_bf16, out_bf16, y_fp32, sx_out,
+                                  static_cast<hipStream_t>(hip_stream));
 }
 
 loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* workspace, size_t ws_bytes, void* hip_stream) {

@@ -703,7 +703,8 @@ static void launch_fp8(const GemmParams& p, bool blockwise, dim3 grid, hipStream
 
 // gemm_wreg.hip
 bool wreg_supports(int64_t M, int64_t N, int64_t K);
-int wreg_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool fp8_out, const void** fn, size_t* lds);
+bool wreg_supports_fused(int64_t M, int64_t N, int64_t K);
+int wreg_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool fp8_out, bool bf16_in, const void** fn, size_t* lds);
 void wreg_launch(const GemmParams& p, dim3 grid, hipStream_t s);
 static void launch_wreg_any(const GemmParams& p, bool, dim3 grid, hipStream_t s) { wreg_launch(p, grid, s); }
 static const char kWregName[] = "wreg32";
@@ -816,9 +817,28 @@ static loka_status set_lds(const void* fn, size_t lds) {
     return LOKA_OK;
 }
 
+static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const uint8_t* xq, const float* sx, const uint8_t* wq,
+                                        const float* sw, const void* gamma, const void* beta, void* out, float* y,
+                                        uint8_t* outq, float* outs, const void* x_bf16, float* sx_out, void* workspace,
+                                        hipStream_t s);
+
 loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* xq, const float* sx, const uint8_t* wq,
                                  const float* sw, const void* gamma, const void* beta, void* out, float* y,
                                  uint8_t* outq, float* outs, void* workspace, hipStream_t s) {
+    return gemm_norm_launch_impl(d, v, xq, sx, wq, sw, gamma, beta, out, y, outq, outs, nullptr, nullptr, workspace, s);
+}
+
+// bf16 X quantized row by row inside the streaming kernel (v must be that variant)
+loka_status fp8_linear_norm_launch(const loka_gemm_desc* d, int v, const void* x_bf16, const uint8_t* wq, const float* sw,
+                                   const void* gamma, const void* beta, void* out, float* y, float* sx_out, hipStream_t s) {
+    if (kVariants[v].name != kWregName || !wreg_supports_fused(d->M, d->N, d->K)) return LOKA_ERR_UNSUPPORTED;
+    return gemm_norm_launch_impl(d, v, nullptr, nullptr, wq, sw, gamma, beta, out, y, nullptr, nullptr, x_bf16, sx_out, nullptr, s);
+}
+
+static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const uint8_t* xq, const float* sx, const uint8_t* wq,
+                                        const float* sw, const void* gamma, const void* beta, void* out, float* y,
+                                        uint8_t* outq, float* outs, const void* x_bf16, float* sx_out, void* workspace,
+                                        hipStream_t s) {
     const VariantInfo& vi = kVariants[v];
     const bool blockwise = d->x_mode == LOKA_SCALE_BLOCK_1x128;
     GemmParams p{};
@@ -833,6 +853,7 @@ loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* 
     p.gamma = static_cast<const uint16_t*>(gamma); p.beta = static_cast<const uint16_t*>(beta);
     p.out = static_cast<uint16_t*>(out); p.y = y;
     p.outq = outq; p.outs = outs;
+    p.xb = static_cast<const uint16_t*>(x_bf16); p.sx_out = sx_out;
     if (outq && vi.name != kWregName) return LOKA_ERR_UNSUPPORTED;   // FP8 output: the row must stay inside one workgroup
     p.norm = d->norm; p.eps = d->eps; p.block_n = d->block_n; p.act = d->act;
     p.tiles_m = static_cast<int>((d->M + vi.bm - 1) / vi.bm);
@@ -850,7 +871,7 @@ loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* 
         size_t lds = 0;
         LOKA_HIP_TRY(hipGetDevice(&dev));
         LOKA_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        const int wgs = wreg_plan(d->M, d->N, d->K, d->batch, cus, p.outq != nullptr, &fn, &lds);
+        const int wgs = wreg_plan(d->M, d->N, d->K, d->batch, cus, p.outq != nullptr, p.xb != nullptr, &fn, &lds);
         if (wgs <= 0) return LOKA_ERR_UNSUPPORTED;
         if (set_lds(fn, lds) != LOKA_OK) return LOKA_ERR_HIP;
         vi.launch(p, false, dim3(static_cast<unsigned>(wgs)), s);

@@ -23,6 +23,8 @@ struct GemmParams {
     uint16_t* out;
     uint8_t* outq;         // FP8 output instead of `out`: e4m3 codes [batch][M][N] ...
     float* outs;           // ... and their row scales [batch][M]
+    const uint16_t* xb;    // fused quantization (streaming kernel): bf16 X [batch][M][K] instead of X / sx ...
+    float* sx_out;         // ... and, optionally, where the row scales it computes are written [batch][M]
     float* y;
     int norm;              // loka_norm
     int block_n, act;      // LOKA_NORM_BLOCKNORM group width; loka_act

@@ -53,7 +53,7 @@ struct WregCfg {
     static_assert(LPW >= 1, "a block is at least 4 KB");
 };
 
-template <int WNC, int KS, int RT, bool FP8OUT>
+template <int WNC, int KS, int RT, bool FP8OUT, bool BF16IN>
 __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, const int blocks_per_problem) {
     using C = WregCfg<WNC, KS, RT>;
     constexpr int NIW = C::NIW, KB = C::KB, NT = C::NT, RB = C::RB, NBUF = C::NBUF, LPW = C::LPW, LDW = C::LDW, SXL = C::SXL;
@@ -100,6 +100,92 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 sr, (__attribute__((address_space(3))) void*)(smem + C::OFF_SX + (((b % NBUF) * 4 + wave) * SXL + q) * 256), 4,
                 tensor_x ? 0 : (m0 + 64 * q + lv) * 4, 0, 0, 0);
+    };
+
+    // ---- fused rowwise quantization (BF16IN): X arrives as bf16 and is quantized here exactly as the quantize
+    // entry point would (row amax, scale = amax / 448, code = e4m3(x * (448 / amax))), so the FP8 copy of X never
+    // travels through HBM.  All 8 waves fetch: wave w owns rows [w RB / 8, +RB / 8) of a block, NLD loads of 16
+    // bytes (8 elements) per lane, a row spread over CH_ROW consecutive lanes (or over IPR loads of a whole wave).
+    // fetch(b) requests block b into registers; convert(b) (one iteration later) reduces the row amax across the
+    // row's lanes, computes the two divisions ONCE per lane for a different row each (an IEEE division costs
+    // hundreds of cycles) and hands the results round by lane shuffles, converts and writes codes and scales
+    // into block b's ring slot in the layout the loads-to-LDS produce on the other path.
+    constexpr int CH_ROW = KB / 8;                                  // 16-byte chunks of bf16 per row
+    constexpr int RPI = CH_ROW >= 64 ? 1 : 64 / CH_ROW;             // rows per wave instruction
+    constexpr int IPR = CH_ROW >= 64 ? CH_ROW / 64 : 1;             // instructions per row
+    constexpr int RW = RB / 8;                                      // rows per wave and block
+    constexpr int NLD = BF16IN ? RW * IPR / RPI : IPR;              // loads per lane and block
+    constexpr int NRG = NLD / IPR;                                  // rows per lane and block
+    static_assert(!BF16IN || (RW * IPR % RPI == 0 && NLD >= 1 && NRG <= 16), "fused quantization: block shape");
+    u32x4 raw[NLD];
+    auto fetch = [&](int b) __attribute__((always_inline)) {
+        const int g = b / blocks_per_problem, m0 = (b - g * blocks_per_problem) * RB;
+        const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(p.xb + static_cast<int64_t>(g) * p.strideX), 0, static_cast<unsigned>(p.M) * (2u * KB), 0x00020000);
+        int lv = lane;
+        asm volatile("; lane id" : "+v"(lv));
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int row = wave * RW + (j / IPR) * RPI + (IPR == 1 ? lv / CH_ROW : 0);
+            const int chunk = IPR == 1 ? lv % CH_ROW : (j % IPR) * 64 + lv;
+            // (the whole offset is the per-lane one, which the descriptor's bound applies to: rows past M read as zeros)
+            raw[j] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                   xr, static_cast<unsigned>(m0 + row) * (2u * KB) + static_cast<unsigned>(chunk * 16), 0, 0));
+        }
+    };
+    auto convert = [&](int b) __attribute__((always_inline)) {
+        const int g = b / blocks_per_problem, m0 = (b - g * blocks_per_problem) * RB;
+        uint8_t* const dst = smem + C::OFF_X + (b % NBUF) * C::XBYTES;
+        float* const sxl = reinterpret_cast<float*>(smem + C::OFF_SX + (b % NBUF) * 4 * SXL * 256);
+        int lv = lane;
+        asm volatile("; lane id" : "+v"(lv));
+        // row amax: integer max of the 15-bit magnitudes (exact), lanes of the row by xor shuffles
+        unsigned am[NRG];
+#pragma unroll
+        for (int rg = 0; rg < NRG; ++rg) {
+            unsigned a = 0u;
+#pragma unroll
+            for (int i = 0; i < IPR; ++i) {
+                const u32x4 w = raw[rg * IPR + i];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const unsigned lo = w[e] & 0x7FFFu, hi = (w[e] >> 16) & 0x7FFFu;
+                    a = a > lo ? a : lo;
+                    a = a > hi ? a : hi;
+                }
+            }
+#pragma unroll
+            for (int msk = 1; msk < (CH_ROW < 64 ? CH_ROW : 64); msk <<= 1) {
+                const unsigned o = static_cast<unsigned>(__shfl_xor(static_cast<int>(a), msk, 64));
+                a = a > o ? a : o;
+            }
+            am[rg] = a;
+        }
+        // lane (lv % 16) = rg of each row's lane group computes that row's scale and factor
+        unsigned mine = am[0];
+#pragma unroll
+        for (int rg = 1; rg < NRG; ++rg) mine = (lv & 15) == rg ? am[rg] : mine;
+        float scale_l, inv_l;
+        group_scale(__uint_as_float(mine << 16), scale_l, inv_l);
+        const int grp_base = IPR == 1 ? (lv / CH_ROW) * CH_ROW : 0;         // first lane of this lane's row group
+#pragma unroll
+        for (int rg = 0; rg < NRG; ++rg) {
+            const float scale = __shfl(scale_l, grp_base + rg, 64), inv = __shfl(inv_l, grp_base + rg, 64);
+            const int row = wave * RW + rg * RPI + (IPR == 1 ? lv / CH_ROW : 0);
+#pragma unroll
+            for (int i = 0; i < IPR; ++i) {
+                const u32x4 w = raw[rg * IPR + i];
+                const int chunk = IPR == 1 ? lv % CH_ROW : i * 64 + lv;      // 8 elements = half a 16-byte chunk of codes
+                u32x2 o;
+                o.x = e4m3x4(bf16_lo(w.x) * inv, bf16_hi(w.x) * inv, bf16_lo(w.y) * inv, bf16_hi(w.y) * inv);
+                o.y = e4m3x4(bf16_lo(w.z) * inv, bf16_hi(w.z) * inv, bf16_lo(w.w) * inv, bf16_hi(w.w) * inv);
+                *reinterpret_cast<u32x2*>(dst + row * KB + ((((chunk >> 1) ^ (row & KEYMASK)) << 4) | ((chunk & 1) << 3))) = o;
+                if (chunk == 0) {
+                    sxl[row] = scale;
+                    if (p.sx_out && m0 + row < p.M) p.sx_out[static_cast<int64_t>(g) * p.M + m0 + row] = scale;
+                }
+            }
+        }
     };
 
     // ---- W fragments of this wave's columns, all of K: wreg[ni][j] feeds MFMA rows with W rows (= output
@@ -161,7 +247,12 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
     // W and the tables of problem g, then the first requests for X from block `bf` on
     auto start_problem = [&](int g, int bf) __attribute__((always_inline)) {
         load_problem(g);
-        if (loader) {
+        if (BF16IN) {
+            fetch(bf);
+            wait_vmcnt<0>();
+            convert(bf);
+            if (bf + 1 < b1) fetch(bf + 1);
+        } else if (loader) {
 #pragma unroll
             for (int i = 0; i < NBUF - 1; ++i)
                 if (bf + i < b1) issue_block(bf + i);
@@ -181,12 +272,19 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         LOKA_STAMP(0);
         if (g != cur_g) {
             // (the staging of W overwrites the X blocks requested so far: they are requested again)
-            if (loader) wait_vmcnt<0>();
+            if (loader || BF16IN) wait_vmcnt<0>();
             start_problem(g, b);
             cur_g = g;
         }
+        if (BF16IN) {
+            // block b + 1 was requested an iteration ago: quantize it into its ring slot (the slot of block b - 1,
+            // whose reads ended before that iteration's statistics barrier)
+            if (b + 1 < b1) {
+                wait_vmcnt<0>();
+                convert(b + 1);
+            }
+        } else if (loader) {
         // block b has landed: the loaders' newer requests (up to NBUF - 2 blocks) may still be in flight
-        if (loader) {
             const int newer = b1 - 1 - b < NBUF - 2 ? b1 - 1 - b : NBUF - 2;
             if (p.y) wait_vmcnt<0>();                                   // Y stores share the counter
             else if (newer >= 2) wait_vmcnt<(NBUF >= 4 ? 2 : 0) * LDW>();
@@ -195,7 +293,11 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         }
         lds_barrier();
         LOKA_STAMP(1);
-        if (loader && b + NBUF - 1 < b1) issue_block(b + NBUF - 1);     // into the slot block b - 1 left
+        if (BF16IN) {
+            if (b + 2 < b1) fetch(b + 2);                                // in flight for a whole iteration
+        } else if (loader && b + NBUF - 1 < b1) {
+            issue_block(b + NBUF - 1);                                  // into the slot block b - 1 left
+        }
 
         // Per-lane offsets are recomputed from an opaque copy of the lane id in every block: derived from a
         // loop-invariant value the compiler would keep dozens of addresses in registers, which W needs.
@@ -525,19 +627,36 @@ struct WregInst {
     int wnc, ks, rb;
     const void* fn;      // bf16 output
     const void* fn_q;    // e4m3 output
+    const void* fn_b;    // bf16 input, quantized in the kernel
     size_t lds;
     void (*launch)(const GemmParams&, int, dim3, hipStream_t);
 };
 
+// Fused quantization is built where the registers allow it: the configurations whose W fragments already fill 128
+// registers per lane (K * N = 256 KB) have no room for a block of raw bf16 beside them (the compiler spills hundreds
+// of registers per lane).
+template <int WNC, int KS, int RT>
+constexpr bool kWregFused = WNC * KS < 512;
+
 template <int WNC, int KS, int RT>
 void launch_wreg(const GemmParams& p, int bpp, dim3 grid, hipStream_t s) {
-    if (p.outq) gemm_wreg_kernel<WNC, KS, RT, true><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);
-    else gemm_wreg_kernel<WNC, KS, RT, false><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);
+    if (p.xb) {
+        if constexpr (kWregFused<WNC, KS, RT>)
+            gemm_wreg_kernel<WNC, KS, RT, false, true><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);
+    } else if (p.outq) gemm_wreg_kernel<WNC, KS, RT, true, false><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);
+    else gemm_wreg_kernel<WNC, KS, RT, false, false><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);
+}
+
+template <int WNC, int KS, int RT>
+const void* wreg_fused_fn() {
+    if constexpr (kWregFused<WNC, KS, RT>) return reinterpret_cast<const void*>(&gemm_wreg_kernel<WNC, KS, RT, false, true>);
+    else return nullptr;
 }
 
 #define LOKA_WREG(WNC, KS, RT)                                                                                   \
-    {WNC, KS, 32 * RT, reinterpret_cast<const void*>(&gemm_wreg_kernel<WNC, KS, RT, false>),                      \
-     reinterpret_cast<const void*>(&gemm_wreg_kernel<WNC, KS, RT, true>), WregCfg<WNC, KS, RT>::LDS,              \
+    {WNC, KS, 32 * RT, reinterpret_cast<const void*>(&gemm_wreg_kernel<WNC, KS, RT, false, false>),               \
+     reinterpret_cast<const void*>(&gemm_wreg_kernel<WNC, KS, RT, true, false>),                                  \
+     wreg_fused_fn<WNC, KS, RT>(), WregCfg<WNC, KS, RT>::LDS,                                                     \
      &launch_wreg<WNC, KS, RT>}
 
 // columns per wave, K / 64, row tiles per block (as many as registers and LDS allow: fewer, longer iterations)
@@ -558,15 +677,21 @@ const WregInst* wreg_pick(int64_t N, int64_t K) {
 
 }  // namespace
 
+bool wreg_supports_fused(int64_t M, int64_t N, int64_t K) {
+    const WregInst* w = wreg_pick(N, K);
+    return w != nullptr && w->fn_b != nullptr && M * K < (int64_t(1) << 31);
+}
+
 bool wreg_supports(int64_t M, int64_t N, int64_t K) {
     return wreg_pick(N, K) != nullptr && M * K < (int64_t(1) << 31) && M * 4 < (int64_t(1) << 31);
 }
 
 // Workgroups to launch and the kernel's entry (for the dynamic-LDS attribute); 0 when unsupported.
-int wreg_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool fp8_out, const void** fn, size_t* lds) {
+int wreg_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool fp8_out, bool bf16_in, const void** fn,
+              size_t* lds) {
     const WregInst* w = wreg_pick(N, K);
     if (!w) return 0;
-    *fn = fp8_out ? w->fn_q : w->fn;
+    *fn = bf16_in ? w->fn_b : fp8_out ? w->fn_q : w->fn;
     *lds = w->lds;
     const int64_t blocks = batch * ((M + w->rb - 1) / w->rb);
     return static_cast<int>(blocks < cus ? blocks : cus);

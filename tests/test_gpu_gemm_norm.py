@@ -499,3 +499,51 @@ def test_bounded_wait_is_reported(monkeypatch):
     # variants without a cross-workgroup wait have nothing to report
     row = B.make_desc(256, 128, 128, variant=B.variant_id("row64x128"))
     assert B.loka_fp8_gemm_norm_check(row, None) == B.LOKA_OK
+
+
+# ----------------------------------------------------------------------------- quantization fused into the layer
+@pytest.mark.parametrize("case", [(300, 256, 256, 1, "rmsnorm"), (1000, 128, 256, 1, "layernorm"), (77, 512, 256, 1, "layernorm"),
+                                  (513, 256, 512, 1, "rmsnorm"), (260, 128, 1024, 1, "layernorm"), (640, 256, 256, 5, "rmsnorm"),
+                                  (130, 128, 512, 3, "none")])
+def test_fused_quantization_gives_the_bits_of_the_two_calls(orc, case):
+    # loka_fp8_linear_norm = loka_quantize(ROW) + loka_fp8_gemm_norm in one kernel: scales, fp32 Y and bf16 O must be
+    # identical bit for bit (same codes, same kernel arithmetic); the two-call path is checked against the oracle above,
+    # and the scales here against the oracle directly
+    M, K, N, G, norm = case
+    x = torch.cat([synth.student_t4(M, K, 50 + g) for g in range(G)], 0)
+    w = torch.cat([synth.weight(K, N, 60 + g) for g in range(G)], 0)
+    gamma, beta = synth.affine(N, 9)
+    xd, wd = x.to(DEV), w.to(DEV)
+    wq = torch.empty(G * N, K, dtype=torch.uint8, device=DEV)
+    sw = torch.empty(G * N, dtype=torch.float32, device=DEV)
+    for g in range(G):
+        q, s_ = B.loka_quantize(wd[g * K:(g + 1) * K], B.SCALE_COL, transpose_out=True)
+        wq[g * N:(g + 1) * N] = q
+        sw[g * N:(g + 1) * N] = s_
+    desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORMS[norm], 1e-5, variant=B.variant_id("wreg32"))
+    xq, sx = B.loka_quantize(xd, B.SCALE_ROW)
+    o2, y2 = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, gamma.to(DEV), beta.to(DEV), want_y=True)
+    o1, y1, sx1 = B.loka_fp8_linear_norm(desc, xd, wq, sw, gamma.to(DEV), beta.to(DEV), want_y=True, want_sx=True)
+    torch.cuda.synchronize()
+    _, sx_o = orc.quantize(synth.bf16_bits(x), orc.SCALE_ROW)
+    assert np.array_equal(sx1.cpu().numpy().view(np.uint32), sx_o.view(np.uint32)), "row scales differ from the oracle's"
+    assert torch.equal(sx1, sx)
+    assert torch.equal(y1, y2), "fp32 Y differs from the two-call path"
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)), "bf16 O differs from the two-call path"
+
+
+def test_fused_quantization_unsupported_shapes():
+    # the configurations whose weights fill the register file, and everything the streaming kernel does not cover
+    for M, K, N in [(4096, 512, 512), (4096, 256, 1024), (4096, 1024, 256), (4096, 4096, 4096)]:
+        desc = B.make_desc(M, N, K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, 1e-5)
+        x = torch.zeros(M, K, dtype=torch.bfloat16, device=DEV)
+        wq = torch.zeros(N, K, dtype=torch.uint8, device=DEV)
+        sw = torch.ones(N, dtype=torch.float32, device=DEV)
+        with pytest.raises(B.LokaError) as e:
+            B.loka_fp8_linear_norm(desc, x, wq, sw)
+        assert e.value.status == B.LOKA_ERR_UNSUPPORTED
+    tens = B.make_desc(256, 256, 256, 1, B.SCALE_TENSOR, B.SCALE_TENSOR, B.NORM_LAYERNORM, 1e-5)
+    with pytest.raises(B.LokaError) as e:
+        B.loka_fp8_linear_norm(tens, torch.zeros(256, 256, dtype=torch.bfloat16, device=DEV),
+                               torch.zeros(256, 256, dtype=torch.uint8, device=DEV), torch.ones(1, device=DEV))
+    assert e.value.status == B.LOKA_ERR_UNSUPPORTED
