@@ -709,6 +709,13 @@ void wreg_launch(const GemmParams& p, dim3 grid, hipStream_t s);
 static void launch_wreg_any(const GemmParams& p, bool, dim3 grid, hipStream_t s) { wreg_launch(p, grid, s); }
 static const char kWregName[] = "wreg32";
 
+// gemm_strip.hip
+bool strip_supports(int64_t M, int64_t N, int64_t K);
+int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, const void** fn, size_t* lds);
+void strip_launch(const GemmParams& p, dim3 grid, hipStream_t s);
+static void launch_strip_any(const GemmParams& p, bool, dim3 grid, hipStream_t s) { strip_launch(p, grid, s); }
+static const char kStripName[] = "strip32";
+
 // gemm_panel32.hip
 const void* panel32_fn(bool blockwise);
 size_t panel32_lds();
@@ -732,6 +739,9 @@ static const VariantInfo kVariants[] = {
     // skinny layers (K * N <= 256 KB, non-blockwise scales): W resident in registers, X streamed in 32-row
     // blocks; one of several instantiations behind one name, workgroup count and LDS decided at launch
     {kWregName, 32, 1024, 512, EPI_ROW_IN_TILE, 0, &launch_wreg_any, nullptr, nullptr},
+    // small layers (K * N <= 64 KB, N <= 256, non-blockwise scales): W resident in LDS, one 32-row strip per wave,
+    // no synchronization between the waves of a workgroup; workgroup count and LDS decided at launch
+    {kStripName, 32, 256, 512, EPI_ROW_IN_TILE, 0, &launch_strip_any, nullptr, nullptr},
     // rows spanning several workgroups: Y + per-tile statistics, then a normalization pass
     LOKA_VARIANT("twopass128x128", 128, 128, 1, 2, 2, EPI_PARTIAL_STATS),
     LOKA_VARIANT("twopass256x256", 256, 256, 1, 2, 2, EPI_PARTIAL_STATS),
@@ -761,6 +771,7 @@ int variant_streaming_id() {
     return -1;
 }
 bool variant_is_streaming(int v) { return kVariants[v].name == kWregName; }
+bool variant_is_strip(int v) { return kVariants[v].name == kStripName; }
 int variant_bn(int v) { return kVariants[v].bn; }
 int variant_bm(int v) { return kVariants[v].bm; }
 
@@ -768,6 +779,8 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
     if (v < 0 || v >= kNumVariants) return false;
     const VariantInfo& vi = kVariants[v];
     if (vi.name == kWregName) return d->x_mode != LOKA_SCALE_BLOCK_1x128 && wreg_supports(d->M, d->N, d->K);
+    if (vi.name == kStripName)
+        return d->x_mode != LOKA_SCALE_BLOCK_1x128 && d->norm != LOKA_NORM_BLOCKNORM && strip_supports(d->M, d->N, d->K);
     // BlockNorm (groups of 256 columns) is built into the kernels whose tile is 256 columns wide
     if (d->norm == LOKA_NORM_BLOCKNORM && vi.launch != &launch_panel32) return false;
     if ((d->x_mode == LOKA_SCALE_BLOCK_1x128 ? vi.fn_block : vi.fn_plain) == nullptr) return false;
@@ -872,6 +885,18 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         LOKA_HIP_TRY(hipGetDevice(&dev));
         LOKA_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         const int wgs = wreg_plan(d->M, d->N, d->K, d->batch, cus, p.outq != nullptr, p.xb != nullptr, &fn, &lds);
+        if (wgs <= 0) return LOKA_ERR_UNSUPPORTED;
+        if (set_lds(fn, lds) != LOKA_OK) return LOKA_ERR_HIP;
+        vi.launch(p, false, dim3(static_cast<unsigned>(wgs)), s);
+        return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
+    }
+    if (vi.name == kStripName) {
+        int dev = 0, cus = 0;
+        const void* fn = nullptr;
+        size_t lds = 0;
+        LOKA_HIP_TRY(hipGetDevice(&dev));
+        LOKA_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        const int wgs = strip_plan(d->M, d->N, d->K, d->batch, cus, &fn, &lds);
         if (wgs <= 0) return LOKA_ERR_UNSUPPORTED;
         if (set_lds(fn, lds) != LOKA_OK) return LOKA_ERR_HIP;
         vi.launch(p, false, dim3(static_cast<unsigned>(wgs)), s);

@@ -1,0 +1,324 @@
+// Small-layer FP8 GEMM with the row norm fused, one row strip per WAVE: W in LDS, X straight into registers.
+//
+// For the many small GEMMs of a recommendation model (Section 2.1; K * N <= 64 KB: 256 x 256, 128 x 512, ...)
+// a whole output row fits the accumulators of ONE wave: a wave takes 32 rows of X, multiplies them with all of
+// W (resident in LDS for the whole problem, read fragment by fragment), and scales, normalizes and stores its
+// 32 x N outputs from registers.  The row statistics need two lanes (l, l ^ 32) and no other wave, so after the
+// weights are in place the 8 waves of a workgroup never synchronize: each runs load -> MFMA -> normalize -> store
+// at its own pace, and the phases of different waves overlap on the CU.  (The streaming kernel for skinny
+// layers splits the row over its 8 waves and runs those phases one after the other behind workgroup barriers;
+// measured at 64 x (4096 x 256 x 256) it needs 7.4 us per 128 rows against 3.1 us of HBM time.)
+//
+// X does not pass through LDS: the MFMA operand of a lane is 32 consecutive K bytes of one row, which two
+// 16-byte loads fetch directly (two lanes cover a 64-byte run of the row); the next strip's operands are
+// requested before the current strip is multiplied.  Roles and the W row permutation are those of the other
+// 32 x 32 x 64 kernels: W rows -> MFMA rows, X rows -> MFMA columns, so a lane ends with 16 consecutive output
+// columns per column block of one output row (= lane % 32).
+#include "gemm_common.h"
+
+namespace loka {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+#ifndef STRIP_NT
+#define STRIP_STORE(v, ptr) (*(ptr) = (v))
+#else
+#define STRIP_STORE(v, ptr) __builtin_nontemporal_store((v), (ptr))
+#endif
+
+template <int NB, int KS>
+struct StripCfg {
+    static constexpr int NT = NB * 32;                    // columns the accumulators cover
+    static constexpr int KB = KS * 64;                    // bytes per row of X / W
+    static constexpr int SWIN = KB / 16 < 16 ? KB / 16 : 16;
+    static constexpr int OFF_W = 0;                       // [NT][KB], 16-byte chunk c of row r at c ^ (r % SWIN)
+    static constexpr int OFF_SW = NT * KB;                // [NT] fp32 column scales (0 beyond N)
+    static constexpr int OFF_GM = OFF_SW + NT * 4;        // [NT] fp32 gamma (1 when absent)
+    static constexpr int OFF_BT = OFF_GM + NT * 4;        // [NT] fp32 beta (0 when absent)
+    static constexpr int OFF_T = OFF_BT + NT * 4;         // [8 waves][2 KB] output staging (see the epilogue)
+    static constexpr int LDS = OFF_T + 8 * 2048;
+    static_assert(NT * KB <= 65536, "W must fit its LDS area");
+};
+
+template <int NB, int KS>
+__global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, const int strips_per_problem) {
+    using C = StripCfg<NB, KS>;
+    constexpr int NT = C::NT, KB = C::KB, KEYMASK = C::SWIN - 1;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, hk = lane >> 5;
+    const bool ln = p.norm == LOKA_NORM_LAYERNORM;
+    const bool tensor_x = p.x_mode == LOKA_SCALE_TENSOR, tensor_w = p.w_mode == LOKA_SCALE_TENSOR;
+    const float inv_n = 1.0f / static_cast<float>(p.N);
+
+    float cnt_lane = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+        if (nb * 32 + hk * 16 < p.N) cnt_lane += 16.f;     // N % 16 == 0: a run of 16 columns is all in or all out
+
+    // contiguous range of strips of this workgroup (strip = 32 rows of one problem)
+    const int64_t total = static_cast<int64_t>(p.batch) * strips_per_problem;
+    int t = static_cast<int>(total * blockIdx.x / gridDim.x);
+    const int t1 = static_cast<int>(total * (blockIdx.x + 1) / gridDim.x);
+
+    while (t < t1) {
+        const int g = t / strips_per_problem;
+        const int seg_end = (g + 1) * strips_per_problem < t1 ? (g + 1) * strips_per_problem : t1;
+
+        // ---- weights and tables of problem g
+        __syncthreads();                                    // every wave has finished with the previous problem's W
+        {
+            const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<uint8_t*>(p.W + static_cast<int64_t>(g) * p.strideW), 0, p.N * KB, 0x00020000);
+            for (int ld = wave; ld < NT * KB / 1024; ld += 8) {
+                const int byte = ld * 1024 + lane * 16;
+                const int row = byte / KB, pos = (byte % KB) >> 4;
+                // rows past N lie behind the descriptor's bound (the offset is the per-lane one) and read as zeros
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void*)(smem + C::OFF_W + ld * 1024),
+                                                         16, row * KB + ((pos ^ (row & KEYMASK)) << 4), 0, 0, 0);
+            }
+            const float* swg = p.sw + static_cast<int64_t>(g) * p.strideSw;
+            float* swl = reinterpret_cast<float*>(smem + C::OFF_SW);
+            float* gml = reinterpret_cast<float*>(smem + C::OFF_GM);
+            float* btl = reinterpret_cast<float*>(smem + C::OFF_BT);
+            for (int n = threadIdx.x; n < NT; n += 512) {
+                const bool in = n < p.N;
+                swl[n] = in ? (tensor_w ? swg[0] : swg[n]) : 0.f;
+                gml[n] = (in && p.gamma && p.norm != LOKA_NORM_NONE) ? bf16_bits_to_f32(p.gamma[n]) : 1.f;
+                btl[n] = (in && p.beta && ln) ? bf16_bits_to_f32(p.beta[n]) : 0.f;
+            }
+            wait_vmcnt<0>();
+            __syncthreads();
+        }
+
+        const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t*>(p.X + static_cast<int64_t>(g) * p.strideX), 0, static_cast<unsigned>(p.M) * KB, 0x00020000);
+        const float* sxg = p.sx + static_cast<int64_t>(g) * p.strideSx;
+        const int s_base = g * strips_per_problem;
+
+        // operands of strip s: row m0 + l32, K bytes [64 j + 32 hk, +32) per K step (rows past M read as zeros)
+        auto load_x = [&](int s, v8i (&x)[KS], float& sxm) __attribute__((always_inline)) {
+            const int m = (s - s_base) * 32 + l32;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                const unsigned off = static_cast<unsigned>(m) * KB + static_cast<unsigned>((4 * j + 2 * hk) * 16);
+                const v4i lo = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(xr, off, 0, 0));
+                const v4i hi = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(xr, off + 16u, 0, 0));
+                x[j] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            }
+            sxm = tensor_x ? sxg[0] : (m < p.M ? sxg[m] : 0.f);
+        };
+
+        // one strip: MFMAs on the operands in x, then (x is dead) the request for the wave's next strip into the
+        // same registers, which arrive while this strip is scaled, normalized and stored
+        auto compute = [&](int s, v8i (&x)[KS], float& sx_io, int s_next) __attribute__((always_inline)) {
+            const float sxm = sx_io;
+            // Lane-derived LDS addresses restart from an opaque copy of the lane id in every strip: W and the
+            // tables do not change between strips, and derived from loop invariants their reads would be hoisted
+            // out of the strip loop into hundreds of registers.
+            int lane_o = lane;
+            asm volatile("; per-strip lane id" : "+v"(lane_o));
+            const int l32 = lane_o & 31, hk = lane_o >> 5;
+            const int m = (s - s_base) * 32 + l32;
+            // W fragment addresses: MFMA row rho of a 32-row block is fed W row wperm(rho) (see the file comment);
+            // 32 nb rows further down for column block nb (which does not change the swizzle key: SWIN <= 16)
+            const int wperm = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
+            const int wkey = wperm & KEYMASK;
+            v16f acc[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
+            // W fragments are read PF MFMAs ahead of their use (an LDS round trip is several MFMAs long)
+            const uint8_t* wbase = smem + C::OFF_W + wperm * KB;
+            constexpr int NF = NB * KS, PF = 4;
+            v8i wf[PF];
+            auto read_w = [&](int f) __attribute__((always_inline)) {           // f = j * NB + nb
+                const int j = f / NB, nb = f % NB;
+                const v4i lo = *reinterpret_cast<const v4i*>(wbase + nb * 32 * KB + (((4 * j + 2 * hk) ^ wkey) << 4));
+                const v4i hi = *reinterpret_cast<const v4i*>(wbase + nb * 32 * KB + (((4 * j + 2 * hk + 1) ^ wkey) << 4));
+                wf[f % PF] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            };
+#pragma unroll
+            for (int f = 0; f < PF - 1 && f < NF; ++f) read_w(f);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (f + PF - 1 < NF) read_w(f + PF - 1);
+                acc[f % NB] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf[f % PF], x[f / NB], acc[f % NB], 0, 0, 0, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (s_next >= 0) load_x(s_next, x, sx_io);
+            __builtin_amdgcn_sched_barrier(0);
+
+            // ---- scales: Y = acc * sx[m] * sw[n]
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const v4f* sw4 = reinterpret_cast<const v4f*>(smem + C::OFF_SW + (nb * 32 + hk * 16) * 4);
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const v4f sc = sw4[a];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[nb][4 * a + e] *= sc[e] * sxm;
+                }
+            }
+            if (p.y && m < p.M) {
+                float* yrow = p.y + static_cast<int64_t>(g) * p.strideO + static_cast<int64_t>(m) * p.N;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    if (nb * 32 + hk * 16 < p.N) {
+#pragma unroll
+                        for (int a = 0; a < 4; ++a)
+                            *reinterpret_cast<v4f*>(yrow + nb * 32 + hk * 16 + 4 * a) =
+                                v4f{acc[nb][4 * a], acc[nb][4 * a + 1], acc[nb][4 * a + 2], acc[nb][4 * a + 3]};
+                    }
+            }
+
+            // ---- row statistics: this lane's columns, then the lane that holds the row's other columns
+            float mean = 0.f, rstd = 1.f;
+            if (p.norm != LOKA_NORM_NONE) {
+                float m2 = 0.f;
+                if (ln) {
+                    float n_ = cnt_lane, sum = 0.f;
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        if (nb * 32 + hk * 16 < p.N) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) sum += acc[nb][i];
+                        }
+                    mean = n_ > 0.f ? sum * __builtin_amdgcn_rcpf(n_) : 0.f;
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        if (nb * 32 + hk * 16 < p.N) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) { const float d = acc[nb][i] - mean; m2 = __builtin_fmaf(d, d, m2); }
+                        }
+                    // symmetric Chan merge: identical bits on both lanes
+                    const float nb_ = wave_shfl_xor(n_, 32), mb = wave_shfl_xor(mean, 32), m2b = wave_shfl_xor(m2, 32);
+                    const float nn = n_ + nb_;
+                    if (nn > 0.f) {
+                        const float d = mb - mean;
+                        const float rn = __builtin_amdgcn_rcpf(nn);
+                        const float newmean = (n_ * mean + nb_ * mb) * rn;
+                        m2 = m2 + m2b + d * d * (n_ * nb_ * rn);
+                        mean = newmean;
+                    }
+                } else {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        if (nb * 32 + hk * 16 < p.N) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) m2 = __builtin_fmaf(acc[nb][i], acc[nb][i], m2);
+                        }
+                    m2 += wave_shfl_xor(m2, 32);
+                }
+                rstd = __builtin_amdgcn_rsqf(m2 * inv_n + p.eps);
+            }
+            const float nmr = -mean * rstd;
+
+            // ---- normalize, affine, bf16.  A lane holds 16 consecutive columns (32 bytes) of ONE row per column
+            // block; stored from there an instruction writes 16-byte pieces 32 bytes apart in 32 rows.  Each wave
+            // instead passes the 32 x 64-byte block through 2 KB of its own LDS (16-byte chunk c of row r at
+            // position c ^ (r / 4 % 4): conflict-free both ways) and stores it with 4 lanes per row: 16 full 64-byte
+            // runs per instruction.  LDS executes one wave's instructions in order: no barrier, one buffer.
+            uint8_t* const tbuf = smem + C::OFF_T + wave * 2048;
+            const int t_wr = l32 * 64, t_key = (l32 >> 2) & 3;
+            const int t_row = lane_o >> 2, t_c = lane_o & 3;                   // store side: row (+ 16 j), chunk
+            uint16_t* const obase = p.out + static_cast<int64_t>(g) * p.strideO + static_cast<int64_t>((s - s_base) * 32) * p.N;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int col = nb * 32 + hk * 16;
+                const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + col * 4);
+                const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + col * 4);
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
+                    float o[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        o[e] = __builtin_fmaf(__builtin_fmaf(acc[nb][8 * half + e], rstd, nmr), gq0[e], bq0[e]);
+                        o[4 + e] = __builtin_fmaf(__builtin_fmaf(acc[nb][8 * half + 4 + e], rstd, nmr), gq1[e], bq1[e]);
+                    }
+                    u32x4 pk;
+                    pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
+                    pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
+                    *reinterpret_cast<u32x4*>(tbuf + t_wr + (((2 * hk + half) ^ t_key) << 4)) = pk;
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int r = 16 * j + t_row;
+                    const u32x4 pk = *reinterpret_cast<const u32x4*>(tbuf + r * 64 + ((t_c ^ ((r >> 2) & 3)) << 4));
+                    const int ccol = nb * 32 + t_c * 8;
+                    if ((s - s_base) * 32 + r < p.M && ccol < p.N)
+                        STRIP_STORE(pk, reinterpret_cast<u32x4*>(obase + static_cast<int64_t>(r) * p.N + ccol));
+                }
+            }
+        };
+
+        // ---- this wave's strips of the segment
+        v8i x[KS];
+        float sxm = 0.f;
+        int s = t + wave;
+        if (s < seg_end) load_x(s, x, sxm);
+        while (s < seg_end) {
+            const int s_next = s + 8 < seg_end ? s + 8 : -1;
+            compute(s, x, sxm, s_next);
+            s += 8;
+        }
+        t = seg_end;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------- host side
+namespace {
+
+struct StripInst {
+    int nb, ks;
+    const void* fn;
+    size_t lds;
+    void (*launch)(const GemmParams&, int, dim3, hipStream_t);
+};
+
+template <int NB, int KS>
+void launch_strip(const GemmParams& p, int spp, dim3 grid, hipStream_t s) {
+    gemm_strip_kernel<NB, KS><<<grid, 512, StripCfg<NB, KS>::LDS, s>>>(p, spp);
+}
+
+#define LOKA_STRIP(NB, KS) \
+    {NB, KS, reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS>), StripCfg<NB, KS>::LDS, &launch_strip<NB, KS>}
+
+const StripInst kStrip[] = {LOKA_STRIP(4, 2), LOKA_STRIP(4, 4), LOKA_STRIP(4, 8), LOKA_STRIP(8, 2), LOKA_STRIP(8, 4)};
+
+const StripInst* strip_pick(int64_t N, int64_t K) {
+    if (K % 64 || N > 256) return nullptr;
+    const int ks = static_cast<int>(K / 64), nb = N <= 128 ? 4 : 8;
+    for (const StripInst& w : kStrip)
+        if (w.nb == nb && w.ks == ks) return &w;
+    return nullptr;
+}
+
+}  // namespace
+
+bool strip_supports(int64_t M, int64_t N, int64_t K) {
+    return strip_pick(N, K) != nullptr && M * K < (int64_t(1) << 31) && M < (int64_t(1) << 26);
+}
+
+// Workgroups to launch and the kernel's entry (for the dynamic-LDS attribute); 0 when unsupported.
+int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, const void** fn, size_t* lds) {
+    const StripInst* w = strip_pick(N, K);
+    if (!w) return 0;
+    *fn = w->fn;
+    *lds = w->lds;
+    const int64_t strips = batch * ((M + 31) / 32);
+    const int64_t wgs = (strips + 7) / 8;                   // at least one strip per wave
+    return static_cast<int>(wgs < cus ? wgs : cus);
+}
+
+void strip_launch(const GemmParams& p, dim3 grid, hipStream_t s) {
+    const StripInst* w = strip_pick(p.N, p.KB);
+    w->launch(p, (p.M + 31) / 32, grid, s);
+}
+
+}  // namespace loka

@@ -175,7 +175,8 @@ def test_c3_skinny_pair_chained(orc):
     print("C3b", r)
 
 
-def test_c4_grouped_launch(orc):
+@pytest.mark.parametrize("variant", [None, "strip32", "wreg32"])
+def test_c4_grouped_launch(orc, variant):
     w = synth.WORKLOADS["C4"]
     G = w.batch
     xs = torch.cat([synth.activations(w, g) for g in range(G)], 0)          # [G*M, K]
@@ -188,7 +189,8 @@ def test_c4_grouped_launch(orc):
         q, s = B.loka_quantize(wd[g * w.K:(g + 1) * w.K], B.SCALE_COL, transpose_out=True)
         wq[g * w.N:(g + 1) * w.N] = q
         sw[g * w.N:(g + 1) * w.N] = s
-    desc = B.make_desc(w.M, w.N, w.K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM)
+    desc = B.make_desc(w.M, w.N, w.K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM,
+                       variant=-1 if variant is None else B.variant_id(variant))
     out, y = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, want_y=True)
     torch.cuda.synchronize()
     for g in (0, 1, 31, 63):
@@ -208,7 +210,7 @@ def test_c4_grouped_launch(orc):
         assert ok, f"group {g}: worst {worst} ulps"
     # a single weight shared by all groups (strideW = 0) must equal group 0's weight applied to every group
     # (same kernel variant for both launches: the order of the row-statistics sums differs between variants)
-    v = B.loka_default_variant(desc)
+    v = B.loka_default_variant(desc) if variant is None else B.variant_id(variant)
     desc0 = B.make_desc(w.M, w.N, w.K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM, variant=v, shared_w=True)
     out_s, _ = B.loka_fp8_gemm_norm(desc0, xq, sx, wq[:w.N], sw[:w.N])
     d1 = B.make_desc(w.M, w.N, w.K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM, variant=v)
@@ -216,11 +218,12 @@ def test_c4_grouped_launch(orc):
     assert torch.equal(out_s[5 * w.M:6 * w.M].view(torch.int16), out_1.view(torch.int16))
 
 
-def test_streaming_variant_crosses_problem_boundaries(orc):
+@pytest.mark.parametrize("variant", ["wreg32", "strip32"])
+def test_streaming_variant_crosses_problem_boundaries(orc, variant):
     # 300 small problems with their own weights: with one row block per problem and fewer workgroups than
     # blocks, some workgroups walk from one problem into the next and must reload W and re-request X
     G, M, K, N = 300, 64, 256, 256
-    v = B.variant_id("wreg32")
+    v = B.variant_id(variant)
     xs = torch.cat([synth.normal(M, K, seed=1000 + g) for g in range(G)], 0)
     ws = torch.cat([synth.weight(K, N, seed=5000 + g) for g in range(G)], 0)
     gamma, beta = synth.affine(N, seed=11)
