@@ -78,7 +78,7 @@ int default_variant(const loka_gemm_desc* d) {
         for (int v = variant_count() - 1; v >= 0; --v)
             if (variant_supports(d, v) && variant_epilogue(v) == 2) return v;
     }
-    // small layers (K * N <= 64 KB, N <= 256) with enough rows: W in LDS, one row strip per wave (measured against
+    // small layers (K * N <= 128 KB, N <= 256) with enough rows: W in LDS, one row strip per wave (measured against
     // the streaming kernel: 64 x (4096 x 256 x 256) 42.5 against 63 us, 65536 x 256 x 128 10.9 against 19.4 us,
     // 65536 x 128 x 256 15.7 against 19.7 us, 65536 x 512 x 128 13.1 against 21.6 us)
     if (d->M * d->batch >= 8192) {

@@ -739,7 +739,7 @@ static const VariantInfo kVariants[] = {
     // skinny layers (K * N <= 256 KB, non-blockwise scales): W resident in registers, X streamed in 32-row
     // blocks; one of several instantiations behind one name, workgroup count and LDS decided at launch
     {kWregName, 32, 1024, 512, EPI_ROW_IN_TILE, 0, &launch_wreg_any, nullptr, nullptr},
-    // small layers (K * N <= 64 KB, N <= 256, non-blockwise scales): W resident in LDS, one 32-row strip per wave,
+    // small layers (K * N <= 128 KB, N <= 256, non-blockwise scales): W resident in LDS, one 32-row strip per wave,
     // no synchronization between the waves of a workgroup; workgroup count and LDS decided at launch
     {kStripName, 32, 256, 512, EPI_ROW_IN_TILE, 0, &launch_strip_any, nullptr, nullptr},
     // rows spanning several workgroups: Y + per-tile statistics, then a normalization pass

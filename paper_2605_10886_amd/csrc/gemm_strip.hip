@@ -1,6 +1,7 @@
 // Small-layer FP8 GEMM with the row norm fused, one row strip per WAVE: W in LDS, X straight into registers.
 //
-// For the many small GEMMs of a recommendation model (Section 2.1; K * N <= 64 KB: 256 x 256, 128 x 512, ...)
+// For the many small GEMMs of a recommendation model (Section 2.1; K * N <= 128 KB, N <= 256: 256 x 256, 512 x 256,
+// 1024 x 128, ...)
 // a whole output row fits the accumulators of ONE wave: a wave takes 32 rows of X, multiplies them with all of
 // W (resident in LDS for the whole problem, read fragment by fragment), and scales, normalizes and stores its
 // 32 x N outputs from registers.  The row statistics need two lanes (l, l ^ 32) and no other wave, so after the
@@ -37,7 +38,7 @@ struct StripCfg {
     static constexpr int OFF_BT = OFF_GM + NT * 4;        // [NT] fp32 beta (0 when absent)
     static constexpr int OFF_T = OFF_BT + NT * 4;         // [8 waves][2 KB] output staging (see the epilogue)
     static constexpr int LDS = OFF_T + 8 * 2048;
-    static_assert(NT * KB <= 65536, "W must fit its LDS area");
+    static_assert(LDS <= 160 * 1024, "W, the tables and the staging buffers must fit the LDS");
 };
 
 template <int NB, int KS>
@@ -289,7 +290,8 @@ void launch_strip(const GemmParams& p, int spp, dim3 grid, hipStream_t s) {
 #define LOKA_STRIP(NB, KS) \
     {NB, KS, reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS>), StripCfg<NB, KS>::LDS, &launch_strip<NB, KS>}
 
-const StripInst kStrip[] = {LOKA_STRIP(4, 2), LOKA_STRIP(4, 4), LOKA_STRIP(4, 8), LOKA_STRIP(8, 2), LOKA_STRIP(8, 4)};
+const StripInst kStrip[] = {LOKA_STRIP(4, 2), LOKA_STRIP(4, 4), LOKA_STRIP(4, 8), LOKA_STRIP(4, 16),
+                            LOKA_STRIP(8, 2), LOKA_STRIP(8, 4), LOKA_STRIP(8, 8)};
 
 const StripInst* strip_pick(int64_t N, int64_t K) {
     if (K % 64 || N > 256) return nullptr;

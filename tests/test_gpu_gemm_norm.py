@@ -96,7 +96,8 @@ def test_c1_every_variant(orc, recipe, norm):
         _run_case(orc, x, wt, recipe, norm, v, tag=f"C1 {recipe} {norm} {B.loka_variant_name(v)}")
 
 
-@pytest.mark.parametrize("shape", [(200, 128, 48), (77, 256, 240), (333, 384, 512), (130, 128, 1008), (64, 512, 2048)])
+@pytest.mark.parametrize("shape", [(200, 128, 48), (77, 256, 240), (333, 384, 512), (130, 128, 1008), (64, 512, 2048),
+                                   (100, 512, 256), (90, 1024, 112)])
 def test_ragged_tiles_every_variant(orc, shape):
     # M not a multiple of any tile height, N not a multiple of the tile width (but of 16), several K steps
     M, K, N = shape
