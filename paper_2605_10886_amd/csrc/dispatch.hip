@@ -81,7 +81,8 @@ int default_variant(const loka_gemm_desc* d) {
     // small layers (K * N <= 128 KB, N <= 256) with enough rows: W in LDS, one row strip per wave (measured against
     // the streaming kernel: 64 x (4096 x 256 x 256) 42.5 against 63 us, 65536 x 256 x 128 10.9 against 19.4 us,
     // 65536 x 128 x 256 15.7 against 19.7 us, 65536 x 512 x 128 13.1 against 21.6 us)
-    if (d->M * d->batch >= 8192) {
+    // (only where W fits the LDS in one piece: the variant that streams K slabs of W is left to the profiler)
+    if (d->M * d->batch >= 8192 && (d->N <= 128 ? 128 : 256) * d->K <= 131072) {
         for (int v = 0; v < variant_count(); ++v)
             if (variant_is_strip(v) && variant_supports(d, v)) return v;
     }

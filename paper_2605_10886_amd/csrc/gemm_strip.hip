@@ -27,10 +27,11 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 #define STRIP_STORE(v, ptr) __builtin_nontemporal_store((v), (ptr))
 #endif
 
-template <int NB, int KS>
+template <int NB, int KS, int NPH>
 struct StripCfg {
     static constexpr int NT = NB * 32;                    // columns the accumulators cover
-    static constexpr int KB = KS * 64;                    // bytes per row of X / W
+    static constexpr int KB = KS * 64;                    // K bytes per phase = bytes per row of the W slab in LDS
+    static constexpr int KBT = NPH * KB;                  // bytes per row of X / W in memory
     static constexpr int SWIN = KB / 16 < 16 ? KB / 16 : 16;
     static constexpr int OFF_W = 0;                       // [NT][KB], 16-byte chunk c of row r at c ^ (r % SWIN)
     static constexpr int OFF_SW = NT * KB;                // [NT] fp32 column scales (0 beyond N)
@@ -41,10 +42,10 @@ struct StripCfg {
     static_assert(LDS <= 160 * 1024, "W, the tables and the staging buffers must fit the LDS");
 };
 
-template <int NB, int KS>
+template <int NB, int KS, int NPH>
 __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, const int strips_per_problem) {
-    using C = StripCfg<NB, KS>;
-    constexpr int NT = C::NT, KB = C::KB, KEYMASK = C::SWIN - 1;
+    using C = StripCfg<NB, KS, NPH>;
+    constexpr int NT = C::NT, KB = C::KB, KBT = C::KBT, KEYMASK = C::SWIN - 1;
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
     const int lane = threadIdx.x & 63;
@@ -68,18 +69,20 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
         const int g = t / strips_per_problem;
         const int seg_end = (g + 1) * strips_per_problem < t1 ? (g + 1) * strips_per_problem : t1;
 
-        // ---- weights and tables of problem g
-        __syncthreads();                                    // every wave has finished with the previous problem's W
-        {
-            const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<uint8_t*>(p.W + static_cast<int64_t>(g) * p.strideW), 0, p.N * KB, 0x00020000);
+        // ---- tables of problem g; its weights (the K slab of phase ph) on request
+        __syncthreads();                                    // every wave has finished with the previous problem
+        const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t*>(p.W + static_cast<int64_t>(g) * p.strideW), 0, static_cast<unsigned>(p.N) * KBT, 0x00020000);
+        auto load_w = [&](int ph) __attribute__((always_inline)) {
             for (int ld = wave; ld < NT * KB / 1024; ld += 8) {
                 const int byte = ld * 1024 + lane * 16;
                 const int row = byte / KB, pos = (byte % KB) >> 4;
                 // rows past N lie behind the descriptor's bound (the offset is the per-lane one) and read as zeros
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void*)(smem + C::OFF_W + ld * 1024),
-                                                         16, row * KB + ((pos ^ (row & KEYMASK)) << 4), 0, 0, 0);
+                                                         16, row * KBT + ph * KB + ((pos ^ (row & KEYMASK)) << 4), 0, 0, 0);
             }
+        };
+        {
             const float* swg = p.sw + static_cast<int64_t>(g) * p.strideSw;
             float* swl = reinterpret_cast<float*>(smem + C::OFF_SW);
             float* gml = reinterpret_cast<float*>(smem + C::OFF_GM);
@@ -90,21 +93,25 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
                 gml[n] = (in && p.gamma && p.norm != LOKA_NORM_NONE) ? bf16_bits_to_f32(p.gamma[n]) : 1.f;
                 btl[n] = (in && p.beta && ln) ? bf16_bits_to_f32(p.beta[n]) : 0.f;
             }
+        }
+        if (NPH == 1) {
+            load_w(0);
             wait_vmcnt<0>();
             __syncthreads();
         }
 
         const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint8_t*>(p.X + static_cast<int64_t>(g) * p.strideX), 0, static_cast<unsigned>(p.M) * KB, 0x00020000);
+            const_cast<uint8_t*>(p.X + static_cast<int64_t>(g) * p.strideX), 0, static_cast<unsigned>(p.M) * KBT, 0x00020000);
         const float* sxg = p.sx + static_cast<int64_t>(g) * p.strideSx;
         const int s_base = g * strips_per_problem;
 
-        // operands of strip s: row m0 + l32, K bytes [64 j + 32 hk, +32) per K step (rows past M read as zeros)
-        auto load_x = [&](int s, v8i (&x)[KS], float& sxm) __attribute__((always_inline)) {
+        // operands of strip s, phase ph: row m0 + l32, K bytes [KB ph + 64 j + 32 hk, +32) per K step (rows past M
+        // read as zeros)
+        auto load_x = [&](int s, int ph, v8i (&x)[KS], float& sxm) __attribute__((always_inline)) {
             const int m = (s - s_base) * 32 + l32;
 #pragma unroll
             for (int j = 0; j < KS; ++j) {
-                const unsigned off = static_cast<unsigned>(m) * KB + static_cast<unsigned>((4 * j + 2 * hk) * 16);
+                const unsigned off = static_cast<unsigned>(m) * KBT + static_cast<unsigned>(ph * KB + (4 * j + 2 * hk) * 16);
                 const v4i lo = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(xr, off, 0, 0));
                 const v4i hi = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(xr, off + 16u, 0, 0));
                 x[j] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -112,26 +119,17 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
             sxm = tensor_x ? sxg[0] : (m < p.M ? sxg[m] : 0.f);
         };
 
-        // one strip: MFMAs on the operands in x, then (x is dead) the request for the wave's next strip into the
-        // same registers, which arrive while this strip is scaled, normalized and stored
-        auto compute = [&](int s, v8i (&x)[KS], float& sx_io, int s_next) __attribute__((always_inline)) {
-            const float sxm = sx_io;
-            // Lane-derived LDS addresses restart from an opaque copy of the lane id in every strip: W and the
-            // tables do not change between strips, and derived from loop invariants their reads would be hoisted
-            // out of the strip loop into hundreds of registers.
+        // MFMAs of one phase of a strip.  Lane-derived LDS addresses restart from an opaque copy of the lane id in
+        // every call: W and the tables do not change between strips, and derived from loop invariants their reads
+        // would be hoisted out of the strip loop into hundreds of registers.
+        auto mma = [&](const v8i (&x)[KS], v16f (&acc)[NB]) __attribute__((always_inline)) {
             int lane_o = lane;
             asm volatile("; per-strip lane id" : "+v"(lane_o));
             const int l32 = lane_o & 31, hk = lane_o >> 5;
-            const int m = (s - s_base) * 32 + l32;
             // W fragment addresses: MFMA row rho of a 32-row block is fed W row wperm(rho) (see the file comment);
             // 32 nb rows further down for column block nb (which does not change the swizzle key: SWIN <= 16)
             const int wperm = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
             const int wkey = wperm & KEYMASK;
-            v16f acc[NB];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
             // W fragments are read PF MFMAs ahead of their use (an LDS round trip is several MFMAs long)
             const uint8_t* wbase = smem + C::OFF_W + wperm * KB;
             constexpr int NF = NB * KS, PF = 4;
@@ -151,8 +149,14 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
                 acc[f % NB] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf[f % PF], x[f / NB], acc[f % NB], 0, 0, 0, 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            if (s_next >= 0) load_x(s_next, x, sx_io);
-            __builtin_amdgcn_sched_barrier(0);
+        };
+
+        // scales, row statistics, normalization and store of one strip, from registers
+        auto epilogue = [&](int s, const float sxm, v16f (&acc)[NB]) __attribute__((always_inline)) {
+            int lane_o = lane;
+            asm volatile("; per-strip lane id" : "+v"(lane_o));
+            const int l32 = lane_o & 31, hk = lane_o >> 5;
+            const int m = (s - s_base) * 32 + l32;
 
             // ---- scales: Y = acc * sx[m] * sw[n]
 #pragma unroll
@@ -261,12 +265,46 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
         // ---- this wave's strips of the segment
         v8i x[KS];
         float sxm = 0.f;
-        int s = t + wave;
-        if (s < seg_end) load_x(s, x, sxm);
-        while (s < seg_end) {
-            const int s_next = s + 8 < seg_end ? s + 8 : -1;
-            compute(s, x, sxm, s_next);
-            s += 8;
+        if (NPH == 1) {
+            // W is complete in LDS: the waves run on their own.  The next strip's operands are requested into the
+            // same registers right after the last MFMA (x is dead then) and arrive during the epilogue.
+            int s = t + wave;
+            if (s < seg_end) load_x(s, 0, x, sxm);
+            while (s < seg_end) {
+                v16f acc[NB];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
+                mma(x, acc);
+                const float sx_cur = sxm;
+                if (s + 8 < seg_end) load_x(s + 8, 0, x, sxm);
+                __builtin_amdgcn_sched_barrier(0);
+                epilogue(s, sx_cur, acc);
+                s += 8;
+            }
+        } else {
+            // W is longer than the LDS: rounds of 8 strips (one per wave), and per round NPH phases in which all
+            // waves multiply the same K slab of W; the epilogues still run unsynchronized
+            const int rounds = (seg_end - t + 7) / 8;
+            for (int r = 0; r < rounds; ++r) {
+                const int s = t + 8 * r + wave;
+                const bool active = s < seg_end;
+                v16f acc[NB];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
+                for (int ph = 0; ph < NPH; ++ph) {
+                    __syncthreads();                            // every wave has read the previous slab (and the tables are written)
+                    load_w(ph);
+                    if (active) load_x(s, ph, x, sxm);
+                    wait_vmcnt<0>();
+                    __syncthreads();
+                    if (active) mma(x, acc);
+                }
+                if (active) epilogue(s, sxm, acc);
+            }
         }
         t = seg_end;
     }
@@ -276,28 +314,30 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
 namespace {
 
 struct StripInst {
-    int nb, ks;
+    int nb, ks, nph;
     const void* fn;
     size_t lds;
     void (*launch)(const GemmParams&, int, dim3, hipStream_t);
 };
 
-template <int NB, int KS>
+template <int NB, int KS, int NPH>
 void launch_strip(const GemmParams& p, int spp, dim3 grid, hipStream_t s) {
-    gemm_strip_kernel<NB, KS><<<grid, 512, StripCfg<NB, KS>::LDS, s>>>(p, spp);
+    gemm_strip_kernel<NB, KS, NPH><<<grid, 512, StripCfg<NB, KS, NPH>::LDS, s>>>(p, spp);
 }
 
-#define LOKA_STRIP(NB, KS) \
-    {NB, KS, reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS>), StripCfg<NB, KS>::LDS, &launch_strip<NB, KS>}
+#define LOKA_STRIP(NB, KS, NPH)                                                                                     \
+    {NB, KS, NPH, reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS, NPH>), StripCfg<NB, KS, NPH>::LDS,        \
+     &launch_strip<NB, KS, NPH>}
 
-const StripInst kStrip[] = {LOKA_STRIP(4, 2), LOKA_STRIP(4, 4), LOKA_STRIP(4, 8), LOKA_STRIP(4, 16),
-                            LOKA_STRIP(8, 2), LOKA_STRIP(8, 4), LOKA_STRIP(8, 8)};
+// column blocks, K steps per phase, phases (K = 64 KS NPH; one phase when W fits the LDS)
+const StripInst kStrip[] = {LOKA_STRIP(4, 2, 1), LOKA_STRIP(4, 4, 1), LOKA_STRIP(4, 8, 1), LOKA_STRIP(4, 16, 1),
+                            LOKA_STRIP(8, 2, 1), LOKA_STRIP(8, 4, 1), LOKA_STRIP(8, 8, 1), LOKA_STRIP(8, 8, 2)};
 
 const StripInst* strip_pick(int64_t N, int64_t K) {
     if (K % 64 || N > 256) return nullptr;
     const int ks = static_cast<int>(K / 64), nb = N <= 128 ? 4 : 8;
     for (const StripInst& w : kStrip)
-        if (w.nb == nb && w.ks == ks) return &w;
+        if (w.nb == nb && w.ks * w.nph == ks) return &w;
     return nullptr;
 }
 

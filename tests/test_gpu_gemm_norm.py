@@ -97,7 +97,7 @@ def test_c1_every_variant(orc, recipe, norm):
 
 
 @pytest.mark.parametrize("shape", [(200, 128, 48), (77, 256, 240), (333, 384, 512), (130, 128, 1008), (64, 512, 2048),
-                                   (100, 512, 256), (90, 1024, 112)])
+                                   (100, 512, 256), (90, 1024, 112), (300, 1024, 240)])
 def test_ragged_tiles_every_variant(orc, shape):
     # M not a multiple of any tile height, N not a multiple of the tile width (but of 16), several K steps
     M, K, N = shape
