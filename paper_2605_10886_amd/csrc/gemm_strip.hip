@@ -17,6 +17,8 @@
 // columns per column block of one output row (= lane % 32).
 #include "gemm_common.h"
 
+#include <type_traits>
+
 namespace loka {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -54,6 +56,7 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
     const bool ln = p.norm == LOKA_NORM_LAYERNORM;
     const bool tensor_x = p.x_mode == LOKA_SCALE_TENSOR, tensor_w = p.w_mode == LOKA_SCALE_TENSOR;
     const float inv_n = 1.0f / static_cast<float>(p.N);
+    const bool affine = p.norm != LOKA_NORM_NONE && (p.gamma != nullptr || (p.beta != nullptr && ln));
 
     float cnt_lane = 0.f;
 #pragma unroll
@@ -232,34 +235,43 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
             const int t_wr = l32 * 64, t_key = (l32 >> 2) & 3;
             const int t_row = lane_o >> 2, t_c = lane_o & 3;                   // store side: row (+ 16 j), chunk
             uint16_t* const obase = p.out + static_cast<int64_t>(g) * p.strideO + static_cast<int64_t>((s - s_base) * 32) * p.N;
+            // (without gamma and beta the affine step is x * 1 + 0: skipped, same bits, no table reads)
+            auto normalize_store = [&](auto affine_tag) __attribute__((always_inline)) {
+                constexpr bool AFFINE = decltype(affine_tag)::value;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int col = nb * 32 + hk * 16;
-                const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + col * 4);
-                const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + col * 4);
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int col = nb * 32 + hk * 16;
+                    const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + col * 4);
+                    const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + col * 4);
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
-                    float o[8];
+                    for (int half = 0; half < 2; ++half) {
+                        float o[8];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        o[e] = __builtin_fmaf(__builtin_fmaf(acc[nb][8 * half + e], rstd, nmr), gq0[e], bq0[e]);
-                        o[4 + e] = __builtin_fmaf(__builtin_fmaf(acc[nb][8 * half + 4 + e], rstd, nmr), gq1[e], bq1[e]);
+                        for (int e = 0; e < 8; ++e) o[e] = __builtin_fmaf(acc[nb][8 * half + e], rstd, nmr);
+                        if (AFFINE) {
+                            const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                o[e] = __builtin_fmaf(o[e], gq0[e], bq0[e]);
+                                o[4 + e] = __builtin_fmaf(o[4 + e], gq1[e], bq1[e]);
+                            }
+                        }
+                        u32x4 pk;
+                        pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
+                        pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
+                        *reinterpret_cast<u32x4*>(tbuf + t_wr + (((2 * hk + half) ^ t_key) << 4)) = pk;
                     }
-                    u32x4 pk;
-                    pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
-                    pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
-                    *reinterpret_cast<u32x4*>(tbuf + t_wr + (((2 * hk + half) ^ t_key) << 4)) = pk;
-                }
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int r = 16 * j + t_row;
-                    const u32x4 pk = *reinterpret_cast<const u32x4*>(tbuf + r * 64 + ((t_c ^ ((r >> 2) & 3)) << 4));
-                    const int ccol = nb * 32 + t_c * 8;
-                    if ((s - s_base) * 32 + r < p.M && ccol < p.N)
-                        STRIP_STORE(pk, reinterpret_cast<u32x4*>(obase + static_cast<int64_t>(r) * p.N + ccol));
+                    for (int j = 0; j < 2; ++j) {
+                        const int r = 16 * j + t_row;
+                        const u32x4 pk = *reinterpret_cast<const u32x4*>(tbuf + r * 64 + ((t_c ^ ((r >> 2) & 3)) << 4));
+                        const int ccol = nb * 32 + t_c * 8;
+                        if ((s - s_base) * 32 + r < p.M && ccol < p.N)
+                            STRIP_STORE(pk, reinterpret_cast<u32x4*>(obase + static_cast<int64_t>(r) * p.N + ccol));
+                    }
                 }
-            }
+            };
+            if (affine) normalize_store(std::true_type{}); else normalize_store(std::false_type{});
         };
 
         // ---- this wave's strips of the segment
