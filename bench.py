@@ -206,6 +206,7 @@ def main():
     mu_t = torch.zeros(K, dtype=torch.float32, device=dev)
     sg_t = torch.zeros(K, K, dtype=torch.float32, device=dev)
     ws_t = torch.empty(max(16, L.loka_tracker_update_workspace(rows, K)), dtype=torch.uint8, device=dev)
+    B.loka_tracker_update(x, 0, mu_t, sg_t, ws_t)          # first launch (module load, function attributes) untimed
     t_trk = float(np.mean(_event_times(lambda: B.loka_tracker_update(x, 0, mu_t, sg_t, ws_t), 5, stream)))
     trk_flops = float(rows) * K * (K + 1)                 # symmetric scatter: K (K + 1) / 2 multiply-adds per row
 
