@@ -551,3 +551,37 @@ def test_fused_quantization_unsupported_shapes():
         B.loka_fp8_linear_norm(tens, torch.zeros(256, 256, dtype=torch.bfloat16, device=DEV),
                                torch.zeros(256, 256, dtype=torch.uint8, device=DEV), torch.ones(1, device=DEV))
     assert e.value.status == B.LOKA_ERR_UNSUPPORTED
+
+
+def test_fused_quantization_c4_full_size(orc):
+    # the grouped workload at full size: identical bits to the two calls on every row, and sampled rows of two
+    # groups against the oracle
+    w = synth.WORKLOADS["C4"]
+    G = w.batch
+    xs = torch.cat([synth.activations(w, g) for g in range(G)], 0)
+    ws = torch.cat([synth.weights(w, g) for g in range(G)], 0)
+    xd, wd = xs.to(DEV), ws.to(DEV)
+    wq = torch.empty(G * w.N, w.K, dtype=torch.uint8, device=DEV)
+    sw = torch.empty(G * w.N, dtype=torch.float32, device=DEV)
+    for g in range(G):
+        q, s_ = B.loka_quantize(wd[g * w.K:(g + 1) * w.K], B.SCALE_COL, transpose_out=True)
+        wq[g * w.N:(g + 1) * w.N] = q
+        sw[g * w.N:(g + 1) * w.N] = s_
+    desc = B.make_desc(w.M, w.N, w.K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM, variant=B.variant_id("wreg32"))
+    xq, sx = B.loka_quantize(xd, B.SCALE_ROW)
+    o2, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+    o1, y1, sx1 = B.loka_fp8_linear_norm(desc, xd, wq, sw, want_y=True, want_sx=True)
+    torch.cuda.synchronize()
+    assert torch.equal(sx1, sx) and torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+    for g in (0, 63):
+        rows = _sample_rows(w.M, 48)
+        xq_o, sx_o = orc.quantize(synth.bf16_bits(xs[g * w.M:(g + 1) * w.M])[rows].copy(), B.SCALE_ROW)
+        wq_o, sw_o = orc.quantize(synth.bf16_bits(ws[g * w.K:(g + 1) * w.K]), B.SCALE_COL, transpose_out=True)
+        y_o, absdot = orc.fp8_gemm(xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, want_absdot=True)
+        idx = torch.from_numpy(rows + g * w.M).to(DEV)
+        assert np.array_equal(sx1[idx].cpu().numpy().view(np.uint32), sx_o.view(np.uint32))
+        err = np.abs(y1[idx].cpu().numpy().astype(np.float64) - y_o)
+        assert (err <= gemm_tolerance(absdot, y_o, w.K)).all(), f"group {g}"
+        ok, worst, _ = check_bf16_out(to_np_bits(o1[idx]), orc.norm(y_o, B.NORM_RMSNORM),
+                                      abs_tol=propagated_abs_tol(y_o, err, B.NORM_RMSNORM, 1e-5))
+        assert ok, f"group {g}: worst {worst} ulps"
