@@ -21,6 +21,8 @@
 // MFMA columns, so a lane ends with 16 consecutive output columns of one output row (= lane % 32).
 #include "gemm_common.h"
 
+#include <type_traits>
+
 namespace loka {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -68,6 +70,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
     const float inv_n = 1.0f / static_cast<float>(p.N);
     const bool blocknorm = p.norm == LOKA_NORM_BLOCKNORM, hswish = p.act == LOKA_ACT_HARDSWISH;
     constexpr int WPG = 256 / WNC;          // waves per BlockNorm group of 256 columns
+    const bool affine = (p.gamma != nullptr && (ln || p.norm == LOKA_NORM_RMSNORM)) || (p.beta != nullptr && ln);
 
     // contiguous range of row blocks of this workgroup
     const int64_t total = static_cast<int64_t>(p.batch) * blocks_per_problem;
@@ -457,14 +460,20 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         LOKA_STAMP(4);
 
         // normalized (+ affine, + activation) values of 8 consecutive columns of row tile rt, as packed bf16
-        auto norm8 = [&](int rt, int ni, int half, const v4f gq0, const v4f gq1, const v4f bq0, const v4f bq1,
-                         const float rstd) __attribute__((always_inline)) {
+        // (without gamma and beta the affine step is x * 1 + 0: skipped, and its table reads with it)
+        auto norm8 = [&](auto affine_tag, int rt, int ni, int half, const v4f gq0, const v4f gq1, const v4f bq0,
+                         const v4f bq1, const float rstd) __attribute__((always_inline)) {
+            constexpr bool AFFINE = decltype(affine_tag)::value;
             const float nmr = -mean_r[rt] * rstd;
             float o[8];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                o[e] = __builtin_fmaf(__builtin_fmaf(acc[rt][ni][8 * half + e], rstd, nmr), gq0[e], bq0[e]);
-                o[4 + e] = __builtin_fmaf(__builtin_fmaf(acc[rt][ni][8 * half + 4 + e], rstd, nmr), gq1[e], bq1[e]);
+                o[e] = __builtin_fmaf(acc[rt][ni][8 * half + e], rstd, nmr);
+                o[4 + e] = __builtin_fmaf(acc[rt][ni][8 * half + 4 + e], rstd, nmr);
+                if (AFFINE) {
+                    o[e] = __builtin_fmaf(o[e], gq0[e], bq0[e]);
+                    o[4 + e] = __builtin_fmaf(o[4 + e], gq1[e], bq1[e]);
+                }
             }
             if (hswish) {
 #pragma unroll
@@ -478,21 +487,26 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         };
         if (!FP8OUT) {
             // ---- bf16 into the staging buffer (row 32 rt + l32; 16-byte chunk c at position c ^ (row % 16))
+            auto stage = [&](auto affine_tag) __attribute__((always_inline)) {
+                constexpr bool AFFINE = decltype(affine_tag)::value;
 #pragma unroll
-            for (int ni = 0; ni < NIW; ++ni) {
-                const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + colbase[ni] * 4);
-                const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + colbase[ni] * 4);
+                for (int ni = 0; ni < NIW; ++ni) {
+                    const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + colbase[ni] * 4);
+                    const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + colbase[ni] * 4);
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
-                    const int c = (colbase[ni] >> 3) + half;
+                    for (int half = 0; half < 2; ++half) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        v4f gq0 = {}, gq1 = {}, bq0 = {}, bq1 = {};
+                        if (AFFINE) { gq0 = g4[2 * half]; gq1 = g4[2 * half + 1]; bq0 = b4[2 * half]; bq1 = b4[2 * half + 1]; }
+                        const int c = (colbase[ni] >> 3) + half;
 #pragma unroll
-                    for (int rt = 0; rt < RT; ++rt)
-                        *reinterpret_cast<u32x4*>(obuf + (rt * 32 + l32) * (NT * 2) + ((c ^ (l32 & 15)) << 4)) =
-                            norm8(rt, ni, half, gq0, gq1, bq0, bq1, rstd_r[rt]);
+                        for (int rt = 0; rt < RT; ++rt)
+                            *reinterpret_cast<u32x4*>(obuf + (rt * 32 + l32) * (NT * 2) + ((c ^ (l32 & 15)) << 4)) =
+                                norm8(affine_tag, rt, ni, half, gq0, gq1, bq0, bq1, rstd_r[rt]);
+                    }
                 }
-            }
+            };
+            if (affine) stage(std::true_type{}); else stage(std::false_type{});
             lds_barrier();
             LOKA_STAMP(5);
             // ---- the storers write the block: 64 consecutive chunks (1 KB) per instruction, whole rows
@@ -531,7 +545,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
                     const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt) {
-                        const u32x4 pk = norm8(rt, ni, half, gq0, gq1, bq0, bq1, rstd_r[rt]);
+                        const u32x4 pk = norm8(std::true_type{}, rt, ni, half, gq0, gq1, bq0, bq1, rstd_r[rt]);
                         unsigned a = amax_b[rt];
                         const unsigned ws4[4] = {pk.x, pk.y, pk.z, pk.w};
 #pragma unroll
@@ -576,7 +590,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
                     const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt) {
-                        const u32x4 pk = norm8(rt, ni, half, gq0, gq1, bq0, bq1, rstd2[rt]);
+                        const u32x4 pk = norm8(std::true_type{}, rt, ni, half, gq0, gq1, bq0, bq1, rstd2[rt]);
                         const float iq = inv_q[rt];
                         u32x2 codes;
                         codes.x = e4m3x4(bf16_lo(pk.x) * iq, bf16_hi(pk.x) * iq, bf16_lo(pk.y) * iq, bf16_hi(pk.y) * iq);
