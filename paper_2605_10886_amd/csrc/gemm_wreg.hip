@@ -268,12 +268,63 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
     start_problem(cur_g, b0);
     { const int tile = b0; (void)tile; LOKA_STAMP(7); }
 
+    // Deferred stores (bf16 output from FP8 input): a finished block is not written out at its end by the four
+    // storer waves, where the other four would wait at the next barrier while the store path takes its 64 bytes
+    // per clock, but by all eight waves, one instruction at a time between the MFMAs of the NEXT block: the
+    // staging buffer is not written again before that block's statistics are merged (without a norm: before a
+    // barrier of its own), and a wave held up by the store path leaves the matrix pipe to the other wave of its
+    // SIMD.
+    constexpr bool DEFER = !FP8OUT && !BF16IN;
+    constexpr int CPR = NT / 8;                                         // 16-byte chunks per bf16 row
+    constexpr int SW_ = DEFER ? 8 : 4;                                  // waves that store (deferred: all of them)
+    constexpr int INSTR = RB * CPR / 64 / SW_;                          // store instructions per storing wave and block
+    bool pending = false;
+    int pend_g = 0, pend_m0 = 0;
+    // store instruction s of the pending block: 64 consecutive chunks (1 KB), whole rows
+    auto store_step = [&](int s, int sg, int sm0) __attribute__((always_inline)) {
+        int lid = lane;
+        asm volatile("; store lane id" : "+v"(lid));
+        const int id = ((DEFER ? wave : wave - 4) + SW_ * s) * 64 + lid;
+        const int r = id / CPR, c = id % CPR;
+        const u32x4 pk = *reinterpret_cast<const u32x4*>(smem + C::OFF_OB + r * (NT * 2) + ((c ^ (r & 15)) << 4));
+        uint16_t* const og = p.out + static_cast<int64_t>(sg) * p.strideO;
+        if (sm0 + r < p.M && c * 8 < p.N)
+            __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(og + static_cast<int64_t>(sm0 + r) * p.N + c * 8));
+    };
+    auto flush_pending = [&]() __attribute__((always_inline)) {
+        if ((DEFER || storer) && pending) {
+#pragma unroll
+            for (int s = 0; s < INSTR; ++s) {
+                if (s % 2 == 0) __builtin_amdgcn_sched_barrier(0);      // two in flight: W leaves few registers free
+                store_step(s, pend_g, pend_m0);
+            }
+        }
+        pending = false;
+    };
+
+    // (loaders) block bb has landed: newer requests (up to NBUF - 2 blocks) may still be in flight.  The counter
+    // also holds this wave's deferred stores, all newer than the loads: "at most n operations outstanding" with
+    // n counting the newer LOADS then still implies that block bb is complete (loads complete in order).
+    auto wait_landed = [&](int bb) __attribute__((always_inline)) {
+        const int newer = b1 - 1 - bb < NBUF - 2 ? b1 - 1 - bb : NBUF - 2;
+        if (p.y) wait_vmcnt<0>();                                       // Y stores share the counter
+        else if (newer >= 2) wait_vmcnt<(NBUF >= 4 ? 2 : 0) * LDW>();
+        else if (newer == 1) wait_vmcnt<(NBUF >= 3 ? 1 : 0) * LDW>();
+        else wait_vmcnt<0>();
+    };
+
     for (int b = b0; b < b1; ++b) {
         const int g = b / blocks_per_problem, m0 = (b - g * blocks_per_problem) * RB;
         const int tile = b;
         (void)tile;
         LOKA_STAMP(0);
+        bool fresh = b == b0;
         if (g != cur_g) {
+            fresh = true;
+            if (DEFER) {
+                flush_pending();                                        // the staging of W overwrites the buffer
+                __syncthreads();
+            }
             // (the staging of W overwrites the X blocks requested so far: they are requested again)
             if (loader || BF16IN) wait_vmcnt<0>();
             start_problem(g, b);
@@ -286,15 +337,12 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
                 wait_vmcnt<0>();
                 convert(b + 1);
             }
-        } else if (loader) {
-        // block b has landed: the loaders' newer requests (up to NBUF - 2 blocks) may still be in flight
-            const int newer = b1 - 1 - b < NBUF - 2 ? b1 - 1 - b : NBUF - 2;
-            if (p.y) wait_vmcnt<0>();                                   // Y stores share the counter
-            else if (newer >= 2) wait_vmcnt<(NBUF >= 4 ? 2 : 0) * LDW>();
-            else if (newer == 1) wait_vmcnt<(NBUF >= 3 ? 1 : 0) * LDW>();
-            else wait_vmcnt<0>();
+            lds_barrier();
+        } else if (fresh || !DEFER) {
+            // (with deferred stores the previous block's last barrier has already covered this)
+            if (loader) wait_landed(b);
+            lds_barrier();
         }
-        lds_barrier();
         LOKA_STAMP(1);
         if (BF16IN) {
             if (b + 2 < b1) fetch(b + 2);                                // in flight for a whole iteration
@@ -340,15 +388,32 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         };
 #pragma unroll
         for (int q = 0; q < XD - 1 && q < NS; ++q) read_xf(q);
+        auto mma_loop = [&](auto store_tag) __attribute__((always_inline)) {
+            constexpr bool STORES = decltype(store_tag)::value;
+            constexpr int TM = NS * NIW;                                // MFMAs of the block
 #pragma unroll
-        for (int q = 0; q < NS; ++q) {
-            __builtin_amdgcn_sched_barrier(0);
-            if (q + XD - 1 < NS) read_xf(q + XD - 1);
+            for (int q = 0; q < NS; ++q) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (q + XD - 1 < NS) read_xf(q + XD - 1);
 #pragma unroll
-            for (int ni = 0; ni < NIW; ++ni)
-                acc[q % RT][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wreg[ni][q / RT], xf[q % XD], acc[q % RT][ni],
-                                                                                 0, 0, 0, 0, 0, 0);
-        }
+                for (int ni = 0; ni < NIW; ++ni) {
+                    acc[q % RT][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wreg[ni][q / RT], xf[q % XD],
+                                                                                     acc[q % RT][ni], 0, 0, 0, 0, 0, 0);
+                    if (STORES) {
+                        // the pending block's stores, spread evenly over the MFMAs, in source order
+                        const int t = q * NIW + ni;
+#pragma unroll
+                        for (int s = t * INSTR / TM; s < (t + 1) * INSTR / TM; ++s) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            store_step(s, pend_g, pend_m0);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+        };
+        if (DEFER && pending) mma_loop(std::true_type{}); else mma_loop(std::false_type{});
+        if (DEFER) pending = false;                                     // the previous block is on its way
         __builtin_amdgcn_sched_barrier(0);
         LOKA_STAMP(2);
 
@@ -456,6 +521,8 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
                 mean_r[rt] = ln ? tmean : 0.f;
                 rstd_r[rt] = __builtin_amdgcn_rsqf(tm2 * (blocknorm ? 1.0f / 256.0f : inv_n) + p.eps);
             }
+        } else if (DEFER) {
+            lds_barrier();      // every wave has read its part of the previous block out of the staging buffer
         }
         LOKA_STAMP(4);
 
@@ -507,23 +574,13 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
                 }
             };
             if (affine) stage(std::true_type{}); else stage(std::false_type{});
+            // (deferred stores: this barrier is also the next block's "X has landed" barrier)
+            if (DEFER && loader && b + 1 < b1 && (b + 1) / blocks_per_problem == g) wait_landed(b + 1);
             lds_barrier();
             LOKA_STAMP(5);
-            // ---- the storers write the block: 64 consecutive chunks (1 KB) per instruction, whole rows
-            if (storer) {
-                constexpr int CPR = NT / 8;                                 // chunks per row
-                constexpr int INSTR = RB * CPR / 64 / 4;                    // per storer wave
-                uint16_t* const og = p.out + static_cast<int64_t>(g) * p.strideO;
-#pragma unroll
-                for (int s = 0; s < INSTR; ++s) {
-                    if (s % 2 == 0) __builtin_amdgcn_sched_barrier(0);      // two in flight: W leaves few registers free
-                    const int id = ((wave - 4) + 4 * s) * 64 + lanev;
-                    const int r = id / CPR, c = id % CPR;
-                    const u32x4 pk = *reinterpret_cast<const u32x4*>(obuf + r * (NT * 2) + ((c ^ (r & 15)) << 4));
-                    if (m0 + r < p.M && c * 8 < p.N)
-                        __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(og + static_cast<int64_t>(m0 + r) * p.N + c * 8));
-                }
-            }
+            // ---- the storers write the block out: now, or between the MFMAs of the next block
+            pending = true; pend_g = g; pend_m0 = m0;
+            if (!DEFER || b + 1 == b1) flush_pending();
         } else {
             // ---- FP8 output for the next layer: the bf16 values above, quantized per row exactly as the
             // quantize entry point would quantize the stored bf16 tensor (amax over the row of |bf16 value|,

@@ -349,12 +349,9 @@ loka_status tracker_update_launch(const void* x, int64_t B, int64_t K, int64_t l
     p.x = static_cast<const uint16_t*>(x); p.B = B; p.ld = ld; p.K = static_cast<int>(K);
     p.T = pl.T; p.pairs = pl.pairs; p.splits = pl.splits; p.rows_per_split = pl.rows_per_split;
     p.partial = reinterpret_cast<float*>(ws); p.colsum = colsum;
-    static bool lds_set = false;                 // per process; the attribute belongs to the function
-    if (!lds_set) {
-        LOKA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&tracker_scatter_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(TRK_LDS)));
-        lds_set = true;
-    }
+    // set on every call (a host-side table write): no process-wide state, and correct on whichever device is current
+    LOKA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&tracker_scatter_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(TRK_LDS)));
     tracker_scatter_kernel<<<dim3(pl.pairs * pl.splits), 512, TRK_LDS, s>>>(p);
     const int KP = pl.T * TRK_T;
     tracker_mean_kernel<<<dim3((KP + 255) / 256), 256, 0, s>>>(colsum, pl.T, pl.pairs, pl.splits, static_cast<int>(K), B, n_old,

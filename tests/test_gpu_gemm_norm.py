@@ -257,6 +257,34 @@ def test_streaming_variant_crosses_problem_boundaries(orc, variant):
         assert ok, f"problem {g}: worst {worst} ulps"
 
 
+@pytest.mark.parametrize("variant,N", [("wreg32", 512), ("wreg32", 1024), ("strip32", 256)])
+def test_streaming_variant_without_norm_many_blocks(orc, variant, N):
+    # several row blocks per workgroup and no normalization: nothing but the kernel's own barriers separates one
+    # block's output staging from the next block's.  O must be the bf16 rounding of Y everywhere (bit-exact),
+    # with and without the fp32 output, and Y must match the oracle on sampled rows.
+    M, K = 40000 + 17, 256
+    v = B.variant_id(variant)
+    x, w = synth.normal(M, K, seed=77), synth.weight(K, N, seed=78)
+    xq, sx = B.loka_quantize(x.to(DEV), B.SCALE_ROW)
+    wq, sw = B.loka_quantize(w.to(DEV), B.SCALE_COL, transpose_out=True)
+    desc = B.make_desc(M, N, K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_NONE, variant=v)
+    assert B.loka_variant_supports(desc, v)
+    out, y = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, want_y=True)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        out2, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+        torch.cuda.synchronize()
+        assert torch.equal(out2.view(torch.int16), y.to(torch.bfloat16).view(torch.int16))
+    assert torch.equal(out.view(torch.int16), y.to(torch.bfloat16).view(torch.int16))
+    rows = np.unique(np.concatenate([np.arange(0, 70), np.arange(M - 70, M), np.arange(0, M, 997)]))
+    xq_o, sx_o = orc.quantize(synth.bf16_bits(x[rows]), B.SCALE_ROW)
+    wq_o, sw_o = orc.quantize(synth.bf16_bits(w), B.SCALE_COL, transpose_out=True)
+    assert np.array_equal(xq[torch.from_numpy(rows).to(DEV)].cpu().numpy(), xq_o)
+    y_o, absdot = orc.fp8_gemm(xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, want_absdot=True)
+    err = np.abs(y[torch.from_numpy(rows).to(DEV)].cpu().numpy().astype(np.float64) - y_o)
+    assert (err <= gemm_tolerance(absdot, y_o, K)).all()
+
+
 # ----------------------------------------------------------------------------- BlockNorm + Hard-Swish
 def _run_blocknorm_case(orc, x, w, recipe, act, variant, rows=None, tag=""):
     M, K = x.shape
