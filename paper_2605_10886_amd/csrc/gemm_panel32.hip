@@ -1,6 +1,6 @@
 // Large-tile FP8 GEMM with the row norm fused across workgroups: 256 x 256 tiles, 8 waves,
 // v_mfma_f32_32x32x64_f8f6f4, persistent panel-synchronous schedule (see gemm.hip for the schedule's
-// description; this file is its throughput-oriented instantiation for non-blockwise scales).
+// description; this file is its throughput-oriented instantiation).
 //
 // Why a second kernel: measured on MI355X, back-to-back 16x16x128 MFMAs issued by ONE wave reach ~70-80 %
 // of the FP8 rate (each instruction reads 16 operand registers for 32 cycles of work), while 32x32x64
