@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--budget", type=float, default=5e-2, help="rel-Frobenius budget the timed variant must meet")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-library", action="store_true", help="skip the vendor-library yardstick leg")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the steps (one per rotated input set) into a HIP graph and time its replays: what a "
+                         "serving loop does with the launch-bound small workloads")
     ap.add_argument("--no-dispatch", action="store_true",
                     help="skip the profiling step: rowwise recipe, library's static variant choice (for clean rocprofv3 stats)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -70,7 +73,8 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    stream = torch.cuda.current_stream()
+    stream = torch.cuda.Stream() if args.graph else torch.cuda.current_stream()   # (the null stream cannot be captured)
+    torch.cuda.set_stream(stream)
     w = synth.WORKLOADS[args.workload]
     M, K, N, G = w.M, w.K, w.N, w.batch
     norm = B.NORMS[w.norm]
@@ -148,11 +152,26 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    steps_timed = args.steps
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for _ in range(n_sets):
+                step()
+        replays = -(-args.steps // n_sets)
+        steps_timed = replays * n_sets
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+    else:
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps_timed
 
     flops = 2.0 * G * M * K * N
     value = flops / (ms_per_step * 1e-3) / 1e12
@@ -267,7 +286,7 @@ def main():
 
     line = {
         "metric": "FP8 GEMM+norm TFLOP/s (% of MI355X FP8 peak); quantize/probe HBM GB/s",
-        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps_timed, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8_e4m3 (fp32 accumulate)", "data": "synthetic",
         "config": {"workload": f"{w.name}: X[{G}x{M},{K}] {w.x_dist}, W[{K},{N}] N(0,1/K), {w.norm}",
@@ -275,6 +294,7 @@ def main():
                    "recipe": RECIPE_NAMES.get((xm, wm), f"{xm}/{wm}"), "variant": B.loka_variant_name(variant),
                    "flops_counted": "2*M*K*N of the FP8 GEMM", "pct_fp8_peak": 100 * value / FP8_PEAK_TFLOPS,
                    "input_sets_rotated": n_sets,
+                   "launch": f"HIP graph of {n_sets} steps, replayed" if args.graph else "eager",
                    "dispatch": "skipped (--no-dispatch)" if args.no_dispatch else
                                {"budget_1e-2": "no FP8 candidate (stay in BF16)" if st_strict != B.LOKA_OK else
                                 RECIPE_NAMES.get((ch_strict["x_mode"], ch_strict["w_mode"])),

@@ -1,0 +1,89 @@
+"""The hot entry points under HIP graph capture.
+
+`loka_quantize` (row / 1x128 modes) and `loka_fp8_gemm_norm` only launch kernels on the caller's stream (scratch comes
+in as a workspace argument and is cleared by a kernel, never by a memset node), so a serving loop can record a step
+once and replay it.  Each case records quantize + GEMM+norm, replays the graph several times with new activations
+written into the same input buffer and eager work on the device between the replays, and compares every replay
+bit for bit with the eager calls on the same input.
+"""
+import ctypes
+
+import pytest
+import torch
+
+from paper_2605_10886_amd import binding as B
+from paper_2605_10886_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+# (M, K, N, batch, norm, what it exercises)
+CASES = [
+    (2048, 512, 512, 1, B.NORM_RMSNORM, "row in one tile"),
+    (16384, 256, 256, 4, B.NORM_RMSNORM, "strip kernel, grouped"),
+    (16384, 256, 1024, 1, B.NORM_LAYERNORM, "streaming kernel, deferred stores"),
+    (4096, 256, 4096, 1, B.NORM_LAYERNORM, "panel-synchronous kernel: counters cleared by a kernel inside the launch"),
+]
+
+
+@pytest.mark.parametrize("M,K,N,G,norm,what", CASES)
+def test_step_replays_from_a_graph(M, K, N, G, norm, what):
+    L = B.lib()
+    rows = G * M
+    xs = [synth.normal(rows, K, seed=300 + i).to(DEV) for i in range(3)]
+    wq = torch.empty(G * N, K, dtype=torch.uint8, device=DEV)
+    sw = torch.empty(G * N, dtype=torch.float32, device=DEV)
+    for g in range(G):
+        q, s = B.loka_quantize(synth.weight(K, N, seed=400 + g).to(DEV), B.SCALE_COL, transpose_out=True)
+        wq[g * N:(g + 1) * N] = q
+        sw[g * N:(g + 1) * N] = s
+    desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, norm, 1e-5, -1)
+
+    x_in = torch.empty(rows, K, dtype=torch.bfloat16, device=DEV)
+    xq = torch.empty(rows, K, dtype=torch.uint8, device=DEV)
+    sx = torch.empty(rows, dtype=torch.float32, device=DEV)
+    out = torch.empty(rows, N, dtype=torch.bfloat16, device=DEV)
+    ws_q = torch.empty(max(16, L.loka_quantize_workspace(B.SCALE_ROW, rows, K, 0)), dtype=torch.uint8, device=DEV)
+    ws_g = torch.empty(max(16, L.loka_fp8_gemm_norm_workspace(ctypes.byref(desc))), dtype=torch.uint8, device=DEV)
+
+    def step(stream):
+        sp = ctypes.c_void_p(stream.cuda_stream)
+        r = L.loka_quantize(x_in.data_ptr(), rows, K, K, B.SCALE_ROW, 0, xq.data_ptr(), sx.data_ptr(), ws_q.data_ptr(),
+                            ws_q.numel(), sp)
+        assert r == 0, r
+        r = L.loka_fp8_gemm_norm(ctypes.byref(desc), xq.data_ptr(), sx.data_ptr(), wq.data_ptr(), sw.data_ptr(), None,
+                                 None, out.data_ptr(), None, ws_g.data_ptr(), ws_g.numel(), sp)
+        assert r == 0, r
+
+    # eager results for every input (also the warm-up that loads the code objects before the capture)
+    cur = torch.cuda.current_stream()
+    want = []
+    for x in xs:
+        x_in.copy_(x)
+        step(cur)
+        torch.cuda.synchronize()
+        want.append((xq.clone(), sx.clone(), out.clone()))
+
+    side = torch.cuda.Stream()
+    side.wait_stream(cur)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+
+    junk = torch.empty(1 << 20, device=DEV)
+    for rep in range(6):
+        i = rep % len(xs)
+        x_in.copy_(xs[i])
+        out.fill_(0)                    # eager work between the replays; stale results would show
+        xq.fill_(0)
+        junk.normal_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xq, want[i][0]), f"{what}: codes, replay {rep}"
+        assert torch.equal(sx, want[i][1]), f"{what}: scales, replay {rep}"
+        assert torch.equal(out.view(torch.int16), want[i][2].view(torch.int16)), f"{what}: O, replay {rep}"
+        if "panel" in what:
+            assert B.loka_fp8_gemm_norm_check(desc, ws_g) == B.LOKA_OK
