@@ -246,9 +246,14 @@ def main():
                 lib_ln = lambda: torch.nn.functional.layer_norm(o_lib, (N,), eps=w.eps)
                 lib_ln()
                 t_ln = float(np.mean(_event_times(lib_ln, 5, stream)))
+                lib_bf = lambda: torch.matmul(x, wt)                     # bf16 in, bf16 out
+                lib_bf()
+                t_bf = float(np.mean(_event_times(lib_bf, 5, stream)))
             library = {"what": "torch._scaled_mm (hipBLASLt) rowwise FP8 GEMM, bf16 out, no norm; + torch layer_norm pass",
                        "gemm_ms": t_lib, "gemm_TFLOPs": flops / t_lib / 1e9, "norm_pass_ms": t_ln,
-                       "unfused_pair_ms": t_lib + t_ln, "fused_kernel_ms": t_gemm}
+                       "unfused_pair_ms": t_lib + t_ln, "fused_kernel_ms": t_gemm,
+                       "bf16_matmul_ms": t_bf, "bf16_matmul_TFLOPs": flops / t_bf / 1e9,
+                       "bf16_matmul_plus_norm_ms": t_bf + t_ln, "fp8_step_ms": ms_per_step}
             del o_lib
         except Exception as e:                                   # noqa: BLE001 - context leg only
             library = {"error": str(e)[:200]}
