@@ -715,6 +715,7 @@ int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, const vo
 void strip_launch(const GemmParams& p, dim3 grid, hipStream_t s);
 static void launch_strip_any(const GemmParams& p, bool, dim3 grid, hipStream_t s) { strip_launch(p, grid, s); }
 static const char kStripName[] = "strip32";
+static const char kPanel32Name[] = "panel32_256x256";
 
 // gemm_panel32.hip
 const void* panel32_fn(bool blockwise);
@@ -750,7 +751,7 @@ static const VariantInfo kVariants[] = {
     // through a few words of global memory and normalize their own tile in registers
     LOKA_VARIANT("panel256x256w8", 256, 256, 1, 2, 4, EPI_PANEL_SYNC),
     // the same schedule on 32x32x64 MFMAs: the throughput variant
-    {"panel32_256x256", 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(false), panel32_fn(true)},
+    {kPanel32Name, 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(false), panel32_fn(true)},
 };
 constexpr int kNumCUs = 256;          // MI355X; the launch re-checks against the device it runs on
 constexpr unsigned kSpinLimit = 1u << 18;   // x s_sleep(16) ~ 0.1 s: far beyond any main loop
@@ -792,9 +793,15 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
 }
 
 // the variant's workspace starts with the flag a workgroup raises when its bounded wait for the panel runs out
-bool variant_has_wait_flag(const loka_gemm_desc* d, int v) {
-    return kVariants[v].epi == EPI_PANEL_SYNC && d->norm != LOKA_NORM_NONE && d->norm != LOKA_NORM_BLOCKNORM;
+// The panel-synchronous launch exchanges row statistics between workgroups (and has a bounded wait with an error
+// flag) unless there is nothing to exchange: no row norm, groups inside a tile, or - in the 32x32 kernel, which
+// then finalizes in the tile - a single tile per row.
+static bool panel_exchanges(const loka_gemm_desc* d, const VariantInfo& vi) {
+    if (vi.epi != EPI_PANEL_SYNC || d->norm == LOKA_NORM_NONE || d->norm == LOKA_NORM_BLOCKNORM) return false;
+    return !(vi.name == kPanel32Name && d->N <= vi.bn);
 }
+
+bool variant_has_wait_flag(const loka_gemm_desc* d, int v) { return panel_exchanges(d, kVariants[v]); }
 
 size_t variant_workspace(const loka_gemm_desc* d, int v) {
     const VariantInfo& vi = kVariants[v];
@@ -803,6 +810,7 @@ size_t variant_workspace(const loka_gemm_desc* d, int v) {
     size_t stats = static_cast<size_t>(d->batch) * d->M * tiles_n * 2 * sizeof(float);
     stats = (stats + 255) & ~size_t(255);
     if (vi.epi == EPI_PANEL_SYNC) {
+        if (!panel_exchanges(d, vi)) return 0;
         // [error flag, 256 B][arrival counters][per-tile row statistics]
         const int64_t panels = d->batch * ((d->M + vi.bm - 1) / vi.bm);
         return 256 + ((static_cast<size_t>(panels) * 4 + 255) & ~size_t(255)) + stats;
@@ -914,7 +922,7 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         if (g <= 0) return LOKA_ERR_UNSUPPORTED;
         if (g > grid.x) g = (static_cast<int64_t>(grid.x) / p.tiles_n) * p.tiles_n;   // fewer tiles than slots
         grid = dim3(static_cast<unsigned>(g));
-        if (d->norm != LOKA_NORM_NONE && d->norm != LOKA_NORM_BLOCKNORM) {
+        if (panel_exchanges(d, vi)) {
             const int64_t panels = static_cast<int64_t>(p.batch) * p.tiles_m;
             const size_t ctr_bytes = (static_cast<size_t>(panels) * 4 + 255) & ~size_t(255);
             uint8_t* ws = static_cast<uint8_t*>(workspace);

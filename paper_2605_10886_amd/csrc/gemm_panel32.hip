@@ -406,7 +406,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         }
         LOKA_STAMP(2);
         const bool blocknorm = p.norm == LOKA_NORM_BLOCKNORM;   // groups of 256 columns = this tile: nothing to exchange
-        if (EPI == EPI_PANEL_SYNC && !blocknorm) {
+        if (EPI == EPI_PANEL_SYNC && !blocknorm && p.tiles_n > 1) {
             // publish (mean, M2) of this tile per row, signal, wait for the panel's other tiles, merge all tiles
             const int panel = g * p.tiles_m + tm;
             float* prow = p.part + (static_cast<int64_t>(g) * p.M) * (2 * p.tiles_n);
