@@ -94,6 +94,23 @@ def test_workloads_full_size_rowwise(orc):
         assert np.array_equal(s_g[idx].cpu().numpy().view(np.uint32), s_o.view(np.uint32)), name
 
 
+@pytest.mark.parametrize("mode_name", ["ROW", "BLOCK_1x128"])
+@pytest.mark.parametrize("shape", [(1000, 256), (32768 + 24, 512), (1000, 1024), (16384 + 8, 1024), (65536 + 8, 256)])
+def test_row_kernel_instances_on_both_sides_of_the_size_rule(orc, mode_name, shape):
+    # the launcher gives a small tensor fewer rows per wave than a large one: both sets of instances, ragged row counts
+    rows, cols = shape
+    mode = getattr(B, "SCALE_" + mode_name)
+    x = synth.normal(rows, cols, seed=rows + cols)
+    q_g, s_g = B.loka_quantize(x.to(DEV), mode)
+    torch.cuda.synchronize()
+    sel = np.unique(np.concatenate([np.arange(min(rows, 130)), np.arange(rows - 130, rows), np.arange(0, rows, 257)]))
+    q_o, s_o = orc.quantize(synth.bf16_bits(x)[sel].copy(), mode)
+    idx = torch.from_numpy(sel).to(DEV)
+    assert np.array_equal(q_g[idx].cpu().numpy(), q_o)
+    s_g = s_g.cpu().numpy().reshape(rows, -1)[sel].ravel()
+    assert np.array_equal(s_g.view(np.uint32), s_o.view(np.uint32))
+
+
 def test_c5_recipes_full_size(orc):
     # outlier-heavy layer: per-tensor and 1x128 activations, 128x128 weights
     w = synth.WORKLOADS["C5"]
