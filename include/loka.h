@@ -44,7 +44,15 @@ typedef enum {
     LOKA_SCALE_ROW = 1,           /* one per row                                -> rows */
     LOKA_SCALE_COL = 2,           /* one per column (weights: per output channel)-> cols */
     LOKA_SCALE_BLOCK_1x128 = 3,   /* one per (row, 128 consecutive columns)     -> rows * cols/128 */
-    LOKA_SCALE_BLOCK_128x128 = 4  /* one per 128 x 128 block                    -> rows/128 * cols/128 */
+    LOKA_SCALE_BLOCK_128x128 = 4, /* one per 128 x 128 block                    -> rows/128 * cols/128 */
+    /* The two block modes with POWER-OF-TWO scales (an extension of this library to the block recipe of
+     * Section 3.3, "Library and Recipe Selection"; group layout and counts as modes 3 and 4):
+     *   scales[g] = the smallest power of two s with amax_g / s <= 448   (amax_g = max(max|x|, 1e-12)),
+     *   q = e4m3_rne(x / s)   (an exact scaling: the only rounding is the e4m3 cast).
+     * Every scale is exactly representable by an 8-bit exponent, so the GEMM can hand the per-block scales to the
+     * matrix cores (scaled MFMA) instead of rescaling accumulators: see loka_fp8_gemm_norm. */
+    LOKA_SCALE_BLOCK_1x128_POW2 = 5,
+    LOKA_SCALE_BLOCK_128x128_POW2 = 6
 } loka_scale_mode;
 
 /* Row normalization fused into the GEMM epilogue (Section 3.2, "Block-wise

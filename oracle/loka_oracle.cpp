@@ -120,7 +120,16 @@ void parallel_rows(int64_t n, int threads, F f) {
     for (auto& th : pool) th.join();
 }
 
-enum { SCALE_TENSOR = 0, SCALE_ROW = 1, SCALE_COL = 2, SCALE_BLOCK_1x128 = 3, SCALE_BLOCK_128x128 = 4 };
+enum { SCALE_TENSOR = 0, SCALE_ROW = 1, SCALE_COL = 2, SCALE_BLOCK_1x128 = 3, SCALE_BLOCK_128x128 = 4,
+       SCALE_BLOCK_1x128_POW2 = 5, SCALE_BLOCK_128x128_POW2 = 6 };   // 5, 6: groups of 3, 4 with power-of-two scales
+
+// group layout of a mode (the power-of-two modes share the layout of the plain block modes)
+int layout_of(int mode) {
+    if (mode == SCALE_BLOCK_1x128_POW2) return SCALE_BLOCK_1x128;
+    if (mode == SCALE_BLOCK_128x128_POW2) return SCALE_BLOCK_128x128;
+    return mode;
+}
+bool is_pow2(int mode) { return mode == SCALE_BLOCK_1x128_POW2 || mode == SCALE_BLOCK_128x128_POW2; }
 enum { NORM_NONE = 0, NORM_LAYERNORM = 1, NORM_RMSNORM = 2 };
 
 const float kE4M3Max = 448.0f;
@@ -128,7 +137,7 @@ const float kAmaxFloor = 1e-12f;
 
 // Index of the scale group that element (r, c) of a [rows, cols] matrix belongs to.
 int64_t group_of(int mode, int64_t r, int64_t c, int64_t cols) {
-    switch (mode) {
+    switch (layout_of(mode)) {
         case SCALE_TENSOR: return 0;
         case SCALE_ROW: return r;
         case SCALE_COL: return c;
@@ -159,7 +168,7 @@ void orc_e4m3_encode_array(const float* t, uint8_t* out, int64_t n) {
 // Number of fp32 scales for a [rows, cols] matrix; -1 if the mode does not
 // divide the shape.
 int64_t orc_scale_count(int mode, int64_t rows, int64_t cols) {
-    switch (mode) {
+    switch (layout_of(mode)) {
         case SCALE_TENSOR: return 1;
         case SCALE_ROW: return rows;
         case SCALE_COL: return cols;
@@ -176,6 +185,9 @@ int64_t orc_scale_count(int mode, int64_t rows, int64_t cols) {
 //      inv_g = 448 / amax_g               (one fp32 division each)
 //   4. t = xf * inv_g (one fp32 multiply), clamped to [-448, 448]
 //   5. code = e4m3_encode(t)
+// Power-of-two modes: step 3 becomes scale_g = the smallest power of two s with amax_g / s <= 448 (found in
+//   double: amax_g / 448 is exact there whenever it is a power of two, and no other quotient of an fp32 by 448
+//   rounds to one), inv_g = 1 / s, so that step 4 is an exact scaling.
 // q is [rows, cols], or [cols, rows] when transpose_out != 0.
 // Returns 0, or -1 on a shape the mode does not divide.
 int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int mode, int transpose_out,
@@ -192,6 +204,14 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int 
     std::vector<float> inv(ng);
     for (int64_t g = 0; g < ng; ++g) {
         float a = amax[g] < kAmaxFloor ? kAmaxFloor : amax[g];
+        if (is_pow2(mode)) {
+            int e = 0;
+            const double m = std::frexp(static_cast<double>(a) / 448.0, &e);   // need = m * 2^e, m in [0.5, 1)
+            const int k = (m == 0.5) ? e - 1 : e;                                 // smallest k with need <= 2^k
+            scales[g] = static_cast<float>(std::ldexp(1.0, k));
+            inv[g] = static_cast<float>(std::ldexp(1.0, -k));
+            continue;
+        }
         scales[g] = a / kE4M3Max;
         inv[g] = kE4M3Max / a;
     }
@@ -222,6 +242,10 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int 
 // Returns 0, -1 on an unsupported combination.
 int orc_fp8_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* xq, const float* sx, int x_mode,
                  const uint8_t* wq, const float* sw, int w_mode, float* y, double* absdot, int threads) {
+    // (the power-of-two block modes differ only in how the scales were chosen: the contraction is the same)
+    if (is_pow2(x_mode) != is_pow2(w_mode)) return -1;
+    x_mode = layout_of(x_mode);
+    w_mode = layout_of(w_mode);
     bool blockwise = (x_mode == SCALE_BLOCK_1x128) || (w_mode == SCALE_BLOCK_128x128);
     if (blockwise && !(x_mode == SCALE_BLOCK_1x128 && w_mode == SCALE_BLOCK_128x128)) return -1;
     if (blockwise && (K % 128 || N % 128)) return -1;

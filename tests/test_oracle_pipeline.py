@@ -120,6 +120,88 @@ def test_quantize_power_of_two_scaling_changes_only_the_scale(orc):
         assert np.array_equal(s2, s1 * np.float32(16.0))
 
 
+def exact_quantize_pow2(x_bits, mode, orc):
+    """Power-of-two block modes re-derived in exact fractions: s = the smallest power of two with amax / s <= 448
+    (found by stepping, not by logarithms), t = x / s exactly."""
+    rows, cols = x_bits.shape
+    xv = [[bf16_bits_to_fraction(int(x_bits[r, c])) for c in range(cols)] for r in range(rows)]
+
+    def gid(r, c):
+        if mode == orc.SCALE_BLOCK_1x128_POW2:
+            return r * (cols // 128) + c // 128
+        return (r // 128) * (cols // 128) + c // 128
+
+    ng = orc.scale_count(mode, rows, cols)
+    amax = [Fraction(0)] * ng
+    for r in range(rows):
+        for c in range(cols):
+            amax[gid(r, c)] = max(amax[gid(r, c)], abs(xv[r][c]))
+    scale = []
+    for a in amax:
+        a = max(a, FLOOR)
+        sc = Fraction(1)
+        while a / sc > F448:
+            sc *= 2
+        while a / (sc / 2) <= F448:
+            sc /= 2
+        scale.append(sc)
+    codes = np.zeros((rows, cols), dtype=np.uint8)
+    for r in range(rows):
+        for c in range(cols):
+            t = xv[r][c] / scale[gid(r, c)]
+            assert abs(t) <= F448
+            codes[r, c] = e4m3_nearest_code(t, negative_zero=(int(x_bits[r, c]) >> 15) == 1)
+    return codes, scale
+
+
+@pytest.mark.parametrize("mode_name", ["BLOCK_1x128_POW2", "BLOCK_128x128_POW2"])
+def test_quantize_power_of_two_modes_against_exact_fractions(orc, mode_name):
+    mode = getattr(orc, "SCALE_" + mode_name)
+    x = synth.student_t4(128, 256, seed=22)
+    x[5, :] = 0                                   # an all-zero row (all-zero 1x128 groups)
+    x[7, 3] = 3.0e4                               # a single large outlier
+    x[9, 0:128] = 0
+    x[9, 17] = 448.0                              # amax / 448 exactly a power of two: the scale is 1, not 2
+    x[11, 128:256] = 0
+    x[11, 200] = 450.0                            # just above: the scale is 2
+    x[13, 0:128] = 0
+    x[13, 1] = 448.0 * 2 ** -20                   # exact power of two below one
+    xb = synth.bf16_bits(x).copy()
+    q, s = orc.quantize(xb, mode, threads=2)
+    q_exact, s_exact = exact_quantize_pow2(xb, mode, orc)
+    assert [Fraction(float(v)) for v in s] == s_exact
+    assert np.array_equal(q, q_exact)
+    # every scale is a power of two, and no smaller one would do
+    mant, _ = np.frexp(s.astype(np.float64))
+    assert np.all(mant == 0.5)
+    if mode == orc.SCALE_BLOCK_1x128_POW2:
+        assert s.reshape(128, 2)[9, 0] == 1.0 and s.reshape(128, 2)[11, 1] == 2.0 and s.reshape(128, 2)[13, 0] == 2.0 ** -20
+        # same group layout as the plain 1x128 mode, scale within [1, 2) of the plain one
+        _, s_plain = orc.quantize(xb, orc.SCALE_BLOCK_1x128)
+        ratio = s.astype(np.float64) / s_plain.astype(np.float64)
+        assert np.all((ratio >= 1.0 - 1e-7) & (ratio < 2.0))
+
+
+def test_gemm_power_of_two_modes_are_the_block_contraction(orc):
+    # the GEMM treats the two power-of-two modes as the block modes (only the scale VALUES differ), rejects a mix
+    M, K, N = 8, 256, 128
+    x, w = synth.normal(M, K, seed=31), synth.weight(K, N, seed=32)
+    xq, sx = orc.quantize(synth.bf16_bits(x), orc.SCALE_BLOCK_1x128_POW2)
+    wq, sw = orc.quantize(synth.bf16_bits(w), orc.SCALE_BLOCK_128x128_POW2, transpose_out=True)
+    y_p = orc.fp8_gemm(xq, sx, orc.SCALE_BLOCK_1x128_POW2, wq, sw, orc.SCALE_BLOCK_128x128_POW2)
+    y_b = orc.fp8_gemm(xq, sx, orc.SCALE_BLOCK_1x128, wq, sw, orc.SCALE_BLOCK_128x128)
+    assert np.array_equal(y_p, y_b)
+    # brute force in exact fractions on a few outputs
+    for (m, n) in [(0, 0), (3, 77), (7, 127)]:
+        tot = Fraction(0)
+        for kb in range(K // 128):
+            part = sum(e4m3_code_value(int(xq[m, k])) * e4m3_code_value(int(wq[n, k])) for k in range(kb * 128, kb * 128 + 128))
+            tot += part * Fraction(float(sx[m * (K // 128) + kb])) * Fraction(float(sw[kb * (N // 128) + n // 128]))
+        assert abs(Fraction(float(y_p[m, n])) - tot) <= abs(tot) * Fraction(1, 2 ** 23)
+    with pytest.raises(ValueError):
+        orc.fp8_gemm(xq, sx, orc.SCALE_BLOCK_1x128_POW2, wq, sw, orc.SCALE_BLOCK_128x128)
+
+
 def test_quantize_zero_matrix(orc):
     xb = np.zeros((4, 128), dtype=np.uint16)
     xb[1, 5] = 0x8000                                               # a negative zero keeps its sign
