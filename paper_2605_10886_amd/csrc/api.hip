@@ -33,7 +33,9 @@ int default_variant(const loka_gemm_desc*);
 size_t tracker_workspace_bytes(int64_t, int64_t);
 loka_status tracker_update_launch(const void*, int64_t, int64_t, int64_t, int64_t, float*, float*, void*, hipStream_t);
 
-static bool mode_ok(int m) { return m >= LOKA_SCALE_TENSOR && m <= LOKA_SCALE_BLOCK_128x128; }
+static bool mode_ok(int m) { return m >= LOKA_SCALE_TENSOR && m <= LOKA_SCALE_BLOCK_128x128_POW2; }
+static bool is_block_x(int m) { return m == LOKA_SCALE_BLOCK_1x128 || m == LOKA_SCALE_BLOCK_1x128_POW2; }
+static bool is_block_w(int m) { return m == LOKA_SCALE_BLOCK_128x128 || m == LOKA_SCALE_BLOCK_128x128_POW2; }
 
 // Shape / enum validation shared by the GEMM entry points; does not look at pointers.
 loka_status validate_desc(const loka_gemm_desc* d, bool fp8) {
@@ -54,8 +56,10 @@ loka_status validate_desc(const loka_gemm_desc* d, bool fp8) {
         if (d->block_n <= 0 || d->N % d->block_n) return LOKA_ERR_SHAPE;
         if (d->block_n != 256) return LOKA_ERR_UNSUPPORTED;
     }
-    const bool xb = d->x_mode == LOKA_SCALE_BLOCK_1x128, wb = d->w_mode == LOKA_SCALE_BLOCK_128x128;
+    const bool xb = is_block_x(d->x_mode), wb = is_block_w(d->w_mode);
     if (xb != wb) return LOKA_ERR_UNSUPPORTED;
+    // (power-of-two scales on both operands or on neither: the scaled matrix instruction takes both)
+    if ((d->x_mode == LOKA_SCALE_BLOCK_1x128_POW2) != (d->w_mode == LOKA_SCALE_BLOCK_128x128_POW2)) return LOKA_ERR_UNSUPPORTED;
     if (xb && (d->N % 128)) return LOKA_ERR_SHAPE;
     if (!xb) {
         if (!(d->x_mode == LOKA_SCALE_TENSOR || d->x_mode == LOKA_SCALE_ROW)) return LOKA_ERR_UNSUPPORTED;
@@ -101,14 +105,16 @@ int64_t loka_scale_count(loka_scale_mode mode, int64_t rows, int64_t cols) {
         case LOKA_SCALE_TENSOR: return 1;
         case LOKA_SCALE_ROW: return rows;
         case LOKA_SCALE_COL: return cols;
-        case LOKA_SCALE_BLOCK_1x128: return (cols % 128) ? -1 : rows * (cols / 128);
-        case LOKA_SCALE_BLOCK_128x128: return (cols % 128 || rows % 128) ? -1 : (rows / 128) * (cols / 128);
+        case LOKA_SCALE_BLOCK_1x128:
+        case LOKA_SCALE_BLOCK_1x128_POW2: return (cols % 128) ? -1 : rows * (cols / 128);
+        case LOKA_SCALE_BLOCK_128x128:
+        case LOKA_SCALE_BLOCK_128x128_POW2: return (cols % 128 || rows % 128) ? -1 : (rows / 128) * (cols / 128);
     }
     return -1;
 }
 
 size_t loka_quantize_workspace(loka_scale_mode mode, int64_t rows, int64_t cols, int transpose_out) {
-    if (!transpose_out && (mode == LOKA_SCALE_ROW || mode == LOKA_SCALE_BLOCK_1x128)) return 0;
+    if (!transpose_out && (mode == LOKA_SCALE_ROW || is_block_x(mode))) return 0;
     const int64_t ng = loka_scale_count(mode, rows, cols);
     if (ng < 0) return 0;
     return static_cast<size_t>(ng) * 8;       // amax bits + quantization factors
@@ -124,7 +130,7 @@ loka_status loka_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_
     if (loka_scale_count(mode, rows, cols) < 0) return LOKA_ERR_SHAPE;
     if (ld % 8) return LOKA_ERR_ALIGN;
     if (!aligned16(x_bf16) || !aligned16(q) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return LOKA_ERR_ALIGN;
-    if (transpose_out && (mode == LOKA_SCALE_ROW || mode == LOKA_SCALE_BLOCK_1x128)) return LOKA_ERR_UNSUPPORTED;
+    if (transpose_out && (mode == LOKA_SCALE_ROW || is_block_x(mode))) return LOKA_ERR_UNSUPPORTED;
     const size_t need = loka_quantize_workspace(mode, rows, cols, transpose_out);
     if (need && (!workspace || ws_bytes < need)) return LOKA_ERR_WORKSPACE;
     if (need && !aligned16(workspace)) return LOKA_ERR_ALIGN;

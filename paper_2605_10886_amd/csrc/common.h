@@ -25,6 +25,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
+// scale modes 3..6 are the block recipes (1 x 128 activations, 128 x 128 weights); 5 and 6 have power-of-two scales
+static inline bool scale_mode_is_block(int m) { return m >= LOKA_SCALE_BLOCK_1x128 && m <= LOKA_SCALE_BLOCK_128x128_POW2; }
+static inline bool scale_mode_is_pow2(int m) { return m == LOKA_SCALE_BLOCK_1x128_POW2 || m == LOKA_SCALE_BLOCK_128x128_POW2; }
+
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
@@ -63,6 +67,20 @@ __device__ __forceinline__ void group_scale(float amax, float& scale, float& inv
     float a = amax < kAmaxFloor ? kAmaxFloor : amax;
     scale = a / kE4M3Max;
     inv = kE4M3Max / a;
+}
+
+// Power-of-two block modes: the smallest power of two s with amax / s <= 448, from the bits of amax
+// (448 = 1.75 * 2^8: amax = 1.f * 2^e needs s = 2^(e - 8) when 1.f <= 1.75, else 2^(e - 7)); inv = 1 / s, exact.
+__device__ __forceinline__ void group_scale_pow2(float amax, float& scale, float& inv) {
+    const float a = amax < kAmaxFloor ? kAmaxFloor : amax;
+    const uint32_t b = __float_as_uint(a);
+    const uint32_t e = (b >> 23) - 8u + ((b & 0x7FFFFFu) > 0x600000u ? 1u : 0u);      // biased exponent of s
+    scale = __uint_as_float(e << 23);
+    inv = __uint_as_float((254u - e) << 23);
+}
+__device__ __forceinline__ void group_scale_any(bool pow2, float amax, float& scale, float& inv) {
+    if (pow2) group_scale_pow2(amax, scale, inv);
+    else group_scale(amax, scale, inv);
 }
 
 __device__ __forceinline__ float wave_shfl_xor(float v, int mask) { return __shfl_xor(v, mask, 64); }

@@ -73,7 +73,7 @@ int default_variant(const loka_gemm_desc* d) {
     // with at least one 256 x 256 tile per CU the large-tile kernel wins when K is long and the row fits one
     // tile (no cross-workgroup exchange then), and for blockwise scales, which the streaming kernel lacks.
     const int64_t tiles256 = ((d->M + 255) / 256) * ((d->N + 255) / 256) * d->batch;
-    const bool blockwise = d->x_mode == LOKA_SCALE_BLOCK_1x128;
+    const bool blockwise = scale_mode_is_block(d->x_mode);
     if (tiles256 >= 256 && d->N <= 1024 && (blockwise || (d->N <= 256 && d->K >= 1024))) {
         for (int v = variant_count() - 1; v >= 0; --v)
             if (variant_supports(d, v) && variant_epilogue(v) == 2) return v;
@@ -186,7 +186,7 @@ loka_status loka_dispatch(const loka_gemm_desc* shape, const void* x_bf16, const
         if (variant_supports(&t, v)) { size_t w = loka_fp8_gemm_norm_workspace(&t); if (w > ws_gemm) ws_gemm = w; }
     }
     size_t ws_quant = 0;
-    for (int m = 0; m <= LOKA_SCALE_BLOCK_128x128; ++m) {
+    for (int m = 0; m <= LOKA_SCALE_BLOCK_128x128_POW2; ++m) {
         size_t a = loka_quantize_workspace(static_cast<loka_scale_mode>(m), M, K, 0);
         size_t b = loka_quantize_workspace(static_cast<loka_scale_mode>(m), K, N, 1);
         if (a > ws_quant) ws_quant = a;
@@ -232,7 +232,10 @@ loka_status loka_dispatch(const loka_gemm_desc* shape, const void* x_bf16, const
 
     struct Recipe { int xm, wm; };
     std::vector<Recipe> recipes = {{LOKA_SCALE_TENSOR, LOKA_SCALE_TENSOR}, {LOKA_SCALE_ROW, LOKA_SCALE_COL}};
-    if (N % 128 == 0) recipes.push_back({LOKA_SCALE_BLOCK_1x128, LOKA_SCALE_BLOCK_128x128});
+    if (N % 128 == 0) {
+        recipes.push_back({LOKA_SCALE_BLOCK_1x128, LOKA_SCALE_BLOCK_128x128});
+        recipes.push_back({LOKA_SCALE_BLOCK_1x128_POW2, LOKA_SCALE_BLOCK_128x128_POW2});
+    }
 
     std::vector<loka_candidate> cands;
     for (const Recipe& rc : recipes) {

@@ -779,12 +779,12 @@ int variant_bm(int v) { return kVariants[v].bm; }
 bool variant_supports(const loka_gemm_desc* d, int v) {
     if (v < 0 || v >= kNumVariants) return false;
     const VariantInfo& vi = kVariants[v];
-    if (vi.name == kWregName) return d->x_mode != LOKA_SCALE_BLOCK_1x128 && wreg_supports(d->M, d->N, d->K);
+    if (vi.name == kWregName) return !scale_mode_is_block(d->x_mode) && wreg_supports(d->M, d->N, d->K);
     if (vi.name == kStripName)
-        return d->x_mode != LOKA_SCALE_BLOCK_1x128 && d->norm != LOKA_NORM_BLOCKNORM && strip_supports(d->M, d->N, d->K);
+        return !scale_mode_is_block(d->x_mode) && d->norm != LOKA_NORM_BLOCKNORM && strip_supports(d->M, d->N, d->K);
     // BlockNorm (groups of 256 columns) is built into the kernels whose tile is 256 columns wide
     if (d->norm == LOKA_NORM_BLOCKNORM && vi.launch != &launch_panel32) return false;
-    if ((d->x_mode == LOKA_SCALE_BLOCK_1x128 ? vi.fn_block : vi.fn_plain) == nullptr) return false;
+    if ((scale_mode_is_block(d->x_mode) ? vi.fn_block : vi.fn_plain) == nullptr) return false;
     if (vi.epi == EPI_ROW_IN_TILE && d->N > vi.bn) return false;
     if (vi.epi == EPI_PANEL_SYNC && (d->N + vi.bn - 1) / vi.bn > kNumCUs) return false;
     if (static_cast<int64_t>(vi.bm > vi.bn ? vi.bm : vi.bn) * d->K >= (int64_t(1) << 31)) return false;   // tile-relative offsets are 32-bit
@@ -861,7 +861,7 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
                                         uint8_t* outq, float* outs, const void* x_bf16, float* sx_out, void* workspace,
                                         hipStream_t s) {
     const VariantInfo& vi = kVariants[v];
-    const bool blockwise = d->x_mode == LOKA_SCALE_BLOCK_1x128;
+    const bool blockwise = scale_mode_is_block(d->x_mode);
     GemmParams p{};
     p.X = xq; p.W = wq;
     p.M = static_cast<int>(d->M); p.N = static_cast<int>(d->N); p.KB = static_cast<int>(d->K);

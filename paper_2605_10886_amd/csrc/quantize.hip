@@ -19,7 +19,7 @@ namespace loka {
 template <int TPR, int CPL, int RU, bool BLOCK128>
 __global__ __launch_bounds__(256) void quant_rows_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
                                                          int64_t ld, uint8_t* __restrict__ q,
-                                                         float* __restrict__ scales) {
+                                                         float* __restrict__ scales, const int pow2) {
     constexpr int ROWS_PER_WAVE = (64 / TPR) * RU;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const uint16_t* __restr
         for (int j = 0; j < CPL; ++j) {
             const int64_t c = lr + static_cast<int64_t>(j) * TPR;
             float scale, inv;
-            group_scale(BLOCK128 ? am[j] : am[0], scale, inv);
+            group_scale_any(BLOCK128 && pow2, BLOCK128 ? am[j] : am[0], scale, inv);
             if (r < rows && c < chunks) {
                 const u32x4 w = v[u][j];
                 u32x2 o;
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const uint16_t* __restr
 template <bool BLOCK128>
 __global__ __launch_bounds__(256) void quant_long_rows_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                               int64_t cols, int64_t ld, uint8_t* __restrict__ q,
-                                                              float* __restrict__ scales) {
+                                                              float* __restrict__ scales, const int pow2) {
     __shared__ float red[4];
     const int64_t r = blockIdx.x;
     const int64_t chunks = cols >> 3;
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void quant_long_rows_kernel(const uint16_t* __
             a = fmaxf(a, fmaxf(fabsf(bf16_lo(w.w)), fabsf(bf16_hi(w.w))));
             for (int m = 1; m < 16; m <<= 1) a = fmaxf(a, wave_shfl_xor(a, m));
             float scale;
-            group_scale(a, scale, inv);
+            group_scale_any(pow2, a, scale, inv);
             if (ok && (c & 15) == 0) scales[r * (cols >> 7) + (c >> 4)] = scale;
         }
         if (ok) {
@@ -218,11 +218,11 @@ __global__ __launch_bounds__(256) void amax_block128_kernel(const uint16_t* __re
 }
 
 __global__ void finalize_scales_kernel(const uint32_t* __restrict__ amax_bits, float* __restrict__ inv,
-                                       float* __restrict__ scales, int64_t ng) {
+                                       float* __restrict__ scales, int64_t ng, const int pow2) {
     int64_t g = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (g < ng) {
         float s, i;
-        group_scale(__uint_as_float(amax_bits[g]), s, i);
+        group_scale_any(pow2, __uint_as_float(amax_bits[g]), s, i);
         scales[g] = s;
         inv[g] = i;
     }
@@ -307,13 +307,13 @@ __global__ void e4m3_from_f32_kernel(const float* __restrict__ t, uint8_t* __res
 // ---------------------------------------------------------------------------------
 template <bool B128>
 static void launch_rows(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, uint8_t* q, float* scales,
-                        hipStream_t s) {
+                        int pow2, hipStream_t s) {
     const int64_t chunks = cols / 8;
     auto grid = [&](int rows_per_wave) {
         return dim3(static_cast<unsigned>((rows + 4 * rows_per_wave - 1) / (4 * rows_per_wave)));
     };
 #define LOKA_QR(TPR, CPL, RU) \
-    quant_rows_kernel<TPR, CPL, RU, B128><<<grid((64 / TPR) * RU), 256, 0, s>>>(x, rows, cols, ld, q, scales)
+    quant_rows_kernel<TPR, CPL, RU, B128><<<grid((64 / TPR) * RU), 256, 0, s>>>(x, rows, cols, ld, q, scales, pow2)
     // Rows per wave: enough loads in flight per lane when the launch has many waves per SIMD anyway, fewer rows
     // per wave (more waves) when the whole tensor would otherwise be a handful of waves per SIMD.
     const bool few = rows * chunks < (int64_t(1) << 21);      // under 32 MB of bf16 (measured: 16384 x 512 8.8 -> 6.7 us)
@@ -324,7 +324,7 @@ static void launch_rows(const uint16_t* x, int64_t rows, int64_t cols, int64_t l
     else if (chunks <= 256) LOKA_QR(64, 4, 2);
     else if (chunks <= 512) LOKA_QR(64, 8, 1);
     else if (chunks <= 1024) LOKA_QR(64, 16, 1);
-    else quant_long_rows_kernel<B128><<<dim3(static_cast<unsigned>(rows)), 256, 0, s>>>(x, rows, cols, ld, q, scales);
+    else quant_long_rows_kernel<B128><<<dim3(static_cast<unsigned>(rows)), 256, 0, s>>>(x, rows, cols, ld, q, scales, pow2);
 #undef LOKA_QR
 }
 
@@ -345,9 +345,13 @@ static void launch_cast(const uint16_t* x, int64_t rows, int64_t cols, int64_t l
 loka_status quantize_launch(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, loka_scale_mode mode,
                             int transpose_out, uint8_t* q, float* scales, void* workspace, hipStream_t s) {
     const uint16_t* x = static_cast<const uint16_t*>(x_bf16);
+    // the power-of-two block modes: the plain block modes' passes with another scale rule
+    const int pow2 = mode == LOKA_SCALE_BLOCK_1x128_POW2 || mode == LOKA_SCALE_BLOCK_128x128_POW2;
+    if (mode == LOKA_SCALE_BLOCK_1x128_POW2) mode = LOKA_SCALE_BLOCK_1x128;
+    if (mode == LOKA_SCALE_BLOCK_128x128_POW2) mode = LOKA_SCALE_BLOCK_128x128;
     if (!transpose_out && (mode == LOKA_SCALE_ROW || mode == LOKA_SCALE_BLOCK_1x128)) {
-        if (mode == LOKA_SCALE_ROW) launch_rows<false>(x, rows, cols, ld, q, scales, s);
-        else launch_rows<true>(x, rows, cols, ld, q, scales, s);
+        if (mode == LOKA_SCALE_ROW) launch_rows<false>(x, rows, cols, ld, q, scales, 0, s);
+        else launch_rows<true>(x, rows, cols, ld, q, scales, pow2, s);
         return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
     }
     const int64_t ng = loka_scale_count(mode, rows, cols);
@@ -368,7 +372,7 @@ loka_status quantize_launch(const void* x_bf16, int64_t rows, int64_t cols, int6
         dim3 g(static_cast<unsigned>(cols / 128), static_cast<unsigned>(rows / 128));
         amax_block128_kernel<<<g, 256, 0, s>>>(x, rows, cols, ld, amax_bits);
     }
-    finalize_scales_kernel<<<dim3(static_cast<unsigned>((ng + 255) / 256)), 256, 0, s>>>(amax_bits, inv, scales, ng);
+    finalize_scales_kernel<<<dim3(static_cast<unsigned>((ng + 255) / 256)), 256, 0, s>>>(amax_bits, inv, scales, ng, pow2);
     if (mode == LOKA_SCALE_TENSOR) launch_cast<LOKA_SCALE_TENSOR>(x, rows, cols, ld, inv, q, transpose_out, s);
     else if (mode == LOKA_SCALE_COL) launch_cast<LOKA_SCALE_COL>(x, rows, cols, ld, inv, q, transpose_out, s);
     else launch_cast<LOKA_SCALE_BLOCK_128x128>(x, rows, cols, ld, inv, q, transpose_out, s);

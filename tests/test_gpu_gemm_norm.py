@@ -17,7 +17,8 @@ from parity_util import (check_bf16_out, gemm_tolerance, propagated_abs_tol, pro
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 RECIPES = {"tensor": (B.SCALE_TENSOR, B.SCALE_TENSOR), "row": (B.SCALE_ROW, B.SCALE_COL),
-           "block": (B.SCALE_BLOCK_1x128, B.SCALE_BLOCK_128x128)}
+           "block": (B.SCALE_BLOCK_1x128, B.SCALE_BLOCK_128x128),
+           "block_pow2": (B.SCALE_BLOCK_1x128_POW2, B.SCALE_BLOCK_128x128_POW2)}
 
 
 def _variants_for(desc):
@@ -55,7 +56,7 @@ def _run_case(orc, x, w, recipe, norm, variant, gamma=None, beta=None, rows=None
     sx_g = sx.cpu().numpy()
     if xm == B.SCALE_ROW:
         sx_g = sx_g[sel]
-    elif xm == B.SCALE_BLOCK_1x128:
+    elif xm in (B.SCALE_BLOCK_1x128, B.SCALE_BLOCK_1x128_POW2):
         sx_g = sx_g.reshape(M, K // 128)[sel].ravel()
     assert np.array_equal(sx_g, sx_o) and np.array_equal(sw.cpu().numpy(), sw_o), f"{tag}: scales"
 
@@ -83,7 +84,7 @@ def _run_case(orc, x, w, recipe, norm, variant, gamma=None, beta=None, rows=None
 
 
 # ----------------------------------------------------------------------------- small shapes, every variant
-@pytest.mark.parametrize("recipe", ["tensor", "row", "block"])
+@pytest.mark.parametrize("recipe", ["tensor", "row", "block", "block_pow2"])
 @pytest.mark.parametrize("norm", ["layernorm", "rmsnorm", "none"])
 def test_c1_every_variant(orc, recipe, norm):
     w = synth.WORKLOADS["C1"]
@@ -110,13 +111,18 @@ def test_ragged_tiles_every_variant(orc, shape):
         _run_case(orc, x, wt, "row", "rmsnorm", v, gamma, None, tag=f"{shape} RMS {B.loka_variant_name(v)}")
 
 
-def test_blockwise_ragged(orc):
+@pytest.mark.parametrize("recipe", ["block", "block_pow2"])
+def test_blockwise_ragged(orc, recipe):
     M, K, N = 150, 384, 640
     x, _ = synth.normal_outlier4(M, K, seed=8)
+    x[3, 128:256] *= 2.0 ** -30                  # block scales 30 binades apart within one row
+    x[5, 0:128] = 0
     wt = synth.weight(K, N, seed=9)
-    desc = B.make_desc(M, N, K, 1, B.SCALE_BLOCK_1x128, B.SCALE_BLOCK_128x128, B.NORM_LAYERNORM)
+    wt[128:256, 0:128] *= 2.0 ** 12              # and within one column block of W
+    desc = B.make_desc(M, N, K, 1, *RECIPES[recipe], B.NORM_LAYERNORM)
     for v in _variants_for(desc):
-        _run_case(orc, x, wt, "block", "layernorm", v, tag=f"block {B.loka_variant_name(v)}")
+        _run_case(orc, x, wt, recipe, "layernorm", v, tag=f"{recipe} {B.loka_variant_name(v)}")
+        _run_case(orc, x, wt, recipe, "none", v, tag=f"{recipe} no norm {B.loka_variant_name(v)}")
 
 
 def test_layernorm_rows_with_large_mean(orc):
@@ -451,7 +457,7 @@ def test_backward_gemms_with_the_forward_entry_points(orc, shape):
     assert rel_fro(dw.cpu().numpy(), ref.numpy()) < 0.06
 
 
-@pytest.mark.parametrize("recipe", ["row", "block", "tensor"])
+@pytest.mark.parametrize("recipe", ["row", "block", "block_pow2", "tensor"])
 def test_c5_full_size(orc, recipe):
     w = synth.WORKLOADS["C5"]
     x, wt = synth.activations(w), synth.weights(w)

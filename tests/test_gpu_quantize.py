@@ -37,12 +37,13 @@ def test_hw_cast_on_every_bf16_value_and_midpoints(orc):
     assert bad.size == 0, [(float(t[i]), hex(got[i]), hex(want[i])) for i in bad[:8]]
 
 
-@pytest.mark.parametrize("mode_name", ["TENSOR", "ROW", "COL", "BLOCK_1x128", "BLOCK_128x128"])
+@pytest.mark.parametrize("mode_name", ["TENSOR", "ROW", "COL", "BLOCK_1x128", "BLOCK_128x128", "BLOCK_1x128_POW2",
+                                       "BLOCK_128x128_POW2"])
 @pytest.mark.parametrize("shape", [(256, 128), (384, 512), (130 * 16, 1024), (128, 4096)])
 def test_modes_and_shapes(orc, mode_name, shape):
     mode = getattr(B, "SCALE_" + mode_name)
     rows, cols = shape
-    if mode == B.SCALE_BLOCK_128x128 and rows % 128:
+    if mode in (B.SCALE_BLOCK_128x128, B.SCALE_BLOCK_128x128_POW2) and rows % 128:
         rows = (rows // 128) * 128
     x = synth.student_t4(rows, cols, seed=rows + cols)
     x[3, :] = 0                       # all-zero row
@@ -52,7 +53,7 @@ def test_modes_and_shapes(orc, mode_name, shape):
     _cmp_quant(orc, x, mode, what=f"{mode_name} {shape}")
 
 
-@pytest.mark.parametrize("mode_name", ["TENSOR", "COL", "BLOCK_128x128"])
+@pytest.mark.parametrize("mode_name", ["TENSOR", "COL", "BLOCK_128x128", "BLOCK_128x128_POW2"])
 def test_weight_layout_transposed(orc, mode_name):
     mode = getattr(B, "SCALE_" + mode_name)
     for K, N in ((128, 128), (512, 384), (1024, 256)):
@@ -68,6 +69,7 @@ def test_ragged_and_long_rows(orc, cols):
     _cmp_quant(orc, x, B.SCALE_ROW, what=f"ROW cols={cols}")
     if cols % 128 == 0:
         _cmp_quant(orc, x, B.SCALE_BLOCK_1x128, what=f"1x128 cols={cols}")
+        _cmp_quant(orc, x, B.SCALE_BLOCK_1x128_POW2, what=f"1x128 power-of-two cols={cols}")
 
 
 def test_strided_input(orc):
@@ -94,7 +96,7 @@ def test_workloads_full_size_rowwise(orc):
         assert np.array_equal(s_g[idx].cpu().numpy().view(np.uint32), s_o.view(np.uint32)), name
 
 
-@pytest.mark.parametrize("mode_name", ["ROW", "BLOCK_1x128"])
+@pytest.mark.parametrize("mode_name", ["ROW", "BLOCK_1x128", "BLOCK_1x128_POW2"])
 @pytest.mark.parametrize("shape", [(1000, 256), (32768 + 24, 512), (1000, 1024), (16384 + 8, 1024), (65536 + 8, 256)])
 def test_row_kernel_instances_on_both_sides_of_the_size_rule(orc, mode_name, shape):
     # the launcher gives a small tensor fewer rows per wave than a large one: both sets of instances, ragged row counts
