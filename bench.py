@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # file, scaled by a plain 1 GiB copy (profiles/bench_C5_panel32_256x256.md); counters cannot be read in-process.
 MEASURED_TRAFFIC_BYTES = {("C5", "panel32_256x256"): 1.241e9 + 0.354e9}
 
-RECIPE_NAMES = {(0, 0): "tensor/tensor", (1, 2): "row/col", (3, 4): "1x128/128x128"}
+RECIPE_NAMES = {(0, 0): "tensor/tensor", (1, 2): "row/col", (3, 4): "1x128/128x128", (5, 6): "1x128/128x128 power-of-two scales"}
 
 
 def _event_times(fn, steps, stream):
@@ -275,10 +275,7 @@ def main():
         n_s = max(16, min(M, int(3e11 // (K * N))))          # ~300 GMAC of fp64 scalar work: 10-20 s on 16 cores
         xb = synth.bf16_bits(x_cpu[:M])[:n_s].copy()
         wb = synth.bf16_bits(w_cpu[:K])
-        o_xm, o_wm = (oracle.SCALE_ROW, oracle.SCALE_COL) if xm != B.SCALE_BLOCK_1x128 else (
-            oracle.SCALE_BLOCK_1x128, oracle.SCALE_BLOCK_128x128)
-        if xm == B.SCALE_TENSOR:
-            o_xm, o_wm = oracle.SCALE_TENSOR, oracle.SCALE_TENSOR
+        o_xm, o_wm = xm, wm                                   # (the two libraries number the scale modes alike)
         wq_o, sw_o = oracle.quantize(wb, o_wm, transpose_out=True)       # weights: offline, as on the GPU
         thr = oracle.default_threads()
         c0 = time.perf_counter()

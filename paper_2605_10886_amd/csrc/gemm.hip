@@ -718,10 +718,14 @@ static const char kStripName[] = "strip32";
 static const char kPanel32Name[] = "panel32_256x256";
 
 // gemm_panel32.hip
-const void* panel32_fn(bool blockwise);
+const void* panel32_fn(int bw);
 size_t panel32_lds();
-void panel32_launch(const GemmParams& p, bool blockwise, dim3 grid, hipStream_t s);
-static void launch_panel32(const GemmParams& p, bool blockwise, dim3 grid, hipStream_t s) { panel32_launch(p, blockwise, grid, s); }
+void panel32_launch(const GemmParams& p, int bw, dim3 grid, hipStream_t s);
+// block scales: power-of-two ones go to the matrix cores, others rescale the accumulators
+static int panel32_bw(const GemmParams& p, bool blockwise) { return !blockwise ? 0 : scale_mode_is_pow2(p.x_mode) ? 2 : 1; }
+static void launch_panel32(const GemmParams& p, bool blockwise, dim3 grid, hipStream_t s) {
+    panel32_launch(p, panel32_bw(p, blockwise), grid, s);
+}
 
 #define LOKA_VARIANT(NAME, BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, EPI)                                        \
     {NAME, BM, BN_SUB * NSPLIT, WAVES_M * WAVES_N * 64, EPI, 2 * (BM * 128 + BN_SUB * 128),                  \
@@ -751,7 +755,7 @@ static const VariantInfo kVariants[] = {
     // through a few words of global memory and normalize their own tile in registers
     LOKA_VARIANT("panel256x256w8", 256, 256, 1, 2, 4, EPI_PANEL_SYNC),
     // the same schedule on 32x32x64 MFMAs: the throughput variant
-    {kPanel32Name, 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(false), panel32_fn(true)},
+    {kPanel32Name, 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(0), panel32_fn(1)},
 };
 constexpr int kNumCUs = 256;          // MI355X; the launch re-checks against the device it runs on
 constexpr unsigned kSpinLimit = 1u << 18;   // x s_sleep(16) ~ 0.1 s: far beyond any main loop
@@ -910,12 +914,14 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         vi.launch(p, false, dim3(static_cast<unsigned>(wgs)), s);
         return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
     }
-    if (set_lds(blockwise ? vi.fn_block : vi.fn_plain, vi.lds) != LOKA_OK) return LOKA_ERR_HIP;
+    const void* kfn = blockwise ? vi.fn_block : vi.fn_plain;
+    if (vi.name == kPanel32Name) kfn = panel32_fn(panel32_bw(p, blockwise));
+    if (set_lds(kfn, vi.lds) != LOKA_OK) return LOKA_ERR_HIP;
     dim3 grid(static_cast<unsigned>(static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.batch));
     if (vi.epi == EPI_PANEL_SYNC) {
         // persistent grid: a multiple of tiles_n workgroups, all resident at once (one per CU)
         int cus = 0, per_cu = 0;
-        if (resident_capacity(blockwise ? vi.fn_block : vi.fn_plain, vi.threads, vi.lds, &cus, &per_cu) != LOKA_OK)
+        if (resident_capacity(kfn, vi.threads, vi.lds, &cus, &per_cu) != LOKA_OK)
             return LOKA_ERR_HIP;
         const int64_t slots = static_cast<int64_t>(cus) * (per_cu > 0 ? 1 : 0);
         int64_t g = (slots / p.tiles_n) * p.tiles_n;

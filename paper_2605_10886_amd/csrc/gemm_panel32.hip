@@ -25,8 +25,11 @@ namespace loka {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-template <int EPI, bool BLOCKWISE>
+// BW: 0 = one scale per row / column / tensor (applied in the epilogue); 1 = block scales, accumulators rescaled
+// per K block; 2 = power-of-two block scales handed to the matrix cores (scaled MFMA), nothing to rescale.
+template <int EPI, int BW>
 __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
+    constexpr bool BLOCKWISE = BW != 0;
     constexpr int BM = 256, BN = 256, NW = 8, WM = 128, WN = 64, MI = 4, NI = 2;
     constexpr int ES = 256 * 128;           // one ring entry: 256 rows x 128 bytes of X or of W
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
@@ -127,29 +130,45 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     // there).  One extra fp32 rounding of the running sum per K step (and a 1-ulp reciprocal in the ratio):
     // K / 128 * 2^-23 relative to sum |terms|, two orders below the matrix pipe's own truncation.
     // The scales of block k + 1 are fetched at the start of step k.
+    // Power-of-two block scales (BW == 2): every scale is 2^(e - 127) with e its fp32 exponent field, which is the
+    // 8-bit scale format of the scaled MFMA: the instruction multiplies the products of a 32-element K run by
+    // 2^(ea - 127) * 2^(eb - 127), ea / eb taken from the lane that holds the run.  A lane's X fragment is one
+    // row's run (scale of that row and K block), a W fragment's 32 rows lie in one 128-column block (one scale
+    // for the wave).  The accumulators then hold the scaled sum itself and the epilogue multiplies by nothing.
     float s_cur[MI], r_sc[MI], sx_nx[MI], sw_nx = 0.f;
+    int sc_x[MI], sc_w = 127;
     const int bw_nb = ((n0 + wave_n * WN < p.N ? n0 + wave_n * WN : p.N - 1) >> 7), bw_nblk = p.N >> 7;
     auto bw_row = [&](int mi) __attribute__((always_inline)) {
         const int m = m0 + wave_m * WM + mi * 32 + l32;
         return static_cast<int64_t>(m < p.M ? m : p.M - 1) * ksteps;
     };
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) { s_cur[mi] = 1.f; r_sc[mi] = 1.f; sx_nx[mi] = 1.f; }
-    if (BLOCKWISE) {
+    for (int mi = 0; mi < MI; ++mi) { s_cur[mi] = 1.f; r_sc[mi] = 1.f; sx_nx[mi] = 1.f; sc_x[mi] = 127; }
+    if (BW == 1) {
         const float sw0 = swg[bw_nb];
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) s_cur[mi] = sxg[bw_row(mi)] * sw0;
     }
+    if (BW == 2) {
+        sc_w = static_cast<int>(__float_as_uint(swg[bw_nb]) >> 23);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) sc_x[mi] = static_cast<int>(__float_as_uint(sxg[bw_row(mi)]) >> 23);
+    }
     // ratio for the step that begins (its scales were fetched one step earlier), then the fetch for the next one
     auto bw_step = [&](int k) __attribute__((always_inline)) {
         if (!BLOCKWISE) return;
-        if (k >= 1) {
+        if (k >= 1 && BW == 1) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
                 const float s_new = sx_nx[mi] * sw_nx;
                 r_sc[mi] = s_cur[mi] * __builtin_amdgcn_rcpf(s_new);
                 s_cur[mi] = s_new;
             }
+        }
+        if (k >= 1 && BW == 2) {
+            sc_w = static_cast<int>(__float_as_uint(sw_nx) >> 23);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) sc_x[mi] = static_cast<int>(__float_as_uint(sx_nx[mi]) >> 23);
         }
         if (k + 1 < ksteps) {
             sw_nx = swg[static_cast<int64_t>(k + 1) * bw_nblk + bw_nb];
@@ -177,7 +196,11 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         bx[mi] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     };
     auto mfma_one = [&](int mi, int ni, int set) __attribute__((always_inline)) {
-        acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(aw[set][ni], bx[mi], acc[mi][ni], 0, 0, 0, 0, 0, 0);
+        if (BW == 2)
+            acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(aw[set][ni], bx[mi], acc[mi][ni], 0, 0, 0, sc_w, 0,
+                                                                         sc_x[mi]);
+        else
+            acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(aw[set][ni], bx[mi], acc[mi][ni], 0, 0, 0, 0, 0, 0);
     };
     auto mfma_row = [&](int mi, int set) __attribute__((always_inline)) {
 #pragma unroll
@@ -195,7 +218,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         read_w(SLOT_W, S_READ, (SET) ^ 1);                                           \
         _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) {                          \
             __builtin_amdgcn_sched_barrier(0);                                       \
-            if (BLOCKWISE && (RESC)) {                                               \
+            if (BW == 1 && (RESC)) {                                                 \
                 _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                    \
                     _Pragma("unroll") for (int i = 0; i < 16; ++i) acc[mi][ni][i] *= r_sc[mi]; \
             }                                                                        \
@@ -298,7 +321,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     for (int mi = 0; mi < MI; ++mi) {
         int m = m0 + wave_m * WM + mi * 32 + l32;
         m = m < p.M ? m : p.M - 1;
-        sxm[mi] = BLOCKWISE ? s_cur[mi] : tensor_x ? sxg[0] : sxg[m];
+        sxm[mi] = BW == 1 ? s_cur[mi] : BW == 2 ? 1.f : tensor_x ? sxg[0] : sxg[m];
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -573,14 +596,17 @@ extern "C" int loka_debug_read_times32(unsigned long long* host, int n) {
 
 constexpr size_t kPanel32Lds = 5 * 256 * 128;   // the ring; the epilogue's scratch aliases it
 
-const void* panel32_fn(bool blockwise) {
-    return blockwise ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, true>)
-                     : reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, false>);
+// bw: 0 plain scales, 1 block scales, 2 power-of-two block scales (see the kernel)
+const void* panel32_fn(int bw) {
+    return bw == 2   ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 2>)
+           : bw == 1 ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 1>)
+                     : reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0>);
 }
 size_t panel32_lds() { return kPanel32Lds; }
-void panel32_launch(const GemmParams& p, bool blockwise, dim3 grid, hipStream_t s) {
-    if (blockwise) gemm_panel32_kernel<EPI_PANEL_SYNC, true><<<grid, 512, kPanel32Lds, s>>>(p);
-    else gemm_panel32_kernel<EPI_PANEL_SYNC, false><<<grid, 512, kPanel32Lds, s>>>(p);
+void panel32_launch(const GemmParams& p, int bw, dim3 grid, hipStream_t s) {
+    if (bw == 2) gemm_panel32_kernel<EPI_PANEL_SYNC, 2><<<grid, 512, kPanel32Lds, s>>>(p);
+    else if (bw == 1) gemm_panel32_kernel<EPI_PANEL_SYNC, 1><<<grid, 512, kPanel32Lds, s>>>(p);
+    else gemm_panel32_kernel<EPI_PANEL_SYNC, 0><<<grid, 512, kPanel32Lds, s>>>(p);
 }
 
 }  // namespace loka
