@@ -92,8 +92,9 @@ int64_t loka_scale_count(loka_scale_mode mode, int64_t rows, int64_t cols);
  *   scales   [loka_scale_count(mode, rows, cols)] fp32, group order: row-major over
  *            (row group, column group)
  *   cols must be a multiple of 16 (rows too when transpose_out != 0).
- * Workspace: loka_quantize_workspace() bytes (0 for ROW and BLOCK_1x128 without
- * transpose); contents are scratch.  */
+ * Workspace: loka_quantize_workspace() bytes (0 for ROW and the two BLOCK_1x128 modes without
+ * transpose); contents are scratch.  transpose_out is not supported for ROW and the BLOCK_1x128 modes
+ * (LOKA_ERR_UNSUPPORTED).  The power-of-two modes replace the two divisions by the rule stated at the enum. */
 size_t loka_quantize_workspace(loka_scale_mode mode, int64_t rows, int64_t cols, int transpose_out);
 loka_status loka_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, loka_scale_mode mode,
                           int transpose_out, uint8_t* q, float* scales, void* workspace, size_t ws_bytes,
@@ -113,6 +114,8 @@ loka_status loka_e4m3_from_f32(const float* t, uint8_t* codes, int64_t n, void* 
  *            = sum_kb acc_kb * sx[m,kb] * sw[kb, n/128]   BLOCK_1x128 x BLOCK_128x128: each
  *                                                         128-wide K block is promoted to an
  *                                                         fp32 accumulator with its scales
+ *                                                         (the _POW2 modes: same sum; x_mode and
+ *                                                         w_mode must both be _POW2 or neither)
  *   O[m,n]   = bf16_rne( LayerNorm / RMSNorm / identity over the N entries of row m )
  *     LayerNorm: (Y-mu)/sqrt(var+eps)*gamma+beta, biased variance;  RMSNorm: Y/sqrt(mean(Y^2)+eps)*gamma.
  *     BlockNorm: Y/sqrt(mean over the element's group of block_n columns (Y^2)+eps), then the activation;
