@@ -89,6 +89,14 @@ def test_gemm_argument_validation():
     assert _gemm(B.make_desc(256, 128, 128, x_mode=B.SCALE_COL)) == B.LOKA_ERR_UNSUPPORTED
     assert _gemm(B.make_desc(256, 128, 128, x_mode=B.SCALE_BLOCK_1x128)) == B.LOKA_ERR_UNSUPPORTED   # needs 128x128 W
     assert _gemm(B.make_desc(256, 144, 128, x_mode=B.SCALE_BLOCK_1x128, w_mode=B.SCALE_BLOCK_128x128)) == B.LOKA_ERR_SHAPE
+    # power-of-two block scales: on both operands or on neither
+    assert _gemm(B.make_desc(256, 128, 128, x_mode=B.SCALE_BLOCK_1x128_POW2, w_mode=B.SCALE_BLOCK_128x128)) == B.LOKA_ERR_UNSUPPORTED
+    assert _gemm(B.make_desc(256, 128, 128, x_mode=B.SCALE_BLOCK_1x128, w_mode=B.SCALE_BLOCK_128x128_POW2)) == B.LOKA_ERR_UNSUPPORTED
+    assert _gemm(B.make_desc(256, 128, 128, x_mode=B.SCALE_ROW, w_mode=B.SCALE_BLOCK_128x128_POW2)) == B.LOKA_ERR_UNSUPPORTED
+    assert _gemm(B.make_desc(256, 128, 128, x_mode=7)) == B.LOKA_ERR_UNSUPPORTED
+    assert B.loka_scale_count(B.SCALE_BLOCK_1x128_POW2, 256, 512) == 256 * 4
+    assert B.loka_scale_count(B.SCALE_BLOCK_128x128_POW2, 256, 512) == 2 * 4
+    assert B.loka_scale_count(B.SCALE_BLOCK_128x128_POW2, 200, 512) == -1
     assert _gemm(B.make_desc(256, 128, 128, norm=5)) == B.LOKA_ERR_UNSUPPORTED
     assert _gemm(good, xq=ODD) == B.LOKA_ERR_ALIGN
     narrow = B.make_desc(256, 512, 128, variant=B.variant_id("row64x128"))  # tile narrower than the row
