@@ -758,7 +758,7 @@ static const VariantInfo kVariants[] = {
     {kPanel32Name, 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(0), panel32_fn(1)},
 };
 constexpr int kNumCUs = 256;          // MI355X; the launch re-checks against the device it runs on
-constexpr unsigned kSpinLimit = 1u << 18;   // x s_sleep(16) ~ 0.1 s: far beyond any main loop
+constexpr unsigned kSpinLimit = 1u << 18;   // polls of ~1 us each (a device-scope load and a short sleep): far beyond any main loop
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 #ifdef LOKA_DEBUG_TIMES

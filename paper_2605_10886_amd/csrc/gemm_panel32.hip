@@ -449,7 +449,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 unsigned spins = 0;
                 while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < static_cast<unsigned>(p.tiles_n)) {
-                    __builtin_amdgcn_s_sleep(16);
+                    __builtin_amdgcn_s_sleep(2);          // (measured: 16 costs 2 % of the kernel at 32768 x 4096 x 4096, 0 gains nothing more)
                     if (++spins > p.spin_limit) {
                         __hip_atomic_store(p.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         break;
