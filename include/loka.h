@@ -181,12 +181,15 @@ loka_status loka_fp8_gemm_norm_fp8out(const loka_gemm_desc* desc, const uint8_t*
 /* Quantization fused into the layer (Section 2.3, "Throughput Analysis": quantization overhead can exceed 30 % of
  * the GEMM's latency, and memory traffic for the low-precision copy can cancel the gain; Section 3.2: activation
  * and (de)quantization can be fused).  One call = loka_quantize(x, LOKA_SCALE_ROW) followed by loka_fp8_gemm_norm,
- * with identical bits in every output, but the e4m3 copy of X never exists in HBM: the streaming skinny-layer kernel
- * reads bf16 rows, takes the row amax, scales, converts and multiplies.
+ * with identical bits in every output (the same kernel variant in both), but the e4m3 copy of X never exists in
+ * HBM: a kernel that keeps whole rows of X in one workgroup reads bf16 rows, takes the row amax, scales, converts
+ * and multiplies.
  *   x_bf16 [batch][M, K] bf16 (strideX in elements), desc->x_mode must be LOKA_SCALE_ROW; wq, sw, gamma, beta,
  *   out_bf16, y_fp32 as in loka_fp8_gemm_norm;  sx_out: fp32 [batch][M] row scales (amax / 448) or NULL.
- * Built for the shapes the streaming kernel covers (N <= 1024, K in {128, 256, 512, 1024}, K * N <= 256 KB);
- * LOKA_ERR_UNSUPPORTED otherwise (use the two calls).  No workspace. */
+ * Two kernels take it: the small-layer strip kernel (variant "strip32": N <= 256, K in {128, 256, 512}, W resident
+ * in LDS) and the streaming skinny-layer kernel ("wreg32": N <= 1024, K in {128, 256, 512, 1024}, K * N < 256 KB).
+ * desc->variant names one, or -1: the strip kernel where it applies, else the streaming kernel.
+ * LOKA_ERR_UNSUPPORTED for every other shape or variant (use the two calls).  No workspace. */
 loka_status loka_fp8_linear_norm(const loka_gemm_desc* desc, const void* x_bf16, const uint8_t* wq, const float* sw,
                                  const void* gamma_bf16, const void* beta_bf16, void* out_bf16, float* y_fp32,
                                  float* sx_out, void* hip_stream);

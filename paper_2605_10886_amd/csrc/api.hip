@@ -18,6 +18,8 @@ size_t variant_workspace(const loka_gemm_desc*, int);
 loka_status fp8_gemm_norm_launch(const loka_gemm_desc*, int, const uint8_t*, const float*, const uint8_t*, const float*,
                                  const void*, const void*, void*, float*, uint8_t*, float*, void*, hipStream_t);
 int variant_streaming_id();
+bool variant_supports_fused(const loka_gemm_desc*, int);
+int variant_fused_default(const loka_gemm_desc*);
 loka_status fp8_linear_norm_launch(const loka_gemm_desc*, int, const void*, const uint8_t*, const float*, const void*,
                                    const void*, void*, float*, float*, hipStream_t);
 bool variant_has_wait_flag(const loka_gemm_desc*, int);
@@ -186,9 +188,9 @@ loka_status loka_fp8_linear_norm(const loka_gemm_desc* desc, const void* x_bf16,
     if (!aligned16(x_bf16) || !aligned16(wq) || !aligned16(sw) || !aligned16(out_bf16) || !aligned16(y_fp32) ||
         !aligned16(gamma_bf16) || !aligned16(beta_bf16) || !aligned16(sx_out))
         return LOKA_ERR_ALIGN;
-    // the streaming kernel keeps whole rows of X in one workgroup: the row amax needs no second pass
-    const int v = variant_streaming_id();
-    if (v < 0 || !variant_supports(desc, v) || (desc->variant >= 0 && desc->variant != v)) return LOKA_ERR_UNSUPPORTED;
+    // kernels that keep whole rows of X in one workgroup (strip32, wreg32): the row amax needs no second pass
+    const int v = desc->variant >= 0 ? desc->variant : variant_fused_default(desc);
+    if (v < 0 || !variant_supports_fused(desc, v)) return LOKA_ERR_UNSUPPORTED;
     return fp8_linear_norm_launch(desc, v, x_bf16, wq, sw, gamma_bf16, beta_bf16, out_bf16, y_fp32, sx_out,
                                   static_cast<hipStream_t>(hip_stream));
 }

@@ -711,7 +711,8 @@ static const char kWregName[] = "wreg32";
 
 // gemm_strip.hip
 bool strip_supports(int64_t M, int64_t N, int64_t K);
-int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, const void** fn, size_t* lds);
+bool strip_supports_fused(int64_t M, int64_t N, int64_t K);
+int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool bf16_in, const void** fn, size_t* lds);
 void strip_launch(const GemmParams& p, dim3 grid, hipStream_t s);
 static void launch_strip_any(const GemmParams& p, bool, dim3 grid, hipStream_t s) { strip_launch(p, grid, s); }
 static const char kStripName[] = "strip32";
@@ -770,6 +771,25 @@ extern "C" int loka_debug_read_times(unsigned long long* host, int n) {
 int variant_count() { return kNumVariants; }
 const char* variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
 int variant_epilogue(int v) { return kVariants[v].epi; }
+bool variant_supports(const loka_gemm_desc* d, int v);
+// kernels that can take bf16 X and quantize it per row themselves (loka_fp8_linear_norm)
+bool variant_supports_fused(const loka_gemm_desc* d, int v) {
+    if (v < 0 || v >= kNumVariants || !variant_supports(d, v) || d->x_mode != LOKA_SCALE_ROW) return false;
+    if (kVariants[v].name == kWregName) return wreg_supports_fused(d->M, d->N, d->K);
+    if (kVariants[v].name == kStripName) return strip_supports_fused(d->M, d->N, d->K);
+    return false;
+}
+// the kernel the fused entry point uses when the caller names none: the strip kernel where it applies (waves that
+// never synchronize, one strip each), else the streaming kernel
+int variant_fused_default(const loka_gemm_desc* d) {
+    int wreg = -1;
+    for (int v = 0; v < kNumVariants; ++v) {
+        if (!variant_supports_fused(d, v)) continue;
+        if (kVariants[v].name == kStripName) return v;
+        wreg = v;
+    }
+    return wreg;
+}
 int variant_streaming_id() {
     for (int v = 0; v < kNumVariants; ++v)
         if (kVariants[v].name == kWregName) return v;
@@ -856,7 +876,7 @@ loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* 
 // bf16 X quantized row by row inside the streaming kernel (v must be that variant)
 loka_status fp8_linear_norm_launch(const loka_gemm_desc* d, int v, const void* x_bf16, const uint8_t* wq, const float* sw,
                                    const void* gamma, const void* beta, void* out, float* y, float* sx_out, hipStream_t s) {
-    if (kVariants[v].name != kWregName || !wreg_supports_fused(d->M, d->N, d->K)) return LOKA_ERR_UNSUPPORTED;
+    if (!variant_supports_fused(d, v)) return LOKA_ERR_UNSUPPORTED;
     return gemm_norm_launch_impl(d, v, nullptr, nullptr, wq, sw, gamma, beta, out, y, nullptr, nullptr, x_bf16, sx_out, nullptr, s);
 }
 
@@ -908,7 +928,7 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         size_t lds = 0;
         LOKA_HIP_TRY(hipGetDevice(&dev));
         LOKA_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        const int wgs = strip_plan(d->M, d->N, d->K, d->batch, cus, &fn, &lds);
+        const int wgs = strip_plan(d->M, d->N, d->K, d->batch, cus, p.xb != nullptr, &fn, &lds);
         if (wgs <= 0) return LOKA_ERR_UNSUPPORTED;
         if (set_lds(fn, lds) != LOKA_OK) return LOKA_ERR_HIP;
         vi.launch(p, false, dim3(static_cast<unsigned>(wgs)), s);

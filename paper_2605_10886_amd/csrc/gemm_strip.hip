@@ -44,9 +44,15 @@ struct StripCfg {
     static_assert(LDS <= 160 * 1024, "W, the tables and the staging buffers must fit the LDS");
 };
 
-template <int NB, int KS, int NPH>
-__global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, const int strips_per_problem) {
+// NWV waves per workgroup; BF16IN: X arrives as bf16 and is quantized per row (amax, scale, e4m3 cast: the
+// arithmetic of the quantize kernel, bit for bit) on its way into the MFMA operand registers, so the FP8 copy of X
+// never exists in memory (Section 3.2: quantization fused with the layer).  A strip's 32 x K bf16 values are a
+// second set of 16 KS registers per lane that must stay live through the previous strip's epilogue: those
+// instances run with 4 waves of up to 512 registers instead of 8 of 256.
+template <int NB, int KS, int NPH, int NWV, bool BF16IN>
+__global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p, const int strips_per_problem) {
     using C = StripCfg<NB, KS, NPH>;
+    static_assert(!BF16IN || NPH == 1, "fused quantization needs the whole row of X in one pass");
     constexpr int NT = C::NT, KB = C::KB, KBT = C::KBT, KEYMASK = C::SWIN - 1;
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
@@ -77,7 +83,7 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
         const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint8_t*>(p.W + static_cast<int64_t>(g) * p.strideW), 0, static_cast<unsigned>(p.N) * KBT, 0x00020000);
         auto load_w = [&](int ph) __attribute__((always_inline)) {
-            for (int ld = wave; ld < NT * KB / 1024; ld += 8) {
+            for (int ld = wave; ld < NT * KB / 1024; ld += NWV) {
                 const int byte = ld * 1024 + lane * 16;
                 const int row = byte / KB, pos = (byte % KB) >> 4;
                 // rows past N lie behind the descriptor's bound (the offset is the per-lane one) and read as zeros
@@ -90,7 +96,7 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
             float* swl = reinterpret_cast<float*>(smem + C::OFF_SW);
             float* gml = reinterpret_cast<float*>(smem + C::OFF_GM);
             float* btl = reinterpret_cast<float*>(smem + C::OFF_BT);
-            for (int n = threadIdx.x; n < NT; n += 512) {
+            for (int n = threadIdx.x; n < NT; n += NWV * 64) {
                 const bool in = n < p.N;
                 swl[n] = in ? (tensor_w ? swg[0] : swg[n]) : 0.f;
                 gml[n] = (in && p.gamma && p.norm != LOKA_NORM_NONE) ? bf16_bits_to_f32(p.gamma[n]) : 1.f;
@@ -120,6 +126,52 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
                 x[j] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
             }
             sxm = tensor_x ? sxg[0] : (m < p.M ? sxg[m] : 0.f);
+        };
+
+        // Fused quantization: the lane's 32 bf16 values per K step (row m0 + l32, K elements [64 j + 32 hk, +32): 64
+        // bytes, four loads), then row amax (integer max of the magnitudes, this lane and lane ^ 32 hold the row),
+        // scale pair, cast.  Rows past M read as zeros.
+        const __amdgpu_buffer_rsrc_t xbr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(BF16IN ? p.xb + static_cast<int64_t>(g) * p.strideX : nullptr), 0,
+            static_cast<unsigned>(p.M) * KBT * 2u, 0x00020000);
+        auto load_raw = [&](int s, u32x4 (&raw)[KS][4]) __attribute__((always_inline)) {
+            const int m = (s - s_base) * 32 + l32;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                const unsigned off = static_cast<unsigned>(m) * (KBT * 2u) + static_cast<unsigned>((64 * j + 32 * hk) * 2);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    raw[j][q] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(xbr, off + 16u * q, 0, 0));
+            }
+        };
+        auto convert = [&](int s, const u32x4 (&raw)[KS][4], v8i (&x)[KS], float& sxm) __attribute__((always_inline)) {
+            unsigned am = 0u;                                   // max over the lane's values of the 15 magnitude bits
+#pragma unroll
+            for (int j = 0; j < KS; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const unsigned w = raw[j][q][e];
+                        const unsigned lo = w & 0x7FFFu, hi = (w >> 16) & 0x7FFFu;
+                        am = am > lo ? am : lo;
+                        am = am > hi ? am : hi;
+                    }
+            const unsigned other = static_cast<unsigned>(__shfl_xor(static_cast<int>(am), 32, 64));
+            am = am > other ? am : other;
+            float scale, inv;
+            group_scale(__uint_as_float(am << 16), scale, inv);
+            sxm = scale;
+            const int m = (s - s_base) * 32 + l32;
+            if (p.sx_out && hk == 0 && m < p.M) p.sx_out[static_cast<int64_t>(g) * p.M + m] = scale;
+#pragma unroll
+            for (int j = 0; j < KS; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const u32x4 w = raw[j][q];
+                    x[j][2 * q] = static_cast<int>(e4m3x4(bf16_lo(w.x) * inv, bf16_hi(w.x) * inv, bf16_lo(w.y) * inv, bf16_hi(w.y) * inv));
+                    x[j][2 * q + 1] = static_cast<int>(e4m3x4(bf16_lo(w.z) * inv, bf16_hi(w.z) * inv, bf16_lo(w.w) * inv, bf16_hi(w.w) * inv));
+                }
         };
 
         // MFMAs of one phase of a strip.  Lane-derived LDS addresses restart from an opaque copy of the lane id in
@@ -277,7 +329,26 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
         // ---- this wave's strips of the segment
         v8i x[KS];
         float sxm = 0.f;
-        if (NPH == 1) {
+        if (NPH == 1 && BF16IN) {
+            // as below, with the raw strip in a register set of its own: requested right after the previous strip's
+            // values have been cast, in flight through that strip's MFMAs and epilogue
+            u32x4 raw[KS][4];
+            int s = t + wave;
+            if (s < seg_end) load_raw(s, raw);
+            while (s < seg_end) {
+                convert(s, raw, x, sxm);
+                if (s + NWV < seg_end) load_raw(s + NWV, raw);
+                __builtin_amdgcn_sched_barrier(0);
+                v16f acc[NB];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
+                mma(x, acc);
+                epilogue(s, sxm, acc);
+                s += NWV;
+            }
+        } else if (NPH == 1) {
             // W is complete in LDS: the waves run on their own.  The next strip's operands are requested into the
             // same registers right after the last MFMA (x is dead then) and arrive during the epilogue.
             int s = t + wave;
@@ -290,17 +361,17 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const GemmParams p, con
                     for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
                 mma(x, acc);
                 const float sx_cur = sxm;
-                if (s + 8 < seg_end) load_x(s + 8, 0, x, sxm);
+                if (s + NWV < seg_end) load_x(s + NWV, 0, x, sxm);
                 __builtin_amdgcn_sched_barrier(0);
                 epilogue(s, sx_cur, acc);
-                s += 8;
+                s += NWV;
             }
         } else {
             // W is longer than the LDS: rounds of 8 strips (one per wave), and per round NPH phases in which all
             // waves multiply the same K slab of W; the epilogues still run unsynchronized
-            const int rounds = (seg_end - t + 7) / 8;
+            const int rounds = (seg_end - t + NWV - 1) / NWV;
             for (int r = 0; r < rounds; ++r) {
-                const int s = t + 8 * r + wave;
+                const int s = t + NWV * r + wave;
                 const bool active = s < seg_end;
                 v16f acc[NB];
 #pragma unroll
@@ -328,18 +399,34 @@ namespace {
 struct StripInst {
     int nb, ks, nph;
     const void* fn;
+    const void* fn_fused;      // bf16 X, quantization fused (single-phase instances only)
     size_t lds;
     void (*launch)(const GemmParams&, int, dim3, hipStream_t);
 };
 
+// waves of a fused-quantization instance: 8 where accumulators, the raw strip and the operands fit 256 registers
+// (N <= 128, K <= 256), else 4 with up to 512 each
+constexpr int fused_waves(int nb, int ks) { return (nb == 4 && ks <= 4) ? 8 : 4; }
+
 template <int NB, int KS, int NPH>
 void launch_strip(const GemmParams& p, int spp, dim3 grid, hipStream_t s) {
-    gemm_strip_kernel<NB, KS, NPH><<<grid, 512, StripCfg<NB, KS, NPH>::LDS, s>>>(p, spp);
+    if (p.xb) {
+        if constexpr (NPH == 1 && KS <= 8)                      // (K = 1024: the raw strip alone would be 256 registers)
+            gemm_strip_kernel<NB, KS, NPH, fused_waves(NB, KS), true><<<grid, fused_waves(NB, KS) * 64, StripCfg<NB, KS, NPH>::LDS, s>>>(p, spp);
+    } else {
+        gemm_strip_kernel<NB, KS, NPH, 8, false><<<grid, 512, StripCfg<NB, KS, NPH>::LDS, s>>>(p, spp);
+    }
+}
+
+template <int NB, int KS, int NPH>
+const void* strip_fused_fn() {
+    if constexpr (NPH == 1 && KS <= 8) return reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS, NPH, fused_waves(NB, KS), true>);
+    else return nullptr;
 }
 
 #define LOKA_STRIP(NB, KS, NPH)                                                                                     \
-    {NB, KS, NPH, reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS, NPH>), StripCfg<NB, KS, NPH>::LDS,        \
-     &launch_strip<NB, KS, NPH>}
+    {NB, KS, NPH, reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS, NPH, 8, false>), strip_fused_fn<NB, KS, NPH>(), \
+     StripCfg<NB, KS, NPH>::LDS, &launch_strip<NB, KS, NPH>}
 
 // column blocks, K steps per phase, phases (K = 64 KS NPH; one phase when W fits the LDS)
 const StripInst kStrip[] = {LOKA_STRIP(4, 2, 1), LOKA_STRIP(4, 4, 1), LOKA_STRIP(4, 8, 1), LOKA_STRIP(4, 16, 1),
@@ -360,13 +447,19 @@ bool strip_supports(int64_t M, int64_t N, int64_t K) {
 }
 
 // Workgroups to launch and the kernel's entry (for the dynamic-LDS attribute); 0 when unsupported.
-int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, const void** fn, size_t* lds) {
+bool strip_supports_fused(int64_t M, int64_t N, int64_t K) {
     const StripInst* w = strip_pick(N, K);
-    if (!w) return 0;
-    *fn = w->fn;
+    return w != nullptr && w->fn_fused != nullptr && strip_supports(M, N, K) && M * K < (int64_t(1) << 30);
+}
+
+int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool bf16_in, const void** fn, size_t* lds) {
+    const StripInst* w = strip_pick(N, K);
+    if (!w || (bf16_in && !w->fn_fused)) return 0;
+    *fn = bf16_in ? w->fn_fused : w->fn;
     *lds = w->lds;
     const int64_t strips = batch * ((M + 31) / 32);
-    const int64_t wgs = (strips + 7) / 8;                   // at least one strip per wave
+    const int waves = bf16_in ? fused_waves(w->nb, w->ks) : 8;
+    const int64_t wgs = (strips + waves - 1) / waves;       // at least one strip per wave
     return static_cast<int>(wgs < cus ? wgs : cus);
 }
 

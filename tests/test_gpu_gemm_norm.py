@@ -543,11 +543,15 @@ def test_bounded_wait_is_reported(monkeypatch):
 @pytest.mark.parametrize("case", [(300, 256, 256, 1, "rmsnorm"), (1000, 128, 256, 1, "layernorm"), (77, 512, 256, 1, "layernorm"),
                                   (513, 256, 512, 1, "rmsnorm"), (260, 128, 1024, 1, "layernorm"), (640, 256, 256, 5, "rmsnorm"),
                                   (130, 128, 512, 3, "none")])
-def test_fused_quantization_gives_the_bits_of_the_two_calls(orc, case):
+@pytest.mark.parametrize("variant", ["wreg32", "strip32"])
+def test_fused_quantization_gives_the_bits_of_the_two_calls(orc, case, variant):
     # loka_fp8_linear_norm = loka_quantize(ROW) + loka_fp8_gemm_norm in one kernel: scales, fp32 Y and bf16 O must be
     # identical bit for bit (same codes, same kernel arithmetic); the two-call path is checked against the oracle above,
     # and the scales here against the oracle directly
     M, K, N, G, norm = case
+    probe = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORMS[norm], 1e-5, variant=B.variant_id(variant))
+    if not B.loka_variant_supports(probe, B.variant_id(variant)):
+        pytest.skip(f"{variant} does not cover this shape")
     x = torch.cat([synth.student_t4(M, K, 50 + g) for g in range(G)], 0)
     w = torch.cat([synth.weight(K, N, 60 + g) for g in range(G)], 0)
     gamma, beta = synth.affine(N, 9)
@@ -558,7 +562,7 @@ def test_fused_quantization_gives_the_bits_of_the_two_calls(orc, case):
         q, s_ = B.loka_quantize(wd[g * K:(g + 1) * K], B.SCALE_COL, transpose_out=True)
         wq[g * N:(g + 1) * N] = q
         sw[g * N:(g + 1) * N] = s_
-    desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORMS[norm], 1e-5, variant=B.variant_id("wreg32"))
+    desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORMS[norm], 1e-5, variant=B.variant_id(variant))
     xq, sx = B.loka_quantize(xd, B.SCALE_ROW)
     o2, y2 = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, gamma.to(DEV), beta.to(DEV), want_y=True)
     o1, y1, sx1 = B.loka_fp8_linear_norm(desc, xd, wq, sw, gamma.to(DEV), beta.to(DEV), want_y=True, want_sx=True)
@@ -571,7 +575,8 @@ def test_fused_quantization_gives_the_bits_of_the_two_calls(orc, case):
 
 
 def test_fused_quantization_unsupported_shapes():
-    # the configurations whose weights fill the register file, and everything the streaming kernel does not cover
+    # the configurations whose weights fill the register file (streaming kernel) or whose raw strip would (strip
+    # kernel, K = 1024), and everything neither kernel covers
     for M, K, N in [(4096, 512, 512), (4096, 256, 1024), (4096, 1024, 256), (4096, 4096, 4096)]:
         desc = B.make_desc(M, N, K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, 1e-5)
         x = torch.zeros(M, K, dtype=torch.bfloat16, device=DEV)
@@ -587,7 +592,8 @@ def test_fused_quantization_unsupported_shapes():
     assert e.value.status == B.LOKA_ERR_UNSUPPORTED
 
 
-def test_fused_quantization_c4_full_size(orc):
+@pytest.mark.parametrize("variant", ["wreg32", "strip32", None])
+def test_fused_quantization_c4_full_size(orc, variant):
     # the grouped workload at full size: identical bits to the two calls on every row, and sampled rows of two
     # groups against the oracle
     w = synth.WORKLOADS["C4"]
@@ -601,7 +607,11 @@ def test_fused_quantization_c4_full_size(orc):
         q, s_ = B.loka_quantize(wd[g * w.K:(g + 1) * w.K], B.SCALE_COL, transpose_out=True)
         wq[g * w.N:(g + 1) * w.N] = q
         sw[g * w.N:(g + 1) * w.N] = s_
-    desc = B.make_desc(w.M, w.N, w.K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM, variant=B.variant_id("wreg32"))
+    # (no variant named: both entry points pick the strip kernel for this shape)
+    desc = B.make_desc(w.M, w.N, w.K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM,
+                       variant=-1 if variant is None else B.variant_id(variant))
+    if variant is None:
+        assert B.loka_variant_name(B.loka_default_variant(desc)) == "strip32"
     xq, sx = B.loka_quantize(xd, B.SCALE_ROW)
     o2, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
     o1, y1, sx1 = B.loka_fp8_linear_norm(desc, xd, wq, sw, want_y=True, want_sx=True)
