@@ -144,6 +144,19 @@ __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p
                     raw[j][q] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(xbr, off + 16u * q, 0, 0));
             }
         };
+        // loads i0 <= i < i1 of the KS * 4 that make up a raw strip (i = 4 j + q)
+        auto load_raw_part = [&](int s, u32x4 (&raw)[KS][4], int i0, int i1) __attribute__((always_inline)) {
+            int lane_o = lane;
+            asm volatile("; per-strip lane id" : "+v"(lane_o));
+            const int m = (s - s_base) * 32 + (lane_o & 31);
+#pragma unroll
+            for (int i = 0; i < KS * 4; ++i)
+                if (i >= i0 && i < i1) {
+                    const unsigned off = static_cast<unsigned>(m) * (KBT * 2u) +
+                                         static_cast<unsigned>((64 * (i / 4) + 32 * (lane_o >> 5)) * 2 + 16 * (i % 4));
+                    raw[i / 4][i % 4] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(xbr, off, 0, 0));
+                }
+        };
         auto convert = [&](int s, const u32x4 (&raw)[KS][4], v8i (&x)[KS], float& sxm) __attribute__((always_inline)) {
             unsigned am = 0u;                                   // max over the lane's values of the 15 magnitude bits
 #pragma unroll
@@ -207,7 +220,8 @@ __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p
         };
 
         // scales, row statistics, normalization and store of one strip, from registers
-        auto epilogue = [&](int s, const float sxm, v16f (&acc)[NB]) __attribute__((always_inline)) {
+        // (after_block(nb) runs when column block nb has been stored and its 16 accumulators are dead)
+        auto epilogue = [&](int s, const float sxm, v16f (&acc)[NB], auto after_block) __attribute__((always_inline)) {
             int lane_o = lane;
             asm volatile("; per-strip lane id" : "+v"(lane_o));
             const int l32 = lane_o & 31, hk = lane_o >> 5;
@@ -321,6 +335,7 @@ __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p
                         if ((s - s_base) * 32 + r < p.M && ccol < p.N)
                             STRIP_STORE(pk, reinterpret_cast<u32x4*>(obase + static_cast<int64_t>(r) * p.N + ccol));
                     }
+                    after_block(nb);
                 }
             };
             if (affine) normalize_store(std::true_type{}); else normalize_store(std::false_type{});
@@ -332,12 +347,18 @@ __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p
         if (NPH == 1 && BF16IN) {
             // as below, with the raw strip in a register set of its own: requested right after the previous strip's
             // values have been cast, in flight through that strip's MFMAs and epilogue
+            // With 8 waves and the larger shapes the raw strip and the accumulators do not fit 256 registers side by
+            // side: the next strip is then requested piece by piece from inside the epilogue, each piece into the
+            // registers of a column block that has just been stored (LATE); the wave waits for it afterwards, and the
+            // other seven cover.
+            constexpr bool LATE = NWV == 8 && !(NB == 4 && KS <= 4);
             u32x4 raw[KS][4];
             int s = t + wave;
             if (s < seg_end) load_raw(s, raw);
             while (s < seg_end) {
                 convert(s, raw, x, sxm);
-                if (s + NWV < seg_end) load_raw(s + NWV, raw);
+                const bool more = s + NWV < seg_end;
+                if (!LATE && more) load_raw(s + NWV, raw);
                 __builtin_amdgcn_sched_barrier(0);
                 v16f acc[NB];
 #pragma unroll
@@ -345,7 +366,9 @@ __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
                 mma(x, acc);
-                epilogue(s, sxm, acc);
+                epilogue(s, sxm, acc, [&](int nb) __attribute__((always_inline)) {
+                    if (LATE && more) load_raw_part(s + NWV, raw, nb * (KS * 4) / NB, (nb + 1) * (KS * 4) / NB);
+                });
                 s += NWV;
             }
         } else if (NPH == 1) {
@@ -363,7 +386,7 @@ __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p
                 const float sx_cur = sxm;
                 if (s + NWV < seg_end) load_x(s + NWV, 0, x, sxm);
                 __builtin_amdgcn_sched_barrier(0);
-                epilogue(s, sx_cur, acc);
+                epilogue(s, sx_cur, acc, [](int) {});
                 s += NWV;
             }
         } else {
@@ -386,7 +409,7 @@ __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p
                     __syncthreads();
                     if (active) mma(x, acc);
                 }
-                if (active) epilogue(s, sxm, acc);
+                if (active) epilogue(s, sxm, acc, [](int) {});
             }
         }
         t = seg_end;
@@ -405,8 +428,9 @@ struct StripInst {
 };
 
 // waves of a fused-quantization instance: 8 where accumulators, the raw strip and the operands fit 256 registers
-// (N <= 128, K <= 256), else 4 with up to 512 each
-constexpr int fused_waves(int nb, int ks) { return (nb == 4 && ks <= 4) ? 8 : 4; }
+// (N <= 128 with K <= 256; N = 256 with K = 128 and the piecewise request), else 4 with up to 512 each (measured:
+// the 8-wave forms that spill are slower than the 4-wave ones, 94 against 71-81 us at 64 x (4096 x 256 x 256))
+constexpr int fused_waves(int nb, int ks) { return ((nb == 4 && ks <= 4) || (nb == 8 && ks == 2)) ? 8 : 4; }
 
 template <int NB, int KS, int NPH>
 void launch_strip(const GemmParams& p, int spp, dim3 grid, hipStream_t s) {

@@ -542,7 +542,11 @@ def test_bounded_wait_is_reported(monkeypatch):
 # ----------------------------------------------------------------------------- quantization fused into the layer
 @pytest.mark.parametrize("case", [(300, 256, 256, 1, "rmsnorm"), (1000, 128, 256, 1, "layernorm"), (77, 512, 256, 1, "layernorm"),
                                   (513, 256, 512, 1, "rmsnorm"), (260, 128, 1024, 1, "layernorm"), (640, 256, 256, 5, "rmsnorm"),
-                                  (130, 128, 512, 3, "none")])
+                                  (130, 128, 512, 3, "none"),
+                                  # several strips per wave: the next strip's prefetch in all its forms (8 waves early,
+                                  # 8 waves piecewise from inside the epilogue, 4 waves)
+                                  (70000, 256, 128, 1, "layernorm"), (70000, 128, 256, 1, "rmsnorm"),
+                                  (40000, 256, 256, 1, "layernorm"), (36000, 512, 128, 1, "rmsnorm")])
 @pytest.mark.parametrize("variant", ["wreg32", "strip32"])
 def test_fused_quantization_gives_the_bits_of_the_two_calls(orc, case, variant):
     # loka_fp8_linear_norm = loka_quantize(ROW) + loka_fp8_gemm_norm in one kernel: scales, fp32 Y and bf16 O must be
