@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--budget", type=float, default=5e-2, help="rel-Frobenius budget the timed variant must meet")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-library", action="store_true", help="skip the vendor-library yardstick leg")
+    ap.add_argument("--fused", action="store_true",
+                    help="the step is ONE call, loka_fp8_linear_norm (rowwise quantization inside the GEMM kernel: same "
+                         "bits, no FP8 copy of X in memory); small-layer workloads only, exits when unsupported")
     ap.add_argument("--graph", action="store_true",
                     help="record the steps (one per rotated input set) into a HIP graph and time its replays: what a "
                          "serving loop does with the launch-bound small workloads")
@@ -144,9 +147,20 @@ def main():
 
     it = [0]
 
+    def fused_step(xin):
+        r = L.loka_fp8_linear_norm(ctypes.byref(desc), xin.data_ptr(), wq.data_ptr(), sw.data_ptr(), None, None,
+                                   out.data_ptr(), None, None, sp)
+        if r != 0:
+            print(f"bench.py: --fused: loka_fp8_linear_norm returned {r} for {w.name} (shape or recipe not covered)",
+                  file=sys.stderr)
+            sys.exit(3)
+
     def step():
-        quant_x(xs[it[0] % n_sets])
-        gemm_norm()
+        if args.fused:
+            fused_step(xs[it[0] % n_sets])
+        else:
+            quant_x(xs[it[0] % n_sets])
+            gemm_norm()
         it[0] += 1
 
     for _ in range(args.warmup):
@@ -292,7 +306,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8_e4m3 (fp32 accumulate)", "data": "synthetic",
         "config": {"workload": f"{w.name}: X[{G}x{M},{K}] {w.x_dist}, W[{K},{N}] N(0,1/K), {w.norm}",
-                   "step": "quantize X + FP8 GEMM with fused scales and row norm (bf16 out)",
+                   "step": ("one call: rowwise quantization, FP8 GEMM, scales and row norm in one kernel (bf16 in, bf16 out)"
+                            if args.fused else "quantize X + FP8 GEMM with fused scales and row norm (bf16 out)"),
                    "recipe": RECIPE_NAMES.get((xm, wm), f"{xm}/{wm}"), "variant": B.loka_variant_name(variant),
                    "flops_counted": "2*M*K*N of the FP8 GEMM", "pct_fp8_peak": 100 * value / FP8_PEAK_TFLOPS,
                    "input_sets_rotated": n_sets,
