@@ -163,3 +163,17 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libloka.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         B.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the measurement script runs on one GPU: any other count (flag or launcher environment) ends with a message and a
+    # non-zero status before anything touches a device
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="2")
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py")], capture_output=True, text=True, timeout=120, env=env)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
