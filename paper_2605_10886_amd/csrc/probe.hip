@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void probe_finalize_kernel(const ProbePartial*
     }
     s0[threadIdx.x] = sse; s1[threadIdx.x] = ssr; s2[threadIdx.x] = rel; s3[threadIdx.x] = mx;
     __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
+    for (unsigned w = 128; w > 0; w >>= 1) {
         if (threadIdx.x < w) {
             s0[threadIdx.x] += s0[threadIdx.x + w];
             s1[threadIdx.x] += s1[threadIdx.x + w];
