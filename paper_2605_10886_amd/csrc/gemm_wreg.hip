@@ -274,10 +274,13 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
     // staging buffer is not written again before that block's statistics are merged (without a norm: before a
     // barrier of its own), and a wave held up by the store path leaves the matrix pipe to the other wave of its
     // SIMD.
-    constexpr bool DEFER = !FP8OUT && !BF16IN;
-    constexpr int CPR = NT / 8;                                         // 16-byte chunks per bf16 row
+    // With FP8 output the deferred step also converts: a lane reads 16 staged bf16 values, scales them with the
+    // row's quantization factor (left in LDS by the block's epilogue) and stores 16 codes.
+    constexpr bool DEFER = !BF16IN;
+    constexpr int CPR = FP8OUT ? NT / 16 : NT / 8;                      // 16-byte output chunks per row
     constexpr int SW_ = DEFER ? 8 : 4;                                  // waves that store (deferred: all of them)
-    constexpr int INSTR = RB * CPR / 64 / SW_;                          // store instructions per storing wave and block
+    constexpr int INSTR_ = RB * CPR / 64 / SW_;
+    constexpr int INSTR = INSTR_ > 0 ? INSTR_ : 1;                      // store instructions per storing wave and block
     bool pending = false;
     int pend_g = 0, pend_m0 = 0;
     // store instruction s of the pending block: 64 consecutive chunks (1 KB), whole rows
@@ -286,6 +289,23 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         asm volatile("; store lane id" : "+v"(lid));
         const int id = ((DEFER ? wave : wave - 4) + SW_ * s) * 64 + lid;
         const int r = id / CPR, c = id % CPR;
+        if (FP8OUT) {
+            if (r < RB) {
+                const uint8_t* ob = smem + C::OFF_OB + r * (NT * 2);
+                const u32x4 v0 = *reinterpret_cast<const u32x4*>(ob + (((2 * c) ^ (r & 15)) << 4));
+                const u32x4 v1 = *reinterpret_cast<const u32x4*>(ob + (((2 * c + 1) ^ (r & 15)) << 4));
+                const float iq = (reinterpret_cast<const float2*>(smem + C::OFF_RED) + 1)[(r * 9 + 8) * 2].y;
+                u32x4 ck;
+                ck.x = e4m3x4(bf16_lo(v0.x) * iq, bf16_hi(v0.x) * iq, bf16_lo(v0.y) * iq, bf16_hi(v0.y) * iq);
+                ck.y = e4m3x4(bf16_lo(v0.z) * iq, bf16_hi(v0.z) * iq, bf16_lo(v0.w) * iq, bf16_hi(v0.w) * iq);
+                ck.z = e4m3x4(bf16_lo(v1.x) * iq, bf16_hi(v1.x) * iq, bf16_lo(v1.y) * iq, bf16_hi(v1.y) * iq);
+                ck.w = e4m3x4(bf16_lo(v1.z) * iq, bf16_hi(v1.z) * iq, bf16_lo(v1.w) * iq, bf16_hi(v1.w) * iq);
+                uint8_t* const oq = p.outq + static_cast<int64_t>(sg) * p.strideO;
+                if (sm0 + r < p.M && c * 16 < p.N)
+                    __builtin_nontemporal_store(ck, reinterpret_cast<u32x4*>(oq + static_cast<int64_t>(sm0 + r) * p.N + c * 16));
+            }
+            return;
+        }
         const u32x4 pk = *reinterpret_cast<const u32x4*>(smem + C::OFF_OB + r * (NT * 2) + ((c ^ (r & 15)) << 4));
         uint16_t* const og = p.out + static_cast<int64_t>(sg) * p.strideO;
         if (sm0 + r < p.M && c * 8 < p.N)
@@ -552,45 +572,13 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
             pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
             return pk;
         };
-        if (!FP8OUT) {
-            // ---- bf16 into the staging buffer (row 32 rt + l32; 16-byte chunk c at position c ^ (row % 16))
-            auto stage = [&](auto affine_tag) __attribute__((always_inline)) {
-                constexpr bool AFFINE = decltype(affine_tag)::value;
+        // ---- bf16 into the staging buffer (row 32 rt + l32; 16-byte chunk c at position c ^ (row % 16)); with FP8
+        // output also the lane's maximum of the bf16 magnitudes per row tile (integer max: exact)
+        unsigned amax_b[RT];
 #pragma unroll
-                for (int ni = 0; ni < NIW; ++ni) {
-                    const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + colbase[ni] * 4);
-                    const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + colbase[ni] * 4);
-#pragma unroll
-                    for (int half = 0; half < 2; ++half) {
-                        __builtin_amdgcn_sched_barrier(0);
-                        v4f gq0 = {}, gq1 = {}, bq0 = {}, bq1 = {};
-                        if (AFFINE) { gq0 = g4[2 * half]; gq1 = g4[2 * half + 1]; bq0 = b4[2 * half]; bq1 = b4[2 * half + 1]; }
-                        const int c = (colbase[ni] >> 3) + half;
-#pragma unroll
-                        for (int rt = 0; rt < RT; ++rt)
-                            *reinterpret_cast<u32x4*>(obuf + (rt * 32 + l32) * (NT * 2) + ((c ^ (l32 & 15)) << 4)) =
-                                norm8(affine_tag, rt, ni, half, gq0, gq1, bq0, bq1, rstd_r[rt]);
-                    }
-                }
-            };
-            if (affine) stage(std::true_type{}); else stage(std::false_type{});
-            // (deferred stores: this barrier is also the next block's "X has landed" barrier)
-            if (DEFER && loader && b + 1 < b1 && (b + 1) / blocks_per_problem == g) wait_landed(b + 1);
-            lds_barrier();
-            LOKA_STAMP(5);
-            // ---- the storers write the block out: now, or between the MFMAs of the next block
-            pending = true; pend_g = g; pend_m0 = m0;
-            if (!DEFER || b + 1 == b1) flush_pending();
-        } else {
-            // ---- FP8 output for the next layer: the bf16 values above, quantized per row exactly as the
-            // quantize entry point would quantize the stored bf16 tensor (amax over the row of |bf16 value|,
-            // scale = amax / 448, code = e4m3(value * (448 / amax))).  Pass 1: row amax (integer max of the
-            // bf16 magnitudes; lanes, then the 8 waves through LDS).  Pass 2: recompute, scale, convert.
-            // (the row amax travels in the unused fourth word of the statistics entries)
-            unsigned* const redq = reinterpret_cast<unsigned*>(smem + C::OFF_RED) + 3;
-            unsigned amax_b[RT];
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) amax_b[rt] = 0u;
+        for (int rt = 0; rt < RT; ++rt) amax_b[rt] = 0u;
+        auto stage = [&](auto affine_tag) __attribute__((always_inline)) {
+            constexpr bool AFFINE = decltype(affine_tag)::value;
 #pragma unroll
             for (int ni = 0; ni < NIW; ++ni) {
                 const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + colbase[ni] * 4);
@@ -599,22 +587,37 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
                     __builtin_amdgcn_sched_barrier(0);
-                    const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
+                    v4f gq0 = {}, gq1 = {}, bq0 = {}, bq1 = {};
+                    if (AFFINE) { gq0 = g4[2 * half]; gq1 = g4[2 * half + 1]; bq0 = b4[2 * half]; bq1 = b4[2 * half + 1]; }
+                    const int c = (colbase[ni] >> 3) + half;
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt) {
-                        const u32x4 pk = norm8(std::true_type{}, rt, ni, half, gq0, gq1, bq0, bq1, rstd_r[rt]);
-                        unsigned a = amax_b[rt];
-                        const unsigned ws4[4] = {pk.x, pk.y, pk.z, pk.w};
+                        const u32x4 pk = norm8(affine_tag, rt, ni, half, gq0, gq1, bq0, bq1, rstd_r[rt]);
+                        *reinterpret_cast<u32x4*>(obuf + (rt * 32 + l32) * (NT * 2) + ((c ^ (l32 & 15)) << 4)) = pk;
+                        if (FP8OUT) {
+                            unsigned a = amax_b[rt];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const unsigned lo = ws4[e] & 0x7FFFu, hi = (ws4[e] >> 16) & 0x7FFFu;
-                            a = a > lo ? a : lo;
-                            a = a > hi ? a : hi;
+                            for (int e = 0; e < 4; ++e) {
+                                const unsigned lo = pk[e] & 0x7FFFu, hi = (pk[e] >> 16) & 0x7FFFu;
+                                a = a > lo ? a : lo;
+                                a = a > hi ? a : hi;
+                            }
+                            if (in) amax_b[rt] = a;
                         }
-                        if (in) amax_b[rt] = a;
                     }
                 }
             }
+        };
+        if (affine) stage(std::true_type{}); else stage(std::false_type{});
+        if (FP8OUT) {
+            // ---- FP8 output for the next layer: the staged bf16 values quantized per row exactly as the quantize
+            // entry point would quantize the stored bf16 tensor (amax over the row of |bf16 value|, scale =
+            // amax / 448, code = e4m3(value * (448 / amax))).  The row amax crosses the 8 waves in the unused fourth
+            // word of the statistics entries; RB threads then compute the row's scale pair once and leave
+            // it in the row's spare entry, where the conversion (store_step, deferred like the bf16 stores) finds
+            // it.  (The normalized values are computed once: recomputing them after the amax was known cost a second
+            // pass over the accumulators, 85 against 58 us at 65536 x 256 x 1024.)
+            unsigned* const redq = reinterpret_cast<unsigned*>(smem + C::OFF_RED) + 3;
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
                 const unsigned o2 = static_cast<unsigned>(__shfl_xor(static_cast<int>(amax_b[rt]), 32, 64));
@@ -622,66 +625,28 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
                 if (hk == 0) redq[((rt * 32 + l32) * 9 + wave) * 4] = amax_b[rt];
             }
             lds_barrier();
-            float inv_q[RT], scale_q[RT];
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
+            float2* const sq = reinterpret_cast<float2*>(smem + C::OFF_RED) + 1;       // words 2, 3 of entry [row][8]
+            // (by a storer wave: a loader's memory counter must not hold a store this young when it next checks
+            // that its X block has landed)
+            if (threadIdx.x >= 256 && threadIdx.x < 256 + RB) {
+                int tl = static_cast<int>(threadIdx.x) - 256;
+                asm volatile("; row id" : "+v"(tl));
                 unsigned a = 0u;
 #pragma unroll
-                for (int w = 0; w < 8; ++w) { const unsigned v = redq[((rt * 32 + l32) * 9 + w) * 4]; a = a > v ? a : v; }
-                group_scale(__uint_as_float(a << 16), scale_q[rt], inv_q[rt]);
-            }
-            // pass 2: codes into the staging buffer (row pitch NT bytes, 16-byte chunk = 16 columns, same swizzle).
-            // The values are recomputed from an opaque copy of rstd: kept from pass 1 they would hold one
-            // register per two outputs across the barrier.
-            float rstd2[RT];
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) { rstd2[rt] = rstd_r[rt]; asm volatile("; pass 2" : "+v"(rstd2[rt])); }
-#pragma unroll
-            for (int ni = 0; ni < NIW; ++ni) {
-                const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + colbase[ni] * 4);
-                const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + colbase[ni] * 4);
-                const int c = colbase[ni] >> 4;
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt) {
-                        const u32x4 pk = norm8(std::true_type{}, rt, ni, half, gq0, gq1, bq0, bq1, rstd2[rt]);
-                        const float iq = inv_q[rt];
-                        u32x2 codes;
-                        codes.x = e4m3x4(bf16_lo(pk.x) * iq, bf16_hi(pk.x) * iq, bf16_lo(pk.y) * iq, bf16_hi(pk.y) * iq);
-                        codes.y = e4m3x4(bf16_lo(pk.z) * iq, bf16_hi(pk.z) * iq, bf16_lo(pk.w) * iq, bf16_hi(pk.w) * iq);
-                        *reinterpret_cast<u32x2*>(obuf + (rt * 32 + l32) * NT + ((c ^ (l32 & 15)) << 4) + 8 * half) = codes;
-                    }
-                }
-            }
-            lds_barrier();
-            LOKA_STAMP(5);
-            if (storer) {
-                constexpr int CPRQ = NT / 16;                               // 16-byte chunks per row
-                constexpr int INSTRQ = RB * CPRQ / 64 / 4 > 0 ? RB * CPRQ / 64 / 4 : 1;
-                uint8_t* const og = p.outq + static_cast<int64_t>(g) * p.strideO;
-#pragma unroll
-                for (int s = 0; s < INSTRQ; ++s) {
-                    if (s % 2 == 0) __builtin_amdgcn_sched_barrier(0);
-                    const int id = ((wave - 4) + 4 * s) * 64 + lanev;
-                    const int r = id / CPRQ, c = id % CPRQ;
-                    if (r < RB) {
-                        const u32x4 ck = *reinterpret_cast<const u32x4*>(obuf + r * NT + ((c ^ (r & 15)) << 4));
-                        if (m0 + r < p.M && c * 16 < p.N)
-                            __builtin_nontemporal_store(ck, reinterpret_cast<u32x4*>(og + static_cast<int64_t>(m0 + r) * p.N + c * 16));
-                    }
-                }
-                if (wave == 4 && hk == 0) {
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt) {
-                        const int m = m0 + rt * 32 + l32;
-                        if (m < p.M) p.outs[static_cast<int64_t>(g) * p.M + m] = scale_q[rt];
-                    }
-                }
+                for (int w = 0; w < 8; ++w) { const unsigned v = redq[(tl * 9 + w) * 4]; a = a > v ? a : v; }
+                float scale, inv;
+                group_scale(__uint_as_float(a << 16), scale, inv);
+                sq[(tl * 9 + 8) * 2] = make_float2(scale, inv);
+                if (m0 + tl < p.M) p.outs[static_cast<int64_t>(g) * p.M + m0 + tl] = scale;
             }
         }
+        // (deferred stores: this barrier is also the next block's "X has landed" barrier)
+        if (DEFER && loader && b + 1 < b1 && (b + 1) / blocks_per_problem == g) wait_landed(b + 1);
+        lds_barrier();
+        LOKA_STAMP(5);
+        // ---- the block is written out: now, or between the MFMAs of the next block
+        pending = true; pend_g = g; pend_m0 = m0;
+        if (!DEFER || b + 1 == b1) flush_pending();
     }
 }
 
