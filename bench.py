@@ -44,12 +44,126 @@ def _event_times(fn, steps, stream):
     return [a.elapsed_time(b) for a, b in evs]
 
 
+def run_c3_pair(args):
+    """The skinny pair C3 as a chain: X -> layer a (65536 x 256 x 1024, LayerNorm) -> layer b (1024 -> 256, LayerNorm).
+
+    Two hand-overs are timed: FP8 (layer a's epilogue emits e4m3 codes + row scales, `loka_fp8_gemm_norm_fp8out`, which
+    layer b consumes directly) and bf16 (layer a writes bf16, a second `loka_quantize` feeds layer b).  `value` is the
+    FP8 hand-over.  One JSON line, same contract as the single-layer workloads.
+    """
+    import ctypes
+
+    import numpy as np
+    import torch
+    from paper_2605_10886_amd import binding as B
+    from paper_2605_10886_amd import synth
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+    sp = ctypes.c_void_p(stream.cuda_stream)
+    L = B.lib()
+    wa, wb = synth.WORKLOADS["C3a"], synth.WORKLOADS["C3b"]
+    M = wa.M
+    x_cpu = synth.activations(wa)
+    w1_cpu, w2_cpu = synth.weights(wa), synth.weights(wb)
+    n_sets = 4
+    xs = [x_cpu.to(dev)] + [x_cpu.to(dev).clone() for _ in range(n_sets - 1)]
+    w1q, s1 = B.loka_quantize(w1_cpu.to(dev), B.SCALE_COL, transpose_out=True)
+    w2q, s2 = B.loka_quantize(w2_cpu.to(dev), B.SCALE_COL, transpose_out=True)
+    da = B.make_desc(M, wa.N, wa.K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, wa.eps, variant=-1)
+    db = B.make_desc(M, wb.N, wb.K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, wb.eps, variant=-1)
+    xq = torch.empty(M, wa.K, dtype=torch.uint8, device=dev)
+    sx = torch.empty(M, dtype=torch.float32, device=dev)
+    hq = torch.empty(M, wa.N, dtype=torch.uint8, device=dev)
+    hs = torch.empty(M, dtype=torch.float32, device=dev)
+    hb = torch.empty(M, wa.N, dtype=torch.bfloat16, device=dev)
+    out = torch.empty(M, wb.N, dtype=torch.bfloat16, device=dev)
+    ws_a = torch.empty(max(16, L.loka_fp8_gemm_norm_workspace(ctypes.byref(da))), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(max(16, L.loka_fp8_gemm_norm_workspace(ctypes.byref(db))), dtype=torch.uint8, device=dev)
+
+    def ok(r):
+        assert r == 0, r
+
+    def quant(src, rows, cols, q, s_):
+        ok(L.loka_quantize(src.data_ptr(), rows, cols, cols, B.SCALE_ROW, 0, q.data_ptr(), s_.data_ptr(), None, 0, sp))
+
+    def layer_b():
+        ok(L.loka_fp8_gemm_norm(ctypes.byref(db), hq.data_ptr(), hs.data_ptr(), w2q.data_ptr(), s2.data_ptr(), None, None,
+                                out.data_ptr(), None, ws_b.data_ptr(), ws_b.numel(), sp))
+
+    def step_fp8(i):
+        quant(xs[i % n_sets], M, wa.K, xq, sx)
+        ok(L.loka_fp8_gemm_norm_fp8out(ctypes.byref(da), xq.data_ptr(), sx.data_ptr(), w1q.data_ptr(), s1.data_ptr(), None,
+                                       None, hq.data_ptr(), hs.data_ptr(), None, sp))
+        layer_b()
+
+    def step_bf16(i):
+        quant(xs[i % n_sets], M, wa.K, xq, sx)
+        ok(L.loka_fp8_gemm_norm(ctypes.byref(da), xq.data_ptr(), sx.data_ptr(), w1q.data_ptr(), s1.data_ptr(), None, None,
+                                hb.data_ptr(), None, ws_a.data_ptr(), ws_a.numel(), sp))
+        quant(hb, M, wa.N, hq, hs)
+        layer_b()
+
+    def timed(fn):
+        for i in range(args.warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms_fp8, ms_bf16 = timed(step_fp8), timed(step_bf16)
+    flops = 2.0 * M * (wa.K * wa.N + wb.K * wb.N)
+    # dominant kernel: layer a with FP8 output (reads Xq + W, writes codes + scales)
+    t_a = float(np.mean(_event_times(lambda: ok(L.loka_fp8_gemm_norm_fp8out(
+        ctypes.byref(da), xq.data_ptr(), sx.data_ptr(), w1q.data_ptr(), s1.data_ptr(), None, None, hq.data_ptr(),
+        hs.data_ptr(), None, sp)), min(args.steps, 20), stream)))
+    bytes_a = M * wa.K + wa.N * wa.K + M * wa.N + M * 4
+    gbs = bytes_a / (t_a * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n_s = M                                  # the whole pair is a few seconds of oracle time
+        thr = oracle.default_threads()
+        w1q_o, s1_o = oracle.quantize(synth.bf16_bits(w1_cpu), oracle.SCALE_COL, transpose_out=True)
+        w2q_o, s2_o = oracle.quantize(synth.bf16_bits(w2_cpu), oracle.SCALE_COL, transpose_out=True)
+        xb = synth.bf16_bits(x_cpu)[:n_s].copy()
+        c0 = time.perf_counter()
+        xq_o, sx_o = oracle.quantize(xb, oracle.SCALE_ROW, threads=thr)
+        y_o = oracle.fp8_gemm(xq_o, sx_o, oracle.SCALE_ROW, w1q_o, s1_o, oracle.SCALE_COL, threads=thr)
+        h_o = oracle.norm(y_o, B.NORM_LAYERNORM, wa.eps, threads=thr)
+        hq_o, hs_o = oracle.quantize(np.ascontiguousarray(h_o), oracle.SCALE_ROW, threads=thr)
+        y2_o = oracle.fp8_gemm(hq_o, hs_o, oracle.SCALE_ROW, w2q_o, s2_o, oracle.SCALE_COL, threads=thr)
+        oracle.norm(y2_o, B.NORM_LAYERNORM, wb.eps, threads=thr)
+        csec = time.perf_counter() - c0
+        cpu = {"value": flops * n_s / M / csec / 1e12, "unit": "TFLOP/s", "cores": thr, "kind": "oracle",
+               "sample": f"{n_s} of {M} rows of the C3 pair (quantize, GEMM, norm, quantize, GEMM, norm), {csec:.1f} s"}
+    print(json.dumps({
+        "metric": "FP8 GEMM+norm TFLOP/s (% of MI355X FP8 peak); quantize/probe HBM GB/s",
+        "value": flops / (ms_fp8 * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_fp8, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8_e4m3 (fp32 accumulate)", "data": "synthetic",
+        "config": {"workload": f"C3 pair: X[{M},{wa.K}] N(0,1) -> W1[{wa.K},{wa.N}] -> LayerNorm -> W2[{wb.K},{wb.N}] -> LayerNorm",
+                   "step": "quantize X + layer a with FP8 output (codes + row scales) + layer b",
+                   "ms_per_step_bf16_handover": ms_bf16, "recipe": "row/col",
+                   "variants": [B.loka_variant_name(B.loka_default_variant(da)), B.loka_variant_name(B.loka_default_variant(db))],
+                   "flops_counted": "2*M*(K1*N1 + K2*N2)"},
+        "roofline": {"kernel": "loka_fp8_gemm_norm_fp8out [wreg32] (layer a)", "bound": "hbm", "achieved": gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_ms": t_a, "algorithmic_bytes": bytes_a},
+        "cpu_baseline": cpu,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3a", "C3b", "C4", "C5"])
+    ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3a", "C3b", "C3pair", "C4", "C5"])
     ap.add_argument("--budget", type=float, default=5e-2, help="rel-Frobenius budget the timed variant must meet")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-library", action="store_true", help="skip the vendor-library yardstick leg")
@@ -68,6 +182,9 @@ def main():
         print("bench.py: this build runs on ONE GPU (the path shards along M with no exchange; see DESIGN.md); "
               "--gpus N with N > 1 is not supported.", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "C3pair":
+        return run_c3_pair(args)
 
     import numpy as np
     import torch
