@@ -171,8 +171,10 @@ loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* wor
  * writes what loka_quantize(O_bf16, LOKA_SCALE_ROW) would produce from it, bit for bit:
  *   oq [batch][M, N] e4m3 codes,  so [batch][M] fp32 row scales (amax of the row's bf16 values / 448).
  * The next layer's loka_fp8_gemm_norm takes (oq, so) as its (xq, sx) with x_mode = LOKA_SCALE_ROW.
- * Built for the shapes the streaming skinny-layer kernel covers (N <= 1024, K in {128, 256, 512, 1024},
- * K * N <= 256 KB, non-blockwise input scales); LOKA_ERR_UNSUPPORTED otherwise.  No workspace.
+ * Built into the two kernels that keep a whole output row together: the streaming skinny-layer kernel ("wreg32":
+ * N <= 1024, K in {128, 256, 512, 1024}, K * N <= 256 KB) and the small-layer strip kernel ("strip32": N <= 256,
+ * K * N <= 256 KB), non-blockwise input scales.  desc->variant names one, or -1: the library's choice for the shape
+ * when it is one of the two, else the streaming kernel.  LOKA_ERR_UNSUPPORTED otherwise.  No workspace.
  * y_fp32 as above (NULL to skip).  oq, so: device pointers, 16-byte aligned, caller-owned. */
 loka_status loka_fp8_gemm_norm_fp8out(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
                                       const float* sw, const void* gamma_bf16, const void* beta_bf16, uint8_t* oq,

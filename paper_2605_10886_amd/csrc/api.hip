@@ -18,6 +18,8 @@ size_t variant_workspace(const loka_gemm_desc*, int);
 loka_status fp8_gemm_norm_launch(const loka_gemm_desc*, int, const uint8_t*, const float*, const uint8_t*, const float*,
                                  const void*, const void*, void*, float*, uint8_t*, float*, void*, hipStream_t);
 int variant_streaming_id();
+bool variant_is_streaming(int);
+bool variant_is_strip(int);
 bool variant_supports_fused(const loka_gemm_desc*, int);
 int variant_fused_default(const loka_gemm_desc*);
 loka_status fp8_linear_norm_launch(const loka_gemm_desc*, int, const void*, const uint8_t*, const float*, const void*,
@@ -219,9 +221,11 @@ loka_status loka_fp8_gemm_norm_fp8out(const loka_gemm_desc* desc, const uint8_t*
     if (!aligned16(xq) || !aligned16(wq) || !aligned16(sx) || !aligned16(sw) || !aligned16(oq) || !aligned16(so) ||
         !aligned16(y_fp32) || !aligned16(gamma_bf16) || !aligned16(beta_bf16))
         return LOKA_ERR_ALIGN;
-    // only the streaming kernel keeps a whole output row inside one workgroup and has this epilogue
-    const int v = variant_streaming_id();
-    if (v < 0 || !variant_supports(desc, v) || (desc->variant >= 0 && desc->variant != v)) return LOKA_ERR_UNSUPPORTED;
+    // the kernels that keep a whole output row inside one workgroup (streaming) or one wave (strip) have this epilogue:
+    // the one the caller names, else the library's choice for the shape when it is one of the two, else the streaming one
+    int v = desc->variant >= 0 ? desc->variant : default_variant(desc);
+    if (desc->variant < 0 && !(v >= 0 && (variant_is_streaming(v) || variant_is_strip(v)))) v = variant_streaming_id();
+    if (v < 0 || !(variant_is_streaming(v) || variant_is_strip(v)) || !variant_supports(desc, v)) return LOKA_ERR_UNSUPPORTED;
     return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, nullptr, y_fp32, oq, so, nullptr,
                                 static_cast<hipStream_t>(hip_stream));
 }

@@ -712,7 +712,7 @@ static const char kWregName[] = "wreg32";
 // gemm_strip.hip
 bool strip_supports(int64_t M, int64_t N, int64_t K);
 bool strip_supports_fused(int64_t M, int64_t N, int64_t K);
-int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool bf16_in, const void** fn, size_t* lds);
+int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool bf16_in, bool fp8_out, const void** fn, size_t* lds);
 void strip_launch(const GemmParams& p, dim3 grid, hipStream_t s);
 static void launch_strip_any(const GemmParams& p, bool, dim3 grid, hipStream_t s) { strip_launch(p, grid, s); }
 static const char kStripName[] = "strip32";
@@ -899,7 +899,8 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
     p.out = static_cast<uint16_t*>(out); p.y = y;
     p.outq = outq; p.outs = outs;
     p.xb = static_cast<const uint16_t*>(x_bf16); p.sx_out = sx_out;
-    if (outq && vi.name != kWregName) return LOKA_ERR_UNSUPPORTED;   // FP8 output: the row must stay inside one workgroup
+    // FP8 output: the row must stay inside one workgroup (streaming kernel) or one wave (strip kernel)
+    if (outq && vi.name != kWregName && vi.name != kStripName) return LOKA_ERR_UNSUPPORTED;
     p.norm = d->norm; p.eps = d->eps; p.block_n = d->block_n; p.act = d->act;
     p.tiles_m = static_cast<int>((d->M + vi.bm - 1) / vi.bm);
     p.tiles_n = static_cast<int>((d->N + vi.bn - 1) / vi.bn);
@@ -928,7 +929,7 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         size_t lds = 0;
         LOKA_HIP_TRY(hipGetDevice(&dev));
         LOKA_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        const int wgs = strip_plan(d->M, d->N, d->K, d->batch, cus, p.xb != nullptr, &fn, &lds);
+        const int wgs = strip_plan(d->M, d->N, d->K, d->batch, cus, p.xb != nullptr, p.outq != nullptr, &fn, &lds);
         if (wgs <= 0) return LOKA_ERR_UNSUPPORTED;
         if (set_lds(fn, lds) != LOKA_OK) return LOKA_ERR_HIP;
         vi.launch(p, false, dim3(static_cast<unsigned>(wgs)), s);

@@ -49,7 +49,7 @@ struct StripCfg {
 // never exists in memory (Section 3.2: quantization fused with the layer).  A strip's 32 x K bf16 values are a
 // second set of 16 KS registers per lane that must stay live through the previous strip's epilogue: those
 // instances run with 4 waves of up to 512 registers instead of 8 of 256.
-template <int NB, int KS, int NPH, int NWV, bool BF16IN>
+template <int NB, int KS, int NPH, int NWV, bool BF16IN, bool FP8OUT>
 __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p, const int strips_per_problem) {
     using C = StripCfg<NB, KS, NPH>;
     static_assert(!BF16IN || NPH == 1, "fused quantization needs the whole row of X in one pass");
@@ -338,7 +338,85 @@ __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p
                     after_block(nb);
                 }
             };
-            if (affine) normalize_store(std::true_type{}); else normalize_store(std::false_type{});
+            // FP8 output for the next layer (Section 3.2: quantization fused before the output is written): the
+            // bf16 values above, quantized per row exactly as the quantize entry point would quantize the stored bf16
+            // tensor.  The whole row lives in this lane and lane ^ 32, so the row amax needs one exchange; the values
+            // are then computed a second time (keeping 128 packed values would not fit beside the accumulators),
+            // cast, and leave through the same staging buffer, two column blocks (64 codes per row) at a time.
+            auto normalize_store_fp8 = [&](auto affine_tag) __attribute__((always_inline)) {
+                constexpr bool AFFINE = decltype(affine_tag)::value;
+                auto packed8 = [&](int nb, int half) __attribute__((always_inline)) {
+                    const int col = nb * 32 + hk * 16;
+                    float o[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = __builtin_fmaf(acc[nb][8 * half + e], rstd, nmr);
+                    if (AFFINE) {
+                        const v4f* g4 = reinterpret_cast<const v4f*>(smem + C::OFF_GM + col * 4);
+                        const v4f* b4 = reinterpret_cast<const v4f*>(smem + C::OFF_BT + col * 4);
+                        const v4f gq0 = g4[2 * half], gq1 = g4[2 * half + 1], bq0 = b4[2 * half], bq1 = b4[2 * half + 1];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            o[e] = __builtin_fmaf(o[e], gq0[e], bq0[e]);
+                            o[4 + e] = __builtin_fmaf(o[4 + e], gq1[e], bq1[e]);
+                        }
+                    }
+                    u32x4 pk;
+                    pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
+                    pk.z = pack_bf16x2(o[4], o[5]); pk.w = pack_bf16x2(o[6], o[7]);
+                    return pk;
+                };
+                unsigned am = 0u;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    if (nb * 32 + hk * 16 < p.N) {
+#pragma unroll
+                        for (int half = 0; half < 2; ++half) {
+                            const u32x4 pk = packed8(nb, half);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const unsigned lo = pk[e] & 0x7FFFu, hi = (pk[e] >> 16) & 0x7FFFu;
+                                am = am > lo ? am : lo;
+                                am = am > hi ? am : hi;
+                            }
+                        }
+                    }
+                const unsigned other = static_cast<unsigned>(__shfl_xor(static_cast<int>(am), 32, 64));
+                am = am > other ? am : other;
+                float scale, inv;
+                group_scale(__uint_as_float(am << 16), scale, inv);
+                if (hk == 0 && m < p.M) p.outs[static_cast<int64_t>(g) * p.M + m] = scale;
+                uint8_t* const qbase = p.outq + static_cast<int64_t>(g) * p.strideO + static_cast<int64_t>((s - s_base) * 32) * p.N;
+#pragma unroll
+                for (int nbp = 0; nbp < NB / 2; ++nbp) {
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const int nb = 2 * nbp + q;
+                        const u32x4 p0 = packed8(nb, 0), p1 = packed8(nb, 1);
+                        u32x4 ck;
+                        ck.x = e4m3x4(bf16_lo(p0.x) * inv, bf16_hi(p0.x) * inv, bf16_lo(p0.y) * inv, bf16_hi(p0.y) * inv);
+                        ck.y = e4m3x4(bf16_lo(p0.z) * inv, bf16_hi(p0.z) * inv, bf16_lo(p0.w) * inv, bf16_hi(p0.w) * inv);
+                        ck.z = e4m3x4(bf16_lo(p1.x) * inv, bf16_hi(p1.x) * inv, bf16_lo(p1.y) * inv, bf16_hi(p1.y) * inv);
+                        ck.w = e4m3x4(bf16_lo(p1.z) * inv, bf16_hi(p1.z) * inv, bf16_lo(p1.w) * inv, bf16_hi(p1.w) * inv);
+                        *reinterpret_cast<u32x4*>(tbuf + t_wr + (((2 * q + hk) ^ t_key) << 4)) = ck;
+                    }
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int r = 16 * j + t_row;
+                        const u32x4 ck = *reinterpret_cast<const u32x4*>(tbuf + r * 64 + ((t_c ^ ((r >> 2) & 3)) << 4));
+                        const int ccol = nbp * 64 + t_c * 16;
+                        if ((s - s_base) * 32 + r < p.M && ccol < p.N)
+                            STRIP_STORE(ck, reinterpret_cast<u32x4*>(qbase + static_cast<int64_t>(r) * p.N + ccol));
+                    }
+                    after_block(2 * nbp);
+                    after_block(2 * nbp + 1);
+                }
+            };
+            // (an instantiation of its own: in one kernel with the bf16 form the larger shapes spill more)
+            if (FP8OUT) {
+                if (affine) normalize_store_fp8(std::true_type{}); else normalize_store_fp8(std::false_type{});
+            } else {
+                if (affine) normalize_store(std::true_type{}); else normalize_store(std::false_type{});
+            }
         };
 
         // ---- this wave's strips of the segment
@@ -423,6 +501,7 @@ struct StripInst {
     int nb, ks, nph;
     const void* fn;
     const void* fn_fused;      // bf16 X, quantization fused (single-phase instances only)
+    const void* fn_q;          // e4m3 output
     size_t lds;
     void (*launch)(const GemmParams&, int, dim3, hipStream_t);
 };
@@ -436,21 +515,24 @@ template <int NB, int KS, int NPH>
 void launch_strip(const GemmParams& p, int spp, dim3 grid, hipStream_t s) {
     if (p.xb) {
         if constexpr (NPH == 1 && KS <= 8)                      // (K = 1024: the raw strip alone would be 256 registers)
-            gemm_strip_kernel<NB, KS, NPH, fused_waves(NB, KS), true><<<grid, fused_waves(NB, KS) * 64, StripCfg<NB, KS, NPH>::LDS, s>>>(p, spp);
+            gemm_strip_kernel<NB, KS, NPH, fused_waves(NB, KS), true, false><<<grid, fused_waves(NB, KS) * 64, StripCfg<NB, KS, NPH>::LDS, s>>>(p, spp);
+    } else if (p.outq) {
+        gemm_strip_kernel<NB, KS, NPH, 8, false, true><<<grid, 512, StripCfg<NB, KS, NPH>::LDS, s>>>(p, spp);
     } else {
-        gemm_strip_kernel<NB, KS, NPH, 8, false><<<grid, 512, StripCfg<NB, KS, NPH>::LDS, s>>>(p, spp);
+        gemm_strip_kernel<NB, KS, NPH, 8, false, false><<<grid, 512, StripCfg<NB, KS, NPH>::LDS, s>>>(p, spp);
     }
 }
 
 template <int NB, int KS, int NPH>
 const void* strip_fused_fn() {
-    if constexpr (NPH == 1 && KS <= 8) return reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS, NPH, fused_waves(NB, KS), true>);
+    if constexpr (NPH == 1 && KS <= 8) return reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS, NPH, fused_waves(NB, KS), true, false>);
     else return nullptr;
 }
 
 #define LOKA_STRIP(NB, KS, NPH)                                                                                     \
-    {NB, KS, NPH, reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS, NPH, 8, false>), strip_fused_fn<NB, KS, NPH>(), \
-     StripCfg<NB, KS, NPH>::LDS, &launch_strip<NB, KS, NPH>}
+    {NB, KS, NPH, reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS, NPH, 8, false, false>), strip_fused_fn<NB, KS, NPH>(), \
+     reinterpret_cast<const void*>(&gemm_strip_kernel<NB, KS, NPH, 8, false, true>), StripCfg<NB, KS, NPH>::LDS,          \
+     &launch_strip<NB, KS, NPH>}
 
 // column blocks, K steps per phase, phases (K = 64 KS NPH; one phase when W fits the LDS)
 const StripInst kStrip[] = {LOKA_STRIP(4, 2, 1), LOKA_STRIP(4, 4, 1), LOKA_STRIP(4, 8, 1), LOKA_STRIP(4, 16, 1),
@@ -476,10 +558,11 @@ bool strip_supports_fused(int64_t M, int64_t N, int64_t K) {
     return w != nullptr && w->fn_fused != nullptr && strip_supports(M, N, K) && M * K < (int64_t(1) << 30);
 }
 
-int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool bf16_in, const void** fn, size_t* lds) {
+int strip_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int cus, bool bf16_in, bool fp8_out, const void** fn,
+               size_t* lds) {
     const StripInst* w = strip_pick(N, K);
-    if (!w || (bf16_in && !w->fn_fused)) return 0;
-    *fn = bf16_in ? w->fn_fused : w->fn;
+    if (!w || (bf16_in && (!w->fn_fused || fp8_out))) return 0;
+    *fn = bf16_in ? w->fn_fused : fp8_out ? w->fn_q : w->fn;
     *lds = w->lds;
     const int64_t strips = batch * ((M + 31) / 32);
     const int waves = bf16_in ? fused_waves(w->nb, w->ks) : 8;
