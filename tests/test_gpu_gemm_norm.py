@@ -391,6 +391,28 @@ def test_fp8_output_equals_quantize_of_the_bf16_output(orc, case, variant):
         assert np.array_equal(oq.cpu().numpy(), q_o) and np.array_equal(so.cpu().numpy(), s_o)
 
 
+@pytest.mark.parametrize("variant", ["wreg32", "strip32"])
+def test_fp8_output_grouped_launch(variant):
+    # several problems with their own weights in one launch, ragged row count: codes and scales of every problem equal
+    # loka_quantize of that launch's bf16 output
+    G, M, K, N = 5, 650, 256, 256
+    v = B.variant_id(variant)
+    x = torch.cat([synth.normal(M, K, 900 + g) for g in range(G)], 0).to(DEV)
+    wq = torch.empty(G * N, K, dtype=torch.uint8, device=DEV)
+    sw = torch.empty(G * N, dtype=torch.float32, device=DEV)
+    for g in range(G):
+        q, s_ = B.loka_quantize(synth.weight(K, N, 950 + g).to(DEV), B.SCALE_COL, transpose_out=True)
+        wq[g * N:(g + 1) * N] = q
+        sw[g * N:(g + 1) * N] = s_
+    xq, sx = B.loka_quantize(x, B.SCALE_ROW)
+    desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_RMSNORM, 1e-5, v)
+    out, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+    oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw)
+    torch.cuda.synchronize()
+    q_ref, s_ref = B.loka_quantize(out, B.SCALE_ROW)
+    assert torch.equal(oq, q_ref) and torch.equal(so.view(torch.int32), s_ref.view(torch.int32))
+
+
 def test_fp8_output_chains_the_skinny_pair(orc):
     # C3 at reduced M: layer a writes codes + row scales, layer b consumes them directly
     wa, wb = synth.WORKLOADS["C3a"], synth.WORKLOADS["C3b"]
