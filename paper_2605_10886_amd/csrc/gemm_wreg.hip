@@ -511,32 +511,43 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         if (p.norm != LOKA_NORM_NONE) {
             LOKA_STAMP(3);
             lds_barrier();
-            // every lane folds the 8 waves of its rows in the same order: identical bits everywhere.  Four
-            // entries are read at a time, the folds are branch-free (an empty part has count 0 and changes nothing).
+            // The two lanes that hold a row (l and l ^ 32) fold four waves' entries each, in order, and merge their
+            // halves symmetrically: identical bits on both, in every wave.  The folds are branch-free (an empty part
+            // has count 0 and changes nothing).
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
                 float tn = 0.f, tmean = 0.f, tm2 = 0.f;
+                float4 r[4];
 #pragma unroll
-                for (int h4 = 0; h4 < 2; ++h4) {
-                    float4 r[4];
+                for (int w = 0; w < 4; ++w) r[w] = red[(rt * 32 + l32) * 9 + 4 * hk + w];
 #pragma unroll
-                    for (int w = 0; w < 4; ++w) r[w] = red[(rt * 32 + l32) * 9 + 4 * h4 + w];
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) {
-                        if (ln) {
-                            const float nn = tn + r[w].x;
-                            const float f = r[w].x > 0.f ? r[w].x * __builtin_amdgcn_rcpf(nn) : 0.f;
-                            const float d = r[w].y - tmean;
-                            tmean = tmean + d * f;
-                            tm2 = tm2 + r[w].z + d * d * tn * f;
-                            tn = nn;
-                        } else if (blocknorm) {
-                            // only the waves that share this wave's group of 256 columns
-                            if ((4 * h4 + w) / WPG == wave / WPG) tm2 += r[w].z;
-                        } else {
-                            tm2 += r[w].z;
-                        }
+                for (int w = 0; w < 4; ++w) {
+                    if (ln) {
+                        const float nn = tn + r[w].x;
+                        const float f = r[w].x > 0.f ? r[w].x * __builtin_amdgcn_rcpf(nn) : 0.f;
+                        const float d = r[w].y - tmean;
+                        tmean = tmean + d * f;
+                        tm2 = tm2 + r[w].z + d * d * tn * f;
+                        tn = nn;
+                    } else if (blocknorm) {
+                        // only the waves that share this wave's group of 256 columns
+                        if ((4 * hk + w) / WPG == wave / WPG) tm2 += r[w].z;
+                    } else {
+                        tm2 += r[w].z;
                     }
+                }
+                if (ln) {
+                    const float nb = wave_shfl_xor(tn, 32), mb = wave_shfl_xor(tmean, 32), m2b = wave_shfl_xor(tm2, 32);
+                    const float nn = tn + nb;
+                    if (nn > 0.f) {
+                        const float d = mb - tmean;
+                        const float rn = __builtin_amdgcn_rcpf(nn);
+                        const float newmean = (tn * tmean + nb * mb) * rn;
+                        tm2 = tm2 + m2b + d * d * (tn * nb * rn);
+                        tmean = newmean;
+                    }
+                } else {
+                    tm2 += wave_shfl_xor(tm2, 32);
                 }
                 mean_r[rt] = ln ? tmean : 0.f;
                 rstd_r[rt] = __builtin_amdgcn_rsqf(tm2 * (blocknorm ? 1.0f / 256.0f : inv_n) + p.eps);
