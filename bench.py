@@ -81,6 +81,7 @@ def run_c3_pair(args):
     out = torch.empty(M, wb.N, dtype=torch.bfloat16, device=dev)
     ws_a = torch.empty(max(16, L.loka_fp8_gemm_norm_workspace(ctypes.byref(da))), dtype=torch.uint8, device=dev)
     ws_b = torch.empty(max(16, L.loka_fp8_gemm_norm_workspace(ctypes.byref(db))), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(max(16, L.loka_fp8_gemm_norm_fp8out_workspace(ctypes.byref(da))), dtype=torch.uint8, device=dev)
 
     def ok(r):
         assert r == 0, r
@@ -95,7 +96,7 @@ def run_c3_pair(args):
     def step_fp8(i):
         quant(xs[i % n_sets], M, wa.K, xq, sx)
         ok(L.loka_fp8_gemm_norm_fp8out(ctypes.byref(da), xq.data_ptr(), sx.data_ptr(), w1q.data_ptr(), s1.data_ptr(), None,
-                                       None, hq.data_ptr(), hs.data_ptr(), None, sp))
+                                       None, hq.data_ptr(), hs.data_ptr(), None, ws_f.data_ptr(), ws_f.numel(), sp))
         layer_b()
 
     def step_bf16(i):
@@ -120,7 +121,7 @@ def run_c3_pair(args):
     # dominant kernel: layer a with FP8 output (reads Xq + W, writes codes + scales)
     t_a = float(np.mean(_event_times(lambda: ok(L.loka_fp8_gemm_norm_fp8out(
         ctypes.byref(da), xq.data_ptr(), sx.data_ptr(), w1q.data_ptr(), s1.data_ptr(), None, None, hq.data_ptr(),
-        hs.data_ptr(), None, sp)), min(args.steps, 20), stream)))
+        hs.data_ptr(), None, ws_f.data_ptr(), ws_f.numel(), sp)), min(args.steps, 20), stream)))
     bytes_a = M * wa.K + wa.N * wa.K + M * wa.N + M * 4
     gbs = bytes_a / (t_a * 1e-3) / 1e9
     cpu = None
@@ -179,7 +180,7 @@ def main():
                     help="after the timed loop run a plain 1 GiB device copy 3x (reference for the HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards along M with no exchange; see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU (the path shards along M with no exchange); "
               "--gpus N with N > 1 is not supported.", file=sys.stderr)
         sys.exit(2)
 

@@ -165,20 +165,31 @@ loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, co
  * without touching the GPU.  Not needed on the hot path; meant for health checks and tests. */
 loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* workspace, size_t ws_bytes, void* hip_stream);
 
-/* FP8 output for the next layer (Section 3.2, "Block-wise Normalization", Case 1: when the whole row is
- * normalized inside one workgroup, "activation and (de)quantization can also be fused together before the
- * final output is written to HBM").  Same computation as loka_fp8_gemm_norm, but instead of bf16 O the call
+/* FP8 output for the next layer (Section 3.2, "Block-wise Normalization", Case 1: once a row is normalized
+ * inside the kernel, the activation and the quantization for the next layer can join the same epilogue, before
+ * anything is written to HBM).  Same computation as loka_fp8_gemm_norm, but instead of bf16 O the call
  * writes what loka_quantize(O_bf16, LOKA_SCALE_ROW) would produce from it, bit for bit:
  *   oq [batch][M, N] e4m3 codes,  so [batch][M] fp32 row scales (amax of the row's bf16 values / 448).
  * The next layer's loka_fp8_gemm_norm takes (oq, so) as its (xq, sx) with x_mode = LOKA_SCALE_ROW.
- * Built into the two kernels that keep a whole output row together: the streaming skinny-layer kernel ("wreg32":
- * N <= 1024, K in {128, 256, 512, 1024}, K * N <= 256 KB) and the small-layer strip kernel ("strip32": N <= 256,
- * K * N <= 256 KB), non-blockwise input scales.  desc->variant names one, or -1: the library's choice for the shape
- * when it is one of the two, else the streaming kernel.  LOKA_ERR_UNSUPPORTED otherwise.  No workspace.
+ * Built into three kernels, non-blockwise input scales:
+ *   "wreg32"  (streaming skinny-layer kernel: N <= 1024, K in {128, 256, 512, 1024}, K * N <= 256 KB) and
+ *   "strip32" (small-layer strip kernel: N <= 256, K * N <= 256 KB): the whole output row is in one workgroup /
+ *             wave; every norm, gamma / beta and activation loka_fp8_gemm_norm takes;
+ *   "panel32_256x256" (large layers, rows wider than a tile): LayerNorm or RMSNorm WITHOUT gamma, beta or an
+ *             activation only - the normalized value then grows with the pre-norm value, so the row minimum and
+ *             maximum, sent along with the row statistics in the one exchange between the row's workgroups, decide
+ *             the row scale; with an affine step the extremum can be anywhere and a second exchange would cost what
+ *             the separate loka_quantize pass costs: LOKA_ERR_UNSUPPORTED, use the two calls.
+ * desc->variant names one, or -1: the library's choice for the shape when it is one of the three, else the
+ * streaming kernel.  LOKA_ERR_UNSUPPORTED otherwise.
+ * Workspace: loka_fp8_gemm_norm_fp8out_workspace(desc) bytes (non-zero only for the panel kernel with rows wider
+ * than 256 columns; NULL / 0 otherwise), device memory, 16-byte aligned, not shared with a call still running;
+ * loka_fp8_gemm_norm_check reports the panel kernel's bounded wait on it as for loka_fp8_gemm_norm.
  * y_fp32 as above (NULL to skip).  oq, so: device pointers, 16-byte aligned, caller-owned. */
+size_t loka_fp8_gemm_norm_fp8out_workspace(const loka_gemm_desc* desc);
 loka_status loka_fp8_gemm_norm_fp8out(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
                                       const float* sw, const void* gamma_bf16, const void* beta_bf16, uint8_t* oq,
-                                      float* so, float* y_fp32, void* hip_stream);
+                                      float* so, float* y_fp32, void* workspace, size_t ws_bytes, void* hip_stream);
 
 /* Quantization fused into the layer (Section 2.3, "Throughput Analysis": quantization overhead can exceed 30 % of
  * the GEMM's latency, and memory traffic for the low-precision copy can cancel the gain; Section 3.2: activation

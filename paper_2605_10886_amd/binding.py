@@ -75,8 +75,9 @@ _SIGNATURES = [
     ("loka_fp8_linear_norm", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                      c_void_p, c_void_p]),
     ("loka_fp8_gemm_norm_check", c_int, [POINTER(GemmDesc), c_void_p, c_size_t, c_void_p]),
+    ("loka_fp8_gemm_norm_fp8out_workspace", c_size_t, [POINTER(GemmDesc)]),
     ("loka_fp8_gemm_norm_fp8out", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
-                                          c_void_p, c_void_p, c_void_p, c_void_p]),
+                                          c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     ("loka_bf16_gemm_workspace", c_size_t, [POINTER(GemmDesc)]),
     ("loka_bf16_gemm", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     ("loka_probe_error_workspace", c_size_t, [c_int64, c_int64]),
@@ -227,7 +228,7 @@ def loka_fp8_gemm_norm_check(desc: GemmDesc, workspace) -> int:
 
 
 def loka_fp8_gemm_norm_fp8out(desc: GemmDesc, xq, sx, wq, sw, gamma=None, beta=None, want_y: bool = False, oq=None,
-                              so=None, y=None):
+                              so=None, y=None, workspace=None):
     """Returns (codes uint8 [batch*M, N], row scales fp32 [batch*M], Y fp32 or None)."""
     rows = desc.batch * desc.M
     dev = xq.device
@@ -237,8 +238,13 @@ def loka_fp8_gemm_norm_fp8out(desc: GemmDesc, xq, sx, wq, sw, gamma=None, beta=N
         so = torch.empty(rows, dtype=torch.float32, device=dev)
     if want_y and y is None:
         y = torch.empty((rows, desc.N), dtype=torch.float32, device=dev)
+    need = int(lib().loka_fp8_gemm_norm_fp8out_workspace(byref(desc)))
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     _check(lib().loka_fp8_gemm_norm_fp8out(byref(desc), _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), _ptr(gamma), _ptr(beta),
-                                           _ptr(oq), _ptr(so), _ptr(y), _stream()), "loka_fp8_gemm_norm_fp8out")
+                                           _ptr(oq), _ptr(so), _ptr(y), _ptr(workspace),
+                                           0 if workspace is None else workspace.numel(), _stream()),
+           "loka_fp8_gemm_norm_fp8out")
     return oq, so, y
 
 

@@ -20,6 +20,7 @@ loka_status fp8_gemm_norm_launch(const loka_gemm_desc*, int, const uint8_t*, con
 int variant_streaming_id();
 bool variant_is_streaming(int);
 bool variant_is_strip(int);
+bool variant_is_panel32(int);
 bool variant_supports_fused(const loka_gemm_desc*, int);
 int variant_fused_default(const loka_gemm_desc*);
 loka_status fp8_linear_norm_launch(const loka_gemm_desc*, int, const void*, const uint8_t*, const float*, const void*,
@@ -212,21 +213,39 @@ loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* wor
     return flag ? LOKA_ERR_TIMEOUT : LOKA_OK;
 }
 
+// The kernels with an FP8-output epilogue: the two that keep a whole output row inside one workgroup (streaming) or
+// one wave (strip), and the large-layer panel kernel (which sends the row extremes along with the row statistics).
+// The one the caller names, else the library's choice for the shape when it is one of the three, else the
+// streaming one.  -1 when the named variant has no such epilogue or cannot run the shape.
+static int fp8out_variant(const loka_gemm_desc* desc) {
+    auto has_epilogue = [](int v) { return variant_is_streaming(v) || variant_is_strip(v) || variant_is_panel32(v); };
+    int v = desc->variant >= 0 ? desc->variant : default_variant(desc);
+    if (desc->variant < 0 && !(v >= 0 && has_epilogue(v) && variant_supports(desc, v))) v = variant_streaming_id();
+    if (v < 0 || !has_epilogue(v) || !variant_supports(desc, v)) return -1;
+    return v;
+}
+
+size_t loka_fp8_gemm_norm_fp8out_workspace(const loka_gemm_desc* desc) {
+    if (validate_desc(desc, true) != LOKA_OK) return 0;
+    const int v = fp8out_variant(desc);
+    return v < 0 ? 0 : variant_workspace(desc, v);
+}
+
 loka_status loka_fp8_gemm_norm_fp8out(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
                                       const float* sw, const void* gamma_bf16, const void* beta_bf16, uint8_t* oq,
-                                      float* so, float* y_fp32, void* hip_stream) {
+                                      float* so, float* y_fp32, void* workspace, size_t ws_bytes, void* hip_stream) {
     if (!desc || !xq || !sx || !wq || !sw || !oq || !so) return LOKA_ERR_NULL;
     const loka_status st = validate_desc(desc, true);
     if (st != LOKA_OK) return st;
     if (!aligned16(xq) || !aligned16(wq) || !aligned16(sx) || !aligned16(sw) || !aligned16(oq) || !aligned16(so) ||
         !aligned16(y_fp32) || !aligned16(gamma_bf16) || !aligned16(beta_bf16))
         return LOKA_ERR_ALIGN;
-    // the kernels that keep a whole output row inside one workgroup (streaming) or one wave (strip) have this epilogue:
-    // the one the caller names, else the library's choice for the shape when it is one of the two, else the streaming one
-    int v = desc->variant >= 0 ? desc->variant : default_variant(desc);
-    if (desc->variant < 0 && !(v >= 0 && (variant_is_streaming(v) || variant_is_strip(v)))) v = variant_streaming_id();
-    if (v < 0 || !(variant_is_streaming(v) || variant_is_strip(v)) || !variant_supports(desc, v)) return LOKA_ERR_UNSUPPORTED;
-    return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, nullptr, y_fp32, oq, so, nullptr,
+    const int v = fp8out_variant(desc);
+    if (v < 0) return LOKA_ERR_UNSUPPORTED;
+    const size_t need = variant_workspace(desc, v);
+    if (need && (!workspace || ws_bytes < need)) return LOKA_ERR_WORKSPACE;
+    if (need && !aligned16(workspace)) return LOKA_ERR_ALIGN;
+    return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, nullptr, y_fp32, oq, so, workspace,
                                 static_cast<hipStream_t>(hip_stream));
 }
 

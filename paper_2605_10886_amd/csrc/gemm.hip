@@ -492,7 +492,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
             // bounded wait: every workgroup of the panel is resident, so this ends after the slowest
             // one's main loop; the limit only turns a scheduling surprise into an error flag
             unsigned spins = 0;
-            while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < static_cast<unsigned>(p.tiles_n)) {
+            while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.arrivals) {
                 __builtin_amdgcn_s_sleep(16);
                 if (++spins > p.spin_limit) {
                     __hip_atomic_store(p.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -719,7 +719,7 @@ static const char kStripName[] = "strip32";
 static const char kPanel32Name[] = "panel32_256x256";
 
 // gemm_panel32.hip
-const void* panel32_fn(int bw);
+const void* panel32_fn(int bw, bool fp8out);
 size_t panel32_lds();
 void panel32_launch(const GemmParams& p, int bw, dim3 grid, hipStream_t s);
 // block scales: power-of-two ones go to the matrix cores, others rescale the accumulators
@@ -756,7 +756,7 @@ static const VariantInfo kVariants[] = {
     // through a few words of global memory and normalize their own tile in registers
     LOKA_VARIANT("panel256x256w8", 256, 256, 1, 2, 4, EPI_PANEL_SYNC),
     // the same schedule on 32x32x64 MFMAs: the throughput variant
-    {kPanel32Name, 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(0), panel32_fn(1)},
+    {kPanel32Name, 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(0, false), panel32_fn(1, false)},
 };
 constexpr int kNumCUs = 256;          // MI355X; the launch re-checks against the device it runs on
 constexpr unsigned kSpinLimit = 1u << 18;   // polls of ~1 us each (a device-scope load and a short sleep): far beyond any main loop
@@ -797,6 +797,7 @@ int variant_streaming_id() {
 }
 bool variant_is_streaming(int v) { return kVariants[v].name == kWregName; }
 bool variant_is_strip(int v) { return kVariants[v].name == kStripName; }
+bool variant_is_panel32(int v) { return kVariants[v].name == kPanel32Name; }
 int variant_bn(int v) { return kVariants[v].bn; }
 int variant_bm(int v) { return kVariants[v].bm; }
 
@@ -832,6 +833,9 @@ size_t variant_workspace(const loka_gemm_desc* d, int v) {
     if (vi.epi == EPI_ROW_IN_TILE || d->norm == LOKA_NORM_NONE || d->norm == LOKA_NORM_BLOCKNORM) return 0;
     const int64_t tiles_n = (d->N + vi.bn - 1) / vi.bn;
     size_t stats = static_cast<size_t>(d->batch) * d->M * tiles_n * 2 * sizeof(float);
+    // the 32x32 panel kernel keeps a record for every row of every 256-row panel, and its FP8-output form exchanges
+    // the row minimum and maximum as well
+    if (vi.name == kPanel32Name) stats = static_cast<size_t>(d->batch) * ((d->M + vi.bm - 1) / vi.bm) * vi.bm * tiles_n * 2 * sizeof(float) * 2;
     stats = (stats + 255) & ~size_t(255);
     if (vi.epi == EPI_PANEL_SYNC) {
         if (!panel_exchanges(d, vi)) return 0;
@@ -899,8 +903,15 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
     p.out = static_cast<uint16_t*>(out); p.y = y;
     p.outq = outq; p.outs = outs;
     p.xb = static_cast<const uint16_t*>(x_bf16); p.sx_out = sx_out;
-    // FP8 output: the row must stay inside one workgroup (streaming kernel) or one wave (strip kernel)
-    if (outq && vi.name != kWregName && vi.name != kStripName) return LOKA_ERR_UNSUPPORTED;
+    // FP8 output: the row stays inside one workgroup (streaming kernel) or one wave (strip kernel), or - panel kernel -
+    // its extreme values travel with the row statistics, which decides the row scale only when the normalized
+    // value grows with the pre-norm value: LayerNorm / RMSNorm without gamma, beta or an activation
+    if (outq && vi.name == kPanel32Name) {
+        if (blockwise || gamma || beta || d->act != LOKA_ACT_NONE) return LOKA_ERR_UNSUPPORTED;
+        if (d->norm != LOKA_NORM_LAYERNORM && d->norm != LOKA_NORM_RMSNORM) return LOKA_ERR_UNSUPPORTED;
+    } else if (outq && vi.name != kWregName && vi.name != kStripName) {
+        return LOKA_ERR_UNSUPPORTED;
+    }
     p.norm = d->norm; p.eps = d->eps; p.block_n = d->block_n; p.act = d->act;
     p.tiles_m = static_cast<int>((d->M + vi.bm - 1) / vi.bm);
     p.tiles_n = static_cast<int>((d->N + vi.bn - 1) / vi.bn);
@@ -936,7 +947,8 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
     }
     const void* kfn = blockwise ? vi.fn_block : vi.fn_plain;
-    if (vi.name == kPanel32Name) kfn = panel32_fn(panel32_bw(p, blockwise));
+    if (vi.name == kPanel32Name) kfn = panel32_fn(panel32_bw(p, blockwise), outq != nullptr);
+    if (!kfn) return LOKA_ERR_UNSUPPORTED;
     if (set_lds(kfn, vi.lds) != LOKA_OK) return LOKA_ERR_HIP;
     dim3 grid(static_cast<unsigned>(static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.batch));
     if (vi.epi == EPI_PANEL_SYNC) {
@@ -957,7 +969,14 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
             p.counters = reinterpret_cast<unsigned*>(ws + 256);
             p.part = reinterpret_cast<float*>(ws + 256 + ctr_bytes);
             p.spin_limit = kSpinLimit;
-            if (const char* e = std::getenv("LOKA_SPIN_LIMIT")) p.spin_limit = static_cast<unsigned>(std::strtoul(e, nullptr, 10));
+            p.arrivals = static_cast<unsigned>(p.tiles_n);
+            // Test hook for the error path: LOKA_SPIN_LIMIT overrides the number of polls, and a limit of 0 also makes
+            // the workgroups wait for one arrival more than there are tiles, so that every wait runs out after its
+            // first poll whatever the timing (the kernel still ends; the output of that launch is invalid).
+            if (const char* e = std::getenv("LOKA_SPIN_LIMIT")) {
+                p.spin_limit = static_cast<unsigned>(std::strtoul(e, nullptr, 10));
+                if (p.spin_limit == 0) p.arrivals += 1;
+            }
             const int64_t words = (256 + static_cast<int64_t>(ctr_bytes)) / 4;
             zero_u32_kernel<<<dim3(static_cast<unsigned>((words + 255) / 256)), 256, 0, s>>>(
                 reinterpret_cast<uint32_t*>(ws), words);

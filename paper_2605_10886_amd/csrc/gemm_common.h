@@ -31,9 +31,11 @@ struct GemmParams {
     float eps;
     int tiles_m, tiles_n;
     float* part;           // EPI_PARTIAL_STATS / EPI_PANEL_SYNC: [batch][M][tiles_n * 2] (mean, M2) or (0, sumsq)
+                           // (gemm_panel32.hip: [batch][tiles_m][tiles_n][256] such pairs, then as many (min, max) pairs)
     unsigned* counters;    // EPI_PANEL_SYNC: arrivals per (problem, m tile), zeroed before the launch
     unsigned* error_flag;  // EPI_PANEL_SYNC: set when a bounded wait ran out
     unsigned spin_limit;
+    unsigned arrivals;     // EPI_PANEL_SYNC: counter value a workgroup waits for (tiles_n; one more in the error-path test)
 };
 
 #ifdef LOKA_DEBUG_TIMES

@@ -27,7 +27,14 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 // BW: 0 = one scale per row / column / tensor (applied in the epilogue); 1 = block scales, accumulators rescaled
 // per K block; 2 = power-of-two block scales handed to the matrix cores (scaled MFMA), nothing to rescale.
-template <int EPI, int BW>
+// FP8OUT: instead of bf16 O the tile leaves as e4m3 codes with one scale per output row, exactly what a rowwise
+// quantization of the bf16 output would give.  Without an affine step the normalized value (y - mean) * rstd grows
+// with y, and so does its bf16 rounding: the row's largest magnitude is reached at the row's largest or smallest
+// y, so the row minimum and maximum travel with the row statistics in the ONE exchange between the workgroups of a
+// panel and every workgroup derives the row scale from them.  (With gamma / beta the extremum can sit anywhere:
+// that needs a second exchange after normalization, as long as the separate quantization pass it would save;
+// the host rejects it.)
+template <int EPI, int BW, bool FP8OUT>
 __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     constexpr bool BLOCKWISE = BW != 0;
     constexpr int BM = 256, BN = 256, NW = 8, WM = 128, WN = 64, MI = 4, NI = 2;
@@ -341,6 +348,9 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     // ------------------------------------------------------------------ epilogue
     float* red = reinterpret_cast<float*>(smem);                                   // [BM][4][3]
     float2* fin = reinterpret_cast<float2*>(smem) + BM * 4 * 3 / 2 + 8;            // [BM] (mean, rstd)
+    float* finq = reinterpret_cast<float*>(fin + BM);                              // [BM] 448 / amax of the output row (FP8OUT)
+    float* red2 = reinterpret_cast<float*>(smem + 16384);                          // [BM][4][2] (min, max) (FP8OUT); the
+                                                                                   // transpose buffers take its place later
     const int64_t obase = static_cast<int64_t>(g) * p.strideO;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
@@ -368,9 +378,10 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
 
     float mean_r[MI], rstd_r[MI];
     const bool ln = p.norm == LOKA_NORM_LAYERNORM;
+    float iq_r[MI];
     if (p.norm == LOKA_NORM_NONE) {
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) { mean_r[mi] = 0.f; rstd_r[mi] = 1.f; }
+        for (int mi = 0; mi < MI; ++mi) { mean_r[mi] = 0.f; rstd_r[mi] = 1.f; iq_r[mi] = 1.f; }
     } else {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
@@ -414,10 +425,28 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 float* r3 = red + ((wave_m * WM + mi * 32 + l32) * 4 + wave_n) * 3;
                 r3[0] = n_; r3[1] = mean; r3[2] = m2;
             }
+            if (FP8OUT) {
+                float lo = __builtin_inff(), hi = -__builtin_inff();
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    if (ncol[ni] < p.N) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            lo = __builtin_fminf(lo, acc[mi][ni][i]);
+                            hi = __builtin_fmaxf(hi, acc[mi][ni][i]);
+                        }
+                    }
+                lo = __builtin_fminf(lo, wave_shfl_xor(lo, 32));
+                hi = __builtin_fmaxf(hi, wave_shfl_xor(hi, 32));
+                if (hk == 0) {
+                    float* r2 = red2 + ((wave_m * WM + mi * 32 + l32) * 4 + wave_n) * 2;
+                    r2[0] = lo; r2[1] = hi;
+                }
+            }
         }
         __syncthreads();
         // tile statistics per row: thread r < 256 merges the four column waves in order
-        float t_mean = 0.f, t_m2 = 0.f;
+        float t_mean = 0.f, t_m2 = 0.f, t_lo = __builtin_inff(), t_hi = -__builtin_inff();
         if (tid < BM) {
             float n_ = 0.f;
 #pragma unroll
@@ -425,21 +454,44 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 const float* r3 = red + (tid * 4 + w) * 3;
                 if (ln) merge_stats(n_, t_mean, t_m2, r3[0], r3[1], r3[2]);
                 else t_m2 += r3[2];
+                if (FP8OUT) {
+                    t_lo = __builtin_fminf(t_lo, red2[(tid * 4 + w) * 2]);
+                    t_hi = __builtin_fmaxf(t_hi, red2[(tid * 4 + w) * 2 + 1]);
+                }
             }
         }
+        // FP8OUT: the row scale from the row's extreme pre-norm values, through the very operations the
+        // normalization applies to every element (one fused multiply-add, bf16 rounding)
+        auto row_scale = [&](int r, float mean, float rstd, float lo, float hi) __attribute__((always_inline)) {
+            const float nmr = -mean * rstd;
+            const unsigned pk = pack_bf16x2(__builtin_fmaf(lo, rstd, nmr), __builtin_fmaf(hi, rstd, nmr));
+            const unsigned a = pk & 0x7FFFu, b = (pk >> 16) & 0x7FFFu;
+            float scale, inv;
+            group_scale(__uint_as_float((a > b ? a : b) << 16), scale, inv);
+            finq[r] = inv;
+            if (tn == 0 && m0 + r < p.M) p.outs[static_cast<int64_t>(g) * p.M + m0 + r] = scale;
+        };
         LOKA_STAMP(2);
         const bool blocknorm = p.norm == LOKA_NORM_BLOCKNORM;   // groups of 256 columns = this tile: nothing to exchange
         if (EPI == EPI_PANEL_SYNC && !blocknorm && p.tiles_n > 1) {
             // publish (mean, M2) of this tile per row, signal, wait for the panel's other tiles, merge all tiles
             const int panel = g * p.tiles_m + tm;
-            float* prow = p.part + (static_cast<int64_t>(g) * p.M) * (2 * p.tiles_n);
+            // Exchange area of a panel: [tiles_n][256 rows] records of 8 bytes, so that a tile's 256 threads write
+            // one contiguous 2 KB run and the merging threads of consecutive rows read consecutive records (a
+            // row-major [row][tile] layout makes every lane of a load touch a cache line of its own, and the 256
+            // workgroups' merges then queue at the L2 channels).  (min, max) per row and tile: a second array of the
+            // same shape behind the statistics of all panels.
+            unsigned long long* pbase = reinterpret_cast<unsigned long long*>(p.part) + static_cast<int64_t>(panel) * p.tiles_n * BM;
+            const int64_t mm_off = static_cast<int64_t>(p.batch) * p.tiles_m * p.tiles_n * BM;
             if (tid < BM) {
-                const int m = m0 + tid;
-                if (m < p.M) {
-                    float* dst = prow + static_cast<int64_t>(m) * (2 * p.tiles_n) + 2 * tn;
-                    __hip_atomic_store(dst, t_mean, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(dst + 1, t_m2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
+                unsigned long long* dst = pbase + tn * BM + tid;
+                __hip_atomic_store(dst, static_cast<unsigned long long>(__float_as_uint(t_mean)) |
+                                            (static_cast<unsigned long long>(__float_as_uint(t_m2)) << 32),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (FP8OUT)
+                    __hip_atomic_store(dst + mm_off, static_cast<unsigned long long>(__float_as_uint(t_lo)) |
+                                                         (static_cast<unsigned long long>(__float_as_uint(t_hi)) << 32),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // the stores have completed before the barrier
             }
             __syncthreads();
@@ -448,7 +500,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 unsigned* ctr = p.counters + panel;
                 __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 unsigned spins = 0;
-                while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < static_cast<unsigned>(p.tiles_n)) {
+                while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.arrivals) {
                     __builtin_amdgcn_s_sleep(2);          // (measured: 16 costs 2 % of the kernel at 32768 x 4096 x 4096, 0 gains nothing more)
                     if (++spins > p.spin_limit) {
                         __hip_atomic_store(p.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -462,19 +514,17 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             // 8-byte loads), symmetric merge of the halves: identical bits in every workgroup of the panel
             {
                 const int r = static_cast<int>(tid) >> 1, sub = static_cast<int>(tid) & 1;
-                int m = m0 + r;
-                m = m < p.M ? m : p.M - 1;
-                const float* src = prow + static_cast<int64_t>(m) * (2 * p.tiles_n);
+                const unsigned long long* src = pbase + r;
                 const int TH = (p.tiles_n + 1) >> 1;
-                float n_ = 0.f, mean = 0.f, m2 = 0.f;
+                float n_ = 0.f, mean = 0.f, m2 = 0.f, lo = __builtin_inff(), hi = -__builtin_inff();
                 for (int t0 = sub * TH; t0 < (sub + 1) * TH && t0 < p.tiles_n; t0 += 8) {
-                    unsigned long long raw[8];
+                    unsigned long long raw[8], raw2[8];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
                         int tt = t0 + u;
                         tt = tt < p.tiles_n ? tt : p.tiles_n - 1;
-                        raw[u] = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src + 2 * tt),
-                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        raw[u] = __hip_atomic_load(src + tt * BM, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (FP8OUT) raw2[u] = __hip_atomic_load(src + mm_off + tt * BM, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
@@ -485,6 +535,10 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                             const int wcols = (tt + 1) * BN <= p.N ? BN : p.N - tt * BN;
                             if (ln) merge_stats(n_, mean, m2, static_cast<float>(wcols), a, b2);
                             else m2 += b2;
+                            if (FP8OUT) {
+                                lo = __builtin_fminf(lo, __uint_as_float(static_cast<unsigned>(raw2[u])));
+                                hi = __builtin_fmaxf(hi, __uint_as_float(static_cast<unsigned>(raw2[u] >> 32)));
+                            }
                         }
                     }
                 }
@@ -501,12 +555,23 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 } else {
                     m2 = m2 + m2b;
                 }
-                if (sub == 0) fin[r] = make_float2(ln ? mean : 0.f, __builtin_amdgcn_rsqf(m2 * inv_n + p.eps));
+                if (FP8OUT) {
+                    lo = __builtin_fminf(lo, wave_shfl_xor(lo, 1));
+                    hi = __builtin_fmaxf(hi, wave_shfl_xor(hi, 1));
+                }
+                if (sub == 0) {
+                    const float2 f = make_float2(ln ? mean : 0.f, __builtin_amdgcn_rsqf(m2 * inv_n + p.eps));
+                    fin[r] = f;
+                    if (FP8OUT) row_scale(r, f.x, f.y, lo, hi);
+                }
             }
         } else {
             // the tile spans the whole row (N <= 256): finalize here
-            if (tid < BM)
-                fin[tid] = make_float2(ln ? t_mean : 0.f, __builtin_amdgcn_rsqf(t_m2 * (blocknorm ? 1.0f / BN : inv_n) + p.eps));
+            if (tid < BM) {
+                const float2 f = make_float2(ln ? t_mean : 0.f, __builtin_amdgcn_rsqf(t_m2 * (blocknorm ? 1.0f / BN : inv_n) + p.eps));
+                fin[tid] = f;
+                if (FP8OUT) row_scale(static_cast<int>(tid), f.x, f.y, t_lo, t_hi);
+            }
         }
         __syncthreads();
 #pragma unroll
@@ -514,6 +579,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             const float2 f = fin[wave_m * WM + mi * 32 + l32];
             mean_r[mi] = f.x;
             rstd_r[mi] = f.y;
+            if (FP8OUT) iq_r[mi] = finq[wave_m * WM + mi * 32 + l32];
         }
     }
     float nmr_r[MI];
@@ -531,6 +597,36 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     uint8_t* const tbuf = smem + 16384 + wave * 2048;
     const int t_wr = l32 * 64, t_key = (l32 >> 2) & 3;
     const int t_row = lane >> 2, t_c = lane & 3;                       // store side: row (+ 16 j), chunk
+    if (FP8OUT) {
+        // 16 codes per lane and sub-tile; the wave's 64 columns of 32 rows pass through the transpose buffer at once
+        // (64-byte rows of codes) and leave as full 64-byte runs, 4 lanes per row
+        (void)has_g; (void)has_b; (void)hswish;
+        const int col = n0 + wave_n * WN + t_c * 16;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                unsigned ck[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(acc[mi][ni][4 * q + e], rstd_r[mi], nmr_r[mi]);
+                    const unsigned p0 = pack_bf16x2(o[0], o[1]), p1 = pack_bf16x2(o[2], o[3]);
+                    ck[q] = e4m3x4(bf16_lo(p0) * iq_r[mi], bf16_hi(p0) * iq_r[mi], bf16_lo(p1) * iq_r[mi], bf16_hi(p1) * iq_r[mi]);
+                }
+                *reinterpret_cast<u32x4*>(tbuf + t_wr + (((2 * ni + hk) ^ t_key) << 4)) = u32x4{ck[0], ck[1], ck[2], ck[3]};
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int r = 16 * j + t_row;
+                const u32x4 ck = *reinterpret_cast<const u32x4*>(tbuf + r * 64 + ((t_c ^ ((r >> 2) & 3)) << 4));
+                const int m = m0 + wave_m * WM + mi * 32 + r;
+                if (m < p.M && col < p.N)
+                    __builtin_nontemporal_store(ck, reinterpret_cast<u32x4*>(p.outq + obase + static_cast<int64_t>(m) * p.N + col));
+            }
+        }
+    } else {
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
         float gm[16], bt[16];
@@ -581,6 +677,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             }
         }
     }
+    }
     LOKA_STAMP(6);
     }
     lds_barrier();              // the epilogue's scratch (slot 0) is read: the next tile may load into it.  The
@@ -596,17 +693,19 @@ extern "C" int loka_debug_read_times32(unsigned long long* host, int n) {
 
 constexpr size_t kPanel32Lds = 5 * 256 * 128;   // the ring; the epilogue's scratch aliases it
 
-// bw: 0 plain scales, 1 block scales, 2 power-of-two block scales (see the kernel)
-const void* panel32_fn(int bw) {
-    return bw == 2   ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 2>)
-           : bw == 1 ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 1>)
-                     : reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0>);
+// bw: 0 plain scales, 1 block scales, 2 power-of-two block scales (see the kernel); fp8out with bw == 0 only
+const void* panel32_fn(int bw, bool fp8out) {
+    if (fp8out) return bw == 0 ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0, true>) : nullptr;
+    return bw == 2   ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 2, false>)
+           : bw == 1 ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 1, false>)
+                     : reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0, false>);
 }
 size_t panel32_lds() { return kPanel32Lds; }
 void panel32_launch(const GemmParams& p, int bw, dim3 grid, hipStream_t s) {
-    if (bw == 2) gemm_panel32_kernel<EPI_PANEL_SYNC, 2><<<grid, 512, kPanel32Lds, s>>>(p);
-    else if (bw == 1) gemm_panel32_kernel<EPI_PANEL_SYNC, 1><<<grid, 512, kPanel32Lds, s>>>(p);
-    else gemm_panel32_kernel<EPI_PANEL_SYNC, 0><<<grid, 512, kPanel32Lds, s>>>(p);
+    if (p.outq) gemm_panel32_kernel<EPI_PANEL_SYNC, 0, true><<<grid, 512, kPanel32Lds, s>>>(p);
+    else if (bw == 2) gemm_panel32_kernel<EPI_PANEL_SYNC, 2, false><<<grid, 512, kPanel32Lds, s>>>(p);
+    else if (bw == 1) gemm_panel32_kernel<EPI_PANEL_SYNC, 1, false><<<grid, 512, kPanel32Lds, s>>>(p);
+    else gemm_panel32_kernel<EPI_PANEL_SYNC, 0, false><<<grid, 512, kPanel32Lds, s>>>(p);
 }
 
 }  // namespace loka

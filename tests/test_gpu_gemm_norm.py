@@ -435,12 +435,103 @@ def test_fp8_output_chains_the_skinny_pair(orc):
     assert torch.equal(out_fused.view(torch.int16), out_ref.view(torch.int16))
 
 
-def test_fp8_output_unsupported_shapes():
-    d = B.make_desc(512, 4096, 4096, 1)                                       # rows wider than a workgroup keeps
+# the large-layer kernel: a row spans several workgroups; the row extremes travel with the row statistics
+PANEL_FP8_CASES = [
+    (700, 512, 1024, "layernorm"),        # 4 tiles per row, ragged last row panel
+    (1300, 256, 4096, "rmsnorm"),         # 16 tiles per row: both halves of the tile fold, several panels per workgroup slot
+    (520, 384, 2320, "layernorm"),        # ragged last column tile (2320 = 9 * 256 + 16)
+    (300, 1024, 256, "layernorm"),        # one tile per row: no exchange, finalized in the tile
+    (260, 128, 176, "rmsnorm"),           # one ragged tile, a single K step
+    (66000, 128, 512, "layernorm"),       # more row panels than the persistent grid has slots
+]
+
+
+@pytest.mark.parametrize("case", PANEL_FP8_CASES)
+def test_fp8_output_of_the_panel_kernel(orc, case):
+    # codes and row scales bit for bit what loka_quantize(O_bf16, ROW) writes from the same kernel's bf16 output
+    # (itself checked against the oracle above), and what the oracle's quantize makes of that tensor
+    M, K, N, norm = case
+    x = synth.student_t4(M, K, seed=11 * M)
+    wt = synth.weight(K, N, seed=11 * N)
+    v = B.variant_id("panel32_256x256")
+    for xm, wm in ((B.SCALE_ROW, B.SCALE_COL), (B.SCALE_TENSOR, B.SCALE_TENSOR)):
+        xq, sx = B.loka_quantize(x.to(DEV), xm)
+        wq, sw = B.loka_quantize(wt.to(DEV), wm, transpose_out=True)
+        desc = B.make_desc(M, N, K, 1, xm, wm, B.NORMS[norm], 1e-5, v)
+        out, y = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, want_y=True)
+        need = B.lib().loka_fp8_gemm_norm_fp8out_workspace(desc)
+        assert (need > 0) == (N > 256)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=DEV)
+        oq, so, y2 = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, want_y=True, workspace=ws)
+        torch.cuda.synchronize()
+        assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
+        assert torch.equal(y, y2)
+        q_ref, s_ref = B.loka_quantize(out, B.SCALE_ROW)
+        assert torch.equal(so.view(torch.int32), s_ref.view(torch.int32)), f"{case} scales differ"
+        assert torch.equal(oq, q_ref), f"{case} codes differ from loka_quantize of the bf16 output"
+        if M <= 2000:
+            q_o, s_o = orc.quantize(to_np_bits(out), B.SCALE_ROW)
+            assert np.array_equal(oq.cpu().numpy(), q_o) and np.array_equal(so.cpu().numpy(), s_o)
+
+
+def test_fp8_output_of_the_panel_kernel_grouped_and_repeated():
+    # several problems in one launch; the same workspace serves consecutive launches (counters cleared by the launch)
+    G, M, K, N = 3, 530, 256, 768
+    v = B.variant_id("panel32_256x256")
+    wq = torch.empty(G * N, K, dtype=torch.uint8, device=DEV)
+    sw = torch.empty(G * N, dtype=torch.float32, device=DEV)
+    for g in range(G):
+        q, s_ = B.loka_quantize(synth.weight(K, N, 960 + g).to(DEV), B.SCALE_COL, transpose_out=True)
+        wq[g * N:(g + 1) * N] = q
+        sw[g * N:(g + 1) * N] = s_
+    desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, 1e-5, v)
+    ws = torch.empty(B.lib().loka_fp8_gemm_norm_fp8out_workspace(desc), dtype=torch.uint8, device=DEV)
+    for rep in range(3):
+        x = torch.cat([synth.normal(M, K, 970 + 10 * rep + g) for g in range(G)], 0).to(DEV)
+        xq, sx = B.loka_quantize(x, B.SCALE_ROW)
+        out, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+        oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws)
+        torch.cuda.synchronize()
+        q_ref, s_ref = B.loka_quantize(out, B.SCALE_ROW)
+        assert torch.equal(oq, q_ref) and torch.equal(so.view(torch.int32), s_ref.view(torch.int32)), rep
+
+
+def test_fp8_output_chains_two_large_layers():
+    # layer a (panel kernel, FP8 out) feeds layer b directly: same bits as bf16 hand-over + loka_quantize
+    M, K, H, N = 1024, 512, 2048, 1024
+    x = synth.student_t4(M, K, seed=31)
+    w1, w2 = synth.weight(K, H, seed=32), synth.weight(H, N, seed=33)
+    xq, sx = B.loka_quantize(x.to(DEV), B.SCALE_ROW)
+    w1q, s1 = B.loka_quantize(w1.to(DEV), B.SCALE_COL, transpose_out=True)
+    w2q, s2 = B.loka_quantize(w2.to(DEV), B.SCALE_COL, transpose_out=True)
+    v = B.variant_id("panel32_256x256")
+    da = B.make_desc(M, H, K, 1, norm=B.NORM_LAYERNORM, variant=v)
+    db = B.make_desc(M, N, H, 1, norm=B.NORM_RMSNORM, variant=v)
+    hq, hs, _ = B.loka_fp8_gemm_norm_fp8out(da, xq, sx, w1q, s1)
+    out_fused, _ = B.loka_fp8_gemm_norm(db, hq, hs, w2q, s2)
+    h, _ = B.loka_fp8_gemm_norm(da, xq, sx, w1q, s1)
+    hq2, hs2 = B.loka_quantize(h, B.SCALE_ROW)
+    out_ref, _ = B.loka_fp8_gemm_norm(db, hq2, hs2, w2q, s2)
+    torch.cuda.synchronize()
+    assert torch.equal(hq, hq2) and torch.equal(hs, hs2)
+    assert torch.equal(out_fused.view(torch.int16), out_ref.view(torch.int16))
+
+
+def test_fp8_output_unsupported_cases():
+    M, K, N = 512, 4096, 4096                                                 # rows wider than a workgroup keeps
+    xq, sx = torch.zeros(M, K, dtype=torch.uint8, device=DEV), torch.ones(M, device=DEV)
+    wq, sw = torch.zeros(N, K, dtype=torch.uint8, device=DEV), torch.ones(N, device=DEV)
+    gamma, beta = synth.affine(N, seed=5)
+    # the panel kernel's row extremes decide the row scale only without an affine step, and only under a row norm
     with pytest.raises(B.LokaError):
-        B.loka_fp8_gemm_norm_fp8out(d, torch.zeros(512, 4096, dtype=torch.uint8, device=DEV),
-                                    torch.ones(512, device=DEV), torch.zeros(4096, 4096, dtype=torch.uint8, device=DEV),
-                                    torch.ones(4096, device=DEV))
+        B.loka_fp8_gemm_norm_fp8out(B.make_desc(M, N, K, 1), xq, sx, wq, sw, gamma.to(DEV), beta.to(DEV))
+    with pytest.raises(B.LokaError):
+        B.loka_fp8_gemm_norm_fp8out(B.make_desc(M, N, K, 1, norm=B.NORM_NONE), xq, sx, wq, sw)
+    with pytest.raises(B.LokaError):
+        B.loka_fp8_gemm_norm_fp8out(B.make_desc(M, N, K, 1, norm=B.NORM_BLOCKNORM, block_n=256), xq, sx, wq, sw)
+    # a tiled variant without the epilogue
+    with pytest.raises(B.LokaError):
+        B.loka_fp8_gemm_norm_fp8out(B.make_desc(M, N, K, 1, variant=B.variant_id("twopass128x128")), xq, sx, wq, sw)
 
 
 # ----------------------------------------------------------------------------- backward-pass GEMMs through the same entry points
@@ -544,7 +635,8 @@ def test_bf16_reference_gemm_grouped(orc):
 
 def test_bounded_wait_is_reported(monkeypatch):
     # the panel-synchronous variants wait for the other tiles of a row panel; a wait that runs out raises a flag
-    # and the kernel still ends.  Forced from the host with a spin limit of zero polls (read at every launch).
+    # and the kernel still ends.  Forced from the host: with a spin limit of zero polls (read at every launch) the
+    # launch also waits for one arrival more than the panel has tiles, so every wait runs out whatever the timing.
     M, K, N = 2048, 256, 2048
     x, wt = synth.normal(M, K, 3).to(DEV), synth.weight(K, N, 4).to(DEV)
     xq, sx = B.loka_quantize(x, B.SCALE_ROW)
@@ -560,6 +652,16 @@ def test_bounded_wait_is_reported(monkeypatch):
     again, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, workspace=ws)
     assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
     assert torch.equal(good, again)
+    # the FP8-output form of the same kernel reports through its own workspace
+    ws_f = torch.empty(B.lib().loka_fp8_gemm_norm_fp8out_workspace(ctypes.byref(desc)), dtype=torch.uint8, device=DEV)
+    monkeypatch.setenv("LOKA_SPIN_LIMIT", "0")
+    B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws_f)
+    assert B.loka_fp8_gemm_norm_check(desc, ws_f) == B.LOKA_ERR_TIMEOUT
+    monkeypatch.delenv("LOKA_SPIN_LIMIT")
+    oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws_f)
+    assert B.loka_fp8_gemm_norm_check(desc, ws_f) == B.LOKA_OK
+    q_ref, s_ref = B.loka_quantize(good, B.SCALE_ROW)
+    assert torch.equal(oq, q_ref) and torch.equal(so, s_ref)
     # variants without a cross-workgroup wait have nothing to report
     row = B.make_desc(256, 128, 128, variant=B.variant_id("row64x128"))
     assert B.loka_fp8_gemm_norm_check(row, None) == B.LOKA_OK
