@@ -174,8 +174,11 @@ def run_pair(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    # Defaults: after an idle period the first launches of a matrix-pipe-bound kernel run at boost clocks, the next
+    # twenty or so well below the sustained rate (C5, per-launch durations in a kernel trace: 482, 485, 523, 555, 613,
+    # 612, ... back to 480-495 us after ~25 launches = 15 ms); 40 warm-up steps put the timed region in the sustained state.
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3a", "C3b", "C3pair", "C4", "C5", "C5pair"])
     ap.add_argument("--budget", type=float, default=5e-2, help="rel-Frobenius budget the timed variant must meet")
     ap.add_argument("--no-cpu-baseline", action="store_true")
