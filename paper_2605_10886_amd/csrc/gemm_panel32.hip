@@ -142,7 +142,15 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     // 2^(ea - 127) * 2^(eb - 127), ea / eb taken from the lane that holds the run.  A lane's X fragment is one
     // row's run (scale of that row and K block), a W fragment's 32 rows lie in one 128-column block (one scale
     // for the wave).  The accumulators then hold the scaled sum itself and the epilogue multiplies by nothing.
+    // X's block scales lie [row][K block]: a lane reading one value per K step touches a cache line of its own each
+    // time (as many L2 requests per step as the operands themselves need).  When a row's scales are 16-byte aligned
+    // (K a multiple of 512) a lane fetches four K blocks at once, every fourth step.
     float s_cur[MI], r_sc[MI], sx_nx[MI], sw_nx = 0.f;
+    v4f sx_q[MI];
+    const bool quad = BLOCKWISE && (ksteps & 3) == 0;
+    auto pick = [](const v4f& v, int j) __attribute__((always_inline)) {
+        return j == 0 ? v[0] : j == 1 ? v[1] : j == 2 ? v[2] : v[3];
+    };
     int sc_x[MI], sc_w = 127;
     const int bw_nb = ((n0 + wave_n * WN < p.N ? n0 + wave_n * WN : p.N - 1) >> 7), bw_nblk = p.N >> 7;
     auto bw_row = [&](int mi) __attribute__((always_inline)) {
@@ -150,20 +158,29 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         return static_cast<int64_t>(m < p.M ? m : p.M - 1) * ksteps;
     };
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) { s_cur[mi] = 1.f; r_sc[mi] = 1.f; sx_nx[mi] = 1.f; sc_x[mi] = 127; }
-    if (BW == 1) {
+    for (int mi = 0; mi < MI; ++mi) {
+        s_cur[mi] = 1.f; r_sc[mi] = 1.f; sx_nx[mi] = 1.f; sc_x[mi] = 127;
+        sx_q[mi] = v4f{1.f, 1.f, 1.f, 1.f};
+    }
+    if (BLOCKWISE) {
         const float sw0 = swg[bw_nb];
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) s_cur[mi] = sxg[bw_row(mi)] * sw0;
-    }
-    if (BW == 2) {
-        sc_w = static_cast<int>(__float_as_uint(swg[bw_nb]) >> 23);
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) sc_x[mi] = static_cast<int>(__float_as_uint(sxg[bw_row(mi)]) >> 23);
+        for (int mi = 0; mi < MI; ++mi) {
+            float sx0;
+            if (quad) { sx_q[mi] = *reinterpret_cast<const v4f*>(sxg + bw_row(mi)); sx0 = sx_q[mi][0]; }
+            else sx0 = sxg[bw_row(mi)];
+            if (BW == 1) s_cur[mi] = sx0 * sw0;
+            else sc_x[mi] = static_cast<int>(__float_as_uint(sx0) >> 23);
+        }
+        if (BW == 2) sc_w = static_cast<int>(__float_as_uint(sw0) >> 23);
     }
     // ratio for the step that begins (its scales were fetched one step earlier), then the fetch for the next one
     auto bw_step = [&](int k) __attribute__((always_inline)) {
         if (!BLOCKWISE) return;
+        if (k >= 1 && quad) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) sx_nx[mi] = pick(sx_q[mi], k & 3);
+        }
         if (k >= 1 && BW == 1) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
@@ -179,8 +196,13 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         }
         if (k + 1 < ksteps) {
             sw_nx = swg[static_cast<int64_t>(k + 1) * bw_nblk + bw_nb];
+            if (!quad) {
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) sx_nx[mi] = sxg[bw_row(mi) + k + 1];
+                for (int mi = 0; mi < MI; ++mi) sx_nx[mi] = sxg[bw_row(mi) + k + 1];
+            } else if (((k + 1) & 3) == 0) {
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) sx_q[mi] = *reinterpret_cast<const v4f*>(sxg + bw_row(mi) + k + 1);
+            }
         }
     };
 
