@@ -474,6 +474,27 @@ def test_fp8_output_of_the_panel_kernel(orc, case):
             assert np.array_equal(oq.cpu().numpy(), q_o) and np.array_equal(so.cpu().numpy(), s_o)
 
 
+def test_fp8_output_of_the_panel_kernel_c5_full_size(orc):
+    # the launch bench.py's C5pair times: 128 row panels x 16 tiles on the persistent grid, 8 rounds per workgroup
+    w = synth.WORKLOADS["C5"]
+    x, wt = synth.activations(w), synth.weights(w)
+    xq, sx = B.loka_quantize(x.to(DEV), B.SCALE_ROW)
+    wq, sw = B.loka_quantize(wt.to(DEV), B.SCALE_COL, transpose_out=True)
+    desc = B.make_desc(w.M, w.N, w.K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORMS[w.norm], w.eps, B.variant_id("panel32_256x256"))
+    out, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+    ws = torch.empty(B.lib().loka_fp8_gemm_norm_fp8out_workspace(desc), dtype=torch.uint8, device=DEV)
+    oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws)
+    torch.cuda.synchronize()
+    assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
+    q_ref, s_ref = B.loka_quantize(out, B.SCALE_ROW)
+    assert torch.equal(so.view(torch.int32), s_ref.view(torch.int32))
+    assert torch.equal(oq, q_ref)
+    rows = _sample_rows(w.M, 64)                      # and the oracle's quantize on sampled rows of that bf16 output
+    idx = torch.as_tensor(rows, device=DEV)
+    q_o, s_o = orc.quantize(to_np_bits(out[idx].contiguous()), B.SCALE_ROW)
+    assert np.array_equal(oq[idx].cpu().numpy(), q_o) and np.array_equal(so[idx].cpu().numpy(), s_o)
+
+
 def test_fp8_output_of_the_panel_kernel_grouped_and_repeated():
     # several problems in one launch; the same workspace serves consecutive launches (counters cleared by the launch)
     G, M, K, N = 3, 530, 256, 768
