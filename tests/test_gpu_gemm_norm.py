@@ -495,6 +495,36 @@ def test_fp8_output_of_the_panel_kernel_c5_full_size(orc):
     assert np.array_equal(oq[idx].cpu().numpy(), q_o) and np.array_equal(so[idx].cpu().numpy(), s_o)
 
 
+@pytest.mark.parametrize("variant,shape", [("wreg32", (200, 256, 512)), ("strip32", (200, 256, 256)),
+                                           ("panel32_256x256", (300, 256, 768))])
+@pytest.mark.parametrize("norm", ["layernorm", "rmsnorm"])
+def test_fp8_output_degenerate_rows(variant, shape, norm):
+    # rows of zeros (amax 0: the scale falls back to the clamp, codes are all zero), a row with one huge element, a row
+    # of one repeated value (LayerNorm output exactly zero), negative-only rows (the row minimum decides the scale)
+    M, K, N = shape
+    x = synth.normal(M, K, seed=77)
+    x[3] = 0
+    x[M - 1] = 0
+    x[10] = 0
+    x[10, 5] = 3.0e4
+    x[20] = 0.5
+    x[30] = -x[30].abs()
+    wt = synth.weight(K, N, seed=78)
+    wt[:, : N // 2] = wt[:, : N // 2].abs()                      # half of the outputs of row 30 certainly negative
+    v = B.variant_id(variant)
+    xq, sx = B.loka_quantize(x.to(DEV), B.SCALE_ROW)
+    wq, sw = B.loka_quantize(wt.to(DEV), B.SCALE_COL, transpose_out=True)
+    desc = B.make_desc(M, N, K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORMS[norm], 1e-5, v)
+    out, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+    oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw)
+    torch.cuda.synchronize()
+    q_ref, s_ref = B.loka_quantize(out, B.SCALE_ROW)
+    assert torch.equal(so.view(torch.int32), s_ref.view(torch.int32))
+    assert torch.equal(oq, q_ref)
+    assert int(oq[3].max()) == 0 and int(oq[M - 1].max()) == 0   # zero rows: zero codes
+    assert float(so[3]) == float(s_ref[3]) > 0.0
+
+
 def test_fp8_output_of_the_panel_kernel_grouped_and_repeated():
     # several problems in one launch; the same workspace serves consecutive launches (counters cleared by the launch)
     G, M, K, N = 3, 530, 256, 768
