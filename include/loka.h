@@ -175,11 +175,10 @@ loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* wor
  *   "wreg32"  (streaming skinny-layer kernel: N <= 1024, K in {128, 256, 512, 1024}, K * N <= 256 KB) and
  *   "strip32" (small-layer strip kernel: N <= 256, K * N <= 256 KB): the whole output row is in one workgroup /
  *             wave; every norm, gamma / beta and activation loka_fp8_gemm_norm takes;
- *   "panel32_256x256" (large layers, rows wider than a tile): LayerNorm or RMSNorm WITHOUT gamma, beta or an
- *             activation only - the normalized value then grows with the pre-norm value, so the row minimum and
- *             maximum, sent along with the row statistics in the one exchange between the row's workgroups, decide
- *             the row scale; with an affine step the extremum can be anywhere and a second exchange would cost what
- *             the separate loka_quantize pass costs: LOKA_ERR_UNSUPPORTED, use the two calls.
+ *   "panel32_256x256" (large layers, rows wider than a tile): LayerNorm or RMSNorm, no activation.  Without
+ *             gamma / beta the normalized value grows with the pre-norm value, so the row minimum and maximum, sent
+ *             along with the row statistics in the one exchange between the row's workgroups, decide the row scale;
+ *             with gamma / beta the row amax of the affine result crosses the workgroups in a second exchange.
  * desc->variant names one, or -1: the library's choice for the shape when it is one of the three, else the
  * streaming kernel.  LOKA_ERR_UNSUPPORTED otherwise.
  * Workspace: loka_fp8_gemm_norm_fp8out_workspace(desc) bytes (non-zero only for the panel kernel with rows wider

@@ -719,7 +719,8 @@ static const char kStripName[] = "strip32";
 static const char kPanel32Name[] = "panel32_256x256";
 
 // gemm_panel32.hip
-const void* panel32_fn(int bw, bool fp8out);
+const void* panel32_fn(int bw, bool fp8out, bool affine);
+bool panel32_affine(const GemmParams& p);
 size_t panel32_lds();
 void panel32_launch(const GemmParams& p, int bw, dim3 grid, hipStream_t s);
 // block scales: power-of-two ones go to the matrix cores, others rescale the accumulators
@@ -756,7 +757,7 @@ static const VariantInfo kVariants[] = {
     // through a few words of global memory and normalize their own tile in registers
     LOKA_VARIANT("panel256x256w8", 256, 256, 1, 2, 4, EPI_PANEL_SYNC),
     // the same schedule on 32x32x64 MFMAs: the throughput variant
-    {kPanel32Name, 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(0, false), panel32_fn(1, false)},
+    {kPanel32Name, 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(0, false, false), panel32_fn(1, false, false)},
 };
 constexpr int kNumCUs = 256;          // MI355X; the launch re-checks against the device it runs on
 constexpr unsigned kSpinLimit = 1u << 18;   // polls of ~1 us each (a device-scope load and a short sleep): far beyond any main loop
@@ -840,7 +841,8 @@ size_t variant_workspace(const loka_gemm_desc* d, int v) {
     if (vi.epi == EPI_PANEL_SYNC) {
         if (!panel_exchanges(d, vi)) return 0;
         // [error flag, 256 B][arrival counters][per-tile row statistics]
-        const int64_t panels = d->batch * ((d->M + vi.bm - 1) / vi.bm);
+        // (the 32x32 kernel has a second arrival counter per panel, for the second exchange of its FP8-output form)
+        const int64_t panels = d->batch * ((d->M + vi.bm - 1) / vi.bm) * (vi.name == kPanel32Name ? 2 : 1);
         return 256 + ((static_cast<size_t>(panels) * 4 + 255) & ~size_t(255)) + stats;
     }
     // fp32 Y staging for the normalization pass (used when the caller does not ask for Y)
@@ -904,10 +906,11 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
     p.outq = outq; p.outs = outs;
     p.xb = static_cast<const uint16_t*>(x_bf16); p.sx_out = sx_out;
     // FP8 output: the row stays inside one workgroup (streaming kernel) or one wave (strip kernel), or - panel kernel -
-    // its extreme values travel with the row statistics, which decides the row scale only when the normalized
-    // value grows with the pre-norm value: LayerNorm / RMSNorm without gamma, beta or an activation
+    // the row amax crosses the workgroups: as the row's extreme pre-norm values along with the row statistics when
+    // there is no gamma / beta (the normalized value then grows with the pre-norm value), else in a second exchange.
+    // LayerNorm / RMSNorm, no activation, non-blockwise scales.
     if (outq && vi.name == kPanel32Name) {
-        if (blockwise || gamma || beta || d->act != LOKA_ACT_NONE) return LOKA_ERR_UNSUPPORTED;
+        if (blockwise || d->act != LOKA_ACT_NONE) return LOKA_ERR_UNSUPPORTED;
         if (d->norm != LOKA_NORM_LAYERNORM && d->norm != LOKA_NORM_RMSNORM) return LOKA_ERR_UNSUPPORTED;
     } else if (outq && vi.name != kWregName && vi.name != kStripName) {
         return LOKA_ERR_UNSUPPORTED;
@@ -947,7 +950,7 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
     }
     const void* kfn = blockwise ? vi.fn_block : vi.fn_plain;
-    if (vi.name == kPanel32Name) kfn = panel32_fn(panel32_bw(p, blockwise), outq != nullptr);
+    if (vi.name == kPanel32Name) kfn = panel32_fn(panel32_bw(p, blockwise), outq != nullptr, panel32_affine(p));
     if (!kfn) return LOKA_ERR_UNSUPPORTED;
     if (set_lds(kfn, vi.lds) != LOKA_OK) return LOKA_ERR_HIP;
     dim3 grid(static_cast<unsigned>(static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.batch));
@@ -962,7 +965,7 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         if (g > grid.x) g = (static_cast<int64_t>(grid.x) / p.tiles_n) * p.tiles_n;   // fewer tiles than slots
         grid = dim3(static_cast<unsigned>(g));
         if (panel_exchanges(d, vi)) {
-            const int64_t panels = static_cast<int64_t>(p.batch) * p.tiles_m;
+            const int64_t panels = static_cast<int64_t>(p.batch) * p.tiles_m * (vi.name == kPanel32Name ? 2 : 1);
             const size_t ctr_bytes = (static_cast<size_t>(panels) * 4 + 255) & ~size_t(255);
             uint8_t* ws = static_cast<uint8_t*>(workspace);
             p.error_flag = reinterpret_cast<unsigned*>(ws);

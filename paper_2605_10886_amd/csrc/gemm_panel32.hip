@@ -34,8 +34,12 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // panel and every workgroup derives the row scale from them.  (With gamma / beta the extremum can sit anywhere:
 // that needs a second exchange after normalization, as long as the separate quantization pass it would save;
 // the host rejects it.)
-template <int EPI, int BW, bool FP8OUT>
+// F8: 0 = bf16 output, 1 = FP8 output without gamma / beta (one exchange), 2 = FP8 output with gamma / beta (the row
+// amax of the affine result crosses the workgroups in a second exchange; an instantiation of its own because it
+// keeps the packed normalized tile in registers).
+template <int EPI, int BW, int F8>
 __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
+    constexpr bool FP8OUT = F8 != 0;
     constexpr bool BLOCKWISE = BW != 0;
     constexpr int BM = 256, BN = 256, NW = 8, WM = 128, WN = 64, MI = 4, NI = 2;
     constexpr int ES = 256 * 128;           // one ring entry: 256 rows x 128 bytes of X or of W
@@ -400,6 +404,9 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
 
     float mean_r[MI], rstd_r[MI];
     const bool ln = p.norm == LOKA_NORM_LAYERNORM;
+    // FP8 output with gamma / beta: the row amax is only known after the affine step, and crosses the workgroups in
+    // a second exchange (below); the row extremes of the pre-norm values are then of no use
+    constexpr bool affine_q = F8 == 2;
     float iq_r[MI];
     if (p.norm == LOKA_NORM_NONE) {
 #pragma unroll
@@ -447,7 +454,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 float* r3 = red + ((wave_m * WM + mi * 32 + l32) * 4 + wave_n) * 3;
                 r3[0] = n_; r3[1] = mean; r3[2] = m2;
             }
-            if (FP8OUT) {
+            if (FP8OUT && !affine_q) {
                 float lo = __builtin_inff(), hi = -__builtin_inff();
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
@@ -476,7 +483,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 const float* r3 = red + (tid * 4 + w) * 3;
                 if (ln) merge_stats(n_, t_mean, t_m2, r3[0], r3[1], r3[2]);
                 else t_m2 += r3[2];
-                if (FP8OUT) {
+                if (FP8OUT && !affine_q) {
                     t_lo = __builtin_fminf(t_lo, red2[(tid * 4 + w) * 2]);
                     t_hi = __builtin_fmaxf(t_hi, red2[(tid * 4 + w) * 2 + 1]);
                 }
@@ -510,7 +517,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 __hip_atomic_store(dst, static_cast<unsigned long long>(__float_as_uint(t_mean)) |
                                             (static_cast<unsigned long long>(__float_as_uint(t_m2)) << 32),
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (FP8OUT)
+                if (FP8OUT && !affine_q)
                     __hip_atomic_store(dst + mm_off, static_cast<unsigned long long>(__float_as_uint(t_lo)) |
                                                          (static_cast<unsigned long long>(__float_as_uint(t_hi)) << 32),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -546,7 +553,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                         int tt = t0 + u;
                         tt = tt < p.tiles_n ? tt : p.tiles_n - 1;
                         raw[u] = __hip_atomic_load(src + tt * BM, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        if (FP8OUT) raw2[u] = __hip_atomic_load(src + mm_off + tt * BM, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (FP8OUT && !affine_q) raw2[u] = __hip_atomic_load(src + mm_off + tt * BM, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
@@ -557,7 +564,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                             const int wcols = (tt + 1) * BN <= p.N ? BN : p.N - tt * BN;
                             if (ln) merge_stats(n_, mean, m2, static_cast<float>(wcols), a, b2);
                             else m2 += b2;
-                            if (FP8OUT) {
+                            if (FP8OUT && !affine_q) {
                                 lo = __builtin_fminf(lo, __uint_as_float(static_cast<unsigned>(raw2[u])));
                                 hi = __builtin_fmaxf(hi, __uint_as_float(static_cast<unsigned>(raw2[u] >> 32)));
                             }
@@ -577,14 +584,14 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 } else {
                     m2 = m2 + m2b;
                 }
-                if (FP8OUT) {
+                if (FP8OUT && !affine_q) {
                     lo = __builtin_fminf(lo, wave_shfl_xor(lo, 1));
                     hi = __builtin_fmaxf(hi, wave_shfl_xor(hi, 1));
                 }
                 if (sub == 0) {
                     const float2 f = make_float2(ln ? mean : 0.f, __builtin_amdgcn_rsqf(m2 * inv_n + p.eps));
                     fin[r] = f;
-                    if (FP8OUT) row_scale(r, f.x, f.y, lo, hi);
+                    if (FP8OUT && !affine_q) row_scale(r, f.x, f.y, lo, hi);
                 }
             }
         } else {
@@ -592,7 +599,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             if (tid < BM) {
                 const float2 f = make_float2(ln ? t_mean : 0.f, __builtin_amdgcn_rsqf(t_m2 * (blocknorm ? 1.0f / BN : inv_n) + p.eps));
                 fin[tid] = f;
-                if (FP8OUT) row_scale(static_cast<int>(tid), f.x, f.y, t_lo, t_hi);
+                if (FP8OUT && !affine_q) row_scale(static_cast<int>(tid), f.x, f.y, t_lo, t_hi);
             }
         }
         __syncthreads();
@@ -601,7 +608,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             const float2 f = fin[wave_m * WM + mi * 32 + l32];
             mean_r[mi] = f.x;
             rstd_r[mi] = f.y;
-            if (FP8OUT) iq_r[mi] = finq[wave_m * WM + mi * 32 + l32];
+            if (FP8OUT && !affine_q) iq_r[mi] = finq[wave_m * WM + mi * 32 + l32];
         }
     }
     float nmr_r[MI];
@@ -620,9 +627,130 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     const int t_wr = l32 * 64, t_key = (l32 >> 2) & 3;
     const int t_row = lane >> 2, t_c = lane & 3;                       // store side: row (+ 16 j), chunk
     if (FP8OUT) {
+        (void)hswish;
+        // With gamma / beta: the normalized bf16 values replace the accumulators (64 packed registers), their row
+        // amax crosses the waves through LDS and the workgroups through a second exchange (records in the area the
+        // row extremes use otherwise, a second arrival counter per panel), and the cast follows.
+        unsigned opk[MI][NI][4][2];
+        if (affine_q) {
+            unsigned am[MI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) am[mi] = 0u;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                float gm[16], bt[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) { gm[e] = 1.f; bt[e] = 0.f; }
+                if (ncol[ni] < p.N) {
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        if (has_g) {
+                            const u32x4 w = *reinterpret_cast<const u32x4*>(p.gamma + ncol[ni] + 8 * half);
+                            float* q = gm + 8 * half;
+                            q[0] = bf16_lo(w.x); q[1] = bf16_hi(w.x); q[2] = bf16_lo(w.y); q[3] = bf16_hi(w.y);
+                            q[4] = bf16_lo(w.z); q[5] = bf16_hi(w.z); q[6] = bf16_lo(w.w); q[7] = bf16_hi(w.w);
+                        }
+                        if (has_b) {
+                            const u32x4 w = *reinterpret_cast<const u32x4*>(p.beta + ncol[ni] + 8 * half);
+                            float* q = bt + 8 * half;
+                            q[0] = bf16_lo(w.x); q[1] = bf16_hi(w.x); q[2] = bf16_lo(w.y); q[3] = bf16_hi(w.y);
+                            q[4] = bf16_lo(w.z); q[5] = bf16_hi(w.z); q[6] = bf16_lo(w.w); q[7] = bf16_hi(w.w);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float o[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            o[e] = __builtin_fmaf(__builtin_fmaf(acc[mi][ni][4 * q + e], rstd_r[mi], nmr_r[mi]), gm[4 * q + e], bt[4 * q + e]);
+                        const unsigned p0 = pack_bf16x2(o[0], o[1]), p1 = pack_bf16x2(o[2], o[3]);
+                        opk[mi][ni][q][0] = p0; opk[mi][ni][q][1] = p1;
+                        if (ncol[ni] < p.N) {
+                            const unsigned a0 = p0 & 0x7FFFu, a1 = (p0 >> 16) & 0x7FFFu, a2 = p1 & 0x7FFFu, a3 = (p1 >> 16) & 0x7FFFu;
+                            const unsigned a01 = a0 > a1 ? a0 : a1, a23 = a2 > a3 ? a2 : a3;
+                            const unsigned a = a01 > a23 ? a01 : a23;
+                            am[mi] = am[mi] > a ? am[mi] : a;
+                        }
+                    }
+            }
+            unsigned* amw = reinterpret_cast<unsigned*>(smem + 16384);        // [BM][4]: row amax per column wave
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const unsigned other = static_cast<unsigned>(__shfl_xor(static_cast<int>(am[mi]), 32, 64));
+                am[mi] = am[mi] > other ? am[mi] : other;
+                if (hk == 0) amw[(wave_m * WM + mi * 32 + l32) * 4 + wave_n] = am[mi];
+            }
+            __syncthreads();
+            unsigned t_am = 0u;
+            if (tid < BM) {
+#pragma unroll
+                for (int w = 0; w < 4; ++w) { const unsigned a = amw[tid * 4 + w]; t_am = t_am > a ? t_am : a; }
+            }
+            auto row_scale_am = [&](int r, unsigned a) __attribute__((always_inline)) {
+                float scale, inv;
+                group_scale(__uint_as_float(a << 16), scale, inv);
+                finq[r] = inv;
+                if (tn == 0 && m0 + r < p.M) p.outs[static_cast<int64_t>(g) * p.M + m0 + r] = scale;
+            };
+            if (p.tiles_n > 1) {
+                const int panel = g * p.tiles_m + tm;
+                const int64_t mm_off = static_cast<int64_t>(p.batch) * p.tiles_m * p.tiles_n * BM;
+                unsigned long long* pam = reinterpret_cast<unsigned long long*>(p.part) + mm_off +
+                                          static_cast<int64_t>(panel) * p.tiles_n * BM;
+                if (tid < BM) {
+                    __hip_atomic_store(pam + tn * BM + tid, static_cast<unsigned long long>(t_am), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                }
+                __syncthreads();
+                if (tid == 0) {
+                    unsigned* ctr = p.counters + static_cast<int64_t>(p.batch) * p.tiles_m + panel;   // the second counter of the panel
+                    __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    unsigned spins = 0;
+                    while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.arrivals) {
+                        __builtin_amdgcn_s_sleep(2);
+                        if (++spins > p.spin_limit) {
+                            __hip_atomic_store(p.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                    }
+                }
+                __syncthreads();
+                {
+                    const int r = static_cast<int>(tid) >> 1, sub = static_cast<int>(tid) & 1;
+                    const int TH = (p.tiles_n + 1) >> 1;
+                    unsigned a = 0u;
+                    for (int t0 = sub * TH; t0 < (sub + 1) * TH && t0 < p.tiles_n; t0 += 8) {
+                        unsigned long long raw[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            int tt = t0 + u;
+                            tt = tt < p.tiles_n ? tt : p.tiles_n - 1;
+                            raw[u] = __hip_atomic_load(pam + tt * BM + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const unsigned v = static_cast<unsigned>(raw[u]);      // (a clamped index repeats a tile: harmless for a maximum)
+                            a = a > v ? a : v;
+                        }
+                    }
+                    const unsigned other = static_cast<unsigned>(__shfl_xor(static_cast<int>(a), 1, 64));
+                    a = a > other ? a : other;
+                    if (sub == 0) row_scale_am(r, a);
+                }
+            } else if (tid < BM) {
+                row_scale_am(static_cast<int>(tid), t_am);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) iq_r[mi] = finq[wave_m * WM + mi * 32 + l32];
+            __syncthreads();                  // amw (aliasing the transpose buffers) and finq are read
+        }
         // 16 codes per lane and sub-tile; the wave's 64 columns of 32 rows pass through the transpose buffer at once
         // (64-byte rows of codes) and leave as full 64-byte runs, 4 lanes per row
-        (void)has_g; (void)has_b; (void)hswish;
         const int col = n0 + wave_n * WN + t_c * 16;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
@@ -631,10 +759,15 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 unsigned ck[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    float o[4];
+                    unsigned p0, p1;
+                    if (affine_q) {
+                        p0 = opk[mi][ni][q][0]; p1 = opk[mi][ni][q][1];
+                    } else {
+                        float o[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(acc[mi][ni][4 * q + e], rstd_r[mi], nmr_r[mi]);
-                    const unsigned p0 = pack_bf16x2(o[0], o[1]), p1 = pack_bf16x2(o[2], o[3]);
+                        for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(acc[mi][ni][4 * q + e], rstd_r[mi], nmr_r[mi]);
+                        p0 = pack_bf16x2(o[0], o[1]); p1 = pack_bf16x2(o[2], o[3]);
+                    }
                     ck[q] = e4m3x4(bf16_lo(p0) * iq_r[mi], bf16_hi(p0) * iq_r[mi], bf16_lo(p1) * iq_r[mi], bf16_hi(p1) * iq_r[mi]);
                 }
                 *reinterpret_cast<u32x4*>(tbuf + t_wr + (((2 * ni + hk) ^ t_key) << 4)) = u32x4{ck[0], ck[1], ck[2], ck[3]};
@@ -715,19 +848,27 @@ extern "C" int loka_debug_read_times32(unsigned long long* host, int n) {
 
 constexpr size_t kPanel32Lds = 5 * 256 * 128;   // the ring; the epilogue's scratch aliases it
 
+// gamma / beta take part in this launch (the kernel ignores gamma outside LayerNorm / RMSNorm and beta outside LayerNorm)
+bool panel32_affine(const GemmParams& p) {
+    const bool ln = p.norm == LOKA_NORM_LAYERNORM;
+    return (p.gamma != nullptr && (ln || p.norm == LOKA_NORM_RMSNORM)) || (p.beta != nullptr && ln);
+}
 // bw: 0 plain scales, 1 block scales, 2 power-of-two block scales (see the kernel); fp8out with bw == 0 only
-const void* panel32_fn(int bw, bool fp8out) {
-    if (fp8out) return bw == 0 ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0, true>) : nullptr;
-    return bw == 2   ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 2, false>)
-           : bw == 1 ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 1, false>)
-                     : reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0, false>);
+const void* panel32_fn(int bw, bool fp8out, bool affine) {
+    if (fp8out) return bw != 0 ? nullptr
+                       : affine ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 2>)
+                                : reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 1>);
+    return bw == 2   ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 2, 0>)
+           : bw == 1 ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 1, 0>)
+                     : reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 0>);
 }
 size_t panel32_lds() { return kPanel32Lds; }
 void panel32_launch(const GemmParams& p, int bw, dim3 grid, hipStream_t s) {
-    if (p.outq) gemm_panel32_kernel<EPI_PANEL_SYNC, 0, true><<<grid, 512, kPanel32Lds, s>>>(p);
-    else if (bw == 2) gemm_panel32_kernel<EPI_PANEL_SYNC, 2, false><<<grid, 512, kPanel32Lds, s>>>(p);
-    else if (bw == 1) gemm_panel32_kernel<EPI_PANEL_SYNC, 1, false><<<grid, 512, kPanel32Lds, s>>>(p);
-    else gemm_panel32_kernel<EPI_PANEL_SYNC, 0, false><<<grid, 512, kPanel32Lds, s>>>(p);
+    if (p.outq && panel32_affine(p)) gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 2><<<grid, 512, kPanel32Lds, s>>>(p);
+    else if (p.outq) gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 1><<<grid, 512, kPanel32Lds, s>>>(p);
+    else if (bw == 2) gemm_panel32_kernel<EPI_PANEL_SYNC, 2, 0><<<grid, 512, kPanel32Lds, s>>>(p);
+    else if (bw == 1) gemm_panel32_kernel<EPI_PANEL_SYNC, 1, 0><<<grid, 512, kPanel32Lds, s>>>(p);
+    else gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 0><<<grid, 512, kPanel32Lds, s>>>(p);
 }
 
 }  // namespace loka

@@ -446,23 +446,27 @@ PANEL_FP8_CASES = [
 ]
 
 
+@pytest.mark.parametrize("affine", [False, True])
 @pytest.mark.parametrize("case", PANEL_FP8_CASES)
-def test_fp8_output_of_the_panel_kernel(orc, case):
+def test_fp8_output_of_the_panel_kernel(orc, case, affine):
     # codes and row scales bit for bit what loka_quantize(O_bf16, ROW) writes from the same kernel's bf16 output
-    # (itself checked against the oracle above), and what the oracle's quantize makes of that tensor
+    # (itself checked against the oracle above), and what the oracle's quantize makes of that tensor.  Without gamma /
+    # beta the row extremes travel with the statistics (one exchange); with them the row amax of the affine result
+    # crosses the workgroups in a second exchange.
     M, K, N, norm = case
     x = synth.student_t4(M, K, seed=11 * M)
     wt = synth.weight(K, N, seed=11 * N)
+    gamma, beta = (t.to(DEV) for t in synth.affine(N, seed=6)) if affine else (None, None)
     v = B.variant_id("panel32_256x256")
     for xm, wm in ((B.SCALE_ROW, B.SCALE_COL), (B.SCALE_TENSOR, B.SCALE_TENSOR)):
         xq, sx = B.loka_quantize(x.to(DEV), xm)
         wq, sw = B.loka_quantize(wt.to(DEV), wm, transpose_out=True)
         desc = B.make_desc(M, N, K, 1, xm, wm, B.NORMS[norm], 1e-5, v)
-        out, y = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, want_y=True)
+        out, y = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, gamma, beta, want_y=True)
         need = B.lib().loka_fp8_gemm_norm_fp8out_workspace(desc)
         assert (need > 0) == (N > 256)
         ws = torch.empty(max(need, 16), dtype=torch.uint8, device=DEV)
-        oq, so, y2 = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, want_y=True, workspace=ws)
+        oq, so, y2 = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, gamma, beta, want_y=True, workspace=ws)
         torch.cuda.synchronize()
         assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
         assert torch.equal(y, y2)
@@ -540,9 +544,11 @@ def test_fp8_output_of_the_panel_kernel_grouped_and_repeated():
     for rep in range(3):
         x = torch.cat([synth.normal(M, K, 970 + 10 * rep + g) for g in range(G)], 0).to(DEV)
         xq, sx = B.loka_quantize(x, B.SCALE_ROW)
-        out, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
-        oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws)
+        gamma, beta = (t.to(DEV) for t in synth.affine(N, seed=rep)) if rep % 2 else (None, None)   # both forms, same workspace
+        out, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, gamma, beta)
+        oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, gamma, beta, workspace=ws)
         torch.cuda.synchronize()
+        assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
         q_ref, s_ref = B.loka_quantize(out, B.SCALE_ROW)
         assert torch.equal(oq, q_ref) and torch.equal(so.view(torch.int32), s_ref.view(torch.int32)), rep
 
@@ -572,10 +578,7 @@ def test_fp8_output_unsupported_cases():
     M, K, N = 512, 4096, 4096                                                 # rows wider than a workgroup keeps
     xq, sx = torch.zeros(M, K, dtype=torch.uint8, device=DEV), torch.ones(M, device=DEV)
     wq, sw = torch.zeros(N, K, dtype=torch.uint8, device=DEV), torch.ones(N, device=DEV)
-    gamma, beta = synth.affine(N, seed=5)
-    # the panel kernel's row extremes decide the row scale only without an affine step, and only under a row norm
-    with pytest.raises(B.LokaError):
-        B.loka_fp8_gemm_norm_fp8out(B.make_desc(M, N, K, 1), xq, sx, wq, sw, gamma.to(DEV), beta.to(DEV))
+    # the panel kernel's FP8 output needs a row norm (LayerNorm / RMSNorm)
     with pytest.raises(B.LokaError):
         B.loka_fp8_gemm_norm_fp8out(B.make_desc(M, N, K, 1, norm=B.NORM_NONE), xq, sx, wq, sw)
     with pytest.raises(B.LokaError):
@@ -707,6 +710,9 @@ def test_bounded_wait_is_reported(monkeypatch):
     ws_f = torch.empty(B.lib().loka_fp8_gemm_norm_fp8out_workspace(ctypes.byref(desc)), dtype=torch.uint8, device=DEV)
     monkeypatch.setenv("LOKA_SPIN_LIMIT", "0")
     B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws_f)
+    assert B.loka_fp8_gemm_norm_check(desc, ws_f) == B.LOKA_ERR_TIMEOUT
+    gamma, beta = (t.to(DEV) for t in synth.affine(N, seed=8))
+    B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, gamma, beta, workspace=ws_f)      # two bounded waits per tile
     assert B.loka_fp8_gemm_norm_check(desc, ws_f) == B.LOKA_ERR_TIMEOUT
     monkeypatch.delenv("LOKA_SPIN_LIMIT")
     oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws_f)
