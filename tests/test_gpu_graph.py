@@ -1,6 +1,6 @@
 """The hot entry points under HIP graph capture.
 
-`loka_quantize` (row / 1x128 modes) and `loka_fp8_gemm_norm` only launch kernels on the caller's stream (scratch comes
+`loka_quantize` (row / 1x128 modes), `loka_fp8_gemm_norm` and `loka_fp8_gemm_norm_fp8out` only launch kernels on the caller's stream (scratch comes
 in as a workspace argument and is cleared by a kernel, never by a memset node), so a serving loop can record a step
 once and replay it.  Each case records quantize + GEMM+norm, replays the graph several times with new activations
 written into the same input buffer and eager work on the device between the replays, and compares every replay
@@ -24,6 +24,8 @@ CASES = [
     (16384, 256, 256, 4, B.NORM_RMSNORM, "strip kernel, grouped"),
     (16384, 256, 1024, 1, B.NORM_LAYERNORM, "streaming kernel, deferred stores"),
     (4096, 256, 4096, 1, B.NORM_LAYERNORM, "panel-synchronous kernel: counters cleared by a kernel inside the launch"),
+    (2048, 512, 2048, 1, B.NORM_LAYERNORM, "panel-synchronous kernel, FP8 output with gamma / beta: two exchanges per tile"),
+    (8192, 256, 1024, 1, B.NORM_RMSNORM, "streaming kernel, FP8 output"),
 ]
 
 
@@ -38,22 +40,33 @@ def test_step_replays_from_a_graph(M, K, N, G, norm, what):
         q, s = B.loka_quantize(synth.weight(K, N, seed=400 + g).to(DEV), B.SCALE_COL, transpose_out=True)
         wq[g * N:(g + 1) * N] = q
         sw[g * N:(g + 1) * N] = s
-    desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, norm, 1e-5, -1)
+    # the library's choice for the shape, except where the case names a kernel that is not that choice
+    variant = B.variant_id("panel32_256x256") if what.startswith("panel-synchronous kernel, FP8") else -1
+    desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, norm, 1e-5, variant)
 
     x_in = torch.empty(rows, K, dtype=torch.bfloat16, device=DEV)
     xq = torch.empty(rows, K, dtype=torch.uint8, device=DEV)
     sx = torch.empty(rows, dtype=torch.float32, device=DEV)
-    out = torch.empty(rows, N, dtype=torch.bfloat16, device=DEV)
+    fp8 = "FP8 output" in what
+    gamma, beta = (t.to(DEV) for t in synth.affine(N, seed=9)) if "gamma" in what else (None, None)
+    gp, bp = (gamma.data_ptr(), beta.data_ptr()) if gamma is not None else (None, None)
+    out = torch.empty(rows, N, dtype=torch.uint8 if fp8 else torch.bfloat16, device=DEV)
+    so = torch.empty(rows, dtype=torch.float32, device=DEV)
+    query = L.loka_fp8_gemm_norm_fp8out_workspace if fp8 else L.loka_fp8_gemm_norm_workspace
     ws_q = torch.empty(max(16, L.loka_quantize_workspace(B.SCALE_ROW, rows, K, 0)), dtype=torch.uint8, device=DEV)
-    ws_g = torch.empty(max(16, L.loka_fp8_gemm_norm_workspace(ctypes.byref(desc))), dtype=torch.uint8, device=DEV)
+    ws_g = torch.empty(max(16, query(ctypes.byref(desc))), dtype=torch.uint8, device=DEV)
 
     def step(stream):
         sp = ctypes.c_void_p(stream.cuda_stream)
         r = L.loka_quantize(x_in.data_ptr(), rows, K, K, B.SCALE_ROW, 0, xq.data_ptr(), sx.data_ptr(), ws_q.data_ptr(),
                             ws_q.numel(), sp)
         assert r == 0, r
-        r = L.loka_fp8_gemm_norm(ctypes.byref(desc), xq.data_ptr(), sx.data_ptr(), wq.data_ptr(), sw.data_ptr(), None,
-                                 None, out.data_ptr(), None, ws_g.data_ptr(), ws_g.numel(), sp)
+        if fp8:
+            r = L.loka_fp8_gemm_norm_fp8out(ctypes.byref(desc), xq.data_ptr(), sx.data_ptr(), wq.data_ptr(), sw.data_ptr(), gp,
+                                            bp, out.data_ptr(), so.data_ptr(), None, ws_g.data_ptr(), ws_g.numel(), sp)
+        else:
+            r = L.loka_fp8_gemm_norm(ctypes.byref(desc), xq.data_ptr(), sx.data_ptr(), wq.data_ptr(), sw.data_ptr(), gp,
+                                     bp, out.data_ptr(), None, ws_g.data_ptr(), ws_g.numel(), sp)
         assert r == 0, r
 
     # eager results for every input (also the warm-up that loads the code objects before the capture)
@@ -63,7 +76,7 @@ def test_step_replays_from_a_graph(M, K, N, G, norm, what):
         x_in.copy_(x)
         step(cur)
         torch.cuda.synchronize()
-        want.append((xq.clone(), sx.clone(), out.clone()))
+        want.append((xq.clone(), sx.clone(), out.clone(), so.clone()))
 
     side = torch.cuda.Stream()
     side.wait_stream(cur)
@@ -77,6 +90,7 @@ def test_step_replays_from_a_graph(M, K, N, G, norm, what):
         i = rep % len(xs)
         x_in.copy_(xs[i])
         out.fill_(0)                    # eager work between the replays; stale results would show
+        so.fill_(0)
         xq.fill_(0)
         junk.normal_()
         torch.cuda.synchronize()
@@ -84,6 +98,8 @@ def test_step_replays_from_a_graph(M, K, N, G, norm, what):
         torch.cuda.synchronize()
         assert torch.equal(xq, want[i][0]), f"{what}: codes, replay {rep}"
         assert torch.equal(sx, want[i][1]), f"{what}: scales, replay {rep}"
-        assert torch.equal(out.view(torch.int16), want[i][2].view(torch.int16)), f"{what}: O, replay {rep}"
+        assert torch.equal(out.view(torch.uint8), want[i][2].view(torch.uint8)), f"{what}: O, replay {rep}"
+        if fp8:
+            assert torch.equal(so, want[i][3]), f"{what}: output row scales, replay {rep}"
         if "panel" in what:
             assert B.loka_fp8_gemm_norm_check(desc, ws_g) == B.LOKA_OK
