@@ -180,7 +180,7 @@ loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* wor
  *             along with the row statistics in the one exchange between the row's workgroups, decide the row scale;
  *             with gamma / beta the row amax of the affine result crosses the workgroups in a second exchange.
  * desc->variant names one, or -1: the library's choice for the shape when it is one of the three, else the
- * streaming kernel.  LOKA_ERR_UNSUPPORTED otherwise.
+ * streaming kernel where it covers the shape, else the panel kernel.  LOKA_ERR_UNSUPPORTED otherwise.
  * Workspace: loka_fp8_gemm_norm_fp8out_workspace(desc) bytes (non-zero only for the panel kernel with rows wider
  * than 256 columns; NULL / 0 otherwise), device memory, 16-byte aligned, not shared with a call still running;
  * loka_fp8_gemm_norm_check reports the panel kernel's bounded wait on it as for loka_fp8_gemm_norm.

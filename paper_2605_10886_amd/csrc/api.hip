@@ -216,13 +216,19 @@ loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* wor
 // The kernels with an FP8-output epilogue: the two that keep a whole output row inside one workgroup (streaming) or
 // one wave (strip), and the large-layer panel kernel (which sends the row extremes along with the row statistics).
 // The one the caller names, else the library's choice for the shape when it is one of the three, else the
-// streaming one.  -1 when the named variant has no such epilogue or cannot run the shape.
+// streaming one where it can run the shape, else the panel kernel.  -1 when the named variant has no such epilogue
+// or cannot run the shape.
 static int fp8out_variant(const loka_gemm_desc* desc) {
-    auto has_epilogue = [](int v) { return variant_is_streaming(v) || variant_is_strip(v) || variant_is_panel32(v); };
-    int v = desc->variant >= 0 ? desc->variant : default_variant(desc);
-    if (desc->variant < 0 && !(v >= 0 && has_epilogue(v) && variant_supports(desc, v))) v = variant_streaming_id();
-    if (v < 0 || !has_epilogue(v) || !variant_supports(desc, v)) return -1;
-    return v;
+    auto usable = [&](int v) {
+        return v >= 0 && (variant_is_streaming(v) || variant_is_strip(v) || variant_is_panel32(v)) && variant_supports(desc, v);
+    };
+    if (desc->variant >= 0) return usable(desc->variant) ? desc->variant : -1;
+    const int v = default_variant(desc);
+    if (usable(v)) return v;
+    if (usable(variant_streaming_id())) return variant_streaming_id();
+    for (int u = 0; u < variant_count(); ++u)             // the panel kernel takes every shape the two others do not
+        if (variant_is_panel32(u) && usable(u)) return u;
+    return -1;
 }
 
 size_t loka_fp8_gemm_norm_fp8out_workspace(const loka_gemm_desc* desc) {
