@@ -31,9 +31,8 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // quantization of the bf16 output would give.  Without an affine step the normalized value (y - mean) * rstd grows
 // with y, and so does its bf16 rounding: the row's largest magnitude is reached at the row's largest or smallest
 // y, so the row minimum and maximum travel with the row statistics in the ONE exchange between the workgroups of a
-// panel and every workgroup derives the row scale from them.  (With gamma / beta the extremum can sit anywhere:
-// that needs a second exchange after normalization, as long as the separate quantization pass it would save;
-// the host rejects it.)
+// panel and every workgroup derives the row scale from them.  With gamma / beta the extremum can sit anywhere: the
+// tile is normalized first and the row amax of the result crosses the workgroups in a second exchange.
 // F8: 0 = bf16 output, 1 = FP8 output without gamma / beta (one exchange), 2 = FP8 output with gamma / beta (the row
 // amax of the affine result crosses the workgroups in a second exchange; an instantiation of its own because it
 // keeps the packed normalized tile in registers).
