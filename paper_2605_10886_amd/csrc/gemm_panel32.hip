@@ -622,6 +622,27 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     // LDS executes one wave's instructions in order, so the same buffer serves every sub-tile without a barrier.
     const bool has_g = p.gamma != nullptr && (ln || p.norm == LOKA_NORM_RMSNORM), has_b = p.beta != nullptr && ln;
     const bool hswish = p.act == LOKA_ACT_HARDSWISH;
+    // gamma and beta of this lane's 16 columns of sub-tile ni (1 and 0 where absent or past N)
+    auto load_affine = [&](int ni, float (&gm)[16], float (&bt)[16]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { gm[e] = 1.f; bt[e] = 0.f; }
+        if (ncol[ni] >= p.N) return;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            if (has_g) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(p.gamma + ncol[ni] + 8 * half);
+                float* q = gm + 8 * half;
+                q[0] = bf16_lo(w.x); q[1] = bf16_hi(w.x); q[2] = bf16_lo(w.y); q[3] = bf16_hi(w.y);
+                q[4] = bf16_lo(w.z); q[5] = bf16_hi(w.z); q[6] = bf16_lo(w.w); q[7] = bf16_hi(w.w);
+            }
+            if (has_b) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(p.beta + ncol[ni] + 8 * half);
+                float* q = bt + 8 * half;
+                q[0] = bf16_lo(w.x); q[1] = bf16_hi(w.x); q[2] = bf16_lo(w.y); q[3] = bf16_hi(w.y);
+                q[4] = bf16_lo(w.z); q[5] = bf16_hi(w.z); q[6] = bf16_lo(w.w); q[7] = bf16_hi(w.w);
+            }
+        }
+    };
     uint8_t* const tbuf = smem + 16384 + wave * 2048;
     const int t_wr = l32 * 64, t_key = (l32 >> 2) & 3;
     const int t_row = lane >> 2, t_c = lane & 3;                       // store side: row (+ 16 j), chunk
@@ -638,25 +659,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
                 float gm[16], bt[16];
-#pragma unroll
-                for (int e = 0; e < 16; ++e) { gm[e] = 1.f; bt[e] = 0.f; }
-                if (ncol[ni] < p.N) {
-#pragma unroll
-                    for (int half = 0; half < 2; ++half) {
-                        if (has_g) {
-                            const u32x4 w = *reinterpret_cast<const u32x4*>(p.gamma + ncol[ni] + 8 * half);
-                            float* q = gm + 8 * half;
-                            q[0] = bf16_lo(w.x); q[1] = bf16_hi(w.x); q[2] = bf16_lo(w.y); q[3] = bf16_hi(w.y);
-                            q[4] = bf16_lo(w.z); q[5] = bf16_hi(w.z); q[6] = bf16_lo(w.w); q[7] = bf16_hi(w.w);
-                        }
-                        if (has_b) {
-                            const u32x4 w = *reinterpret_cast<const u32x4*>(p.beta + ncol[ni] + 8 * half);
-                            float* q = bt + 8 * half;
-                            q[0] = bf16_lo(w.x); q[1] = bf16_hi(w.x); q[2] = bf16_lo(w.y); q[3] = bf16_hi(w.y);
-                            q[4] = bf16_lo(w.z); q[5] = bf16_hi(w.z); q[6] = bf16_lo(w.w); q[7] = bf16_hi(w.w);
-                        }
-                    }
-                }
+                load_affine(ni, gm, bt);
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -784,25 +787,7 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
         float gm[16], bt[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { gm[e] = 1.f; bt[e] = 0.f; }
-        if (ncol[ni] < p.N) {
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                if (has_g) {
-                    const u32x4 w = *reinterpret_cast<const u32x4*>(p.gamma + ncol[ni] + 8 * half);
-                    float* q = gm + 8 * half;
-                    q[0] = bf16_lo(w.x); q[1] = bf16_hi(w.x); q[2] = bf16_lo(w.y); q[3] = bf16_hi(w.y);
-                    q[4] = bf16_lo(w.z); q[5] = bf16_hi(w.z); q[6] = bf16_lo(w.w); q[7] = bf16_hi(w.w);
-                }
-                if (has_b) {
-                    const u32x4 w = *reinterpret_cast<const u32x4*>(p.beta + ncol[ni] + 8 * half);
-                    float* q = bt + 8 * half;
-                    q[0] = bf16_lo(w.x); q[1] = bf16_hi(w.x); q[2] = bf16_lo(w.y); q[3] = bf16_hi(w.y);
-                    q[4] = bf16_lo(w.z); q[5] = bf16_hi(w.z); q[6] = bf16_lo(w.w); q[7] = bf16_hi(w.w);
-                }
-            }
-        }
+        load_affine(ni, gm, bt);
         const int col = n0 + wave_n * WN + ni * 32 + t_c * 8;         // store side: this lane's 8 columns
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
