@@ -110,6 +110,29 @@ def test_gemm_argument_validation():
     assert _gemm(grouped) == B.LOKA_ERR_SHAPE
 
 
+def test_fp8_output_argument_validation():
+    L = B.lib()
+
+    def f8(desc, xq=FAKE, oq=FAKE, so=FAKE, ws=None, nws=0):
+        return L.loka_fp8_gemm_norm_fp8out(ctypes.byref(desc), xq, FAKE, FAKE, FAKE, None, None, oq, so, None, ws, nws, None)
+
+    panel = B.make_desc(1000, 2048, 512, variant=B.variant_id("panel32_256x256"))
+    assert f8(panel, xq=None) == B.LOKA_ERR_NULL
+    assert f8(panel, so=None) == B.LOKA_ERR_NULL
+    assert f8(panel, oq=ODD) == B.LOKA_ERR_ALIGN
+    # records of every row of every 256-row panel, statistics and extremes, two arrival counters per panel, the flag
+    need = L.loka_fp8_gemm_norm_fp8out_workspace(ctypes.byref(panel))
+    assert need >= 4 * 256 * 8 * 8 * 2 + 2 * 4 * 4 + 256
+    assert f8(panel) == B.LOKA_ERR_WORKSPACE
+    assert f8(panel, ws=FAKE, nws=need - 1) == B.LOKA_ERR_WORKSPACE
+    assert f8(panel, ws=ODD, nws=need) == B.LOKA_ERR_ALIGN
+    # kernels that keep the row together need none; a tiled variant has no such epilogue
+    assert L.loka_fp8_gemm_norm_fp8out_workspace(ctypes.byref(B.make_desc(1000, 256, 256, variant=B.variant_id("strip32")))) == 0
+    assert L.loka_fp8_gemm_norm_fp8out_workspace(ctypes.byref(B.make_desc(1000, 512, 256, variant=B.variant_id("wreg32")))) == 0
+    assert f8(B.make_desc(1000, 2048, 512, variant=B.variant_id("twopass128x128"))) == B.LOKA_ERR_UNSUPPORTED
+    assert f8(B.make_desc(1000, 2048, 100)) == B.LOKA_ERR_SHAPE
+
+
 def test_probe_and_bf16_argument_validation():
     L = B.lib()
     assert L.loka_probe_error(None, FAKE, 8, 16, 16, FAKE, None, FAKE, 1 << 20, None) == B.LOKA_ERR_NULL
