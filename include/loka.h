@@ -160,7 +160,8 @@ loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, co
  * workgroup wait for the other tiles of its row panel.  The wait is bounded: if it runs out (it never does when
  * the launch's workgroups are all resident, which the launch arranges), the workgroup raises a flag in the
  * workspace and goes on, so the kernel always ends; the output of that launch is then invalid.  This call reports
- * the flag of the LAST loka_fp8_gemm_norm call that used `workspace` with `desc`: LOKA_OK, or LOKA_ERR_TIMEOUT.
+ * the flag of the LAST loka_fp8_gemm_norm or loka_fp8_gemm_norm_fp8out call that used `workspace` with `desc`:
+ * LOKA_OK, or LOKA_ERR_TIMEOUT.
  * It SYNCHRONIZES hip_stream (4 bytes are copied to the host); variants without such a wait return LOKA_OK
  * without touching the GPU.  Not needed on the hot path; meant for health checks and tests. */
 loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* workspace, size_t ws_bytes, void* hip_stream);

@@ -198,21 +198,6 @@ loka_status loka_fp8_linear_norm(const loka_gemm_desc* desc, const void* x_bf16,
                                   static_cast<hipStream_t>(hip_stream));
 }
 
-loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* workspace, size_t ws_bytes, void* hip_stream) {
-    if (!desc) return LOKA_ERR_NULL;
-    const loka_status st = validate_desc(desc, true);
-    if (st != LOKA_OK) return st;
-    const int v = resolve_variant(desc);
-    if (v < 0) return LOKA_ERR_UNSUPPORTED;
-    if (!variant_has_wait_flag(desc, v)) return LOKA_OK;
-    if (!workspace || ws_bytes < variant_workspace(desc, v)) return LOKA_ERR_WORKSPACE;
-    unsigned flag = 0;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    LOKA_HIP_TRY(hipMemcpyAsync(&flag, workspace, sizeof(flag), hipMemcpyDeviceToHost, s));
-    LOKA_HIP_TRY(hipStreamSynchronize(s));
-    return flag ? LOKA_ERR_TIMEOUT : LOKA_OK;
-}
-
 // The kernels with an FP8-output epilogue: the two that keep a whole output row inside one workgroup (streaming) or
 // one wave (strip), and the large-layer panel kernel (which sends the row extremes along with the row statistics).
 // The one the caller names, else the library's choice for the shape when it is one of the three, else the
@@ -229,6 +214,27 @@ static int fp8out_variant(const loka_gemm_desc* desc) {
     for (int u = 0; u < variant_count(); ++u)             // the panel kernel takes every shape the two others do not
         if (variant_is_panel32(u) && usable(u)) return u;
     return -1;
+}
+
+loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* workspace, size_t ws_bytes, void* hip_stream) {
+    if (!desc) return LOKA_ERR_NULL;
+    const loka_status st = validate_desc(desc, true);
+    if (st != LOKA_OK) return st;
+    // the variant loka_fp8_gemm_norm runs for desc, or (desc->variant < 0 only: the two choices can differ) the one
+    // loka_fp8_gemm_norm_fp8out runs; every workspace with a bounded wait begins with the flag
+    int v = resolve_variant(desc);
+    if (v < 0 || !variant_has_wait_flag(desc, v)) {
+        const int vq = fp8out_variant(desc);
+        if (vq >= 0 && variant_has_wait_flag(desc, vq)) v = vq;
+    }
+    if (v < 0) return LOKA_ERR_UNSUPPORTED;
+    if (!variant_has_wait_flag(desc, v)) return LOKA_OK;
+    if (!workspace || ws_bytes < variant_workspace(desc, v)) return LOKA_ERR_WORKSPACE;
+    unsigned flag = 0;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    LOKA_HIP_TRY(hipMemcpyAsync(&flag, workspace, sizeof(flag), hipMemcpyDeviceToHost, s));
+    LOKA_HIP_TRY(hipStreamSynchronize(s));
+    return flag ? LOKA_ERR_TIMEOUT : LOKA_OK;
 }
 
 size_t loka_fp8_gemm_norm_fp8out_workspace(const loka_gemm_desc* desc) {
