@@ -478,16 +478,19 @@ def test_fp8_output_of_the_panel_kernel(orc, case, affine):
             assert np.array_equal(oq.cpu().numpy(), q_o) and np.array_equal(so.cpu().numpy(), s_o)
 
 
-def test_fp8_output_of_the_panel_kernel_c5_full_size(orc):
+@pytest.mark.parametrize("affine", [False, True])
+def test_fp8_output_of_the_panel_kernel_c5_full_size(orc, affine):
     # the launch bench.py's C5pair times: 128 row panels x 16 tiles on the persistent grid, 8 rounds per workgroup
+    # (with gamma / beta: two exchanges per tile)
     w = synth.WORKLOADS["C5"]
     x, wt = synth.activations(w), synth.weights(w)
+    gamma, beta = (t.to(DEV) for t in synth.affine(w.N, seed=12)) if affine else (None, None)
     xq, sx = B.loka_quantize(x.to(DEV), B.SCALE_ROW)
     wq, sw = B.loka_quantize(wt.to(DEV), B.SCALE_COL, transpose_out=True)
     desc = B.make_desc(w.M, w.N, w.K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORMS[w.norm], w.eps, B.variant_id("panel32_256x256"))
-    out, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+    out, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, gamma, beta)
     ws = torch.empty(B.lib().loka_fp8_gemm_norm_fp8out_workspace(desc), dtype=torch.uint8, device=DEV)
-    oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws)
+    oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, gamma, beta, workspace=ws)
     torch.cuda.synchronize()
     assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
     q_ref, s_ref = B.loka_quantize(out, B.SCALE_ROW)
