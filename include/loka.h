@@ -176,14 +176,15 @@ loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* wor
  *   "wreg32"  (streaming skinny-layer kernel: N <= 1024, K in {128, 256, 512, 1024}, K * N <= 256 KB) and
  *   "strip32" (small-layer strip kernel: N <= 256, K * N <= 256 KB): the whole output row is in one workgroup /
  *             wave; every norm, gamma / beta and activation loka_fp8_gemm_norm takes;
- *   "panel32_256x256" (large layers, rows wider than a tile): LayerNorm or RMSNorm, no activation.  Without
- *             gamma / beta the normalized value grows with the pre-norm value, so the row minimum and maximum, sent
- *             along with the row statistics in the one exchange between the row's workgroups, decide the row scale;
- *             with gamma / beta the row amax of the affine result crosses the workgroups in a second exchange.
+ *   "panel32_256x256" (large layers, rows wider than a tile): LayerNorm, RMSNorm or BlockNorm (+ Hard-Swish).
+ *             LayerNorm / RMSNorm without gamma / beta: the normalized value grows with the pre-norm value, so the
+ *             row minimum and maximum, sent along with the row statistics in the one exchange between the row's
+ *             workgroups, decide the row scale; with gamma / beta, under BlockNorm or with an activation the row
+ *             amax of the result crosses the workgroups in a second exchange.  LOKA_NORM_NONE: unsupported.
  * desc->variant names one, or -1: the library's choice for the shape when it is one of the three, else the
  * streaming kernel where it covers the shape, else the panel kernel.  LOKA_ERR_UNSUPPORTED otherwise.
  * Workspace: loka_fp8_gemm_norm_fp8out_workspace(desc) bytes (non-zero only for the panel kernel with rows wider
- * than 256 columns; NULL / 0 otherwise), device memory, 16-byte aligned, not shared with a call still running;
+ * than 256 columns - also under BlockNorm, where loka_fp8_gemm_norm needs none -; NULL / 0 otherwise), device memory, 16-byte aligned, not shared with a call still running;
  * loka_fp8_gemm_norm_check reports the panel kernel's bounded wait on it as for loka_fp8_gemm_norm.
  * y_fp32 as above (NULL to skip).  oq, so: device pointers, 16-byte aligned, caller-owned. */
 size_t loka_fp8_gemm_norm_fp8out_workspace(const loka_gemm_desc* desc);

@@ -14,7 +14,7 @@ loka_status e4m3_from_f32_launch(const float*, uint8_t*, int64_t, hipStream_t);
 int variant_count();
 const char* variant_name(int);
 bool variant_supports(const loka_gemm_desc*, int);
-size_t variant_workspace(const loka_gemm_desc*, int);
+size_t variant_workspace(const loka_gemm_desc*, int, bool fp8out = false);
 loka_status fp8_gemm_norm_launch(const loka_gemm_desc*, int, const uint8_t*, const float*, const uint8_t*, const float*,
                                  const void*, const void*, void*, float*, uint8_t*, float*, void*, hipStream_t);
 int variant_streaming_id();
@@ -25,7 +25,7 @@ bool variant_supports_fused(const loka_gemm_desc*, int);
 int variant_fused_default(const loka_gemm_desc*);
 loka_status fp8_linear_norm_launch(const loka_gemm_desc*, int, const void*, const uint8_t*, const float*, const void*,
                                    const void*, void*, float*, float*, hipStream_t);
-bool variant_has_wait_flag(const loka_gemm_desc*, int);
+bool variant_has_wait_flag(const loka_gemm_desc*, int, bool fp8out = false);
 size_t bf16_gemm_workspace_bytes(const loka_gemm_desc*);
 loka_status bf16_gemm_launch(const loka_gemm_desc*, const void*, const void*, float*, void*, hipStream_t);
 // probe.hip
@@ -223,13 +223,14 @@ loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* wor
     // the variant loka_fp8_gemm_norm runs for desc, or (desc->variant < 0 only: the two choices can differ) the one
     // loka_fp8_gemm_norm_fp8out runs; every workspace with a bounded wait begins with the flag
     int v = resolve_variant(desc);
+    bool q = false;
     if (v < 0 || !variant_has_wait_flag(desc, v)) {
         const int vq = fp8out_variant(desc);
-        if (vq >= 0 && variant_has_wait_flag(desc, vq)) v = vq;
+        if (vq >= 0 && variant_has_wait_flag(desc, vq, true)) { v = vq; q = true; }
     }
     if (v < 0) return LOKA_ERR_UNSUPPORTED;
-    if (!variant_has_wait_flag(desc, v)) return LOKA_OK;
-    if (!workspace || ws_bytes < variant_workspace(desc, v)) return LOKA_ERR_WORKSPACE;
+    if (!variant_has_wait_flag(desc, v, q)) return LOKA_OK;
+    if (!workspace || ws_bytes < variant_workspace(desc, v, q)) return LOKA_ERR_WORKSPACE;
     unsigned flag = 0;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     LOKA_HIP_TRY(hipMemcpyAsync(&flag, workspace, sizeof(flag), hipMemcpyDeviceToHost, s));
@@ -240,7 +241,7 @@ loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* wor
 size_t loka_fp8_gemm_norm_fp8out_workspace(const loka_gemm_desc* desc) {
     if (validate_desc(desc, true) != LOKA_OK) return 0;
     const int v = fp8out_variant(desc);
-    return v < 0 ? 0 : variant_workspace(desc, v);
+    return v < 0 ? 0 : variant_workspace(desc, v, true);
 }
 
 loka_status loka_fp8_gemm_norm_fp8out(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
@@ -254,7 +255,7 @@ loka_status loka_fp8_gemm_norm_fp8out(const loka_gemm_desc* desc, const uint8_t*
         return LOKA_ERR_ALIGN;
     const int v = fp8out_variant(desc);
     if (v < 0) return LOKA_ERR_UNSUPPORTED;
-    const size_t need = variant_workspace(desc, v);
+    const size_t need = variant_workspace(desc, v, true);
     if (need && (!workspace || ws_bytes < need)) return LOKA_ERR_WORKSPACE;
     if (need && !aligned16(workspace)) return LOKA_ERR_ALIGN;
     return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, nullptr, y_fp32, oq, so, workspace,

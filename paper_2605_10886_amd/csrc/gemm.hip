@@ -822,16 +822,20 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
 // The panel-synchronous launch exchanges row statistics between workgroups (and has a bounded wait with an error
 // flag) unless there is nothing to exchange: no row norm, groups inside a tile, or - in the 32x32 kernel, which
 // then finalizes in the tile - a single tile per row.
-static bool panel_exchanges(const loka_gemm_desc* d, const VariantInfo& vi) {
-    if (vi.epi != EPI_PANEL_SYNC || d->norm == LOKA_NORM_NONE || d->norm == LOKA_NORM_BLOCKNORM) return false;
+// With FP8 output the 32x32 kernel also exchanges under BlockNorm: the groups stay inside a tile, the row amax of
+// the result does not.
+static bool panel_exchanges(const loka_gemm_desc* d, const VariantInfo& vi, bool fp8out = false) {
+    if (vi.epi != EPI_PANEL_SYNC || d->norm == LOKA_NORM_NONE) return false;
+    if (d->norm == LOKA_NORM_BLOCKNORM && !(fp8out && vi.name == kPanel32Name)) return false;
     return !(vi.name == kPanel32Name && d->N <= vi.bn);
 }
 
-bool variant_has_wait_flag(const loka_gemm_desc* d, int v) { return panel_exchanges(d, kVariants[v]); }
+bool variant_has_wait_flag(const loka_gemm_desc* d, int v, bool fp8out) { return panel_exchanges(d, kVariants[v], fp8out); }
 
-size_t variant_workspace(const loka_gemm_desc* d, int v) {
+size_t variant_workspace(const loka_gemm_desc* d, int v, bool fp8out) {
     const VariantInfo& vi = kVariants[v];
-    if (vi.epi == EPI_ROW_IN_TILE || d->norm == LOKA_NORM_NONE || d->norm == LOKA_NORM_BLOCKNORM) return 0;
+    if (vi.epi == EPI_ROW_IN_TILE || d->norm == LOKA_NORM_NONE) return 0;
+    if (d->norm == LOKA_NORM_BLOCKNORM && !panel_exchanges(d, vi, fp8out)) return 0;
     const int64_t tiles_n = (d->N + vi.bn - 1) / vi.bn;
     size_t stats = static_cast<size_t>(d->batch) * d->M * tiles_n * 2 * sizeof(float);
     // the 32x32 panel kernel keeps a record for every row of every 256-row panel, and its FP8-output form exchanges
@@ -839,7 +843,7 @@ size_t variant_workspace(const loka_gemm_desc* d, int v) {
     if (vi.name == kPanel32Name) stats = static_cast<size_t>(d->batch) * ((d->M + vi.bm - 1) / vi.bm) * vi.bm * tiles_n * 2 * sizeof(float) * 2;
     stats = (stats + 255) & ~size_t(255);
     if (vi.epi == EPI_PANEL_SYNC) {
-        if (!panel_exchanges(d, vi)) return 0;
+        if (!panel_exchanges(d, vi, fp8out)) return 0;
         // [error flag, 256 B][arrival counters][per-tile row statistics]
         // (the 32x32 kernel has a second arrival counter per panel, for the second exchange of its FP8-output form)
         const int64_t panels = d->batch * ((d->M + vi.bm - 1) / vi.bm) * (vi.name == kPanel32Name ? 2 : 1);
@@ -908,10 +912,10 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
     // FP8 output: the row stays inside one workgroup (streaming kernel) or one wave (strip kernel), or - panel kernel -
     // the row amax crosses the workgroups: as the row's extreme pre-norm values along with the row statistics when
     // there is no gamma / beta (the normalized value then grows with the pre-norm value), else in a second exchange.
-    // LayerNorm / RMSNorm, no activation, non-blockwise scales.
+    // The second exchange also serves BlockNorm (+ Hard-Swish), whose statistics never leave the tile.  A row norm is
+    // required; non-blockwise scales.
     if (outq && vi.name == kPanel32Name) {
-        if (blockwise || d->act != LOKA_ACT_NONE) return LOKA_ERR_UNSUPPORTED;
-        if (d->norm != LOKA_NORM_LAYERNORM && d->norm != LOKA_NORM_RMSNORM) return LOKA_ERR_UNSUPPORTED;
+        if (blockwise || d->norm == LOKA_NORM_NONE) return LOKA_ERR_UNSUPPORTED;
     } else if (outq && vi.name != kWregName && vi.name != kStripName) {
         return LOKA_ERR_UNSUPPORTED;
     }
@@ -964,7 +968,7 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         if (g <= 0) return LOKA_ERR_UNSUPPORTED;
         if (g > grid.x) g = (static_cast<int64_t>(grid.x) / p.tiles_n) * p.tiles_n;   // fewer tiles than slots
         grid = dim3(static_cast<unsigned>(g));
-        if (panel_exchanges(d, vi)) {
+        if (panel_exchanges(d, vi, outq != nullptr)) {
             const int64_t panels = static_cast<int64_t>(p.batch) * p.tiles_m * (vi.name == kPanel32Name ? 2 : 1);
             const size_t ctr_bytes = (static_cast<size_t>(panels) * 4 + 255) & ~size_t(255);
             uint8_t* ws = static_cast<uint8_t*>(workspace);

@@ -33,9 +33,9 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // y, so the row minimum and maximum travel with the row statistics in the ONE exchange between the workgroups of a
 // panel and every workgroup derives the row scale from them.  With gamma / beta the extremum can sit anywhere: the
 // tile is normalized first and the row amax of the result crosses the workgroups in a second exchange.
-// F8: 0 = bf16 output, 1 = FP8 output without gamma / beta (one exchange), 2 = FP8 output with gamma / beta (the row
-// amax of the affine result crosses the workgroups in a second exchange; an instantiation of its own because it
-// keeps the packed normalized tile in registers).
+// F8: 0 = bf16 output, 1 = FP8 output without gamma / beta (one exchange), 2 = FP8 output with gamma / beta, BlockNorm
+// or an activation (the row amax of the result crosses the workgroups in a second exchange; an instantiation of its
+// own because it keeps the packed normalized tile in registers).
 template <int EPI, int BW, int F8>
 __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     constexpr bool FP8OUT = F8 != 0;
@@ -666,8 +666,11 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                     for (int q = 0; q < 4; ++q) {
                         float o[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            o[e] = __builtin_fmaf(__builtin_fmaf(acc[mi][ni][4 * q + e], rstd_r[mi], nmr_r[mi]), gm[4 * q + e], bt[4 * q + e]);
+                        for (int e = 0; e < 4; ++e) {
+                            o[e] = __builtin_fmaf(acc[mi][ni][4 * q + e], rstd_r[mi], nmr_r[mi]);
+                            if (has_g || has_b) o[e] = __builtin_fmaf(o[e], gm[4 * q + e], bt[4 * q + e]);
+                            if (hswish) o[e] = o[e] * __builtin_fminf(__builtin_fmaxf(o[e] + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
+                        }
                         const unsigned p0 = pack_bf16x2(o[0], o[1]), p1 = pack_bf16x2(o[2], o[3]);
                         opk[mi][ni][q][0] = p0; opk[mi][ni][q][1] = p1;
                         if (ncol[ni] < p.N) {
@@ -832,10 +835,13 @@ extern "C" int loka_debug_read_times32(unsigned long long* host, int n) {
 
 constexpr size_t kPanel32Lds = 5 * 256 * 128;   // the ring; the epilogue's scratch aliases it
 
-// gamma / beta take part in this launch (the kernel ignores gamma outside LayerNorm / RMSNorm and beta outside LayerNorm)
+// The normalized value is not a growing function of the pre-norm value along the row: gamma / beta take part (the
+// kernel ignores gamma outside LayerNorm / RMSNorm and beta outside LayerNorm), or the row is normalized group by
+// group (BlockNorm), or an activation follows.  The FP8-output launch then takes the form with the second exchange.
 bool panel32_affine(const GemmParams& p) {
     const bool ln = p.norm == LOKA_NORM_LAYERNORM;
-    return (p.gamma != nullptr && (ln || p.norm == LOKA_NORM_RMSNORM)) || (p.beta != nullptr && ln);
+    return (p.gamma != nullptr && (ln || p.norm == LOKA_NORM_RMSNORM)) || (p.beta != nullptr && ln) ||
+           p.norm == LOKA_NORM_BLOCKNORM || p.act != LOKA_ACT_NONE;
 }
 // bw: 0 plain scales, 1 block scales, 2 power-of-two block scales (see the kernel); fp8out with bw == 0 only
 const void* panel32_fn(int bw, bool fp8out, bool affine) {
