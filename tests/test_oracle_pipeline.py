@@ -328,6 +328,55 @@ def test_gemm_blockwise_structure_and_equal_scale_reduction(orc):
     assert np.allclose(yb, yt, rtol=2.0 ** -22, atol=0)
 
 
+def test_gemm_blockwise_absdot_is_the_scaled_sum_of_product_magnitudes(orc):
+    # absdot scales the element-wise GEMM gate of the block recipes, so it gets pins of its own.
+    # (a) integer codes, a distinct power-of-two scale per (row, K block) and (K block, column block): every term
+    #     is exact in fp64, so the result must EQUAL sum_kb (|X_kb| |W_kb|^T) sx[m,kb] sw[kb,nb]
+    rng = np.random.default_rng(33)
+    M, N, K = 5, 256, 256                                        # two K blocks, two column blocks
+    xi, xq = _int_codes(rng, (M, K), -6, 6)
+    wi, wq = _int_codes(rng, (N, K), -6, 6)
+    KB, NB = K // 128, N // 128
+    sx = (2.0 ** rng.permutation(np.arange(-5, -5 + M * KB))).reshape(M, KB).astype(np.float32)     # all distinct
+    sw = (2.0 ** rng.permutation(np.arange(-2, -2 + KB * NB))).reshape(KB, NB).astype(np.float32)
+    y, ad = orc.fp8_gemm(xq, sx.ravel(), orc.SCALE_BLOCK_1x128, wq, sw.ravel(), orc.SCALE_BLOCK_128x128, want_absdot=True)
+    want_y = np.zeros((M, N)); want_ad = np.zeros((M, N))
+    for kb in range(KB):
+        blk = slice(kb * 128, (kb + 1) * 128)
+        s = sx[:, kb][:, None].astype(np.float64) * np.repeat(sw[kb], 128)[None, :].astype(np.float64)
+        want_y += (xi[:, blk] @ wi[:, blk].T) * s
+        want_ad += (np.abs(xi[:, blk]) @ np.abs(wi[:, blk]).T) * s
+    assert np.array_equal(y.astype(np.float64), want_y)
+    assert np.array_equal(ad, want_ad)
+    assert (ad >= np.abs(want_y)).all() and (ad > np.abs(want_y)).any()      # mixed signs: a strict upper bound somewhere
+    # swapping the two K blocks' scales of one row changes that row's absdot (the scale sits on the right block)
+    sx2 = sx.copy(); sx2[0] = sx2[0, ::-1]
+    _, ad2 = orc.fp8_gemm(xq, sx2.ravel(), orc.SCALE_BLOCK_1x128, wq, sw.ravel(), orc.SCALE_BLOCK_128x128, want_absdot=True)
+    assert not np.array_equal(ad2[0], ad[0]) and np.array_equal(ad2[1:], ad[1:])
+    # (b) arbitrary codes and arbitrary fp32 scales against exact fractions on sampled outputs
+    xq = rng.integers(0, 0x7F, size=(M, K)).astype(np.uint8) | (rng.integers(0, 2, size=(M, K)) << 7).astype(np.uint8)
+    wq = rng.integers(0, 0x7F, size=(N, K)).astype(np.uint8) | (rng.integers(0, 2, size=(N, K)) << 7).astype(np.uint8)
+    sx = rng.uniform(1e-3, 0.2, (M, KB)).astype(np.float32)
+    sw = rng.uniform(1e-3, 0.2, (KB, NB)).astype(np.float32)
+    y, ad = orc.fp8_gemm(xq, sx.ravel(), orc.SCALE_BLOCK_1x128, wq, sw.ravel(), orc.SCALE_BLOCK_128x128, want_absdot=True)
+    for m, n in [(0, 0), (1, 127), (2, 128), (4, 255), (3, 200)]:
+        ex_y = ex_a = Fraction(0)
+        for kb in range(KB):
+            s = Fraction(float(sx[m, kb])) * Fraction(float(sw[kb, n // 128]))
+            ps = [e4m3_code_value(int(xq[m, k])) * e4m3_code_value(int(wq[n, k])) for k in range(kb * 128, (kb + 1) * 128)]
+            ex_y += sum(ps) * s
+            ex_a += sum(abs(p) for p in ps) * s
+        assert abs(float(ad[m, n]) - float(ex_a)) <= float(ex_a) * 2.0 ** -48, (m, n)
+        assert abs(float(y[m, n]) - float(ex_y)) <= float(ex_a) * 2.0 ** -48 + abs(float(ex_y)) * 2.0 ** -23, (m, n)
+    # the non-block recipes' absdot against exact fractions too (row / column scales that are not powers of two)
+    sxr = rng.uniform(1e-3, 0.2, M).astype(np.float32); swc = rng.uniform(1e-3, 0.2, N).astype(np.float32)
+    _, adr = orc.fp8_gemm(xq, sxr, orc.SCALE_ROW, wq, swc, orc.SCALE_COL, want_absdot=True)
+    for m, n in [(0, 3), (4, 250)]:
+        ex_a = sum(abs(e4m3_code_value(int(xq[m, k])) * e4m3_code_value(int(wq[n, k]))) for k in range(K))
+        ex_a *= Fraction(float(sxr[m])) * Fraction(float(swc[n]))
+        assert abs(float(adr[m, n]) - float(ex_a)) <= float(ex_a) * 2.0 ** -48, (m, n)
+
+
 def test_gemm_rejects_mixed_block_modes(orc):
     z = np.zeros((128, 128), dtype=np.uint8)
     s = np.ones(128, dtype=np.float32)
@@ -486,6 +535,34 @@ def test_tracker_closed_forms(orc):
     n, ab = orc.tracker_update(synth.bf16_bits(x), 0, mu, sg, want_abs=True)
     want = np.zeros((K, K)); want[3, 3] = 2.0
     assert np.array_equal(sg, want.astype(np.float32)) and np.array_equal(ab, want) and np.all(mu == 0)
+
+
+def test_tracker_abs_scatter_with_nonzero_column_means(orc):
+    # abs_scatter bounds the fp32 accumulation of the GPU's X^T X - B mu mu^T evaluation, so it must be the magnitude
+    # of BOTH terms: |X|^T |X| + B |mu_b| |mu_b|^T (numpy, fp64).  Columns with large means of either sign make the
+    # second term and the |x| reconstruction matter; a dropped term or a sign slip moves the result by tens of per cent.
+    rng = np.random.default_rng(43)
+    B_, K = 57, 12
+    loc = np.array([9.0, -7.5, 0.0, 3.0, -0.25, 12.0, -12.0, 1.0, 0.0, -4.0, 6.5, 0.5])
+    x = _bf16_matrix(rng, B_, K, loc, rng.uniform(0.3, 2.0, K))
+    xd = x.double().numpy()
+    mub = xd.mean(0)
+    mu = np.zeros(K, dtype=np.float32); sg = np.zeros((K, K), dtype=np.float32)
+    n, ab = orc.tracker_update(synth.bf16_bits(x), 0, mu, sg, want_abs=True)
+    want = np.abs(xd).T @ np.abs(xd) + B_ * np.outer(np.abs(mub), np.abs(mub))
+    np.testing.assert_allclose(ab, want, rtol=1e-12, atol=0)
+    # each term alone is far from the sum here (so the check above sees either one missing)
+    assert (np.abs(xd).T @ np.abs(xd) < 0.75 * want).any() and (B_ * np.outer(np.abs(mub), np.abs(mub)) < 0.75 * want).all()
+    # it does bound the two evaluations' magnitudes: |scatter| <= abs_scatter, and it is symmetric
+    c = xd - mub
+    assert (np.abs(c.T @ c) <= ab * (1 + 1e-12)).all() and np.allclose(ab, ab.T, rtol=1e-13, atol=0)
+    # a stored state (second batch) does not enter abs_scatter: it describes the incoming batch only
+    x2 = _bf16_matrix(rng, 20, K, -loc, 1.0)
+    x2d = x2.double().numpy()
+    n2, ab2 = orc.tracker_update(synth.bf16_bits(x2), n, mu, sg, want_abs=True)
+    want2 = np.abs(x2d).T @ np.abs(x2d) + 20 * np.outer(np.abs(x2d.mean(0)), np.abs(x2d.mean(0)))
+    np.testing.assert_allclose(ab2, want2, rtol=1e-12, atol=0)
+    assert n2 == B_ + 20
 
 
 def test_layernorm_moments_of_fp64_row(orc):
