@@ -11,7 +11,7 @@ import torch
 
 from paper_2605_10886_amd import binding as B
 from paper_2605_10886_amd import synth
-from parity_util import (check_bf16_out, gemm_tolerance, propagated_abs_tol, propagated_abs_tol_blocknorm, rel_fro,
+from parity_util import (check_bf16_out, check_fp32_y, propagated_abs_tol, propagated_abs_tol_blocknorm, rel_fro,
                          to_np_bits)
 
 pytestmark = pytest.mark.gpu
@@ -21,11 +21,18 @@ RECIPES = {"tensor": (B.SCALE_TENSOR, B.SCALE_TENSOR), "row": (B.SCALE_ROW, B.SC
            "block_pow2": (B.SCALE_BLOCK_1x128_POW2, B.SCALE_BLOCK_128x128_POW2)}
 
 
+# Caps on the rel-Frobenius distance of fp32 Y from the oracle at full size: at most twice what was measured on MI355X
+# (C2 2.2e-5, C3 1.4e-5, C5 row / block / tensor 5.7e-5 / 5.0e-5 / 7.1e-5: the matrix pipe's truncation on that data;
+# heavier tails and outlier channels widen the spread of product magnitudes inside a group of 8).  The sharper,
+# data-dependent gates are in parity_util.check_fp32_y.
+FRO_CAP = {"C2": 4.4e-5, "C3": 2.8e-5, "C5 row": 1.14e-4, "C5 block": 1.0e-4, "C5 block_pow2": 1.5e-4, "C5 tensor": 1.42e-4}
+
+
 def _variants_for(desc):
     return [v for v in range(B.loka_variant_count()) if B.loka_variant_supports(desc, v)]
 
 
-def _run_case(orc, x, w, recipe, norm, variant, gamma=None, beta=None, rows=None, tag=""):
+def _run_case(orc, x, w, recipe, norm, variant, gamma=None, beta=None, rows=None, tag="", fro_cap=None):
     """One problem, full GPU run; oracle on `rows` (all when None).  Returns measured error figures."""
     M, K = x.shape
     N = w.shape[1]
@@ -62,12 +69,8 @@ def _run_case(orc, x, w, recipe, norm, variant, gamma=None, beta=None, rows=None
 
     y_o, absdot = orc.fp8_gemm(np.ascontiguousarray(xq_o), sx_o, xm, wq_o, sw_o, wm, want_absdot=True)
     y_g = y[idx].cpu().numpy()
-    err = np.abs(y_g.astype(np.float64) - y_o.astype(np.float64))
-    tol = gemm_tolerance(absdot, y_o, K)
-    worst = float((err / np.maximum(tol, 1e-300)).max())
-    assert worst <= 1.0, f"{tag}: fp32 Y off by {worst:.3g} x tolerance"
-    fro = rel_fro(y_g, y_o)
-    assert fro <= 2e-4, f"{tag}: rel-Frobenius of Y vs oracle {fro:.3g}"
+    fig = check_fp32_y(y_g, y_o, absdot, xq_o, sx_o, xm, wq_o, sw_o, wm, K, tag, fro_cap)
+    err = fig.pop("err")
 
     gb = None if gamma is None else synth.bf16_bits(gamma)
     bb = None if beta is None else synth.bf16_bits(beta)
@@ -80,7 +83,7 @@ def _run_case(orc, x, w, recipe, norm, variant, gamma=None, beta=None, rows=None
     o_iso = orc.norm(np.ascontiguousarray(y_g), B.NORMS[norm], 1e-5, gb, bb)
     ok1, w1, _ = check_bf16_out(o_g, o_iso, max_ulp=1)
     assert ok1, f"{tag}: norm arithmetic alone is off by {w1} ulps"
-    return {"y_rel_fro": fro, "y_worst_over_tol": worst, "o_worst_ulp": worst_ulp, "o_abs_clause": n_abs}
+    return dict(fig, o_worst_ulp=worst_ulp, o_abs_clause=n_abs)
 
 
 # ----------------------------------------------------------------------------- small shapes, every variant
@@ -163,7 +166,7 @@ def test_c2_full_size_both_recipes(orc):
     w = synth.WORKLOADS["C2"]
     x, wt = synth.activations(w), synth.weights(w)
     for recipe in ("row", "tensor"):
-        r = _run_case(orc, x, wt, recipe, w.norm, -1, rows=_sample_rows(w.M, 512), tag=f"C2 {recipe}")
+        r = _run_case(orc, x, wt, recipe, w.norm, -1, rows=_sample_rows(w.M, 512), tag=f"C2 {recipe}", fro_cap=FRO_CAP["C2"])
         print("C2", recipe, r)
 
 
@@ -172,13 +175,13 @@ def test_c3_skinny_pair_chained(orc):
     wa, wb = synth.WORKLOADS["C3a"], synth.WORKLOADS["C3b"]
     x, w1, w2 = synth.activations(wa), synth.weights(wa), synth.weights(wb)
     rows = _sample_rows(wa.M, 160)
-    r = _run_case(orc, x, w1, "row", "layernorm", -1, rows=rows, tag="C3a")
+    r = _run_case(orc, x, w1, "row", "layernorm", -1, rows=rows, tag="C3a", fro_cap=FRO_CAP["C3"])
     print("C3a", r)
     xq, sx = B.loka_quantize(x.to(DEV), B.SCALE_ROW)
     wq, sw = B.loka_quantize(w1.to(DEV), B.SCALE_COL, transpose_out=True)
     da = B.make_desc(wa.M, wa.N, wa.K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM)
     h, _ = B.loka_fp8_gemm_norm(da, xq, sx, wq, sw)
-    r = _run_case(orc, h.cpu(), w2, "row", "layernorm", -1, rows=rows, tag="C3b")
+    r = _run_case(orc, h.cpu(), w2, "row", "layernorm", -1, rows=rows, tag="C3b", fro_cap=FRO_CAP["C3"])
     print("C3b", r)
 
 
@@ -209,8 +212,7 @@ def test_c4_grouped_launch(orc, variant):
         idx = torch.from_numpy(rows + g * w.M).to(DEV)
         assert np.array_equal(xq[idx].cpu().numpy(), xq_o)
         y_g = y[idx].cpu().numpy()
-        err = np.abs(y_g.astype(np.float64) - y_o)
-        assert (err <= gemm_tolerance(absdot, y_o, w.K)).all(), f"group {g}"
+        err = check_fp32_y(y_g, y_o, absdot, xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, w.K, f"group {g}", 2.8e-5)["err"]
         o_o = orc.norm(y_o, B.NORM_RMSNORM)
         ok, worst, _ = check_bf16_out(to_np_bits(out[idx]), o_o,
                                       abs_tol=propagated_abs_tol(y_o, err, B.NORM_RMSNORM, 1e-5))
@@ -255,8 +257,7 @@ def test_streaming_variant_crosses_problem_boundaries(orc, variant):
         assert np.array_equal(xq[g * M:(g + 1) * M].cpu().numpy(), xq_o)
         y_o, absdot = orc.fp8_gemm(xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, want_absdot=True)
         y_g = y[g * M:(g + 1) * M].cpu().numpy()
-        err = np.abs(y_g.astype(np.float64) - y_o)
-        assert (err <= gemm_tolerance(absdot, y_o, K)).all(), f"problem {g}"
+        err = check_fp32_y(y_g, y_o, absdot, xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, K, f"problem {g}")["err"]
         o_o = orc.norm(y_o, B.NORM_LAYERNORM, 1e-5, gb, bb)
         ok, worst, _ = check_bf16_out(to_np_bits(out[g * M:(g + 1) * M]), o_o,
                                       abs_tol=propagated_abs_tol(y_o, err, B.NORM_LAYERNORM, 1e-5, gamma.float().numpy()))
@@ -287,8 +288,8 @@ def test_streaming_variant_without_norm_many_blocks(orc, variant, N):
     wq_o, sw_o = orc.quantize(synth.bf16_bits(w), B.SCALE_COL, transpose_out=True)
     assert np.array_equal(xq[torch.from_numpy(rows).to(DEV)].cpu().numpy(), xq_o)
     y_o, absdot = orc.fp8_gemm(xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, want_absdot=True)
-    err = np.abs(y[torch.from_numpy(rows).to(DEV)].cpu().numpy().astype(np.float64) - y_o)
-    assert (err <= gemm_tolerance(absdot, y_o, K)).all()
+    check_fp32_y(y[torch.from_numpy(rows).to(DEV)].cpu().numpy(), y_o, absdot, xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o,
+                 B.SCALE_COL, K, f"{variant} N={N}")
 
 
 # ----------------------------------------------------------------------------- BlockNorm + Hard-Swish
@@ -315,8 +316,7 @@ def _run_blocknorm_case(orc, x, w, recipe, act, variant, rows=None, tag=""):
     assert np.array_equal(xq[idx].cpu().numpy(), xq_o) and np.array_equal(wq.cpu().numpy(), wq_o), f"{tag}: codes"
     y_o, absdot = orc.fp8_gemm(np.ascontiguousarray(xq_o), sx_o, xm, wq_o, sw_o, wm, want_absdot=True)
     y_g = y[idx].cpu().numpy()
-    err = np.abs(y_g.astype(np.float64) - y_o.astype(np.float64))
-    assert (err <= gemm_tolerance(absdot, y_o, K)).all(), f"{tag}: fp32 Y"
+    err = check_fp32_y(y_g, y_o, absdot, xq_o, sx_o, xm, wq_o, sw_o, wm, K, tag)["err"]
     o_o = orc.blocknorm(y_o, 256, 1e-5, act)
     o_g = to_np_bits(out[idx])
     ok, worst, n_abs = check_bf16_out(o_g, o_o, abs_tol=propagated_abs_tol_blocknorm(y_o, err, 256, 1e-5, act == B.ACT_HARDSWISH))
@@ -392,7 +392,7 @@ def test_fp8_output_equals_quantize_of_the_bf16_output(orc, case, variant):
 
 
 @pytest.mark.parametrize("variant", ["wreg32", "strip32"])
-def test_fp8_output_grouped_launch(variant):
+def test_fp8_output_grouped_launch(orc, variant):
     # several problems with their own weights in one launch, ragged row count: codes and scales of every problem equal
     # loka_quantize of that launch's bf16 output
     G, M, K, N = 5, 650, 256, 256
@@ -411,6 +411,8 @@ def test_fp8_output_grouped_launch(variant):
     torch.cuda.synchronize()
     q_ref, s_ref = B.loka_quantize(out, B.SCALE_ROW)
     assert torch.equal(oq, q_ref) and torch.equal(so.view(torch.int32), s_ref.view(torch.int32))
+    q_o, s_o = orc.quantize(to_np_bits(out), orc.SCALE_ROW)                # the oracle's quantization of that output
+    assert np.array_equal(oq.cpu().numpy(), q_o) and np.array_equal(so.cpu().numpy().view(np.uint32), s_o.view(np.uint32))
 
 
 def test_fp8_output_chains_the_skinny_pair(orc):
@@ -433,6 +435,8 @@ def test_fp8_output_chains_the_skinny_pair(orc):
     torch.cuda.synchronize()
     assert torch.equal(hq, hq2) and torch.equal(hs, hs2)
     assert torch.equal(out_fused.view(torch.int16), out_ref.view(torch.int16))
+    hq_o, hs_o = orc.quantize(to_np_bits(h), orc.SCALE_ROW)               # the hand-over is the oracle's quantization of h
+    assert np.array_equal(hq.cpu().numpy(), hq_o) and np.array_equal(hs.cpu().numpy().view(np.uint32), hs_o.view(np.uint32))
 
 
 # the large-layer kernel: a row spans several workgroups; the row extremes travel with the row statistics
@@ -505,7 +509,7 @@ def test_fp8_output_of_the_panel_kernel_c5_full_size(orc, affine):
 @pytest.mark.parametrize("variant,shape", [("wreg32", (200, 256, 512)), ("strip32", (200, 256, 256)),
                                            ("panel32_256x256", (300, 256, 768))])
 @pytest.mark.parametrize("norm", ["layernorm", "rmsnorm"])
-def test_fp8_output_degenerate_rows(variant, shape, norm):
+def test_fp8_output_degenerate_rows(orc, variant, shape, norm):
     # rows of zeros (amax 0: the scale falls back to the clamp, codes are all zero), a row with one huge element, a row
     # of one repeated value (LayerNorm output exactly zero), negative-only rows (the row minimum decides the scale)
     M, K, N = shape
@@ -530,6 +534,24 @@ def test_fp8_output_degenerate_rows(variant, shape, norm):
     assert torch.equal(oq, q_ref)
     assert int(oq[3].max()) == 0 and int(oq[M - 1].max()) == 0   # zero rows: zero codes
     assert float(so[3]) == float(s_ref[3]) > 0.0
+    # against the oracle: its quantization of this bf16 output gives the same codes and scales bit for bit, and the bf16
+    # output itself is the oracle's (GEMM on the oracle's own codes, norm) within 2 ulps, degenerate rows included
+    q_o, s_o = orc.quantize(to_np_bits(out), orc.SCALE_ROW)
+    assert np.array_equal(oq.cpu().numpy(), q_o) and np.array_equal(so.cpu().numpy().view(np.uint32), s_o.view(np.uint32))
+    xq_o, sx_o = orc.quantize(synth.bf16_bits(x), orc.SCALE_ROW)
+    wq_o, sw_o = orc.quantize(synth.bf16_bits(wt), orc.SCALE_COL, transpose_out=True)
+    assert np.array_equal(xq.cpu().numpy(), xq_o)
+    y_o, absdot = orc.fp8_gemm(xq_o, sx_o, orc.SCALE_ROW, wq_o, sw_o, orc.SCALE_COL, want_absdot=True)
+    o_o = orc.norm(y_o, B.NORMS[norm], 1e-5)
+    # (Y is not returned by this call: bound its difference by the operands' truncation bound)
+    dy = 7 * 2.0 ** -13 * absdot
+    ok, worst, _ = check_bf16_out(to_np_bits(out), o_o, abs_tol=propagated_abs_tol(y_o, dy, B.NORMS[norm], 1e-5))
+    assert ok, f"bf16 O beyond 2 ulps of the oracle (worst {worst})"
+    assert np.all(o_o[3] == 0) and np.all(to_np_bits(out)[3] & 0x7FFF == 0)        # zero row: (0 - 0) / sqrt(eps)
+    assert s_o[3] == np.float32(1e-12) / np.float32(448.0)                          # the amax floor sets its scale
+    # row 10 (a single huge input): its FP8 row scale is set by the largest normalized value, on both sides
+    q_oo, s_oo = orc.quantize(o_o, orc.SCALE_ROW)
+    assert np.allclose(so.cpu().numpy(), s_oo, rtol=2.0 ** -6, atol=0)
 
 
 @pytest.mark.parametrize("act", [B.ACT_NONE, B.ACT_HARDSWISH])
@@ -583,7 +605,7 @@ def test_fp8_output_of_the_panel_kernel_grouped_and_repeated():
         assert torch.equal(oq, q_ref) and torch.equal(so.view(torch.int32), s_ref.view(torch.int32)), rep
 
 
-def test_fp8_output_chains_two_large_layers():
+def test_fp8_output_chains_two_large_layers(orc):
     # layer a (panel kernel, FP8 out) feeds layer b directly: same bits as bf16 hand-over + loka_quantize
     M, K, H, N = 1024, 512, 2048, 1024
     x = synth.student_t4(M, K, seed=31)
@@ -602,10 +624,12 @@ def test_fp8_output_chains_two_large_layers():
     torch.cuda.synchronize()
     assert torch.equal(hq, hq2) and torch.equal(hs, hs2)
     assert torch.equal(out_fused.view(torch.int16), out_ref.view(torch.int16))
+    hq_o, hs_o = orc.quantize(to_np_bits(h), orc.SCALE_ROW)
+    assert np.array_equal(hq.cpu().numpy(), hq_o) and np.array_equal(hs.cpu().numpy().view(np.uint32), hs_o.view(np.uint32))
 
 
 @pytest.mark.parametrize("shape", [(2048, 512, 2048), (1000, 256, 256), (3000, 256, 1024), (600, 2048, 512)])
-def test_fp8_output_with_the_library_choice(shape):
+def test_fp8_output_with_the_library_choice(orc, shape):
     # variant -1: whichever kernel the library picks must deliver codes and scales that decode to the bf16 output of
     # the plain call within the e4m3 step (half a step of 2^-3 relative to the row amax, plus the kernels' own
     # last-bit differences)
@@ -621,6 +645,15 @@ def test_fp8_output_with_the_library_choice(shape):
     amax = out.float().abs().amax(dim=1, keepdim=True)
     assert torch.equal(so, torch.clamp(amax[:, 0], min=1e-12) / 448.0) or torch.allclose(so, amax[:, 0] / 448.0, rtol=2e-2)
     assert bool(((dec - out.float()).abs() <= amax * (2.0 ** -4 + 2.0 ** -6)).all())
+    # the oracle's quantization of the plain call's bf16 output: same scales up to the two kernels' last-bit
+    # differences in the row's largest value, and codes at most one e4m3 step apart where those differences cross a
+    # rounding boundary (bit-exact when the library picks the same kernel for both calls)
+    q_o, s_o = orc.quantize(to_np_bits(out), orc.SCALE_ROW)
+    assert np.allclose(so.cpu().numpy(), s_o, rtol=2.0 ** -6, atol=0)
+    dec_o = torch.from_numpy(q_o).view(torch.float8_e4m3fn).float() * torch.from_numpy(s_o)[:, None]
+    assert bool(((dec.cpu() - dec_o).abs() <= amax.cpu() * 2.0 ** -4).all())
+    if np.array_equal(so.cpu().numpy().view(np.uint32), s_o.view(np.uint32)):
+        assert (oq.cpu().numpy() != q_o).mean() < 1e-3
 
 
 def test_fp8_output_unsupported_cases():
@@ -655,8 +688,7 @@ def test_backward_gemms_with_the_forward_entry_points(orc, shape):
     wq_o, sw_o = orc.quantize(synth.bf16_bits(w), B.SCALE_ROW)
     assert np.array_equal(dyq.cpu().numpy(), dyq_o) and np.array_equal(wq.cpu().numpy(), wq_o)
     dx_o, ad = orc.fp8_gemm(dyq_o, sdy_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, want_absdot=True)
-    err = np.abs(dx.cpu().numpy().astype(np.float64) - dx_o)
-    assert (err <= gemm_tolerance(ad, dx_o, N)).all(), "dX"
+    check_fp32_y(dx.cpu().numpy(), dx_o, ad, dyq_o, sdy_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, N, "dX")
     ref = dy.double() @ w.double().T                                        # sanity against the unquantized product
     assert rel_fro(dx.cpu().numpy(), ref.numpy()) < 0.06
 
@@ -669,8 +701,7 @@ def test_backward_gemms_with_the_forward_entry_points(orc, shape):
     dytq_o, sdyt_o = orc.quantize(synth.bf16_bits(dy), B.SCALE_COL, transpose_out=True)
     assert np.array_equal(xtq.cpu().numpy(), xtq_o) and np.array_equal(dytq.cpu().numpy(), dytq_o)
     dw_o, ad = orc.fp8_gemm(xtq_o, sxt_o, B.SCALE_ROW, dytq_o, sdyt_o, B.SCALE_COL, want_absdot=True)
-    err = np.abs(dw.cpu().numpy().astype(np.float64) - dw_o)
-    assert (err <= gemm_tolerance(ad, dw_o, M)).all(), "dW"
+    check_fp32_y(dw.cpu().numpy(), dw_o, ad, xtq_o, sxt_o, B.SCALE_ROW, dytq_o, sdyt_o, B.SCALE_COL, M, "dW")
     ref = x.double().T @ dy.double()
     assert rel_fro(dw.cpu().numpy(), ref.numpy()) < 0.06
 
@@ -687,7 +718,8 @@ def test_c5_full_size(orc, recipe):
     for v in _variants_for(desc):
         if recipe != "row" and v != B.loka_default_variant(desc):
             continue
-        r = _run_case(orc, x, wt, recipe, "layernorm", v, rows=rows, tag=f"C5 {recipe} {B.loka_variant_name(v)}")
+        r = _run_case(orc, x, wt, recipe, "layernorm", v, rows=rows, tag=f"C5 {recipe} {B.loka_variant_name(v)}",
+                      fro_cap=FRO_CAP["C5 " + recipe])
         print("C5", recipe, B.loka_variant_name(v), r)
 
 
@@ -860,8 +892,8 @@ def test_fused_quantization_c4_full_size(orc, variant):
         y_o, absdot = orc.fp8_gemm(xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, want_absdot=True)
         idx = torch.from_numpy(rows + g * w.M).to(DEV)
         assert np.array_equal(sx1[idx].cpu().numpy().view(np.uint32), sx_o.view(np.uint32))
-        err = np.abs(y1[idx].cpu().numpy().astype(np.float64) - y_o)
-        assert (err <= gemm_tolerance(absdot, y_o, w.K)).all(), f"group {g}"
+        err = check_fp32_y(y1[idx].cpu().numpy(), y_o, absdot, xq_o, sx_o, B.SCALE_ROW, wq_o, sw_o, B.SCALE_COL, w.K,
+                           f"group {g}", 2.8e-5)["err"]
         ok, worst, _ = check_bf16_out(to_np_bits(o1[idx]), orc.norm(y_o, B.NORM_RMSNORM),
                                       abs_tol=propagated_abs_tol(y_o, err, B.NORM_RMSNORM, 1e-5))
         assert ok, f"group {g}: worst {worst} ulps"
