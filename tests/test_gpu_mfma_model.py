@@ -131,7 +131,9 @@ def test_adversarial_groups_give_exactly_the_modelled_value():
         assert not bad, f"{B.loka_variant_name(v)}: " + "; ".join(bad)
         off = np.ones_like(y, dtype=bool)
         off[np.arange(len(_CASES)), np.arange(len(_CASES))] = False
-        assert np.array_equal(y[off], y_m[off].astype(np.float32).astype(np.float64))   # the cross terms too (mostly zero)
+        # the cross terms (case i's row against case j's column: a few non-zero groups each) follow the model too, up
+        # to the order of their fp32 sums
+        assert np.allclose(y[off], y_m[off], rtol=2.0 ** -22, atol=0)
 
 
 @pytest.mark.parametrize("kind", ["uniform codes", "gaussian", "gaussian with outlier channels"])
