@@ -158,13 +158,21 @@ loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, co
 
 /* Variants whose row statistics cross workgroups inside one launch (rows wider than a tile) make every
  * workgroup wait for the other tiles of its row panel.  The wait is bounded: if it runs out (it never does when
- * the launch's workgroups are all resident, which the launch arranges), the workgroup raises a flag in the
- * workspace and goes on, so the kernel always ends; the output of that launch is then invalid.  This call reports
- * the flag of the LAST loka_fp8_gemm_norm or loka_fp8_gemm_norm_fp8out call that used `workspace` with `desc`:
+ * the launch's workgroups are all resident, which the launch arranges on an otherwise idle device), the workgroup
+ * marks the launch in the workspace, writes the rows of its tile as NaN (FP8 output: a NaN row scale) so that
+ * nothing downstream can take them for results, and goes on: the kernel always ends.  This call reports
+ * the mark of the LAST loka_fp8_gemm_norm or loka_fp8_gemm_norm_fp8out call that used `workspace` with `desc`:
  * LOKA_OK, or LOKA_ERR_TIMEOUT.
  * It SYNCHRONIZES hip_stream (4 bytes are copied to the host); variants without such a wait return LOKA_OK
  * without touching the GPU.  Not needed on the hot path; meant for health checks and tests. */
 loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* Test aid for the error path of those bounded waits: from now on every such wait polls at most `polls` times
+ * (process-wide; a negative value restores the library's limit).  With polls == 0 the waits also look for a value
+ * no workgroup writes, so every one of them runs out after its first poll whatever the timing: the kernels still
+ * end, the rows of the affected tiles are written as NaN (bf16 output) or get a NaN row scale (FP8 output), and
+ * loka_fp8_gemm_norm_check reports LOKA_ERR_TIMEOUT.  Host only; takes effect at the next launch. */
+void loka_test_set_spin_limit(int64_t polls);
 
 /* FP8 output for the next layer (Section 3.2, "Block-wise Normalization", Case 1: once a row is normalized
  * inside the kernel, the activation and the quantization for the next layer can join the same epilogue, before

@@ -75,6 +75,7 @@ _SIGNATURES = [
     ("loka_fp8_linear_norm", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                      c_void_p, c_void_p]),
     ("loka_fp8_gemm_norm_check", c_int, [POINTER(GemmDesc), c_void_p, c_size_t, c_void_p]),
+    ("loka_test_set_spin_limit", None, [c_int64]),
     ("loka_fp8_gemm_norm_fp8out_workspace", c_size_t, [POINTER(GemmDesc)]),
     ("loka_fp8_gemm_norm_fp8out", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                           c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
@@ -225,6 +226,10 @@ def loka_fp8_gemm_norm_check(desc: GemmDesc, workspace) -> int:
     LOKA_ERR_TIMEOUT."""
     return int(lib().loka_fp8_gemm_norm_check(byref(desc), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                               _stream()))
+
+
+def loka_test_set_spin_limit(polls: int) -> None:
+    lib().loka_test_set_spin_limit(int(polls))
 
 
 def loka_fp8_gemm_norm_fp8out(desc: GemmDesc, xq, sx, wq, sw, gamma=None, beta=None, want_y: bool = False, oq=None,

@@ -26,8 +26,9 @@ int variant_fused_default(const loka_gemm_desc*);
 loka_status fp8_linear_norm_launch(const loka_gemm_desc*, int, const void*, const uint8_t*, const float*, const void*,
                                    const void*, void*, float*, float*, hipStream_t);
 bool variant_has_wait_flag(const loka_gemm_desc*, int, bool fp8out = false);
+void test_set_spin_limit(long long);
 size_t bf16_gemm_workspace_bytes(const loka_gemm_desc*);
-loka_status bf16_gemm_launch(const loka_gemm_desc*, const void*, const void*, float*, void*, hipStream_t);
+loka_status bf16_gemm_launch(const loka_gemm_desc*, const void*, const void*, float*, void*, hipStream_t, bool weights_ready = false);
 // probe.hip
 size_t probe_workspace_bytes();
 loka_status probe_launch(const float*, const float*, int64_t, int64_t, int64_t, loka_probe_stats*, float*, void*,
@@ -76,10 +77,6 @@ loka_status validate_desc(const loka_gemm_desc* d, bool fp8) {
 
 int resolve_variant(const loka_gemm_desc* d) {
     if (d->variant >= 0) return variant_supports(d, d->variant) ? d->variant : -1;
-    if (const char* f = std::getenv("LOKA_FORCE_VARIANT")) {
-        const int v = std::atoi(f);
-        if (variant_supports(d, v)) return v;
-    }
     return default_variant(d);
 }
 
@@ -231,12 +228,16 @@ loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* wor
     if (v < 0) return LOKA_ERR_UNSUPPORTED;
     if (!variant_has_wait_flag(desc, v, q)) return LOKA_OK;
     if (!workspace || ws_bytes < variant_workspace(desc, v, q)) return LOKA_ERR_WORKSPACE;
-    unsigned flag = 0;
+    // header of the workspace: [0] the nonce of the last launch that used it, [1] the nonce of the last launch in
+    // which a wait ran out (0 in both: never used)
+    unsigned long long hdr[2] = {0, 0};
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    LOKA_HIP_TRY(hipMemcpyAsync(&flag, workspace, sizeof(flag), hipMemcpyDeviceToHost, s));
+    LOKA_HIP_TRY(hipMemcpyAsync(hdr, workspace, sizeof(hdr), hipMemcpyDeviceToHost, s));
     LOKA_HIP_TRY(hipStreamSynchronize(s));
-    return flag ? LOKA_ERR_TIMEOUT : LOKA_OK;
+    return (hdr[0] != 0 && hdr[0] == hdr[1]) ? LOKA_ERR_TIMEOUT : LOKA_OK;
 }
+
+void loka_test_set_spin_limit(int64_t polls) { test_set_spin_limit(polls); }
 
 size_t loka_fp8_gemm_norm_fp8out_workspace(const loka_gemm_desc* desc) {
     if (validate_desc(desc, true) != LOKA_OK) return 0;

@@ -21,11 +21,21 @@ bool variant_is_strip(int);
 int variant_bn(int);
 int variant_bm(int);
 loka_status validate_desc(const loka_gemm_desc* d, bool fp8);
+loka_status bf16_gemm_launch(const loka_gemm_desc*, const void*, const void*, float*, void*, hipStream_t, bool weights_ready);
 
 namespace {
 
-using ShapeKey = std::tuple<int64_t, int64_t, int64_t, int64_t, int, double, double>;   // M N K batch norm budget floor
-using RecipeKey = std::tuple<int64_t, int64_t, int64_t, int64_t, int, int, int>;        // M N K batch norm x_mode w_mode
+// what a profiled choice depends on besides the shape: the epilogue (norm, group width, activation), whether the
+// problems of a grouped launch share one weight, and the device it was measured on
+using Epilogue = std::tuple<int, int, int, int, int>;                                    // norm block_n act shared_w device
+using ShapeKey = std::tuple<int64_t, int64_t, int64_t, int64_t, Epilogue, double, double>;   // M N K batch epilogue budget floor
+using RecipeKey = std::tuple<int64_t, int64_t, int64_t, int64_t, Epilogue, int, int>;        // M N K batch epilogue x_mode w_mode
+
+Epilogue epilogue_of(const loka_gemm_desc* d) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) dev = -1;          // (no device: host-only queries still get an answer)
+    return Epilogue(d->norm, d->norm == LOKA_NORM_BLOCKNORM ? d->block_n : 0, d->act, d->batch > 1 && d->strideW == 0 ? 1 : 0, dev);
+}
 
 struct CachedChoice {
     loka_choice choice;
@@ -36,9 +46,9 @@ std::mutex g_mu;
 std::map<ShapeKey, CachedChoice> g_choices;
 std::map<RecipeKey, int> g_best_variant;
 
-bool log_on() {
-    const char* e = std::getenv("LOKA_LOG");
-    return e && e[0] && e[0] != '0';
+bool log_on() {       // LOKA_LOG, read once per process
+    static const bool on = [] { const char* e = std::getenv("LOKA_LOG"); return e && e[0] && e[0] != '0'; }();
+    return on;
 }
 
 struct DevBuf {
@@ -55,8 +65,9 @@ struct DevBuf {
 // rows wider than every such tile go to the two-pass schedule.
 int default_variant(const loka_gemm_desc* d) {
     {
+        const RecipeKey rk(d->M, d->N, d->K, d->batch, epilogue_of(d), d->x_mode, d->w_mode);
         std::lock_guard<std::mutex> lk(g_mu);
-        auto it = g_best_variant.find(RecipeKey(d->M, d->N, d->K, d->batch, d->norm, d->x_mode, d->w_mode));
+        auto it = g_best_variant.find(rk);
         if (it != g_best_variant.end() && variant_supports(d, it->second)) return it->second;
     }
     if (d->norm == LOKA_NORM_BLOCKNORM) {
@@ -160,7 +171,7 @@ loka_status loka_dispatch(const loka_gemm_desc* shape, const void* x_bf16, const
     if (!(err_budget >= 0.0)) return LOKA_ERR_UNSUPPORTED;
     if (!aligned16(x_bf16) || !aligned16(w_bf16)) return LOKA_ERR_ALIGN;
 
-    const ShapeKey key(d.M, d.N, d.K, d.batch, d.norm, err_budget, min_speedup);
+    const ShapeKey key(d.M, d.N, d.K, d.batch, epilogue_of(&d), err_budget, min_speedup);
     {
         std::lock_guard<std::mutex> lk(g_mu);
         auto it = g_choices.find(key);
@@ -226,8 +237,12 @@ loka_status loka_dispatch(const loka_gemm_desc* shape, const void* x_bf16, const
     };
 
     // BF16 reference: Yref and the baseline time
+    // (its weights are transposed once, outside the timed region: the same offline weight preparation the FP8
+    // candidates get, whose weights are quantized before their timing starts)
     float usec_bf16 = 0.f;
-    st = time_region([&] { return loka_bf16_gemm(&d, xb, wb, yref.as<float>(), ws_b.p, ws_bf16, s); }, &usec_bf16);
+    st = loka_bf16_gemm(&d, xb, wb, yref.as<float>(), ws_b.p, ws_bf16, s);
+    if (st != LOKA_OK) return st;
+    st = time_region([&] { return bf16_gemm_launch(&d, xb, wb, yref.as<float>(), ws_b.p, s, true); }, &usec_bf16);
     if (st != LOKA_OK) return st;
 
     struct Recipe { int xm, wm; };
@@ -286,12 +301,20 @@ loka_status loka_dispatch(const loka_gemm_desc* shape, const void* x_bf16, const
             if (st != LOKA_OK) return st;
             LOKA_HIP_TRY(hipMemcpyAsync(&c.stats, stats_d.p, sizeof(loka_probe_stats), hipMemcpyDeviceToHost, s));
             LOKA_HIP_TRY(hipStreamSynchronize(s));
+            // a candidate whose cross-workgroup wait ran out (the device was not its alone) produced no result:
+            // neither its time nor its error means anything
+            st = loka_fp8_gemm_norm_check(&t, ws_g.p, ws_gemm, s);
+            if (st == LOKA_ERR_TIMEOUT) {
+                if (log_on()) std::fprintf(stderr, "[loka] %s: a bounded wait ran out, candidate dropped\n", variant_name(v));
+                continue;
+            }
+            if (st != LOKA_OK) return st;
             cands.push_back(c);
             if (best_v < 0 || c.usec_gemm < best_usec) { best_v = v; best_usec = c.usec_gemm; }
         }
         if (best_v >= 0) {
             std::lock_guard<std::mutex> lk(g_mu);
-            g_best_variant[RecipeKey(M, N, K, B, d.norm, rc.xm, rc.wm)] = best_v;
+            g_best_variant[RecipeKey(M, N, K, B, epilogue_of(&d), rc.xm, rc.wm)] = best_v;
         }
     }
 
@@ -319,7 +342,8 @@ loka_status loka_dispatch(const loka_gemm_desc* shape, const void* x_bf16, const
             std::fprintf(stderr, "[loka] M=%lld N=%lld K=%lld B=%lld x=%d w=%d %-16s %8.1f us (gemm %8.1f) rel_fro %.4g mere %.4g %s\n",
                          (long long)M, (long long)N, (long long)K, (long long)B, c.x_mode, c.w_mode, variant_name(c.variant),
                          c.usec, c.usec_gemm, c.stats.rel_fro, c.stats.mere, c.feasible ? "feasible" : "-");
-        std::fprintf(stderr, "[loka] bf16 %.1f us; budget %.3g floor %.3g -> %s\n", usec_bf16, err_budget, min_speedup,
+        std::fprintf(stderr, "[loka] bf16 reference %.1f us (%.0f %% of the 2.5 PFLOP/s BF16 peak; weights prepared outside the timing); budget %.3g floor %.3g -> %s\n",
+                     usec_bf16, 100.0 * 2.0 * M * N * K * B / (usec_bf16 * 1e-6) / 2.5e15, err_budget, min_speedup,
                      pick >= 0 ? variant_name(cands[pick].variant) : "no FP8 candidate (stay in BF16)");
     }
     {

@@ -21,7 +21,10 @@
 // position): key(r) takes 8 values over the 8 same-parity rows of each operand's read pattern.
 #include "gemm_common.h"
 
-#include <cstdlib>
+#include <atomic>
+#include <chrono>
+#include <mutex>
+#include <vector>
 
 namespace loka {
 
@@ -60,6 +63,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
         const int G = gridDim.x;
         tile_first = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
         tile_stride = G;
+        // the workspace remembers which launch used it last (a wait that runs out records the same value beside it)
+        if (p.header && blockIdx.x == 0 && threadIdx.x == 0)
+            __hip_atomic_store(p.header, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   for (int tile = tile_first; tile < total_tiles; tile += tile_stride) {
     int t = tile;
@@ -140,7 +146,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     const float* sxg = p.sx + static_cast<int64_t>(g) * p.strideSx;
     const float* swg = p.sw + static_cast<int64_t>(g) * p.strideSw;
 
-    LOKA_STAMP(0);
 #pragma unroll
     for (int j = 0; j < JN; ++j) issue_j(j, 0, 0, 0, 0, true);   // stage 0, every wave's share
 
@@ -296,7 +301,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     // ------------------------------------------------------------------ epilogue
     // lane owns row m (per mi) and, per N-part h and tile ti, columns ncol(h) + coff_of(ti) + [0, 4)
     __syncthreads();                       // all waves are done reading the stages: LDS is free
-    LOKA_STAMP(1);
     float* red = reinterpret_cast<float*>(smem);   // [BM][WAVES_N][3]
     const int64_t obase = static_cast<int64_t>(g) * p.strideO;
     const bool tensor_x = p.x_mode == LOKA_SCALE_TENSOR, tensor_w = p.w_mode == LOKA_SCALE_TENSOR;
@@ -463,10 +467,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
 
     if (EPI == EPI_PANEL_SYNC && p.norm != LOKA_NORM_NONE) {
         // The row spans tiles_n workgroups that run in the same round.  Each publishes its tile's
-        // (mean, M2) [or (0, sumsq)] per row, bumps the panel's arrival counter, waits until all
-        // tiles_n have arrived, and merges every tile's statistics in one fixed order, so all of them
-        // normalize with identical row statistics.  Only these few words per row leave the CU.
-        LOKA_STAMP(2);
+        // (mean, M2) [or (0, sumsq)] per row, signals its arrival, waits until all tiles_n have arrived, and
+        // merges every tile's statistics in one fixed order, so all of them normalize with identical row
+        // statistics.  Only these few words per row leave the CU.
         const int panel = g * p.tiles_m + tm;
         float* prow = p.part + (static_cast<int64_t>(g) * p.M) * (2 * p.tiles_n);
         if (wave_n == 0 && q == 0) {
@@ -480,28 +483,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                     __hip_atomic_store(dst + 1, rstd_r[mi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the stores have completed before the barrier
         }
-        __syncthreads();
-        LOKA_STAMP(3);
-        if (threadIdx.x == 0) {
-            unsigned* ctr = p.counters + panel;
-            // the publishers' stores completed before the barrier, so a relaxed add orders after them;
-            // polling is relaxed too (an acquiring poll would invalidate the L2 under the neighbours' main loops)
-            __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            // bounded wait: every workgroup of the panel is resident, so this ends after the slowest
-            // one's main loop; the limit only turns a scheduling surprise into an error flag
-            unsigned spins = 0;
-            while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.arrivals) {
-                __builtin_amdgcn_s_sleep(16);
-                if (++spins > p.spin_limit) {
-                    __hip_atomic_store(p.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-            }
-        }
-        __syncthreads();
-        LOKA_STAMP(4);
+        int* lds_word = reinterpret_cast<int*>(smem) + BM * WAVES_N * 3 + 4;                  // between `red` and `fin`
+        const bool arrived = panel_publish_and_wait(p, p.flags + static_cast<int64_t>(panel) * p.tiles_n, tn, p.tiles_n, lds_word);
         const bool ln = p.norm == LOKA_NORM_LAYERNORM;
         // Merge: the workgroup's BM rows are spread over its threads (TPR threads per row, each folding a
         // contiguous share of the row's tiles_n entries in order, read with device-coherent 8-byte loads
@@ -557,7 +541,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
                         m2 = m2 + m2b;
                     }
                 }
-                if (sub == 0 && r < BM) fin[r] = make_float2(ln ? mean : 0.f, __builtin_amdgcn_rsqf(m2 * inv_n + p.eps));
+                // (a wait that ran out: the row statistics are not to be trusted, the tile's rows leave as NaN)
+                if (sub == 0 && r < BM)
+                    fin[r] = arrived ? make_float2(ln ? mean : 0.f, __builtin_amdgcn_rsqf(m2 * inv_n + p.eps))
+                                     : make_float2(__builtin_nanf(""), __builtin_nanf(""));
             }
             __syncthreads();
 #pragma unroll
@@ -569,7 +556,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
         }
     }
 
-    LOKA_STAMP(5);
     // ---- normalize, affine, bf16 store
     const bool has_g = p.gamma != nullptr, has_b = p.beta != nullptr && p.norm == LOKA_NORM_LAYERNORM;
 #pragma unroll
@@ -612,7 +598,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
             }
         }
     }
-    LOKA_STAMP(6);
   }  // tile loop
 }
 
@@ -759,15 +744,10 @@ static const VariantInfo kVariants[] = {
     // the same schedule on 32x32x64 MFMAs: the throughput variant
     {kPanel32Name, 256, 256, 512, EPI_PANEL_SYNC, panel32_lds(), &launch_panel32, panel32_fn(0, false, false), panel32_fn(1, false, false)},
 };
-constexpr int kNumCUs = 256;          // MI355X; the launch re-checks against the device it runs on
+constexpr int kMaxRowTiles = 256;     // shape limit of the panel-synchronous schedule (a row's tiles must be co-resident:
+                                      // the launch checks them against the CU count of the device it runs on)
 constexpr unsigned kSpinLimit = 1u << 18;   // polls of ~1 us each (a device-scope load and a short sleep): far beyond any main loop
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-
-#ifdef LOKA_DEBUG_TIMES
-extern "C" int loka_debug_read_times(unsigned long long* host, int n) {
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(loka_dbg_times), sizeof(unsigned long long) * n) == hipSuccess ? 0 : 1;
-}
-#endif
 
 int variant_count() { return kNumVariants; }
 const char* variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
@@ -812,7 +792,7 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
     if (d->norm == LOKA_NORM_BLOCKNORM && vi.launch != &launch_panel32) return false;
     if ((scale_mode_is_block(d->x_mode) ? vi.fn_block : vi.fn_plain) == nullptr) return false;
     if (vi.epi == EPI_ROW_IN_TILE && d->N > vi.bn) return false;
-    if (vi.epi == EPI_PANEL_SYNC && (d->N + vi.bn - 1) / vi.bn > kNumCUs) return false;
+    if (vi.epi == EPI_PANEL_SYNC && (d->N + vi.bn - 1) / vi.bn > kMaxRowTiles) return false;
     if (static_cast<int64_t>(vi.bm > vi.bn ? vi.bm : vi.bn) * d->K >= (int64_t(1) << 31)) return false;   // tile-relative offsets are 32-bit
     const int64_t tiles = ((d->M + vi.bm - 1) / vi.bm) * ((d->N + vi.bn - 1) / vi.bn) * d->batch;
     return tiles < (int64_t(1) << 31);
@@ -832,6 +812,13 @@ static bool panel_exchanges(const loka_gemm_desc* d, const VariantInfo& vi, bool
 
 bool variant_has_wait_flag(const loka_gemm_desc* d, int v, bool fp8out) { return panel_exchanges(d, kVariants[v], fp8out); }
 
+// one 8-byte arrival word per (row panel, tile of the panel); the 32x32 kernel has a second set for the second
+// exchange of its FP8-output form
+static size_t panel_flag_bytes(const loka_gemm_desc* d, const VariantInfo& vi) {
+    const int64_t panels = d->batch * ((d->M + vi.bm - 1) / vi.bm), tiles_n = (d->N + vi.bn - 1) / vi.bn;
+    return (static_cast<size_t>(panels) * tiles_n * 8 * (vi.name == kPanel32Name ? 2 : 1) + 255) & ~size_t(255);
+}
+
 size_t variant_workspace(const loka_gemm_desc* d, int v, bool fp8out) {
     const VariantInfo& vi = kVariants[v];
     if (vi.epi == EPI_ROW_IN_TILE || d->norm == LOKA_NORM_NONE) return 0;
@@ -844,10 +831,8 @@ size_t variant_workspace(const loka_gemm_desc* d, int v, bool fp8out) {
     stats = (stats + 255) & ~size_t(255);
     if (vi.epi == EPI_PANEL_SYNC) {
         if (!panel_exchanges(d, vi, fp8out)) return 0;
-        // [error flag, 256 B][arrival counters][per-tile row statistics]
-        // (the 32x32 kernel has a second arrival counter per panel, for the second exchange of its FP8-output form)
-        const int64_t panels = d->batch * ((d->M + vi.bm - 1) / vi.bm) * (vi.name == kPanel32Name ? 2 : 1);
-        return 256 + ((static_cast<size_t>(panels) * 4 + 255) & ~size_t(255)) + stats;
+        // [header, 256 B: launch nonce, nonce of the last launch with a wait that ran out][arrival words][per-tile row statistics]
+        return 256 + panel_flag_bytes(d, vi) + stats;
     }
     // fp32 Y staging for the normalization pass (used when the caller does not ask for Y)
     return stats + static_cast<size_t>(d->batch) * d->M * d->N * sizeof(float);
@@ -858,19 +843,67 @@ __global__ void zero_u32_kernel(uint32_t* p, int64_t n) {
     if (i < n) p[i] = 0u;
 }
 
-// CUs of the current device and workgroups of `fn` that fit on one of them.
-static loka_status resident_capacity(const void* fn, int threads, size_t lds, int* cus, int* per_cu) {
-    int dev = 0;
-    LOKA_HIP_TRY(hipGetDevice(&dev));
-    LOKA_HIP_TRY(hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev));
-    LOKA_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, fn, threads, lds));
+// ---- what a launch needs to know about the device and its kernels, asked once per process and device.
+// The hot calls then do nothing but fill the parameter block and launch.
+namespace {
+constexpr int kMaxDevices = 64;
+struct FnState { const void* fn; size_t lds; int threads; int per_cu; };   // attribute set; workgroups per CU (-1: not asked yet)
+struct DeviceState {
+    int cus = 0;                       // 0: not asked yet
+    std::vector<FnState> fns;
+};
+std::mutex g_dev_mu;
+DeviceState g_dev[kMaxDevices];
+std::atomic<long long> g_spin_override{-1};   // loka_test_set_spin_limit
+std::atomic<unsigned long long> g_nonce_seq{0};
+}  // namespace
+
+// Current device and its CU count.
+static loka_status device_cus(int* dev, int* cus) {
+    LOKA_HIP_TRY(hipGetDevice(dev));
+    if (*dev < 0 || *dev >= kMaxDevices) return LOKA_ERR_HIP;
+    std::lock_guard<std::mutex> lk(g_dev_mu);
+    DeviceState& st = g_dev[*dev];
+    if (st.cus == 0) LOKA_HIP_TRY(hipDeviceGetAttribute(&st.cus, hipDeviceAttributeMultiprocessorCount, *dev));
+    *cus = st.cus;
+    return LOKA_OK;
+}
+int device_cu_count() {
+    int dev = 0, cus = 0;
+    return device_cus(&dev, &cus) == LOKA_OK ? cus : 0;
+}
+
+// Makes `fn` launchable with `lds` bytes of dynamic LDS on device `dev` (once) and returns how many of its
+// workgroups fit a CU (asked once).
+static loka_status prepare_fn(int dev, const void* fn, int threads, size_t lds, int* per_cu) {
+    std::lock_guard<std::mutex> lk(g_dev_mu);
+    for (FnState& f : g_dev[dev].fns)
+        if (f.fn == fn && f.lds == lds && f.threads == threads) {
+            if (per_cu && f.per_cu < 0) LOKA_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&f.per_cu, fn, threads, lds));
+            if (per_cu) *per_cu = f.per_cu;
+            return LOKA_OK;
+        }
+    FnState f{fn, lds, threads, -1};
+    LOKA_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    if (per_cu) LOKA_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&f.per_cu, fn, threads, lds));
+    g_dev[dev].fns.push_back(f);
+    if (per_cu) *per_cu = f.per_cu;
     return LOKA_OK;
 }
 
-static loka_status set_lds(const void* fn, size_t lds) {
-    LOKA_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
-    return LOKA_OK;
+// A 64-bit value no earlier launch of this process has used and stale memory will not hold: odd, never 0.
+static unsigned long long fresh_nonce() {
+    static const unsigned long long seed = [] {
+        unsigned long long z = static_cast<unsigned long long>(std::chrono::steady_clock::now().time_since_epoch().count());
+        z ^= reinterpret_cast<uintptr_t>(&g_nonce_seq) * 0x9E3779B97F4A7C15ull;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    }();
+    return (seed + 4ull * g_nonce_seq.fetch_add(1, std::memory_order_relaxed)) | 1ull;
 }
+
+void test_set_spin_limit(long long polls) { g_spin_override.store(polls, std::memory_order_relaxed); }
 
 static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const uint8_t* xq, const float* sx, const uint8_t* wq,
                                         const float* sw, const void* gamma, const void* beta, void* out, float* y,
@@ -929,64 +962,59 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         p.part = static_cast<float*>(workspace);
         if (!y) p.y = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + stats);
     }
-    if (vi.name == kWregName) {
-        int dev = 0, cus = 0;
+    int dev = 0, cus = 0;
+    if (device_cus(&dev, &cus) != LOKA_OK) return LOKA_ERR_HIP;
+    if (vi.name == kWregName || vi.name == kStripName) {
         const void* fn = nullptr;
         size_t lds = 0;
-        LOKA_HIP_TRY(hipGetDevice(&dev));
-        LOKA_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        const int wgs = wreg_plan(d->M, d->N, d->K, d->batch, cus, p.outq != nullptr, p.xb != nullptr, &fn, &lds);
+        const int wgs = vi.name == kWregName
+                            ? wreg_plan(d->M, d->N, d->K, d->batch, cus, p.outq != nullptr, p.xb != nullptr, &fn, &lds)
+                            : strip_plan(d->M, d->N, d->K, d->batch, cus, p.xb != nullptr, p.outq != nullptr, &fn, &lds);
         if (wgs <= 0) return LOKA_ERR_UNSUPPORTED;
-        if (set_lds(fn, lds) != LOKA_OK) return LOKA_ERR_HIP;
-        vi.launch(p, false, dim3(static_cast<unsigned>(wgs)), s);
-        return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
-    }
-    if (vi.name == kStripName) {
-        int dev = 0, cus = 0;
-        const void* fn = nullptr;
-        size_t lds = 0;
-        LOKA_HIP_TRY(hipGetDevice(&dev));
-        LOKA_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        const int wgs = strip_plan(d->M, d->N, d->K, d->batch, cus, p.xb != nullptr, p.outq != nullptr, &fn, &lds);
-        if (wgs <= 0) return LOKA_ERR_UNSUPPORTED;
-        if (set_lds(fn, lds) != LOKA_OK) return LOKA_ERR_HIP;
+        if (prepare_fn(dev, fn, vi.threads, lds, nullptr) != LOKA_OK) return LOKA_ERR_HIP;
         vi.launch(p, false, dim3(static_cast<unsigned>(wgs)), s);
         return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
     }
     const void* kfn = blockwise ? vi.fn_block : vi.fn_plain;
     if (vi.name == kPanel32Name) kfn = panel32_fn(panel32_bw(p, blockwise), outq != nullptr, panel32_affine(p));
     if (!kfn) return LOKA_ERR_UNSUPPORTED;
-    if (set_lds(kfn, vi.lds) != LOKA_OK) return LOKA_ERR_HIP;
+    int per_cu = 0;
+    if (prepare_fn(dev, kfn, vi.threads, vi.lds, &per_cu) != LOKA_OK) return LOKA_ERR_HIP;
     dim3 grid(static_cast<unsigned>(static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.batch));
     if (vi.epi == EPI_PANEL_SYNC) {
         // persistent grid: a multiple of tiles_n workgroups, all resident at once (one per CU)
-        int cus = 0, per_cu = 0;
-        if (resident_capacity(kfn, vi.threads, vi.lds, &cus, &per_cu) != LOKA_OK)
-            return LOKA_ERR_HIP;
         const int64_t slots = static_cast<int64_t>(cus) * (per_cu > 0 ? 1 : 0);
         int64_t g = (slots / p.tiles_n) * p.tiles_n;
         if (g <= 0) return LOKA_ERR_UNSUPPORTED;
         if (g > grid.x) g = (static_cast<int64_t>(grid.x) / p.tiles_n) * p.tiles_n;   // fewer tiles than slots
         grid = dim3(static_cast<unsigned>(g));
         if (panel_exchanges(d, vi, outq != nullptr)) {
-            const int64_t panels = static_cast<int64_t>(p.batch) * p.tiles_m * (vi.name == kPanel32Name ? 2 : 1);
-            const size_t ctr_bytes = (static_cast<size_t>(panels) * 4 + 255) & ~size_t(255);
+            const size_t flag_bytes = panel_flag_bytes(d, vi);
             uint8_t* ws = static_cast<uint8_t*>(workspace);
-            p.error_flag = reinterpret_cast<unsigned*>(ws);
-            p.counters = reinterpret_cast<unsigned*>(ws + 256);
-            p.part = reinterpret_cast<float*>(ws + 256 + ctr_bytes);
+            p.header = reinterpret_cast<unsigned long long*>(ws);
+            p.flags = reinterpret_cast<unsigned long long*>(ws + 256);
+            p.part = reinterpret_cast<float*>(ws + 256 + flag_bytes);
             p.spin_limit = kSpinLimit;
-            p.arrivals = static_cast<unsigned>(p.tiles_n);
-            // Test hook for the error path: LOKA_SPIN_LIMIT overrides the number of polls, and a limit of 0 also makes
-            // the workgroups wait for one arrival more than there are tiles, so that every wait runs out after its
-            // first poll whatever the timing (the kernel still ends; the output of that launch is invalid).
-            if (const char* e = std::getenv("LOKA_SPIN_LIMIT")) {
-                p.spin_limit = static_cast<unsigned>(std::strtoul(e, nullptr, 10));
-                if (p.spin_limit == 0) p.arrivals += 1;
+            p.nonce = fresh_nonce();
+            p.expect = p.nonce;
+            // Test hook for the error path (loka_test_set_spin_limit): a limit of 0 polls also makes the workgroups
+            // look for a value nobody writes, so that every wait runs out after its first poll whatever the timing
+            // (the kernel still ends; the rows of that launch leave as NaN).
+            const long long ov = g_spin_override.load(std::memory_order_relaxed);
+            if (ov >= 0) {
+                p.spin_limit = static_cast<unsigned>(ov);
+                if (ov == 0) p.expect = p.nonce + 2;
             }
-            const int64_t words = (256 + static_cast<int64_t>(ctr_bytes)) / 4;
-            zero_u32_kernel<<<dim3(static_cast<unsigned>((words + 255) / 256)), 256, 0, s>>>(
-                reinterpret_cast<uint32_t*>(ws), words);
+            // Arrival words are compared with the launch's nonce, which is new for every launch: nothing to clear.
+            // A launch that is being recorded into a graph will be replayed with the SAME nonce, so there the header
+            // and the arrival words are cleared by a kernel in front of it (part of the recording).
+            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing(s, &cap) != hipSuccess) return LOKA_ERR_HIP;
+            if (cap != hipStreamCaptureStatusNone) {
+                const int64_t words = (256 + static_cast<int64_t>(flag_bytes)) / 4;
+                zero_u32_kernel<<<dim3(static_cast<unsigned>((words + 255) / 256)), 256, 0, s>>>(
+                    reinterpret_cast<uint32_t*>(ws), words);
+            }
         }
     }
     vi.launch(p, blockwise, grid, s);
@@ -1009,11 +1037,13 @@ size_t bf16_gemm_workspace_bytes(const loka_gemm_desc* d) {
     return static_cast<size_t>(nw) * d->K * d->N * 2;
 }
 
+// weights_ready: the workspace already holds the transposed weights of an earlier call with the same w (the
+// dispatcher times the reference with its weights prepared once, like the FP8 candidates' quantized weights)
 loka_status bf16_gemm_launch(const loka_gemm_desc* d, const void* x, const void* w, float* yref, void* workspace,
-                             hipStream_t s) {
+                             hipStream_t s, bool weights_ready) {
     uint16_t* wt = static_cast<uint16_t*>(workspace);
     const int64_t nw = d->strideW ? d->batch : 1;
-    for (int64_t g = 0; g < nw; ++g) {
+    for (int64_t g = 0; g < nw && !weights_ready; ++g) {
         dim3 grid(static_cast<unsigned>((d->N + 63) / 64), static_cast<unsigned>((d->K + 63) / 64));
         transpose_bf16_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(w) + g * d->strideW,
                                                    static_cast<int>(d->K), static_cast<int>(d->N), wt + g * d->K * d->N);
@@ -1030,7 +1060,9 @@ loka_status bf16_gemm_launch(const loka_gemm_desc* d, const void* x, const void*
     p.tiles_n = static_cast<int>((d->N + BN - 1) / BN);
     auto fn = &gemm_kernel<BM, BN, 1, 2, 2, true, false, EPI_PARTIAL_STATS>;
     constexpr size_t lds = 2 * (BM * 128 + BN * 128);
-    if (set_lds(reinterpret_cast<const void*>(fn), lds) != LOKA_OK) return LOKA_ERR_HIP;
+    int dev = 0, cus = 0;
+    if (device_cus(&dev, &cus) != LOKA_OK || prepare_fn(dev, reinterpret_cast<const void*>(fn), 256, lds, nullptr) != LOKA_OK)
+        return LOKA_ERR_HIP;
     const dim3 grid(static_cast<unsigned>(static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.batch));
     fn<<<grid, 256, lds, s>>>(p);
     return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;

@@ -56,6 +56,9 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         const int G = gridDim.x;
         tile_first = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
         tile_stride = G;
+        // the workspace remembers which launch used it last (a wait that runs out records the same value beside it)
+        if (p.header && blockIdx.x == 0 && threadIdx.x == 0)
+            __hip_atomic_store(p.header, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // loop-invariant lane offsets
     const int ld_row = lane >> 3, ld_pos = lane & 7;
@@ -70,7 +73,6 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     const int wkey = ((wrow >> 1) & 1) | (((wrow >> 2) & 1) << 1) | (((wrow >> 4) & 1) << 2);
     const int w_off0 = wrow * 128 + (((2 * hk) ^ wkey) << 4), w_off1 = wrow * 128 + (((2 * hk + 1) ^ wkey) << 4);
     const int ksteps = p.KB / 128;
-    const float inv_n = 1.0f / static_cast<float>(p.N);
 
     // buffer descriptors of the tile whose operands are being streamed (bounds = the rows that exist: rows
     // past the end of X or W read as zeros)
@@ -276,7 +278,6 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     // trip through L2 under load is ~1 us for 64 KB, ~0.6 us for 32 KB; a step is ~1.2 us).
     // All of a wave's loads return in issue order, so "vmcnt(4)" = everything but the newest entry's share.
     auto mod5 = [](int v) { return v >= 5 ? v - 5 : v; };
-    LOKA_STAMP(0);
     // entry e of a tile lives in slot (e + 1) % 5: slot 0, which the epilogue uses as scratch, is the last to fill
     if (!prefetched) {
         issue_x(1, 0);
@@ -328,6 +329,9 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     const int lane = lane_o, l32 = lane & 31, hk = lane >> 5;
     const unsigned tid = static_cast<unsigned>(tid_o);
     (void)lane;
+    int n_o = p.N;                                          // (1 / N likewise: recomputed per tile, not kept in a register)
+    asm volatile("; row length" : "+s"(n_o));
+    const float inv_n = 1.0f / static_cast<float>(n_o);
     // scales of this lane's rows and columns: requested before the last eight MFMAs so that the round trip
     // through L2 is covered (the fragment registers of the other K half are free by now)
     // lane: rows m(mi) = m0 + 128 wave_m + 32 mi + l32; columns ncol(ni) + [0, 16), ncol = n0 + 64 wave_n + 32 ni + 16 hk
@@ -360,7 +364,6 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     for (int mi = 0; mi < MI; ++mi) mfma_row(mi, 1);
 #undef LOKA_HALF_STEP
     __syncthreads();                                        // LDS is free for the epilogue
-    LOKA_STAMP(1);
     // the next tile's first four ring entries stream in while this tile's statistics are exchanged
     prefetched = tile + tile_stride < total_tiles;
     if (prefetched) {
@@ -496,11 +499,13 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             const unsigned a = pk & 0x7FFFu, b = (pk >> 16) & 0x7FFFu;
             float scale, inv;
             group_scale(__uint_as_float((a > b ? a : b) << 16), scale, inv);
+            if (!(rstd == rstd)) scale = rstd;                    // poisoned row: the scale says so
             finq[r] = inv;
             if (tn == 0 && m0 + r < p.M) p.outs[static_cast<int64_t>(g) * p.M + m0 + r] = scale;
         };
-        LOKA_STAMP(2);
         const bool blocknorm = p.norm == LOKA_NORM_BLOCKNORM;   // groups of 256 columns = this tile: nothing to exchange
+        bool arrived = true;                                    // false: a wait for the panel's other tiles ran out
+        int* const lds_word = reinterpret_cast<int*>(smem + 16000);   // (free between finq and red2)
         if (EPI == EPI_PANEL_SYNC && !blocknorm && p.tiles_n > 1) {
             // publish (mean, M2) of this tile per row, signal, wait for the panel's other tiles, merge all tiles
             const int panel = g * p.tiles_m + tm;
@@ -520,24 +525,8 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                     __hip_atomic_store(dst + mm_off, static_cast<unsigned long long>(__float_as_uint(t_lo)) |
                                                          (static_cast<unsigned long long>(__float_as_uint(t_hi)) << 32),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // the stores have completed before the barrier
             }
-            __syncthreads();
-            LOKA_STAMP(3);
-            if (tid == 0) {
-                unsigned* ctr = p.counters + panel;
-                __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                unsigned spins = 0;
-                while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.arrivals) {
-                    __builtin_amdgcn_s_sleep(2);          // (measured: 16 costs 2 % of the kernel at 32768 x 4096 x 4096, 0 gains nothing more)
-                    if (++spins > p.spin_limit) {
-                        __hip_atomic_store(p.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        break;
-                    }
-                }
-            }
-            __syncthreads();
-            LOKA_STAMP(4);
+            arrived = panel_publish_and_wait(p, p.flags + static_cast<int64_t>(panel) * p.tiles_n, tn, p.tiles_n, lds_word);
             // two threads per row, each folds a contiguous half of the row's tiles in order (device-coherent
             // 8-byte loads), symmetric merge of the halves: identical bits in every workgroup of the panel
             {
@@ -588,7 +577,10 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                     hi = __builtin_fmaxf(hi, wave_shfl_xor(hi, 1));
                 }
                 if (sub == 0) {
-                    const float2 f = make_float2(ln ? mean : 0.f, __builtin_amdgcn_rsqf(m2 * inv_n + p.eps));
+                    // (a wait that ran out: the statistics are not to be trusted; the tile's rows leave as NaN, their
+                    // FP8 row scale as NaN)
+                    const float2 f = arrived ? make_float2(ln ? mean : 0.f, __builtin_amdgcn_rsqf(m2 * inv_n + p.eps))
+                                             : make_float2(__builtin_nanf(""), __builtin_nanf(""));
                     fin[r] = f;
                     if (FP8OUT && !affine_q) row_scale(r, f.x, f.y, lo, hi);
                 }
@@ -613,7 +605,6 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     float nmr_r[MI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) nmr_r[mi] = -mean_r[mi] * rstd_r[mi];
-    LOKA_STAMP(5);
 
     // ---- normalize, affine, bf16 store.  A lane holds 16 consecutive columns of ONE row per 32 x 32 sub-tile;
     // stored from there, an instruction would touch 32 rows with 32 bytes each.  Each wave instead passes the
@@ -694,9 +685,11 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
 #pragma unroll
                 for (int w = 0; w < 4; ++w) { const unsigned a = amw[tid * 4 + w]; t_am = t_am > a ? t_am : a; }
             }
+            bool amax_ok = true;
             auto row_scale_am = [&](int r, unsigned a) __attribute__((always_inline)) {
                 float scale, inv;
                 group_scale(__uint_as_float(a << 16), scale, inv);
+                if (!amax_ok) scale = __builtin_nanf("");           // the wait for the other tiles' amax ran out
                 finq[r] = inv;
                 if (tn == 0 && m0 + r < p.M) p.outs[static_cast<int64_t>(g) * p.M + m0 + r] = scale;
             };
@@ -708,22 +701,12 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
                 if (tid < BM) {
                     __hip_atomic_store(pam + tn * BM + tid, static_cast<unsigned long long>(t_am), __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                 }
-                __syncthreads();
-                if (tid == 0) {
-                    unsigned* ctr = p.counters + static_cast<int64_t>(p.batch) * p.tiles_m + panel;   // the second counter of the panel
-                    __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    unsigned spins = 0;
-                    while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.arrivals) {
-                        __builtin_amdgcn_s_sleep(2);
-                        if (++spins > p.spin_limit) {
-                            __hip_atomic_store(p.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            break;
-                        }
-                    }
-                }
-                __syncthreads();
+                // (the second set of arrival words of the panel)
+                const bool arrived2 = panel_publish_and_wait(
+                    p, p.flags + (static_cast<int64_t>(p.batch) * p.tiles_m + panel) * p.tiles_n, tn, p.tiles_n,
+                    reinterpret_cast<int*>(smem + 16000));
+                amax_ok = arrived2;
                 {
                     const int r = static_cast<int>(tid) >> 1, sub = static_cast<int>(tid) & 1;
                     const int TH = (p.tiles_n + 1) >> 1;
@@ -820,18 +803,11 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
         }
     }
     }
-    LOKA_STAMP(6);
     }
     lds_barrier();              // the epilogue's scratch (slot 0) is read: the next tile may load into it.  The
                                 // stores stay in flight.
   }
 }
-
-#ifdef LOKA_DEBUG_TIMES
-extern "C" int loka_debug_read_times32(unsigned long long* host, int n) {
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(loka_dbg_times), sizeof(unsigned long long) * n) == hipSuccess ? 0 : 1;
-}
-#endif
 
 constexpr size_t kPanel32Lds = 5 * 256 * 128;   // the ring; the epilogue's scratch aliases it
 

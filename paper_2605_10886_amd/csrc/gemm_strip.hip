@@ -23,11 +23,6 @@ namespace loka {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-#ifndef STRIP_NT
-#define STRIP_STORE(v, ptr) (*(ptr) = (v))
-#else
-#define STRIP_STORE(v, ptr) __builtin_nontemporal_store((v), (ptr))
-#endif
 
 template <int NB, int KS, int NPH>
 struct StripCfg {
@@ -333,7 +328,7 @@ __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p
                         const u32x4 pk = *reinterpret_cast<const u32x4*>(tbuf + r * 64 + ((t_c ^ ((r >> 2) & 3)) << 4));
                         const int ccol = nb * 32 + t_c * 8;
                         if ((s - s_base) * 32 + r < p.M && ccol < p.N)
-                            STRIP_STORE(pk, reinterpret_cast<u32x4*>(obase + static_cast<int64_t>(r) * p.N + ccol));
+                            *reinterpret_cast<u32x4*>(obase + static_cast<int64_t>(r) * p.N + ccol) = pk;
                     }
                     after_block(nb);
                 }
@@ -405,7 +400,7 @@ __global__ __launch_bounds__(NWV * 64) void gemm_strip_kernel(const GemmParams p
                         const u32x4 ck = *reinterpret_cast<const u32x4*>(tbuf + r * 64 + ((t_c ^ ((r >> 2) & 3)) << 4));
                         const int ccol = nbp * 64 + t_c * 16;
                         if ((s - s_base) * 32 + r < p.M && ccol < p.N)
-                            STRIP_STORE(ck, reinterpret_cast<u32x4*>(qbase + static_cast<int64_t>(r) * p.N + ccol));
+                            *reinterpret_cast<u32x4*>(qbase + static_cast<int64_t>(r) * p.N + ccol) = ck;
                     }
                     after_block(2 * nbp);
                     after_block(2 * nbp + 1);

@@ -263,10 +263,8 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         __syncthreads();                                                // scales / gamma / beta are in LDS
     };
 
-    { const int tile = b0; (void)tile; LOKA_STAMP(6); }
     int cur_g = b0 / blocks_per_problem;
     start_problem(cur_g, b0);
-    { const int tile = b0; (void)tile; LOKA_STAMP(7); }
 
     // Deferred stores (bf16 output from FP8 input): a finished block is not written out at its end by the four
     // storer waves, where the other four would wait at the next barrier while the store path takes its 64 bytes
@@ -337,7 +335,6 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         const int g = b / blocks_per_problem, m0 = (b - g * blocks_per_problem) * RB;
         const int tile = b;
         (void)tile;
-        LOKA_STAMP(0);
         bool fresh = b == b0;
         if (g != cur_g) {
             fresh = true;
@@ -363,7 +360,6 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
             if (loader) wait_landed(b);
             lds_barrier();
         }
-        LOKA_STAMP(1);
         if (BF16IN) {
             if (b + 2 < b1) fetch(b + 2);                                // in flight for a whole iteration
         } else if (loader && b + NBUF - 1 < b1) {
@@ -435,7 +431,6 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         if (DEFER && pending) mma_loop(std::true_type{}); else mma_loop(std::false_type{});
         if (DEFER) pending = false;                                     // the previous block is on its way
         __builtin_amdgcn_sched_barrier(0);
-        LOKA_STAMP(2);
 
         // ---- scales, row statistics (lane -> pair of lanes with the same row -> the 8 waves through LDS)
         const float* sxl = reinterpret_cast<const float*>(smem + C::OFF_SX + (b % NBUF) * 4 * SXL * 256);
@@ -509,7 +504,6 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) { mean_r[rt] = 0.f; rstd_r[rt] = 1.f; }
         if (p.norm != LOKA_NORM_NONE) {
-            LOKA_STAMP(3);
             lds_barrier();
             // The two lanes that hold a row (l and l ^ 32) fold four waves' entries each, in order, and merge their
             // halves symmetrically: identical bits on both, in every wave.  The folds are branch-free (an empty part
@@ -555,7 +549,6 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         } else if (DEFER) {
             lds_barrier();      // every wave has read its part of the previous block out of the staging buffer
         }
-        LOKA_STAMP(4);
 
         // normalized (+ affine, + activation) values of 8 consecutive columns of row tile rt, as packed bf16
         // (without gamma and beta the affine step is x * 1 + 0: skipped, and its table reads with it)
@@ -654,18 +647,11 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         // (deferred stores: this barrier is also the next block's "X has landed" barrier)
         if (DEFER && loader && b + 1 < b1 && (b + 1) / blocks_per_problem == g) wait_landed(b + 1);
         lds_barrier();
-        LOKA_STAMP(5);
         // ---- the block is written out: now, or between the MFMAs of the next block
         pending = true; pend_g = g; pend_m0 = m0;
         if (!DEFER || b + 1 == b1) flush_pending();
     }
 }
-
-#ifdef LOKA_DEBUG_TIMES
-extern "C" int loka_debug_read_times_wreg(unsigned long long* host, int n) {
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(loka_dbg_times), sizeof(unsigned long long) * n) == hipSuccess ? 0 : 1;
-}
-#endif
 
 // ---------------------------------------------------------------------------------------------- host side
 namespace {

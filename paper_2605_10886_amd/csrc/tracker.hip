@@ -33,7 +33,9 @@ constexpr int TRK_MS = 64;                      // batch rows per pipeline stage
 constexpr int TRK_TILEB = TRK_MS * TRK_T * 2;   // one operand tile of a stage (32 KB)
 constexpr int TRK_STAGEB = 2 * TRK_TILEB;       // i tile, then j tile
 constexpr size_t TRK_LDS = 2 * TRK_STAGEB + 2 * TRK_T * sizeof(double);
-constexpr int TRK_CUS = 256;                    // workgroups resident at once (one per CU)
+constexpr int TRK_PLAN_SLOTS = 256;             // cost model only: workgroups assumed in flight per round (the CU count of an
+                                                // MI355X).  It steers the number of row splits (and with it the workspace
+                                                // size, which must not depend on the device); results do not depend on it
 
 // Work decomposition: workgroup = (tile pair ti <= tj, one of S equal row ranges of the batch).  All
 // workgroups in flight walk their rows at the same pace, so the workgroups of an XCD that share a column
@@ -57,7 +59,7 @@ TrackerPlan tracker_plan(int64_t B, int64_t K) {
     int64_t best_s = 1;
     double best = 1e300;
     for (int64_t sp = 1; sp <= max_s; ++sp) {
-        const int64_t rounds = (static_cast<int64_t>(pl.pairs) * sp + TRK_CUS - 1) / TRK_CUS;
+        const int64_t rounds = (static_cast<int64_t>(pl.pairs) * sp + TRK_PLAN_SLOTS - 1) / TRK_PLAN_SLOTS;
         const double cost = static_cast<double>(rounds) * ((steps + sp - 1) / sp + 3) + 0.1 * pl.pairs * static_cast<double>(sp);
         if (cost < best) { best = cost; best_s = sp; }
     }

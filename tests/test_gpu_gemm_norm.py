@@ -101,7 +101,10 @@ def test_c1_every_variant(orc, recipe, norm):
 
 
 @pytest.mark.parametrize("shape", [(200, 128, 48), (77, 256, 240), (333, 384, 512), (130, 128, 1008), (64, 512, 2048),
-                                   (100, 512, 256), (90, 1024, 112), (300, 1024, 240)])
+                                   (100, 512, 256), (90, 1024, 112), (300, 1024, 240),
+                                   # rows wider than a tile with 5 and 10 (ragged) tiles per row: the persistent grid is
+                                   # then not a multiple of 8 and a panel's workgroups sit on several XCDs
+                                   (700, 256, 1280), (520, 128, 2320)])
 def test_ragged_tiles_every_variant(orc, shape):
     # M not a multiple of any tile height, N not a multiple of the tile width (but of 16), several K steps
     M, K, N = shape
@@ -766,41 +769,79 @@ def test_bf16_reference_gemm_grouped(orc):
         assert rel_fro(y[g * M:(g + 1) * M], y_o) <= 1e-5
 
 
-def test_bounded_wait_is_reported(monkeypatch):
-    # the panel-synchronous variants wait for the other tiles of a row panel; a wait that runs out raises a flag
-    # and the kernel still ends.  Forced from the host: with a spin limit of zero polls (read at every launch) the
-    # launch also waits for one arrival more than the panel has tiles, so every wait runs out whatever the timing.
+def test_bounded_wait_is_reported():
+    # the panel-synchronous variants wait for the other tiles of a row panel; a wait that runs out marks the launch in
+    # the workspace, the tile's rows leave as NaN, and the kernel still ends.  Forced from the host: with a limit of
+    # zero polls the launch also looks for an arrival value nobody writes, so every wait runs out whatever the timing.
     M, K, N = 2048, 256, 2048
     x, wt = synth.normal(M, K, 3).to(DEV), synth.weight(K, N, 4).to(DEV)
     xq, sx = B.loka_quantize(x, B.SCALE_ROW)
     wq, sw = B.loka_quantize(wt, B.SCALE_COL, transpose_out=True)
+    for vname in ("panel32_256x256", "panel256x256w8"):
+        desc = B.make_desc(M, N, K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, 1e-5, variant=B.variant_id(vname))
+        # uninitialised workspace contents must not matter: fill it with a pattern first
+        ws = torch.full((B.lib().loka_fp8_gemm_norm_workspace(ctypes.byref(desc)),), 0xA5, dtype=torch.uint8, device=DEV)
+        good, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, workspace=ws)
+        assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
+        assert not bool(torch.isnan(good.float()).any())
+        try:
+            B.loka_test_set_spin_limit(0)
+            bad, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, workspace=ws)
+            assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_ERR_TIMEOUT
+            assert bool(torch.isnan(bad.float()).all())              # nobody can take that launch's output for a result
+        finally:
+            B.loka_test_set_spin_limit(-1)
+        again, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, workspace=ws)
+        assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
+        assert torch.equal(good, again)
+        if vname == "panel32_256x256":
+            good32 = good
     desc = B.make_desc(M, N, K, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, 1e-5, variant=B.variant_id("panel32_256x256"))
-    ws = torch.empty(B.lib().loka_fp8_gemm_norm_workspace(ctypes.byref(desc)), dtype=torch.uint8, device=DEV)
-    good, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, workspace=ws)
-    assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
-    monkeypatch.setenv("LOKA_SPIN_LIMIT", "0")
-    B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, workspace=ws)
-    assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_ERR_TIMEOUT
-    monkeypatch.delenv("LOKA_SPIN_LIMIT")
-    again, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw, workspace=ws)
-    assert B.loka_fp8_gemm_norm_check(desc, ws) == B.LOKA_OK
-    assert torch.equal(good, again)
     # the FP8-output form of the same kernel reports through its own workspace
-    ws_f = torch.empty(B.lib().loka_fp8_gemm_norm_fp8out_workspace(ctypes.byref(desc)), dtype=torch.uint8, device=DEV)
-    monkeypatch.setenv("LOKA_SPIN_LIMIT", "0")
-    B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws_f)
-    assert B.loka_fp8_gemm_norm_check(desc, ws_f) == B.LOKA_ERR_TIMEOUT
+    ws_f = torch.full((B.lib().loka_fp8_gemm_norm_fp8out_workspace(ctypes.byref(desc)),), 0x5A, dtype=torch.uint8, device=DEV)
     gamma, beta = (t.to(DEV) for t in synth.affine(N, seed=8))
-    B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, gamma, beta, workspace=ws_f)      # two bounded waits per tile
-    assert B.loka_fp8_gemm_norm_check(desc, ws_f) == B.LOKA_ERR_TIMEOUT
-    monkeypatch.delenv("LOKA_SPIN_LIMIT")
+    try:
+        B.loka_test_set_spin_limit(0)
+        _, so_bad, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws_f)
+        assert B.loka_fp8_gemm_norm_check(desc, ws_f) == B.LOKA_ERR_TIMEOUT
+        assert bool(torch.isnan(so_bad).all())                       # FP8 output: the row scales say so
+        _, so_bad2, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, gamma, beta, workspace=ws_f)   # two bounded waits per tile
+        assert B.loka_fp8_gemm_norm_check(desc, ws_f) == B.LOKA_ERR_TIMEOUT
+        assert bool(torch.isnan(so_bad2).all())
+    finally:
+        B.loka_test_set_spin_limit(-1)
     oq, so, _ = B.loka_fp8_gemm_norm_fp8out(desc, xq, sx, wq, sw, workspace=ws_f)
     assert B.loka_fp8_gemm_norm_check(desc, ws_f) == B.LOKA_OK
-    q_ref, s_ref = B.loka_quantize(good, B.SCALE_ROW)
+    q_ref, s_ref = B.loka_quantize(good32, B.SCALE_ROW)
     assert torch.equal(oq, q_ref) and torch.equal(so, s_ref)
+    # a workspace that no launch has used yet has nothing to report
+    fresh = torch.zeros_like(ws_f)
+    assert B.loka_fp8_gemm_norm_check(desc, fresh) == B.LOKA_OK
     # variants without a cross-workgroup wait have nothing to report
     row = B.make_desc(256, 128, 128, variant=B.variant_id("row64x128"))
     assert B.loka_fp8_gemm_norm_check(row, None) == B.LOKA_OK
+
+
+def test_dispatch_drops_a_candidate_whose_wait_ran_out():
+    # the profiler must not time or probe a launch that produced nothing: with every wait forced to run out, the
+    # panel-synchronous candidates disappear from the table and the choice falls on a kernel without such a wait
+    M, K, N = 1024, 256, 1024
+    x, wt = synth.normal(M, K, 5).to(DEV), synth.weight(K, N, 6).to(DEV)
+    shape = B.make_desc(M, N, K, 1, norm=B.NORM_LAYERNORM)
+    B.loka_dispatch_clear()
+    st, ch, table = B.loka_dispatch(shape, x, wt, 5e-2)
+    names = {r["variant_name"] for r in table}
+    assert st == B.LOKA_OK and "panel32_256x256" in names
+    B.loka_dispatch_clear()
+    try:
+        B.loka_test_set_spin_limit(0)
+        st2, ch2, table2 = B.loka_dispatch(shape, x, wt, 5e-2)
+    finally:
+        B.loka_test_set_spin_limit(-1)
+        B.loka_dispatch_clear()
+    names2 = {r["variant_name"] for r in table2}
+    assert st2 == B.LOKA_OK and not (names2 & {"panel32_256x256", "panel256x256w8"}) and names2
+    assert ch2["variant_name"] in names2
 
 
 # ----------------------------------------------------------------------------- quantization fused into the layer
