@@ -167,6 +167,24 @@ loka_status loka_fp8_gemm_norm(const loka_gemm_desc* desc, const uint8_t* xq, co
  * without touching the GPU.  Not needed on the hot path; meant for health checks and tests. */
 loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, serving loops that must not call the
+ * allocator, harnesses that forbid it): loka_fp8_gemm_norm with its workspace taken from a device array the LIBRARY
+ * owns (16 MiB per GPU the library runs on, held until the process ends) instead of from the caller.  Same arguments
+ * otherwise, same kernels, same bits in out_bf16 / y_fp32.  The call allocates nothing and calls no allocating
+ * routine; the first call on a device asks the runtime for the array's address on that device (set-up).
+ *   - LOKA_ERR_WORKSPACE when the variant chosen for `desc` needs more scratch than
+ *     LOKA_STATIC_SCRATCH_BYTES (loka_fp8_gemm_norm_workspace(desc) tells how much): use
+ *     loka_fp8_gemm_norm with a caller-owned workspace for those.
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (different streams, different
+ *     threads) race on it and must be serialized by the caller.  Nothing in the array has to be cleared between
+ *     calls (the kernels recognize stale contents), and no call relies on what an earlier one left there.
+ *   - A bounded wait that runs out (see loka_fp8_gemm_norm_check; there is no workspace to hand to it here) shows
+ *     in the output itself: the affected rows are NaN. */
+#define LOKA_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+loka_status loka_fp8_gemm_norm_static(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
+                                      const float* sw, const void* gamma_bf16, const void* beta_bf16, void* out_bf16,
+                                      float* y_fp32, void* hip_stream);
+
 /* Test aid for the error path of those bounded waits: from now on every such wait polls at most `polls` times
  * (process-wide; a negative value restores the library's limit).  With polls == 0 the waits also look for a value
  * no workgroup writes, so every one of them runs out after its first poll whatever the timing: the kernels still

@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libloka.so")
 
 LOKA_OK = 0
+STATIC_SCRATCH_BYTES = 16 << 20       # LOKA_STATIC_SCRATCH_BYTES of include/loka.h
 LOKA_ERR_NULL, LOKA_ERR_SHAPE, LOKA_ERR_ALIGN, LOKA_ERR_UNSUPPORTED = 1, 2, 3, 4
 LOKA_ERR_WORKSPACE, LOKA_ERR_HIP, LOKA_ERR_NO_CANDIDATE, LOKA_ERR_TIMEOUT = 5, 6, 7, 8
 SCALE_TENSOR, SCALE_ROW, SCALE_COL, SCALE_BLOCK_1x128, SCALE_BLOCK_128x128, SCALE_BLOCK_1x128_POW2, SCALE_BLOCK_128x128_POW2 = range(7)
@@ -75,6 +76,8 @@ _SIGNATURES = [
     ("loka_fp8_linear_norm", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                      c_void_p, c_void_p]),
     ("loka_fp8_gemm_norm_check", c_int, [POINTER(GemmDesc), c_void_p, c_size_t, c_void_p]),
+    ("loka_fp8_gemm_norm_static", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                          c_void_p, c_void_p, c_void_p]),
     ("loka_test_set_spin_limit", None, [c_int64]),
     ("loka_fp8_gemm_norm_fp8out_workspace", c_size_t, [POINTER(GemmDesc)]),
     ("loka_fp8_gemm_norm_fp8out", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -226,6 +229,19 @@ def loka_fp8_gemm_norm_check(desc: GemmDesc, workspace) -> int:
     LOKA_ERR_TIMEOUT."""
     return int(lib().loka_fp8_gemm_norm_check(byref(desc), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                               _stream()))
+
+
+def loka_fp8_gemm_norm_static(desc: GemmDesc, xq, sx, wq, sw, gamma=None, beta=None, want_y: bool = False, out=None, y=None):
+    """loka_fp8_gemm_norm with the library's own scratch (the call allocates nothing; the output tensors here are made
+    by the caller of this helper, before the call).  Returns (O bf16, Y fp32 or None)."""
+    rows = desc.batch * desc.M
+    if out is None:
+        out = torch.empty((rows, desc.N), dtype=torch.bfloat16, device=xq.device)
+    if want_y and y is None:
+        y = torch.empty((rows, desc.N), dtype=torch.float32, device=xq.device)
+    _check(lib().loka_fp8_gemm_norm_static(byref(desc), _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), _ptr(gamma), _ptr(beta),
+                                           _ptr(out), _ptr(y), _stream()), "loka_fp8_gemm_norm_static")
+    return out, y
 
 
 def loka_test_set_spin_limit(polls: int) -> None:

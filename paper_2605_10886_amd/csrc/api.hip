@@ -4,6 +4,7 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 namespace loka {
 // quantize.hip
@@ -152,6 +153,55 @@ const char* loka_variant_name(int variant) { return variant_name(variant); }
 int loka_variant_supports(const loka_gemm_desc* desc, int variant) {
     if (validate_desc(desc, true) != LOKA_OK) return 0;
     return variant_supports(desc, variant) ? 1 : 0;
+}
+
+// ---- loka_fp8_gemm_norm_static: the scratch of loka_fp8_gemm_norm in library-owned device memory.
+// `static_scratch` is a host-side stand-in for a device array: its device address is asked from the runtime once per
+// device (with that device current) and only that address is ever handed to kernels or copies.
+constexpr size_t kStaticScratchBytes = LOKA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char static_scratch[kStaticScratchBytes];
+namespace {
+constexpr int kScratchMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kScratchMaxDevices] = {};
+}  // namespace
+
+// Device address of the current device's copy of the array (set-up on the first call per device).
+static loka_status static_scratch_address(void** ptr) {
+    int dev = 0;
+    LOKA_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kScratchMaxDevices) return LOKA_ERR_HIP;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        LOKA_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch)));
+        if (!p) return LOKA_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return LOKA_OK;
+}
+
+loka_status loka_fp8_gemm_norm_static(const loka_gemm_desc* desc, const uint8_t* xq, const float* sx, const uint8_t* wq,
+                                      const float* sw, const void* gamma_bf16, const void* beta_bf16, void* out_bf16,
+                                      float* y_fp32, void* hip_stream) {
+    if (!desc || !xq || !sx || !wq || !sw || !out_bf16) return LOKA_ERR_NULL;
+    const loka_status st = validate_desc(desc, true);
+    if (st != LOKA_OK) return st;
+    if (!aligned16(xq) || !aligned16(wq) || !aligned16(sx) || !aligned16(sw) || !aligned16(out_bf16) ||
+        !aligned16(y_fp32) || !aligned16(gamma_bf16) || !aligned16(beta_bf16))
+        return LOKA_ERR_ALIGN;
+    const int v = resolve_variant(desc);
+    if (v < 0) return LOKA_ERR_UNSUPPORTED;
+    const size_t need = variant_workspace(desc, v);
+    if (need > kStaticScratchBytes) return LOKA_ERR_WORKSPACE;      // beyond the array: use loka_fp8_gemm_norm with a workspace
+    void* ws = nullptr;
+    if (need) {
+        const loka_status sa = static_scratch_address(&ws);
+        if (sa != LOKA_OK) return sa;
+    }
+    return fp8_gemm_norm_launch(desc, v, xq, sx, wq, sw, gamma_bf16, beta_bf16, out_bf16, y_fp32, nullptr, nullptr, ws,
+                                static_cast<hipStream_t>(hip_stream));
 }
 
 size_t loka_fp8_gemm_norm_workspace(const loka_gemm_desc* desc) {
