@@ -174,12 +174,11 @@ def run_pair(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # Defaults: after an idle period the first launches of a matrix-pipe-bound kernel run at boost clocks, the next
-    # twenty or so well below the sustained rate (C5, per-launch durations in a kernel trace: 482, 485, 523, 555, 613,
-    # 612, ... back to 480-495 us after ~25 launches = 15 ms); 40 warm-up steps put the timed region in the sustained state.
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3a", "C3b", "C3pair", "C4", "C5", "C5pair"])
+    ap.add_argument("--settle-ms", type=float, default=60.0,
+                    help="untimed settle phase before the warm-up steps: the step is repeated for at least this long")
     ap.add_argument("--budget", type=float, default=5e-2, help="rel-Frobenius budget the timed variant must meet")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-library", action="store_true", help="skip the vendor-library yardstick leg")
@@ -296,6 +295,19 @@ def main():
             gemm_norm()
         it[0] += 1
 
+    # Untimed settle phase, disclosed as config.settle_ms: after an idle period the first launches of a matrix-pipe-bound
+    # kernel run at boost clocks and the next twenty or so well below the sustained rate (C5, per-launch durations in a
+    # kernel trace: 482, 485, 523, 555, 613, 612, ... back to 480-495 us after ~25 launches = 15 ms).  The step is run
+    # for at least args.settle_ms of wall time before the W warm-up steps and the K timed steps the flags ask for, so
+    # that those are taken in the sustained state whatever W is.
+    settle_t0 = time.perf_counter()
+    settle_steps = 0
+    while (time.perf_counter() - settle_t0) * 1e3 < args.settle_ms:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
+        settle_steps += 8
+    settle_ms = (time.perf_counter() - settle_t0) * 1e3
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -355,6 +367,17 @@ def main():
 
     roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, B.loka_variant_name(variant)))
     roofline["algorithmic_bytes"] = gemm_bytes
+    # the same rate against what this machine delivers for the bounding resource right now (register-only FP8 matrix
+    # instructions / a plain copy through HBM; loka_machine_ceiling), measured in the sustained state
+    ceil_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    if roofline["bound"] == "mfma":
+        ceiling = B.loka_machine_ceiling(0, 60.0, ceil_buf)
+        roofline["measured_ceiling"] = {"what": "FP8 32x32x64 matrix instructions from registers, all CUs", "value": ceiling, "unit": "TFLOP/s"}
+    else:
+        ceiling = B.loka_machine_ceiling(2, 30.0, ceil_buf)
+        roofline["measured_ceiling"] = {"what": "plain copy, 512 MiB read + 512 MiB written", "value": ceiling, "unit": "GB/s"}
+    roofline["frac_of_measured_ceiling"] = roofline["achieved"] / ceiling
+    del ceil_buf
 
     # ---- probe leg (offline in the method): Y store, BF16 reference GEMM, error statistics
     y = torch.empty(rows, N, dtype=torch.float32, device=dev)
@@ -443,7 +466,7 @@ def main():
                             if args.fused else "quantize X + FP8 GEMM with fused scales and row norm (bf16 out)"),
                    "recipe": RECIPE_NAMES.get((xm, wm), f"{xm}/{wm}"), "variant": B.loka_variant_name(variant),
                    "flops_counted": "2*M*K*N of the FP8 GEMM", "pct_fp8_peak": 100 * value / FP8_PEAK_TFLOPS,
-                   "input_sets_rotated": n_sets,
+                   "input_sets_rotated": n_sets, "settle_ms": round(settle_ms, 1), "settle_steps_untimed": settle_steps,
                    "launch": f"HIP graph of {n_sets} steps, replayed" if args.graph else "eager",
                    "dispatch": "skipped (--no-dispatch)" if args.no_dispatch else
                                {"budget_1e-2": "no FP8 candidate (stay in BF16)" if st_strict != B.LOKA_OK else

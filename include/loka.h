@@ -104,6 +104,19 @@ loka_status loka_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_
  * the same device routine loka_quantize uses.  t and codes are device pointers. */
 loka_status loka_e4m3_from_f32(const float* t, uint8_t* codes, int64_t n, void* hip_stream);
 
+/* Measurement aid: what this machine delivers for the two resources the kernels are bound by, so that a rate can be
+ * reported against a MEASURED ceiling beside the datasheet peak (the sustained shader clock under matrix load is
+ * below the clock the datasheet assumes).
+ *   kind 0: FP8 matrix rate, TFLOP/s (register-resident 32x32x64 matrix instructions back to back on every CU)
+ *   kind 1: BF16 matrix rate, TFLOP/s (32x32x16)
+ *   kind 2: HBM copy rate, GB/s (bytes read + written), first half of `scratch` copied to the second
+ * Runs back-to-back launches for about `millis` milliseconds (clocks settle under load during the first tens of
+ * milliseconds) and returns the LAST launch's rate in *value_host (host memory).  scratch: device memory, 16-byte
+ * aligned, at least 4 MiB (kind 2: at least 64 MiB; use >= 1 GiB to stay clear of the last-level cache).
+ * SYNCHRONIZES; not a hot call. */
+loka_status loka_machine_ceiling(int kind, double millis, void* scratch, size_t scratch_bytes, double* value_host,
+                                 void* hip_stream);
+
 /* ---------------------------------------------------------------- FP8 GEMM + fused norm
  * O = norm( (Xq . Wq^T) scaled )  for `batch` independent problems of one shape
  * (Section 2.1: LRMs are dominated by many small GEMMs each followed by a

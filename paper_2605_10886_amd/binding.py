@@ -67,6 +67,7 @@ _SIGNATURES = [
     ("loka_quantize", c_int, [c_void_p, c_int64, c_int64, c_int64, c_int, c_int, c_void_p, c_void_p, c_void_p,
                               c_size_t, c_void_p]),
     ("loka_e4m3_from_f32", c_int, [c_void_p, c_void_p, c_int64, c_void_p]),
+    ("loka_machine_ceiling", c_int, [c_int, c_double, c_void_p, c_size_t, POINTER(c_double), c_void_p]),
     ("loka_variant_count", c_int, []),
     ("loka_variant_name", c_char_p, [c_int]),
     ("loka_variant_supports", c_int, [POINTER(GemmDesc), c_int]),
@@ -161,6 +162,14 @@ def loka_e4m3_from_f32(t: torch.Tensor) -> torch.Tensor:
     out = torch.empty(t.shape, dtype=torch.uint8, device=t.device)
     _check(lib().loka_e4m3_from_f32(_ptr(t), _ptr(out), t.numel(), _stream()), "loka_e4m3_from_f32")
     return out
+
+
+def loka_machine_ceiling(kind: int, millis: float, scratch: torch.Tensor) -> float:
+    """kind 0 / 1: FP8 / BF16 matrix rate in TFLOP/s; 2: copy rate in GB/s.  Synchronizes."""
+    v = c_double(0.0)
+    _check(lib().loka_machine_ceiling(kind, millis, _ptr(scratch), scratch.numel() * scratch.element_size(), byref(v),
+                                      _stream()), "loka_machine_ceiling")
+    return float(v.value)
 
 
 def loka_variant_count() -> int:

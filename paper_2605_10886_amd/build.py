@@ -18,7 +18,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libloka.so")
-SOURCES = ["api.hip", "quantize.hip", "gemm.hip", "gemm_panel32.hip", "gemm_wreg.hip", "gemm_strip.hip", "probe.hip", "dispatch.hip", "tracker.hip"]
+SOURCES = ["api.hip", "quantize.hip", "gemm.hip", "gemm_panel32.hip", "gemm_wreg.hip", "gemm_strip.hip", "probe.hip", "dispatch.hip", "tracker.hip", "ceiling.hip"]
 
 # -packed-fp32-ops off: packed fp32 VALU forms are kept out of the generated code.
 # No fast-math: divisions and square roots stay correctly rounded, no FMA contraction

@@ -28,6 +28,8 @@ loka_status fp8_linear_norm_launch(const loka_gemm_desc*, int, const void*, cons
                                    const void*, void*, float*, float*, hipStream_t);
 bool variant_has_wait_flag(const loka_gemm_desc*, int, bool fp8out = false);
 void test_set_spin_limit(long long);
+// ceiling.hip
+loka_status machine_ceiling(int, double, void*, size_t, double*, hipStream_t);
 size_t bf16_gemm_workspace_bytes(const loka_gemm_desc*);
 loka_status bf16_gemm_launch(const loka_gemm_desc*, const void*, const void*, float*, void*, hipStream_t, bool weights_ready = false);
 // probe.hip
@@ -288,6 +290,15 @@ loka_status loka_fp8_gemm_norm_check(const loka_gemm_desc* desc, const void* wor
 }
 
 void loka_test_set_spin_limit(int64_t polls) { test_set_spin_limit(polls); }
+
+loka_status loka_machine_ceiling(int kind, double millis, void* scratch, size_t scratch_bytes, double* value_host,
+                                 void* hip_stream) {
+    if (!scratch || !value_host) return LOKA_ERR_NULL;
+    if (kind < 0 || kind > 2 || !(millis > 0.0)) return LOKA_ERR_UNSUPPORTED;
+    if (!aligned16(scratch)) return LOKA_ERR_ALIGN;
+    if (scratch_bytes < (size_t(1) << 22) || (kind == 2 && scratch_bytes < (size_t(1) << 26))) return LOKA_ERR_WORKSPACE;
+    return machine_ceiling(kind, millis, scratch, scratch_bytes, value_host, static_cast<hipStream_t>(hip_stream));
+}
 
 size_t loka_fp8_gemm_norm_fp8out_workspace(const loka_gemm_desc* desc) {
     if (validate_desc(desc, true) != LOKA_OK) return 0;

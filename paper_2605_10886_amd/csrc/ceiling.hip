@@ -1,0 +1,96 @@
+// Measured ceilings of the machine the library runs on: what the FP8 / BF16 matrix pipes deliver from registers
+// alone, and what a plain copy moves through HBM.  A measurement aid (loka_machine_ceiling): the benchmark reports a
+// kernel's rate against these beside its rate against the datasheet peaks, because the sustained shader clock under
+// matrix load sits below the clock the datasheet figures assume.
+#include "common.h"
+
+namespace loka {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// One wave issues back-to-back MFMAs on 8 independent accumulator sets; operands never change (the result is
+// meaningless, only the issue rate matters).  The accumulators are written out so the loop cannot be removed.
+template <bool BF16>
+__global__ __launch_bounds__(512) void mfma_rate_kernel(float* sink, int iters) {
+    v16f acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+    const int t = static_cast<int>(threadIdx.x);
+    v8i a = v8i{t, t + 1, t + 2, t + 3, t + 4, t + 5, t + 6, t + 7};
+    v8i b = v8i{t * 3, t * 3 + 1, t * 3 + 2, t * 3 + 3, t * 3 + 4, t * 3 + 5, t * 3 + 6, t * 3 + 7};
+    a &= v8i{0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F};   // small finite codes
+    b &= v8i{0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (BF16) {
+                const v4i a4 = v4i{a[0], a[1], a[2], a[3]}, b4 = v4i{b[0], b[1], b[2], b[3]};
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a4), __builtin_bit_cast(v8bf, b4), acc[j], 0, 0, 0);
+            } else {
+                acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[j], 0, 0, 0, 0, 0, 0);
+            }
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += acc[j][i];
+    if (s == 123.456f) sink[blockIdx.x * blockDim.x + threadIdx.x] = s;     // (never true: keeps the loop)
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+int device_cu_count();
+
+// kind 0 / 1: FP8 / BF16 matrix rate in TFLOP/s over ~`millis` ms of back-to-back launches (the clock settles during
+// the first tens of milliseconds under load; the rate of the LAST launch is returned);  kind 2: copy rate in GB/s
+// (bytes read + written) of `scratch_bytes` / 2 bytes from the first half of `scratch` to the second.
+loka_status machine_ceiling(int kind, double millis, void* scratch, size_t scratch_bytes, double* value, hipStream_t s) {
+    const int cus = device_cu_count();
+    if (cus <= 0) return LOKA_ERR_HIP;
+    hipEvent_t e0, e1;
+    LOKA_HIP_TRY(hipEventCreate(&e0));
+    LOKA_HIP_TRY(hipEventCreate(&e1));
+    struct Guard { hipEvent_t a, b; ~Guard() { (void)hipEventDestroy(a); (void)hipEventDestroy(b); } } guard{e0, e1};
+    float ms = 0.f;
+    double total = 0.0, last = 0.0;
+    if (kind == 0 || kind == 1) {
+        const int iters = 4096;
+        // per launch: CUs x 8 waves x iters x 8 MFMAs of 2 * 32 * 32 * K flops
+        const double flops = static_cast<double>(cus) * 8 * iters * 8 * 2.0 * 32 * 32 * (kind == 0 ? 64 : 16);
+        while (total < millis) {
+            LOKA_HIP_TRY(hipEventRecord(e0, s));
+            if (kind == 0) mfma_rate_kernel<false><<<dim3(cus), 512, 0, s>>>(static_cast<float*>(scratch), iters);
+            else mfma_rate_kernel<true><<<dim3(cus), 512, 0, s>>>(static_cast<float*>(scratch), iters);
+            LOKA_HIP_TRY(hipEventRecord(e1, s));
+            LOKA_HIP_TRY(hipEventSynchronize(e1));
+            LOKA_HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+            total += ms;
+            last = flops / (ms * 1e-3) / 1e12;
+        }
+    } else {
+        const int64_t n16 = static_cast<int64_t>(scratch_bytes / 2 / 16);
+        const u32x4* src = static_cast<const u32x4*>(scratch);
+        u32x4* dst = static_cast<u32x4*>(scratch) + n16;
+        while (total < millis) {
+            LOKA_HIP_TRY(hipEventRecord(e0, s));
+            copy_kernel<<<dim3(cus * 8), 256, 0, s>>>(src, dst, n16);
+            LOKA_HIP_TRY(hipEventRecord(e1, s));
+            LOKA_HIP_TRY(hipEventSynchronize(e1));
+            LOKA_HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+            total += ms;
+            last = 2.0 * n16 * 16 / (ms * 1e-3) / 1e9;
+        }
+    }
+    *value = last;
+    return LOKA_OK;
+}
+
+}  // namespace loka

@@ -18,6 +18,7 @@ bool variant_supports(const loka_gemm_desc*, int);
 int variant_epilogue(int);
 bool variant_is_streaming(int);
 bool variant_is_strip(int);
+bool variant_is_exact(int);
 int variant_bn(int);
 int variant_bm(int);
 loka_status validate_desc(const loka_gemm_desc* d, bool fp8);
@@ -105,7 +106,8 @@ int default_variant(const loka_gemm_desc* d) {
     int best = -1;
     int64_t best_bn = 0, best_bm = 0;
     for (int v = 0; v < variant_count(); ++v) {
-        if (variant_epilogue(v) != 0 || variant_is_streaming(v) || variant_is_strip(v) || !variant_supports(d, v)) continue;
+        // (the exact-product forms of these tiles are never the static choice: they trade speed for accuracy)
+        if (variant_epilogue(v) != 0 || variant_is_streaming(v) || variant_is_strip(v) || variant_is_exact(v) || !variant_supports(d, v)) continue;
         const int64_t bn = variant_bn(v), bm = variant_bm(v);
         const int64_t tiles = ((d->M + bm - 1) / bm) * d->batch;
         bool better;

@@ -100,13 +100,20 @@ def model_rows(n_rows: int, N: int, K: int, budget: float = 1.4e8, cap: int = 48
     return np.unique(np.linspace(0, n_rows - 1, r).round().astype(np.int64))
 
 
-def check_fp32_y(y_g, y_o, absdot, xq_o, sx_o, xm, wq_o, sw_o, wm, K, tag="", fro_cap=None):
+def check_fp32_y(y_g, y_o, absdot, xq_o, sx_o, xm, wq_o, sw_o, wm, K, tag="", fro_cap=None, exact=False):
     """fp32 Y of the GPU (`y_g`, the oracle's rows) against the oracle (`y_o`, `absdot`) and against the matrix-pipe
     model of the same codes and scales (see the module docstring).  xq_o [R, K] codes of those rows, sx_o their
-    scales (row: [R]; block: [R * K/128]; tensor: [1]); wq_o [N, K], sw_o.  Returns the measured figures."""
+    scales (row: [R]; block: [R * K/128]; tensor: [1]); wq_o [N, K], sw_o.  Returns the measured figures.
+    exact=True: a kernel variant that multiplies exactly (e4m3 widened to bf16, BF16 matrix instruction): the stated
+    1e-5 applies against the oracle itself, per element and in rel-Frobenius."""
     y_g = y_g.astype(np.float64); y_o = y_o.astype(np.float64)
     R, N = y_o.shape
     err = np.abs(y_g - y_o)
+    if exact:
+        worst = float((err / np.maximum(STATED_TOL * absdot, 1e-300)).max())
+        fro = rel_fro(y_g, y_o)
+        assert worst <= 1.0 and fro <= STATED_TOL, f"{tag}: exact-product variant off by {worst:.3g} x (1e-5 * absdot), rel-Frobenius {fro:.3g}"
+        return {"err": err, "y_rel_fro": fro, "y_worst_over_1e-5_absdot": worst}
     tol = gemm_tolerance(absdot, y_o, K)
     worst = float((err / np.maximum(tol, 1e-300)).max())
     assert worst <= 1.0, f"{tag}: fp32 Y off by {worst:.3g} x the rigorous bound"

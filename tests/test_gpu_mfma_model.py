@@ -37,10 +37,13 @@ def _gpu_y(xq, sx, xm, wq, sw, wm, variant):
     return y.cpu().numpy().astype(np.float64)
 
 
-def _variants(M, N, K, xm=B.SCALE_TENSOR, wm=B.SCALE_TENSOR):
+def _variants(M, N, K, xm=B.SCALE_TENSOR, wm=B.SCALE_TENSOR, exact=False):
+    """The variants that run the shape: those on the FP8 matrix instructions, or (exact=True) the exact-product ones
+    (e4m3 widened to bf16 in registers, BF16 matrix instruction)."""
     d = B.make_desc(M, N, K, 1, xm, wm, B.NORM_NONE)
-    vs = [v for v in range(B.loka_variant_count()) if B.loka_variant_supports(d, v)]
-    assert len(vs) >= 8                       # 16x16x128 and 32x32x64 kernels, tiled / streaming / strip / panel
+    vs = [v for v in range(B.loka_variant_count())
+          if B.loka_variant_supports(d, v) and B.loka_variant_name(v).startswith("exact") == exact]
+    assert len(vs) >= (1 if exact else 8)     # 16x16x128 and 32x32x64 kernels, tiled / streaming / strip / panel
     return vs
 
 
@@ -131,9 +134,21 @@ def test_adversarial_groups_give_exactly_the_modelled_value():
         assert not bad, f"{B.loka_variant_name(v)}: " + "; ".join(bad)
         off = np.ones_like(y, dtype=bool)
         off[np.arange(len(_CASES)), np.arange(len(_CASES))] = False
+        assert (got[lost] != exact[np.arange(len(_CASES)), np.arange(len(_CASES))][lost]).all()
         # the cross terms (case i's row against case j's column: a few non-zero groups each) follow the model too, up
         # to the order of their fp32 sums
         assert np.allclose(y[off], y_m[off], rtol=2.0 ** -22, atol=0)
+
+
+    # the exact-product variants give the ORACLE's value on every one of these cases (fp32 rounding of the exact sum)
+    for v in _variants(M, N, K, exact=True):
+        y = _gpu_y(xq, one, B.SCALE_TENSOR, wq, one, B.SCALE_TENSOR, v)
+        got = np.array([y[i, i] for i in range(len(_CASES))])
+        ex = np.array([exact[i, i] for i in range(len(_CASES))])
+        bad = [f"{_CASES[i][0]}: got {got[i]!r}, exact {ex[i]!r}" for i in range(len(_CASES))
+               if (lost[i] and got[i] != ex[i]) or abs(got[i] - ex[i]) > 2.0 ** -23 * abs(ex[i])]
+        assert not bad, f"{B.loka_variant_name(v)}: " + "; ".join(bad)
+        assert np.allclose(y, exact, rtol=2.0 ** -22, atol=0)
 
 
 @pytest.mark.parametrize("kind", ["uniform codes", "gaussian", "gaussian with outlier channels"])
@@ -163,3 +178,9 @@ def test_random_operands_match_the_model_up_to_accumulation_order(orc, kind):
         assert worst <= 1.0 and fro <= 1e-6, f"{B.loka_variant_name(v)}: {worst:.3g} x (1e-5 absdot), rel-Frobenius {fro:.3g}"
         fro_go = float(np.linalg.norm(y - y_o) / np.linalg.norm(y_o))
         assert abs(fro_go - fro_mo) <= 0.02 * fro_mo + 1e-6
+    # the exact-product variants: the stated tolerance against the oracle itself
+    for v in _variants(M, N, K, B.SCALE_ROW, B.SCALE_COL, exact=True):
+        y = _gpu_y(xq, sx, B.SCALE_ROW, wq, sw, B.SCALE_COL, v)
+        worst = float((np.abs(y - y_o) / (1e-5 * absdot)).max())
+        fro = float(np.linalg.norm(y - y_o) / np.linalg.norm(y_o))
+        assert worst <= 1.0 and fro <= 1e-6, f"{B.loka_variant_name(v)}: {worst:.3g} x (1e-5 absdot), rel-Frobenius {fro:.3g}"

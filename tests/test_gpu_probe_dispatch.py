@@ -126,3 +126,16 @@ def test_dispatch_outlier_layer_prefers_finer_scales():
     mid = (e_b + min(e_r, e_t)) / 2
     st, ch, table = B.loka_dispatch(desc, x, wt, mid)
     assert st == B.LOKA_OK and ch["x_mode"] == B.SCALE_BLOCK_1x128
+
+
+def test_machine_ceilings_are_plausible():
+    # the measurement aid behind bench.py's "fraction of the measured ceiling": register-only matrix rates below the
+    # datasheet peaks (5.0 / 2.5 PFLOP/s) but well above half of them, a copy rate below 8 TB/s and above 2
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device=DEV)
+    f8 = B.loka_machine_ceiling(0, 20.0, buf)
+    bf = B.loka_machine_ceiling(1, 20.0, buf)
+    cp = B.loka_machine_ceiling(2, 10.0, buf)
+    print("ceilings: fp8 %.0f TFLOP/s, bf16 %.0f TFLOP/s, copy %.0f GB/s" % (f8, bf, cp))
+    assert 2500.0 < f8 < 5100.0 and 1250.0 < bf < 2600.0 and 2000.0 < cp < 8000.0
+    with pytest.raises(B.LokaError):
+        B.loka_machine_ceiling(3, 1.0, buf)
