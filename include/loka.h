@@ -28,7 +28,7 @@ extern "C" {
 typedef enum {
     LOKA_OK = 0,
     LOKA_ERR_NULL = 1,         /* a required pointer is NULL */
-    LOKA_ERR_SHAPE = 2,        /* non-positive size, K not a multiple of 128, a block mode that does not divide the shape, ld < cols */
+    LOKA_ERR_SHAPE = 2,        /* non-positive size, K not a multiple of 16, a block mode that does not divide the shape, ld < cols */
     LOKA_ERR_ALIGN = 3,        /* a pointer or stride is not 16-byte aligned */
     LOKA_ERR_UNSUPPORTED = 4,  /* enum out of range, or a scale/norm/N/variant combination no kernel covers */
     LOKA_ERR_WORKSPACE = 5,    /* workspace NULL or smaller than the *_workspace() query */
@@ -135,7 +135,8 @@ loka_status loka_machine_ceiling(int kind, double millis, void* scratch, size_t 
  *     gamma and beta are ignored.
  * There is no bias input (Section 3.2, "No Bias").
  * Supported scale pairs: x in {TENSOR, ROW} with w in {TENSOR, COL}; or x = BLOCK_1x128
- * with w = BLOCK_128x128 (needs N % 128 == 0).  K % 128 == 0, N % 16 == 0.
+ * with w = BLOCK_128x128 (needs N % 128 == 0 and K % 128 == 0).  K % 16 == 0, N % 16 == 0 (a K that is not a
+ * multiple of 128 is taken by the general tiled kernels, which mask the tail of the last K step).
  */
 typedef struct {
     int64_t M, N, K;
@@ -253,7 +254,7 @@ loka_status loka_fp8_linear_norm(const loka_gemm_desc* desc, const void* x_bf16,
  * Analysis"; the paper's reference is TF32, this build's is BF16 operands with fp32
  * accumulate).  x [batch][M, K] bf16, w [batch][K, N] bf16 (strideW 0 = shared),
  * yref [batch][M, N] fp32.  Only M, N, K, batch and the strides of `desc` are read.
- * K % 32 == 0, N % 16 == 0.  Workspace: loka_bf16_gemm_workspace() bytes (a transposed copy of W). */
+ * K % 8 == 0, N % 16 == 0.  Workspace: loka_bf16_gemm_workspace() bytes (a transposed copy of W). */
 size_t loka_bf16_gemm_workspace(const loka_gemm_desc* desc);
 loka_status loka_bf16_gemm(const loka_gemm_desc* desc, const void* x_bf16, const void* w_bf16, float* yref_fp32,
                            void* workspace, size_t ws_bytes, void* hip_stream);

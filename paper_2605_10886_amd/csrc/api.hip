@@ -52,7 +52,7 @@ loka_status validate_desc(const loka_gemm_desc* d, bool fp8) {
     if (d->M <= 0 || d->N <= 0 || d->K <= 0 || d->batch <= 0) return LOKA_ERR_SHAPE;
     if (d->M > INT32_MAX || d->N > INT32_MAX || d->K > INT32_MAX / 2 || d->batch > INT32_MAX) return LOKA_ERR_SHAPE;
     if (d->N % 16) return LOKA_ERR_SHAPE;
-    if (fp8 ? (d->K % 128) : (d->K % 64)) return LOKA_ERR_SHAPE;
+    if (fp8 ? (d->K % 16) : (d->K % 8)) return LOKA_ERR_SHAPE;
     if (d->strideX < 0 || d->strideW < 0 || d->strideO < 0) return LOKA_ERR_SHAPE;
     if (d->batch > 1 && d->strideO < d->M * d->N) return LOKA_ERR_SHAPE;
     if ((d->strideX % 16) || (d->strideW % 16) || (d->strideO % 8)) return LOKA_ERR_ALIGN;
@@ -69,7 +69,7 @@ loka_status validate_desc(const loka_gemm_desc* d, bool fp8) {
     if (xb != wb) return LOKA_ERR_UNSUPPORTED;
     // (power-of-two scales on both operands or on neither: the scaled matrix instruction takes both)
     if ((d->x_mode == LOKA_SCALE_BLOCK_1x128_POW2) != (d->w_mode == LOKA_SCALE_BLOCK_128x128_POW2)) return LOKA_ERR_UNSUPPORTED;
-    if (xb && (d->N % 128)) return LOKA_ERR_SHAPE;
+    if (xb && (d->N % 128 || d->K % 128)) return LOKA_ERR_SHAPE;
     if (!xb) {
         if (!(d->x_mode == LOKA_SCALE_TENSOR || d->x_mode == LOKA_SCALE_ROW)) return LOKA_ERR_UNSUPPORTED;
         if (!(d->w_mode == LOKA_SCALE_TENSOR || d->w_mode == LOKA_SCALE_COL)) return LOKA_ERR_UNSUPPORTED;

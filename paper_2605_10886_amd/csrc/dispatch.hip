@@ -249,7 +249,7 @@ loka_status loka_dispatch(const loka_gemm_desc* shape, const void* x_bf16, const
 
     struct Recipe { int xm, wm; };
     std::vector<Recipe> recipes = {{LOKA_SCALE_TENSOR, LOKA_SCALE_TENSOR}, {LOKA_SCALE_ROW, LOKA_SCALE_COL}};
-    if (N % 128 == 0) {
+    if (N % 128 == 0 && K % 128 == 0) {
         recipes.push_back({LOKA_SCALE_BLOCK_1x128, LOKA_SCALE_BLOCK_128x128});
         recipes.push_back({LOKA_SCALE_BLOCK_1x128_POW2, LOKA_SCALE_BLOCK_128x128_POW2});
     }

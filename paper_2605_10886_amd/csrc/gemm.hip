@@ -112,26 +112,35 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     constexpr int XG = BM / 8, WGR = BN_SUB / 8;
     static_assert(XG % NW == 0 && WGR % NW == 0 && NW % 4 == 0 && XG % 4 == 0, "loader split");
     constexpr int XJ = XG / NW, JN = XJ + WGR / NW;
-    const int x_lane_off = ld_row * p.KB + (((ld_pos ^ (ld_row >> 1)) << 4) ^ ((wave & 1) << 6));
-    const int w_lane_off = ld_row * p.KB + (((ld_pos ^ ((ld_row >> 1) & 1)) << 4) ^ ((wave & 3) << 5));
+    const int x_chunk = ((ld_pos ^ (ld_row >> 1)) << 4) ^ ((wave & 1) << 6);       // byte offset inside the 128-byte K step
+    const int w_chunk = ((ld_pos ^ ((ld_row >> 1) & 1)) << 4) ^ ((wave & 3) << 5);
+    const int x_lane_off = ld_row * p.KB + x_chunk;
+    const int w_lane_off = ld_row * p.KB + w_chunk;
+    // K need not be a multiple of the 128-byte step (a multiple of 16 bytes is enough): in the last step of such a K the
+    // lanes whose 16-byte chunk lies past the end of the row get an offset beyond every descriptor's bound and load
+    // zeros (in BOTH operands: a stray NaN code times zero would still be NaN), so the step contracts zeros there.
+    const int ktail = p.KB & 127;
+    const int x_lane_tail = x_chunk < ktail ? x_lane_off : 0x7FFFFFFF;
+    const int w_lane_tail = w_chunk < ktail ? w_lane_off : 0x7FFFFFFF;
     const int x_rows = p.M - m0 < BM ? p.M - m0 : BM, w_rows = p.N - n0 < BN ? p.N - n0 : BN;
     const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(Xg + static_cast<int64_t>(m0) * p.KB), 0, x_rows * p.KB, 0x00020000);
     const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(Wg + static_cast<int64_t>(n0) * p.KB), 0, w_rows * p.KB, 0x00020000);
     auto issue_j = [&](int j, int stage_x, int stage_w, int kb, int h, bool with_x) __attribute__((always_inline)) {
+        const bool tail = kb + 128 > p.KB;                    // uniform: the ragged last step
         if (j < XJ) {
             if (with_x) {
                 const int grp = wave + j * NW;                // uniform
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
                     x_rsrc, (__attribute__((address_space(3))) void*)(xbuf + stage_x * XS + grp * 1024), 16,
-                    x_lane_off, grp * 8 * p.KB + kb, 0, 0);
+                    tail ? x_lane_tail : x_lane_off, grp * 8 * p.KB + kb, 0, 0);
             }
         } else {
             const int grp = wave + (j - XJ) * NW;             // uniform
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 w_rsrc, (__attribute__((address_space(3))) void*)(wbuf + stage_w * WS + grp * 1024), 16,
-                w_lane_off, (h * BN_SUB + grp * 8) * p.KB + kb, 0, 0);
+                tail ? w_lane_tail : w_lane_off, (h * BN_SUB + grp * 8) * p.KB + kb, 0, 0);
         }
     };
 
@@ -154,7 +163,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
 #pragma unroll
             for (int ti = 0; ti < NI; ++ti) acc[h][mi][ti] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    const int ksteps = p.KB / 128;
+    const int ksteps = (p.KB + 127) / 128;
     const int iters = ksteps * NSPLIT;
 
     // blockwise scales: sx[m, kb] per row of this lane, sw[kb, nb] per N-part
@@ -834,6 +843,9 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
     if (vi.name == kWregName) return !scale_mode_is_block(d->x_mode) && wreg_supports(d->M, d->N, d->K);
     if (vi.name == kStripName)
         return !scale_mode_is_block(d->x_mode) && d->norm != LOKA_NORM_BLOCKNORM && strip_supports(d->M, d->N, d->K);
+    // a K that is not a multiple of 128 (the non-blockwise recipes allow any multiple of 16): the general tiled kernel
+    // masks the tail of the last K step; the 32x32 panel kernel does not
+    if (vi.name == kPanel32Name && d->K % 128) return false;
     // BlockNorm (groups of 256 columns) is built into the kernels whose tile is 256 columns wide
     if (d->norm == LOKA_NORM_BLOCKNORM && vi.launch != &launch_panel32) return false;
     if ((scale_mode_is_block(d->x_mode) ? vi.fn_block : vi.fn_plain) == nullptr) return false;

@@ -83,7 +83,15 @@ def test_gemm_argument_validation():
     good = B.make_desc(256, 128, 128)
     assert _gemm(good, xq=None) == B.LOKA_ERR_NULL
     assert _gemm(good, out=None) == B.LOKA_ERR_NULL
-    assert _gemm(B.make_desc(256, 128, 100)) == B.LOKA_ERR_SHAPE            # K % 128
+    assert _gemm(B.make_desc(256, 128, 100)) == B.LOKA_ERR_SHAPE            # K % 16
+    # the block recipes contract whole 128-wide K blocks
+    assert _gemm(B.make_desc(256, 128, 192, x_mode=B.SCALE_BLOCK_1x128, w_mode=B.SCALE_BLOCK_128x128)) == B.LOKA_ERR_SHAPE
+    # a K that is a multiple of 16 but not of 128 is a valid shape: some variant takes it, the large-layer and the
+    # register-resident kernels do not
+    ragged = B.make_desc(2048, 1024, 123200)              # K = 16 * 7700 (Section 2.3's largest shape)
+    assert B.loka_default_variant(ragged) >= 0
+    assert B.loka_variant_supports(ragged, B.variant_id("row64x1024")) and B.loka_variant_supports(ragged, B.variant_id("twopass128x128"))
+    assert not B.loka_variant_supports(ragged, B.variant_id("panel32_256x256")) and not B.loka_variant_supports(ragged, B.variant_id("wreg32"))
     assert _gemm(B.make_desc(256, 120, 128)) == B.LOKA_ERR_SHAPE            # N % 16
     assert _gemm(B.make_desc(0, 128, 128)) == B.LOKA_ERR_SHAPE
     assert _gemm(B.make_desc(256, 128, 128, x_mode=B.SCALE_COL)) == B.LOKA_ERR_UNSUPPORTED
@@ -140,7 +148,7 @@ def test_probe_and_bf16_argument_validation():
     assert L.loka_probe_error(FAKE, FAKE, 8, 16, 8, FAKE, None, FAKE, 1 << 20, None) == B.LOKA_ERR_SHAPE
     assert L.loka_probe_error(FAKE, FAKE, 8, 16, 16, FAKE, None, None, 0, None) == B.LOKA_ERR_WORKSPACE
     assert L.loka_probe_error(FAKE, ODD, 8, 16, 16, FAKE, None, FAKE, 1 << 20, None) == B.LOKA_ERR_ALIGN
-    d = B.make_desc(256, 128, 96)                                           # K % 64 for the BF16 GEMM
+    d = B.make_desc(256, 128, 100)                                          # K % 8 for the BF16 GEMM
     assert L.loka_bf16_gemm(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, 1 << 20, None) == B.LOKA_ERR_SHAPE
     d = B.make_desc(256, 128, 128)
     assert L.loka_bf16_gemm(ctypes.byref(d), FAKE, FAKE, FAKE, None, 0, None) == B.LOKA_ERR_WORKSPACE

@@ -118,6 +118,50 @@ def test_ragged_tiles_every_variant(orc, shape):
         _run_case(orc, x, wt, "row", "rmsnorm", v, gamma, None, tag=f"{shape} RMS {B.loka_variant_name(v)}")
 
 
+@pytest.mark.parametrize("shape", [(200, 144, 128), (333, 400, 512), (130, 1008, 256), (90, 112, 1024), (77, 16, 48),
+                                   (300, 2000, 1280), (64, 4080, 2320)])
+def test_ragged_k_every_variant(orc, shape):
+    # K a multiple of 16 but not of the kernels' 128-byte K step: the last step's tail is masked in both operands.
+    # Codes past the end of a row must not leak in: the operands are cut out of larger matrices whose neighbouring
+    # elements are NaN codes after quantization would be impossible, so X and W are laid out with a following row that
+    # starts with large values instead (a leak changes the result far beyond the tolerance).
+    M, K, N = shape
+    x = synth.student_t4(M, K, seed=M + K)
+    wt = synth.weight(K, N, seed=N + K)
+    x[:, :16] *= 50.0                                  # the bytes that follow a row's end in memory are the next row's start
+    gamma, beta = synth.affine(N, seed=4)
+    for recipe in ("row", "tensor"):
+        desc = B.make_desc(M, N, K, 1, *RECIPES[recipe], B.NORM_LAYERNORM)
+        vs = _variants_for(desc)
+        names = {B.loka_variant_name(v) for v in vs}
+        assert vs and not (names & {"panel32_256x256", "wreg32", "strip32"})
+        assert B.loka_default_variant(desc) in vs
+        for v in vs:
+            _run_case(orc, x, wt, recipe, "layernorm", v, gamma, beta, tag=f"{shape} {recipe} LN {B.loka_variant_name(v)}")
+            _run_case(orc, x, wt, recipe, "none", v, tag=f"{shape} {recipe} none {B.loka_variant_name(v)}")
+    # the block recipes need whole 128-wide K blocks
+    if K % 128:
+        with pytest.raises(B.LokaError):
+            B.loka_fp8_gemm_norm(B.make_desc(M, 128, K, 1, *RECIPES["block"], B.NORM_NONE),
+                                 torch.zeros(M, K, dtype=torch.uint8, device=DEV), torch.ones(M, device=DEV),
+                                 torch.zeros(128, K, dtype=torch.uint8, device=DEV), torch.ones(128, device=DEV))
+
+
+def test_ragged_k_largest_shape_of_the_throughput_study(orc):
+    # Section 2.3, "Throughput Analysis": the study's shapes run up to (2048, 123200) @ (123200, 1024); K = 16 * 7700.
+    # Full size on the GPU, the oracle on sampled rows; the library's own choice of kernel and the dispatcher's table.
+    M, K, N = 2048, 123200, 1024
+    x = synth.normal(M, K, seed=21)
+    wt = synth.weight(K, N, seed=22)
+    rows = _sample_rows(M, 8)[::4]
+    r = _run_case(orc, x, wt, "row", "layernorm", -1, rows=rows, tag="2048x123200x1024")
+    print("2048x123200x1024", r)
+    st, ch, table = B.loka_dispatch(B.make_desc(M, N, K, 1, norm=B.NORM_LAYERNORM), x.to(DEV), wt.to(DEV), 5e-2)
+    assert st == B.LOKA_OK and ch["variant"] >= 0
+    print("dispatch 2048x123200x1024:", ch["variant_name"], [(t["variant_name"], round(t["usec_gemm"])) for t in table])
+    B.loka_dispatch_clear()
+
+
 @pytest.mark.parametrize("recipe", ["block", "block_pow2"])
 def test_blockwise_ragged(orc, recipe):
     M, K, N = 150, 384, 640
@@ -762,7 +806,8 @@ def test_repeatable_bits():
 
 
 # ----------------------------------------------------------------------------- BF16 reference GEMM
-@pytest.mark.parametrize("shape", [(256, 128, 128), (300, 192, 272), (1024, 512, 512)])
+@pytest.mark.parametrize("shape", [(256, 128, 128), (300, 192, 272), (1024, 512, 512),
+                                   (200, 72, 144), (130, 1000, 64), (80, 8, 16)])       # K a multiple of 8 only
 def test_bf16_reference_gemm(orc, shape):
     M, K, N = shape
     x = synth.student_t4(M, K, seed=M + 1)
