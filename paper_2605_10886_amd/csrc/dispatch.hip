@@ -81,6 +81,14 @@ int default_variant(const loka_gemm_desc* d) {
                 if (variant_supports(d, v) && (pass == 1 || variant_is_streaming(v) == stream)) return v;
         return -1;
     }
+    // few output tiles and a long K (weight gradients; the widest layers at small batch): split K over several
+    // workgroups per tile (measured at 2048 x 123200 x 1024 with LayerNorm: see the variant's table entry)
+    {
+        const int64_t t128 = ((d->M + 127) / 128) * ((d->N + 127) / 128) * d->batch;
+        if (t128 <= 128 && d->K >= 2048)
+            for (int v = 0; v < variant_count(); ++v)
+                if (variant_epilogue(v) == 3 && variant_supports(d, v)) return v;
+    }
     // Measured on the skinny shapes (65536 x 1024 x 256, 65536 x 256 x 1024, 16384 x 512 x 512, 64 x 4096 x 256 x 256):
     // with at least one 256 x 256 tile per CU the large-tile kernel wins when K is long and the row fits one
     // tile (no cross-workgroup exchange then), and for blockwise scales, which the streaming kernel lacks.

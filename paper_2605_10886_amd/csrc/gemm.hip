@@ -85,8 +85,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
   for (int tile = tile_first; tile < total_tiles; tile += tile_stride) {
     int t = tile;
     const int tn = t % p.tiles_n; t /= p.tiles_n;
-    const int tm = t % p.tiles_m;
-    const int g = t / p.tiles_m;
+    const int tm = t % p.tiles_m; t /= p.tiles_m;
+    // EPI_SPLITK: the launch has ksplit workgroups per output tile (blockIdx.y), each contracts its own range of K steps
+    const int g = t;
+    const int ks = EPI == EPI_SPLITK ? static_cast<int>(blockIdx.y) : 0;
+    const int k_lo = ks * p.k_per_split;                       // first K step of this workgroup
+    const int kb0 = k_lo * 128;
     const int m0 = tm * BM, n0 = tn * BN;
 
     const uint8_t* Xg = p.X + static_cast<int64_t>(g) * p.strideX;
@@ -128,6 +132,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(Wg + static_cast<int64_t>(n0) * p.KB), 0, w_rows * p.KB, 0x00020000);
     auto issue_j = [&](int j, int stage_x, int stage_w, int kb, int h, bool with_x) __attribute__((always_inline)) {
+        kb += kb0;
         const bool tail = kb + 128 > p.KB;                    // uniform: the ragged last step
         if (j < XJ) {
             if (with_x) {
@@ -163,7 +168,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
 #pragma unroll
             for (int ti = 0; ti < NI; ++ti) acc[h][mi][ti] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    const int ksteps = (p.KB + 127) / 128;
+    const int ksteps_all = (p.KB + 127) / 128;
+    const int ksteps = EPI == EPI_SPLITK ? (ksteps_all - k_lo < p.k_per_split ? ksteps_all - k_lo : p.k_per_split) : ksteps_all;
     const int iters = ksteps * NSPLIT;
 
     // blockwise scales: sx[m, kb] per row of this lane, sw[kb, nb] per N-part
@@ -182,7 +188,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     // workgroup barriers: while A reads its 12 operand fragments of stage k from LDS, B runs the 32 MFMAs
     // of stage k-1 from registers; then A computes stage k while B reads stage k.  The MFMA pipe of every
     // SIMD always has a computing wave, and the LDS reads of one group hide behind the other's MFMAs.
-    constexpr bool PINGPONG = (NW == 8 && WAVES_M == 2 && NSPLIT == 1 && !IS_BF16 && !BLOCKWISE && !EXACT);
+    constexpr bool PINGPONG = (NW == 8 && WAVES_M == 2 && NSPLIT == 1 && !IS_BF16 && !BLOCKWISE && !EXACT && EPI != EPI_SPLITK);
     if constexpr (PINGPONG) {
         const bool grp_b = wave >= 4;                           // wave-uniform
         v8i bx[MI], aw[NI];
@@ -268,7 +274,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
             for (int mi = 0; mi < MI; ++mi) {
                 int m = m0 + wave_m * WM + mi * 16 + l16;
                 m = m < p.M ? m : p.M - 1;
-                sxk[mi] = sxg[static_cast<int64_t>(m) * ksteps + k];
+                sxk[mi] = sxg[static_cast<int64_t>(m) * ksteps_all + k_lo + k];
             }
         }
 #pragma unroll
@@ -278,7 +284,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
             if (BLOCKWISE) {
                 int nrun = n0 + hh * BN_SUB + wave_n * WN + q * 8;
                 nrun = nrun < p.N ? nrun : p.N - 1;
-                swk = swg[static_cast<int64_t>(k) * (p.N >> 7) + (nrun >> 7)];
+                swk = swg[static_cast<int64_t>(k_lo + k) * (p.N >> 7) + (nrun >> 7)];
             }
             // W fragments are fetched one tile ahead of the MFMAs that consume them
             v4i lo = *reinterpret_cast<const v4i*>(ws + w_off0);
@@ -395,6 +401,25 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
         }
     }
     if (IS_BF16) continue;                 // reference GEMM: fp32 Y only
+    if (EPI == EPI_SPLITK) {
+        // this K range's share of Y (scales applied: they are factors of every term) goes to the partial buffer; a second
+        // kernel adds the ranges in a fixed order and normalizes the row
+        float* const part = p.part + (static_cast<int64_t>(ks) * p.batch + g) * p.M * p.N;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int m = m0 + wave_m * WM + mi * 16 + l16;
+            if (m < p.M) {
+#pragma unroll
+                for (int h = 0; h < NSPLIT; ++h)
+#pragma unroll
+                    for (int ti = 0; ti < NI; ++ti) {
+                        const int n = ncol[h] + coff_of(ti);
+                        if (n < p.N) *reinterpret_cast<v4f*>(part + static_cast<int64_t>(m) * p.N + n) = acc[h][mi][ti];
+                    }
+            }
+        }
+        continue;
+    }
 
     // ---- row statistics (reciprocals and the inverse square root are the 1-ulp hardware ones: their
     // error is four orders of magnitude below a bf16 ulp, and the IEEE sequences are ~300 cycles each)
@@ -689,6 +714,84 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(const float* __restrict_
     }
 }
 
+// Second kernel of the split-K schedule: one wave per output row adds the row's ksplit partial sums in a fixed order
+// (repeatable bits), takes the row statistics of the sum in registers (two sweeps over the lane's values: no
+// E[y^2] - mean^2 cancellation), normalizes and writes bf16 O (and fp32 Y when asked).  N <= 8192: a lane holds
+// N / 64 values.  part: [ksplit][rows][N] fp32 with rows = batch * M; row r of problem g lies at g * strideO + m * N
+// in O / Y.
+constexpr int kSplitkMaxN = 8192;
+__global__ __launch_bounds__(256) void splitk_norm_rows_kernel(const float* __restrict__ part, int ksplit, int64_t rows,
+                                                               int M, int N, int64_t strideO, int norm, float eps,
+                                                               const uint16_t* __restrict__ gamma,
+                                                               const uint16_t* __restrict__ beta, uint16_t* __restrict__ out,
+                                                               float* __restrict__ y) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    constexpr int MAXC = kSplitkMaxN / 256;          // float4 chunks per lane
+    v4f v[MAXC];
+    const int chunks = N >> 2;
+    const int64_t slab = rows * static_cast<int64_t>(N);
+    const float* src = part + r * N;
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        const int c = lane + 64 * j;
+        v[j] = v4f{0.f, 0.f, 0.f, 0.f};
+        if (c < chunks) {
+            for (int k = 0; k < ksplit; ++k) v[j] += *reinterpret_cast<const v4f*>(src + k * slab + 4 * c);
+            s += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
+        }
+    }
+    const int64_t g = r / M, m = r - g * M;
+    const int64_t obase = g * strideO + m * N;
+    if (y) {
+#pragma unroll
+        for (int j = 0; j < MAXC; ++j) {
+            const int c = lane + 64 * j;
+            if (c < chunks) *reinterpret_cast<v4f*>(y + obase + 4 * c) = v[j];
+        }
+    }
+    float mean = 0.f, rstd = 1.f;
+    if (norm == LOKA_NORM_LAYERNORM || norm == LOKA_NORM_RMSNORM) {
+        if (norm == LOKA_NORM_LAYERNORM) {
+            for (int msk = 1; msk < 64; msk <<= 1) s += wave_shfl_xor(s, msk);
+            mean = s / static_cast<float>(N);
+        }
+        float m2 = 0.f;
+#pragma unroll
+        for (int j = 0; j < MAXC; ++j) {
+            const int c = lane + 64 * j;
+            if (c < chunks) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { const float d = v[j][e] - mean; m2 += d * d; }
+            }
+        }
+        for (int msk = 1; msk < 64; msk <<= 1) m2 += wave_shfl_xor(m2, msk);
+        rstd = 1.0f / sqrtf(m2 / static_cast<float>(N) + eps);
+    }
+    const bool has_g = gamma != nullptr && norm != LOKA_NORM_NONE, has_b = beta != nullptr && norm == LOKA_NORM_LAYERNORM;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        const int c = lane + 64 * j;
+        if (c >= chunks) continue;
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (v[j][e] - mean) * rstd;
+        if (has_g) {
+            const u32x2 w = *reinterpret_cast<const u32x2*>(gamma + 4 * c);
+            o[0] *= bf16_lo(w.x); o[1] *= bf16_hi(w.x); o[2] *= bf16_lo(w.y); o[3] *= bf16_hi(w.y);
+        }
+        if (has_b) {
+            const u32x2 w = *reinterpret_cast<const u32x2*>(beta + 4 * c);
+            o[0] += bf16_lo(w.x); o[1] += bf16_hi(w.x); o[2] += bf16_lo(w.y); o[3] += bf16_hi(w.y);
+        }
+        u32x2 pk;
+        pk.x = pack_bf16x2(o[0], o[1]); pk.y = pack_bf16x2(o[2], o[3]);
+        *reinterpret_cast<u32x2*>(out + obase + 4 * c) = pk;
+    }
+}
+
 // [K, N] bf16 -> [N, K] bf16 (the reference GEMM reads K-contiguous operands like the FP8 one)
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ w, int K, int N,
                                                              uint16_t* __restrict__ wt) {
@@ -792,6 +895,9 @@ static const VariantInfo kVariants[] = {
     LOKA_VARIANT("twopass128x128", 128, 128, 1, 2, 2, EPI_PARTIAL_STATS),
     LOKA_VARIANT("twopass256x256", 256, 256, 1, 2, 2, EPI_PARTIAL_STATS),
     LOKA_VARIANT("twopass256x256w8", 256, 256, 1, 2, 4, EPI_PARTIAL_STATS),
+    // split K: layers with few output tiles and a long K (weight gradients, the widest layers at small batch); ksplit
+    // workgroups per tile contract a K range each into fp32 partial sums, a second kernel adds them and normalizes
+    LOKA_VARIANT("splitk128x128", 128, 128, 1, 2, 2, EPI_SPLITK),
     // persistent, panel-synchronous: the tiles_n workgroups of a row panel exchange row statistics
     // through a few words of global memory and normalize their own tile in registers
     LOKA_VARIANT("panel256x256w8", 256, 256, 1, 2, 4, EPI_PANEL_SYNC),
@@ -837,6 +943,21 @@ bool variant_is_exact(int v) { return kVariants[v].launch != nullptr && kVariant
 int variant_bn(int v) { return kVariants[v].bn; }
 int variant_bm(int v) { return kVariants[v].bm; }
 
+// Split K: the number of K ranges and their length in 128-byte steps.  Enough ranges to give an MI355X's 256 CUs about
+// two workgroups each, at least 4 steps per range, at most 64 ranges.  (A fixed figure, not the device's CU count: the
+// workspace size follows from it and must not depend on the device.)
+static void splitk_plan(const loka_gemm_desc* d, const VariantInfo& vi, int* ksplit, int* per) {
+    const int64_t tiles = ((d->M + vi.bm - 1) / vi.bm) * ((d->N + vi.bn - 1) / vi.bn) * d->batch;
+    const int64_t steps = (d->K + 127) / 128;
+    int64_t want = (512 + tiles - 1) / tiles;
+    if (want > 64) want = 64;
+    if (want > steps / 4) want = steps / 4;
+    if (want < 1) want = 1;
+    const int64_t len = (steps + want - 1) / want;
+    *per = static_cast<int>(len);
+    *ksplit = static_cast<int>((steps + len - 1) / len);
+}
+
 bool variant_supports(const loka_gemm_desc* d, int v) {
     if (v < 0 || v >= kNumVariants) return false;
     const VariantInfo& vi = kVariants[v];
@@ -849,6 +970,12 @@ bool variant_supports(const loka_gemm_desc* d, int v) {
     // BlockNorm (groups of 256 columns) is built into the kernels whose tile is 256 columns wide
     if (d->norm == LOKA_NORM_BLOCKNORM && vi.launch != &launch_panel32) return false;
     if ((scale_mode_is_block(d->x_mode) ? vi.fn_block : vi.fn_plain) == nullptr) return false;
+    if (vi.epi == EPI_SPLITK) {
+        // (offered where K actually gets split: with a single range it is the two-pass schedule with more traffic)
+        int ksplit = 1, per = 1;
+        splitk_plan(d, vi, &ksplit, &per);
+        if (d->N > kSplitkMaxN || d->norm == LOKA_NORM_BLOCKNORM || ksplit < 2) return false;
+    }
     if (vi.epi == EPI_ROW_IN_TILE && d->N > vi.bn) return false;
     if (vi.epi == EPI_PANEL_SYNC && (d->N + vi.bn - 1) / vi.bn > kMaxRowTiles) return false;
     if (static_cast<int64_t>(vi.bm > vi.bn ? vi.bm : vi.bn) * d->K >= (int64_t(1) << 31)) return false;   // tile-relative offsets are 32-bit
@@ -879,6 +1006,11 @@ static size_t panel_flag_bytes(const loka_gemm_desc* d, const VariantInfo& vi) {
 
 size_t variant_workspace(const loka_gemm_desc* d, int v, bool fp8out) {
     const VariantInfo& vi = kVariants[v];
+    if (vi.epi == EPI_SPLITK) {
+        int ksplit = 1, per = 1;
+        splitk_plan(d, vi, &ksplit, &per);
+        return static_cast<size_t>(ksplit) * d->batch * d->M * d->N * sizeof(float);
+    }
     if (vi.epi == EPI_ROW_IN_TILE || d->norm == LOKA_NORM_NONE) return 0;
     if (d->norm == LOKA_NORM_BLOCKNORM && !panel_exchanges(d, vi, fp8out)) return 0;
     const int64_t tiles_n = (d->N + vi.bn - 1) / vi.bn;
@@ -1074,6 +1206,17 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
                     reinterpret_cast<uint32_t*>(ws), words);
             }
         }
+    }
+    if (vi.epi == EPI_SPLITK) {
+        splitk_plan(d, vi, &p.ksplit, &p.k_per_split);
+        p.part = static_cast<float*>(workspace);
+        p.y = nullptr;                                  // (the second kernel writes Y)
+        grid.y = static_cast<unsigned>(p.ksplit);
+        vi.launch(p, blockwise, grid, s);
+        const int64_t rows = static_cast<int64_t>(d->batch) * d->M;
+        splitk_norm_rows_kernel<<<dim3(static_cast<unsigned>((rows + 3) / 4)), 256, 0, s>>>(
+            p.part, p.ksplit, rows, p.M, p.N, p.strideO, d->norm, d->eps, p.gamma, p.beta, p.out, y);
+        return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
     }
     vi.launch(p, blockwise, grid, s);
     if (two_pass) {

@@ -5,7 +5,7 @@
 
 namespace loka {
 
-enum { EPI_ROW_IN_TILE = 0, EPI_PARTIAL_STATS = 1, EPI_PANEL_SYNC = 2 };
+enum { EPI_ROW_IN_TILE = 0, EPI_PARTIAL_STATS = 1, EPI_PANEL_SYNC = 2, EPI_SPLITK = 3 };
 
 struct GemmParams {
     const uint8_t* X;      // [batch][M][KB] bytes (KB = K for FP8, 2K for BF16)
@@ -30,6 +30,7 @@ struct GemmParams {
     int block_n, act;      // LOKA_NORM_BLOCKNORM group width; loka_act
     float eps;
     int tiles_m, tiles_n;
+    int ksplit, k_per_split;   // EPI_SPLITK: number of K ranges, and 128-byte K steps per range; part = [ksplit][batch][M][N] fp32
     float* part;           // EPI_PARTIAL_STATS / EPI_PANEL_SYNC: [batch][M][tiles_n * 2] (mean, M2) or (0, sumsq)
                            // (gemm_panel32.hip: [batch][tiles_m][tiles_n][256] such pairs, then as many (min, max) pairs)
     // EPI_PANEL_SYNC, the exchange between the workgroups of a row panel (see panel_publish_and_wait):

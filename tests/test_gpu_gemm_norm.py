@@ -162,6 +162,34 @@ def test_ragged_k_largest_shape_of_the_throughput_study(orc):
     B.loka_dispatch_clear()
 
 
+@pytest.mark.parametrize("case", [(256, 16384, 1024, "row", "none"), (256, 16384, 1024, "block", "none"),
+                                  (512, 8192, 512, "tensor", "layernorm"), (300, 4096, 2320, "row", "rmsnorm"),
+                                  (128, 32768, 256, "block_pow2", "layernorm")])
+def test_split_k_few_tiles_long_k(orc, case):
+    # few output tiles and a long K (the shape of a weight-gradient GEMM, or of a wide layer at small batch): several
+    # workgroups per tile contract a K range each, a second kernel adds the partial sums in a fixed order and normalizes
+    M, K, N, recipe, norm = case
+    x = synth.student_t4(M, K, seed=5 * M)
+    wt = synth.weight(K, N, seed=5 * N)
+    gamma, beta = synth.affine(N, seed=9) if norm != "none" else (None, None)
+    v = B.variant_id("splitk128x128")
+    desc = B.make_desc(M, N, K, 1, *RECIPES[recipe], B.NORMS[norm], 1e-5, v)
+    assert B.loka_variant_supports(desc, v)
+    assert B.loka_default_variant(B.make_desc(M, N, K, 1, *RECIPES[recipe], B.NORMS[norm])) == v
+    r = _run_case(orc, x, wt, recipe, norm, v, gamma, beta if norm == "layernorm" else None, tag=f"split-K {case}")
+    print("split-K", case, r)
+    # repeatable bits: the partial sums are added in a fixed order
+    xq, sx = B.loka_quantize(x.to(DEV), RECIPES[recipe][0])
+    wq, sw = B.loka_quantize(wt.to(DEV), RECIPES[recipe][1], transpose_out=True)
+    a, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+    for _ in range(3):
+        b, _ = B.loka_fp8_gemm_norm(desc, xq, sx, wq, sw)
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    # not offered where K would not be split
+    assert not B.loka_variant_supports(B.make_desc(32768, 4096, 4096, 1, variant=v), v)
+    assert not B.loka_variant_supports(B.make_desc(256, 128, 128, 1, variant=v), v)
+
+
 @pytest.mark.parametrize("recipe", ["block", "block_pow2"])
 def test_blockwise_ragged(orc, recipe):
     M, K, N = 150, 384, 640
