@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "loka_oracle.cpp")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-SCALE_TENSOR, SCALE_ROW, SCALE_COL, SCALE_BLOCK_1x128, SCALE_BLOCK_128x128, SCALE_BLOCK_1x128_POW2, SCALE_BLOCK_128x128_POW2 = range(7)
+SCALE_TENSOR, SCALE_ROW, SCALE_COL, SCALE_BLOCK_1x128, SCALE_BLOCK_128x128, SCALE_BLOCK_1x128_POW2, SCALE_BLOCK_128x128_POW2, SCALE_BLOCK_128x1 = range(8)
 NORM_NONE, NORM_LAYERNORM, NORM_RMSNORM = range(3)
 
 _lib = None

@@ -121,7 +121,12 @@ void parallel_rows(int64_t n, int threads, F f) {
 }
 
 enum { SCALE_TENSOR = 0, SCALE_ROW = 1, SCALE_COL = 2, SCALE_BLOCK_1x128 = 3, SCALE_BLOCK_128x128 = 4,
-       SCALE_BLOCK_1x128_POW2 = 5, SCALE_BLOCK_128x128_POW2 = 6 };   // 5, 6: groups of 3, 4 with power-of-two scales
+       SCALE_BLOCK_1x128_POW2 = 5, SCALE_BLOCK_128x128_POW2 = 6,    // 5, 6: groups of 3, 4 with power-of-two scales
+       // 128 consecutive ROWS of one column: the 1 x 128 groups of the TRANSPOSED matrix.  The block recipe's groups
+       // have to run along the dimension a GEMM contracts; in the weight-gradient GEMM of the backward pass (Section
+       // 3.3, "Trainer Integration": forward and backward GEMMs are routed separately) dW = X^T dY that is the batch
+       // dimension, the rows of X.  Scales are ordered as the transposed matrix's groups: [column][row block].
+       SCALE_BLOCK_128x1 = 7 };
 
 // group layout of a mode (the power-of-two modes share the layout of the plain block modes)
 int layout_of(int mode) {
@@ -145,6 +150,11 @@ int64_t group_of(int mode, int64_t r, int64_t c, int64_t cols) {
         case SCALE_BLOCK_128x128: return (r / 128) * (cols / 128) + c / 128;
     }
     return -1;
+}
+// (mode 7 needs the row count: its groups are numbered [column][row block])
+int64_t group_of(int mode, int64_t r, int64_t c, int64_t rows, int64_t cols) {
+    if (mode == SCALE_BLOCK_128x1) return c * (rows / 128) + r / 128;
+    return group_of(mode, r, c, cols);
 }
 
 }  // namespace
@@ -174,6 +184,7 @@ int64_t orc_scale_count(int mode, int64_t rows, int64_t cols) {
         case SCALE_COL: return cols;
         case SCALE_BLOCK_1x128: return cols % 128 ? -1 : rows * (cols / 128);
         case SCALE_BLOCK_128x128: return (cols % 128 || rows % 128) ? -1 : (rows / 128) * (cols / 128);
+        case SCALE_BLOCK_128x1: return rows % 128 ? -1 : (rows / 128) * cols;
     }
     return -1;
 }
@@ -198,7 +209,7 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int 
     for (int64_t r = 0; r < rows; ++r)
         for (int64_t c = 0; c < cols; ++c) {
             float a = std::fabs(bf16_to_f32(x[r * ld + c]));
-            float& m = amax[group_of(mode, r, c, cols)];
+            float& m = amax[group_of(mode, r, c, rows, cols)];
             if (a > m) m = a;
         }
     std::vector<float> inv(ng);
@@ -219,7 +230,7 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int 
         for (int64_t r = lo; r < hi; ++r)
             for (int64_t c = 0; c < cols; ++c) {
                 float xf = bf16_to_f32(x[r * ld + c]);
-                float t = xf * inv[group_of(mode, r, c, cols)];
+                float t = xf * inv[group_of(mode, r, c, rows, cols)];
                 if (t > kE4M3Max) t = kE4M3Max;
                 if (t < -kE4M3Max) t = -kE4M3Max;
                 uint8_t code = e4m3_encode(t);

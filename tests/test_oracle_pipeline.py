@@ -31,7 +31,8 @@ def exact_quantize(x_bits, mode, orc):
     def gid(r, c):
         return {orc.SCALE_TENSOR: 0, orc.SCALE_ROW: r, orc.SCALE_COL: c,
                 orc.SCALE_BLOCK_1x128: r * (cols // 128) + c // 128,
-                orc.SCALE_BLOCK_128x128: (r // 128) * (cols // 128) + c // 128}[mode]
+                orc.SCALE_BLOCK_128x128: (r // 128) * (cols // 128) + c // 128,
+                orc.SCALE_BLOCK_128x1: c * (rows // 128) + r // 128}[mode]
 
     ng = orc.scale_count(mode, rows, cols)
     amax = [Fraction(0)] * ng
@@ -90,6 +91,28 @@ def test_quantize_every_mode_against_exact_fractions(orc, mode_name):
     q_exact, s_exact = exact_quantize(xb, mode, orc)
     assert [Fraction(float(v)) for v in s] == s_exact
     assert np.array_equal(q, q_exact)
+
+
+def test_quantize_column_blocks_are_the_row_blocks_of_the_transposed_matrix(orc):
+    # BLOCK_128x1 (128 consecutive rows of one column share a scale; used for the operands of the weight-gradient GEMM,
+    # whose contraction runs over the rows) against (a) exact fractions and (b) its definition: with the output
+    # transposed, codes and scales are exactly the 1 x 128 quantization of the transposed matrix, scale for scale
+    x = synth.student_t4(256, 48, seed=23)
+    x[130:250, 7] = 0                             # an all-zero group (rows 128..255 of column 7 are not all zero: 250..255 stay)
+    x[128:256, 9] = 0                             # an all-zero group
+    x[3, 11] = 2.5e4
+    xb = synth.bf16_bits(x).copy()
+    q, s = orc.quantize(xb, orc.SCALE_BLOCK_128x1, threads=2)
+    q_exact, s_exact = exact_quantize(xb, orc.SCALE_BLOCK_128x1, orc)
+    assert [Fraction(float(v)) for v in s] == s_exact and np.array_equal(q, q_exact)
+    qt, st = orc.quantize(xb, orc.SCALE_BLOCK_128x1, transpose_out=True)
+    xt = np.ascontiguousarray(xb.T)
+    q_ref, s_ref = orc.quantize(xt, orc.SCALE_BLOCK_1x128)
+    assert qt.shape == (48, 256) and np.array_equal(qt, q_ref) and np.array_equal(f32_bits(st), f32_bits(s_ref))
+    assert np.array_equal(qt, q.T) and np.array_equal(f32_bits(st), f32_bits(s))
+    assert s.shape == (2 * 48,) and s[9 * 2 + 1] == np.float32(1e-12) / np.float32(448.0)
+    with pytest.raises(ValueError):
+        orc.quantize(xb[:200].copy(), orc.SCALE_BLOCK_128x1)
 
 
 def test_quantize_half_ulp_bound_and_amax_hits_448(orc):
