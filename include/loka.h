@@ -52,7 +52,13 @@ typedef enum {
      * Every scale is exactly representable by an 8-bit exponent, so the GEMM can hand the per-block scales to the
      * matrix cores (scaled MFMA) instead of rescaling accumulators: see loka_fp8_gemm_norm. */
     LOKA_SCALE_BLOCK_1x128_POW2 = 5,
-    LOKA_SCALE_BLOCK_128x128_POW2 = 6
+    LOKA_SCALE_BLOCK_128x128_POW2 = 6,
+    /* loka_quantize only, with transpose_out: one scale per (128 consecutive ROWS, column) -> rows/128 * cols, ordered
+     * [column][row block].  The transposed codes [cols, rows] with these scales ARE a BLOCK_1x128 operand (its groups run
+     * along the rows of the input): what the weight-gradient GEMM of the backward pass needs, whose contraction runs
+     * over the batch rows (Section 3.3, "Trainer Integration": dW = X^T dY with X quantized this way and dY quantized
+     * BLOCK_128x128 with transpose_out; see loka_fp8_gemm_norm).  rows % 128 == 0. */
+    LOKA_SCALE_BLOCK_128x1 = 7
 } loka_scale_mode;
 
 /* Row normalization fused into the GEMM epilogue (Section 3.2, "Block-wise
@@ -92,8 +98,9 @@ int64_t loka_scale_count(loka_scale_mode mode, int64_t rows, int64_t cols);
  *   scales   [loka_scale_count(mode, rows, cols)] fp32, group order: row-major over
  *            (row group, column group)
  *   cols must be a multiple of 16 (rows too when transpose_out != 0).
- * Workspace: loka_quantize_workspace() bytes (0 for ROW and the two BLOCK_1x128 modes without
- * transpose); contents are scratch.  transpose_out is not supported for ROW and the BLOCK_1x128 modes
+ * Workspace: loka_quantize_workspace() bytes (non-zero only for TENSOR and COL, whose groups span workgroups: amax
+ * pass, scales, cast pass; every other mode is ONE pass, 3 bytes of traffic per element); contents are scratch.
+ * transpose_out is not supported for ROW and the BLOCK_1x128 modes and is required for BLOCK_128x1
  * (LOKA_ERR_UNSUPPORTED).  The power-of-two modes replace the two divisions by the rule stated at the enum. */
 size_t loka_quantize_workspace(loka_scale_mode mode, int64_t rows, int64_t cols, int transpose_out);
 loka_status loka_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, loka_scale_mode mode,

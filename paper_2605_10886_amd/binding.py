@@ -20,7 +20,7 @@ LOKA_OK = 0
 STATIC_SCRATCH_BYTES = 16 << 20       # LOKA_STATIC_SCRATCH_BYTES of include/loka.h
 LOKA_ERR_NULL, LOKA_ERR_SHAPE, LOKA_ERR_ALIGN, LOKA_ERR_UNSUPPORTED = 1, 2, 3, 4
 LOKA_ERR_WORKSPACE, LOKA_ERR_HIP, LOKA_ERR_NO_CANDIDATE, LOKA_ERR_TIMEOUT = 5, 6, 7, 8
-SCALE_TENSOR, SCALE_ROW, SCALE_COL, SCALE_BLOCK_1x128, SCALE_BLOCK_128x128, SCALE_BLOCK_1x128_POW2, SCALE_BLOCK_128x128_POW2 = range(7)
+SCALE_TENSOR, SCALE_ROW, SCALE_COL, SCALE_BLOCK_1x128, SCALE_BLOCK_128x128, SCALE_BLOCK_1x128_POW2, SCALE_BLOCK_128x128_POW2, SCALE_BLOCK_128x1 = range(8)
 NORM_NONE, NORM_LAYERNORM, NORM_RMSNORM, NORM_BLOCKNORM = range(4)
 NORMS = {"none": NORM_NONE, "layernorm": NORM_LAYERNORM, "rmsnorm": NORM_RMSNORM, "blocknorm": NORM_BLOCKNORM}
 ACT_NONE, ACT_HARDSWISH = 0, 1

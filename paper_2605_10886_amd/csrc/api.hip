@@ -42,7 +42,8 @@ int default_variant(const loka_gemm_desc*);
 size_t tracker_workspace_bytes(int64_t, int64_t);
 loka_status tracker_update_launch(const void*, int64_t, int64_t, int64_t, int64_t, float*, float*, void*, hipStream_t);
 
-static bool mode_ok(int m) { return m >= LOKA_SCALE_TENSOR && m <= LOKA_SCALE_BLOCK_128x128_POW2; }
+static bool mode_ok(int m) { return m >= LOKA_SCALE_TENSOR && m <= LOKA_SCALE_BLOCK_128x128_POW2; }       // modes a GEMM operand can have
+static bool quant_mode_ok(int m) { return m >= LOKA_SCALE_TENSOR && m <= LOKA_SCALE_BLOCK_128x1; }
 static bool is_block_x(int m) { return m == LOKA_SCALE_BLOCK_1x128 || m == LOKA_SCALE_BLOCK_1x128_POW2; }
 static bool is_block_w(int m) { return m == LOKA_SCALE_BLOCK_128x128 || m == LOKA_SCALE_BLOCK_128x128_POW2; }
 
@@ -114,12 +115,14 @@ int64_t loka_scale_count(loka_scale_mode mode, int64_t rows, int64_t cols) {
         case LOKA_SCALE_BLOCK_1x128_POW2: return (cols % 128) ? -1 : rows * (cols / 128);
         case LOKA_SCALE_BLOCK_128x128:
         case LOKA_SCALE_BLOCK_128x128_POW2: return (cols % 128 || rows % 128) ? -1 : (rows / 128) * (cols / 128);
+        case LOKA_SCALE_BLOCK_128x1: return (rows % 128) ? -1 : (rows / 128) * cols;
     }
     return -1;
 }
 
 size_t loka_quantize_workspace(loka_scale_mode mode, int64_t rows, int64_t cols, int transpose_out) {
     if (!transpose_out && (mode == LOKA_SCALE_ROW || is_block_x(mode))) return 0;
+    if (is_block_w(mode) || mode == LOKA_SCALE_BLOCK_128x1) return 0;      // groups that fit a workgroup: one pass
     const int64_t ng = loka_scale_count(mode, rows, cols);
     if (ng < 0) return 0;
     return static_cast<size_t>(ng) * 8;       // amax bits + quantization factors
@@ -129,13 +132,14 @@ loka_status loka_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_
                           int transpose_out, uint8_t* q, float* scales, void* workspace, size_t ws_bytes,
                           void* hip_stream) {
     if (!x_bf16 || !q || !scales) return LOKA_ERR_NULL;
-    if (!mode_ok(mode)) return LOKA_ERR_UNSUPPORTED;
+    if (!quant_mode_ok(mode)) return LOKA_ERR_UNSUPPORTED;
     if (rows <= 0 || cols <= 0 || ld < cols) return LOKA_ERR_SHAPE;
     if (cols % 16 || (transpose_out && rows % 16)) return LOKA_ERR_SHAPE;
     if (loka_scale_count(mode, rows, cols) < 0) return LOKA_ERR_SHAPE;
     if (ld % 8) return LOKA_ERR_ALIGN;
     if (!aligned16(x_bf16) || !aligned16(q) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return LOKA_ERR_ALIGN;
     if (transpose_out && (mode == LOKA_SCALE_ROW || is_block_x(mode))) return LOKA_ERR_UNSUPPORTED;
+    if (!transpose_out && mode == LOKA_SCALE_BLOCK_128x1) return LOKA_ERR_UNSUPPORTED;
     const size_t need = loka_quantize_workspace(mode, rows, cols, transpose_out);
     if (need && (!workspace || ws_bytes < need)) return LOKA_ERR_WORKSPACE;
     if (need && !aligned16(workspace)) return LOKA_ERR_ALIGN;

@@ -198,25 +198,6 @@ __global__ __launch_bounds__(256) void amax_col_kernel(const uint16_t* __restric
     for (int j = 0; j < 8; ++j) atomicMax(amax_bits + c * 8 + j, __float_as_uint(a[j]));
 }
 
-// BLOCK_128x128: one workgroup per block, plain store (no atomics needed).
-__global__ __launch_bounds__(256) void amax_block128_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
-                                                            int64_t ld, uint32_t* __restrict__ amax_bits) {
-    __shared__ float red[4];
-    const int64_t bc = blockIdx.x, br = blockIdx.y;
-    const int cc = threadIdx.x & 15, rr = threadIdx.x >> 4;     // 16 chunks x 16 rows per sweep
-    float a = 0.f;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        const int64_t r = br * 128 + s * 16 + rr;
-        a = fmaxf(a, chunk_amax(*reinterpret_cast<const u32x4*>(x + r * ld + bc * 128 + cc * 8)));
-    }
-    for (int m = 1; m < 64; m <<= 1) a = fmaxf(a, wave_shfl_xor(a, m));
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
-    __syncthreads();
-    if (threadIdx.x == 0)
-        amax_bits[br * (cols >> 7) + bc] = __float_as_uint(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])));
-}
-
 __global__ void finalize_scales_kernel(const uint32_t* __restrict__ amax_bits, float* __restrict__ inv,
                                        float* __restrict__ scales, int64_t ng, const int pow2) {
     int64_t g = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -236,14 +217,10 @@ __device__ __forceinline__ void load_inv8(const float* __restrict__ inv, int64_t
         const float v = inv[0];
 #pragma unroll
         for (int j = 0; j < 8; ++j) f[j] = v;
-    } else if (MODE == LOKA_SCALE_COL) {
+    } else {
         const float4 a = *reinterpret_cast<const float4*>(inv + c8);
         const float4 b = *reinterpret_cast<const float4*>(inv + c8 + 4);
         f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
-    } else {
-        const float v = inv[(r >> 7) * (cols >> 7) + (c8 >> 7)];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) f[j] = v;
     }
 }
 
@@ -297,6 +274,102 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
     const int64_t c = c0 + cc, r = r0 + rr;
     if (c < cols && r < rows)
         *reinterpret_cast<u32x4*>(q + c * rows + r) = *reinterpret_cast<const u32x4*>(&tile[cc][rr]);
+}
+
+// Single-pass quantization of the modes whose scale groups fit one workgroup: a workgroup takes a 128 x 128 tile
+// (8 sweeps of 16 rows x 16 chunks of 8 elements: 32 registers per thread), finds the amax of its groups on chip,
+// scales, casts and stores - every element is read once and written once (3 bytes per element).
+//   COLGROUPS == false: the whole tile is one group (BLOCK_128x128 and its power-of-two form); scales [rows/128][cols/128]
+//   COLGROUPS == true:  every column of the tile is a group (BLOCK_128x1); scales [cols][rows/128]
+//   TRANSPOSE: codes leave as [cols, rows] through an LDS tile (64-byte runs per output row)
+// rows % 128 == 0; cols % 16 == 0 (COLGROUPS) or % 128 == 0: chunks past the last column are skipped.
+template <bool COLGROUPS, bool TRANSPOSE>
+__global__ __launch_bounds__(256) void quant_tile128_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                            int64_t ld, uint8_t* __restrict__ q, float* __restrict__ scales,
+                                                            const int pow2) {
+    __shared__ float red[4 * 128];                      // per wave: column maxima (COLGROUPS) or one value
+    __shared__ float inv_s[128];
+    __shared__ __attribute__((aligned(16))) uint8_t tile[TRANSPOSE ? 128 * (128 + 16) : 16];   // [c][r], rows padded to 144 bytes
+    const int t = static_cast<int>(threadIdx.x), lane = t & 63, wave = t >> 6;
+    const int cc = t & 15, rr = t >> 4;                 // chunk column, row within a sweep
+    const int64_t r0 = static_cast<int64_t>(blockIdx.y) * 128, c0 = static_cast<int64_t>(blockIdx.x) * 128;
+    const bool live = c0 + cc * 8 < cols;
+    u32x4 w[8];
+#pragma unroll
+    for (int sw = 0; sw < 8; ++sw) {
+        w[sw] = u32x4{0u, 0u, 0u, 0u};
+        if (live) w[sw] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + (r0 + sw * 16 + rr) * ld + c0 + cc * 8));
+    }
+    float inv8[8];
+    if (COLGROUPS) {
+        float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int sw = 0; sw < 8; ++sw) {
+            a[0] = fmaxf(a[0], fabsf(bf16_lo(w[sw].x))); a[1] = fmaxf(a[1], fabsf(bf16_hi(w[sw].x)));
+            a[2] = fmaxf(a[2], fabsf(bf16_lo(w[sw].y))); a[3] = fmaxf(a[3], fabsf(bf16_hi(w[sw].y)));
+            a[4] = fmaxf(a[4], fabsf(bf16_lo(w[sw].z))); a[5] = fmaxf(a[5], fabsf(bf16_hi(w[sw].z)));
+            a[6] = fmaxf(a[6], fabsf(bf16_lo(w[sw].w))); a[7] = fmaxf(a[7], fabsf(bf16_hi(w[sw].w)));
+        }
+        // lanes l, l ^ 16, l ^ 32, l ^ 48 of a wave hold the same columns (rows rr differ); then the 4 waves through LDS
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            a[j] = fmaxf(a[j], wave_shfl_xor(a[j], 16));
+            a[j] = fmaxf(a[j], wave_shfl_xor(a[j], 32));
+        }
+        if (lane < 16) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) red[wave * 128 + cc * 8 + j] = a[j];
+        }
+        __syncthreads();
+        if (t < 128) {
+            const float am = fmaxf(fmaxf(red[t], red[128 + t]), fmaxf(red[256 + t], red[384 + t]));
+            float sc, iv;
+            group_scale_any(pow2 != 0, am, sc, iv);
+            inv_s[t] = iv;
+            if (c0 + t < cols) scales[(c0 + t) * (rows >> 7) + blockIdx.y] = sc;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) inv8[j] = inv_s[cc * 8 + j];
+    } else {
+        float a = 0.f;
+#pragma unroll
+        for (int sw = 0; sw < 8; ++sw) a = fmaxf(a, chunk_amax(w[sw]));
+        for (int m = 1; m < 64; m <<= 1) a = fmaxf(a, wave_shfl_xor(a, m));
+        if (lane == 0) red[wave] = a;
+        __syncthreads();
+        float sc, iv;
+        group_scale_any(pow2 != 0, fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])), sc, iv);
+        if (t == 0) scales[blockIdx.y * (cols >> 7) + blockIdx.x] = sc;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) inv8[j] = iv;
+    }
+#pragma unroll
+    for (int sw = 0; sw < 8; ++sw) {
+        const uint32_t lo = e4m3x4(bf16_lo(w[sw].x) * inv8[0], bf16_hi(w[sw].x) * inv8[1], bf16_lo(w[sw].y) * inv8[2], bf16_hi(w[sw].y) * inv8[3]);
+        const uint32_t hi = e4m3x4(bf16_lo(w[sw].z) * inv8[4], bf16_hi(w[sw].z) * inv8[5], bf16_lo(w[sw].w) * inv8[6], bf16_hi(w[sw].w) * inv8[7]);
+        const int r = sw * 16 + rr;
+        if (TRANSPOSE) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                tile[(cc * 8 + j) * 144 + r] = static_cast<uint8_t>(lo >> (8 * j));
+                tile[(cc * 8 + 4 + j) * 144 + r] = static_cast<uint8_t>(hi >> (8 * j));
+            }
+        } else if (live) {
+            *reinterpret_cast<u32x2*>(q + (r0 + r) * cols + c0 + cc * 8) = u32x2{lo, hi};
+        }
+    }
+    if (TRANSPOSE) {
+        __syncthreads();
+        // output row c0 + c: 128 codes; thread -> (c = t / 2, half of 64 bytes)
+        const int c = t >> 1, half = (t & 1) * 64;
+        if (c0 + c < cols) {
+            uint8_t* dst = q + (c0 + c) * rows + r0 + half;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<u32x4*>(dst + 16 * j) = *reinterpret_cast<const u32x4*>(tile + c * 144 + half + 16 * j);
+        }
+    }
 }
 
 __global__ void e4m3_from_f32_kernel(const float* __restrict__ t, uint8_t* __restrict__ codes, int64_t n) {
@@ -354,6 +427,14 @@ loka_status quantize_launch(const void* x_bf16, int64_t rows, int64_t cols, int6
         else launch_rows<true>(x, rows, cols, ld, q, scales, pow2, s);
         return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
     }
+    if (mode == LOKA_SCALE_BLOCK_128x128 || mode == LOKA_SCALE_BLOCK_128x1) {
+        // groups that fit a workgroup: one pass
+        const dim3 g(static_cast<unsigned>((cols + 127) / 128), static_cast<unsigned>(rows / 128));
+        if (mode == LOKA_SCALE_BLOCK_128x1) quant_tile128_kernel<true, true><<<g, 256, 0, s>>>(x, rows, cols, ld, q, scales, 0);
+        else if (transpose_out) quant_tile128_kernel<false, true><<<g, 256, 0, s>>>(x, rows, cols, ld, q, scales, pow2);
+        else quant_tile128_kernel<false, false><<<g, 256, 0, s>>>(x, rows, cols, ld, q, scales, pow2);
+        return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
+    }
     const int64_t ng = loka_scale_count(mode, rows, cols);
     uint32_t* amax_bits = static_cast<uint32_t*>(workspace);
     float* inv = reinterpret_cast<float*>(amax_bits + ng);
@@ -368,14 +449,10 @@ loka_status quantize_launch(const void* x_bf16, int64_t rows, int64_t cols, int6
         dim3 g(static_cast<unsigned>((cols / 8 + 255) / 256),
                static_cast<unsigned>((rows + kColRowsPerBlock - 1) / kColRowsPerBlock));
         amax_col_kernel<<<g, 256, 0, s>>>(x, rows, cols, ld, amax_bits);
-    } else {  // BLOCK_128x128
-        dim3 g(static_cast<unsigned>(cols / 128), static_cast<unsigned>(rows / 128));
-        amax_block128_kernel<<<g, 256, 0, s>>>(x, rows, cols, ld, amax_bits);
     }
     finalize_scales_kernel<<<dim3(static_cast<unsigned>((ng + 255) / 256)), 256, 0, s>>>(amax_bits, inv, scales, ng, pow2);
     if (mode == LOKA_SCALE_TENSOR) launch_cast<LOKA_SCALE_TENSOR>(x, rows, cols, ld, inv, q, transpose_out, s);
-    else if (mode == LOKA_SCALE_COL) launch_cast<LOKA_SCALE_COL>(x, rows, cols, ld, inv, q, transpose_out, s);
-    else launch_cast<LOKA_SCALE_BLOCK_128x128>(x, rows, cols, ld, inv, q, transpose_out, s);
+    else launch_cast<LOKA_SCALE_COL>(x, rows, cols, ld, inv, q, transpose_out, s);
     return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
 }
 

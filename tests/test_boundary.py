@@ -60,7 +60,12 @@ def test_quantize_argument_validation():
     L = B.lib()
     q = L.loka_quantize
     assert q(None, 16, 128, 128, B.SCALE_ROW, 0, FAKE, FAKE, None, 0, None) == B.LOKA_ERR_NULL
-    assert q(FAKE, 16, 128, 128, 7, 0, FAKE, FAKE, None, 0, None) == B.LOKA_ERR_UNSUPPORTED
+    assert q(FAKE, 16, 128, 128, 8, 0, FAKE, FAKE, None, 0, None) == B.LOKA_ERR_UNSUPPORTED          # no such mode
+    assert q(FAKE, 128, 128, 128, B.SCALE_BLOCK_128x1, 0, FAKE, FAKE, None, 0, None) == B.LOKA_ERR_UNSUPPORTED   # needs transpose_out
+    assert q(FAKE, 100, 128, 128, B.SCALE_BLOCK_128x1, 1, FAKE, FAKE, None, 0, None) == B.LOKA_ERR_SHAPE         # rows % 128
+    assert B.loka_scale_count(B.SCALE_BLOCK_128x1, 256, 48) == 2 * 48
+    # a GEMM operand cannot carry that mode (its transposed output is a BLOCK_1x128 operand)
+    assert _gemm(B.make_desc(256, 128, 128, x_mode=B.SCALE_BLOCK_128x1)) == B.LOKA_ERR_UNSUPPORTED
     assert q(FAKE, 0, 128, 128, B.SCALE_ROW, 0, FAKE, FAKE, None, 0, None) == B.LOKA_ERR_SHAPE
     assert q(FAKE, 16, 120, 120, B.SCALE_ROW, 0, FAKE, FAKE, None, 0, None) == B.LOKA_ERR_SHAPE       # cols % 16
     assert q(FAKE, 16, 128, 64, B.SCALE_ROW, 0, FAKE, FAKE, None, 0, None) == B.LOKA_ERR_SHAPE        # ld < cols

@@ -800,6 +800,40 @@ def test_backward_gemms_with_the_forward_entry_points(orc, shape):
     assert rel_fro(dw.cpu().numpy(), ref.numpy()) < 0.06
 
 
+@pytest.mark.parametrize("shape", [(1024, 256, 384), (4096, 512, 512), (65536, 256, 1024)])
+def test_weight_gradient_with_block_scales_along_the_batch(orc, shape):
+    # dW = X^T dY with the block recipe: the contraction runs over the batch rows, so the scale groups do too.  X is
+    # quantized BLOCK_128x1 and dY BLOCK_128x128, both in ONE pass with the output transposed; the GEMM is the forward
+    # entry point with (M', N', K') = (K, N, M), which the library runs split over K (few output tiles, long K).
+    M, K, N = shape
+    x = synth.normal(M, K, seed=2 * M + 1)
+    dy = synth.normal(M, N, seed=2 * N + 1, std=0.02)
+    dy[:, 5] *= 300.0                                        # one channel of the gradient with outliers
+    xtq, sxt = B.loka_quantize(x.to(DEV), B.SCALE_BLOCK_128x1, transpose_out=True)          # [K, M], [K, M/128]
+    dytq, sdyt = B.loka_quantize(dy.to(DEV), B.SCALE_BLOCK_128x128, transpose_out=True)     # [N, M], [M/128, N/128]
+    d = B.make_desc(K, N, M, 1, B.SCALE_BLOCK_1x128, B.SCALE_BLOCK_128x128, B.NORM_NONE)
+    if M >= 2048:
+        assert B.loka_variant_name(B.loka_default_variant(d)) == "splitk128x128"
+    out, dw = B.loka_fp8_gemm_norm(d, xtq, sxt, dytq, sdyt, want_y=True)
+    torch.cuda.synchronize()
+    xtq_o, sxt_o = orc.quantize(synth.bf16_bits(x), orc.SCALE_BLOCK_128x1, transpose_out=True)
+    dytq_o, sdyt_o = orc.quantize(synth.bf16_bits(dy), orc.SCALE_BLOCK_128x128, transpose_out=True)
+    assert np.array_equal(xtq.cpu().numpy(), xtq_o) and np.array_equal(sxt.cpu().numpy().view(np.uint32), sxt_o.view(np.uint32))
+    assert np.array_equal(dytq.cpu().numpy(), dytq_o) and np.array_equal(sdyt.cpu().numpy().view(np.uint32), sdyt_o.view(np.uint32))
+    rows = np.unique(np.linspace(0, K - 1, 24).round().astype(int))      # sampled rows of dW
+    sx_sel = sxt_o.reshape(K, M // 128)[rows].ravel()
+    dw_o, ad = orc.fp8_gemm(np.ascontiguousarray(xtq_o[rows]), sx_sel, orc.SCALE_BLOCK_1x128, dytq_o, sdyt_o,
+                            orc.SCALE_BLOCK_128x128, want_absdot=True)
+    idx = torch.from_numpy(rows).to(DEV)
+    fig = check_fp32_y(dw[idx].cpu().numpy(), dw_o, ad, xtq_o[rows], sx_sel, B.SCALE_BLOCK_1x128, dytq_o, sdyt_o,
+                       B.SCALE_BLOCK_128x128, M, f"dW {shape}")
+    fig.pop("err")
+    print("dW", shape, fig)
+    assert torch.equal(out[idx].view(torch.int16), dw[idx].to(torch.bfloat16).view(torch.int16))     # bf16 O = rounding of Y
+    ref = (x.double().T @ dy.double())[rows]                                # sanity against the unquantized product
+    assert rel_fro(dw[idx].cpu().numpy(), ref.numpy()) < 0.05
+
+
 @pytest.mark.parametrize("recipe", ["row", "block", "block_pow2", "tensor"])
 def test_c5_full_size(orc, recipe):
     w = synth.WORKLOADS["C5"]

@@ -61,6 +61,24 @@ def test_weight_layout_transposed(orc, mode_name):
         _cmp_quant(orc, w, mode, transpose_out=True, what=f"{mode_name} W[{K},{N}]^T")
 
 
+@pytest.mark.parametrize("shape", [(128, 16), (256, 48), (1024, 256), (4096, 1008), (65536, 256), (384, 2064)])
+def test_column_blocks_for_the_weight_gradient_operands(orc, shape):
+    # BLOCK_128x1 with the output transposed: the [cols, rows] codes and [cols][rows/128] scales a BLOCK_1x128 operand
+    # has; one pass over the input
+    rows, cols = shape
+    x = synth.student_t4(rows, cols, seed=rows + cols)
+    x[0:128, 3] = 0                   # an all-zero group
+    x[rows - 2, 5] = 3.0e4            # a single outlier in a group
+    if rows >= 256:
+        x[128:256, 7] = -448.0        # a constant group
+    _cmp_quant(orc, x, B.SCALE_BLOCK_128x1, transpose_out=True, what=f"128x1 {shape}")
+    assert B.lib().loka_quantize_workspace(B.SCALE_BLOCK_128x1, rows, cols, 1) == 0
+    assert B.lib().loka_quantize_workspace(B.SCALE_BLOCK_128x128, 256, 256, 1) == 0
+    with pytest.raises(B.LokaError) as e:
+        B.loka_quantize(x.to(DEV), B.SCALE_BLOCK_128x1, transpose_out=False)
+    assert e.value.status == B.LOKA_ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("cols", [16, 48, 208, 1040, 2064, 8192, 8192 + 512, 16384 + 128])
 def test_ragged_and_long_rows(orc, cols):
     # widths that are not a power of two, and rows beyond the register-resident kernels
