@@ -171,12 +171,140 @@ def run_pair(args):
     }))
 
 
+def run_backward(args):
+    """Backward GEMMs of one layer (Section 3.3, "Trainer Integration": forward and backward GEMMs are routed
+    separately), e.g. C3abwd = the layer of C3a: X [M, K], W [K, N], dY [M, N] (all bf16, resident).
+
+      dX = dY W^T : quantize dY rowwise (one pass); W quantized as it lies, one scale per row k (offline: weights are
+                    static between optimizer steps); FP8 GEMM (M, K, contraction N), bf16 dX.
+      dW = X^T dY : quantize X  BLOCK_128x1  with transposed output (one pass) -> [K, M] codes, [K, M/128] scales,
+                    quantize dY BLOCK_128x128 with transposed output (one pass) -> [N, M] codes, [M/128, N/128] scales;
+                    FP8 GEMM (K, N, contraction M) with block scales, split over K; fp32 + bf16 dW.
+    One JSON line; `value` counts the 4*M*K*N flops of the two GEMMs over the whole step (three quantize calls, two GEMMs).
+    """
+    import ctypes
+
+    import numpy as np
+    import torch
+    from paper_2605_10886_amd import binding as B
+    from paper_2605_10886_amd import synth
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+    sp = ctypes.c_void_p(stream.cuda_stream)
+    L = B.lib()
+    w = synth.WORKLOADS[args.workload[:-3]]
+    M, K, N = w.M, w.K, w.N
+    x_cpu, w_cpu = synth.activations(w), synth.weights(w)
+    dy_cpu = synth.normal(M, N, seed=w.seed + 77, std=0.02)
+    n_sets = max(1, min(8, int(640e6 // (2 * M * (K + N) * 1.5))))
+    xs = [x_cpu.to(dev).clone() for _ in range(n_sets)]
+    dys = [dy_cpu.to(dev).clone() for _ in range(n_sets)]
+    wq, sw = B.loka_quantize(w_cpu.to(dev), B.SCALE_ROW)                       # [K, N] as it lies, scale per k
+    d_dx = B.make_desc(M, K, N, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_NONE)
+    d_dw = B.make_desc(K, N, M, 1, B.SCALE_BLOCK_1x128, B.SCALE_BLOCK_128x128, B.NORM_NONE)
+    dyq = torch.empty(M, N, dtype=torch.uint8, device=dev); sdy = torch.empty(M, dtype=torch.float32, device=dev)
+    xtq = torch.empty(K, M, dtype=torch.uint8, device=dev); sxt = torch.empty(K * (M // 128), dtype=torch.float32, device=dev)
+    dytq = torch.empty(N, M, dtype=torch.uint8, device=dev); sdyt = torch.empty((M // 128) * (N // 128), dtype=torch.float32, device=dev)
+    dx = torch.empty(M, K, dtype=torch.bfloat16, device=dev)
+    dw = torch.empty(K, N, dtype=torch.bfloat16, device=dev); dw32 = torch.empty(K, N, dtype=torch.float32, device=dev)
+    ws_dx = torch.empty(max(16, L.loka_fp8_gemm_norm_workspace(ctypes.byref(d_dx))), dtype=torch.uint8, device=dev)
+    ws_dw = torch.empty(max(16, L.loka_fp8_gemm_norm_workspace(ctypes.byref(d_dw))), dtype=torch.uint8, device=dev)
+
+    def ok(r):
+        assert r == 0, r
+
+    def q_dy_row(i):
+        ok(L.loka_quantize(dys[i % n_sets].data_ptr(), M, N, N, B.SCALE_ROW, 0, dyq.data_ptr(), sdy.data_ptr(), None, 0, sp))
+
+    def q_x_t(i):
+        ok(L.loka_quantize(xs[i % n_sets].data_ptr(), M, K, K, B.SCALE_BLOCK_128x1, 1, xtq.data_ptr(), sxt.data_ptr(), None, 0, sp))
+
+    def q_dy_t(i):
+        ok(L.loka_quantize(dys[i % n_sets].data_ptr(), M, N, N, B.SCALE_BLOCK_128x128, 1, dytq.data_ptr(), sdyt.data_ptr(), None, 0, sp))
+
+    def g_dx():
+        ok(L.loka_fp8_gemm_norm(ctypes.byref(d_dx), dyq.data_ptr(), sdy.data_ptr(), wq.data_ptr(), sw.data_ptr(), None, None,
+                                dx.data_ptr(), None, ws_dx.data_ptr(), ws_dx.numel(), sp))
+
+    def g_dw():
+        ok(L.loka_fp8_gemm_norm(ctypes.byref(d_dw), xtq.data_ptr(), sxt.data_ptr(), dytq.data_ptr(), sdyt.data_ptr(), None, None,
+                                dw.data_ptr(), dw32.data_ptr(), ws_dw.data_ptr(), ws_dw.numel(), sp))
+
+    def step(i):
+        q_dy_row(i); g_dx(); q_x_t(i); q_dy_t(i); g_dw()
+
+    t0 = time.perf_counter()
+    n_settle = 0
+    while (time.perf_counter() - t0) * 1e3 < args.settle_ms:
+        for i in range(4):
+            step(i)
+        torch.cuda.synchronize()
+        n_settle += 4
+    settle_ms = (time.perf_counter() - t0) * 1e3
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    flops = 4.0 * M * K * N
+    k = min(args.steps, 20)
+    parts = {}
+    for name, fn in (("quantize_dY_row", q_dy_row), ("quantize_X_128x1_T", q_x_t), ("quantize_dY_128x128_T", q_dy_t)):
+        parts[name] = float(np.mean(_event_times(lambda: fn(0), k, stream)))
+    q_dy_row(0); q_x_t(0); q_dy_t(0)
+    parts["gemm_dX"] = float(np.mean(_event_times(g_dx, k, stream)))
+    parts["gemm_dW"] = float(np.mean(_event_times(g_dw, k, stream)))
+    bytes_q = {"quantize_dY_row": 3 * M * N + 4 * M, "quantize_X_128x1_T": 3 * M * K + 4 * K * (M // 128),
+               "quantize_dY_128x128_T": 3 * M * N}
+    bytes_dx = M * N + K * N + 2 * M * K                    # codes in, bf16 dX out
+    bytes_dw = K * M + N * M + 6 * K * N + 4 * K * (M // 128)   # codes in, bf16 + fp32 dW out
+    dom, dom_bytes = ("gemm_dX", bytes_dx) if parts["gemm_dX"] >= parts["gemm_dW"] else ("gemm_dW", bytes_dw)
+    gbs = dom_bytes / (parts[dom] * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        thr = oracle.default_threads()
+        n_s = int(max(128, min(M, (3e11 // (2 * K * N)) // 128 * 128)))      # rows of the batch the oracle takes (whole 128-row blocks)
+        xb, dyb = synth.bf16_bits(x_cpu)[:n_s].copy(), synth.bf16_bits(dy_cpu)[:n_s].copy()
+        wq_o, sw_o = oracle.quantize(synth.bf16_bits(w_cpu), oracle.SCALE_ROW)
+        c0 = time.perf_counter()
+        dyq_o, sdy_o = oracle.quantize(dyb, oracle.SCALE_ROW, threads=thr)
+        oracle.fp8_gemm(dyq_o, sdy_o, oracle.SCALE_ROW, wq_o, sw_o, oracle.SCALE_COL, threads=thr)
+        xtq_o, sxt_o = oracle.quantize(xb, oracle.SCALE_BLOCK_128x1, transpose_out=True, threads=thr)
+        dytq_o, sdyt_o = oracle.quantize(dyb, oracle.SCALE_BLOCK_128x128, transpose_out=True, threads=thr)
+        oracle.fp8_gemm(xtq_o, sxt_o, oracle.SCALE_BLOCK_1x128, dytq_o, sdyt_o, oracle.SCALE_BLOCK_128x128, threads=thr)
+        csec = time.perf_counter() - c0
+        cpu = {"value": 4.0 * n_s * K * N / csec / 1e12, "unit": "TFLOP/s", "cores": thr, "kind": "oracle",
+               "sample": f"{n_s} of {M} batch rows of {w.name}'s backward GEMMs (3 quantize passes, dX and dW in fp64), {csec:.1f} s"}
+    print(json.dumps({
+        "metric": "FP8 GEMM+norm TFLOP/s (% of MI355X FP8 peak); quantize/probe HBM GB/s",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8_e4m3 (fp32 accumulate)", "data": "synthetic",
+        "config": {"workload": f"{w.name} backward: dX = dY W^T and dW = X^T dY for X[{M},{K}], W[{K},{N}], dY[{M},{N}] N(0, 0.02^2)",
+                   "step": "quantize dY (row) + dX GEMM + quantize X (128x1, transposed) + quantize dY (128x128, transposed) + dW GEMM (split K)",
+                   "variants": {"dX": B.loka_variant_name(B.loka_default_variant(d_dx)), "dW": B.loka_variant_name(B.loka_default_variant(d_dw))},
+                   "flops_counted": "4*M*K*N", "settle_ms": round(settle_ms, 1), "settle_steps_untimed": n_settle,
+                   "input_sets_rotated": n_sets},
+        "roofline": {"kernel": f"loka_fp8_gemm_norm ({dom})", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": None, "avg_launch_ms": parts[dom], "algorithmic_bytes": dom_bytes},
+        "cpu_baseline": cpu,
+        "kernels": {n_: {"ms": t, **({"GBps": bytes_q[n_] / t / 1e6, "frac_hbm": bytes_q[n_] / t / 1e6 / HBM_PEAK_GBS} if n_ in bytes_q else
+                                    {"TFLOPs": 2.0 * M * K * N / t / 1e9})} for n_, t in parts.items()},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3a", "C3b", "C3pair", "C4", "C5", "C5pair"])
+    ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3a", "C3b", "C3pair", "C4", "C5", "C5pair", "C2bwd", "C3abwd", "C3bbwd"])
     ap.add_argument("--settle-ms", type=float, default=60.0,
                     help="untimed settle phase before the warm-up steps: the step is repeated for at least this long")
     ap.add_argument("--budget", type=float, default=5e-2, help="rel-Frobenius budget the timed variant must meet")
@@ -200,6 +328,8 @@ def main():
 
     if args.workload in ("C3pair", "C5pair"):
         return run_pair(args)
+    if args.workload.endswith("bwd"):
+        return run_backward(args)
 
     import numpy as np
     import torch
@@ -442,7 +572,7 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        n_s = max(16, min(M, int(3e11 // (K * N))))          # ~300 GMAC of fp64 scalar work: 10-20 s on 16 cores
+        n_s = max(16, min(M, int(6e11 // (K * N))))          # up to ~600 GMAC of fp64 scalar work: 10-20 s on 16 cores
         xb = synth.bf16_bits(x_cpu[:M])[:n_s].copy()
         wb = synth.bf16_bits(w_cpu[:K])
         o_xm, o_wm = xm, wm                                   # (the two libraries number the scale modes alike)

@@ -291,14 +291,14 @@ __global__ __launch_bounds__(256) void quant_tile128_kernel(const uint16_t* __re
     __shared__ float inv_s[128];
     __shared__ __attribute__((aligned(16))) uint8_t tile[TRANSPOSE ? 128 * (128 + 16) : 16];   // [c][r], rows padded to 144 bytes
     const int t = static_cast<int>(threadIdx.x), lane = t & 63, wave = t >> 6;
-    const int cc = t & 15, rr = t >> 4;                 // chunk column, row within a sweep
+    const int cc = t & 15, rr = t >> 4;                 // chunk column; the thread's 8 consecutive rows are rr * 8 + [0, 8)
     const int64_t r0 = static_cast<int64_t>(blockIdx.y) * 128, c0 = static_cast<int64_t>(blockIdx.x) * 128;
     const bool live = c0 + cc * 8 < cols;
     u32x4 w[8];
 #pragma unroll
     for (int sw = 0; sw < 8; ++sw) {
         w[sw] = u32x4{0u, 0u, 0u, 0u};
-        if (live) w[sw] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + (r0 + sw * 16 + rr) * ld + c0 + cc * 8));
+        if (live) w[sw] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + (r0 + rr * 8 + sw) * ld + c0 + cc * 8));
     }
     float inv8[8];
     if (COLGROUPS) {
@@ -344,30 +344,40 @@ __global__ __launch_bounds__(256) void quant_tile128_kernel(const uint16_t* __re
 #pragma unroll
         for (int j = 0; j < 8; ++j) inv8[j] = iv;
     }
+    uint32_t lo[8], hi[8];                              // codes of row rr * 8 + sw, columns cc * 8 + [0, 4) and + [4, 8)
 #pragma unroll
     for (int sw = 0; sw < 8; ++sw) {
-        const uint32_t lo = e4m3x4(bf16_lo(w[sw].x) * inv8[0], bf16_hi(w[sw].x) * inv8[1], bf16_lo(w[sw].y) * inv8[2], bf16_hi(w[sw].y) * inv8[3]);
-        const uint32_t hi = e4m3x4(bf16_lo(w[sw].z) * inv8[4], bf16_hi(w[sw].z) * inv8[5], bf16_lo(w[sw].w) * inv8[6], bf16_hi(w[sw].w) * inv8[7]);
-        const int r = sw * 16 + rr;
-        if (TRANSPOSE) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                tile[(cc * 8 + j) * 144 + r] = static_cast<uint8_t>(lo >> (8 * j));
-                tile[(cc * 8 + 4 + j) * 144 + r] = static_cast<uint8_t>(hi >> (8 * j));
-            }
-        } else if (live) {
-            *reinterpret_cast<u32x2*>(q + (r0 + r) * cols + c0 + cc * 8) = u32x2{lo, hi};
-        }
+        lo[sw] = e4m3x4(bf16_lo(w[sw].x) * inv8[0], bf16_hi(w[sw].x) * inv8[1], bf16_lo(w[sw].y) * inv8[2], bf16_hi(w[sw].y) * inv8[3]);
+        hi[sw] = e4m3x4(bf16_lo(w[sw].z) * inv8[4], bf16_hi(w[sw].z) * inv8[5], bf16_lo(w[sw].w) * inv8[6], bf16_hi(w[sw].w) * inv8[7]);
+        if (!TRANSPOSE && live) *reinterpret_cast<u32x2*>(q + (r0 + rr * 8 + sw) * cols + c0 + cc * 8) = u32x2{lo[sw], hi[sw]};
     }
     if (TRANSPOSE) {
+        // the thread's 8 x 8 block of codes is transposed in registers (byte permutes on 4 x 4 sub-blocks), so that each
+        // of its 8 columns becomes one 8-byte run of consecutive rows; the runs go through LDS and leave as 64-byte runs
+        auto t4 = [](uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, uint32_t (&c)[4]) __attribute__((always_inline)) {
+            const uint32_t p0 = __builtin_amdgcn_perm(a1, a0, 0x05010400u), p1 = __builtin_amdgcn_perm(a1, a0, 0x07030602u);
+            const uint32_t p2 = __builtin_amdgcn_perm(a3, a2, 0x05010400u), p3 = __builtin_amdgcn_perm(a3, a2, 0x07030602u);
+            c[0] = __builtin_amdgcn_perm(p2, p0, 0x05040100u); c[1] = __builtin_amdgcn_perm(p2, p0, 0x07060302u);
+            c[2] = __builtin_amdgcn_perm(p3, p1, 0x05040100u); c[3] = __builtin_amdgcn_perm(p3, p1, 0x07060302u);
+        };
+        uint32_t a[4], b[4], c[4], d[4];
+        t4(lo[0], lo[1], lo[2], lo[3], a);                  // columns 0..3, rows 0..3
+        t4(lo[4], lo[5], lo[6], lo[7], b);                  // columns 0..3, rows 4..7
+        t4(hi[0], hi[1], hi[2], hi[3], c);                  // columns 4..7, rows 0..3
+        t4(hi[4], hi[5], hi[6], hi[7], d);                  // columns 4..7, rows 4..7
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            *reinterpret_cast<u32x2*>(tile + (cc * 8 + j) * 144 + rr * 8) = u32x2{a[j], b[j]};
+            *reinterpret_cast<u32x2*>(tile + (cc * 8 + 4 + j) * 144 + rr * 8) = u32x2{c[j], d[j]};
+        }
         __syncthreads();
-        // output row c0 + c: 128 codes; thread -> (c = t / 2, half of 64 bytes)
-        const int c = t >> 1, half = (t & 1) * 64;
-        if (c0 + c < cols) {
-            uint8_t* dst = q + (c0 + c) * rows + r0 + half;
+        // output row c0 + c: 128 codes; thread -> (column t / 2, half of 64 bytes)
+        const int col = t >> 1, half = (t & 1) * 64;
+        if (c0 + col < cols) {
+            uint8_t* dst = q + (c0 + col) * rows + r0 + half;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                *reinterpret_cast<u32x4*>(dst + 16 * j) = *reinterpret_cast<const u32x4*>(tile + c * 144 + half + 16 * j);
+                *reinterpret_cast<u32x4*>(dst + 16 * j) = *reinterpret_cast<const u32x4*>(tile + col * 144 + half + 16 * j);
         }
     }
 }
