@@ -25,9 +25,12 @@ FP8_PEAK_TFLOPS = 5000.0      # MI355X dense FP8 MFMA, published
 BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
-# HBM-side bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# file, scaled by a plain 1 GiB copy (profiles/bench_C5_panel32_256x256.md); counters cannot be read in-process.
-MEASURED_TRAFFIC_BYTES = {("C5", "panel32_256x256"): 1.208e9 + 0.317e9}
+# HBM-side bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
+# (counters cannot be read in-process), scaled by a plain copy of known size in the same runs: FETCH_SIZE x 2 KiB,
+# WRITE_SIZE x 1 KiB (profiles/bench_C5_panel32_256x256.md, profiles/bench_skinny_workloads.md).
+MEASURED_TRAFFIC_BYTES = {("C5", "panel32_256x256"): 1.214e9 + 0.277e9, ("C1", "row32x128"): 0.29e6 + 0.07e6,
+                          ("C2", "wreg32"): 10.9e6 + 16.8e6, ("C3a", "wreg32"): 19.5e6 + 134.2e6,
+                          ("C3b", "panel32_256x256"): 69.9e6 + 34.2e6, ("C4", "strip32"): 85.4e6 + 134.3e6}
 
 RECIPE_NAMES = {(0, 0): "tensor/tensor", (1, 2): "row/col", (3, 4): "1x128/128x128", (5, 6): "1x128/128x128 power-of-two scales"}
 
