@@ -32,6 +32,19 @@ MEASURED_TRAFFIC_BYTES = {("C5", "panel32_256x256"): 1.214e9 + 0.277e9, ("C1", "
                           ("C2", "wreg32"): 10.9e6 + 16.8e6, ("C3a", "wreg32"): 19.5e6 + 134.2e6,
                           ("C3b", "panel32_256x256"): 69.9e6 + 34.2e6, ("C4", "strip32"): 85.4e6 + 134.3e6}
 
+def pick_under(table, budget, usec_bf16):
+    """The library's selection rule (loka_dispatch_select: fastest candidate within the error budget) applied to the
+    candidate table the profiling step has just measured, for one more budget: no further launches."""
+    from paper_2605_10886_amd import binding as B
+    if not table:
+        return None
+    i = B.loka_dispatch_select([r["usec"] for r in table], [r["stats"]["rel_fro"] for r in table], budget, 0.0,
+                               usec_bf16 or 0.0)
+    if i < 0:
+        return "no FP8 candidate (stay in BF16)"
+    return f'{RECIPE_NAMES.get((table[i]["x_mode"], table[i]["w_mode"]))} [{table[i]["variant_name"]}]'
+
+
 RECIPE_NAMES = {(0, 0): "tensor/tensor", (1, 2): "row/col", (3, 4): "1x128/128x128", (5, 6): "1x128/128x128 power-of-two scales"}
 
 
@@ -604,6 +617,7 @@ def main():
                    "dispatch": "skipped (--no-dispatch)" if args.no_dispatch else
                                {"budget_1e-2": "no FP8 candidate (stay in BF16)" if st_strict != B.LOKA_OK else
                                 RECIPE_NAMES.get((ch_strict["x_mode"], ch_strict["w_mode"])),
+                                "budget_3e-2": pick_under(table, 3e-2, ch["usec_bf16"]),
                                 "budget_used": args.budget, "usec_bf16": ch["usec_bf16"],
                                 "candidates": [{"recipe": RECIPE_NAMES.get((r["x_mode"], r["w_mode"])),
                                                 "variant": r["variant_name"], "usec": round(r["usec"], 1),
