@@ -714,21 +714,25 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(const float* __restrict_
     }
 }
 
-// Second kernel of the split-K schedule: one wave per output row adds the row's ksplit partial sums in a fixed order
-// (repeatable bits), takes the row statistics of the sum in registers (two sweeps over the lane's values: no
-// E[y^2] - mean^2 cancellation), normalizes and writes bf16 O (and fp32 Y when asked).  N <= 8192: a lane holds
-// N / 64 values.  part: [ksplit][rows][N] fp32 with rows = batch * M; row r of problem g lies at g * strideO + m * N
-// in O / Y.
+// Second kernel of the split-K schedule: WPR waves per output row (1, or 4 = a whole workgroup when the output has
+// few rows, as a weight gradient does) add the row's ksplit partial sums in a fixed order (repeatable bits; eight
+// partials are requested before the first is added, so the loads overlap while the additions keep their order), take
+// the row statistics of the sum in registers (two sweeps over the thread's values: no E[y^2] - mean^2 cancellation),
+// normalize and write bf16 O (and fp32 Y when asked).  N <= 8192: a thread holds N / (64 WPR) values.
+// part: [ksplit][rows][N] fp32 with rows = batch * M; row r of problem g lies at g * strideO + m * N in O / Y.
 constexpr int kSplitkMaxN = 8192;
+template <int WPR>
 __global__ __launch_bounds__(256) void splitk_norm_rows_kernel(const float* __restrict__ part, int ksplit, int64_t rows,
                                                                int M, int N, int64_t strideO, int norm, float eps,
                                                                const uint16_t* __restrict__ gamma,
                                                                const uint16_t* __restrict__ beta, uint16_t* __restrict__ out,
                                                                float* __restrict__ y) {
-    const int lane = threadIdx.x & 63;
-    const int64_t r = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (r >= rows) return;
-    constexpr int MAXC = kSplitkMaxN / 256;          // float4 chunks per lane
+    constexpr int TPR = 64 * WPR;                    // threads per row
+    __shared__ float red[4];
+    const int tr = threadIdx.x & (TPR - 1);
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * (256 / TPR) + threadIdx.x / TPR;
+    if (WPR == 1 && r >= rows) return;               // (WPR == 4: one row per workgroup, the grid is exactly the rows)
+    constexpr int MAXC = kSplitkMaxN / (4 * TPR);    // float4 chunks per thread
     v4f v[MAXC];
     const int chunks = N >> 2;
     const int64_t slab = rows * static_cast<int64_t>(N);
@@ -736,10 +740,19 @@ __global__ __launch_bounds__(256) void splitk_norm_rows_kernel(const float* __re
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-        const int c = lane + 64 * j;
+        const int c = tr + TPR * j;
         v[j] = v4f{0.f, 0.f, 0.f, 0.f};
         if (c < chunks) {
-            for (int k = 0; k < ksplit; ++k) v[j] += *reinterpret_cast<const v4f*>(src + k * slab + 4 * c);
+            const float* sc = src + 4 * c;
+            int k = 0;
+            for (; k + 8 <= ksplit; k += 8) {
+                v4f t[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(sc + (k + u) * slab));
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[j] += t[u];
+            }
+            for (; k < ksplit; ++k) v[j] += __builtin_nontemporal_load(reinterpret_cast<const v4f*>(sc + k * slab));
             s += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
         }
     }
@@ -748,32 +761,39 @@ __global__ __launch_bounds__(256) void splitk_norm_rows_kernel(const float* __re
     if (y) {
 #pragma unroll
         for (int j = 0; j < MAXC; ++j) {
-            const int c = lane + 64 * j;
+            const int c = tr + TPR * j;
             if (c < chunks) *reinterpret_cast<v4f*>(y + obase + 4 * c) = v[j];
         }
     }
+    // sum over the row's threads: the wave by shuffles, the (up to four) waves through LDS in wave order
+    auto row_sum = [&](float x) __attribute__((always_inline)) {
+        for (int msk = 1; msk < 64; msk <<= 1) x += wave_shfl_xor(x, msk);
+        if (WPR > 1) {
+            __syncthreads();                         // (the previous use of red has been read)
+            if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+            __syncthreads();
+            x = (red[0] + red[1]) + (red[2] + red[3]);
+        }
+        return x;
+    };
     float mean = 0.f, rstd = 1.f;
     if (norm == LOKA_NORM_LAYERNORM || norm == LOKA_NORM_RMSNORM) {
-        if (norm == LOKA_NORM_LAYERNORM) {
-            for (int msk = 1; msk < 64; msk <<= 1) s += wave_shfl_xor(s, msk);
-            mean = s / static_cast<float>(N);
-        }
+        if (norm == LOKA_NORM_LAYERNORM) mean = row_sum(s) / static_cast<float>(N);
         float m2 = 0.f;
 #pragma unroll
         for (int j = 0; j < MAXC; ++j) {
-            const int c = lane + 64 * j;
+            const int c = tr + TPR * j;
             if (c < chunks) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) { const float d = v[j][e] - mean; m2 += d * d; }
             }
         }
-        for (int msk = 1; msk < 64; msk <<= 1) m2 += wave_shfl_xor(m2, msk);
-        rstd = 1.0f / sqrtf(m2 / static_cast<float>(N) + eps);
+        rstd = 1.0f / sqrtf(row_sum(m2) / static_cast<float>(N) + eps);
     }
     const bool has_g = gamma != nullptr && norm != LOKA_NORM_NONE, has_b = beta != nullptr && norm == LOKA_NORM_LAYERNORM;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-        const int c = lane + 64 * j;
+        const int c = tr + TPR * j;
         if (c >= chunks) continue;
         float o[4];
 #pragma unroll
@@ -1214,8 +1234,13 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         grid.y = static_cast<unsigned>(p.ksplit);
         vi.launch(p, blockwise, grid, s);
         const int64_t rows = static_cast<int64_t>(d->batch) * d->M;
-        splitk_norm_rows_kernel<<<dim3(static_cast<unsigned>((rows + 3) / 4)), 256, 0, s>>>(
-            p.part, p.ksplit, rows, p.M, p.N, p.strideO, d->norm, d->eps, p.gamma, p.beta, p.out, y);
+        // few rows (a weight gradient's K x N output): a workgroup per row, else a wave per row
+        if (rows < 8192)
+            splitk_norm_rows_kernel<4><<<dim3(static_cast<unsigned>(rows)), 256, 0, s>>>(
+                p.part, p.ksplit, rows, p.M, p.N, p.strideO, d->norm, d->eps, p.gamma, p.beta, p.out, y);
+        else
+            splitk_norm_rows_kernel<1><<<dim3(static_cast<unsigned>((rows + 3) / 4)), 256, 0, s>>>(
+                p.part, p.ksplit, rows, p.M, p.N, p.strideO, d->norm, d->eps, p.gamma, p.beta, p.out, y);
         return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
     }
     vi.launch(p, blockwise, grid, s);
