@@ -425,11 +425,22 @@ def main():
 
     it = [0]
 
+    fused_entry = ["loka_fp8_linear_norm"]
+
     def fused_step(xin):
-        r = L.loka_fp8_linear_norm(ctypes.byref(desc), xin.data_ptr(), wq.data_ptr(), sw.data_ptr(), None, None,
-                                   out.data_ptr(), None, None, sp)
+        # quantization inside the GEMM kernel's main loop where a kernel has that form; else the streaming kernel's
+        # quantize prologue (one launch, the quantized activation handed back in xq / sx)
+        r = B.LOKA_ERR_UNSUPPORTED
+        if fused_entry[0] == "loka_fp8_linear_norm":
+            r = L.loka_fp8_linear_norm(ctypes.byref(desc), xin.data_ptr(), wq.data_ptr(), sw.data_ptr(), None, None,
+                                       out.data_ptr(), None, None, sp)
+            if r == B.LOKA_ERR_UNSUPPORTED:
+                fused_entry[0] = "loka_fp8_linear_norm_xq"
+        if fused_entry[0] == "loka_fp8_linear_norm_xq":
+            r = L.loka_fp8_linear_norm_xq(ctypes.byref(desc), xin.data_ptr(), xq.data_ptr(), sx.data_ptr(), wq.data_ptr(),
+                                          sw.data_ptr(), None, None, out.data_ptr(), None, sp)
         if r != 0:
-            print(f"bench.py: --fused: loka_fp8_linear_norm returned {r} for {w.name} (shape or recipe not covered)",
+            print(f"bench.py: --fused: {fused_entry[0]} returned {r} for {w.name} (shape or recipe not covered)",
                   file=sys.stderr)
             sys.exit(3)
 
@@ -608,7 +619,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8_e4m3 (fp32 accumulate)", "data": "synthetic",
         "config": {"workload": f"{w.name}: X[{G}x{M},{K}] {w.x_dist}, W[{K},{N}] N(0,1/K), {w.norm}",
-                   "step": ("one call: rowwise quantization, FP8 GEMM, scales and row norm in one kernel (bf16 in, bf16 out)"
+                   "step": (f"one call ({fused_entry[0]}): rowwise quantization, FP8 GEMM, scales and row norm in one kernel (bf16 in, bf16 out)"
                             if args.fused else "quantize X + FP8 GEMM with fused scales and row norm (bf16 out)"),
                    "recipe": RECIPE_NAMES.get((xm, wm), f"{xm}/{wm}"), "variant": B.loka_variant_name(variant),
                    "flops_counted": "2*M*K*N of the FP8 GEMM", "pct_fp8_peak": 100 * value / FP8_PEAK_TFLOPS,

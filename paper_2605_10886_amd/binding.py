@@ -76,6 +76,8 @@ _SIGNATURES = [
                                    c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     ("loka_fp8_linear_norm", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                      c_void_p, c_void_p]),
+    ("loka_fp8_linear_norm_xq", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                        c_void_p, c_void_p, c_void_p]),
     ("loka_fp8_gemm_norm_check", c_int, [POINTER(GemmDesc), c_void_p, c_size_t, c_void_p]),
     ("loka_fp8_gemm_norm_static", c_int, [POINTER(GemmDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                           c_void_p, c_void_p, c_void_p]),
@@ -231,6 +233,23 @@ def loka_fp8_linear_norm(desc: GemmDesc, x, wq, sw, gamma=None, beta=None, want_
     _check(lib().loka_fp8_linear_norm(byref(desc), _ptr(x), _ptr(wq), _ptr(sw), _ptr(gamma), _ptr(beta), _ptr(out), _ptr(y),
                                       _ptr(sx), _stream()), "loka_fp8_linear_norm")
     return out, y, sx
+
+
+def loka_fp8_linear_norm_xq(desc: GemmDesc, x, wq, sw, gamma=None, beta=None, want_y: bool = False, out=None, xq=None, sx=None):
+    """One launch: every workgroup quantizes the rows it consumes (rowwise), then GEMM + norm.  Returns (O bf16, Y fp32 or
+    None, xq codes, sx row scales)."""
+    rows = desc.batch * desc.M
+    dev = x.device
+    if out is None:
+        out = torch.empty((rows, desc.N), dtype=torch.bfloat16, device=dev)
+    if xq is None:
+        xq = torch.empty((rows, desc.K), dtype=torch.uint8, device=dev)
+    if sx is None:
+        sx = torch.empty(rows, dtype=torch.float32, device=dev)
+    y = torch.empty((rows, desc.N), dtype=torch.float32, device=dev) if want_y else None
+    _check(lib().loka_fp8_linear_norm_xq(byref(desc), _ptr(x), _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), _ptr(gamma), _ptr(beta),
+                                         _ptr(out), _ptr(y), _stream()), "loka_fp8_linear_norm_xq")
+    return out, y, xq, sx
 
 
 def loka_fp8_gemm_norm_check(desc: GemmDesc, workspace) -> int:

@@ -23,6 +23,10 @@ bool variant_is_streaming(int);
 bool variant_is_strip(int);
 bool variant_is_panel32(int);
 bool variant_supports_fused(const loka_gemm_desc*, int);
+bool variant_supports_xq(const loka_gemm_desc*, int);
+int variant_xq_default(const loka_gemm_desc*);
+loka_status fp8_linear_norm_xq_launch(const loka_gemm_desc*, int, const void*, uint8_t*, float*, const uint8_t*, const float*,
+                                      const void*, const void*, void*, float*, hipStream_t);
 int variant_fused_default(const loka_gemm_desc*);
 loka_status fp8_linear_norm_launch(const loka_gemm_desc*, int, const void*, const uint8_t*, const float*, const void*,
                                    const void*, void*, float*, float*, hipStream_t);
@@ -249,6 +253,22 @@ loka_status loka_fp8_linear_norm(const loka_gemm_desc* desc, const void* x_bf16,
     if (v < 0 || !variant_supports_fused(desc, v)) return LOKA_ERR_UNSUPPORTED;
     return fp8_linear_norm_launch(desc, v, x_bf16, wq, sw, gamma_bf16, beta_bf16, out_bf16, y_fp32, sx_out,
                                   static_cast<hipStream_t>(hip_stream));
+}
+
+loka_status loka_fp8_linear_norm_xq(const loka_gemm_desc* desc, const void* x_bf16, uint8_t* xq_out, float* sx_out,
+                                    const uint8_t* wq, const float* sw, const void* gamma_bf16, const void* beta_bf16,
+                                    void* out_bf16, float* y_fp32, void* hip_stream) {
+    if (!desc || !x_bf16 || !xq_out || !sx_out || !wq || !sw || !out_bf16) return LOKA_ERR_NULL;
+    const loka_status st = validate_desc(desc, true);
+    if (st != LOKA_OK) return st;
+    if (desc->x_mode != LOKA_SCALE_ROW) return LOKA_ERR_UNSUPPORTED;
+    if (!aligned16(x_bf16) || !aligned16(xq_out) || !aligned16(sx_out) || !aligned16(wq) || !aligned16(sw) ||
+        !aligned16(out_bf16) || !aligned16(y_fp32) || !aligned16(gamma_bf16) || !aligned16(beta_bf16))
+        return LOKA_ERR_ALIGN;
+    const int v = desc->variant >= 0 ? desc->variant : variant_xq_default(desc);
+    if (v < 0 || !variant_supports_xq(desc, v)) return LOKA_ERR_UNSUPPORTED;
+    return fp8_linear_norm_xq_launch(desc, v, x_bf16, xq_out, sx_out, wq, sw, gamma_bf16, beta_bf16, out_bf16, y_fp32,
+                                     static_cast<hipStream_t>(hip_stream));
 }
 
 // The kernels with an FP8-output epilogue: the two that keep a whole output row inside one workgroup (streaming) or

@@ -940,6 +940,17 @@ bool variant_supports_fused(const loka_gemm_desc* d, int v) {
     if (kVariants[v].name == kStripName) return strip_supports_fused(d->M, d->N, d->K);
     return false;
 }
+// the streaming kernel with its quantize prologue (loka_fp8_linear_norm_xq): every shape the kernel covers, row scales
+// for X, one problem or separate activations per problem
+bool variant_supports_xq(const loka_gemm_desc* d, int v) {
+    if (v < 0 || v >= kNumVariants || !variant_supports(d, v) || d->x_mode != LOKA_SCALE_ROW) return false;
+    return kVariants[v].name == kWregName && (d->batch == 1 || d->strideX != 0);
+}
+int variant_xq_default(const loka_gemm_desc* d) {
+    for (int v = 0; v < kNumVariants; ++v)
+        if (variant_supports_xq(d, v)) return v;
+    return -1;
+}
 // the kernel the fused entry point uses when the caller names none: the strip kernel where it applies (waves that
 // never synchronize, one strip each), else the streaming kernel
 int variant_fused_default(const loka_gemm_desc* d) {
@@ -1118,7 +1129,7 @@ void test_set_spin_limit(long long polls) { g_spin_override.store(polls, std::me
 static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const uint8_t* xq, const float* sx, const uint8_t* wq,
                                         const float* sw, const void* gamma, const void* beta, void* out, float* y,
                                         uint8_t* outq, float* outs, const void* x_bf16, float* sx_out, void* workspace,
-                                        hipStream_t s);
+                                        hipStream_t s, bool quantize_prologue = false);
 
 loka_status fp8_gemm_norm_launch(const loka_gemm_desc* d, int v, const uint8_t* xq, const float* sx, const uint8_t* wq,
                                  const float* sw, const void* gamma, const void* beta, void* out, float* y,
@@ -1133,10 +1144,20 @@ loka_status fp8_linear_norm_launch(const loka_gemm_desc* d, int v, const void* x
     return gemm_norm_launch_impl(d, v, nullptr, nullptr, wq, sw, gamma, beta, out, y, nullptr, nullptr, x_bf16, sx_out, nullptr, s);
 }
 
+// bf16 X quantized row by row by the workgroup that consumes the rows, codes and scales handed back (v must be the
+// streaming kernel's variant; every shape it covers)
+loka_status fp8_linear_norm_xq_launch(const loka_gemm_desc* d, int v, const void* x_bf16, uint8_t* xq_out, float* sx_out,
+                                      const uint8_t* wq, const float* sw, const void* gamma, const void* beta, void* out,
+                                      float* y, hipStream_t s) {
+    if (!variant_supports_xq(d, v)) return LOKA_ERR_UNSUPPORTED;
+    return gemm_norm_launch_impl(d, v, xq_out, sx_out, wq, sw, gamma, beta, out, y, nullptr, nullptr, x_bf16, nullptr, nullptr, s,
+                                 true);
+}
+
 static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const uint8_t* xq, const float* sx, const uint8_t* wq,
                                         const float* sw, const void* gamma, const void* beta, void* out, float* y,
                                         uint8_t* outq, float* outs, const void* x_bf16, float* sx_out, void* workspace,
-                                        hipStream_t s) {
+                                        hipStream_t s, bool quantize_prologue) {
     const VariantInfo& vi = kVariants[v];
     const bool blockwise = scale_mode_is_block(d->x_mode);
     GemmParams p{};
@@ -1152,6 +1173,7 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
     p.out = static_cast<uint16_t*>(out); p.y = y;
     p.outq = outq; p.outs = outs;
     p.xb = static_cast<const uint16_t*>(x_bf16); p.sx_out = sx_out;
+    p.qpro = quantize_prologue ? 1 : 0;
     // FP8 output: the row stays inside one workgroup (streaming kernel) or one wave (strip kernel), or - panel kernel -
     // the row amax crosses the workgroups: as the row's extreme pre-norm values along with the row statistics when
     // there is no gamma / beta (the normalized value then grows with the pre-norm value), else in a second exchange.
@@ -1178,7 +1200,7 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         const void* fn = nullptr;
         size_t lds = 0;
         const int wgs = vi.name == kWregName
-                            ? wreg_plan(d->M, d->N, d->K, d->batch, cus, p.outq != nullptr, p.xb != nullptr, &fn, &lds)
+                            ? wreg_plan(d->M, d->N, d->K, d->batch, cus, p.outq != nullptr, p.xb != nullptr && !p.qpro, &fn, &lds)
                             : strip_plan(d->M, d->N, d->K, d->batch, cus, p.xb != nullptr, p.outq != nullptr, &fn, &lds);
         if (wgs <= 0) return LOKA_ERR_UNSUPPORTED;
         if (prepare_fn(dev, fn, vi.threads, lds, nullptr) != LOKA_OK) return LOKA_ERR_HIP;

@@ -25,6 +25,7 @@ struct GemmParams {
     float* outs;           // ... and their row scales [batch][M]
     const uint16_t* xb;    // fused quantization (streaming kernel): bf16 X [batch][M][K] instead of X / sx ...
     float* sx_out;         // ... and, optionally, where the row scales it computes are written [batch][M]
+    int qpro;              // quantize prologue (streaming kernel): xb is quantized row by row into X / sx (written, then read back)
     float* y;
     int norm;              // loka_norm
     int block_n, act;      // LOKA_NORM_BLOCKNORM group width; loka_act

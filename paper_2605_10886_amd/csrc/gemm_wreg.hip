@@ -55,6 +55,147 @@ struct WregCfg {
     static_assert(LPW >= 1, "a block is at least 4 KB");
 };
 
+// Quantize prologue (GemmParams::qpro): the workgroup first quantizes ITS OWN rows of the bf16 activation - row
+// blocks [b0, b1), the only ones it will read - exactly as the quantize entry point would (row amax, scale = amax /
+// 448, code = e4m3(x * (448 / amax)); same helper functions, same bits) and writes codes and row scales to global
+// memory where the caller wants them.  The layer costs one launch instead of two.  The bf16 rows of the first QB
+// blocks are requested at kernel entry and travel while the weights are loaded; they are converted once the weights
+// are in registers, and the codes of the blocks the ring would have requested first go straight into their ring slots
+// (the main loop starts without a round trip for X).  Later blocks stream back from global memory (this XCD's L2)
+// like any FP8 input: no other workgroup reads these rows, so the only ordering needed is inside the workgroup -
+// every wave waits for its stores to be acknowledged (s_waitcnt vmcnt(0)) before the barrier in front of the first
+// such read.
+// Wave w owns rows [w RB / 8, +RB / 8) of a block; a row is spread over CH_ROW consecutive lanes (or over IPR loads
+// of a whole wave).
+template <class C, int KB, int RB>
+struct QuantPrologue {
+    static constexpr int CH_ROW = KB / 8;                                  // 16-byte chunks of bf16 per row
+    static constexpr int RPI = CH_ROW >= 64 ? 1 : 64 / CH_ROW;             // rows per wave instruction
+    static constexpr int IPR = CH_ROW >= 64 ? CH_ROW / 64 : 1;             // instructions per row
+    static constexpr int RW = RB / 8;                                      // rows per wave and block
+    static constexpr int NLD = RW * IPR / RPI;                             // loads per lane and block
+    static constexpr int NRG = NLD / IPR;                                  // rows per lane and block
+    static constexpr int QB = 16 / NLD >= 1 ? 16 / NLD : 1;                // blocks per chunk: 64 registers of raw bf16
+    static_assert(RW * IPR % RPI == 0 && NLD >= 1 && NRG <= 16 && CH_ROW >= 16, "quantize prologue: block shape");
+    static_assert(QB >= C::NBUF - 1, "the blocks the ring starts with lie in the first chunk");
+
+    // requests the bf16 rows of blocks [bb, bb + QB) (below b1)
+    static __device__ __forceinline__ void fetch(const GemmParams& p, int bb, int b1, int blocks_per_problem, int wave,
+                                                 u32x4 (&raw)[QB][NLD]) {
+        int lv = static_cast<int>(threadIdx.x) & 63;
+        asm volatile("; lane id" : "+v"(lv));
+#pragma unroll
+        for (int u = 0; u < QB; ++u) {
+            // always QB * NLD loads, so that a caller can wait for "all but these": a block past the end is requested
+            // beyond the descriptor's bound and reads as zeros
+            const bool dead = bb + u >= b1;                                // (uniform)
+            const int b = dead ? bb : bb + u;
+            const int g = b / blocks_per_problem, m0 = (b - g * blocks_per_problem) * RB;
+            const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<uint16_t*>(p.xb + static_cast<int64_t>(g) * p.strideX), 0, static_cast<unsigned>(p.M) * (2u * KB), 0x00020000);
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) {
+                const int row = wave * RW + (j / IPR) * RPI + (IPR == 1 ? lv / CH_ROW : 0);
+                const int chunk = IPR == 1 ? lv % CH_ROW : (j % IPR) * 64 + lv;
+                // (the whole offset is the per-lane one, which the descriptor's bound applies to: rows past M read as zeros)
+                const unsigned off = static_cast<unsigned>(m0 + row) * (2u * KB) + static_cast<unsigned>(chunk * 16);
+                raw[u][j] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(xr, dead ? 0xFFFFFF00u : off, 0, 0));
+            }
+        }
+    }
+
+    // converts them (the loads have landed) and stores codes and scales to global memory; blocks below lds_end also
+    // into their ring slots, in the layout the loads-to-LDS produce.  The chunk's QB * NRG <= 16 rows per lane group
+    // share ONE division pair per lane (lane i of a row's lane group computes the scale and factor of the chunk's i-th
+    // row).  The pass is bound by its vector instructions (two waves per SIMD, every element costs a handful), so the
+    // instruction count is what is kept down.
+    static __device__ __forceinline__ void convert(const GemmParams& p, int bb, int b1, int blocks_per_problem, int wave,
+                                                   const u32x4 (&raw)[QB][NLD], uint8_t* smem, int lds_end) {
+        static_assert(QB * NRG <= 16, "one row per lane of a 16-lane group");
+        int lv = static_cast<int>(threadIdx.x) & 63;
+        asm volatile("; lane id" : "+v"(lv));
+        // row amax: integer max of the 15-bit magnitudes (exact), lanes of the row by xor shuffles
+        // (a lane's 8 or 16 magnitudes as packed 16-bit maxima; the 16 lanes of a row of the data-parallel primitives by
+        // four of those, with no LDS round trip; rows of lanes by xor shuffles)
+        typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+        unsigned am[QB][NRG];
+#pragma unroll
+        for (int u = 0; u < QB; ++u) {
+            if (bb + u >= b1) {                                             // (uniform) nothing was fetched
+#pragma unroll
+                for (int rg = 0; rg < NRG; ++rg) am[u][rg] = 0u;
+                continue;
+            }
+#pragma unroll
+            for (int rg = 0; rg < NRG; ++rg) {
+                us2 a2 = {0, 0};
+#pragma unroll
+                for (int i = 0; i < IPR; ++i) {
+                    const u32x4 w = raw[u][rg * IPR + i];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a2 = __builtin_elementwise_max(a2, __builtin_bit_cast(us2, w[e] & 0x7FFF7FFFu));
+                }
+                unsigned a = a2[0] > a2[1] ? a2[0] : a2[1];
+                unsigned o;
+                o = static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(a), 0xB1, 0xF, 0xF, false));   // lane ^ 1
+                a = a > o ? a : o;
+                o = static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(a), 0x4E, 0xF, 0xF, false));   // lane ^ 2
+                a = a > o ? a : o;
+                o = static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(a), 0x141, 0xF, 0xF, false));  // the other quad of 8
+                a = a > o ? a : o;
+                o = static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(a), 0x140, 0xF, 0xF, false));  // the other half of 16
+                a = a > o ? a : o;
+#pragma unroll
+                for (int msk = 16; msk < (CH_ROW < 64 ? CH_ROW : 64); msk <<= 1) {
+                    o = static_cast<unsigned>(__shfl_xor(static_cast<int>(a), msk, 64));
+                    a = a > o ? a : o;
+                }
+                am[u][rg] = a;
+            }
+        }
+        unsigned mine = am[0][0];
+#pragma unroll
+        for (int u = 0; u < QB; ++u)
+#pragma unroll
+            for (int rg = 0; rg < NRG; ++rg) mine = (lv & 15) == u * NRG + rg ? am[u][rg] : mine;
+        float scale_l, inv_l;
+        group_scale(__uint_as_float(mine << 16), scale_l, inv_l);
+        const int grp_base = IPR == 1 ? (lv / CH_ROW) * CH_ROW : 0;         // first lane of this lane's row group
+#pragma unroll
+        for (int u = 0; u < QB; ++u) {
+            if (bb + u >= b1) continue;                                     // (uniform)
+            constexpr bool dead = false;
+            const int b = bb + u;
+            const int g = b / blocks_per_problem, m0 = (b - g * blocks_per_problem) * RB;
+            uint8_t* const xq = const_cast<uint8_t*>(p.X) + static_cast<int64_t>(g) * p.strideX;
+            float* const sxo = const_cast<float*>(p.sx) + static_cast<int64_t>(g) * p.strideSx;
+            const bool to_lds = b < lds_end;                                // (uniform)
+            uint8_t* const dst = smem + C::OFF_X + (b % C::NBUF) * C::XBYTES;
+            float* const sxl = reinterpret_cast<float*>(smem + C::OFF_SX + (b % C::NBUF) * 4 * C::SXL * 256);
+#pragma unroll
+            for (int rg = 0; rg < NRG; ++rg) {
+                const float scale = __shfl(scale_l, grp_base + u * NRG + rg, 64), inv = __shfl(inv_l, grp_base + u * NRG + rg, 64);
+                const int row = wave * RW + rg * RPI + (IPR == 1 ? lv / CH_ROW : 0);
+                const bool live = !dead && m0 + row < p.M;
+#pragma unroll
+                for (int i = 0; i < IPR; ++i) {
+                    const u32x4 w = raw[u][rg * IPR + i];
+                    const int chunk = IPR == 1 ? lv % CH_ROW : i * 64 + lv;  // 8 elements -> 8 codes = half a 16-byte chunk
+                    u32x2 o;
+                    o.x = e4m3x4(bf16_lo(w.x) * inv, bf16_hi(w.x) * inv, bf16_lo(w.y) * inv, bf16_hi(w.y) * inv);
+                    o.y = e4m3x4(bf16_lo(w.z) * inv, bf16_hi(w.z) * inv, bf16_lo(w.w) * inv, bf16_hi(w.w) * inv);
+                    if (live) *reinterpret_cast<u32x2*>(xq + static_cast<int64_t>(m0 + row) * KB + chunk * 8) = o;
+                    if (live && chunk == 0) sxo[m0 + row] = scale;
+                    if (to_lds) {
+                        *reinterpret_cast<u32x2*>(dst + row * KB + ((((chunk >> 1) ^ (row & (C::SWIN - 1))) << 4) | ((chunk & 1) << 3))) = o;
+                        if (chunk == 0) sxl[row] = scale;
+                    }
+                }
+            }
+        }
+    }
+};
+
 template <int WNC, int KS, int RT, bool FP8OUT, bool BF16IN>
 __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, const int blocks_per_problem) {
     using C = WregCfg<WNC, KS, RT>;
@@ -197,7 +338,9 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
     // reads straight from global memory put 8x the requests on the same few L2 lines and take twice as long).
     // The staging area overlays the X ring and the output buffer: callers re-request X afterwards.
     v8i wreg[NIW][KS];
-    auto load_problem = [&](int g) __attribute__((always_inline)) {
+    using QP = QuantPrologue<C, KB, RB>;
+    u32x4 rawq[QP::QB][QP::NLD];
+    auto load_problem = [&](int g, bool first) __attribute__((always_inline)) {
         constexpr int RROWS = 131072 / KB;                              // W rows per round
         constexpr int ROUNDS = (NT + RROWS - 1) / RROWS;
         int lv = lane;
@@ -217,7 +360,15 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void*)(smem + ld * 1024), 16,
                                                          row * KB + ((pos ^ (row & KEYMASK)) << 4), r * RROWS * KB, 0, 0);
             }
-            wait_vmcnt<0>();
+            // quantize prologue: the bf16 rows of the workgroup's first blocks are requested BEHIND the first round of W
+            // (loads return in order: W, which comes from L2, is not held up by rows that come from HBM) and travel
+            // while W's fragments are read and the next round is fetched
+            if (!BF16IN && r == 0 && first && p.qpro) {
+                QP::fetch(p, b0, b1, blocks_per_problem, wave, rawq);
+                wait_vmcnt<QP::QB * QP::NLD>();
+            } else {
+                wait_vmcnt<0>();
+            }
             __syncthreads();
 #pragma unroll
             for (int ni = 0; ni < NIW; ++ni) {
@@ -248,13 +399,31 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         }
     };
     // W and the tables of problem g, then the first requests for X from block `bf` on
-    auto start_problem = [&](int g, int bf) __attribute__((always_inline)) {
-        load_problem(g);
+    const bool qpro = !BF16IN && p.qpro != 0;
+    bool ack_pending = false;      // quantize prologue: stores of codes that will be read back are not yet known to have arrived
+    auto start_problem = [&](int g, int bf, bool first) __attribute__((always_inline)) {
+        load_problem(g, first);
         if (BF16IN) {
             fetch(bf);
             wait_vmcnt<0>();
             convert(bf);
             if (bf + 1 < b1) fetch(bf + 1);
+        } else if (qpro && first) {
+            // (load_problem has waited for every load of this wave and ended with a barrier: the rows are here, the
+            // ring is free)  The blocks the ring would request now get their codes directly; the rest of the
+            // workgroup's blocks are converted chunk by chunk; then every store must be acknowledged before the
+            // first block is read back
+            wait_vmcnt<0>();
+            QP::convert(p, b0, b1, blocks_per_problem, wave, rawq, smem, bf + NBUF - 1);
+            for (int bb = b0 + QP::QB; bb < b1; bb += QP::QB) {
+                QP::fetch(p, bb, b1, blocks_per_problem, wave, rawq);
+                wait_vmcnt<0>();
+                QP::convert(p, bb, b1, blocks_per_problem, wave, rawq, smem, 0);
+            }
+            // blocks beyond the ring's first ones - and every block of a later problem, whose start requests its
+            // blocks anew - are read back from global memory: not before every wave's stores have been acknowledged,
+            // which the first iteration of the main loop checks after its MFMAs
+            ack_pending = b1 - bf > NBUF - 1 || (b1 - 1) / blocks_per_problem != bf / blocks_per_problem;
         } else if (loader) {
 #pragma unroll
             for (int i = 0; i < NBUF - 1; ++i)
@@ -264,7 +433,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
     };
 
     int cur_g = b0 / blocks_per_problem;
-    start_problem(cur_g, b0);
+    start_problem(cur_g, b0, true);
 
     // Deferred stores (bf16 output from FP8 input): a finished block is not written out at its end by the four
     // storer waves, where the other four would wait at the next barrier while the store path takes its 64 bytes
@@ -344,7 +513,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
             }
             // (the staging of W overwrites the X blocks requested so far: they are requested again)
             if (loader || BF16IN) wait_vmcnt<0>();
-            start_problem(g, b);
+            start_problem(g, b, false);
             cur_g = g;
         }
         if (BF16IN) {
@@ -362,7 +531,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         }
         if (BF16IN) {
             if (b + 2 < b1) fetch(b + 2);                                // in flight for a whole iteration
-        } else if (loader && b + NBUF - 1 < b1) {
+        } else if (loader && b + NBUF - 1 < b1 && !ack_pending) {
             issue_block(b + NBUF - 1);                                  // into the slot block b - 1 left
         }
 
@@ -431,6 +600,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         if (DEFER && pending) mma_loop(std::true_type{}); else mma_loop(std::false_type{});
         if (DEFER) pending = false;                                     // the previous block is on its way
         __builtin_amdgcn_sched_barrier(0);
+        if (!BF16IN && ack_pending) wait_vmcnt<0>();                    // (quantize prologue) this wave's codes have arrived ...
 
         // ---- scales, row statistics (lane -> pair of lanes with the same row -> the 8 waves through LDS)
         const float* sxl = reinterpret_cast<const float*>(smem + C::OFF_SX + (b % NBUF) * 4 * SXL * 256);
@@ -548,6 +718,11 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
             }
         } else if (DEFER) {
             lds_barrier();      // every wave has read its part of the previous block out of the staging buffer
+        }
+        if (!BF16IN && ack_pending) {
+            // ... and, a barrier later, every wave's: the first block that is read back may be requested
+            if (loader && b + NBUF - 1 < b1) issue_block(b + NBUF - 1);
+            ack_pending = false;
         }
 
         // normalized (+ affine, + activation) values of 8 consecutive columns of row tile rt, as packed bf16
@@ -673,7 +848,7 @@ constexpr bool kWregFused = WNC * KS < 512;
 
 template <int WNC, int KS, int RT>
 void launch_wreg(const GemmParams& p, int bpp, dim3 grid, hipStream_t s) {
-    if (p.xb) {
+    if (p.xb && !p.qpro) {
         if constexpr (kWregFused<WNC, KS, RT>)
             gemm_wreg_kernel<WNC, KS, RT, false, true><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);
     } else if (p.outq) gemm_wreg_kernel<WNC, KS, RT, true, false><<<grid, 512, WregCfg<WNC, KS, RT>::LDS, s>>>(p, bpp);

@@ -146,6 +146,27 @@ def test_fp8_output_argument_validation():
     assert f8(B.make_desc(1000, 2048, 100)) == B.LOKA_ERR_SHAPE
 
 
+def test_quantize_prologue_argument_validation():
+    L = B.lib()
+
+    def xq(desc, x=FAKE, q=FAKE, sx=FAKE, out=FAKE):
+        return L.loka_fp8_linear_norm_xq(ctypes.byref(desc), x, q, sx, FAKE, FAKE, None, None, out, None, None)
+
+    skinny = B.make_desc(4096, 512, 512, x_mode=B.SCALE_ROW, w_mode=B.SCALE_COL)
+    assert xq(skinny, x=None) == B.LOKA_ERR_NULL
+    assert xq(skinny, q=None) == B.LOKA_ERR_NULL
+    assert xq(skinny, sx=None) == B.LOKA_ERR_NULL
+    assert xq(skinny, q=ODD) == B.LOKA_ERR_ALIGN
+    assert xq(B.make_desc(4096, 512, 100, x_mode=B.SCALE_ROW, w_mode=B.SCALE_COL)) == B.LOKA_ERR_SHAPE
+    # only with one scale per row of X, only on the streaming kernel and the shapes it covers
+    assert xq(B.make_desc(4096, 512, 512, x_mode=B.SCALE_TENSOR, w_mode=B.SCALE_TENSOR)) == B.LOKA_ERR_UNSUPPORTED
+    assert xq(B.make_desc(4096, 4096, 4096, x_mode=B.SCALE_ROW, w_mode=B.SCALE_COL)) == B.LOKA_ERR_UNSUPPORTED
+    assert xq(B.make_desc(4096, 256, 256, x_mode=B.SCALE_ROW, w_mode=B.SCALE_COL, variant=B.variant_id("strip32"))) == B.LOKA_ERR_UNSUPPORTED
+    shared_x = B.make_desc(4096, 256, 256, batch=4, x_mode=B.SCALE_ROW, w_mode=B.SCALE_COL)
+    shared_x.strideX = 0
+    assert xq(shared_x) == B.LOKA_ERR_UNSUPPORTED
+
+
 def test_probe_and_bf16_argument_validation():
     L = B.lib()
     assert L.loka_probe_error(None, FAKE, 8, 16, 16, FAKE, None, FAKE, 1 << 20, None) == B.LOKA_ERR_NULL

@@ -1009,6 +1009,71 @@ def test_fused_quantization_gives_the_bits_of_the_two_calls(orc, case, variant):
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)), "bf16 O differs from the two-call path"
 
 
+@pytest.mark.parametrize("case", [
+    (16384, 512, 512, 1, "rmsnorm"),       # C2
+    (8192 + 40, 256, 1024, 1, "layernorm"),  # the C3a layer, ragged last block
+    (4096 + 8, 1024, 256, 1, "layernorm"),   # the C3b layer
+    (1000, 128, 256, 1, "none"),
+    (2048 + 16, 256, 256, 3, "rmsnorm"),     # grouped: a workgroup's rows cross problems
+    (520, 512, 128, 5, "layernorm"),
+], ids=lambda c: "x".join(str(v) for v in c))
+def test_quantize_prologue_gives_the_bits_of_the_two_calls(orc, case):
+    # loka_fp8_linear_norm_xq: every workgroup of the streaming kernel quantizes the rows it consumes, then runs the
+    # kernel of loka_fp8_gemm_norm: codes and row scales must be the oracle's (every row), fp32 Y and bf16 O those of
+    # the two calls, which are checked against the oracle elsewhere in this file
+    M, K, N, G, norm = case
+    v = B.variant_id("wreg32")
+    desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORMS[norm], 1e-5, variant=v)
+    assert B.loka_variant_supports(desc, v)
+    x = torch.cat([synth.student_t4(M, K, 150 + g) for g in range(G)], 0)
+    x[3] = 0                                                     # an all-zero row: the amax floor
+    x[M - 1, 7] = 3.0e4                                          # an outlier in the last row of the first problem
+    w = torch.cat([synth.weight(K, N, 160 + g) for g in range(G)], 0)
+    gamma, beta = synth.affine(N, 19)
+    xd, wd = x.to(DEV), w.to(DEV)
+    wq = torch.empty(G * N, K, dtype=torch.uint8, device=DEV)
+    sw = torch.empty(G * N, dtype=torch.float32, device=DEV)
+    for g in range(G):
+        q, s_ = B.loka_quantize(wd[g * K:(g + 1) * K], B.SCALE_COL, transpose_out=True)
+        wq[g * N:(g + 1) * N] = q
+        sw[g * N:(g + 1) * N] = s_
+    xq2, sx2 = B.loka_quantize(xd, B.SCALE_ROW)
+    o2, y2 = B.loka_fp8_gemm_norm(desc, xq2, sx2, wq, sw, gamma.to(DEV), beta.to(DEV), want_y=True)
+    # output buffers pre-filled: every byte must be written by the call
+    xq1 = torch.full((G * M, K), 0x5A, dtype=torch.uint8, device=DEV)
+    sx1 = torch.full((G * M,), -1.0, dtype=torch.float32, device=DEV)
+    for rep in range(2):                                         # (the second call finds its own codes in place)
+        o1, y1, _, _ = B.loka_fp8_linear_norm_xq(desc, xd, wq, sw, gamma.to(DEV), beta.to(DEV), want_y=True, xq=xq1, sx=sx1)
+        torch.cuda.synchronize()
+        xq_o, sx_o = orc.quantize(synth.bf16_bits(x), orc.SCALE_ROW)
+        assert np.array_equal(xq1.cpu().numpy(), xq_o), "codes differ from the oracle's"
+        assert np.array_equal(sx1.cpu().numpy().view(np.uint32), sx_o.view(np.uint32)), "row scales differ from the oracle's"
+        assert torch.equal(y1, y2), "fp32 Y differs from the two-call path"
+        assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)), "bf16 O differs from the two-call path"
+    d_def = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORMS[norm], 1e-5, variant=-1)
+    o3, _, _, _ = B.loka_fp8_linear_norm_xq(d_def, xd, wq, sw, gamma.to(DEV), beta.to(DEV))
+    assert torch.equal(o3.view(torch.int16), o2.view(torch.int16))
+
+
+def test_quantize_prologue_unsupported():
+    x = torch.zeros(512, 4096, dtype=torch.bfloat16, device=DEV)
+    wq = torch.zeros(4096, 4096, dtype=torch.uint8, device=DEV)
+    sw = torch.ones(4096, dtype=torch.float32, device=DEV)
+    with pytest.raises(B.LokaError) as e:                        # a layer the streaming kernel does not cover
+        B.loka_fp8_linear_norm_xq(B.make_desc(512, 4096, 4096, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, 1e-5), x, wq, sw)
+    assert e.value.status == B.LOKA_ERR_UNSUPPORTED
+    x = torch.zeros(512, 256, dtype=torch.bfloat16, device=DEV)
+    wq = torch.zeros(256, 256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.LokaError) as e:                        # per-tensor activation scale: no row-local amax
+        B.loka_fp8_linear_norm_xq(B.make_desc(512, 256, 256, 1, B.SCALE_TENSOR, B.SCALE_TENSOR, B.NORM_LAYERNORM, 1e-5), x, wq,
+                                  torch.ones(1, device=DEV))
+    assert e.value.status == B.LOKA_ERR_UNSUPPORTED
+    with pytest.raises(B.LokaError) as e:                        # another kernel named
+        B.loka_fp8_linear_norm_xq(B.make_desc(512, 256, 256, 1, B.SCALE_ROW, B.SCALE_COL, B.NORM_LAYERNORM, 1e-5,
+                                              variant=B.variant_id("strip32")), x, wq, torch.ones(256, device=DEV))
+    assert e.value.status == B.LOKA_ERR_UNSUPPORTED
+
+
 def test_fused_quantization_unsupported_shapes():
     # the configurations whose weights fill the register file (streaming kernel) or whose raw strip would (strip
     # kernel, K = 1024), and everything neither kernel covers
