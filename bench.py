@@ -326,6 +326,10 @@ def main():
     ap.add_argument("--budget", type=float, default=5e-2, help="rel-Frobenius budget the timed variant must meet")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-library", action="store_true", help="skip the vendor-library yardstick leg")
+    ap.add_argument("--ablate-epilogue", action="store_true",
+                    help="also time the GEMM call of the same shape, recipe and kernel with other epilogues (no norm, BlockNorm, "
+                         "RMSNorm, LayerNorm, FP8 output): what the statistics, the exchange between workgroups and the store "
+                         "cost, by subtraction; reported as `epilogue_ablation`")
     ap.add_argument("--fused", action="store_true",
                     help="the step is ONE call, loka_fp8_linear_norm (rowwise quantization inside the GEMM kernel: same "
                          "bits, no FP8 copy of X in memory); small-layer workloads only, exits when unsupported")
@@ -530,11 +534,57 @@ def main():
     if roofline["bound"] == "mfma":
         ceiling = B.loka_machine_ceiling(0, 60.0, ceil_buf)
         roofline["measured_ceiling"] = {"what": "FP8 32x32x64 matrix instructions from registers, all CUs", "value": ceiling, "unit": "TFLOP/s"}
+        if B.loka_variant_name(variant) == "panel32_256x256":
+            # the same kernel's operand stream with no arithmetic (64 KB per 256 x 256 tile and K step of 128), against
+            # what the launch needs on average
+            stream_gbs = B.loka_machine_ceiling(3, 30.0, ceil_buf)
+            tiles = G * ((M + 255) // 256) * ((N + 255) // 256)
+            need_gbs = tiles * (K // 128) * 65536.0 / (t_gemm * 1e-3) / 1e9
+            roofline["operand_delivery"] = {"what": "operand bytes into LDS per launch / launch time, against the same stream "
+                                                    "with no arithmetic (loads that write LDS, the kernel's request shape)",
+                                            "needed": need_gbs, "measured_ceiling": stream_gbs, "unit": "GB/s",
+                                            "frac": need_gbs / stream_gbs}
     else:
         ceiling = B.loka_machine_ceiling(2, 30.0, ceil_buf)
         roofline["measured_ceiling"] = {"what": "plain copy, 512 MiB read + 512 MiB written", "value": ceiling, "unit": "GB/s"}
     roofline["frac_of_measured_ceiling"] = roofline["achieved"] / ceiling
     del ceil_buf
+
+    # ---- epilogue ablation (on request): the same launch with other epilogues, event-timed in the same alternation
+    ablation = None
+    if args.ablate_epilogue:
+        ablation = {}
+        oq = torch.empty(rows, N, dtype=torch.uint8, device=dev)
+        so = torch.empty(rows, dtype=torch.float32, device=dev)
+        for name, nrm, f8 in (("none", B.NORM_NONE, False), ("blocknorm", B.NORM_BLOCKNORM, False),
+                              ("rmsnorm", B.NORM_RMSNORM, False), ("layernorm", B.NORM_LAYERNORM, False),
+                              ("layernorm_fp8out", B.NORM_LAYERNORM, True)):
+            if nrm == B.NORM_BLOCKNORM and N % 256:
+                continue
+            d2 = B.make_desc(M, N, K, G, xm, wm, nrm, w.eps, variant=variant, block_n=256 if nrm == B.NORM_BLOCKNORM else 0)
+            if f8:
+                need = L.loka_fp8_gemm_norm_fp8out_workspace(ctypes.byref(d2))
+            else:
+                need = L.loka_fp8_gemm_norm_workspace(ctypes.byref(d2))
+            ws2 = torch.empty(max(16, need), dtype=torch.uint8, device=dev)
+
+            def call():
+                if f8:
+                    return L.loka_fp8_gemm_norm_fp8out(ctypes.byref(d2), xq.data_ptr(), sx.data_ptr(), wq.data_ptr(), sw.data_ptr(),
+                                                       None, None, oq.data_ptr(), so.data_ptr(), None, ws2.data_ptr(), ws2.numel(), sp)
+                return L.loka_fp8_gemm_norm(ctypes.byref(d2), xq.data_ptr(), sx.data_ptr(), wq.data_ptr(), sw.data_ptr(), None,
+                                            None, out.data_ptr(), None, ws2.data_ptr(), ws2.numel(), sp)
+            if call() != 0:
+                continue
+            for i in range(10):
+                quant_x(xs[i % n_sets]); call()
+            ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(k_steps)]
+            for i, (e1, e2) in enumerate(ev2):
+                quant_x(xs[i % n_sets])
+                e1.record(stream); call(); e2.record(stream)
+            torch.cuda.synchronize()
+            ablation[name] = {"ms": float(np.mean([a.elapsed_time(b_) for a, b_ in ev2])),
+                              "min_ms": float(np.min([a.elapsed_time(b_) for a, b_ in ev2]))}
 
     # ---- probe leg (offline in the method): Y store, BF16 reference GEMM, error statistics
     y = torch.empty(rows, N, dtype=torch.float32, device=dev)
@@ -639,6 +689,7 @@ def main():
         "cpu_baseline": cpu,
         "kernels": kernels,
         "library_yardstick": library,
+        "epilogue_ablation": ablation,
         "probe_stats": pstats,
     }
     if args.calib_copy:

@@ -167,7 +167,8 @@ def loka_e4m3_from_f32(t: torch.Tensor) -> torch.Tensor:
 
 
 def loka_machine_ceiling(kind: int, millis: float, scratch: torch.Tensor) -> float:
-    """kind 0 / 1: FP8 / BF16 matrix rate in TFLOP/s; 2: copy rate in GB/s.  Synchronizes."""
+    """kind 0 / 1: FP8 / BF16 matrix rate in TFLOP/s; 2: copy rate in GB/s; 3: rate at which the large-layer kernel's operand
+    stream reaches the LDS of all CUs, GB/s.  Synchronizes."""
     v = c_double(0.0)
     _check(lib().loka_machine_ceiling(kind, millis, _ptr(scratch), scratch.numel() * scratch.element_size(), byref(v),
                                       _stream()), "loka_machine_ceiling")

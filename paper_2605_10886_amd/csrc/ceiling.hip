@@ -55,11 +55,60 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
     }
 }
 
+// The large-layer kernel's operand stream without its arithmetic: one workgroup of 8 waves per CU pulls, per K step of
+// 128 bytes, 256 rows of a row panel of its own and 256 rows of a matrix that all workgroups share (64 KB) into a ring
+// of five 32 KB LDS entries with loads that write LDS directly (four 1 KB loads per wave and entry, eight rows of 128
+// bytes each: the kernel's own request shape), two steps in flight, one barrier per step.  Nothing reads the LDS: what
+// is measured is how fast L2 (the shared matrix, re-read by every workgroup) and HBM / the last-level cache (the
+// panels) deliver operands to the CUs at this request shape and depth.
+__global__ __launch_bounds__(512) void lds_stream_kernel(const uint8_t* __restrict__ base, int kb_row, int tiles_shared,
+                                                         int rounds, float* sink) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem_stream[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ksteps = kb_row / 128;
+    const int64_t tile_bytes = 256ll * kb_row;
+    const uint8_t* shared = base + static_cast<int64_t>(gridDim.x) * tile_bytes;       // behind the panels
+    const int lane_off = (lane >> 3) * kb_row + (lane & 7) * 16;
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(base + static_cast<int64_t>(blockIdx.x) * tile_bytes), 0, static_cast<int>(tile_bytes), 0x00020000);
+    int e = 0;
+    for (int r = 0; r < rounds; ++r) {
+        const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t*>(shared + static_cast<int64_t>((r + blockIdx.x) % tiles_shared) * tile_bytes), 0,
+            static_cast<int>(tile_bytes), 0x00020000);
+        for (int k = 0; k < ksteps; ++k) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int grp = wave + 8 * j;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    xr, (__attribute__((address_space(3))) void*)(smem_stream + (e % 5) * 32768 + grp * 1024), 16, lane_off,
+                    grp * 8 * kb_row + k * 128, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int grp = wave + 8 * j;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    wr, (__attribute__((address_space(3))) void*)(smem_stream + ((e + 1) % 5) * 32768 + grp * 1024), 16, lane_off,
+                    grp * 8 * kb_row + k * 128, 0, 0);
+            }
+            e += 2;
+            __builtin_amdgcn_s_waitcnt(0x0F70 | 8);        // all but the newest step's loads of this wave have landed
+            __builtin_amdgcn_s_barrier();
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    const float v = reinterpret_cast<const float*>(smem_stream)[threadIdx.x];
+    if (v == 123.456f && sink) sink[blockIdx.x] = v;        // (never true for the zero-filled scratch: keeps the loads)
+}
+
 int device_cu_count();
 
 // kind 0 / 1: FP8 / BF16 matrix rate in TFLOP/s over ~`millis` ms of back-to-back launches (the clock settles during
 // the first tens of milliseconds under load; the rate of the LAST launch is returned);  kind 2: copy rate in GB/s
-// (bytes read + written) of `scratch_bytes` / 2 bytes from the first half of `scratch` to the second.
+// (bytes read + written) of `scratch_bytes` / 2 bytes from the first half of `scratch` to the second;  kind 3: rate in
+// GB/s at which the large-layer kernel's operand stream reaches the LDS of all CUs (no arithmetic).
 loka_status machine_ceiling(int kind, double millis, void* scratch, size_t scratch_bytes, double* value, hipStream_t s) {
     const int cus = device_cu_count();
     if (cus <= 0) return LOKA_ERR_HIP;
@@ -82,6 +131,25 @@ loka_status machine_ceiling(int kind, double millis, void* scratch, size_t scrat
             LOKA_HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
             total += ms;
             last = flops / (ms * 1e-3) / 1e12;
+        }
+    } else if (kind == 3) {
+        // rows of 4096 bytes (the large layer's K), 32 K steps per tile, 8 tiles per workgroup: a workgroup pulls 16 MB,
+        // half of it from a 16 MB matrix (16 tiles) every workgroup reads
+        const int kb_row = 4096, tiles_shared = 16, rounds = 8;
+        const size_t need = (static_cast<size_t>(cus) + tiles_shared) * 256 * kb_row;
+        if (scratch_bytes < need) return LOKA_ERR_WORKSPACE;
+        LOKA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&lds_stream_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 32768));
+        const double bytes = static_cast<double>(cus) * rounds * (kb_row / 128) * 65536.0;
+        while (total < millis) {
+            LOKA_HIP_TRY(hipEventRecord(e0, s));
+            lds_stream_kernel<<<dim3(cus), 512, 5 * 32768, s>>>(static_cast<const uint8_t*>(scratch), kb_row, tiles_shared, rounds,
+                                                               nullptr);
+            LOKA_HIP_TRY(hipEventRecord(e1, s));
+            LOKA_HIP_TRY(hipEventSynchronize(e1));
+            LOKA_HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+            total += ms;
+            last = bytes / (ms * 1e-3) / 1e9;
         }
     } else {
         const int64_t n16 = static_cast<int64_t>(scratch_bytes / 2 / 16);

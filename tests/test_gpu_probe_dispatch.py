@@ -135,7 +135,10 @@ def test_machine_ceilings_are_plausible():
     f8 = B.loka_machine_ceiling(0, 20.0, buf)
     bf = B.loka_machine_ceiling(1, 20.0, buf)
     cp = B.loka_machine_ceiling(2, 10.0, buf)
-    print("ceilings: fp8 %.0f TFLOP/s, bf16 %.0f TFLOP/s, copy %.0f GB/s" % (f8, bf, cp))
-    assert 2500.0 < f8 < 5100.0 and 1250.0 < bf < 2600.0 and 2000.0 < cp < 8000.0
+    st = B.loka_machine_ceiling(3, 10.0, buf)       # operands into the LDS of every CU, no arithmetic
+    print("ceilings: fp8 %.0f TFLOP/s, bf16 %.0f TFLOP/s, copy %.0f GB/s, operand stream %.0f GB/s" % (f8, bf, cp, st))
+    assert 2500.0 < f8 < 5100.0 and 1250.0 < bf < 2600.0 and 2000.0 < cp < 8000.0 and 4000.0 < st < 40000.0
     with pytest.raises(B.LokaError):
-        B.loka_machine_ceiling(3, 1.0, buf)
+        B.loka_machine_ceiling(4, 1.0, buf)
+    with pytest.raises(B.LokaError):                # the operand stream needs a panel per CU and the shared matrix
+        B.loka_machine_ceiling(3, 1.0, buf[:1 << 26])
