@@ -117,9 +117,10 @@ loka_status loka_e4m3_from_f32(const float* t, uint8_t* codes, int64_t n, void* 
  *   kind 0: FP8 matrix rate, TFLOP/s (register-resident 32x32x64 matrix instructions back to back on every CU)
  *   kind 1: BF16 matrix rate, TFLOP/s (32x32x16)
  *   kind 2: HBM copy rate, GB/s (bytes read + written), first half of `scratch` copied to the second
- *   kind 3: operand delivery rate, GB/s: the large-layer kernel's operand stream (per CU and K step 32 KB of a row
- *           panel of its own and 32 KB of a 16 MB matrix every CU reads, loads that write LDS directly, the kernel's
- *           request shape and depth) with no arithmetic; scratch at least (CUs + 16) MiB (LOKA_ERR_WORKSPACE otherwise)
+ *   kind 3: operand delivery rate, GB/s: the large-layer kernel's operand stream for a 32768 x 4096 x 4096 layer on
+ *           that kernel's schedule (per CU and K step 32 KB of a row panel shared by the 16 workgroups of the panel and
+ *           32 KB of the weight matrix, loads that write LDS directly, the kernel's request shape and depth) with no
+ *           arithmetic; scratch at least 144 MiB (LOKA_ERR_WORKSPACE otherwise)
  * Runs back-to-back launches for about `millis` milliseconds (clocks settle under load during the first tens of
  * milliseconds) and returns the LAST launch's rate in *value_host (host memory).  scratch: device memory, 16-byte
  * aligned, at least 4 MiB (kind 2: at least 64 MiB; use >= 1 GiB to stay clear of the last-level cache).

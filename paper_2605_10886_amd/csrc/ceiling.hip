@@ -55,28 +55,29 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
     }
 }
 
-// The large-layer kernel's operand stream without its arithmetic: one workgroup of 8 waves per CU pulls, per K step of
-// 128 bytes, 256 rows of a row panel of its own and 256 rows of a matrix that all workgroups share (64 KB) into a ring
-// of five 32 KB LDS entries with loads that write LDS directly (four 1 KB loads per wave and entry, eight rows of 128
-// bytes each: the kernel's own request shape), two steps in flight, one barrier per step.  Nothing reads the LDS: what
-// is measured is how fast L2 (the shared matrix, re-read by every workgroup) and HBM / the last-level cache (the
-// panels) deliver operands to the CUs at this request shape and depth.
-__global__ __launch_bounds__(512) void lds_stream_kernel(const uint8_t* __restrict__ base, int kb_row, int tiles_shared,
-                                                         int rounds, float* sink) {
+// The large-layer kernel's operand stream without its arithmetic, on that kernel's schedule for a 32768 x 4096 x 4096
+// layer: one workgroup of 8 waves per CU walks tiles first, first + G, ... (the same XCD-aware numbering: the 16
+// workgroups of a 256-row panel run side by side on one XCD and share the panel, all panels share the weight matrix)
+// and pulls, per K step of 128 bytes, the tile's 256 rows of X and 256 rows of W (64 KB) into a ring of five 32 KB LDS
+// entries with loads that write LDS directly (four 1 KB loads per wave and entry, eight rows of 128 bytes each: the
+// kernel's own request shape), at most one older step outstanding at the step's barrier.  Nothing reads the LDS: what
+// is measured is how fast L2 and what lies behind it deliver this schedule's operands to the CUs.
+__global__ __launch_bounds__(512) void lds_stream_kernel(const uint8_t* __restrict__ x, const uint8_t* __restrict__ w, int kb_row,
+                                                         int tiles_n, int total_tiles, float* sink) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem_stream[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ksteps = kb_row / 128;
-    const int64_t tile_bytes = 256ll * kb_row;
-    const uint8_t* shared = base + static_cast<int64_t>(gridDim.x) * tile_bytes;       // behind the panels
-    const int lane_off = (lane >> 3) * kb_row + (lane & 7) * 16;
-    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t*>(base + static_cast<int64_t>(blockIdx.x) * tile_bytes), 0, static_cast<int>(tile_bytes), 0x00020000);
+    const int G = gridDim.x;
+    const int tile_first = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+    const int lane_off = (lane >> 3) * kb_row + (((lane & 7) ^ (lane >> 4)) << 4);
     int e = 0;
-    for (int r = 0; r < rounds; ++r) {
+    for (int tile = tile_first; tile < total_tiles; tile += G) {
+        const int tn = tile % tiles_n, tm = tile / tiles_n;
+        const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t*>(x + static_cast<int64_t>(tm) * 256 * kb_row), 0, 256 * kb_row, 0x00020000);
         const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint8_t*>(shared + static_cast<int64_t>((r + blockIdx.x) % tiles_shared) * tile_bytes), 0,
-            static_cast<int>(tile_bytes), 0x00020000);
+            const_cast<uint8_t*>(w + static_cast<int64_t>(tn) * 256 * kb_row), 0, 256 * kb_row, 0x00020000);
         for (int k = 0; k < ksteps; ++k) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(512) void lds_stream_kernel(const uint8_t* __restri
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     const float v = reinterpret_cast<const float*>(smem_stream)[threadIdx.x];
-    if (v == 123.456f && sink) sink[blockIdx.x] = v;        // (never true for the zero-filled scratch: keeps the loads)
+    if (v == 123.456f && sink) sink[blockIdx.x] = v;        // (keeps the loads; sink is null in the measurement)
 }
 
 int device_cu_count();
@@ -133,18 +134,20 @@ loka_status machine_ceiling(int kind, double millis, void* scratch, size_t scrat
             last = flops / (ms * 1e-3) / 1e12;
         }
     } else if (kind == 3) {
-        // rows of 4096 bytes (the large layer's K), 32 K steps per tile, 8 tiles per workgroup: a workgroup pulls 16 MB,
-        // half of it from a 16 MB matrix (16 tiles) every workgroup reads
-        const int kb_row = 4096, tiles_shared = 16, rounds = 8;
-        const size_t need = (static_cast<size_t>(cus) + tiles_shared) * 256 * kb_row;
+        // X 32768 x 4096 bytes (128 panels of 256 rows), W 4096 x 4096 (16 tiles), 32 K steps per tile, 2048 tiles
+        const int kb_row = 4096, tiles_m = 128, tiles_n = 16;
+        const size_t need = static_cast<size_t>(tiles_m + tiles_n) * 256 * kb_row;
         if (scratch_bytes < need) return LOKA_ERR_WORKSPACE;
         LOKA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&lds_stream_kernel),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 32768));
-        const double bytes = static_cast<double>(cus) * rounds * (kb_row / 128) * 65536.0;
+        const uint8_t* x = static_cast<const uint8_t*>(scratch);
+        const uint8_t* w = x + static_cast<size_t>(tiles_m) * 256 * kb_row;
+        const int grid = (cus / tiles_n) * tiles_n;           // whole panels side by side, as the kernel launches
+        if (grid <= 0) return LOKA_ERR_UNSUPPORTED;
+        const double bytes = static_cast<double>(tiles_m) * tiles_n * (kb_row / 128) * 65536.0;
         while (total < millis) {
             LOKA_HIP_TRY(hipEventRecord(e0, s));
-            lds_stream_kernel<<<dim3(cus), 512, 5 * 32768, s>>>(static_cast<const uint8_t*>(scratch), kb_row, tiles_shared, rounds,
-                                                               nullptr);
+            lds_stream_kernel<<<dim3(grid), 512, 5 * 32768, s>>>(x, w, kb_row, tiles_n, tiles_m * tiles_n, nullptr);
             LOKA_HIP_TRY(hipEventRecord(e1, s));
             LOKA_HIP_TRY(hipEventSynchronize(e1));
             LOKA_HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
