@@ -159,7 +159,11 @@ typedef struct {
                                  (at 0 when the operand's stride is 0) */
     int32_t norm;             /* loka_norm */
     float eps;
-    int32_t variant;          /* kernel variant id (see loka_variant_name), or -1 = library's choice for the shape */
+    int32_t variant;          /* kernel variant id (see loka_variant_name), or -1 = library's choice for the shape.
+                               * The choice behind -1 is looked up at every call and a loka_dispatch (or
+                               * loka_dispatch_clear) in between can change it: a caller that sizes a workspace, launches
+                               * and checks in separate calls while another thread may dispatch should resolve it once
+                               * (variant = loka_default_variant(desc)) and pass the same id to all three. */
     int32_t block_n;          /* LOKA_NORM_BLOCKNORM: group width; 256 is built (N % 256 == 0).  Ignored otherwise */
     int32_t act;              /* loka_act; LOKA_ACT_HARDSWISH needs LOKA_NORM_BLOCKNORM */
 } loka_gemm_desc;
