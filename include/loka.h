@@ -121,6 +121,9 @@ loka_status loka_e4m3_from_f32(const float* t, uint8_t* codes, int64_t n, void* 
  *           that kernel's schedule (per CU and K step 32 KB of a row panel shared by the 16 workgroups of the panel and
  *           32 KB of the weight matrix, loads that write LDS directly, the kernel's request shape and depth) with no
  *           arithmetic; scratch at least 144 MiB (LOKA_ERR_WORKSPACE otherwise)
+ *   kind 4, 5: as 0, 1, but every instruction of a round takes different operand registers filled with pseudo-random
+ *           codes (consecutive instructions toggle the multipliers' inputs as quantized data does; kinds 0 and 1
+ *           repeat one pair of registers of small codes, the least switching activity and the highest clock)
  * Runs back-to-back launches for about `millis` milliseconds (clocks settle under load during the first tens of
  * milliseconds) and returns the LAST launch's rate in *value_host (host memory).  scratch: device memory, 16-byte
  * aligned, at least 4 MiB (kind 2: at least 64 MiB; use >= 1 GiB to stay clear of the last-level cache).

@@ -10,7 +10,11 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 // One wave issues back-to-back MFMAs on 8 independent accumulator sets; operands never change (the result is
 // meaningless, only the issue rate matters).  The accumulators are written out so the loop cannot be removed.
-template <bool BF16>
+// VARIED: every one of the 8 instructions of a round takes different operand registers filled with pseudo-random
+// codes of both signs and all exponents (as quantized data has), so that consecutive instructions toggle the
+// multipliers' inputs; otherwise all instructions take the same two registers of small positive codes (the least
+// switching activity the pipe can see: the highest clock it will hold).
+template <bool BF16, bool VARIED>
 __global__ __launch_bounds__(512) void mfma_rate_kernel(float* sink, int iters) {
     v16f acc[8];
 #pragma unroll
@@ -18,18 +22,40 @@ __global__ __launch_bounds__(512) void mfma_rate_kernel(float* sink, int iters) 
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
     const int t = static_cast<int>(threadIdx.x);
-    v8i a = v8i{t, t + 1, t + 2, t + 3, t + 4, t + 5, t + 6, t + 7};
-    v8i b = v8i{t * 3, t * 3 + 1, t * 3 + 2, t * 3 + 3, t * 3 + 4, t * 3 + 5, t * 3 + 6, t * 3 + 7};
-    a &= v8i{0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F};   // small finite codes
-    b &= v8i{0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F};
+    constexpr int NS = VARIED ? 8 : 1;
+    v8i a[NS], b[NS];
+    if (VARIED) {
+        unsigned z = 0x9E3779B9u * static_cast<unsigned>(t + 1) + blockIdx.x;
+#pragma unroll
+        for (int j = 0; j < NS; ++j)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                z = z * 1664525u + 1013904223u;
+                unsigned wa = z ^ (z >> 15);
+                z = z * 1664525u + 1013904223u;
+                unsigned wb = z ^ (z >> 13);
+                // no NaN codes (0x7F / 0xFF): clear bit 0 of bytes whose low seven bits are all ones
+                wa &= ~(((wa & (wa >> 1) & (wa >> 2) & (wa >> 3) & (wa >> 4) & (wa >> 5) & (wa >> 6)) & 0x01010101u));
+                wb &= ~(((wb & (wb >> 1) & (wb >> 2) & (wb >> 3) & (wb >> 4) & (wb >> 5) & (wb >> 6)) & 0x01010101u));
+                // (BF16: keep the exponents moderate so the sums stay finite)
+                a[j][i] = BF16 ? static_cast<int>((wa & 0x8FFF8FFFu) | 0x30003000u) : static_cast<int>(wa);
+                b[j][i] = BF16 ? static_cast<int>((wb & 0x8FFF8FFFu) | 0x30003000u) : static_cast<int>(wb);
+            }
+    } else {
+        a[0] = v8i{t, t + 1, t + 2, t + 3, t + 4, t + 5, t + 6, t + 7};
+        b[0] = v8i{t * 3, t * 3 + 1, t * 3 + 2, t * 3 + 3, t * 3 + 4, t * 3 + 5, t * 3 + 6, t * 3 + 7};
+        a[0] &= v8i{0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F};   // small finite codes
+        b[0] &= v8i{0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F, 0x3F3F3F3F};
+    }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
+            const v8i aj = a[VARIED ? j : 0], bj = b[VARIED ? j : 0];
             if (BF16) {
-                const v4i a4 = v4i{a[0], a[1], a[2], a[3]}, b4 = v4i{b[0], b[1], b[2], b[3]};
+                const v4i a4 = v4i{aj[0], aj[1], aj[2], aj[3]}, b4 = v4i{bj[0], bj[1], bj[2], bj[3]};
                 acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a4), __builtin_bit_cast(v8bf, b4), acc[j], 0, 0, 0);
             } else {
-                acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[j], 0, 0, 0, 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(aj, bj, acc[j], 0, 0, 0, 0, 0, 0);
             }
         }
     }
@@ -109,7 +135,8 @@ int device_cu_count();
 // kind 0 / 1: FP8 / BF16 matrix rate in TFLOP/s over ~`millis` ms of back-to-back launches (the clock settles during
 // the first tens of milliseconds under load; the rate of the LAST launch is returned);  kind 2: copy rate in GB/s
 // (bytes read + written) of `scratch_bytes` / 2 bytes from the first half of `scratch` to the second;  kind 3: rate in
-// GB/s at which the large-layer kernel's operand stream reaches the LDS of all CUs (no arithmetic).
+// GB/s at which the large-layer kernel's operand stream reaches the LDS of all CUs (no arithmetic);  kind 4 / 5: as
+// 0 / 1 with operands that differ from instruction to instruction (pseudo-random codes).
 loka_status machine_ceiling(int kind, double millis, void* scratch, size_t scratch_bytes, double* value, hipStream_t s) {
     const int cus = device_cu_count();
     if (cus <= 0) return LOKA_ERR_HIP;
@@ -119,14 +146,16 @@ loka_status machine_ceiling(int kind, double millis, void* scratch, size_t scrat
     struct Guard { hipEvent_t a, b; ~Guard() { (void)hipEventDestroy(a); (void)hipEventDestroy(b); } } guard{e0, e1};
     float ms = 0.f;
     double total = 0.0, last = 0.0;
-    if (kind == 0 || kind == 1) {
+    if (kind == 0 || kind == 1 || kind == 4 || kind == 5) {
         const int iters = 4096;
         // per launch: CUs x 8 waves x iters x 8 MFMAs of 2 * 32 * 32 * K flops
-        const double flops = static_cast<double>(cus) * 8 * iters * 8 * 2.0 * 32 * 32 * (kind == 0 ? 64 : 16);
+        const double flops = static_cast<double>(cus) * 8 * iters * 8 * 2.0 * 32 * 32 * ((kind == 0 || kind == 4) ? 64 : 16);
         while (total < millis) {
             LOKA_HIP_TRY(hipEventRecord(e0, s));
-            if (kind == 0) mfma_rate_kernel<false><<<dim3(cus), 512, 0, s>>>(static_cast<float*>(scratch), iters);
-            else mfma_rate_kernel<true><<<dim3(cus), 512, 0, s>>>(static_cast<float*>(scratch), iters);
+            if (kind == 0) mfma_rate_kernel<false, false><<<dim3(cus), 512, 0, s>>>(static_cast<float*>(scratch), iters);
+            else if (kind == 1) mfma_rate_kernel<true, false><<<dim3(cus), 512, 0, s>>>(static_cast<float*>(scratch), iters);
+            else if (kind == 4) mfma_rate_kernel<false, true><<<dim3(cus), 512, 0, s>>>(static_cast<float*>(scratch), iters);
+            else mfma_rate_kernel<true, true><<<dim3(cus), 512, 0, s>>>(static_cast<float*>(scratch), iters);
             LOKA_HIP_TRY(hipEventRecord(e1, s));
             LOKA_HIP_TRY(hipEventSynchronize(e1));
             LOKA_HIP_TRY(hipEventElapsedTime(&ms, e0, e1));

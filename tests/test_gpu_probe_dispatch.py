@@ -138,7 +138,11 @@ def test_machine_ceilings_are_plausible():
     st = B.loka_machine_ceiling(3, 10.0, buf)       # operands into the LDS of every CU, no arithmetic
     print("ceilings: fp8 %.0f TFLOP/s, bf16 %.0f TFLOP/s, copy %.0f GB/s, operand stream %.0f GB/s" % (f8, bf, cp, st))
     assert 2500.0 < f8 < 5100.0 and 1250.0 < bf < 2600.0 and 2000.0 < cp < 8000.0 and 4000.0 < st < 40000.0
+    f8v = B.loka_machine_ceiling(4, 20.0, buf)      # the same instructions on operands that change every instruction
+    bfv = B.loka_machine_ceiling(5, 20.0, buf)
+    print("ceilings with varied operands: fp8 %.0f TFLOP/s, bf16 %.0f TFLOP/s" % (f8v, bfv))
+    assert 1500.0 < f8v <= f8 * 1.02 and 800.0 < bfv <= bf * 1.02
     with pytest.raises(B.LokaError):
-        B.loka_machine_ceiling(4, 1.0, buf)
+        B.loka_machine_ceiling(6, 1.0, buf)
     with pytest.raises(B.LokaError):                # the operand stream needs a panel per CU and the shared matrix
         B.loka_machine_ceiling(3, 1.0, buf[:1 << 26])
