@@ -1,6 +1,6 @@
 """The hot entry points under HIP graph capture.
 
-`loka_quantize` (row / 1x128 modes), `loka_fp8_gemm_norm` and `loka_fp8_gemm_norm_fp8out` only launch kernels on the caller's stream (scratch comes
+`loka_quantize` (row / 1x128 modes), `loka_fp8_gemm_norm`, `loka_fp8_gemm_norm_fp8out` and `loka_fp8_linear_norm_xq` only launch kernels on the caller's stream (scratch comes
 in as a workspace argument and is cleared by a kernel, never by a memset node), so a serving loop can record a step
 once and replay it.  Each case records quantize + GEMM+norm, replays the graph several times with new activations
 written into the same input buffer and eager work on the device between the replays, and compares every replay
@@ -26,6 +26,8 @@ CASES = [
     (4096, 256, 4096, 1, B.NORM_LAYERNORM, "panel-synchronous kernel: counters cleared by a kernel inside the launch"),
     (2048, 512, 2048, 1, B.NORM_LAYERNORM, "panel-synchronous kernel, FP8 output with gamma / beta: two exchanges per tile"),
     (8192, 256, 1024, 1, B.NORM_RMSNORM, "streaming kernel, FP8 output"),
+    (8192 + 24, 512, 512, 1, B.NORM_RMSNORM, "streaming kernel, one launch: quantize prologue"),
+    (2048 + 8, 256, 512, 3, B.NORM_LAYERNORM, "streaming kernel, one launch: quantize prologue, grouped"),
 ]
 
 
@@ -48,6 +50,7 @@ def test_step_replays_from_a_graph(M, K, N, G, norm, what):
     xq = torch.empty(rows, K, dtype=torch.uint8, device=DEV)
     sx = torch.empty(rows, dtype=torch.float32, device=DEV)
     fp8 = "FP8 output" in what
+    one_launch = "one launch" in what
     gamma, beta = (t.to(DEV) for t in synth.affine(N, seed=9)) if "gamma" in what else (None, None)
     gp, bp = (gamma.data_ptr(), beta.data_ptr()) if gamma is not None else (None, None)
     out = torch.empty(rows, N, dtype=torch.uint8 if fp8 else torch.bfloat16, device=DEV)
@@ -58,6 +61,11 @@ def test_step_replays_from_a_graph(M, K, N, G, norm, what):
 
     def step(stream):
         sp = ctypes.c_void_p(stream.cuda_stream)
+        if one_launch:
+            r = L.loka_fp8_linear_norm_xq(ctypes.byref(desc), x_in.data_ptr(), xq.data_ptr(), sx.data_ptr(), wq.data_ptr(),
+                                          sw.data_ptr(), gp, bp, out.data_ptr(), None, sp)
+            assert r == 0, r
+            return
         r = L.loka_quantize(x_in.data_ptr(), rows, K, K, B.SCALE_ROW, 0, xq.data_ptr(), sx.data_ptr(), ws_q.data_ptr(),
                             ws_q.numel(), sp)
         assert r == 0, r
@@ -69,6 +77,9 @@ def test_step_replays_from_a_graph(M, K, N, G, norm, what):
                                      bp, out.data_ptr(), None, ws_g.data_ptr(), ws_g.numel(), sp)
         assert r == 0, r
 
+    if one_launch:
+        # the expected bits are those of the two eager calls
+        desc.variant = B.variant_id("wreg32")
     # eager results for every input (also the warm-up that loads the code objects before the capture)
     cur = torch.cuda.current_stream()
     want = []
@@ -77,6 +88,11 @@ def test_step_replays_from_a_graph(M, K, N, G, norm, what):
         step(cur)
         torch.cuda.synchronize()
         want.append((xq.clone(), sx.clone(), out.clone(), so.clone()))
+        if one_launch:
+            xq2, sx2 = B.loka_quantize(x, B.SCALE_ROW)
+            o2, _ = B.loka_fp8_gemm_norm(desc, xq2, sx2, wq, sw, gamma, beta)
+            torch.cuda.synchronize()
+            assert torch.equal(xq, xq2) and torch.equal(sx, sx2) and torch.equal(out.view(torch.int16), o2.view(torch.int16))
 
     side = torch.cuda.Stream()
     side.wait_stream(cur)
