@@ -124,6 +124,8 @@ loka_status loka_e4m3_from_f32(const float* t, uint8_t* codes, int64_t n, void* 
  *   kind 4, 5: as 0, 1, but every instruction of a round takes different operand registers filled with pseudo-random
  *           codes (consecutive instructions toggle the multipliers' inputs as quantized data does; kinds 0 and 1
  *           repeat one pair of registers of small codes, the least switching activity and the highest clock)
+ *   kind 6, 7: the FP8 rate with the 16x16x128 form of the matrix instruction, on constant (6) and on changing (7)
+ *           operands (kinds 0 and 4 use the 32x32x64 form, which the large-layer kernel issues)
  * Runs back-to-back launches for about `millis` milliseconds (clocks settle under load during the first tens of
  * milliseconds) and returns the LAST launch's rate in *value_host (host memory).  scratch: device memory, 16-byte
  * aligned, at least 4 MiB (kind 2: at least 64 MiB; use >= 1 GiB to stay clear of the last-level cache).

@@ -318,7 +318,7 @@ void loka_test_set_spin_limit(int64_t polls) { test_set_spin_limit(polls); }
 loka_status loka_machine_ceiling(int kind, double millis, void* scratch, size_t scratch_bytes, double* value_host,
                                  void* hip_stream) {
     if (!scratch || !value_host) return LOKA_ERR_NULL;
-    if (kind < 0 || kind > 5 || !(millis > 0.0)) return LOKA_ERR_UNSUPPORTED;
+    if (kind < 0 || kind > 7 || !(millis > 0.0)) return LOKA_ERR_UNSUPPORTED;
     if (!aligned16(scratch)) return LOKA_ERR_ALIGN;
     if (scratch_bytes < (size_t(1) << 22) || (kind == 2 && scratch_bytes < (size_t(1) << 26))) return LOKA_ERR_WORKSPACE;
     return machine_ceiling(kind, millis, scratch, scratch_bytes, value_host, static_cast<hipStream_t>(hip_stream));

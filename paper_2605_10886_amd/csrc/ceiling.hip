@@ -81,6 +81,39 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
     }
 }
 
+// The same measurement with the 16x16x128 form of the FP8 instruction (half the outputs, twice the K per instruction:
+// the same flops per cycle, twice the operand registers read per flop).
+template <bool VARIED>
+__global__ __launch_bounds__(512) void mfma_rate16_kernel(float* sink, int iters) {
+    v4f acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
+    const int t = static_cast<int>(threadIdx.x);
+    v8i a[8], b[8];
+    unsigned z = 0x9E3779B9u * static_cast<unsigned>(t + 1) + blockIdx.x;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            z = z * 1664525u + 1013904223u;
+            unsigned wa = z ^ (z >> 15);
+            z = z * 1664525u + 1013904223u;
+            unsigned wb = z ^ (z >> 13);
+            wa &= ~(((wa & (wa >> 1) & (wa >> 2) & (wa >> 3) & (wa >> 4) & (wa >> 5) & (wa >> 6)) & 0x01010101u));   // no NaN codes
+            wb &= ~(((wb & (wb >> 1) & (wb >> 2) & (wb >> 3) & (wb >> 4) & (wb >> 5) & (wb >> 6)) & 0x01010101u));
+            a[j][i] = VARIED ? static_cast<int>(wa) : 0x38383838;
+            b[j][i] = VARIED ? static_cast<int>(wb) : 0x38383838;
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[j], b[j], acc[j], 0, 0, 0, 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += (acc[j][0] + acc[j][1]) + (acc[j][2] + acc[j][3]);
+    if (s == 123.456f) sink[blockIdx.x * blockDim.x + threadIdx.x] = s;     // (never true: keeps the loop)
+}
+
 // The large-layer kernel's operand stream without its arithmetic, on that kernel's schedule for a 32768 x 4096 x 4096
 // layer: one workgroup of 8 waves per CU walks tiles first, first + G, ... (the same XCD-aware numbering: the 16
 // workgroups of a 256-row panel run side by side on one XCD and share the panel, all panels share the weight matrix)
@@ -136,7 +169,8 @@ int device_cu_count();
 // the first tens of milliseconds under load; the rate of the LAST launch is returned);  kind 2: copy rate in GB/s
 // (bytes read + written) of `scratch_bytes` / 2 bytes from the first half of `scratch` to the second;  kind 3: rate in
 // GB/s at which the large-layer kernel's operand stream reaches the LDS of all CUs (no arithmetic);  kind 4 / 5: as
-// 0 / 1 with operands that differ from instruction to instruction (pseudo-random codes).
+// 0 / 1 with operands that differ from instruction to instruction (pseudo-random codes);  kind 6 / 7: the FP8 rate
+// with the 16x16x128 form of the instruction, on constant and on changing operands.
 loka_status machine_ceiling(int kind, double millis, void* scratch, size_t scratch_bytes, double* value, hipStream_t s) {
     const int cus = device_cu_count();
     if (cus <= 0) return LOKA_ERR_HIP;
@@ -146,7 +180,20 @@ loka_status machine_ceiling(int kind, double millis, void* scratch, size_t scrat
     struct Guard { hipEvent_t a, b; ~Guard() { (void)hipEventDestroy(a); (void)hipEventDestroy(b); } } guard{e0, e1};
     float ms = 0.f;
     double total = 0.0, last = 0.0;
-    if (kind == 0 || kind == 1 || kind == 4 || kind == 5) {
+    if (kind == 6 || kind == 7) {
+        const int iters = 8192;
+        const double flops = static_cast<double>(cus) * 8 * iters * 8 * 2.0 * 16 * 16 * 128;
+        while (total < millis) {
+            LOKA_HIP_TRY(hipEventRecord(e0, s));
+            if (kind == 6) mfma_rate16_kernel<false><<<dim3(cus), 512, 0, s>>>(static_cast<float*>(scratch), iters);
+            else mfma_rate16_kernel<true><<<dim3(cus), 512, 0, s>>>(static_cast<float*>(scratch), iters);
+            LOKA_HIP_TRY(hipEventRecord(e1, s));
+            LOKA_HIP_TRY(hipEventSynchronize(e1));
+            LOKA_HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+            total += ms;
+            last = flops / (ms * 1e-3) / 1e12;
+        }
+    } else if (kind == 0 || kind == 1 || kind == 4 || kind == 5) {
         const int iters = 4096;
         // per launch: CUs x 8 waves x iters x 8 MFMAs of 2 * 32 * 32 * K flops
         const double flops = static_cast<double>(cus) * 8 * iters * 8 * 2.0 * 32 * 32 * ((kind == 0 || kind == 4) ? 64 : 16);

@@ -142,7 +142,10 @@ def test_machine_ceilings_are_plausible():
     bfv = B.loka_machine_ceiling(5, 20.0, buf)
     print("ceilings with varied operands: fp8 %.0f TFLOP/s, bf16 %.0f TFLOP/s" % (f8v, bfv))
     assert 1500.0 < f8v <= f8 * 1.02 and 800.0 < bfv <= bf * 1.02
+    f16c, f16v = B.loka_machine_ceiling(6, 20.0, buf), B.loka_machine_ceiling(7, 20.0, buf)     # the 16x16x128 form
+    print("ceilings, 16x16x128 form: fp8 %.0f TFLOP/s on constant, %.0f on varied operands" % (f16c, f16v))
+    assert 2500.0 < f16c < 5100.0 and 1500.0 < f16v <= f16c * 1.02
     with pytest.raises(B.LokaError):
-        B.loka_machine_ceiling(6, 1.0, buf)
+        B.loka_machine_ceiling(8, 1.0, buf)
     with pytest.raises(B.LokaError):                # the operand stream needs a panel per CU and the shared matrix
         B.loka_machine_ceiling(3, 1.0, buf[:1 << 26])
