@@ -270,16 +270,18 @@ loka_status loka_fp8_linear_norm(const loka_gemm_desc* desc, const void* x_bf16,
 
 /* The same layer in one launch for EVERY shape the streaming kernel covers (variant "wreg32": N <= 1024, K in
  * {128, 256, 512, 1024}, K * N <= 256 KB - the skinny layers of Section 2.1, where Section 2.3 finds the quantization
- * pass above 30 % of the GEMM's latency), with the quantized activation handed back: each workgroup first quantizes
- * the rows it is about to consume (row amax, scale = amax / 448, e4m3 codes: the bits loka_quantize(x, LOKA_SCALE_ROW)
- * writes), stores them to xq_out / sx_out, and streams them back from its L2 while the weights load; the rest is the
- * kernel of loka_fp8_gemm_norm, so out_bf16 and y_fp32 carry the bits of the two calls.  A trainer keeps xq_out / sx_out
- * where it would have kept the output of the separate quantize call.
+ * pass above 30 % of the GEMM's latency) and, on the large-tile kernel (variant "panel32_256x256"), for layers whose
+ * output row fits one tile (N <= 256) with K in {512, 1024, 2048}; with the quantized activation handed back: each
+ * workgroup first quantizes the rows it is about to consume (row amax, scale = amax / 448, e4m3 codes: the bits
+ * loka_quantize(x, LOKA_SCALE_ROW) writes), stores them to xq_out / sx_out, and streams them back from its L2; the rest
+ * is the kernel of loka_fp8_gemm_norm, so out_bf16 and y_fp32 carry the bits of the two calls on the same variant.  A
+ * trainer keeps xq_out / sx_out where it would have kept the output of the separate quantize call.
  *   x_bf16 [batch][M, K] bf16 (strideX in elements; with batch > 1 strideX must not be 0);
  *   xq_out [batch][M, K] e4m3 codes and sx_out [batch][M] fp32 row scales: device memory, 16-byte aligned, written by
  *   the call, not to be read or written by anything else until the call's kernel has finished;
  *   wq, sw, gamma, beta, out_bf16, y_fp32 as in loka_fp8_gemm_norm.  desc->x_mode must be LOKA_SCALE_ROW;
- *   desc->variant names "wreg32" or is -1.  LOKA_ERR_UNSUPPORTED for shapes the streaming kernel does not cover.
+ *   desc->variant names one of the two kernels, or is -1: the library's choice for the shape where that kernel has
+ *   the prologue, else the other.  LOKA_ERR_UNSUPPORTED for shapes neither covers.
  * No workspace, no allocation. */
 loka_status loka_fp8_linear_norm_xq(const loka_gemm_desc* desc, const void* x_bf16, uint8_t* xq_out, float* sx_out,
                                     const uint8_t* wq, const float* sw, const void* gamma_bf16, const void* beta_bf16,

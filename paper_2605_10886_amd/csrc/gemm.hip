@@ -866,7 +866,7 @@ static const char kStripName[] = "strip32";
 static const char kPanel32Name[] = "panel32_256x256";
 
 // gemm_panel32.hip
-const void* panel32_fn(int bw, bool fp8out, bool affine);
+const void* panel32_fn(int bw, bool fp8out, bool affine, bool qpro = false);
 bool panel32_affine(const GemmParams& p);
 size_t panel32_lds();
 void panel32_launch(const GemmParams& p, int bw, dim3 grid, hipStream_t s);
@@ -944,9 +944,19 @@ bool variant_supports_fused(const loka_gemm_desc* d, int v) {
 // for X, one problem or separate activations per problem
 bool variant_supports_xq(const loka_gemm_desc* d, int v) {
     if (v < 0 || v >= kNumVariants || !variant_supports(d, v) || d->x_mode != LOKA_SCALE_ROW) return false;
-    return kVariants[v].name == kWregName && (d->batch == 1 || d->strideX != 0);
+    if (d->batch != 1 && d->strideX == 0) return false;
+    if (kVariants[v].name == kWregName) return true;
+    // the large-tile kernel when a tile spans the output row (its rows of X then belong to one workgroup) and a row of
+    // X is 1, 2 or 4 loads of a whole wave
+    if (kVariants[v].name == kPanel32Name)
+        return d->N <= 256 && (d->K == 512 || d->K == 1024 || d->K == 2048) && d->M * d->K < (int64_t(1) << 31);
+    return false;
 }
+int default_variant(const loka_gemm_desc* d);
+// the library's choice for the shape when it has the prologue, else the first kernel that has it
 int variant_xq_default(const loka_gemm_desc* d) {
+    const int v0 = default_variant(d);
+    if (variant_supports_xq(d, v0)) return v0;
     for (int v = 0; v < kNumVariants; ++v)
         if (variant_supports_xq(d, v)) return v;
     return -1;
@@ -1208,7 +1218,7 @@ static loka_status gemm_norm_launch_impl(const loka_gemm_desc* d, int v, const u
         return hipGetLastError() == hipSuccess ? LOKA_OK : LOKA_ERR_HIP;
     }
     const void* kfn = blockwise ? vi.fn_block : vi.fn_plain;
-    if (vi.name == kPanel32Name) kfn = panel32_fn(panel32_bw(p, blockwise), outq != nullptr, panel32_affine(p));
+    if (vi.name == kPanel32Name) kfn = panel32_fn(panel32_bw(p, blockwise), outq != nullptr, panel32_affine(p), p.qpro != 0);
     if (!kfn) return LOKA_ERR_UNSUPPORTED;
     int per_cu = 0;
     if (prepare_fn(dev, kfn, vi.threads, vi.lds, &per_cu) != LOKA_OK) return LOKA_ERR_HIP;

@@ -36,7 +36,104 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // F8: 0 = bf16 output, 1 = FP8 output without gamma / beta (one exchange), 2 = FP8 output with gamma / beta, BlockNorm
 // or an activation (the row amax of the result crosses the workgroups in a second exchange; an instantiation of its
 // own because it keeps the packed normalized tile in registers).
-template <int EPI, int BW, int F8>
+// Quantize prologue (QPRO instantiation; GemmParams::qpro): when a tile spans the whole output row (N <= 256), the 256
+// rows of X a tile reads are read by no other workgroup, so the workgroup can quantize them itself - rowwise, exactly
+// as the quantize entry point would (row amax, scale = amax / 448, code = e4m3(x * (448 / amax)); same helper
+// functions, same bits) - write codes and row scales where the caller wants them, and then stream them back like any
+// FP8 input (they come from this XCD's L2).  One launch instead of two; the only ordering needed is inside the
+// workgroup: every wave waits for its stores to be acknowledged before the barrier in front of the first read.
+// Wave w takes rows [32 w, +32) of each of the workgroup's tiles, RG rows at a time (16 loads of 16 bytes per lane in
+// flight, the next group requested before the current one is converted); a row is LPR loads of a whole wave
+// (K = 512 LPR elements).
+template <int LPR>
+__device__ __forceinline__ void panel32_quantize_own_rows(const GemmParams& p, int tile_first, int tile_stride, int total_tiles,
+                                                          int wave) {
+    constexpr int RG = 16 / LPR;                 // rows per group
+    constexpr int NG = 32 / RG;                  // groups per tile and wave
+    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+    int lv = static_cast<int>(threadIdx.x) & 63;
+    asm volatile("; lane id" : "+v"(lv));
+    const int K = p.KB;                          // elements per row (= bytes per row of codes)
+    u32x4 raw[2][RG][LPR];
+    // group q of the workgroup's tile sequence: tile tile_first + (q / NG) * tile_stride, rows 32 wave + (q % NG) * RG + [0, RG)
+    const int ntiles = tile_first < total_tiles ? (total_tiles - 1 - tile_first) / tile_stride + 1 : 0;
+    const int ngroups = ntiles * NG;
+    auto locate = [&](int q, int& g, int& m0) __attribute__((always_inline)) {
+        const int tile = tile_first + (q / NG) * tile_stride;
+        g = tile / p.tiles_m;                    // (tiles_n == 1)
+        m0 = (tile - g * p.tiles_m) * 256 + 32 * wave + (q % NG) * RG;
+    };
+    auto fetch = [&](int q, u32x4 (&dst)[RG][LPR]) __attribute__((always_inline)) {
+        int g, m0;
+        locate(q, g, m0);
+        const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(p.xb + static_cast<int64_t>(g) * p.strideX), 0, static_cast<unsigned>(p.M) * (2u * K), 0x00020000);
+#pragma unroll
+        for (int rr = 0; rr < RG; ++rr)
+#pragma unroll
+            for (int i = 0; i < LPR; ++i)
+                // (rows past M lie beyond the descriptor's bound and read as zeros)
+                dst[rr][i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                           xr, static_cast<unsigned>(m0 + rr) * (2u * K) + static_cast<unsigned>((i * 64 + lv) * 16), 0, 0));
+    };
+    auto convert = [&](int q, const u32x4 (&src)[RG][LPR]) __attribute__((always_inline)) {
+        int g, m0;
+        locate(q, g, m0);
+        uint8_t* const xq = const_cast<uint8_t*>(p.X) + static_cast<int64_t>(g) * p.strideX;
+        float* const sxo = const_cast<float*>(p.sx) + static_cast<int64_t>(g) * p.strideSx;
+        // row amax: packed 16-bit maxima of the magnitudes (exact), the 16 lanes of a DPP row by four data-parallel
+        // moves, the four rows of lanes by two xor shuffles
+        unsigned mine = 0u;
+#pragma unroll
+        for (int rr = 0; rr < RG; ++rr) {
+            us2 a2 = {0, 0};
+#pragma unroll
+            for (int i = 0; i < LPR; ++i)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a2 = __builtin_elementwise_max(a2, __builtin_bit_cast(us2, src[rr][i][e] & 0x7FFF7FFFu));
+            unsigned a = a2[0] > a2[1] ? a2[0] : a2[1], o;
+            o = static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(a), 0xB1, 0xF, 0xF, false)); a = a > o ? a : o;
+            o = static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(a), 0x4E, 0xF, 0xF, false)); a = a > o ? a : o;
+            o = static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(a), 0x141, 0xF, 0xF, false)); a = a > o ? a : o;
+            o = static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(a), 0x140, 0xF, 0xF, false)); a = a > o ? a : o;
+            o = static_cast<unsigned>(__shfl_xor(static_cast<int>(a), 16, 64)); a = a > o ? a : o;
+            o = static_cast<unsigned>(__shfl_xor(static_cast<int>(a), 32, 64)); a = a > o ? a : o;
+            mine = lv == rr ? a : mine;          // lane rr keeps row rr's amax: one division pair per lane, not per row and lane
+        }
+        float scale_l, inv_l;
+        group_scale(__uint_as_float(mine << 16), scale_l, inv_l);
+        if (lv < RG && m0 + lv < p.M) sxo[m0 + lv] = scale_l;
+#pragma unroll
+        for (int rr = 0; rr < RG; ++rr) {
+            const float inv = __shfl(inv_l, rr, 64);
+            const bool live = m0 + rr < p.M;
+#pragma unroll
+            for (int i = 0; i < LPR; ++i) {
+                const u32x4 w = src[rr][i];
+                u32x2 o;
+                o.x = e4m3x4(bf16_lo(w.x) * inv, bf16_hi(w.x) * inv, bf16_lo(w.y) * inv, bf16_hi(w.y) * inv);
+                o.y = e4m3x4(bf16_lo(w.z) * inv, bf16_hi(w.z) * inv, bf16_lo(w.w) * inv, bf16_hi(w.w) * inv);
+                if (live) *reinterpret_cast<u32x2*>(xq + static_cast<int64_t>(m0 + rr) * K + (i * 64 + lv) * 8) = o;
+            }
+        }
+    };
+    if (ngroups > 0) fetch(0, raw[0]);
+    for (int q = 0; q < ngroups; q += 2) {
+        // (two groups per iteration so that the buffers keep compile-time names)
+        if (q + 1 < ngroups) { fetch(q + 1, raw[1]); wait_vmcnt<RG * LPR>(); } else wait_vmcnt<0>();
+        convert(q, raw[0]);
+        if (q + 1 < ngroups) {
+            // ("at most RG * LPR operations outstanding" covers group q + 1 although the stores of group q are in
+            // flight too: loads return in order, so whatever part of the completed operations are stores, the completed
+            // loads are the oldest ones, and there are at least as many of them as group q + 1 has)
+            if (q + 2 < ngroups) { fetch(q + 2, raw[0]); wait_vmcnt<RG * LPR>(); } else wait_vmcnt<0>();
+            convert(q + 1, raw[1]);
+        }
+    }
+    wait_vmcnt<0>();                             // codes and scales are in L2 before this wave passes the barrier
+}
+
+template <int EPI, int BW, int F8, bool QPRO = false>
 __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
     constexpr bool FP8OUT = F8 != 0;
     constexpr bool BLOCKWISE = BW != 0;
@@ -92,6 +189,12 @@ __global__ __launch_bounds__(512) void gemm_panel32_kernel(const GemmParams p) {
             w_rows * p.KB, 0x00020000);
     };
     bool prefetched = false;        // ring entries X(0) W(0) X(1) W(1) of `tile` were requested during the previous epilogue
+    if (QPRO) {
+        if (p.KB == 512) panel32_quantize_own_rows<1>(p, tile_first, tile_stride, total_tiles, wave);
+        else if (p.KB == 1024) panel32_quantize_own_rows<2>(p, tile_first, tile_stride, total_tiles, wave);
+        else panel32_quantize_own_rows<4>(p, tile_first, tile_stride, total_tiles, wave);
+        __syncthreads();
+    }
 
   for (int tile = tile_first; tile < total_tiles; tile += tile_stride) {
     int t = tile;
@@ -820,7 +923,8 @@ bool panel32_affine(const GemmParams& p) {
            p.norm == LOKA_NORM_BLOCKNORM || p.act != LOKA_ACT_NONE;
 }
 // bw: 0 plain scales, 1 block scales, 2 power-of-two block scales (see the kernel); fp8out with bw == 0 only
-const void* panel32_fn(int bw, bool fp8out, bool affine) {
+const void* panel32_fn(int bw, bool fp8out, bool affine, bool qpro) {
+    if (qpro) return (bw != 0 || fp8out) ? nullptr : reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 0, true>);
     if (fp8out) return bw != 0 ? nullptr
                        : affine ? reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 2>)
                                 : reinterpret_cast<const void*>(&gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 1>);
@@ -830,7 +934,8 @@ const void* panel32_fn(int bw, bool fp8out, bool affine) {
 }
 size_t panel32_lds() { return kPanel32Lds; }
 void panel32_launch(const GemmParams& p, int bw, dim3 grid, hipStream_t s) {
-    if (p.outq && panel32_affine(p)) gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 2><<<grid, 512, kPanel32Lds, s>>>(p);
+    if (p.qpro) gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 0, true><<<grid, 512, kPanel32Lds, s>>>(p);
+    else if (p.outq && panel32_affine(p)) gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 2><<<grid, 512, kPanel32Lds, s>>>(p);
     else if (p.outq) gemm_panel32_kernel<EPI_PANEL_SYNC, 0, 1><<<grid, 512, kPanel32Lds, s>>>(p);
     else if (bw == 2) gemm_panel32_kernel<EPI_PANEL_SYNC, 2, 0><<<grid, 512, kPanel32Lds, s>>>(p);
     else if (bw == 1) gemm_panel32_kernel<EPI_PANEL_SYNC, 1, 0><<<grid, 512, kPanel32Lds, s>>>(p);

@@ -1010,19 +1010,24 @@ def test_fused_quantization_gives_the_bits_of_the_two_calls(orc, case, variant):
 
 
 @pytest.mark.parametrize("case", [
-    (16384, 512, 512, 1, "rmsnorm"),       # C2
-    (8192 + 40, 256, 1024, 1, "layernorm"),  # the C3a layer, ragged last block
-    (4096 + 8, 1024, 256, 1, "layernorm"),   # the C3b layer
-    (1000, 128, 256, 1, "none"),
-    (2048 + 16, 256, 256, 3, "rmsnorm"),     # grouped: a workgroup's rows cross problems
-    (520, 512, 128, 5, "layernorm"),
+    (16384, 512, 512, 1, "rmsnorm", "wreg32"),       # C2
+    (8192 + 40, 256, 1024, 1, "layernorm", "wreg32"),  # the C3a layer, ragged last block
+    (4096 + 8, 1024, 256, 1, "layernorm", "wreg32"),   # the C3b layer
+    (1000, 128, 256, 1, "none", "wreg32"),
+    (2048 + 16, 256, 256, 3, "rmsnorm", "wreg32"),     # grouped: a workgroup's rows cross problems
+    (520, 512, 128, 5, "layernorm", "wreg32"),
+    # the large-tile kernel where a tile spans the output row: 1, 2 and 4 loads of a wave per row of X
+    (65536 + 72, 1024, 256, 1, "layernorm", "panel32_256x256"),   # the C3b layer and a ragged last tile; two tiles per workgroup
+    (3000, 512, 128, 1, "rmsnorm", "panel32_256x256"),
+    (1500, 2048, 256, 3, "layernorm", "panel32_256x256"),         # grouped
+    (256 * 300 + 8, 512, 256, 1, "none", "panel32_256x256"),      # more tiles than workgroups: several tiles each
 ], ids=lambda c: "x".join(str(v) for v in c))
 def test_quantize_prologue_gives_the_bits_of_the_two_calls(orc, case):
-    # loka_fp8_linear_norm_xq: every workgroup of the streaming kernel quantizes the rows it consumes, then runs the
-    # kernel of loka_fp8_gemm_norm: codes and row scales must be the oracle's (every row), fp32 Y and bf16 O those of
-    # the two calls, which are checked against the oracle elsewhere in this file
-    M, K, N, G, norm = case
-    v = B.variant_id("wreg32")
+    # loka_fp8_linear_norm_xq: every workgroup quantizes the rows it consumes, then runs the kernel of
+    # loka_fp8_gemm_norm: codes and row scales must be the oracle's (every row), fp32 Y and bf16 O those of the two calls,
+    # which are checked against the oracle elsewhere in this file
+    M, K, N, G, norm, vname = case
+    v = B.variant_id(vname)
     desc = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORMS[norm], 1e-5, variant=v)
     assert B.loka_variant_supports(desc, v)
     x = torch.cat([synth.student_t4(M, K, 150 + g) for g in range(G)], 0)
@@ -1050,9 +1055,16 @@ def test_quantize_prologue_gives_the_bits_of_the_two_calls(orc, case):
         assert np.array_equal(sx1.cpu().numpy().view(np.uint32), sx_o.view(np.uint32)), "row scales differ from the oracle's"
         assert torch.equal(y1, y2), "fp32 Y differs from the two-call path"
         assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)), "bf16 O differs from the two-call path"
+    # (no kernel named: the library's choice for the shape where that kernel has the prologue; the bits are those of the
+    # two calls on the same kernel)
     d_def = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORMS[norm], 1e-5, variant=-1)
-    o3, _, _, _ = B.loka_fp8_linear_norm_xq(d_def, xd, wq, sw, gamma.to(DEV), beta.to(DEV))
-    assert torch.equal(o3.view(torch.int16), o2.view(torch.int16))
+    o3, _, xq3, sx3 = B.loka_fp8_linear_norm_xq(d_def, xd, wq, sw, gamma.to(DEV), beta.to(DEV))
+    v_def = B.loka_default_variant(d_def)
+    if B.loka_variant_name(v_def) in ("wreg32", "panel32_256x256"):
+        d_pin = B.make_desc(M, N, K, G, B.SCALE_ROW, B.SCALE_COL, B.NORMS[norm], 1e-5, variant=v_def)
+        o4, _ = B.loka_fp8_gemm_norm(d_pin, xq2, sx2, wq, sw, gamma.to(DEV), beta.to(DEV))
+        assert torch.equal(o3.view(torch.int16), o4.view(torch.int16))
+    assert torch.equal(xq3, xq2) and torch.equal(sx3, sx2)
 
 
 def test_quantize_prologue_unsupported():
