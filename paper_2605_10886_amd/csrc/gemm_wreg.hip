@@ -450,6 +450,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
     constexpr int INSTR = INSTR_ > 0 ? INSTR_ : 1;                      // store instructions per storing wave and block
     bool pending = false;
     int pend_g = 0, pend_m0 = 0;
+    __amdgpu_buffer_rsrc_t pend_rsrc = __builtin_amdgcn_make_buffer_rsrc(p.out, 0, 0, 0x00020000);   // (bf16 output) the pending block's rows
     // store instruction s of the pending block: 64 consecutive chunks (1 KB), whole rows
     auto store_step = [&](int s, int sg, int sm0) __attribute__((always_inline)) {
         int lid = lane;
@@ -473,10 +474,19 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
             }
             return;
         }
-        const u32x4 pk = *reinterpret_cast<const u32x4*>(smem + C::OFF_OB + r * (NT * 2) + ((c ^ (r & 15)) << 4));
-        uint16_t* const og = p.out + static_cast<int64_t>(sg) * p.strideO;
-        if (sm0 + r < p.M && c * 8 < p.N)
-            __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(og + static_cast<int64_t>(sm0 + r) * p.N + c * 8));
+        // bf16 output: a buffer store relative to the block's first row.  The descriptor ends with the last row that
+        // exists (rows past M are dropped by its bound, no compare and no branch), the per-lane offset is 32 bits wide
+        // (a block is at most RB * N * 2 bytes), columns past N get an offset beyond the bound.
+        const unsigned ur = static_cast<unsigned>(id) / CPR, uc = static_cast<unsigned>(id) % CPR;
+        const u32x4 pk = *reinterpret_cast<const u32x4*>(smem + C::OFF_OB + ur * (NT * 2) + ((uc ^ (ur & 15)) << 4));
+        const unsigned voff = uc * 8 < static_cast<unsigned>(p.N) ? ur * (2u * static_cast<unsigned>(p.N)) + uc * 16 : 0xFFFFFFF0u;
+        __builtin_amdgcn_raw_buffer_store_b128(pk, pend_rsrc, static_cast<int>(voff), 0, 2 /* streaming (nt) */);
+    };
+    // descriptor of block (sg, sm0) of the bf16 output: its rows that exist
+    auto out_rsrc = [&](int sg, int sm0) __attribute__((always_inline)) {
+        const int rows_here = p.M - sm0 < RB ? p.M - sm0 : RB;
+        return __builtin_amdgcn_make_buffer_rsrc(
+            p.out + static_cast<int64_t>(sg) * p.strideO + static_cast<int64_t>(sm0) * p.N, 0, rows_here * p.N * 2, 0x00020000);
     };
     auto flush_pending = [&]() __attribute__((always_inline)) {
         if ((DEFER || storer) && pending) {
@@ -824,6 +834,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         lds_barrier();
         // ---- the block is written out: now, or between the MFMAs of the next block
         pending = true; pend_g = g; pend_m0 = m0;
+        if (!FP8OUT) pend_rsrc = out_rsrc(g, m0);
         if (!DEFER || b + 1 == b1) flush_pending();
     }
 }
