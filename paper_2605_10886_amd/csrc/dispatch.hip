@@ -20,6 +20,7 @@ bool variant_is_streaming(int);
 bool variant_is_strip(int);
 bool variant_is_exact(int);
 int variant_bn(int);
+int variant_splitk_choice(const loka_gemm_desc*);
 int variant_bm(int);
 loka_status validate_desc(const loka_gemm_desc* d, bool fp8);
 loka_status bf16_gemm_launch(const loka_gemm_desc*, const void*, const void*, float*, void*, hipStream_t, bool weights_ready);
@@ -85,9 +86,10 @@ int default_variant(const loka_gemm_desc* d) {
     // workgroups per tile (measured at 2048 x 123200 x 1024 with LayerNorm: see the variant's table entry)
     {
         const int64_t t128 = ((d->M + 127) / 128) * ((d->N + 127) / 128) * d->batch;
-        if (t128 <= 128 && d->K >= 2048)
-            for (int v = 0; v < variant_count(); ++v)
-                if (variant_epilogue(v) == 3 && variant_supports(d, v)) return v;
+        if (t128 <= 128 && d->K >= 2048) {
+            const int v = variant_splitk_choice(d);
+            if (v >= 0) return v;
+        }
     }
     // Measured on the skinny shapes (65536 x 1024 x 256, 65536 x 256 x 1024, 16384 x 512 x 512, 64 x 4096 x 256 x 256):
     // with at least one 256 x 256 tile per CU the large-tile kernel wins when K is long and the row fits one

@@ -42,6 +42,14 @@ __device__ __forceinline__ v8bf e4m3x8_to_bf16(int w0, int w1) {
     return v8bf{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
 }
 
+// Stages of 128 bytes per row kept in LDS, and the bytes a launch asks for: two stages (one in flight) everywhere but in
+// the eight-wave form of the split-K schedule, whose short chains of K steps need several loads in flight to hide the
+// memory latency (its ring also carries 1 KB of block scales per stage).
+constexpr int gemm_stages(int epi, int waves) { return (epi == EPI_SPLITK && waves == 8) ? 4 : 2; }
+constexpr size_t gemm_lds_bytes(int bm, int bn_sub, int epi, int waves) {
+    return static_cast<size_t>(gemm_stages(epi, waves)) * (bm * 128 + bn_sub * 128 + (gemm_stages(epi, waves) > 2 ? 1024 : 0));
+}
+
 template <int BM, int BN_SUB, int NSPLIT, int WAVES_M, int WAVES_N, bool IS_BF16, bool BLOCKWISE, int EPI, bool EXACT = false>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmParams p) {
     static_assert(!EXACT || (!IS_BF16 && !BLOCKWISE), "the exact-product form is built for the non-blockwise FP8 recipes");
@@ -53,13 +61,15 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     constexpr int BN = BN_SUB * NSPLIT;
     constexpr int XS = BM * 128;               // bytes of one X stage
     constexpr int WS = BN_SUB * 128;           // bytes of one W stage
+    constexpr int NST = gemm_stages(EPI, NW);  // stages in LDS (split K with eight waves: a ring of 4, three in flight)
+    constexpr bool RING = NST > 2;
     static_assert(WM % 16 == 0 && WN % 16 == 0 && (NI == 2 || NI == 4 || NI == 8), "tile shape");
     static_assert(BM % 8 == 0 && BN_SUB % 8 == 0, "loader works on 8-row groups");
     static_assert(!(BLOCKWISE && (WN > 128 || 128 % WN)), "a wave's columns must stay inside one 128-column block");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-    uint8_t* const xbuf = smem;                // 2 stages
-    uint8_t* const wbuf = smem + 2 * XS;       // 2 stages
+    uint8_t* const xbuf = smem;                // NST stages
+    uint8_t* const wbuf = smem + NST * XS;     // NST stages
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -176,8 +186,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     const float* sxg = p.sx + static_cast<int64_t>(g) * p.strideSx;
     const float* swg = p.sw + static_cast<int64_t>(g) * p.strideSw;
 
+    if constexpr (!RING) {
 #pragma unroll
-    for (int j = 0; j < JN; ++j) issue_j(j, 0, 0, 0, 0, true);   // stage 0, every wave's share
+        for (int j = 0; j < JN; ++j) issue_j(j, 0, 0, 0, 0, true);   // stage 0, every wave's share
+    }
 
     // loads of the next stage are issued in the first ISSUE_STEPS tile steps of the running stage
     constexpr int ISSUE_STEPS = NI >= 4 ? NI / 2 : NI;
@@ -189,7 +201,105 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const GemmP
     // of stage k-1 from registers; then A computes stage k while B reads stage k.  The MFMA pipe of every
     // SIMD always has a computing wave, and the LDS reads of one group hide behind the other's MFMAs.
     constexpr bool PINGPONG = (NW == 8 && WAVES_M == 2 && NSPLIT == 1 && !IS_BF16 && !BLOCKWISE && !EXACT && EPI != EPI_SPLITK);
-    if constexpr (PINGPONG) {
+    if constexpr (RING) {
+        // Split K: a workgroup's share is a chain of short K steps (8 MFMAs per wave) whose operands come from HBM.
+        // With one stage in flight every step waits a whole memory round trip (measured: 1.7 - 2.5 us per step, whatever
+        // the number of ranges).  Here a ring of NST stages keeps NST - 1 of them in flight: the loads of stage k + NST - 1
+        // go out between the MFMAs of stage k, into the slot stage k - 1 left, and the wait at the top of a step leaves
+        // the newer stages' loads outstanding (loads complete in order, every wave issues the same number per stage).
+        // (Measured at 65536 x 256 x 1024 as a weight gradient: 0.9 us per step, of which 0.55 us remain with neither
+        // loads nor LDS reads in the loop - the MFMAs into fresh accumulators and the 32 multiply-adds that promote
+        // them, wave by wave; reading the next step's fragments into a second register set between the MFMAs changes
+        // nothing.  The four-wave instantiation keeps the two-stage loop below, two workgroups per CU covering each
+        // other's round trips: per CU and step it is the faster one once a range has more than about a hundred steps.)
+        // Block scales travel with their stage: a per-step load from global memory in the loop would be younger than
+        // the stages in flight, and waiting for it would wait for them.  Waves 0 and 1 fetch the step's scale of 64 rows
+        // of X each (one 4-byte load per lane, straight into LDS), wave 2 the scale of the W block, the other waves a load
+        // that is out of range (zeros, into a spare quarter of the slot): the same count on every wave.
+        static_assert(NSPLIT == 1 && !IS_BF16 && !EXACT && NST == 4, "split K: plain FP8 tiles on a ring of four stages");
+        static_assert(!BLOCKWISE || (NW >= 4 && BM == 128 && BN == 128), "scale loads are laid out for a 128 x 128 tile and at least four waves");
+        constexpr int D = NST - 1;
+        constexpr int JT = JN + (BLOCKWISE ? 1 : 0);                    // loads per wave and stage
+        uint8_t* const sbuf = smem + NST * (XS + WS);                   // [NST][256 floats]: sx of the tile's rows, then sw
+        // (descriptor and step from wave-uniform values, handed over through scalar registers: derived from branches on
+        // the wave id the compiler would wrap every scale load in a loop over the lanes' descriptors)
+        int s_rows = p.M - m0 - 64 * wave;
+        s_rows = s_rows < 0 ? 0 : (s_rows > 64 ? 64 : s_rows);
+        const float* s_base = wave < 2 ? sxg + static_cast<int64_t>(m0 + 64 * wave) * ksteps_all : swg + (n0 >> 7);
+        int s_rec = wave < 2 ? s_rows * ksteps_all * 4 : (wave == 2 ? (ksteps_all * (p.N >> 7) - (n0 >> 7)) * 4 : 0);
+        int s_step = wave < 2 ? 4 : (p.N >> 7) * 4;                     // bytes from one K step's scale to the next
+        const uint64_t s_addr = reinterpret_cast<uint64_t>(s_base);
+        const uint64_t s_addr_u = static_cast<uint64_t>(static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(s_addr)))) |
+                                  (static_cast<uint64_t>(static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(s_addr >> 32)))) << 32);
+        s_rec = __builtin_amdgcn_readfirstlane(BLOCKWISE ? s_rec : 0);
+        s_step = __builtin_amdgcn_readfirstlane(s_step);
+        const __amdgpu_buffer_rsrc_t s_rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<float*>(s_addr_u), 0, s_rec, 0x00020000);
+        // waves 0, 1: the lane's row (checked against the descriptor's bound); wave 2: lane 0 takes the block's scale
+        const int s_voff = wave < 2 ? lane * ksteps_all * 4 : (lane == 0 ? 0 : 0x7FFFFFF0);
+        auto issue_stage = [&](int j0, int j1, int slot, int k) __attribute__((always_inline)) {
+            if (BLOCKWISE && j0 == 0)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(s_rsrc, (__attribute__((address_space(3))) void*)(sbuf + slot * 1024 + (wave < 3 ? wave : 3) * 256),
+                                                         4, s_voff, (k_lo + k) * s_step, 0, 0);
+#pragma unroll
+            for (int j = j0; j < j1 && j < JN; ++j) issue_j(j, slot, slot, k * 128, 0, true);
+        };
+#pragma unroll
+        for (int s = 0; s < D; ++s)
+            if (s < ksteps) issue_stage(0, JN, s, s);
+        for (int k = 0; k < ksteps; ++k) {
+            const int newer = ksteps - 1 - k < D - 1 ? ksteps - 1 - k : D - 1;   // stages requested after stage k
+            if (newer >= 2) wait_vmcnt<2 * JT>();
+            else if (newer == 1) wait_vmcnt<JT>();
+            else wait_vmcnt<0>();
+            lds_barrier();                                      // everyone's share of stage k is here; everyone left step k - 1
+            const bool more = k + D < ksteps;
+            const int slot = k % NST, nslot = (k + D) % NST;
+            const uint8_t* xs = xbuf + slot * XS;
+            const uint8_t* ws = wbuf + slot * WS;
+            v8i bx[MI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const v4i lo = *reinterpret_cast<const v4i*>(xs + x_off0 + mi * 16 * 128);
+                const v4i hi = *reinterpret_cast<const v4i*>(xs + x_off1 + mi * 16 * 128);
+                bx[mi] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            }
+            float sxk[MI], swk = 0.f;
+            if (BLOCKWISE) {
+                const float* sl = reinterpret_cast<const float*>(sbuf + slot * 1024);
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) sxk[mi] = sl[wave_m * WM + mi * 16 + l16];
+                swk = sl[128];
+            }
+            v4i lo = *reinterpret_cast<const v4i*>(ws + w_off0);
+            v4i hi = *reinterpret_cast<const v4i*>(ws + w_off1);      // coff_of(0) == 0
+#pragma unroll
+            for (int ti = 0; ti < NI; ++ti) {
+                if (more && ti < ISSUE_STEPS) issue_stage(ti * J_PER_STEP, (ti + 1) * J_PER_STEP, nslot, k + D);
+                v4i lo_n = lo, hi_n = hi;
+                if (ti + 1 < NI) {
+                    lo_n = *reinterpret_cast<const v4i*>(ws + w_off0 + coff_of(ti + 1) * 128);
+                    hi_n = *reinterpret_cast<const v4i*>(ws + w_off1 + coff_of(ti + 1) * 128);
+                }
+                const v8i aw = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    if (BLOCKWISE) {
+                        // promote this 128-wide K block into the fp32 accumulator with its scales
+                        const v4f c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aw, bx[mi], v4f{0.f, 0.f, 0.f, 0.f},
+                                                                                        0, 0, 0, 0, 0, 0);
+                        const float s = sxk[mi] * swk;
+                        acc[0][mi][ti] += c * s;
+                    } else {
+                        acc[0][mi][ti] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aw, bx[mi], acc[0][mi][ti],
+                                                                                         0, 0, 0, 0, 0, 0);
+                    }
+                }
+                lo = lo_n;
+                hi = hi_n;
+            }
+        }
+    } else if constexpr (PINGPONG) {
         const bool grp_b = wave >= 4;                           // wave-uniform
         v8i bx[MI], aw[NI];
         auto read_frags = [&](int k) __attribute__((always_inline)) {
@@ -842,7 +952,7 @@ struct VariantInfo {
 
 template <int BM, int BN_SUB, int NSPLIT, int WAVES_M, int WAVES_N, int EPI>
 static void launch_fp8(const GemmParams& p, bool blockwise, dim3 grid, hipStream_t s) {
-    constexpr size_t lds = 2 * (BM * 128 + BN_SUB * 128);
+    constexpr size_t lds = gemm_lds_bytes(BM, BN_SUB, EPI, WAVES_M * WAVES_N);
     constexpr int threads = WAVES_M * WAVES_N * 64;
     if (blockwise) gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, true, EPI><<<grid, threads, lds, s>>>(p);
     else gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, false, EPI><<<grid, threads, lds, s>>>(p);
@@ -887,7 +997,7 @@ static void launch_exact(const GemmParams& p, bool, dim3 grid, hipStream_t s) {
      reinterpret_cast<const void*>(&gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, false, EPI, true>), nullptr}
 
 #define LOKA_VARIANT(NAME, BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, EPI)                                        \
-    {NAME, BM, BN_SUB * NSPLIT, WAVES_M * WAVES_N * 64, EPI, 2 * (BM * 128 + BN_SUB * 128),                  \
+    {NAME, BM, BN_SUB * NSPLIT, WAVES_M * WAVES_N * 64, EPI, gemm_lds_bytes(BM, BN_SUB, EPI, WAVES_M * WAVES_N), \
      &launch_fp8<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, EPI>,                                                 \
      reinterpret_cast<const void*>(&gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, false, EPI>),   \
      reinterpret_cast<const void*>(&gemm_kernel<BM, BN_SUB, NSPLIT, WAVES_M, WAVES_N, false, true, EPI>)}
@@ -916,8 +1026,11 @@ static const VariantInfo kVariants[] = {
     LOKA_VARIANT("twopass256x256", 256, 256, 1, 2, 2, EPI_PARTIAL_STATS),
     LOKA_VARIANT("twopass256x256w8", 256, 256, 1, 2, 4, EPI_PARTIAL_STATS),
     // split K: layers with few output tiles and a long K (weight gradients, the widest layers at small batch); ksplit
-    // workgroups per tile contract a K range each into fp32 partial sums, a second kernel adds them and normalizes
-    LOKA_VARIANT("splitk128x128", 128, 128, 1, 2, 2, EPI_SPLITK),
+    // workgroups per tile contract a K range each into fp32 partial sums, a second kernel adds them and normalizes.
+    // Two forms: eight waves on a ring of four LDS stages, one workgroup per CU (short ranges: a weight gradient), and
+    // four waves on two stages, two workgroups per CU (long ranges)
+    LOKA_VARIANT("splitk128x128", 128, 128, 1, 2, 4, EPI_SPLITK),
+    LOKA_VARIANT("splitk128x128s2", 128, 128, 1, 2, 2, EPI_SPLITK),
     // persistent, panel-synchronous: the tiles_n workgroups of a row panel exchange row statistics
     // through a few words of global memory and normalize their own tile in registers
     LOKA_VARIANT("panel256x256w8", 256, 256, 1, 2, 4, EPI_PANEL_SYNC),
@@ -984,19 +1097,36 @@ bool variant_is_exact(int v) { return kVariants[v].launch != nullptr && kVariant
 int variant_bn(int v) { return kVariants[v].bn; }
 int variant_bm(int v) { return kVariants[v].bm; }
 
-// Split K: the number of K ranges and their length in 128-byte steps.  Enough ranges to give an MI355X's 256 CUs about
-// two workgroups each, at least 4 steps per range, at most 64 ranges.  (A fixed figure, not the device's CU count: the
-// workspace size follows from it and must not depend on the device.)
+// Split K: the number of K ranges and their length in 128-byte steps.  The ring form: as many ranges as give an
+// MI355X's 256 CUs one workgroup each and no more (its stages fill a CU's LDS: a 257th workgroup would be a second
+// round).  The two-stage form: about two workgroups per CU.  At least 4 steps per range, at most 64 ranges.  (Fixed
+// figures, not the device's CU count: the workspace size follows from them and must not depend on the device.)
 static void splitk_plan(const loka_gemm_desc* d, const VariantInfo& vi, int* ksplit, int* per) {
     const int64_t tiles = ((d->M + vi.bm - 1) / vi.bm) * ((d->N + vi.bn - 1) / vi.bn) * d->batch;
     const int64_t steps = (d->K + 127) / 128;
-    int64_t want = (512 + tiles - 1) / tiles;
+    int64_t want = vi.threads == 512 ? 256 / tiles : (512 + tiles - 1) / tiles;
     if (want > 64) want = 64;
     if (want > steps / 4) want = steps / 4;
     if (want < 1) want = 1;
     const int64_t len = (steps + want - 1) / want;
     *per = static_cast<int>(len);
     *ksplit = static_cast<int>((steps + len - 1) / len);
+}
+
+bool variant_supports(const loka_gemm_desc* d, int v);
+// the split-K form for the shape: the ring form unless its ranges would be long (measured: 65536 x 256 x 1024 as a weight
+// gradient, 32 steps per range, 43.5 us against 48.5 us for the two-stage form; 2048 x 123200 x 1024, 482 steps per range,
+// 437 us against 400 us), the other form where only one of them splits K at all
+int variant_splitk_choice(const loka_gemm_desc* d) {
+    int ring = -1, two = -1;
+    for (int v = 0; v < kNumVariants; ++v) {
+        if (kVariants[v].epi != EPI_SPLITK || !variant_supports(d, v)) continue;
+        if (kVariants[v].threads == 512) ring = v; else two = v;
+    }
+    if (ring < 0 || two < 0) return ring >= 0 ? ring : two;
+    int ksplit = 1, per = 1;
+    splitk_plan(d, kVariants[ring], &ksplit, &per);
+    return per <= 128 ? ring : two;
 }
 
 bool variant_supports(const loka_gemm_desc* d, int v) {

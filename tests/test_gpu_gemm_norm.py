@@ -154,6 +154,8 @@ def test_ragged_k_largest_shape_of_the_throughput_study(orc):
     x = synth.normal(M, K, seed=21)
     wt = synth.weight(K, N, seed=22)
     rows = _sample_rows(M, 8)[::4]
+    # (ranges of several hundred K steps: the two-stage form of the split-K schedule is the static choice)
+    assert B.loka_variant_name(B.loka_default_variant(B.make_desc(M, N, K, 1, norm=B.NORM_LAYERNORM))) == "splitk128x128s2"
     r = _run_case(orc, x, wt, "row", "layernorm", -1, rows=rows, tag="2048x123200x1024")
     print("2048x123200x1024", r)
     st, ch, table = B.loka_dispatch(B.make_desc(M, N, K, 1, norm=B.NORM_LAYERNORM), x.to(DEV), wt.to(DEV), 5e-2)
@@ -165,17 +167,20 @@ def test_ragged_k_largest_shape_of_the_throughput_study(orc):
 @pytest.mark.parametrize("case", [(256, 16384, 1024, "row", "none"), (256, 16384, 1024, "block", "none"),
                                   (512, 8192, 512, "tensor", "layernorm"), (300, 4096, 2320, "row", "rmsnorm"),
                                   (128, 32768, 256, "block_pow2", "layernorm")])
-def test_split_k_few_tiles_long_k(orc, case):
+@pytest.mark.parametrize("form", ["splitk128x128", "splitk128x128s2"])
+def test_split_k_few_tiles_long_k(orc, case, form):
     # few output tiles and a long K (the shape of a weight-gradient GEMM, or of a wide layer at small batch): several
-    # workgroups per tile contract a K range each, a second kernel adds the partial sums in a fixed order and normalizes
+    # workgroups per tile contract a K range each, a second kernel adds the partial sums in a fixed order and normalizes.
+    # Two forms of the main kernel: a ring of four LDS stages (the choice for ranges of up to 128 K steps, as here) and
+    # the two-stage loop (long ranges)
     M, K, N, recipe, norm = case
     x = synth.student_t4(M, K, seed=5 * M)
     wt = synth.weight(K, N, seed=5 * N)
     gamma, beta = synth.affine(N, seed=9) if norm != "none" else (None, None)
-    v = B.variant_id("splitk128x128")
+    v = B.variant_id(form)
     desc = B.make_desc(M, N, K, 1, *RECIPES[recipe], B.NORMS[norm], 1e-5, v)
     assert B.loka_variant_supports(desc, v)
-    assert B.loka_default_variant(B.make_desc(M, N, K, 1, *RECIPES[recipe], B.NORMS[norm])) == v
+    assert B.loka_variant_name(B.loka_default_variant(B.make_desc(M, N, K, 1, *RECIPES[recipe], B.NORMS[norm]))) == "splitk128x128"
     r = _run_case(orc, x, wt, recipe, norm, v, gamma, beta if norm == "layernorm" else None, tag=f"split-K {case}")
     print("split-K", case, r)
     # repeatable bits: the partial sums are added in a fixed order
