@@ -685,45 +685,37 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
         for (int rt = 0; rt < RT; ++rt) { mean_r[rt] = 0.f; rstd_r[rt] = 1.f; }
         if (p.norm != LOKA_NORM_NONE) {
             lds_barrier();
-            // The two lanes that hold a row (l and l ^ 32) fold four waves' entries each, in order, and merge their
-            // halves symmetrically: identical bits on both, in every wave.  The folds are branch-free (an empty part
-            // has count 0 and changes nothing).
+            // The two lanes that hold a row (l and l ^ 32) take four waves' entries each and add their halves (a + b ==
+            // b + a: identical bits on both, in every wave).  LayerNorm: the parts' counts add up to N exactly, so the
+            // row mean is sum(n_w mean_w) / N and the centred sum of squares is sum(m2_w + n_w (mean_w - mean)^2) - the
+            // combination of per-part (count, mean, M2) written without the chain of pairwise merges and their
+            // reciprocals (an empty part has count 0 and mean 0 and adds nothing).
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
-                float tn = 0.f, tmean = 0.f, tm2 = 0.f;
+                float tm2 = 0.f, tmean = 0.f;
                 float4 r[4];
 #pragma unroll
                 for (int w = 0; w < 4; ++w) r[w] = red[(rt * 32 + l32) * 9 + 4 * hk + w];
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    if (ln) {
-                        const float nn = tn + r[w].x;
-                        const float f = r[w].x > 0.f ? r[w].x * __builtin_amdgcn_rcpf(nn) : 0.f;
-                        const float d = r[w].y - tmean;
-                        tmean = tmean + d * f;
-                        tm2 = tm2 + r[w].z + d * d * tn * f;
-                        tn = nn;
-                    } else if (blocknorm) {
-                        // only the waves that share this wave's group of 256 columns
-                        if ((4 * hk + w) / WPG == wave / WPG) tm2 += r[w].z;
-                    } else {
-                        tm2 += r[w].z;
-                    }
-                }
                 if (ln) {
-                    const float nb = wave_shfl_xor(tn, 32), mb = wave_shfl_xor(tmean, 32), m2b = wave_shfl_xor(tm2, 32);
-                    const float nn = tn + nb;
-                    if (nn > 0.f) {
-                        const float d = mb - tmean;
-                        const float rn = __builtin_amdgcn_rcpf(nn);
-                        const float newmean = (tn * tmean + nb * mb) * rn;
-                        tm2 = tm2 + m2b + d * d * (tn * nb * rn);
-                        tmean = newmean;
+                    float s1 = 0.f;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) s1 = __builtin_fmaf(r[w].x, r[w].y, s1);
+                    s1 += wave_shfl_xor(s1, 32);
+                    tmean = s1 * inv_n;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        const float d = r[w].y - tmean;
+                        tm2 += __builtin_fmaf(r[w].x * d, d, r[w].z);
                     }
                 } else {
-                    tm2 += wave_shfl_xor(tm2, 32);
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        // BlockNorm: only the waves that share this wave's group of 256 columns
+                        if (!blocknorm || (4 * hk + w) / WPG == wave / WPG) tm2 += r[w].z;
+                    }
                 }
-                mean_r[rt] = ln ? tmean : 0.f;
+                tm2 += wave_shfl_xor(tm2, 32);
+                mean_r[rt] = tmean;
                 rstd_r[rt] = __builtin_amdgcn_rsqf(tm2 * (blocknorm ? 1.0f / 256.0f : inv_n) + p.eps);
             }
         } else if (DEFER) {
