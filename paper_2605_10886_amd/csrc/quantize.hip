@@ -371,13 +371,15 @@ __global__ __launch_bounds__(256) void quant_tile128_kernel(const uint16_t* __re
             *reinterpret_cast<u32x2*>(tile + (cc * 8 + 4 + j) * 144 + rr * 8) = u32x2{c[j], d[j]};
         }
         __syncthreads();
-        // output row c0 + c: 128 codes; thread -> (column t / 2, half of 64 bytes)
-        const int col = t >> 1, half = (t & 1) * 64;
-        if (c0 + col < cols) {
-            uint8_t* dst = q + (c0 + col) * rows + r0 + half;
+        // output row c0 + c: 128 codes.  Eight consecutive lanes write one row's 128 bytes, a store instruction of a
+        // wave eight whole rows (full cache lines per request: with a thread per half row, four stores apart, every
+        // instruction scattered 16-byte pieces over 32 lines)
+        const int chunk = (t & 7) * 16;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                *reinterpret_cast<u32x4*>(dst + 16 * j) = *reinterpret_cast<const u32x4*>(tile + col * 144 + half + 16 * j);
+        for (int j = 0; j < 4; ++j) {
+            const int col = j * 32 + (t >> 3);
+            if (c0 + col < cols)
+                *reinterpret_cast<u32x4*>(q + (c0 + col) * rows + r0 + chunk) = *reinterpret_cast<const u32x4*>(tile + col * 144 + chunk);
         }
     }
 }
