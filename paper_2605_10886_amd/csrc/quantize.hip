@@ -365,21 +365,24 @@ __global__ __launch_bounds__(256) void quant_tile128_kernel(const uint16_t* __re
         t4(lo[4], lo[5], lo[6], lo[7], b);                  // columns 0..3, rows 4..7
         t4(hi[0], hi[1], hi[2], hi[3], c);                  // columns 4..7, rows 0..3
         t4(hi[4], hi[5], hi[6], hi[7], d);                  // columns 4..7, rows 4..7
+        // (LDS row = output row: 16 runs of 8 codes, run rr at position rr ^ cc with cc = the row's chunk column: the 64
+        // lanes of a write then spread over all banks two deep, where unswizzled they met on 16 of the 64)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            *reinterpret_cast<u32x2*>(tile + (cc * 8 + j) * 144 + rr * 8) = u32x2{a[j], b[j]};
-            *reinterpret_cast<u32x2*>(tile + (cc * 8 + 4 + j) * 144 + rr * 8) = u32x2{c[j], d[j]};
+            *reinterpret_cast<u32x2*>(tile + (cc * 8 + j) * 144 + ((rr ^ cc) << 3)) = u32x2{a[j], b[j]};
+            *reinterpret_cast<u32x2*>(tile + (cc * 8 + 4 + j) * 144 + ((rr ^ cc) << 3)) = u32x2{c[j], d[j]};
         }
         __syncthreads();
         // output row c0 + c: 128 codes.  Eight consecutive lanes write one row's 128 bytes, a store instruction of a
         // wave eight whole rows (full cache lines per request: with a thread per half row, four stores apart, every
         // instruction scattered 16-byte pieces over 32 lines)
-        const int chunk = (t & 7) * 16;
+        const int chunk = t & 7;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int col = j * 32 + (t >> 3);
-            if (c0 + col < cols)
-                *reinterpret_cast<u32x4*>(q + (c0 + col) * rows + r0 + chunk) = *reinterpret_cast<const u32x4*>(tile + col * 144 + chunk);
+            const int col = j * 32 + (t >> 3), key = col >> 3;           // the row's runs 2 chunk, 2 chunk + 1 sit at ^ key
+            u32x4 v = *reinterpret_cast<const u32x4*>(tile + col * 144 + ((chunk ^ (key >> 1)) << 4));
+            if (key & 1) v = u32x4{v.z, v.w, v.x, v.y};
+            if (c0 + col < cols) *reinterpret_cast<u32x4*>(q + (c0 + col) * rows + r0 + chunk * 16) = v;
         }
     }
 }
