@@ -166,7 +166,8 @@ def test_ragged_k_largest_shape_of_the_throughput_study(orc):
 
 @pytest.mark.parametrize("case", [(256, 16384, 1024, "row", "none"), (256, 16384, 1024, "block", "none"),
                                   (512, 8192, 512, "tensor", "layernorm"), (300, 4096, 2320, "row", "rmsnorm"),
-                                  (128, 32768, 256, "block_pow2", "layernorm")])
+                                  (128, 32768, 256, "block_pow2", "layernorm"),
+                                  (300, 4096, 640, "block", "layernorm")])      # block scales with a ragged last row tile
 @pytest.mark.parametrize("form", ["splitk128x128", "splitk128x128s2"])
 def test_split_k_few_tiles_long_k(orc, case, form):
     # few output tiles and a long K (the shape of a weight-gradient GEMM, or of a wide layer at small batch): several
