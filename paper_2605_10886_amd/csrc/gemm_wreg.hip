@@ -776,14 +776,12 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
                         const u32x4 pk = norm8(affine_tag, rt, ni, half, gq0, gq1, bq0, bq1, rstd_r[rt]);
                         *reinterpret_cast<u32x4*>(obuf + (rt * 32 + l32) * (NT * 2) + ((c ^ (l32 & 15)) << 4)) = pk;
                         if (FP8OUT) {
-                            unsigned a = amax_b[rt];
+                            // (two 16-bit magnitudes per word, packed integer maximum; the halves are folded after the loop)
+                            typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+                            us2 a = __builtin_bit_cast(us2, amax_b[rt]);
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const unsigned lo = pk[e] & 0x7FFFu, hi = (pk[e] >> 16) & 0x7FFFu;
-                                a = a > lo ? a : lo;
-                                a = a > hi ? a : hi;
-                            }
-                            if (in) amax_b[rt] = a;
+                            for (int e = 0; e < 4; ++e) a = __builtin_elementwise_max(a, __builtin_bit_cast(us2, pk[e] & 0x7FFF7FFFu));
+                            if (in) amax_b[rt] = __builtin_bit_cast(unsigned, a);
                         }
                     }
                 }
@@ -801,6 +799,7 @@ __global__ __launch_bounds__(512) void gemm_wreg_kernel(const GemmParams p, cons
             unsigned* const redq = reinterpret_cast<unsigned*>(smem + C::OFF_RED) + 3;
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
+                amax_b[rt] = (amax_b[rt] & 0xFFFFu) > (amax_b[rt] >> 16) ? (amax_b[rt] & 0xFFFFu) : (amax_b[rt] >> 16);
                 const unsigned o2 = static_cast<unsigned>(__shfl_xor(static_cast<int>(amax_b[rt]), 32, 64));
                 amax_b[rt] = amax_b[rt] > o2 ? amax_b[rt] : o2;
                 if (hk == 0) redq[((rt * 32 + l32) * 9 + wave) * 4] = amax_b[rt];
